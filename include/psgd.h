@@ -1,0 +1,144 @@
+/*
+ * psgd.h -- C ABI of the MI355X (gfx950) PowerSGD+ compressor library.
+ *
+ * The library implements the per-step, per-layer low-rank gradient compressor of
+ * "From PowerSGD to PowerSGD+" (arXiv 2509.11254) for matrix variables X in R^{m x n}, m >= n
+ * (Section 1, problem statement):
+ *
+ *   error feedback      M = (1/N) sum_i G^(i) + E                       Eq. (7a), averaged over workers
+ *   SSP-Comp            P = M Q_{t-1};  P~ = QR(P);  Q_t = M^T P~       Algorithm 1, Eq. (9)
+ *   SVD-Comp            P~ = U[:, :r] of SVD(M);     Q_t = M^T P~       Algorithm 1, Definition 3
+ *   residual            E_{t+1} = M - P~ Q_t^T                          Algorithm 2 (error update)
+ *   reconstruction      Delta_hat = P~ Q_t^T                            Algorithm 1 (return value)
+ *
+ * The N workers' gradients live on one GPU and are averaged there (this replaces the All-Reduce
+ * Mean of Algorithm 1).  The library keeps a single error buffer E per layer, the mean of the
+ * per-worker residuals e^(i); by linearity of the compressor (Appendix B, notations) P~, Q,
+ * Delta_hat and mean_i e^(i) are the same as in the per-worker form.  Which of SSP-Comp and
+ * SVD-Comp runs at step t (mod(t, tau) = 0 selects SVD-Comp, Algorithm 2) is the caller's decision:
+ * call psgd_compress or psgd_compress_refresh.
+ *
+ * General conventions
+ *   - Every matrix argument is caller-owned DEVICE memory; the library never frees or keeps it
+ *     beyond the call.  Pointer tables (G, E, Q, P arrays of pointers) are HOST arrays of device
+ *     pointers.  The library owns only the host-side psgd_ctx and works inside the device
+ *     workspace the caller passes (psgd_workspace_bytes bytes, 256-byte aligned, device memory).
+ *   - Storage: row-major, `rows x cols` with leading dimension `ld` (elements).  The logical
+ *     matrix has m = max(rows, cols), n = min(rows, cols); when rows < cols the stored buffer is
+ *     the transpose of the logical matrix and is used as is (no physical transpose).
+ *     P~ is m x r and Q is n x r, both fp32, row-major, contiguous (leading dimension r).
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
+ *     the call returns without waiting for it.  Nothing is read back to the host.
+ *   - Return value: PSGD_OK or a negative PSGD_E_* code.  On an argument error nothing is
+ *     enqueued.  No exceptions, no aborts.
+ *   - Calls that share a workspace must be stream-ordered; two calls running at the same time on
+ *     one workspace race.
+ */
+#ifndef PSGD_H_
+#define PSGD_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct psgd_ctx psgd_ctx;
+
+enum { PSGD_F32 = 0, PSGD_BF16 = 1 };
+
+enum {
+    PSGD_OK = 0,
+    PSGD_E_INVALID_ARG = -1, /* null pointer, bad enum, bad count                           */
+    PSGD_E_SHAPE = -2,       /* rows/cols < 1, r < 1, r > min(rows, cols), r + oversampling too large */
+    PSGD_E_ALIGN = -3,       /* ld < cols, ld not a multiple of 8, pointer not 16-byte aligned */
+    PSGD_E_HIP = -4,         /* a HIP runtime call failed (psgd_last_hip_error gives its code) */
+    PSGD_E_NOMEM = -5        /* host allocation failed                                      */
+};
+
+/* One matrix variable.  G^(i) and E of this layer all share rows, cols and ld. */
+typedef struct {
+    int64_t rows;       /* stored rows                                                       */
+    int64_t cols;       /* stored columns                                                    */
+    int64_t ld;         /* leading dimension in elements, >= cols, multiple of 8; 0 means round_up(cols, 8) == cols required */
+    int32_t r;          /* compression rank, 1 <= r <= min(rows, cols)                       */
+    int32_t grad_dtype; /* PSGD_F32 or PSGD_BF16: element type of the G^(i) buffers          */
+} psgd_layer_desc;
+
+typedef struct {
+    int32_t refresh_iters;      /* subspace iterations of the SVD refresh; 0 = default (8)            */
+    int32_t refresh_oversample; /* extra block columns beyond r; negative = default (at least 8,
+                                   block width rounded up to a multiple of 32)                        */
+    int32_t refresh_warm_start; /* 1: psgd_compress_refresh starts from span(Q_{t-1}) plus random
+                                   columns; 0: random start.  Default 1.                             */
+    uint32_t seed;              /* seed of the counter-based generator for the random start      */
+    float rank_tol;             /* a column of P whose part orthogonal to the earlier columns is
+                                   at most rank_tol times its norm gives a zero column of P~;
+                                   0 = default (1e-5)                                                */
+    int32_t reserved[3];
+} psgd_options;
+
+/* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */
+typedef struct {
+    int32_t rank_deficient; /* number of columns of P~ zeroed by the rank test                  */
+    int32_t reserved;
+    float sigma_max;        /* refresh only: largest and r-th Ritz value (singular value estimates) */
+    float sigma_r;
+} psgd_layer_status;
+
+/* psgd_init -- plan the batched launches for a fixed set of layers (Algorithm 2, "Require"/"Initialize":
+ * rank r per layer, number of workers N).  Host only; allocates the context with malloc.
+ * Errors: INVALID_ARG (null out/layers, n_layers < 1, n_workers < 1, bad dtype), SHAPE, ALIGN, NOMEM. */
+int psgd_init(psgd_ctx **out, int n_layers, const psgd_layer_desc *layers, int n_workers,
+              const psgd_options *opt /* nullable: defaults */);
+
+/* Bytes of device workspace every compute call needs (partials, packed operands, small factors). */
+size_t psgd_workspace_bytes(const psgd_ctx *ctx);
+
+/* psgd_compress -- one SSP-Comp step for every layer (Algorithm 1 SSP-Comp + Eq. (7a) + residual):
+ *   M = mean_i G[l*N + i] + E[l];  P = M Q[l];  P~ = QR(P) (R_ii > 0);  Q[l] <- M^T P~;
+ *   E[l] <- M - P~ Q[l]^T;  P[l] <- P~.
+ * G: n_layers*n_workers read-only device pointers (layer-major), element type grad_dtype.
+ * E: n_layers fp32 buffers rows x cols (ld), updated in place.  Q: n x r fp32, in Q_{t-1}, out Q_t.
+ * P: m x r fp32, out.  Errors: INVALID_ARG (null table or entry), ALIGN (pointer alignment), HIP. */
+int psgd_compress(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
+                  float *const *E, float *const *Q, float *const *P);
+
+/* psgd_compress_refresh -- one SVD-Comp step for every layer (Algorithm 1 SVD-Comp + Eq. (7a) +
+ * residual): as psgd_compress, but P~ spans the top-r left singular subspace of M (Definition 3)
+ * and Q = M^T P~.  P~'s columns are the Ritz vectors in order of decreasing singular value.
+ * Q on entry is only used as a starting guess (and not at all with refresh_warm_start = 0). */
+int psgd_compress_refresh(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
+                          float *const *E, float *const *Q, float *const *P);
+
+/* psgd_refresh -- the optimal rank-r compressor of Definition 3 on a given matrix, nothing else:
+ * M (rows x cols, ld of layer `layer`, fp32, read-only) -> P (m x r), Q = M^T P~ (n x r),
+ * sigma (r fp32 singular value estimates, device, nullable). */
+int psgd_refresh(psgd_ctx *ctx, void *workspace, void *stream, int layer, const float *M, float *P,
+                 float *Q, float *sigma);
+
+/* psgd_decompress -- Delta_hat[l] = P~[l] Q[l]^T in the layer's storage orientation (Algorithm 1,
+ * return value).  out[l]: rows x cols (ld), element type out_dtype (PSGD_F32 or PSGD_BF16). */
+int psgd_decompress(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
+                    const float *const *Q, void *const *out, int out_dtype);
+
+/* Copy the per-layer diagnostics of the last call to the host.  Synchronises `stream`. */
+int psgd_status(psgd_ctx *ctx, void *workspace, void *stream, int layer, psgd_layer_status *out);
+
+/* Algorithmic HBM bytes of one psgd_compress over all layers: sum over layers of
+ * rows*cols*(N*sizeof(G) + 16) plus the thin matrices (see the design notes for the model). */
+double psgd_algorithmic_bytes(const psgd_ctx *ctx);
+
+/* Plain device copy kernel (dst <- src, n_bytes multiple of 16) used to calibrate profiler counters
+ * and to measure the attainable copy bandwidth with the same launch machinery. */
+int psgd_copy_bytes(void *stream, void *dst, const void *src, size_t n_bytes);
+
+int psgd_last_hip_error(const psgd_ctx *ctx);
+const char *psgd_strerror(int code);
+void psgd_destroy(psgd_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PSGD_H_ */

@@ -1,0 +1,542 @@
+// Host side of the C ABI declared in include/psgd.h: argument checks, launch planning, workspace
+// layout, pointer-table upload, and the sequences of batched launches that make up one SSP-Comp
+// step, one SVD-Comp step (Algorithm 1) and the reconstruction.
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/psgd.h"
+#include "psgd_dev.h"
+
+namespace psgd {
+hipError_t launch_prod(int nb, bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
+                       int max_tiles, hipStream_t st);
+hipError_t launch_outer(int nb, bool decomp, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                        void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
+                       hipStream_t st);
+hipError_t launch_reduce(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int cp,
+                         hipStream_t st);
+hipError_t launch_gram(const LayerDev* layers, const int* ids, int n_ids, int w, int role, hipStream_t st);
+hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2,
+                       int accumulate_status, hipStream_t st);
+hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w_in, int w_out,
+                        int src_role, int dst_role, int upper, hipStream_t st);
+hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
+                             int src_role, int warm, uint32_t seed, hipStream_t st);
+hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
+                         hipStream_t st);
+hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t st);
+}  // namespace psgd
+
+using namespace psgd;
+
+namespace {
+
+constexpr int kMaxWidth = 192;      // widest thin block (packed Cholesky factor must fit in LDS)
+constexpr int kTargetTiles = 1024;  // workgroups per product launch we try to reach by splitting the reduction
+constexpr int kMaxSplit = 32;
+
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+struct Plan {            // host copy of what a layer needs
+    psgd_layer_desc d;
+    int transposed;
+    int rowsP, colsP;
+    int m, n;
+};
+
+struct Lists {
+    std::vector<int> norm, tr;   // layer ids stored row-major as logical / as the transpose
+};
+
+}  // namespace
+
+struct psgd_ctx {
+    int n_layers = 0;
+    int n_workers = 0;
+    psgd_options opt{};
+    std::vector<Plan> plan;
+    Lists lists;
+    int rmax = 0;
+    int cpc = 0;     // packed width of the compress step: 32 * ceil(rmax / 32)
+    int wz = 0;      // block width of the subspace iteration
+    // batched splits
+    int split_row_b = 1, split_col_b = 1;
+    // workspace layout (byte offsets)
+    size_t off_layers = 0, off_ids = 0, off_gtab = 0, off_outs = 0, off_single_part[2] = {0, 0};
+    std::vector<size_t> off_layer;   // start of each layer's private region
+    size_t ws_bytes = 0;
+    size_t max_part_single[2] = {0, 0};
+    // cached tables
+    void* bound_ws = nullptr;
+    bool tables_valid = false;
+    std::vector<const void*> hG;
+    std::vector<float*> hE, hQ, hP;
+    std::vector<void*> hOut;
+    std::vector<int> hIds;
+    std::vector<LayerDev> hLayers;   // n_layers + 1 (last = scratch descriptor of single-layer calls)
+    int last_hip = 0;
+    double algo_bytes = 0.0;
+};
+
+namespace {
+
+int fail_hip(psgd_ctx* c, hipError_t e) {
+    c->last_hip = (int)e;
+    return PSGD_E_HIP;
+}
+
+#define PSGD_TRY(expr)                                   \
+    do {                                                 \
+        hipError_t e__ = (expr);                         \
+        if (e__ != hipSuccess) return fail_hip(ctx, e__); \
+    } while (0)
+
+struct LayerRegion {
+    size_t part[2], pack[2][4], z[2], gram, tmat, evec, jwork, eval, status, end;
+};
+
+// byte layout of one layer's private workspace region, relative to its start
+LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
+    LayerRegion R{};
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
+    const int lenP[2] = {p.rowsP, p.colsP};
+    const int split[2] = {c->split_row_b, c->split_col_b};
+    for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
+    for (int s = 0; s < 2; ++s)
+        for (int k = 0; k < 4; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->wz * sizeof(bf16_t));
+    const int len[2] = {(int)p.d.rows, (int)p.d.cols};
+    for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
+    const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
+    R.gram = take((size_t)kMaxGramSplit * w2 * sizeof(double));
+    R.tmat = take(w2 * sizeof(double));
+    R.evec = take(w2 * sizeof(double));
+    R.jwork = take(w2 * sizeof(double));
+    R.eval = take((size_t)(c->wz + 2) * sizeof(double));
+    R.status = take(4 * sizeof(int));
+    R.end = o;
+    return R;
+}
+
+int choose_split(int64_t base_tiles, int min_chunks) {
+    if (base_tiles >= kTargetTiles) return 1;
+    int64_t s = (kTargetTiles + base_tiles - 1) / base_tiles;
+    if (s > kMaxSplit) s = kMaxSplit;
+    if (s > min_chunks) s = min_chunks;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
+    const Plan& p = c->plan[l];
+    const LayerRegion R = layer_region(c, p);
+    char* base = ws + c->off_layer[l];
+    LayerDev L{};
+    L.rows = (int)p.d.rows; L.cols = (int)p.d.cols; L.ld = p.d.ld; L.r = p.d.r; L.wz = c->wz;
+    L.gdt = p.d.grad_dtype; L.n_workers = c->n_workers; L.transposed = p.transposed;
+    L.rowsP = p.rowsP; L.colsP = p.colsP;
+    L.split_row = c->split_row_b; L.split_col = c->split_col_b;
+    L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab) + (size_t)l * c->n_workers;
+    L.S = c->hE.empty() ? nullptr : c->hE[l];
+    const int side_p = side_of_role(p.transposed, ROLE_P), side_q = side_of_role(p.transposed, ROLE_Q);
+    L.thin[ROLE_P] = ThinRef{c->hP.empty() ? nullptr : c->hP[l], p.d.r, p.d.r};
+    L.thin[ROLE_Q] = ThinRef{c->hQ.empty() ? nullptr : c->hQ[l], p.d.r, p.d.r};
+    L.thin[ROLE_ZP] = ThinRef{reinterpret_cast<float*>(base + R.z[side_p]), c->wz, c->wz};
+    L.thin[ROLE_ZQ] = ThinRef{reinterpret_cast<float*>(base + R.z[side_q]), c->wz, c->wz};
+    for (int s = 0; s < 2; ++s) {
+        L.part[s] = reinterpret_cast<float*>(base + R.part[s]);
+        L.pack[s].n_hi = reinterpret_cast<bf16_t*>(base + R.pack[s][0]);
+        L.pack[s].n_lo = reinterpret_cast<bf16_t*>(base + R.pack[s][1]);
+        L.pack[s].t_hi = reinterpret_cast<bf16_t*>(base + R.pack[s][2]);
+        L.pack[s].t_lo = reinterpret_cast<bf16_t*>(base + R.pack[s][3]);
+    }
+    L.gram = reinterpret_cast<double*>(base + R.gram);
+    L.tmat = reinterpret_cast<double*>(base + R.tmat);
+    L.evec = reinterpret_cast<double*>(base + R.evec);
+    L.jwork = reinterpret_cast<double*>(base + R.jwork);
+    L.eval = reinterpret_cast<double*>(base + R.eval);
+    L.status = reinterpret_cast<int*>(base + R.status);
+    *out = L;
+}
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Refresh the cached host tables from the caller's; returns true when the device copy is stale.
+template <typename T, typename U>
+bool sync_table(std::vector<T>& cache, U const* user, size_t n) {
+    if (!user) return false;
+    bool changed = cache.size() != n;
+    if (changed) cache.assign(n, nullptr);
+    for (size_t i = 0; i < n; ++i)
+        if (cache[i] != (T)user[i]) { cache[i] = (T)user[i]; changed = true; }
+    return changed;
+}
+
+int check_table(const void* const* tab, size_t n) {
+    if (!tab) return PSGD_E_INVALID_ARG;
+    for (size_t i = 0; i < n; ++i) {
+        if (!tab[i]) return PSGD_E_INVALID_ARG;
+        if (!aligned16(tab[i])) return PSGD_E_ALIGN;
+    }
+    return PSGD_OK;
+}
+
+// Upload descriptors, id lists and pointer tables when anything they hold has changed.
+int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool force) {
+    char* ws = reinterpret_cast<char*>(workspace);
+    if (!force && ctx->tables_valid && ctx->bound_ws == workspace) return PSGD_OK;
+    const int nl = ctx->n_layers;
+    ctx->hLayers.resize(nl + 1);
+    for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, &ctx->hLayers[l]);
+    ctx->hLayers[nl] = ctx->hLayers[0];
+    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers, ctx->hLayers.data(), (size_t)(nl + 1) * sizeof(LayerDev),
+                            hipMemcpyHostToDevice, st));
+    std::vector<int>& ids = ctx->hIds;
+    ids.assign(3 * (size_t)nl + 1, 0);
+    for (int l = 0; l < nl; ++l) ids[l] = l;
+    for (size_t i = 0; i < ctx->lists.norm.size(); ++i) ids[nl + i] = ctx->lists.norm[i];
+    for (size_t i = 0; i < ctx->lists.tr.size(); ++i) ids[2 * (size_t)nl + i] = ctx->lists.tr[i];
+    ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
+    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    if (!ctx->hG.empty())
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab, ctx->hG.data(), ctx->hG.size() * sizeof(void*),
+                                hipMemcpyHostToDevice, st));
+    ctx->bound_ws = workspace;
+    ctx->tables_valid = true;
+    return PSGD_OK;
+}
+
+struct Launcher {
+    psgd_ctx* ctx;
+    char* ws;
+    hipStream_t st;
+    const LayerDev* layers;
+    const int *ids_all, *ids_norm, *ids_tr;
+    int n_all, n_norm, n_tr;
+    // geometry maxima over the layers addressed by this launcher
+    int max_rows = 0, max_cols = 0, max_rowsP = 0, max_colsP = 0;
+    int tiles_row = 0, tiles_col = 0, tiles_outer = 0;
+    hipError_t err = hipSuccess;
+
+    void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+    int max_len() const { return max_rows > max_cols ? max_rows : max_cols; }
+    int max_lenP() const { return max_rowsP > max_colsP ? max_rowsP : max_colsP; }
+
+    void pack(int role, int cp) { note(launch_pack(layers, ids_all, n_all, max_lenP(), role, cp, st)); }
+    void reduce(int role, int cp) { note(launch_reduce(layers, ids_all, n_all, max_len(), role, cp, st)); }
+    // product whose result is P-like (lives on the long side) or Q-like
+    void prod(bool p_like, bool form, int nb) {
+        // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
+        note(launch_prod(nb, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, st));
+        note(launch_prod(nb, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, st));
+    }
+    void orth(int role, int w, double tol2) {
+        for (int pass = 0; pass < 2; ++pass) {
+            note(launch_gram(layers, ids_all, n_all, w, role, st));
+            note(launch_chol(layers, ids_all, n_all, w, role, tol2, pass, st));
+            note(launch_apply(layers, ids_all, n_all, max_len(), w, w, role, role, 1, st));
+        }
+    }
+    void residual(int nb) { note(launch_outer(nb, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st)); }
+};
+
+void geometry(const psgd_ctx* c, int l, int split_row, int split_col, Launcher& L) {
+    const Plan& p = c->plan[l];
+    auto mx = [](int& a, int b) { if (b > a) a = b; };
+    mx(L.max_rows, (int)p.d.rows); mx(L.max_cols, (int)p.d.cols);
+    mx(L.max_rowsP, p.rowsP); mx(L.max_colsP, p.colsP);
+    mx(L.tiles_row, (int)((p.d.rows + 127) / 128) * split_row);
+    mx(L.tiles_col, (int)((p.d.cols + 127) / 128) * split_col);
+    mx(L.tiles_outer, (int)((p.d.rows + 127) / 128) * (int)((p.d.cols + 127) / 128));
+}
+
+Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
+    Launcher L{};
+    L.ctx = ctx; L.ws = reinterpret_cast<char*>(workspace); L.st = st;
+    L.layers = reinterpret_cast<const LayerDev*>(L.ws + ctx->off_layers);
+    const int nl = ctx->n_layers;
+    const int* ids = reinterpret_cast<const int*>(L.ws + ctx->off_ids);
+    L.ids_all = ids; L.ids_norm = ids + nl; L.ids_tr = ids + 2 * (size_t)nl;
+    L.n_all = nl; L.n_norm = (int)ctx->lists.norm.size(); L.n_tr = (int)ctx->lists.tr.size();
+    for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, L);
+    return L;
+}
+
+double tol2_of(const psgd_ctx* c) {
+    const double t = c->opt.rank_tol > 0.f ? (double)c->opt.rank_tol : 1e-5;
+    return t * t;
+}
+
+// Block subspace iteration + Rayleigh-Ritz for the layers of `L`: leaves P~ (Ritz vectors of the r
+// largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
+void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out) {
+    const int wz = ctx->wz, nbz = wz / 32;
+    const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 8;
+    const double tol2 = tol2_of(ctx);
+    L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
+                             ctx->opt.seed, L.st));
+    for (int it = 0; it < iters; ++it) {
+        L.pack(ROLE_ZQ, wz);
+        L.prod(true, form_first && it == 0, nbz);     // Z = M Y
+        L.reduce(ROLE_ZP, wz);
+        L.orth(ROLE_ZP, wz, tol2);
+        L.pack(ROLE_ZP, wz);
+        L.prod(false, false, nbz);                    // Y = M^T Z
+        L.reduce(ROLE_ZQ, wz);
+        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2);
+    }
+    L.note(launch_gram(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, L.st));
+    L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
+    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZP, ROLE_P, 0, L.st));
+    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, 0, L.st));
+}
+
+}  // namespace
+
+extern "C" {
+
+int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n_workers, const psgd_options* opt) {
+    if (!out) return PSGD_E_INVALID_ARG;
+    *out = nullptr;
+    if (!layers || n_layers < 1 || n_layers > 65535 || n_workers < 1 || n_workers > 4096) return PSGD_E_INVALID_ARG;
+    psgd_ctx* c = new (std::nothrow) psgd_ctx();
+    if (!c) return PSGD_E_NOMEM;
+    c->n_layers = n_layers;
+    c->n_workers = n_workers;
+    if (opt) c->opt = *opt;
+    else { c->opt = psgd_options{}; c->opt.refresh_warm_start = 1; c->opt.refresh_oversample = -1; c->opt.seed = 0x5eed5eedu; }
+    int rc = PSGD_OK;
+    int rmax = 0;
+    c->plan.resize(n_layers);
+    for (int l = 0; l < n_layers && rc == PSGD_OK; ++l) {
+        psgd_layer_desc d = layers[l];
+        if (d.rows < 1 || d.cols < 1 || d.rows > (1 << 24) || d.cols > (1 << 24)) { rc = PSGD_E_SHAPE; break; }
+        if (d.r < 1 || d.r > d.rows || d.r > d.cols) { rc = PSGD_E_SHAPE; break; }
+        if (d.grad_dtype != PSGD_F32 && d.grad_dtype != PSGD_BF16) { rc = PSGD_E_INVALID_ARG; break; }
+        if (d.ld == 0) d.ld = d.cols;
+        if (d.ld < d.cols || d.ld % 8 != 0) { rc = PSGD_E_ALIGN; break; }
+        Plan& p = c->plan[l];
+        p.d = d;
+        p.transposed = d.rows < d.cols ? 1 : 0;
+        p.rowsP = (int)round_up(d.rows, kLenPad);
+        p.colsP = (int)round_up(d.cols, kLenPad);
+        p.m = (int)(d.rows >= d.cols ? d.rows : d.cols);
+        p.n = (int)(d.rows >= d.cols ? d.cols : d.rows);
+        (p.transposed ? c->lists.tr : c->lists.norm).push_back(l);
+        if (d.r > rmax) rmax = d.r;
+    }
+    if (rc == PSGD_OK) {
+        c->rmax = rmax;
+        c->cpc = (int)round_up(rmax, 32);
+        int over = c->opt.refresh_oversample;
+        if (over < 0) over = 8;
+        c->wz = (int)round_up(rmax + over, 32);
+        int nmin = c->plan[0].n;
+        for (auto& p : c->plan) if (p.n < nmin) nmin = p.n;
+        while (c->wz > 32 && c->wz > nmin && c->wz - 32 >= rmax) c->wz -= 32;   // block no wider than the matrix
+        if (c->wz > kMaxWidth || c->cpc > kMaxWidth) rc = PSGD_E_SHAPE;
+    }
+    if (rc != PSGD_OK) { delete c; return rc; }
+    // reduction splits of the batched launches
+    int64_t base_row = 0, base_col = 0;
+    int min_chunks_row = 1 << 30, min_chunks_col = 1 << 30;
+    for (auto& p : c->plan) {
+        base_row += (p.d.rows + 127) / 128;
+        base_col += (p.d.cols + 127) / 128;
+        const int cr = (int)((p.d.cols + 63) / 64), cc = (int)((p.d.rows + 63) / 64);
+        if (cr < min_chunks_row) min_chunks_row = cr;
+        if (cc < min_chunks_col) min_chunks_col = cc;
+    }
+    c->split_row_b = choose_split(base_row, min_chunks_row);
+    c->split_col_b = choose_split(base_col, min_chunks_col);
+    // workspace layout
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
+    c->off_layers = take((size_t)(n_layers + 1) * sizeof(LayerDev));
+    c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
+    c->off_gtab = take((size_t)n_layers * n_workers * sizeof(void*));
+    c->off_outs = take((size_t)n_layers * sizeof(void*));
+    int max_rowsP = 0, max_colsP = 0;
+    for (auto& p : c->plan) { if (p.rowsP > max_rowsP) max_rowsP = p.rowsP; if (p.colsP > max_colsP) max_colsP = p.colsP; }
+    c->off_single_part[0] = take((size_t)kMaxSplit * max_rowsP * c->wz * sizeof(float));
+    c->off_single_part[1] = take((size_t)kMaxSplit * max_colsP * c->wz * sizeof(float));
+    c->off_layer.resize(n_layers);
+    double bytes = 0.0;
+    for (int l = 0; l < n_layers; ++l) {
+        c->off_layer[l] = o;
+        o += layer_region(c, c->plan[l]).end;
+        const Plan& p = c->plan[l];
+        const double sg = p.d.grad_dtype == PSGD_BF16 ? 2.0 : 4.0;
+        // two passes separated by the global QR: either M is stored between them (N*sg + 16 bytes
+        // per element) or formed twice from the gradients (2*N*sg + 12); the smaller one counts
+        const double a = n_workers * sg + 16.0, b = 2.0 * n_workers * sg + 12.0;
+        bytes += (double)p.d.rows * (double)p.d.cols * (a < b ? a : b);
+        bytes += 4.0 * 4.0 * (double)(p.d.rows + p.d.cols) * p.d.r;
+    }
+    c->ws_bytes = o;
+    c->algo_bytes = bytes;
+    *out = c;
+    return PSGD_OK;
+}
+
+size_t psgd_workspace_bytes(const psgd_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+double psgd_algorithmic_bytes(const psgd_ctx* ctx) { return ctx ? ctx->algo_bytes : 0.0; }
+
+static int bind_common(psgd_ctx* ctx, void* workspace, hipStream_t st, const void* const* G, float* const* E,
+                       float* const* Q, float* const* P) {
+    if (!ctx || !workspace) return PSGD_E_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return PSGD_E_ALIGN;
+    const size_t nl = (size_t)ctx->n_layers;
+    int rc;
+    if (G && (rc = check_table(G, nl * ctx->n_workers)) != PSGD_OK) return rc;
+    if (E && (rc = check_table(reinterpret_cast<const void* const*>(E), nl)) != PSGD_OK) return rc;
+    if (Q && (rc = check_table(reinterpret_cast<const void* const*>(Q), nl)) != PSGD_OK) return rc;
+    if (P && (rc = check_table(reinterpret_cast<const void* const*>(P), nl)) != PSGD_OK) return rc;
+    bool changed = false;
+    changed |= sync_table(ctx->hG, G, nl * ctx->n_workers);
+    changed |= sync_table(ctx->hE, E, nl);
+    changed |= sync_table(ctx->hQ, Q, nl);
+    changed |= sync_table(ctx->hP, P, nl);
+    return upload_tables(ctx, workspace, st, changed);
+}
+
+int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* const* G, float* const* E,
+                  float* const* Q, float* const* P) {
+    if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, G, E, Q, P);
+    if (rc != PSGD_OK) return rc;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_Q, cp);
+    L.prod(true, true, nb);          // P = M Q_{t-1}, M formed and stored on the way
+    L.reduce(ROLE_P, cp);
+    L.orth(ROLE_P, ctx->rmax, tol2_of(ctx));
+    L.pack(ROLE_P, cp);
+    L.prod(false, false, nb);        // Q_t = M^T P~
+    L.reduce(ROLE_Q, cp);
+    L.pack(ROLE_Q, cp);
+    L.residual(nb);                  // E <- M - P~ Q_t^T
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const void* const* G, float* const* E,
+                          float* const* Q, float* const* P) {
+    if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, G, E, Q, P);
+    if (rc != PSGD_OK) return rc;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_P, cp);
+    L.pack(ROLE_Q, cp);
+    L.residual(nb);
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const float* M, float* P, float* Q,
+                 float* sigma) {
+    if (!ctx || !workspace || !M || !P || !Q) return PSGD_E_INVALID_ARG;
+    if (layer < 0 || layer >= ctx->n_layers) return PSGD_E_INVALID_ARG;
+    if (!aligned16(M) || !aligned16(P) || !aligned16(Q)) return PSGD_E_ALIGN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, nullptr, nullptr, nullptr, nullptr);
+    if (rc != PSGD_OK) return rc;
+    char* ws = reinterpret_cast<char*>(workspace);
+    const Plan& p = ctx->plan[layer];
+    // scratch descriptor: this layer's private regions, the caller's M/P/Q, splits sized for one layer
+    LayerDev D;
+    build_layer_dev(ctx, ws, layer, &D);
+    D.S = const_cast<float*>(M);
+    D.thin[ROLE_P].ptr = P;
+    D.thin[ROLE_Q].ptr = Q;
+    D.split_row = choose_split((p.d.rows + 127) / 128, (int)((p.d.cols + 63) / 64));
+    D.split_col = choose_split((p.d.cols + 127) / 128, (int)((p.d.rows + 63) / 64));
+    D.part[0] = reinterpret_cast<float*>(ws + ctx->off_single_part[0]);
+    D.part[1] = reinterpret_cast<float*>(ws + ctx->off_single_part[1]);
+    ctx->hLayers[ctx->n_layers] = D;
+    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev),
+                            hipMemcpyHostToDevice, st));
+    Launcher L{};
+    L.ctx = ctx; L.ws = ws; L.st = st;
+    L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers);
+    const int* ids = reinterpret_cast<const int*>(ws + ctx->off_ids) + 3 * (size_t)ctx->n_layers;
+    L.ids_all = ids; L.n_all = 1;
+    L.ids_norm = ids; L.n_norm = p.transposed ? 0 : 1;
+    L.ids_tr = ids; L.n_tr = p.transposed ? 1 : 0;
+    geometry(ctx, layer, D.split_row, D.split_col, L);
+    refresh_sequence(ctx, L, false, false, sigma);
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
+                    void* const* out, int out_dtype) {
+    if (!ctx || !P || !Q || !out) return PSGD_E_INVALID_ARG;
+    if (out_dtype != PSGD_F32 && out_dtype != PSGD_BF16) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = check_table(reinterpret_cast<const void* const*>(out), (size_t)ctx->n_layers);
+    if (rc != PSGD_OK) return rc;
+    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    if (rc != PSGD_OK) return rc;
+    char* ws = reinterpret_cast<char*>(workspace);
+    sync_table(ctx->hOut, out, (size_t)ctx->n_layers);
+    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*),
+                                hipMemcpyHostToDevice, st));
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_P, cp);
+    L.pack(ROLE_Q, cp);
+    L.note(launch_outer(nb, true, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+                        reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_status(psgd_ctx* ctx, void* workspace, void* stream, int layer, psgd_layer_status* out) {
+    if (!ctx || !workspace || !out || layer < 0 || layer >= ctx->n_layers) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    PSGD_TRY(hipStreamSynchronize(st));
+    char* ws = reinterpret_cast<char*>(workspace);
+    const LayerRegion R = layer_region(ctx, ctx->plan[layer]);
+    int raw[4] = {0, 0, 0, 0};
+    PSGD_TRY(hipMemcpy(raw, ws + ctx->off_layer[layer] + R.status, sizeof(raw), hipMemcpyDeviceToHost));
+    out->rank_deficient = raw[0];
+    out->reserved = 0;
+    std::memcpy(&out->sigma_max, &raw[2], sizeof(float));
+    std::memcpy(&out->sigma_r, &raw[3], sizeof(float));
+    return PSGD_OK;
+}
+
+int psgd_copy_bytes(void* stream, void* dst, const void* src, size_t n_bytes) {
+    if (!dst || !src || (n_bytes & 15u) || !aligned16(dst) || !aligned16(src)) return PSGD_E_INVALID_ARG;
+    hipError_t e = launch_copy(dst, src, n_bytes, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PSGD_OK : PSGD_E_HIP;
+}
+
+int psgd_last_hip_error(const psgd_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+const char* psgd_strerror(int code) {
+    switch (code) {
+        case PSGD_OK: return "ok";
+        case PSGD_E_INVALID_ARG: return "invalid argument";
+        case PSGD_E_SHAPE: return "unsupported shape or rank";
+        case PSGD_E_ALIGN: return "leading dimension or pointer alignment";
+        case PSGD_E_HIP: return "HIP runtime error";
+        case PSGD_E_NOMEM: return "out of host memory";
+        default: return "unknown error";
+    }
+}
+
+void psgd_destroy(psgd_ctx* ctx) { delete ctx; }
+
+}  // extern "C"

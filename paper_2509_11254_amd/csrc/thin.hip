@@ -1,0 +1,552 @@
+// Kernels on the thin (len x w) matrices of the compressor: operand packing, reduction of the
+// split products, the orthonormaliser, the Rayleigh-Ritz step of the refresh, random start blocks.
+//
+// Orthonormalisation (Section 2, "QR decomposition": Q-factor of the economic QR) is CholeskyQR2:
+//   G = X^T X (fp64, exact products of the fp32 entries);  G_s = D G D with D = diag(G)^{-1/2};
+//   G_s = R_s^T R_s (Cholesky, fp64);  X <- X (D R_s^{-1});  then the same once more on the result.
+// The Q-factor it converges to is the one with a positive diagonal of R.  A pivot of the scaled
+// Cholesky at step k equals (norm of column k's part orthogonal to the earlier columns / norm of
+// column k)^2; if it is <= rank_tol^2 the column is declared dependent and its P~ column is zero.
+#include "psgd_dev.h"
+
+namespace psgd {
+
+// --------------------------------------------------------------------------------------------
+// pack: thin fp32 (len x width, ld) -> split-bf16 operand copies, row-major and transposed.
+// --------------------------------------------------------------------------------------------
+__device__ inline void split_bf16_t(float x, bf16_t& hi, bf16_t& lo) {
+    hi = (bf16_t)x;
+    lo = (bf16_t)(x - (float)hi);
+}
+
+__global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restrict__ layers,
+                                                        const int* __restrict__ ids, int role, int cp) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int side = side_of_role(L.transposed, role);
+    const int len = side_len(L, side), lenP = side_lenP(L, side);
+    const int i0 = blockIdx.x * 64;
+    if (i0 >= lenP) return;
+    const ThinRef T = L.thin[role];
+    const PackRef K = L.pack[side];
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* tile = reinterpret_cast<float*>(smem);      // [64][cp + 1]
+    const int tw = cp + 1;
+    for (int e = threadIdx.x; e < 64 * cp; e += kThreads) {
+        const int i = e / cp, c = e % cp;
+        float v = 0.f;
+        if (i0 + i < len && c < T.width) v = T.ptr[(int64_t)(i0 + i) * T.ld + c];
+        tile[i * tw + c] = v;
+    }
+    __syncthreads();
+    // row-major copies: one 16-byte vector = 8 consecutive columns of one row
+    for (int v = threadIdx.x; v < 64 * (cp / 8); v += kThreads) {
+        const int i = v / (cp / 8), c0 = 8 * (v % (cp / 8));
+        bf16x8 h, l;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            bf16_t hh, ll;
+            split_bf16_t(tile[i * tw + c0 + u], hh, ll);
+            h[u] = hh; l[u] = ll;
+        }
+        const int64_t off = (int64_t)(i0 + i) * cp + c0;
+        *reinterpret_cast<bf16x8*>(K.n_hi + off) = h;
+        *reinterpret_cast<bf16x8*>(K.n_lo + off) = l;
+    }
+    // transposed copies: one vector = 8 consecutive rows of one column
+    for (int v = threadIdx.x; v < cp * 8; v += kThreads) {
+        const int c = v >> 3, ib = 8 * (v & 7);
+        bf16x8 h, l;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            bf16_t hh, ll;
+            split_bf16_t(tile[(ib + u) * tw + c], hh, ll);
+            h[u] = hh; l[u] = ll;
+        }
+        const int64_t off = (int64_t)c * lenP + i0 + ib;
+        *reinterpret_cast<bf16x8*>(K.t_hi + off) = h;
+        *reinterpret_cast<bf16x8*>(K.t_lo + off) = l;
+    }
+}
+
+hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
+                       hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    dim3 grid(max_lenP / 64, n_ids), block(kThreads);
+    const size_t lds = (size_t)64 * (cp + 1) * sizeof(float);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pack_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(pack_kernel, grid, block, lds, st, layers, ids, role, cp);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// reduce: thin[role] <- sum over splits of the partial products (fixed order: deterministic).
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void reduce_kernel(const LayerDev* __restrict__ layers,
+                                                          const int* __restrict__ ids, int role, int cp) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int side = side_of_role(L.transposed, role);
+    const int len = side_len(L, side), lenP = side_lenP(L, side);
+    const int n_split = side == SIDE_L ? L.split_row : L.split_col;
+    const ThinRef T = L.thin[role];
+    const float* __restrict__ part = L.part[side];
+    const int64_t total = (int64_t)len * cp;
+    const int64_t plane = (int64_t)lenP * cp;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
+        const int i = (int)(e / cp), c = (int)(e % cp);
+        if (c >= T.width) continue;
+        float s = 0.f;
+        for (int sp = 0; sp < n_split; ++sp) s += part[sp * plane + e];
+        T.ptr[(int64_t)i * T.ld + c] = s;
+    }
+}
+
+hipError_t launch_reduce(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int cp,
+                         hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    const int64_t total = (int64_t)max_len * cp;
+    int gx = (int)((total + kThreads * 4 - 1) / (kThreads * 4));
+    if (gx < 1) gx = 1;
+    dim3 grid(gx, n_ids), block(kThreads);
+    hipLaunchKernelGGL(reduce_kernel, grid, block, 0, st, layers, ids, role, cp);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// gram: partial Gram matrices X^T X in fp64.  blockIdx.x = split + kMaxGramSplit * block_pair,
+// block pairs (bi <= bj) of 64-wide column blocks; gram[split][i*w + j] is written for i in block
+// bi, j in block bj (the strict lower triangle of the matrix of blocks is never written or read).
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void gram_kernel(const LayerDev* __restrict__ layers,
+                                                        const int* __restrict__ ids, int role) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int side = side_of_role(L.transposed, role);
+    const int len = side_len(L, side);
+    const ThinRef T = L.thin[role];
+    const int w = T.width;
+    const int nblk = (w + 63) / 64;
+    const int sp = blockIdx.x % kMaxGramSplit;
+    int bp = blockIdx.x / kMaxGramSplit;
+    if (bp >= nblk * (nblk + 1) / 2) return;
+    int bi = 0;
+    while (bp >= nblk - bi) { bp -= nblk - bi; ++bi; }
+    const int bj = bi + bp;
+    int rows_per = (len + kMaxGramSplit - 1) / kMaxGramSplit;
+    rows_per = (rows_per + 63) / 64 * 64;
+    const int r0 = sp * rows_per, r1 = min(len, r0 + rows_per);
+
+    __shared__ float sa[64][65];
+    __shared__ float sb[64][65];
+    const int ti = threadIdx.x >> 4, tj = threadIdx.x & 15;
+    double acc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
+    for (int rt = r0; rt < r1; rt += 64) {
+        for (int e = threadIdx.x; e < 64 * 64; e += kThreads) {
+            const int i = e >> 6, c = e & 63;
+            const int row = rt + i;
+            float va = 0.f, vb = 0.f;
+            if (row < r1) {
+                const float* xr = T.ptr + (int64_t)row * T.ld;
+                if (bi * 64 + c < w) va = xr[bi * 64 + c];
+                if (bj * 64 + c < w) vb = xr[bj * 64 + c];
+            }
+            sa[i][c] = va;
+            sb[i][c] = vb;
+        }
+        __syncthreads();
+        for (int i = 0; i < 64; ++i) {
+            double av[4], bv[4];
+#pragma unroll
+            for (int a = 0; a < 4; ++a) av[a] = (double)sa[i][ti + 16 * a];
+#pragma unroll
+            for (int b = 0; b < 4; ++b) bv[b] = (double)sb[i][tj + 16 * b];
+#pragma unroll
+            for (int a = 0; a < 4; ++a)
+#pragma unroll
+                for (int b = 0; b < 4; ++b) acc[a][b] += av[a] * bv[b];
+        }
+        __syncthreads();
+    }
+    double* __restrict__ g = L.gram + (int64_t)sp * w * w;
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const int i = bi * 64 + ti + 16 * a, j = bj * 64 + tj + 16 * b;
+            if (i < w && j < w) g[(int64_t)i * w + j] = acc[a][b];
+        }
+}
+
+hipError_t launch_gram(const LayerDev* layers, const int* ids, int n_ids, int w, int role, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    const int nblk = (w + 63) / 64;
+    dim3 grid(kMaxGramSplit * nblk * (nblk + 1) / 2, n_ids), block(kThreads);
+    hipLaunchKernelGGL(gram_kernel, grid, block, 0, st, layers, ids, role);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// chol: one workgroup per layer.  Sums the partial Gram matrices, scales to unit diagonal,
+// Cholesky-factorises (upper, packed in LDS), inverts the factor and writes tmat = D R_s^{-1}.
+// --------------------------------------------------------------------------------------------
+__device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)) / 2 + (j - i); }   // i <= j
+
+__global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
+                                                        const int* __restrict__ ids, int role, double tol2,
+                                                        int accumulate_status) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int w = L.thin[role].width;
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* a = reinterpret_cast<double*>(smem);          // packed upper triangle, w(w+1)/2
+    double* dsc = a + (w * (w + 1)) / 2;                  // [w] scaling
+    int* bad = reinterpret_cast<int*>(dsc + w);           // [w] dependent-column flags
+    const int t = threadIdx.x;
+    const int ntri = (w * (w + 1)) / 2;
+    // sum of partials (fixed order)
+    for (int i = 0; i < w; ++i)
+        for (int j = i + t; j < w; j += kThreads) {
+            double s = 0.0;
+            for (int sp = 0; sp < kMaxGramSplit; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)i * w + j];
+            a[tri_idx(i, j, w)] = s;
+        }
+    __syncthreads();
+    for (int i = t; i < w; i += kThreads) {
+        const double d = a[tri_idx(i, i, w)];
+        dsc[i] = d > 0.0 ? 1.0 / sqrt(d) : 0.0;
+        bad[i] = d > 0.0 ? 0 : 1;
+    }
+    __syncthreads();
+    for (int i = 0; i < w; ++i)
+        for (int j = i + t; j < w; j += kThreads) a[tri_idx(i, j, w)] *= dsc[i] * dsc[j];
+    __syncthreads();
+    // right-looking Cholesky, A = R^T R, R overwrites the upper triangle
+    for (int k = 0; k < w; ++k) {
+        const double piv = a[tri_idx(k, k, w)];
+        const bool dep = bad[k] || !(piv > tol2);
+        __syncthreads();
+        if (dep) {
+            if (t == 0) bad[k] = 1;
+            for (int j = k + t; j < w; j += kThreads) a[tri_idx(k, j, w)] = (j == k) ? 1.0 : 0.0;
+        } else {
+            const double rkk = sqrt(piv);
+            for (int j = k + t; j < w; j += kThreads) a[tri_idx(k, j, w)] = (j == k) ? rkk : a[tri_idx(k, j, w)] / rkk;
+        }
+        __syncthreads();
+        if (!dep) {
+            const int nrem = w - k - 1;
+            for (int e = t; e < nrem * nrem; e += kThreads) {
+                const int i = k + 1 + e / nrem, j = k + 1 + e % nrem;
+                if (i <= j) a[tri_idx(i, j, w)] -= a[tri_idx(k, i, w)] * a[tri_idx(k, j, w)];
+            }
+        }
+        __syncthreads();
+    }
+    // inverse of the upper-triangular factor, one column per thread: T = R^{-1}
+    double* __restrict__ tm = L.tmat;
+    for (int j = t; j < w; j += kThreads) {
+        for (int i = w - 1; i > j; --i) tm[(int64_t)i * w + j] = 0.0;
+        tm[(int64_t)j * w + j] = 1.0 / a[tri_idx(j, j, w)];
+        for (int i = j - 1; i >= 0; --i) {
+            double s = 0.0;
+            for (int l = i + 1; l <= j; ++l) s += a[tri_idx(i, l, w)] * tm[(int64_t)l * w + j];
+            tm[(int64_t)i * w + j] = -s / a[tri_idx(i, i, w)];
+        }
+    }
+    __syncthreads();
+    // tmat = D T with the dependent columns zeroed
+    for (int e = t; e < w * w; e += kThreads) {
+        const int i = e / w, j = e % w;
+        tm[e] = bad[j] ? 0.0 : tm[e] * dsc[i];
+    }
+    if (t == 0) {
+        int nbad = 0;
+        for (int i = 0; i < w; ++i) nbad += bad[i];
+        L.status[0] = accumulate_status ? max(L.status[0], nbad) : nbad;
+    }
+    (void)ntri;
+}
+
+hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2,
+                       int accumulate_status, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    dim3 grid(1, n_ids), block(kThreads);
+    const size_t lds = (size_t)((w * (w + 1)) / 2 + w) * sizeof(double) + (size_t)w * sizeof(int);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chol_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, accumulate_status);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// apply: thin[dst] (len x w_out) <- thin[src] (len x w_in) * tmat[:, :w_out]   (fp64 accumulate);
+// w_in and w_out are the widths of the two thin matrices, tmat is w_in x w_in row-major.
+// In place (dst == src) is allowed: a workgroup reads its 64 rows completely before writing them.
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
+                                                         const int* __restrict__ ids, int src_role, int dst_role,
+                                                         int upper) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int side = side_of_role(L.transposed, src_role);
+    const int len = side_len(L, side);
+    const int i0 = blockIdx.x * 64;
+    if (i0 >= len) return;
+    const ThinRef X = L.thin[src_role];
+    const ThinRef Y = L.thin[dst_role];
+    const int w_in = X.width, w_out = Y.width;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* sx = reinterpret_cast<float*>(smem);     // [64][w_in + 1]
+    float* so = sx + 64 * (w_in + 1);               // [64][w_out + 1]
+    const int t = threadIdx.x;
+    for (int e = t; e < 64 * w_in; e += kThreads) {
+        const int i = e / w_in, c = e % w_in;
+        sx[i * (w_in + 1) + c] = (i0 + i < len) ? X.ptr[(int64_t)(i0 + i) * X.ld + c] : 0.f;
+    }
+    __syncthreads();
+    const int i = t & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const double* __restrict__ tm = L.tmat;
+    for (int c = wv; c < w_out; c += 4) {
+        double s = 0.0;
+        const int jmax = upper ? min(c + 1, w_in) : w_in;
+        for (int j = 0; j < jmax; ++j) s += (double)sx[i * (w_in + 1) + j] * tm[(int64_t)j * w_in + c];
+        so[i * (w_out + 1) + c] = (float)s;
+    }
+    __syncthreads();
+    for (int e = t; e < 64 * w_out; e += kThreads) {
+        const int ii = e / w_out, c = e % w_out;
+        if (i0 + ii < len) Y.ptr[(int64_t)(i0 + ii) * Y.ld + c] = so[ii * (w_out + 1) + c];
+    }
+}
+
+// w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
+hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w_in, int w_out,
+                        int src_role, int dst_role, int upper, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    dim3 grid((max_len + 63) / 64, n_ids), block(kThreads);
+    const size_t lds = (size_t)64 * (w_in + 1 + w_out + 1) * sizeof(float);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(apply_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, upper);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// start block of the subspace iteration: columns [0, n_copy) from thin[src_role] (warm start),
+// the others uniform in (-1, 1) from a counter-based hash of (seed, layer, row, column).
+// --------------------------------------------------------------------------------------------
+__device__ inline uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+
+__global__ __launch_bounds__(kThreads) void init_block_kernel(const LayerDev* __restrict__ layers,
+                                                              const int* __restrict__ ids, int dst_role,
+                                                              int src_role, int warm, uint32_t seed) {
+    const int lid = ids[blockIdx.y];
+    const LayerDev& L = layers[lid];
+    const int side = side_of_role(L.transposed, dst_role);
+    const int len = side_len(L, side);
+    const ThinRef Y = L.thin[dst_role];
+    const ThinRef X = L.thin[src_role];
+    const int n_copy = warm ? min(X.width, Y.width) : 0;
+    const int64_t total = (int64_t)len * Y.width;
+    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
+        const int i = (int)(e / Y.width), c = (int)(e % Y.width);
+        float v;
+        if (c < n_copy) {
+            v = X.ptr[(int64_t)i * X.ld + c];
+        } else {
+            uint32_t h = mix32(seed ^ mix32((uint32_t)lid * 0x9e3779b9u + 0x85ebca6bu));
+            h = mix32(h ^ mix32((uint32_t)i + 0x632be5abu) ^ mix32((uint32_t)c * 0xc2b2ae35u + 0x27d4eb2fu));
+            v = (float)(h >> 8) * (2.0f / 16777216.0f) - 1.0f;
+        }
+        Y.ptr[(int64_t)i * Y.ld + c] = v;
+    }
+}
+
+hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
+                             int src_role, int warm, uint32_t seed, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    const int64_t total = (int64_t)max_len * w;
+    int gx = (int)((total + kThreads * 4 - 1) / (kThreads * 4));
+    if (gx < 1) gx = 1;
+    dim3 grid(gx, n_ids), block(kThreads);
+    hipLaunchKernelGGL(init_block_kernel, grid, block, 0, st, layers, ids, dst_role, src_role, warm, seed);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// Rayleigh-Ritz: eigen-decomposition of the w x w Gram matrix H = Y^T Y (Y = M^T Z, Z orthonormal)
+// by cyclic two-sided Jacobi in fp64 with a round-robin ordering (w/2 disjoint rotations per round).
+// One workgroup per layer.  On exit tmat[:, k] is the eigenvector of the k-th largest eigenvalue,
+// so that P~ = Z tmat[:, :r] are the leading left singular vectors (Definition 3) and
+// Q = Y tmat[:, :r] = M^T P~.  status gets sigma_1 and sigma_r = sqrt(eigenvalue).
+// --------------------------------------------------------------------------------------------
+constexpr int kJacobiThreads = 1024;
+constexpr int kJacobiMaxSweeps = 30;
+
+__global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* __restrict__ layers,
+                                                                const int* __restrict__ ids, int role,
+                                                                int use_lds, float* __restrict__ sigma_out) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int w = L.thin[role].width;
+    const int n = (w + 1) & ~1;      // even size for the round-robin schedule (a zero row/column is added)
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* cs = reinterpret_cast<double*>(smem);      // [n/2] cos, [n/2] sin
+    int* pq = reinterpret_cast<int*>(cs + n);          // [n/2] p, [n/2] q
+    double* red = reinterpret_cast<double*>(pq + n);   // [2] reduction scratch
+    double* a = use_lds ? red + 2 : L.jwork;           // n x n working copy of H
+    double* v = use_lds ? a + n * n : L.evec;          // n x n accumulated rotations
+    const int t = threadIdx.x;
+    // H (symmetric) = sum of the partial Gram matrices; gram_kernel wrote the upper triangle
+    for (int e = t; e < n * n; e += kJacobiThreads) {
+        const int i = e / n, j = e % n;
+        double s = 0.0;
+        if (i < w && j < w) {
+            const int ii = min(i, j), jj = max(i, j);
+            for (int sp = 0; sp < kMaxGramSplit; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)ii * w + jj];
+        }
+        a[e] = s;
+        v[e] = (i == j) ? 1.0 : 0.0;
+    }
+    __syncthreads();
+
+    const int half = n / 2;
+    for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
+        // convergence: off-diagonal mass relative to the diagonal
+        if (t < 2) red[t] = 0.0;
+        __syncthreads();
+        double off = 0.0, dia = 0.0;
+        for (int e = t; e < n * n; e += kJacobiThreads) {
+            const int i = e / n, j = e % n;
+            const double x = a[e];
+            if (i == j) dia += x * x; else off += x * x;
+        }
+        for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
+        if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
+        __syncthreads();
+        const bool done = red[0] <= 1e-26 * red[1];
+        __syncthreads();
+        if (done) break;
+        for (int rd = 0; rd < n - 1; ++rd) {
+            if (t < half) {
+                int p, q;
+                if (t == 0) { p = n - 1; q = rd; }
+                else { p = (rd + t) % (n - 1); q = (rd - t + (n - 1)) % (n - 1); }
+                if (p > q) { const int tmp = p; p = q; q = tmp; }
+                const double app = a[p * n + p], aqq = a[q * n + q], apq = a[p * n + q];
+                double c = 1.0, s = 0.0;
+                if (fabs(apq) > 1e-300 && fabs(apq) > 1e-18 * sqrt(fabs(app * aqq))) {
+                    const double tau = (aqq - app) / (2.0 * apq);
+                    const double tt = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+                    c = 1.0 / sqrt(1.0 + tt * tt);
+                    s = tt * c;
+                }
+                cs[t] = c; cs[half + t] = s; pq[t] = p; pq[half + t] = q;
+            }
+            __syncthreads();
+            // rows: A <- J^T A
+            for (int e = t; e < half * n; e += kJacobiThreads) {
+                const int k = e / n, j = e % n;
+                const int p = pq[k], q = pq[half + k];
+                const double c = cs[k], s = cs[half + k];
+                const double x = a[p * n + j], y = a[q * n + j];
+                a[p * n + j] = c * x - s * y;
+                a[q * n + j] = s * x + c * y;
+            }
+            __syncthreads();
+            // columns: A <- A J, V <- V J
+            for (int e = t; e < half * n; e += kJacobiThreads) {
+                const int k = e / n, i = e % n;
+                const int p = pq[k], q = pq[half + k];
+                const double c = cs[k], s = cs[half + k];
+                const double x = a[i * n + p], y = a[i * n + q];
+                a[i * n + p] = c * x - s * y;
+                a[i * n + q] = s * x + c * y;
+                const double vx = v[i * n + p], vy = v[i * n + q];
+                v[i * n + p] = c * vx - s * vy;
+                v[i * n + q] = s * vx + c * vy;
+            }
+            __syncthreads();
+        }
+    }
+    // sort: rank of eigenvalue j = number of eigenvalues that come before it (ties by index)
+    double* __restrict__ tm = L.tmat;
+    for (int j = t; j < w; j += kJacobiThreads) {
+        const double lj = a[j * n + j];
+        int rank = 0;
+        for (int k = 0; k < w; ++k) {
+            const double lk = a[k * n + k];
+            rank += (lk > lj || (lk == lj && k < j)) ? 1 : 0;
+        }
+        pq[j] = rank;     // w <= n entries available
+        L.eval[rank] = lj;
+    }
+    __syncthreads();
+    for (int e = t; e < w * w; e += kJacobiThreads) {
+        const int i = e / w, j = e % w;
+        tm[(int64_t)i * w + pq[j]] = v[i * n + j];
+    }
+    __syncthreads();
+    __threadfence_block();
+    const int r = L.r;
+    for (int k = t; k < r; k += kJacobiThreads) {
+        const float sg = (float)sqrt(fmax(L.eval[k], 0.0));
+        if (sigma_out) sigma_out[k] = sg;
+        if (k == 0) L.status[2] = __float_as_int(sg);
+        if (k == r - 1) L.status[3] = __float_as_int(sg);
+    }
+}
+
+size_t jacobi_lds_bytes(int w, int use_lds) {
+    const int n = (w + 1) & ~1;
+    size_t b = (size_t)n * sizeof(double) + (size_t)n * sizeof(int) + 2 * sizeof(double);
+    if (use_lds) b += (size_t)2 * n * n * sizeof(double);
+    return b;
+}
+
+hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
+                         hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    const int use_lds = jacobi_lds_bytes(w, 1) <= 150 * 1024 ? 1 : 0;
+    const size_t lds = jacobi_lds_bytes(w, use_lds);
+    dim3 grid(1, n_ids), block(kJacobiThreads);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(jacobi_kernel, grid, block, lds, st, layers, ids, role, use_lds, sigma_out);
+    return hipGetLastError();
+}
+
+// plain copy, 16 bytes per thread per iteration (profiler calibration / attainable copy bandwidth)
+__global__ __launch_bounds__(kThreads) void copy_kernel(uint4* __restrict__ dst, const uint4* __restrict__ src,
+                                                        size_t n_vec) {
+    for (size_t i = (size_t)blockIdx.x * kThreads + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * kThreads)
+        dst[i] = src[i];
+}
+
+hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t st) {
+    const size_t n_vec = n_bytes / 16;
+    if (n_vec == 0) return hipSuccess;
+    size_t gx = (n_vec + kThreads - 1) / kThreads;
+    if (gx > 256 * 64) gx = 256 * 64;
+    hipLaunchKernelGGL(copy_kernel, dim3((unsigned)gx), dim3(kThreads), 0, st, reinterpret_cast<uint4*>(dst),
+                       reinterpret_cast<const uint4*>(src), n_vec);
+    return hipGetLastError();
+}
+
+}  // namespace psgd

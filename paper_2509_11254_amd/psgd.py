@@ -1,0 +1,195 @@
+"""Thin ctypes binding over libpsgd.so (the C ABI of include/psgd.h).
+
+Argument marshalling only: every step of the compressor runs in the library's HIP kernels.
+PyTorch provides device memory (tensors whose data_ptr() is handed over) and the stream.
+There is no CPU or PyTorch fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libpsgd.so")
+
+PSGD_F32, PSGD_BF16 = 0, 1
+PSGD_OK = 0
+PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -2, -3, -4, -5
+
+EXPORTS = [
+    "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_refresh",
+    "psgd_decompress", "psgd_status", "psgd_algorithmic_bytes", "psgd_copy_bytes", "psgd_last_hip_error",
+    "psgd_strerror", "psgd_destroy",
+]
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [("rows", C.c_int64), ("cols", C.c_int64), ("ld", C.c_int64), ("r", C.c_int32),
+                ("grad_dtype", C.c_int32)]
+
+
+class Options(C.Structure):
+    _fields_ = [("refresh_iters", C.c_int32), ("refresh_oversample", C.c_int32),
+                ("refresh_warm_start", C.c_int32), ("seed", C.c_uint32), ("rank_tol", C.c_float),
+                ("reserved", C.c_int32 * 3)]
+
+
+class LayerStatus(C.Structure):
+    _fields_ = [("rank_deficient", C.c_int32), ("reserved", C.c_int32), ("sigma_max", C.c_float),
+                ("sigma_r", C.c_float)]
+
+
+class PsgdError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"psgd error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library() -> C.CDLL:
+    """Load libpsgd.so; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2509_11254_amd.build` "
+            "(hipcc, gfx950). The compressor has no CPU fallback.")
+    # PyTorch owns the device memory and the streams handed to the library, so both must talk to
+    # the same HIP runtime instance: import torch first, then libpsgd.so binds to the runtime
+    # (libamdhip64.so.7) that torch has already loaded instead of opening a second one.
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    vp, pp = C.c_void_p, C.POINTER(C.c_void_p)
+    lib.psgd_init.argtypes = [pp, C.c_int, C.POINTER(LayerDesc), C.c_int, C.POINTER(Options)]
+    lib.psgd_init.restype = C.c_int
+    lib.psgd_workspace_bytes.argtypes = [vp]
+    lib.psgd_workspace_bytes.restype = C.c_size_t
+    for name in ("psgd_compress", "psgd_compress_refresh"):
+        fn = getattr(lib, name)
+        fn.argtypes = [vp, vp, vp, pp, pp, pp, pp]
+        fn.restype = C.c_int
+    lib.psgd_refresh.argtypes = [vp, vp, vp, C.c_int, vp, vp, vp, vp]
+    lib.psgd_refresh.restype = C.c_int
+    lib.psgd_decompress.argtypes = [vp, vp, vp, pp, pp, pp, C.c_int]
+    lib.psgd_decompress.restype = C.c_int
+    lib.psgd_status.argtypes = [vp, vp, vp, C.c_int, C.POINTER(LayerStatus)]
+    lib.psgd_status.restype = C.c_int
+    lib.psgd_algorithmic_bytes.argtypes = [vp]
+    lib.psgd_algorithmic_bytes.restype = C.c_double
+    lib.psgd_copy_bytes.argtypes = [vp, vp, vp, C.c_size_t]
+    lib.psgd_copy_bytes.restype = C.c_int
+    lib.psgd_last_hip_error.argtypes = [vp]
+    lib.psgd_last_hip_error.restype = C.c_int
+    lib.psgd_strerror.argtypes = [C.c_int]
+    lib.psgd_strerror.restype = C.c_char_p
+    lib.psgd_destroy.argtypes = [vp]
+    lib.psgd_destroy.restype = None
+    _lib = lib
+    return lib
+
+
+def _check(lib, ctx, rc: int):
+    if rc != PSGD_OK:
+        msg = lib.psgd_strerror(rc).decode()
+        if rc == PSGD_E_HIP and ctx:
+            msg += f" (hipError {lib.psgd_last_hip_error(ctx)})"
+        raise PsgdError(rc, msg)
+
+
+def _ptr_table(tensors: Sequence) -> C.Array:
+    arr = (C.c_void_p * len(tensors))()
+    for i, t in enumerate(tensors):
+        arr[i] = t.data_ptr()
+    return arr
+
+
+def _stream_handle(stream) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+class Compressor:
+    """psgd_init + a torch-allocated workspace; methods mirror the C entry points one to one.
+
+    layers: sequence of (rows, cols, r, grad_dtype) or (rows, cols, r, grad_dtype, ld).
+    """
+
+    def __init__(self, layers: Sequence[Sequence[int]], n_workers: int, *, refresh_iters: int = 0,
+                 refresh_oversample: int = -1, refresh_warm_start: bool = True, seed: int = 0x5EED5EED,
+                 rank_tol: float = 0.0, device: str = "cuda:0", allocate: bool = True):
+        self.lib = load_library()
+        self.n_layers = len(layers)
+        self.n_workers = int(n_workers)
+        descs = (LayerDesc * max(1, self.n_layers))()
+        for i, l in enumerate(layers):
+            descs[i].rows, descs[i].cols, descs[i].r, descs[i].grad_dtype = int(l[0]), int(l[1]), int(l[2]), int(l[3])
+            descs[i].ld = int(l[4]) if len(l) > 4 else 0
+        opt = Options(int(refresh_iters), int(refresh_oversample), 1 if refresh_warm_start else 0,
+                      int(seed) & 0xFFFFFFFF, float(rank_tol))
+        self.ctx = C.c_void_p()
+        rc = self.lib.psgd_init(C.byref(self.ctx), self.n_layers, descs, self.n_workers, C.byref(opt))
+        _check(self.lib, None, rc)
+        self.layers = [tuple(l) for l in layers]
+        self.workspace_bytes = int(self.lib.psgd_workspace_bytes(self.ctx))
+        self.workspace = None
+        if allocate:
+            import torch
+            self.workspace = torch.empty(self.workspace_bytes + 256, dtype=torch.uint8, device=device)
+            self._ws_ptr = (self.workspace.data_ptr() + 255) // 256 * 256
+        self._keep = None
+
+    def __del__(self):
+        try:
+            if getattr(self, "ctx", None) is not None and self.ctx:
+                self.lib.psgd_destroy(self.ctx)
+                self.ctx = None
+        except Exception:
+            pass
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        return float(self.lib.psgd_algorithmic_bytes(self.ctx))
+
+    def _tables(self, G, E, Q, P):
+        flat_g = [g for per_layer in G for g in per_layer] if G and isinstance(G[0], (list, tuple)) else list(G)
+        tabs = (_ptr_table(flat_g), _ptr_table(E), _ptr_table(Q), _ptr_table(P))
+        self._keep = tabs
+        return tabs
+
+    def compress(self, G, E, Q, P, stream=None) -> None:
+        """psgd_compress: G[l][i] gradients, E[l] error buffers (in place), Q[l] in/out, P[l] out."""
+        tg, te, tq, tp = self._tables(G, E, Q, P)
+        _check(self.lib, self.ctx, self.lib.psgd_compress(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def compress_refresh(self, G, E, Q, P, stream=None) -> None:
+        tg, te, tq, tp = self._tables(G, E, Q, P)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_compress_refresh(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def refresh(self, layer: int, M, P, Q, sigma=None, stream=None) -> None:
+        _check(self.lib, self.ctx,
+               self.lib.psgd_refresh(self.ctx, self._ws_ptr, _stream_handle(stream), int(layer), M.data_ptr(),
+                                     P.data_ptr(), Q.data_ptr(), sigma.data_ptr() if sigma is not None else None))
+
+    def decompress(self, P, Q, out, out_dtype: int = PSGD_F32, stream=None) -> None:
+        tp, tq, to = _ptr_table(P), _ptr_table(Q), _ptr_table(out)
+        self._keep = (tp, tq, to)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_decompress(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, to, int(out_dtype)))
+
+    def status(self, layer: int, stream=None) -> LayerStatus:
+        st = LayerStatus()
+        _check(self.lib, self.ctx,
+               self.lib.psgd_status(self.ctx, self._ws_ptr, _stream_handle(stream), int(layer), C.byref(st)))
+        return st
+
+
+def copy_bytes(dst, src, n_bytes: int, stream=None) -> None:
+    lib = load_library()
+    rc = lib.psgd_copy_bytes(_stream_handle(stream), dst.data_ptr(), src.data_ptr(), int(n_bytes))
+    _check(lib, None, rc)

@@ -1,0 +1,293 @@
+"""GPU parity: the HIP path, called through the C ABI, against the fp64 CPU oracle, element by element.
+
+Tolerances (relative Frobenius error against the oracle's value): 1e-4 for fp32 gradients, 2e-2 for
+bf16 gradients; refreshed subspaces within sin(theta_max) <= 1e-4.  E is compared against
+||E_oracle||_F (not ||M||_F).
+"""
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2509_11254_amd import psgd, synth
+from gpu_harness import Case, back, logical, oracle_inputs, to_dev_f32, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+
+
+def _workload_inputs(wl, step=0, err_scale=0.3, seed_off=0):
+    grads, errs, qs = [], [], []
+    for l, spec in enumerate(wl.layers):
+        sig = synth.signal_matrix(spec, wl, l)
+        grads.append([synth.worker_gradient(spec, wl, l, w, step, sig) for w in range(wl.n_workers)])
+        rng = np.random.default_rng([wl.seed, 909, l, seed_off])
+        errs.append((err_scale * synth.noise_sigma(spec, wl) * rng.standard_normal((spec.rows, spec.cols))).astype(np.float32))
+        qs.append(synth.initial_q(spec.n, wl.r, wl.seed, l))
+    return grads, errs, qs
+
+
+def _check_step(case, wl, grads, errs, qs, refresh, tol, check_pq=True):
+    worst = {}
+    for l, spec in enumerate(wl.layers):
+        g, e = oracle_inputs(grads[l], errs[l], spec.rows, spec.cols, wl.n_workers)
+        out = orc.compress_step(0 if refresh else 1, 1 if refresh else None, wl.r, qs[l].astype(np.float64), g, e)
+        p_gpu, q_gpu, e_gpu = case.outputs(l)
+        e_gpu = logical(e_gpu, spec.rows, spec.cols)
+        assert np.all(np.isfinite(p_gpu)) and np.all(np.isfinite(q_gpu)) and np.all(np.isfinite(e_gpu))
+        errs_l = {"E": orc.rel_fro(e_gpu, out.e_mean)}
+        if refresh:
+            errs_l["sin"] = orc.sin_theta_max(out.comp.p_tilde, p_gpu)
+            errs_l["dhat"] = orc.rel_fro(p_gpu @ q_gpu.T, out.comp.delta_hat)
+        elif check_pq:
+            errs_l["P"] = orc.rel_fro(p_gpu, out.comp.p_tilde)
+            errs_l["Q"] = orc.rel_fro(q_gpu, out.comp.q)
+        errs_l["orth"] = float(np.abs(p_gpu.T @ p_gpu - np.eye(wl.r)).max())
+        for k, v in errs_l.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+        assert errs_l["orth"] < 2e-5, (l, errs_l)
+        for k in ("E", "P", "Q", "dhat"):
+            if k in errs_l:
+                assert errs_l[k] <= tol, (spec, k, errs_l)
+        if "sin" in errs_l:
+            assert errs_l["sin"] <= 1e-4, (spec, errs_l)
+    return worst
+
+
+def _run_case(wl, refresh=False, lds=None, **opts):
+    grads, errs, qs = _workload_inputs(wl)
+    case = Case([(s.rows, s.cols) for s in wl.layers], wl.r, wl.n_workers, wl.grad_dtype, lds=lds, **opts)
+    case.upload(grads, errs, qs)
+    case.compress(refresh=refresh)
+    return _check_step(case, wl, grads, errs, qs, refresh, TOL[wl.grad_dtype])
+
+
+# ------------------------------------------------------------------ single SSP step, many shapes
+def test_ssp_step_config1():
+    w = _run_case(synth.config1())
+    print("config1 ssp", w)
+
+
+@pytest.mark.parametrize("rows,cols,ld", [(333, 203, 208), (130, 129, 136), (64, 8, 8), (1000, 40, 40), (129, 600, 600)])
+def test_ssp_step_ragged_shapes(rows, cols, ld):
+    wl = synth.scaled_down(synth.config2(), rows, cols)
+    wl.r = min(8, min(rows, cols) // 2)      # r = n would make E exactly zero (nothing to compare relatively)
+    print(rows, cols, _run_case(wl, lds=[ld]))
+
+
+def test_ssp_step_bf16_r32_four_workers():
+    wl = synth.scaled_down(synth.config3(), 640, 384)
+    print(_run_case(wl))
+
+
+def test_ssp_step_transposed_storage_bf16():
+    wl = synth.scaled_down(synth.config3(), 384, 1024)
+    print(_run_case(wl))
+
+
+def test_ssp_step_r64_single_worker_bf16():
+    wl = synth.scaled_down(synth.config4(), 1100, 512)
+    print(_run_case(wl))
+
+
+def test_ssp_step_r128():
+    """r = 128 on a slowly decaying spectrum (0.95^k).  Q_{t-1} comes from one earlier oracle step, as it
+    does in a run (Algorithm 2 starts with a refresh, so Q is never a random matrix); the columns of
+    P = M Q_{t-1} are then close to orthogonal and the step is well conditioned."""
+    wl = synth.scaled_down(synth.config5a(), 768, 512)
+    grads, errs, qs = _workload_inputs(wl)
+    spec = wl.layers[0]
+    g0 = [synth.gradient_as_f64(synth.worker_gradient(spec, wl, 0, w, 7)) for w in range(wl.n_workers)]
+    warm = orc.compress_step(0, 1, wl.r, qs[0].astype(np.float64), g0, [np.zeros((spec.rows, spec.cols))] * wl.n_workers)
+    qs = [warm.comp.q.astype(np.float32)]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, errs, qs)
+    case.compress()
+    print(_check_step(case, wl, grads, errs, qs, False, 1e-4))
+
+
+def test_ssp_step_r128_random_q_ill_conditioned():
+    """Same matrix from a random Q: cond(P) ~ sigma_1/sigma_128 ~ 700, and the Q-factor of P moves by
+    cond(P) times the relative error of P.  The split-bf16 products carry 2^-17 per operand, so the
+    bar here is cond(P) * 2^-17 ~ 5e-3 on P~ (E is less sensitive); the invariants still hold tightly."""
+    wl = synth.scaled_down(synth.config5a(), 768, 512)
+    grads, errs, qs = _workload_inputs(wl)
+    case = Case([(768, 512)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, errs, qs)
+    case.compress()
+    w = _check_step(case, wl, grads, errs, qs, False, 5e-3)
+    print(w)
+    p, q, e = case.outputs(0)
+    mat = orc.worker_mean(oracle_inputs(grads[0], errs[0], 768, 512, wl.n_workers)[0]) + errs[0].astype(np.float64)
+    assert np.linalg.norm(e - (mat - p @ (p.T @ mat))) <= 2e-5 * np.linalg.norm(mat)     # E = (I - P~P~^T) M
+    assert np.linalg.norm(q - mat.T @ p) <= 2e-5 * np.linalg.norm(mat)                   # Q = M^T P~
+
+
+def test_ssp_step_batched_mixed_layers():
+    base = synth.config3()
+    wl = synth.scaled_down(base, 256, 256)
+    wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c"),
+                 synth.LayerSpec(256, 256, "d"), synth.LayerSpec(200, 136, "e")]
+    print(_run_case(wl))
+
+
+# ------------------------------------------------------------------ trajectory, teacher-forced (config 1)
+def test_config1_trajectory_teacher_forced():
+    wl = synth.config1()
+    spec = wl.layers[0]
+    sig = synth.signal_matrix(spec, wl, 0)
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    e_w = [np.zeros((spec.rows, spec.cols)) for _ in range(wl.n_workers)]
+    q = synth.initial_q(spec.n, wl.r, wl.seed).astype(np.float64)
+    worst = {}
+    for t in range(wl.steps):
+        grads = [synth.worker_gradient(spec, wl, 0, w, t, sig) for w in range(wl.n_workers)]
+        refresh = orc.is_refresh_step(t, wl.tau)
+        out = orc.compress_step(t, wl.tau, wl.r, q, [synth.gradient_as_f64(g) for g in grads], e_w)
+        # teacher forcing: the GPU gets the oracle's E_t (mean of the per-worker buffers) and Q_{t-1}
+        e_mean = orc.worker_mean(e_w).astype(np.float32)
+        case.upload([grads], [e_mean], [q.astype(np.float32)])
+        case.compress(refresh=refresh)
+        p_gpu, q_gpu, e_gpu = case.outputs(0)
+        ref_e = orc.compress_step(t, wl.tau, wl.r, q.astype(np.float32).astype(np.float64),
+                                  [synth.gradient_as_f64(g) for g in grads], [e_mean.astype(np.float64)] * wl.n_workers)
+        errs = {"E": orc.rel_fro(e_gpu, ref_e.e_mean)}
+        if refresh:
+            # the r = 4 cut of this workload lies inside the noise bulk (sigma_4 ~ sigma_5): the
+            # subspace itself is ill-conditioned, so compare what is well-posed: the captured energy
+            s = ref_e.comp.sigma
+            tail = float(np.sum(s[wl.r:] ** 2))
+            errs["tail"] = abs(float(np.sum(e_gpu ** 2)) - tail) / float(np.sum(s ** 2))
+            assert errs["tail"] <= 1e-4, (t, errs)
+        else:
+            errs["P"] = orc.rel_fro(p_gpu, ref_e.comp.p_tilde)
+            errs["Q"] = orc.rel_fro(q_gpu, ref_e.comp.q)
+            assert max(errs.values()) <= 1e-4, (t, errs)
+        for k, v in errs.items():
+            worst[k] = max(worst.get(k, 0.0), v)
+        e_w, q = out.e_next, out.comp.q
+    print("config1 trajectory worst", worst)
+
+
+# ------------------------------------------------------------------ refresh (SVD-Comp)
+def test_refresh_prescribed_svd():
+    torch = torch_mod()
+    m, n, r = 1536, 640, 16
+    sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.5 * 0.9 ** np.arange(48)])
+    mat, u, v = synth.prescribed_svd_matrix(m, n, sigma, seed=11, noise_std=1e-6)
+    comp = psgd.Compressor([(m, n, r, psgd.PSGD_F32)], 1)
+    M = to_dev_f32(mat)
+    P = torch.empty((m, r), device="cuda")
+    Q = torch.empty((n, r), device="cuda")
+    S = torch.empty((r,), device="cuda")
+    comp.refresh(0, M, P, Q, S)
+    torch.cuda.synchronize()
+    out = orc.svd_comp([mat.astype(np.float64)], r)
+    p_gpu, q_gpu = back(P), back(Q)
+    assert orc.sin_theta_max(out.p_tilde, p_gpu) <= 1e-4
+    assert orc.sin_theta_max(u[:, :r], p_gpu) <= 1e-3            # the prescribed factors (noise perturbs them)
+    np.testing.assert_allclose(back(S), out.sigma[:r], rtol=1e-4)
+    assert orc.rel_fro(p_gpu @ q_gpu.T, out.delta_hat) <= 1e-4
+    assert np.abs(p_gpu.T @ p_gpu - np.eye(r)).max() < 2e-5
+    # columns are the Ritz vectors in order: Q = V_r Sigma_r up to sign
+    signs = np.sign(np.sum(p_gpu * out.p_tilde, axis=0))
+    assert orc.rel_fro(q_gpu * signs[None, :], out.q) <= 1e-3
+    st = comp.status(0)
+    assert st.rank_deficient == 0
+    assert st.sigma_max == pytest.approx(out.sigma[0], rel=1e-4)
+    assert st.sigma_r == pytest.approx(out.sigma[r - 1], rel=1e-4)
+
+
+def test_refresh_step_config2_shape_small_and_transposed():
+    wl = synth.scaled_down(synth.config2(), 768, 512)
+    print(_run_case(wl, refresh=True))
+    wl = synth.scaled_down(synth.config2(), 512, 768)
+    print(_run_case(wl, refresh=True))
+
+
+def test_refresh_exact_rank_r_gives_zero_error():
+    torch = torch_mod()
+    m, n, r = 512, 256, 8
+    mat, _, _ = synth.prescribed_svd_matrix(m, n, np.linspace(3, 1, r), seed=5)
+    case = Case([(m, n)], r, 1, synth.F32)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 1)])
+    case.compress(refresh=True)
+    _, _, e = case.outputs(0)
+    assert np.linalg.norm(e) <= 2e-5 * np.linalg.norm(mat)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 1)])
+    case.compress(refresh=False)
+    _, _, e = case.outputs(0)
+    assert np.linalg.norm(e) <= 2e-5 * np.linalg.norm(mat)
+
+
+# ------------------------------------------------------------------ decompress
+@pytest.mark.parametrize("rows,cols", [(640, 384), (200, 328)])
+def test_decompress_matches_outer_product(rows, cols):
+    torch = torch_mod()
+    r = 12
+    m, n = max(rows, cols), min(rows, cols)
+    rng = np.random.default_rng(3)
+    p = rng.standard_normal((m, r)).astype(np.float32)
+    q = rng.standard_normal((n, r)).astype(np.float32)
+    comp = psgd.Compressor([(rows, cols, r, psgd.PSGD_F32)], 1)
+    P, Q = to_dev_f32(p), to_dev_f32(q)
+    ref = logical(orc.decompress(p, q), rows, cols)       # stored orientation
+    out32 = torch.full((rows, cols), float("nan"), device="cuda")
+    comp.decompress([P], [Q], [out32], psgd.PSGD_F32)
+    out16 = torch.full((rows, cols), float("nan"), device="cuda", dtype=torch.bfloat16)
+    comp.decompress([P], [Q], [out16], psgd.PSGD_BF16)
+    torch.cuda.synchronize()
+    assert orc.rel_fro(back(out32), ref) <= 1e-5
+    assert orc.rel_fro(back(out16), ref) <= 4e-3          # bf16 rounding of the output (2^-9 per element)
+
+
+# ------------------------------------------------------------------ degenerate inputs
+def test_rank_deficient_projection_is_flagged_and_projector_stays_valid():
+    m, n, r = 384, 256, 4
+    mat, _, _ = synth.prescribed_svd_matrix(m, n, [2.0, 1.0], seed=9)      # rank 2 < r
+    case = Case([(m, n)], r, 1, synth.F32)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 2)])
+    case.compress()
+    p, q, e = case.outputs(0)
+    st = case.comp.status(0)
+    assert st.rank_deficient == 2
+    assert np.all(p[:, 2:] == 0)
+    np.testing.assert_allclose(p[:, :2].T @ p[:, :2], np.eye(2), atol=2e-5)
+    assert np.linalg.norm(e - (mat - p @ (p.T @ mat))) <= 1e-4 * np.linalg.norm(mat)
+    assert np.linalg.norm(e) <= 2e-5 * np.linalg.norm(mat)
+
+
+def test_zero_gradient_gives_zero_outputs():
+    m, n, r = 256, 128, 4
+    case = Case([(m, n)], r, 2, synth.F32)
+    z = np.zeros((m, n), np.float32)
+    case.upload([[z, z]], [z], [synth.initial_q(n, r, 3)])
+    case.compress()
+    p, q, e = case.outputs(0)
+    assert np.all(p == 0) and np.all(q == 0) and np.all(e == 0)
+    assert case.comp.status(0).rank_deficient == r
+
+
+def test_abi_rejects_misaligned_pointers():
+    torch = torch_mod()
+    case = Case([(256, 128)], 4, 1, synth.F32)
+    buf = torch.zeros(256 * 128 + 4, device="cuda")
+    g = buf[1:1 + 256 * 128].view(256, 128)          # 4-byte aligned only
+    e = torch.zeros((256, 128), device="cuda")
+    q = torch.zeros((128, 4), device="cuda")
+    p = torch.zeros((256, 4), device="cuda")
+    with pytest.raises(psgd.PsgdError) as ei:
+        case.comp.compress([[g]], [e], [q], [p])
+    assert ei.value.code == psgd.PSGD_E_ALIGN
+
+
+# ------------------------------------------------------------------ full size (config 2), bench launch configuration
+def test_config2_full_size_ssp_step():
+    wl = synth.config2()
+    spec = wl.layers[0]
+    grads, errs, qs = _workload_inputs(wl, err_scale=1.0)
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, errs, qs)
+    case.compress()
+    w = _check_step(case, wl, grads, errs, qs, False, 1e-4)
+    print("config2 full", w)
