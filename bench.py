@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the PowerSGD+ compressor hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of synthetic gradients:
+psgd_compress (or psgd_compress_refresh when step % tau == 0, Algorithm 2) followed by
+psgd_decompress.  Inputs are resident in HBM before the timed region; three gradient sets are
+rotated so that a step never finds its gradients in the 256 MB memory-side cache.
+
+Prints ONE JSON line (see the fields below).  `value` is gigabytes of gradient compressed per
+second: N * sum_l rows_l*cols_l * sizeof(G) * steps / time.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5a"])
+    ap.add_argument("--sets", type=int, default=3, help="rotating gradient sets")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decompress", action="store_true")
+    ap.add_argument("--rank", type=int, default=0, help="override the compression rank (sweep r = 8..64)")
+    return ap.parse_args()
+
+
+def make_workload(name, rank):
+    from paper_2509_11254_amd import synth
+    wl = {"c1": synth.config1, "c2": synth.config2, "c3": synth.config3, "c4": synth.config4,
+          "c5a": synth.config5a}[name]()
+    if rank > 0:
+        wl.r = rank
+    return wl
+
+
+def device_gradients(wl, n_sets, torch):
+    """Same recipe as synth.worker_gradient (shared low-rank signal + fresh iid noise per worker),
+    drawn on the device with torch's generator: the full-size sets are throughput inputs only."""
+    from paper_2509_11254_amd import synth
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed)
+    gdt = torch.bfloat16 if wl.grad_dtype == synth.BF16 else torch.float32
+    spectrum = torch.tensor(wl.spectrum, dtype=torch.float32, device="cuda")
+    sets = [[] for _ in range(n_sets)]
+    E, Q, P, OUT = [], [], [], []
+    sig_cache = {}
+    for l, spec in enumerate(wl.layers):
+        key = (spec.rows, spec.cols)
+        k = wl.signal_rank
+        u, _ = torch.linalg.qr(torch.randn((spec.rows, k), generator=gen, device="cuda"))
+        v, _ = torch.linalg.qr(torch.randn((spec.cols, k), generator=gen, device="cuda"))
+        signal = (u * spectrum[None, :]) @ v.T
+        sigma = synth.noise_sigma(spec, wl)
+        for s in range(n_sets):
+            per_worker = []
+            for w in range(wl.n_workers):
+                g = signal + sigma * torch.randn((spec.rows, spec.cols), generator=gen, device="cuda")
+                per_worker.append(g.to(gdt).contiguous())
+            sets[s].append(per_worker)
+        del signal, u, v
+        E.append(torch.zeros((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
+        Q.append(torch.randn((spec.n, wl.r), generator=gen, device="cuda"))
+        P.append(torch.zeros((spec.m, wl.r), dtype=torch.float32, device="cuda"))
+        if key not in sig_cache:
+            sig_cache[key] = torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda")
+        OUT.append(sig_cache[key])      # one reconstruction buffer per distinct shape (write-only output)
+    return sets, E, Q, P, OUT
+
+
+def cpu_baseline(wl, sets, E, Q, torch):
+    """The fp64 NumPy oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import psgd_oracle as orc
+    # sample: the first layer of each distinct shape, one SSP step with all workers (largest first)
+    seen, sample = set(), []
+    for l, spec in enumerate(wl.layers):
+        if (spec.rows, spec.cols) not in seen:
+            seen.add((spec.rows, spec.cols))
+            sample.append(l)
+    budget_elems = 160e6     # about 10-30 s of oracle work
+    chosen, used = [], 0.0
+    for l in sample:
+        ne = wl.layers[l].rows * wl.layers[l].cols * wl.n_workers
+        if chosen and used + ne > budget_elems:
+            continue
+        chosen.append(l)
+        used += ne
+    t_total, bytes_total = 0.0, 0.0
+    for l in chosen:
+        spec = wl.layers[l]
+        g = [x.float().cpu().numpy().astype(np.float64) for x in sets[0][l]]
+        e = [E[l].cpu().numpy().astype(np.float64)] * wl.n_workers
+        q = Q[l].cpu().numpy().astype(np.float64)
+        if spec.transposed:
+            g = [x.T for x in g]
+            e = [x.T for x in e]
+        t0 = time.perf_counter()
+        orc.compress_step(1, None, wl.r, q, g, e)
+        t_total += time.perf_counter() - t0
+        bytes_total += spec.rows * spec.cols * wl.n_workers * (2 if wl.grad_dtype == "bf16" else 4)
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": bytes_total / t_total / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+            "sample": "one SSP-Comp step (all %d workers, fp64 NumPy) on layers %s of %s: %.1f s" % (
+                wl.n_workers, [wl.layers[l].name or l for l in chosen], wl.name, t_total)}
+
+
+def read_traffic(tag):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    path = os.path.join(ROOT, "profiles", "sweep1_%s_pmc.txt" % tag)
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2509_11254_amd import psgd, synth
+
+    torch.cuda.set_device(0)
+    wl = make_workload(args.workload, args.rank)
+    gd = psgd.PSGD_BF16 if wl.grad_dtype == synth.BF16 else psgd.PSGD_F32
+    sg = 2 if wl.grad_dtype == synth.BF16 else 4
+    layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
+    comp = psgd.Compressor(layers, wl.n_workers)
+    sets, E, Q, P, OUT = device_gradients(wl, args.sets, torch)
+    elems = sum(s.rows * s.cols for s in wl.layers)
+    grad_bytes = elems * wl.n_workers * sg
+    tau = wl.tau
+
+    def step(t):
+        G = sets[t % args.sets]
+        if t % tau == 0:
+            comp.compress_refresh(G, E, Q, P)
+        else:
+            comp.compress(G, E, Q, P)
+        if not args.no_decompress:
+            comp.decompress(P, Q, OUT)
+
+    t = 0
+    for _ in range(args.warmup):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    comp.profile_enable(4 * args.steps + 64)
+    n_refresh = sum(1 for k in range(t, t + args.steps) if k % tau == 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = comp.profile_read()
+    comp.profile_enable(0)
+
+    # ---- breakdown outside the timed region: SSP-only steps, refresh-only steps, decompress
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) / n * 1e3
+
+    n_b = max(3, min(20, args.steps))
+    ssp_ms = timed(lambda i: comp.compress(sets[i % args.sets], E, Q, P), n_b)
+    comp.profile_enable(4 * n_b + 8)
+    for i in range(n_b):
+        comp.compress(sets[i % args.sets], E, Q, P)
+    torch.cuda.synchronize()
+    prof_ssp = comp.profile_read()
+    comp.profile_enable(0)
+    refresh_ms = timed(lambda i: comp.compress_refresh(sets[i % args.sets], E, Q, P), max(2, min(5, n_b)))
+    dec_ms = timed(lambda i: comp.decompress(P, Q, OUT), n_b)
+
+    # ---- roofline of the dominant kernel: the first streaming pass (reads N gradients + E, writes M)
+    # (event pairs recorded inside the timed region; the SSP-only loop is the fallback when the timed
+    # region held no SSP step)
+    s1_ms, s1_n = prof["sweep1"] if prof["sweep1"][1] > 0 else prof_ssp["sweep1"]
+    per_launch_ms = s1_ms / max(1, s1_n)
+    s1_bytes = elems * (wl.n_workers * sg + 8) + sum((s.rows + s.cols) * 4 * 32 * ((wl.r + 31) // 32) for s in wl.layers)
+    achieved = s1_bytes / (per_launch_ms * 1e-3) / 1e9 if per_launch_ms > 0 else 0.0
+    traffic = read_traffic(args.workload)
+    kernels = {}
+    for tag, (ms, n) in (prof if prof["sweep1"][1] > 0 else prof_ssp).items():
+        kernels[tag + "_ms"] = ms / max(1, n)
+
+    out = {
+        "metric": "compress GB/s of gradient",
+        "value": grad_bytes * args.steps / elapsed / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": dict(wl.describe(), refresh_steps_in_timed_region=n_refresh, gradient_sets=args.sets,
+                       decompress_in_step=not args.no_decompress),
+        "roofline": {"bound": "hbm", "kernel": "prod_kernel (M = mean G + E formed, stored, P = M Q)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "bytes_per_launch": s1_bytes, "ms_per_launch": per_launch_ms},
+        "breakdown": dict(kernels, ssp_step_ms=ssp_ms, refresh_step_ms=refresh_ms,
+                          refresh_ms_per_layer=refresh_ms / len(wl.layers), decompress_ms=dec_ms,
+                          ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
+                          ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, sets, E, Q, torch)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -127,12 +127,23 @@ int psgd_decompress(psgd_ctx *ctx, void *workspace, void *stream, const float *c
 int psgd_status(psgd_ctx *ctx, void *workspace, void *stream, int layer, psgd_layer_status *out);
 
 /* Algorithmic HBM bytes of one psgd_compress over all layers: sum over layers of
- * rows*cols*(N*sizeof(G) + 16) plus the thin matrices (see the design notes for the model). */
+ * rows*cols*min(N*sizeof(G) + 16, 2*N*sizeof(G) + 12) -- M stored between the two passes, or
+ * formed twice -- plus 16*(rows + cols)*r for the thin matrices. */
 double psgd_algorithmic_bytes(const psgd_ctx *ctx);
 
 /* Plain device copy kernel (dst <- src, n_bytes multiple of 16) used to calibrate profiler counters
  * and to measure the attainable copy bandwidth with the same launch machinery. */
 int psgd_copy_bytes(void *stream, void *dst, const void *src, size_t n_bytes);
+
+/* Timing of the three streaming kernels of psgd_compress with HIP event pairs recorded on the
+ * caller's stream around each launch: tag 0 = first pass (M formed, P = M Q), tag 1 = second pass
+ * (Q = M^T P~), tag 2 = residual.  psgd_profile_enable allocates max_records event pairs (0 turns
+ * timing off and frees them); once they are used up further launches are not timed.
+ * psgd_profile_read waits for the recorded events, adds the elapsed milliseconds and the number of
+ * records per tag into total_ms[0..n_tags) / count[0..n_tags) (host arrays), and resets the pool. */
+enum { PSGD_PROF_SWEEP1 = 0, PSGD_PROF_SWEEP2 = 1, PSGD_PROF_RESIDUAL = 2, PSGD_PROF_TAGS = 3 };
+int psgd_profile_enable(psgd_ctx *ctx, int max_records);
+int psgd_profile_read(psgd_ctx *ctx, double *total_ms, int *count, int n_tags);
 
 int psgd_last_hip_error(const psgd_ctx *ctx);
 const char *psgd_strerror(int code);

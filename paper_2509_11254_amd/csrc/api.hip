@@ -81,6 +81,11 @@ struct psgd_ctx {
     std::vector<LayerDev> hLayers;   // n_layers + 1 (last = scratch descriptor of single-layer calls)
     int last_hip = 0;
     double algo_bytes = 0.0;
+    // optional timing of the three streaming kernels with event pairs on the caller's stream
+    bool prof_on = false;
+    std::vector<hipEvent_t> prof_ev;      // pairs (start, stop)
+    std::vector<int> prof_tag;            // tag of each pair
+    size_t prof_used = 0;                 // pairs recorded so far
 };
 
 namespace {
@@ -222,8 +227,18 @@ struct Launcher {
     int max_rows = 0, max_cols = 0, max_rowsP = 0, max_colsP = 0;
     int tiles_row = 0, tiles_col = 0, tiles_outer = 0;
     hipError_t err = hipSuccess;
+    bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
+    // event pair around one tagged launch group (only when profiling is on and pairs are left)
+    int prof_begin(int tag) {
+        if (prof_mute || !ctx->prof_on || ctx->prof_used >= ctx->prof_ev.size() / 2) return -1;
+        const int k = (int)ctx->prof_used++;
+        ctx->prof_tag[k] = tag;
+        note(hipEventRecord(ctx->prof_ev[2 * k], st));
+        return k;
+    }
+    void prof_end(int k) { if (k >= 0) note(hipEventRecord(ctx->prof_ev[2 * k + 1], st)); }
     int max_len() const { return max_rows > max_cols ? max_rows : max_cols; }
     int max_lenP() const { return max_rowsP > max_colsP ? max_rowsP : max_colsP; }
 
@@ -232,8 +247,10 @@ struct Launcher {
     // product whose result is P-like (lives on the long side) or Q-like
     void prod(bool p_like, bool form, int nb) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
+        const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         note(launch_prod(nb, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, st));
         note(launch_prod(nb, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, st));
+        prof_end(k);
     }
     void orth(int role, int w, double tol2) {
         for (int pass = 0; pass < 2; ++pass) {
@@ -242,7 +259,11 @@ struct Launcher {
             note(launch_apply(layers, ids_all, n_all, max_len(), w, w, role, role, 1, st));
         }
     }
-    void residual(int nb) { note(launch_outer(nb, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st)); }
+    void residual(int nb) {
+        const int k = prof_begin(PSGD_PROF_RESIDUAL);
+        note(launch_outer(nb, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        prof_end(k);
+    }
 };
 
 void geometry(const psgd_ctx* c, int l, int split_row, int split_col, Launcher& L) {
@@ -278,6 +299,7 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     const int wz = ctx->wz, nbz = wz / 32;
     const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 8;
     const double tol2 = tol2_of(ctx);
+    L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
                              ctx->opt.seed, L.st));
     for (int it = 0; it < iters; ++it) {
@@ -294,6 +316,7 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZP, ROLE_P, 0, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, 0, L.st));
+    L.prof_mute = false;
 }
 
 }  // namespace
@@ -537,6 +560,39 @@ const char* psgd_strerror(int code) {
     }
 }
 
-void psgd_destroy(psgd_ctx* ctx) { delete ctx; }
+int psgd_profile_enable(psgd_ctx* ctx, int max_records) {
+    if (!ctx || max_records < 0 || max_records > (1 << 20)) return PSGD_E_INVALID_ARG;
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    ctx->prof_ev.clear();
+    ctx->prof_tag.assign((size_t)max_records, 0);
+    ctx->prof_used = 0;
+    ctx->prof_on = max_records > 0;
+    for (int i = 0; i < 2 * max_records; ++i) {
+        hipEvent_t e;
+        PSGD_TRY(hipEventCreate(&e));
+        ctx->prof_ev.push_back(e);
+    }
+    return PSGD_OK;
+}
+
+int psgd_profile_read(psgd_ctx* ctx, double* total_ms, int* count, int n_tags) {
+    if (!ctx || !total_ms || !count || n_tags < 1) return PSGD_E_INVALID_ARG;
+    for (int t = 0; t < n_tags; ++t) { total_ms[t] = 0.0; count[t] = 0; }
+    for (size_t k = 0; k < ctx->prof_used; ++k) {
+        PSGD_TRY(hipEventSynchronize(ctx->prof_ev[2 * k + 1]));
+        float ms = 0.f;
+        PSGD_TRY(hipEventElapsedTime(&ms, ctx->prof_ev[2 * k], ctx->prof_ev[2 * k + 1]));
+        const int t = ctx->prof_tag[k];
+        if (t >= 0 && t < n_tags) { total_ms[t] += ms; count[t] += 1; }
+    }
+    ctx->prof_used = 0;
+    return PSGD_OK;
+}
+
+void psgd_destroy(psgd_ctx* ctx) {
+    if (!ctx) return;
+    for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
+    delete ctx;
+}
 
 }  // extern "C"

@@ -20,8 +20,9 @@ PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_refresh",
     "psgd_decompress", "psgd_status", "psgd_algorithmic_bytes", "psgd_copy_bytes", "psgd_last_hip_error",
-    "psgd_strerror", "psgd_destroy",
+    "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_read",
 ]
+PROF_TAGS = ("sweep1", "sweep2", "residual")
 
 
 class LayerDesc(C.Structure):
@@ -86,6 +87,10 @@ def load_library() -> C.CDLL:
     lib.psgd_last_hip_error.restype = C.c_int
     lib.psgd_strerror.argtypes = [C.c_int]
     lib.psgd_strerror.restype = C.c_char_p
+    lib.psgd_profile_enable.argtypes = [vp, C.c_int]
+    lib.psgd_profile_enable.restype = C.c_int
+    lib.psgd_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int), C.c_int]
+    lib.psgd_profile_read.restype = C.c_int
     lib.psgd_destroy.argtypes = [vp]
     lib.psgd_destroy.restype = None
     _lib = lib
@@ -181,6 +186,16 @@ class Compressor:
         self._keep = (tp, tq, to)
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, to, int(out_dtype)))
+
+    def profile_enable(self, max_records: int) -> None:
+        _check(self.lib, self.ctx, self.lib.psgd_profile_enable(self.ctx, int(max_records)))
+
+    def profile_read(self) -> dict:
+        """{tag: (total_ms, count)} of the event pairs recorded since the last read."""
+        n = len(PROF_TAGS)
+        ms, cnt = (C.c_double * n)(), (C.c_int * n)()
+        _check(self.lib, self.ctx, self.lib.psgd_profile_read(self.ctx, ms, cnt, n))
+        return {PROF_TAGS[i]: (float(ms[i]), int(cnt[i])) for i in range(n)}
 
     def status(self, layer: int, stream=None) -> LayerStatus:
         st = LayerStatus()
