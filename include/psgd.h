@@ -76,7 +76,11 @@ typedef struct {
     float rank_tol;             /* a column of P whose part orthogonal to the earlier columns is
                                    at most rank_tol times its norm gives a zero column of P~;
                                    0 = default (1e-5)                                                */
-    int32_t reserved[3];
+    int32_t precision;          /* bf16 planes per fp32 operand of the matrix-core products: 2 = three
+                                   products per term (16 mantissa bits), 3 = six products (24 bits,
+                                   fp32-faithful); 0 = default: 3 if any layer has fp32 gradients,
+                                   else 2                                                            */
+    int32_t reserved[2];
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */

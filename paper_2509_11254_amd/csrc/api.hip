@@ -12,31 +12,31 @@
 #include "psgd_dev.h"
 
 namespace psgd {
-hipError_t launch_prod(int nb, bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                       int max_tiles, hipStream_t st);
-hipError_t launch_outer(int nb, bool decomp, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                        void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
+                       int n_ids, int max_tiles, int out_role, int epi, hipStream_t st);
+hipError_t launch_outer(int nb, int planes, bool decomp, const LayerDev* layers, const int* ids, int n_ids,
+                        int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
+                         int out_role, int epi, hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
                        hipStream_t st);
-hipError_t launch_reduce(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int cp,
-                         hipStream_t st);
-hipError_t launch_gram(const LayerDev* layers, const int* ids, int n_ids, int w, int role, hipStream_t st);
-hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2,
-                       int accumulate_status, hipStream_t st);
-hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w_in, int w_out,
-                        int src_role, int dst_role, int upper, hipStream_t st);
+hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
+                       int slot_rows, hipStream_t st);
+hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
+                        int src_role, int dst_role, int mode, int cp, hipStream_t st);
 hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
                              int src_role, int warm, uint32_t seed, hipStream_t st);
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
                          hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t st);
+enum ApplyModeHost { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
 }  // namespace psgd
 
 using namespace psgd;
 
 namespace {
 
-constexpr int kMaxWidth = 192;      // widest thin block (packed Cholesky factor must fit in LDS)
+constexpr int kMaxWidth = 192;      // widest thin block (packed Cholesky factor and product operands must fit in LDS)
 constexpr int kTargetTiles = 1024;  // workgroups per product launch we try to reach by splitting the reduction
 constexpr int kMaxSplit = 32;
 
@@ -64,6 +64,7 @@ struct psgd_ctx {
     int rmax = 0;
     int cpc = 0;     // packed width of the compress step: 32 * ceil(rmax / 32)
     int wz = 0;      // block width of the subspace iteration
+    int planes = 2;  // bf16 planes per fp32 operand of the MFMA products (2: 3 products, 3: 6 products)
     // batched splits
     int split_row_b = 1, split_col_b = 1;
     // workspace layout (byte offsets)
@@ -102,7 +103,7 @@ int fail_hip(psgd_ctx* c, hipError_t e) {
     } while (0)
 
 struct LayerRegion {
-    size_t part[2], pack[2][4], z[2], gram, tmat, evec, jwork, eval, status, end;
+    size_t part[2], pack[2][6], z[2], gram, tmat, evec, jwork, eval, status, end;
 };
 
 // byte layout of one layer's private workspace region, relative to its start
@@ -114,11 +115,12 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     const int split[2] = {c->split_row_b, c->split_col_b};
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
-        for (int k = 0; k < 4; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->wz * sizeof(bf16_t));
+        for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->wz * sizeof(bf16_t));
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
     for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
     const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
-    R.gram = take((size_t)kMaxGramSplit * w2 * sizeof(double));
+    const int max_lenP = lenP[0] > lenP[1] ? lenP[0] : lenP[1];
+    R.gram = take((size_t)(max_lenP / kGramRows2) * w2 * sizeof(double));
     R.tmat = take(w2 * sizeof(double));
     R.evec = take(w2 * sizeof(double));
     R.jwork = take(w2 * sizeof(double));
@@ -143,7 +145,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
     char* base = ws + c->off_layer[l];
     LayerDev L{};
     L.rows = (int)p.d.rows; L.cols = (int)p.d.cols; L.ld = p.d.ld; L.r = p.d.r; L.wz = c->wz;
-    L.gdt = p.d.grad_dtype; L.n_workers = c->n_workers; L.transposed = p.transposed;
+    L.gdt = p.d.grad_dtype; L.n_workers = c->n_workers; L.transposed = p.transposed; L.planes = c->planes;
     L.rowsP = p.rowsP; L.colsP = p.colsP;
     L.split_row = c->split_row_b; L.split_col = c->split_col_b;
     L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab) + (size_t)l * c->n_workers;
@@ -155,10 +157,10 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
     L.thin[ROLE_ZQ] = ThinRef{reinterpret_cast<float*>(base + R.z[side_q]), c->wz, c->wz};
     for (int s = 0; s < 2; ++s) {
         L.part[s] = reinterpret_cast<float*>(base + R.part[s]);
-        L.pack[s].n_hi = reinterpret_cast<bf16_t*>(base + R.pack[s][0]);
-        L.pack[s].n_lo = reinterpret_cast<bf16_t*>(base + R.pack[s][1]);
-        L.pack[s].t_hi = reinterpret_cast<bf16_t*>(base + R.pack[s][2]);
-        L.pack[s].t_lo = reinterpret_cast<bf16_t*>(base + R.pack[s][3]);
+        for (int k = 0; k < c->planes; ++k) {
+            L.pack[s].n[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k]);
+            L.pack[s].t[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k + 1]);
+        }
     }
     L.gram = reinterpret_cast<double*>(base + R.gram);
     L.tmat = reinterpret_cast<double*>(base + R.tmat);
@@ -225,7 +227,8 @@ struct Launcher {
     int n_all, n_norm, n_tr;
     // geometry maxima over the layers addressed by this launcher
     int max_rows = 0, max_cols = 0, max_rowsP = 0, max_colsP = 0;
-    int tiles_row = 0, tiles_col = 0, tiles_outer = 0;
+    int tiles_row = 0, tiles_col = 0, tiles_outer = 0, blocks_row = 0, blocks_col = 0;
+    int split_row = 1, split_col = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
 
@@ -243,25 +246,30 @@ struct Launcher {
     int max_lenP() const { return max_rowsP > max_colsP ? max_rowsP : max_colsP; }
 
     void pack(int role, int cp) { note(launch_pack(layers, ids_all, n_all, max_lenP(), role, cp, st)); }
-    void reduce(int role, int cp) { note(launch_reduce(layers, ids_all, n_all, max_len(), role, cp, st)); }
-    // product whose result is P-like (lives on the long side) or Q-like
-    void prod(bool p_like, bool form, int nb) {
+    // product whose result is P-like (lives on the long side) or Q-like, stored in thin[out_role]
+    void prod(bool p_like, bool form, int nb, int out_role, int epi) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
-        note(launch_prod(nb, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, st));
-        note(launch_prod(nb, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, st));
+        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, epi, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, epi, st));
         prof_end(k);
+        // split reductions are completed (and the epilogue run) by a second, small launch
+        const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
+        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, st));
+        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, st));
     }
-    void orth(int role, int w, double tol2) {
-        for (int pass = 0; pass < 2; ++pass) {
-            note(launch_gram(layers, ids_all, n_all, w, role, st));
-            note(launch_chol(layers, ids_all, n_all, w, role, tol2, pass, st));
-            note(launch_apply(layers, ids_all, n_all, max_len(), w, w, role, role, 1, st));
-        }
+    // CholeskyQR2 on thin[role], whose partial Gram matrices the producing product has just written;
+    // the result is final after pass 1 unless the conditioning asks for pass 2 (decided on the device);
+    // cp > 0: also leave the split-bf16 operand copies of the result
+    void orth(int role, int w, double tol2, int cp) {
+        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 1, kGramRows1, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS1, cp, st));
+        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 2, kGramRows2, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS2, cp, st));
     }
     void residual(int nb) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
-        note(launch_outer(nb, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        note(launch_outer(nb, ctx->planes, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
         prof_end(k);
     }
 };
@@ -273,6 +281,9 @@ void geometry(const psgd_ctx* c, int l, int split_row, int split_col, Launcher& 
     mx(L.max_rowsP, p.rowsP); mx(L.max_colsP, p.colsP);
     mx(L.tiles_row, (int)((p.d.rows + 127) / 128) * split_row);
     mx(L.tiles_col, (int)((p.d.cols + 127) / 128) * split_col);
+    mx(L.blocks_row, (int)((p.d.rows + 127) / 128));
+    mx(L.blocks_col, (int)((p.d.cols + 127) / 128));
+    L.split_row = split_row; L.split_col = split_col;
     mx(L.tiles_outer, (int)((p.d.rows + 127) / 128) * (int)((p.d.cols + 127) / 128));
 }
 
@@ -295,27 +306,26 @@ double tol2_of(const psgd_ctx* c) {
 
 // Block subspace iteration + Rayleigh-Ritz for the layers of `L`: leaves P~ (Ritz vectors of the r
 // largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
-void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out) {
+void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp) {
     const int wz = ctx->wz, nbz = wz / 32;
     const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 8;
     const double tol2 = tol2_of(ctx);
     L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
                              ctx->opt.seed, L.st));
+    L.pack(ROLE_ZQ, wz);
     for (int it = 0; it < iters; ++it) {
-        L.pack(ROLE_ZQ, wz);
-        L.prod(true, form_first && it == 0, nbz);     // Z = M Y
-        L.reduce(ROLE_ZP, wz);
-        L.orth(ROLE_ZP, wz, tol2);
-        L.pack(ROLE_ZP, wz);
-        L.prod(false, false, nbz);                    // Y = M^T Z
-        L.reduce(ROLE_ZQ, wz);
-        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2);
+        L.prod(true, form_first && it == 0, nbz, ROLE_ZP, EPI_GRAM);     // Z = M Y
+        L.orth(ROLE_ZP, wz, tol2, wz);
+        L.prod(false, false, nbz, ROLE_ZQ, EPI_GRAM);                    // Y = M^T Z
+        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2, wz);
     }
-    L.note(launch_gram(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, L.st));
+    // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
-    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZP, ROLE_P, 0, L.st));
-    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, 0, L.st));
+    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZP, ROLE_P, APPLY_RITZ,
+                        final_cp, L.st));
+    L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, APPLY_RITZ,
+                        final_cp, L.st));
     L.prof_mute = false;
 }
 
@@ -352,6 +362,15 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         p.n = (int)(d.rows >= d.cols ? d.cols : d.rows);
         (p.transposed ? c->lists.tr : c->lists.norm).push_back(l);
         if (d.r > rmax) rmax = d.r;
+    }
+    if (rc == PSGD_OK) {
+        // operand planes: bf16 gradients are compared at 2e-2, two planes (2^-17) are ample; fp32
+        // gradients are held to 1e-4 of ||E||, which can be 100x smaller than ||M||: three planes
+        bool any_f32 = false;
+        for (auto& p : c->plan) any_f32 |= (p.d.grad_dtype == PSGD_F32);
+        const int prec = c->opt.precision;
+        if (prec != 0 && prec != 2 && prec != 3) rc = PSGD_E_INVALID_ARG;
+        c->planes = prec ? prec : (any_f32 ? 3 : 2);
     }
     if (rc == PSGD_OK) {
         c->rmax = rmax;
@@ -438,14 +457,10 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp);
-    L.prod(true, true, nb);          // P = M Q_{t-1}, M formed and stored on the way
-    L.reduce(ROLE_P, cp);
-    L.orth(ROLE_P, ctx->rmax, tol2_of(ctx));
-    L.pack(ROLE_P, cp);
-    L.prod(false, false, nb);        // Q_t = M^T P~
-    L.reduce(ROLE_Q, cp);
-    L.pack(ROLE_Q, cp);
-    L.residual(nb);                  // E <- M - P~ Q_t^T
+    L.prod(true, true, nb, ROLE_P, EPI_GRAM);      // P = M Q_{t-1}; M formed and stored on the way
+    L.orth(ROLE_P, ctx->rmax, tol2_of(ctx), cp);   // P~ = QR(P), operand copies of P~
+    L.prod(false, false, nb, ROLE_Q, EPI_PACK);    // Q_t = M^T P~, operand copies of Q_t
+    L.residual(nb);                                // E <- M - P~ Q_t^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -457,11 +472,8 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
     Launcher L = batch_launcher(ctx, workspace, st);
-    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr);
-    const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp);
-    L.pack(ROLE_Q, cp);
-    L.residual(nb);
+    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc);
+    L.residual(ctx->cpc / 32);
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -497,7 +509,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     L.ids_norm = ids; L.n_norm = p.transposed ? 0 : 1;
     L.ids_tr = ids; L.n_tr = p.transposed ? 1 : 0;
     geometry(ctx, layer, D.split_row, D.split_col, L);
-    refresh_sequence(ctx, L, false, false, sigma);
+    refresh_sequence(ctx, L, false, false, sigma, 0);
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -519,7 +531,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_P, cp);
     L.pack(ROLE_Q, cp);
-    L.note(launch_outer(nb, true, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+    L.note(launch_outer(nb, ctx->planes, true, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;

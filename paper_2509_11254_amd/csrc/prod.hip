@@ -102,14 +102,40 @@ __device__ inline void store_m4(const LayerDev& L, int row, int col, float4 m) {
     }
 }
 
-__device__ inline void split_bf16(float x, bf16_t& hi, bf16_t& lo) {
-    hi = (bf16_t)x;
-    lo = (bf16_t)(x - (float)hi);
+// Epilogue on a complete 128 x cp output tile held in LDS as fp32 [BT][tw]: store the rows of the
+// thin result, then either the partial Gram matrix of these rows (fp64, upper triangle, slot = block
+// index) or the split-bf16 operand copies of the rows.  Called by all threads of the workgroup.
+__device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int out_side, int ob, int out_len,
+                                     int out_lenP, int cp, int epi, const float* otile, int tw) {
+    const int t = threadIdx.x;
+    const int w = T.width;
+    for (int e = t; e < BT * w; e += kThreads) {
+        const int row = e / w, col = e % w;
+        if (ob * BT + row < out_len) T.ptr[(int64_t)(ob * BT + row) * T.ld + col] = otile[row * tw + col];
+    }
+    if (epi == EPI_GRAM) {
+        double* __restrict__ g = L.gram + (int64_t)ob * w * w;
+        for (int e = t; e < w * w; e += kThreads) {
+            const int i = e / w, j = e % w;
+            if (i > j) continue;
+            double s = 0.0;
+#pragma unroll 8
+            for (int row = 0; row < BT; ++row) s += (double)otile[row * tw + i] * (double)otile[row * tw + j];
+            g[e] = s;
+        }
+    } else if (epi == EPI_PACK) {
+        write_packs(L.pack[out_side], L.planes, otile, tw, cp, ob * BT, BT, out_lenP);
+    }
 }
 
-template <int NB, bool COLMODE, bool FORM>
+// MFMA products kept per pair of split operands: with two planes hi*hi + lo*hi + hi*lo, with three
+// planes also mid*mid and the two products with the third plane (everything down to 2^-24).
+template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL == 2 ? (ka + kb <= 1) : (ka + kb <= 2); }
+
+template <int NB, int PL, bool COLMODE, bool FORM>
 __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restrict__ layers,
-                                                        const int* __restrict__ ids, int cp) {
+                                                        const int* __restrict__ ids, int cp, int out_role,
+                                                        int epi) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int out_side = COLMODE ? SIDE_W : SIDE_L;
     const int src_side = COLMODE ? SIDE_L : SIDE_W;
@@ -128,18 +154,16 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
     const int ch1 = min(n_chunks, ch0 + cps);
 
     extern __shared__ __align__(16) unsigned char smem[];
-    bf16_t* a_hi = reinterpret_cast<bf16_t*>(smem);
-    bf16_t* a_lo = a_hi + BT * LDSW;
-    bf16_t* b_hi = a_lo + BT * LDSW;
-    bf16_t* b_lo = b_hi + NB * 32 * LDSW;
+    bf16_t* a_pl = reinterpret_cast<bf16_t*>(smem);          // PL planes of [BT][LDSW]
+    bf16_t* b_pl = a_pl + PL * BT * LDSW;                    // PL planes of [32 NB][LDSW]
+    constexpr int APL = BT * LDSW, BPL = NB * 32 * LDSW;
 
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const float inv_n = 1.0f / (float)L.n_workers;
     const int src_lenP = side_lenP(L, src_side);
-    const bf16_t* __restrict__ xt_hi = L.pack[src_side].t_hi;
-    const bf16_t* __restrict__ xt_lo = L.pack[src_side].t_lo;
+    const PackRef XK = L.pack[src_side];
 
     floatx16 acc[NB];
 #pragma unroll
@@ -159,14 +183,22 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
             for (int u = 0; u < 8; ++u) {
                 const int row = r0 + 16 * u;
                 if (FORM) store_m4(L, ob * BT + row, col, m[u]);
-                bf16x4 h, l;
-                bf16_t hh, ll;
-                split_bf16(m[u].x, hh, ll); h[0] = hh; l[0] = ll;
-                split_bf16(m[u].y, hh, ll); h[1] = hh; l[1] = ll;
-                split_bf16(m[u].z, hh, ll); h[2] = hh; l[2] = ll;
-                split_bf16(m[u].w, hh, ll); h[3] = hh; l[3] = ll;
-                *reinterpret_cast<bf16x4*>(a_hi + row * LDSW + 4 * c4) = h;
-                *reinterpret_cast<bf16x4*>(a_lo + row * LDSW + 4 * c4) = l;
+                bf16x4 o[PL];
+                bf16_t q[PL];
+                split_planes<PL>(m[u].x, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][0] = q[k];
+                split_planes<PL>(m[u].y, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][1] = q[k];
+                split_planes<PL>(m[u].z, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][2] = q[k];
+                split_planes<PL>(m[u].w, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][3] = q[k];
+#pragma unroll
+                for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_pl + k * APL + row * LDSW + 4 * c4) = o[k];
             }
         } else {
             const int c4 = t & 31, rg = t >> 5;
@@ -177,20 +209,28 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
 #pragma unroll
                 for (int u = 0; u < 8; ++u) store_m4(L, k0 + 8 * rg + u, col, m[u]);
             }
-            bf16x8 h[4], l[4];
+            bf16x8 o[4][PL];
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
-                bf16_t hh, ll;
-                split_bf16(m[u].x, hh, ll); h[0][u] = hh; l[0][u] = ll;
-                split_bf16(m[u].y, hh, ll); h[1][u] = hh; l[1][u] = ll;
-                split_bf16(m[u].z, hh, ll); h[2][u] = hh; l[2][u] = ll;
-                split_bf16(m[u].w, hh, ll); h[3][u] = hh; l[3][u] = ll;
+                bf16_t q[PL];
+                split_planes<PL>(m[u].x, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[0][k][u] = q[k];
+                split_planes<PL>(m[u].y, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[1][k][u] = q[k];
+                split_planes<PL>(m[u].z, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[2][k][u] = q[k];
+                split_planes<PL>(m[u].w, q);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[3][k][u] = q[k];
             }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                *reinterpret_cast<bf16x8*>(a_hi + (4 * c4 + q) * LDSW + 8 * rg) = h[q];
-                *reinterpret_cast<bf16x8*>(a_lo + (4 * c4 + q) * LDSW + 8 * rg) = l[q];
-            }
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * rg) = o[q][k];
         }
         // ---- thin operand chunk: pre-split, transposed [cp][lenP] -> LDS [cp][LDSW]
 #pragma unroll
@@ -198,58 +238,155 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
             const int v = t + it * kThreads;        // 0 .. 32*NB*8-1
             const int c = v >> 3, part = v & 7;
             const int64_t goff = (int64_t)c * src_lenP + k0 + 8 * part;
-            *reinterpret_cast<uint4*>(b_hi + c * LDSW + 8 * part) = *reinterpret_cast<const uint4*>(xt_hi + goff);
-            *reinterpret_cast<uint4*>(b_lo + c * LDSW + 8 * part) = *reinterpret_cast<const uint4*>(xt_lo + goff);
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                *reinterpret_cast<uint4*>(b_pl + k * BPL + c * LDSW + 8 * part) =
+                    *reinterpret_cast<const uint4*>(XK.t[k] + goff);
         }
         __syncthreads();
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
             const int aoff = (32 * wv + li) * LDSW + 16 * ks + 8 * lg;
-            const bf16x8 ah = *reinterpret_cast<const bf16x8*>(a_hi + aoff);
-            const bf16x8 al = *reinterpret_cast<const bf16x8*>(a_lo + aoff);
+            bf16x8 av[PL];
+#pragma unroll
+            for (int k = 0; k < PL; ++k) av[k] = *reinterpret_cast<const bf16x8*>(a_pl + k * APL + aoff);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const int boff = (32 * nb + li) * LDSW + 16 * ks + 8 * lg;
-                const bf16x8 bh = *reinterpret_cast<const bf16x8*>(b_hi + boff);
-                const bf16x8 bl = *reinterpret_cast<const bf16x8*>(b_lo + boff);
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh, acc[nb], 0, 0, 0);
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh, acc[nb], 0, 0, 0);
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl, acc[nb], 0, 0, 0);
+                bf16x8 bv[PL];
+#pragma unroll
+                for (int k = 0; k < PL; ++k) bv[k] = *reinterpret_cast<const bf16x8*>(b_pl + k * BPL + boff);
+                // smallest products first
+#pragma unroll
+                for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                    for (int ka = 0; ka < PL; ++ka) {
+                        const int kb = sum - ka;
+                        if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bv[kb], acc[nb], 0, 0, 0);
+                    }
             }
         }
         __syncthreads();
     }
-    // ---- partial product of this split: part[out_side][sp][lenP][cp]
     const int out_lenP = side_lenP(L, out_side);
-    float* __restrict__ dst = L.part[out_side] + ((int64_t)sp * out_lenP + (int64_t)ob * BT + 32 * wv) * cp;
+    const ThinRef T = L.thin[out_role];
+    if (n_split > 1) {
+        // This workgroup holds one of n_split partial sums: store it and leave; finish_kernel adds
+        // them up in split order.  Layout [split][column][row]: only the T.width real columns are
+        // stored, and a lane's four consecutive accumulator rows go out as one 16-byte store.
+        const int64_t plane = (int64_t)out_lenP * T.width;
+        float* __restrict__ dst = L.part[out_side] + sp * plane + (int64_t)ob * BT + 32 * wv + 4 * lg;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int col = 32 * nb + li;
+            if (col < T.width) {
+#pragma unroll
+                for (int vq = 0; vq < 4; ++vq)
+                    *reinterpret_cast<float4*>(dst + (int64_t)col * out_lenP + 8 * vq) =
+                        make_float4(acc[nb][4 * vq], acc[nb][4 * vq + 1], acc[nb][4 * vq + 2], acc[nb][4 * vq + 3]);
+            }
+        }
+        return;
+    }
+    // ---- single split: the tile is complete; stage it in LDS (the operand buffers are dead: all
+    // MFMA reads are behind a barrier) and run the epilogue here
+    float* otile = reinterpret_cast<float*>(smem);    // [BT][cp + 1]
+    const int tw = cp + 1;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            const int row = 8 * (v >> 2) + 4 * lg + (v & 3);
-            dst[(int64_t)row * cp + 32 * nb + li] = acc[nb][v];
+            const int row = 32 * wv + 8 * (v >> 2) + 4 * lg + (v & 3);
+            otile[row * tw + 32 * nb + li] = acc[nb][v];
         }
+    __syncthreads();
+    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
 }
 
-size_t prod_lds_bytes(int nb) { return (size_t)(2 * BT * LDSW + 2 * nb * 32 * LDSW) * sizeof(bf16_t); }
+// Sum of the partial products of a split launch + the same epilogue.  One workgroup per 128-row
+// output block; the partials are added in split order, so the result is deterministic.
+__global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
+                                                          const int* __restrict__ ids, int colmode, int cp,
+                                                          int out_role, int epi) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int out_side = colmode ? SIDE_W : SIDE_L;
+    const int out_len = colmode ? L.cols : L.rows;
+    const int n_split = colmode ? L.split_col : L.split_row;
+    const int ob = blockIdx.x;
+    if (n_split <= 1 || ob * BT >= out_len) return;
+    const int out_lenP = side_lenP(L, out_side);
+    const ThinRef T = L.thin[out_role];
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* otile = reinterpret_cast<float*>(smem);    // [BT][cp + 1]
+    const int tw = cp + 1;
+    const int t = threadIdx.x;
+    for (int e = t; e < BT * cp; e += kThreads) otile[(e / cp) * tw + e % cp] = 0.f;
+    __syncthreads();
+    const int64_t plane = (int64_t)out_lenP * T.width;
+    const float* __restrict__ src = L.part[out_side] + (int64_t)ob * BT;
+    for (int item = t; item < T.width * (BT / 4); item += kThreads) {
+        const int col = item / (BT / 4), r4 = 4 * (item % (BT / 4));
+        const float* __restrict__ sc = src + (int64_t)col * out_lenP + r4;
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        int s2 = 0;
+        for (; s2 + 8 <= n_split; s2 += 8) {          // 8 independent 16-byte loads in flight
+            float4 x[8];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) x[d] = *reinterpret_cast<const float4*>(sc + (s2 + d) * plane);
+#pragma unroll
+            for (int d = 0; d < 8; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
+        }
+        for (; s2 < n_split; ++s2) {
+            const float4 x = *reinterpret_cast<const float4*>(sc + s2 * plane);
+            sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
+        }
+        otile[(r4 + 0) * tw + col] = sum.x;
+        otile[(r4 + 1) * tw + col] = sum.y;
+        otile[(r4 + 2) * tw + col] = sum.z;
+        otile[(r4 + 3) * tw + col] = sum.w;
+    }
+    __syncthreads();
+    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
+}
 
-template <int NB>
+hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
+                         int out_role, int epi, hipStream_t st) {
+    if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
+    dim3 grid(max_blocks, n_ids), block(kThreads);
+    const size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(finish_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi);
+    return hipGetLastError();
+}
+
+size_t prod_lds_bytes(int nb, int planes) {
+    const size_t operands = (size_t)planes * (BT * LDSW + nb * 32 * LDSW) * sizeof(bf16_t);
+    const size_t tile = (size_t)BT * (32 * nb + 1) * sizeof(float);
+    return operands > tile ? operands : tile;
+}
+
+template <int NB, int PL>
 static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                            int max_tiles, hipStream_t st) {
+                            int max_tiles, int out_role, int epi, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
     dim3 grid(max_tiles, n_ids), block(kThreads);
-    const size_t lds = prod_lds_bytes(NB);
+    const size_t lds = prod_lds_bytes(NB, PL);
     const int cp = 32 * NB;
 #define PSGD_LAUNCH(C, F)                                                                              \
     do {                                                                                               \
-        auto kfn = prod_kernel<NB, C, F>;                                                              \
+        auto kfn = prod_kernel<NB, PL, C, F>;                                                          \
         if (lds > 48 * 1024) {                                                                         \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                     \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
             if (e != hipSuccess) return e;                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);                                \
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, out_role, epi);                 \
     } while (0)
     if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
     else         { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
@@ -257,20 +394,18 @@ static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, con
     return hipGetLastError();
 }
 
-// nb = width / 32 of the thin operand (1..8).
-hipError_t launch_prod(int nb, bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                       int max_tiles, hipStream_t st) {
+// nb = width / 32 of the thin operand (1..6); planes = 2 or 3 bf16 planes per operand.
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
+                       int n_ids, int max_tiles, int out_role, int epi, hipStream_t st) {
+#define PSGD_CASE(N)                                                                                          \
+    case N:                                                                                                   \
+        return planes == 2 ? launch_nb<N, 2>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, st) \
+                           : launch_nb<N, 3>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, st);
     switch (nb) {
-        case 1: return launch_nb<1>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 2: return launch_nb<2>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 3: return launch_nb<3>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 4: return launch_nb<4>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 5: return launch_nb<5>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 6: return launch_nb<6>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 7: return launch_nb<7>(colmode, form, layers, ids, n_ids, max_tiles, st);
-        case 8: return launch_nb<8>(colmode, form, layers, ids, n_ids, max_tiles, st);
+        PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;
     }
+#undef PSGD_CASE
 }
 
 }  // namespace psgd

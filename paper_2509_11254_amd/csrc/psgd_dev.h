@@ -19,11 +19,14 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
 
 constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kLenPad = 128;       // packed operand rows are padded (with zeros) to this multiple
-constexpr int kMaxGramSplit = 8;   // row blocks of the partial Gram matrices
+constexpr int kGramRows1 = 128;    // rows per partial Gram matrix written by a product's epilogue
+constexpr int kGramRows2 = 64;     // rows per partial Gram matrix written by the apply kernel
 
 enum Side { SIDE_L = 0, SIDE_W = 1 };
 // Roles: the paper's P~ and Q (user buffers, leading dimension r) and the two wide internal
 // blocks of the subspace iteration (leading dimension wz).
+// what a product's epilogue does besides storing the thin result
+enum Epilogue { EPI_NONE = 0, EPI_GRAM = 1, EPI_PACK = 2 };
 enum Role { ROLE_P = 0, ROLE_Q = 1, ROLE_ZP = 2, ROLE_ZQ = 3, ROLE_COUNT = 4 };
 
 struct ThinRef {
@@ -32,15 +35,15 @@ struct ThinRef {
     int width;
 };
 
-// Split-bf16 operand copies of one thin matrix X (len x width), zero padded to lenP x cp:
-//   n_hi/n_lo : [lenP][cp]   row-major      (A/B operand of the rank-r outer product)
-//   t_hi/t_lo : [cp][lenP]   transposed     (B operand of the tall-skinny products)
-// X = hi + lo up to 2^-17 relative, each half a bf16.
+// Split-bf16 operand copies of one thin matrix X (len x width), zero padded to lenP x cp.
+// X is written as a sum of `planes` bf16 numbers, plane 0 the rounded value and each further plane
+// the rounded remainder: two planes carry 16 mantissa bits (|error| <= 2^-17 |x|), three carry 24.
+//   n[k] : [lenP][cp]   row-major      (A/B operand of the rank-r outer product)
+//   t[k] : [cp][lenP]   transposed     (B operand of the tall-skinny products)
+constexpr int kMaxPlanes = 3;
 struct PackRef {
-    bf16_t* n_hi;
-    bf16_t* n_lo;
-    bf16_t* t_hi;
-    bf16_t* t_lo;
+    bf16_t* n[kMaxPlanes];
+    bf16_t* t[kMaxPlanes];
 };
 
 struct LayerDev {
@@ -51,26 +54,75 @@ struct LayerDev {
     int gdt;           // PSGD_F32 / PSGD_BF16
     int n_workers;
     int transposed;    // rows < cols: P~ is W-side
+    int planes;        // 2 or 3 bf16 planes per fp32 operand (3 or 6 MFMA products per term)
     int rowsP, colsP;  // rows / cols rounded up to kLenPad
     int split_row;     // k-splits of the row-mode product  (reduction over cols)
     int split_col;     // k-splits of the column-mode product (reduction over rows)
     const void* const* G;   // n_workers device pointers
     float* S;               // E on entry, M between the sweeps, E_{t+1} on exit
     ThinRef thin[ROLE_COUNT];
-    float* part[2];         // per side: [split][lenP][cpmax] fp32 partial products
+    float* part[2];         // per side: [split][width][lenP] fp32 partial products of a split reduction
     PackRef pack[2];        // per side
-    double* gram;           // [kMaxGramSplit][wmax*wmax] partial Gram matrices
+    double* gram;           // [slots][w*w] partial Gram matrices, one slot per row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right
     double* evec;           // [wmax*wmax] accumulated Jacobi rotations
     double* jwork;          // [wmax*wmax] Jacobi working copy of the projected Gram matrix
     double* eval;           // [wmax]
-    int* status;            // [4] : rank_deficient, -, sigma_max bits, sigma_r bits
+    int* status;            // [4] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits
 };
 
 __host__ __device__ inline int side_of_role(int transposed, int role) {
     // P-like roles live on the long side (m): L-side unless the storage is transposed.
     const int p_like = (role == ROLE_P || role == ROLE_ZP);
     return (p_like != (transposed != 0)) ? SIDE_L : SIDE_W;
+}
+
+// x = p[0] + p[1] (+ p[2]) with every p a bf16; the remainder after the last plane is dropped.
+template <int PL>
+__device__ inline void split_planes(float x, bf16_t (&p)[PL]) {
+    float rem = x;
+#pragma unroll
+    for (int k = 0; k < PL; ++k) {
+        p[k] = (bf16_t)rem;
+        rem -= (float)p[k];
+    }
+}
+
+// Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
+// nrows a multiple of 8); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
+__device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
+                                   int nrows, int lenP) {
+    const int t = threadIdx.x;
+    for (int v = t; v < nrows * (cp / 8); v += kThreads) {
+        const int row = v / (cp / 8), c0 = 8 * (v % (cp / 8));
+        bf16x8 o[kMaxPlanes];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            bf16_t q[kMaxPlanes];
+            split_planes<kMaxPlanes>(tile[row * tw + c0 + u], q);
+#pragma unroll
+            for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
+        }
+        const int64_t off = (int64_t)(row0 + row) * cp + c0;
+#pragma unroll
+        for (int k = 0; k < kMaxPlanes; ++k)
+            if (k < planes) *reinterpret_cast<bf16x8*>(K.n[k] + off) = o[k];
+    }
+    for (int v = t; v < cp * (nrows / 8); v += kThreads) {
+        const int c = v / (nrows / 8), ib = 8 * (v % (nrows / 8));
+        bf16x8 o[kMaxPlanes];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            bf16_t q[kMaxPlanes];
+            split_planes<kMaxPlanes>(tile[(ib + u) * tw + c], q);
+#pragma unroll
+            for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
+        }
+        const int64_t off = (int64_t)c * lenP + row0 + ib;
+#pragma unroll
+        for (int k = 0; k < kMaxPlanes; ++k)
+            if (k < planes) *reinterpret_cast<bf16x8*>(K.t[k] + off) = o[k];
+    }
 }
 
 __device__ inline int side_len(const LayerDev& L, int side) { return side == SIDE_L ? L.rows : L.cols; }

@@ -14,11 +14,6 @@ namespace psgd {
 // --------------------------------------------------------------------------------------------
 // pack: thin fp32 (len x width, ld) -> split-bf16 operand copies, row-major and transposed.
 // --------------------------------------------------------------------------------------------
-__device__ inline void split_bf16_t(float x, bf16_t& hi, bf16_t& lo) {
-    hi = (bf16_t)x;
-    lo = (bf16_t)(x - (float)hi);
-}
-
 __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
@@ -27,7 +22,6 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restri
     const int i0 = blockIdx.x * 64;
     if (i0 >= lenP) return;
     const ThinRef T = L.thin[role];
-    const PackRef K = L.pack[side];
     extern __shared__ __align__(16) unsigned char smem[];
     float* tile = reinterpret_cast<float*>(smem);      // [64][cp + 1]
     const int tw = cp + 1;
@@ -38,34 +32,7 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restri
         tile[i * tw + c] = v;
     }
     __syncthreads();
-    // row-major copies: one 16-byte vector = 8 consecutive columns of one row
-    for (int v = threadIdx.x; v < 64 * (cp / 8); v += kThreads) {
-        const int i = v / (cp / 8), c0 = 8 * (v % (cp / 8));
-        bf16x8 h, l;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            bf16_t hh, ll;
-            split_bf16_t(tile[i * tw + c0 + u], hh, ll);
-            h[u] = hh; l[u] = ll;
-        }
-        const int64_t off = (int64_t)(i0 + i) * cp + c0;
-        *reinterpret_cast<bf16x8*>(K.n_hi + off) = h;
-        *reinterpret_cast<bf16x8*>(K.n_lo + off) = l;
-    }
-    // transposed copies: one vector = 8 consecutive rows of one column
-    for (int v = threadIdx.x; v < cp * 8; v += kThreads) {
-        const int c = v >> 3, ib = 8 * (v & 7);
-        bf16x8 h, l;
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            bf16_t hh, ll;
-            split_bf16_t(tile[(ib + u) * tw + c], hh, ll);
-            h[u] = hh; l[u] = ll;
-        }
-        const int64_t off = (int64_t)c * lenP + i0 + ib;
-        *reinterpret_cast<bf16x8*>(K.t_hi + off) = h;
-        *reinterpret_cast<bf16x8*>(K.t_lo + off) = l;
-    }
+    write_packs(L.pack[side], L.planes, tile, tw, cp, i0, 64, lenP);
 }
 
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
@@ -83,138 +50,45 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 }
 
 // --------------------------------------------------------------------------------------------
-// reduce: thin[role] <- sum over splits of the partial products (fixed order: deterministic).
+// chol: one workgroup per layer.  Sums the partial Gram matrices (slots of `slot_rows` rows, fixed
+// order), scales to unit diagonal, Cholesky-factorises (upper, packed in LDS), inverts the factor
+// and writes tmat = D R_s^{-1}.  pass 1 also decides whether the second CholeskyQR pass is needed:
+// the smallest pivot of the scaled factorisation is about 1/cond^2 of the column-scaled matrix and
+// the first pass leaves an orthogonality error of about 1e-16/pivot; below kSecondPassPivot the
+// flag status[1] is set and the pass-2 kernels (which exit at once otherwise) do their work.
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void reduce_kernel(const LayerDev* __restrict__ layers,
-                                                          const int* __restrict__ ids, int role, int cp) {
-    const LayerDev& L = layers[ids[blockIdx.y]];
-    const int side = side_of_role(L.transposed, role);
-    const int len = side_len(L, side), lenP = side_lenP(L, side);
-    const int n_split = side == SIDE_L ? L.split_row : L.split_col;
-    const ThinRef T = L.thin[role];
-    const float* __restrict__ part = L.part[side];
-    const int64_t total = (int64_t)len * cp;
-    const int64_t plane = (int64_t)lenP * cp;
-    for (int64_t e = (int64_t)blockIdx.x * kThreads + threadIdx.x; e < total; e += (int64_t)gridDim.x * kThreads) {
-        const int i = (int)(e / cp), c = (int)(e % cp);
-        if (c >= T.width) continue;
-        float s = 0.f;
-        for (int sp = 0; sp < n_split; ++sp) s += part[sp * plane + e];
-        T.ptr[(int64_t)i * T.ld + c] = s;
-    }
-}
+constexpr double kSecondPassPivot = 1e-6;
 
-hipError_t launch_reduce(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int cp,
-                         hipStream_t st) {
-    if (n_ids <= 0) return hipSuccess;
-    const int64_t total = (int64_t)max_len * cp;
-    int gx = (int)((total + kThreads * 4 - 1) / (kThreads * 4));
-    if (gx < 1) gx = 1;
-    dim3 grid(gx, n_ids), block(kThreads);
-    hipLaunchKernelGGL(reduce_kernel, grid, block, 0, st, layers, ids, role, cp);
-    return hipGetLastError();
-}
-
-// --------------------------------------------------------------------------------------------
-// gram: partial Gram matrices X^T X in fp64.  blockIdx.x = split + kMaxGramSplit * block_pair,
-// block pairs (bi <= bj) of 64-wide column blocks; gram[split][i*w + j] is written for i in block
-// bi, j in block bj (the strict lower triangle of the matrix of blocks is never written or read).
-// --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void gram_kernel(const LayerDev* __restrict__ layers,
-                                                        const int* __restrict__ ids, int role) {
-    const LayerDev& L = layers[ids[blockIdx.y]];
-    const int side = side_of_role(L.transposed, role);
-    const int len = side_len(L, side);
-    const ThinRef T = L.thin[role];
-    const int w = T.width;
-    const int nblk = (w + 63) / 64;
-    const int sp = blockIdx.x % kMaxGramSplit;
-    int bp = blockIdx.x / kMaxGramSplit;
-    if (bp >= nblk * (nblk + 1) / 2) return;
-    int bi = 0;
-    while (bp >= nblk - bi) { bp -= nblk - bi; ++bi; }
-    const int bj = bi + bp;
-    int rows_per = (len + kMaxGramSplit - 1) / kMaxGramSplit;
-    rows_per = (rows_per + 63) / 64 * 64;
-    const int r0 = sp * rows_per, r1 = min(len, r0 + rows_per);
-
-    __shared__ float sa[64][65];
-    __shared__ float sb[64][65];
-    const int ti = threadIdx.x >> 4, tj = threadIdx.x & 15;
-    double acc[4][4];
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = 0.0;
-    for (int rt = r0; rt < r1; rt += 64) {
-        for (int e = threadIdx.x; e < 64 * 64; e += kThreads) {
-            const int i = e >> 6, c = e & 63;
-            const int row = rt + i;
-            float va = 0.f, vb = 0.f;
-            if (row < r1) {
-                const float* xr = T.ptr + (int64_t)row * T.ld;
-                if (bi * 64 + c < w) va = xr[bi * 64 + c];
-                if (bj * 64 + c < w) vb = xr[bj * 64 + c];
-            }
-            sa[i][c] = va;
-            sb[i][c] = vb;
-        }
-        __syncthreads();
-        for (int i = 0; i < 64; ++i) {
-            double av[4], bv[4];
-#pragma unroll
-            for (int a = 0; a < 4; ++a) av[a] = (double)sa[i][ti + 16 * a];
-#pragma unroll
-            for (int b = 0; b < 4; ++b) bv[b] = (double)sb[i][tj + 16 * b];
-#pragma unroll
-            for (int a = 0; a < 4; ++a)
-#pragma unroll
-                for (int b = 0; b < 4; ++b) acc[a][b] += av[a] * bv[b];
-        }
-        __syncthreads();
-    }
-    double* __restrict__ g = L.gram + (int64_t)sp * w * w;
-#pragma unroll
-    for (int a = 0; a < 4; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int i = bi * 64 + ti + 16 * a, j = bj * 64 + tj + 16 * b;
-            if (i < w && j < w) g[(int64_t)i * w + j] = acc[a][b];
-        }
-}
-
-hipError_t launch_gram(const LayerDev* layers, const int* ids, int n_ids, int w, int role, hipStream_t st) {
-    if (n_ids <= 0) return hipSuccess;
-    const int nblk = (w + 63) / 64;
-    dim3 grid(kMaxGramSplit * nblk * (nblk + 1) / 2, n_ids), block(kThreads);
-    hipLaunchKernelGGL(gram_kernel, grid, block, 0, st, layers, ids, role);
-    return hipGetLastError();
-}
-
-// --------------------------------------------------------------------------------------------
-// chol: one workgroup per layer.  Sums the partial Gram matrices, scales to unit diagonal,
-// Cholesky-factorises (upper, packed in LDS), inverts the factor and writes tmat = D R_s^{-1}.
-// --------------------------------------------------------------------------------------------
 __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)) / 2 + (j - i); }   // i <= j
 
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int accumulate_status) {
+                                                        int pass, int slot_rows) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (pass == 2 && L.status[1] == 0) return;
+    const int side = side_of_role(L.transposed, role);
+    const int n_slots = (side_len(L, side) + slot_rows - 1) / slot_rows;
     const int w = L.thin[role].width;
     extern __shared__ __align__(16) unsigned char smem[];
     double* a = reinterpret_cast<double*>(smem);          // packed upper triangle, w(w+1)/2
     double* dsc = a + (w * (w + 1)) / 2;                  // [w] scaling
     int* bad = reinterpret_cast<int*>(dsc + w);           // [w] dependent-column flags
     const int t = threadIdx.x;
-    const int ntri = (w * (w + 1)) / 2;
-    // sum of partials (fixed order)
-    for (int i = 0; i < w; ++i)
-        for (int j = i + t; j < w; j += kThreads) {
-            double s = 0.0;
-            for (int sp = 0; sp < kMaxGramSplit; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)i * w + j];
-            a[tri_idx(i, j, w)] = s;
+    for (int e = t; e < w * w; e += kThreads) {
+        const int i = e / w, j = e % w;
+        if (i > j) continue;
+        const double* __restrict__ g = L.gram + e;
+        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        int sl = 0;
+        for (; sl + 4 <= n_slots; sl += 4) {      // independent loads in flight; order of the sum is fixed
+            s0 += g[(int64_t)(sl + 0) * w * w];
+            s1 += g[(int64_t)(sl + 1) * w * w];
+            s2 += g[(int64_t)(sl + 2) * w * w];
+            s3 += g[(int64_t)(sl + 3) * w * w];
         }
+        for (; sl < n_slots; ++sl) s0 += g[(int64_t)sl * w * w];
+        a[tri_idx(i, j, w)] = (s0 + s1) + (s2 + s3);
+    }
     __syncthreads();
     for (int i = t; i < w; i += kThreads) {
         const double d = a[tri_idx(i, i, w)];
@@ -222,13 +96,17 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
         bad[i] = d > 0.0 ? 0 : 1;
     }
     __syncthreads();
-    for (int i = 0; i < w; ++i)
-        for (int j = i + t; j < w; j += kThreads) a[tri_idx(i, j, w)] *= dsc[i] * dsc[j];
+    for (int e = t; e < w * w; e += kThreads) {
+        const int i = e / w, j = e % w;
+        if (i <= j) a[tri_idx(i, j, w)] *= dsc[i] * dsc[j];
+    }
     __syncthreads();
     // right-looking Cholesky, A = R^T R, R overwrites the upper triangle
+    double min_piv = 1.0;
     for (int k = 0; k < w; ++k) {
         const double piv = a[tri_idx(k, k, w)];
         const bool dep = bad[k] || !(piv > tol2);
+        if (!dep && piv < min_piv) min_piv = piv;
         __syncthreads();
         if (dep) {
             if (t == 0) bad[k] = 1;
@@ -267,13 +145,17 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
     if (t == 0) {
         int nbad = 0;
         for (int i = 0; i < w; ++i) nbad += bad[i];
-        L.status[0] = accumulate_status ? max(L.status[0], nbad) : nbad;
+        if (pass == 1) {
+            L.status[0] = nbad;
+            L.status[1] = (min_piv < kSecondPassPivot) ? 1 : 0;
+        } else {
+            L.status[0] = max(L.status[0], nbad);
+        }
     }
-    (void)ntri;
 }
 
-hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2,
-                       int accumulate_status, hipStream_t st) {
+hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
+                       int slot_rows, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
     const size_t lds = (size_t)((w * (w + 1)) / 2 + w) * sizeof(double) + (size_t)w * sizeof(int);
@@ -282,7 +164,7 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, accumulate_status);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows);
     return hipGetLastError();
 }
 
@@ -290,55 +172,85 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
 // apply: thin[dst] (len x w_out) <- thin[src] (len x w_in) * tmat[:, :w_out]   (fp64 accumulate);
 // w_in and w_out are the widths of the two thin matrices, tmat is w_in x w_in row-major.
 // In place (dst == src) is allowed: a workgroup reads its 64 rows completely before writing them.
+// Fused follow-ups, chosen by `mode` and the layer's second-pass flag:
+//   APPLY_PASS1  (upper-triangular tmat): flag set   -> also the partial Gram matrix of the result
+//                                         flag clear -> result is final: operand copies if cp > 0
+//   APPLY_PASS2  (upper-triangular tmat): flag clear -> nothing to do; else final + operand copies
+//   APPLY_RITZ   (full tmat)            : final + operand copies if cp > 0
 // --------------------------------------------------------------------------------------------
+enum ApplyMode { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
+
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
-                                                         int upper) {
+                                                         int mode, int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    const int need2 = L.status[1];
+    if (mode == APPLY_PASS2 && !need2) return;
     const int side = side_of_role(L.transposed, src_role);
-    const int len = side_len(L, side);
-    const int i0 = blockIdx.x * 64;
-    if (i0 >= len) return;
+    const int len = side_len(L, side), lenP = side_lenP(L, side);
+    const int i0 = blockIdx.x * kGramRows2;
+    const bool do_gram = (mode == APPLY_PASS1) && need2;
+    const bool do_pack = !do_gram && cp > 0;
+    if (i0 >= (do_pack ? lenP : len)) return;
     const ThinRef X = L.thin[src_role];
     const ThinRef Y = L.thin[dst_role];
     const int w_in = X.width, w_out = Y.width;
+    const bool upper = mode != APPLY_RITZ;
+    const int ow = (cp > w_out ? cp : w_out) + 1;     // stride of the output tile (zero padded to cp)
     extern __shared__ __align__(16) unsigned char smem[];
     float* sx = reinterpret_cast<float*>(smem);     // [64][w_in + 1]
-    float* so = sx + 64 * (w_in + 1);               // [64][w_out + 1]
+    float* so = sx + kGramRows2 * (w_in + 1);       // [64][ow]
     const int t = threadIdx.x;
-    for (int e = t; e < 64 * w_in; e += kThreads) {
+    for (int e = t; e < kGramRows2 * w_in; e += kThreads) {
         const int i = e / w_in, c = e % w_in;
         sx[i * (w_in + 1) + c] = (i0 + i < len) ? X.ptr[(int64_t)(i0 + i) * X.ld + c] : 0.f;
     }
+    for (int e = t; e < kGramRows2 * ow; e += kThreads) so[e] = 0.f;
     __syncthreads();
-    const int i = t & 63;
-    const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-    const double* __restrict__ tm = L.tmat;
-    for (int c = wv; c < w_out; c += 4) {
-        double s = 0.0;
-        const int jmax = upper ? min(c + 1, w_in) : w_in;
-        for (int j = 0; j < jmax; ++j) s += (double)sx[i * (w_in + 1) + j] * tm[(int64_t)j * w_in + c];
-        so[i * (w_out + 1) + c] = (float)s;
+    {
+        const int i = t & 63;
+        const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
+        const double* __restrict__ tm = L.tmat;
+        for (int c = wv; c < w_out; c += 4) {
+            double s = 0.0;
+            const int jmax = upper ? min(c + 1, w_in) : w_in;
+            for (int j = 0; j < jmax; ++j) s += (double)sx[i * (w_in + 1) + j] * tm[(int64_t)j * w_in + c];
+            so[i * ow + c] = (float)s;
+        }
     }
     __syncthreads();
-    for (int e = t; e < 64 * w_out; e += kThreads) {
+    for (int e = t; e < kGramRows2 * w_out; e += kThreads) {
         const int ii = e / w_out, c = e % w_out;
-        if (i0 + ii < len) Y.ptr[(int64_t)(i0 + ii) * Y.ld + c] = so[ii * (w_out + 1) + c];
+        if (i0 + ii < len) Y.ptr[(int64_t)(i0 + ii) * Y.ld + c] = so[ii * ow + c];
+    }
+    if (do_gram) {
+        double* __restrict__ g = L.gram + (int64_t)blockIdx.x * w_out * w_out;
+        for (int e = t; e < w_out * w_out; e += kThreads) {
+            const int i = e / w_out, j = e % w_out;
+            if (i > j) continue;
+            double s = 0.0;
+#pragma unroll 8
+            for (int row = 0; row < kGramRows2; ++row) s += (double)so[row * ow + i] * (double)so[row * ow + j];
+            g[e] = s;
+        }
+    } else if (do_pack) {
+        write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP);
     }
 }
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
-hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w_in, int w_out,
-                        int src_role, int dst_role, int upper, hipStream_t st) {
+hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
+                        int src_role, int dst_role, int mode, int cp, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
-    dim3 grid((max_len + 63) / 64, n_ids), block(kThreads);
-    const size_t lds = (size_t)64 * (w_in + 1 + w_out + 1) * sizeof(float);
+    dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
+    const int ow = (cp > w_out ? cp : w_out) + 1;
+    const size_t lds = (size_t)kGramRows2 * (w_in + 1 + ow) * sizeof(float);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(apply_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, upper);
+    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp);
     return hipGetLastError();
 }
 
@@ -394,7 +306,7 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 // so that P~ = Z tmat[:, :r] are the leading left singular vectors (Definition 3) and
 // Q = Y tmat[:, :r] = M^T P~.  status gets sigma_1 and sigma_r = sqrt(eigenvalue).
 // --------------------------------------------------------------------------------------------
-constexpr int kJacobiThreads = 1024;
+constexpr int kJacobiThreads = 256;
 constexpr int kJacobiMaxSweeps = 30;
 
 __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* __restrict__ layers,
@@ -402,6 +314,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
                                                                 int use_lds, float* __restrict__ sigma_out) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int w = L.thin[role].width;
+    const int n_slots = (side_len(L, side_of_role(L.transposed, role)) + kGramRows1 - 1) / kGramRows1;
     const int n = (w + 1) & ~1;      // even size for the round-robin schedule (a zero row/column is added)
     extern __shared__ __align__(16) unsigned char smem[];
     double* cs = reinterpret_cast<double*>(smem);      // [n/2] cos, [n/2] sin
@@ -410,13 +323,13 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
     double* a = use_lds ? red + 2 : L.jwork;           // n x n working copy of H
     double* v = use_lds ? a + n * n : L.evec;          // n x n accumulated rotations
     const int t = threadIdx.x;
-    // H (symmetric) = sum of the partial Gram matrices; gram_kernel wrote the upper triangle
+    // H (symmetric) = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue
     for (int e = t; e < n * n; e += kJacobiThreads) {
         const int i = e / n, j = e % n;
         double s = 0.0;
         if (i < w && j < w) {
             const int ii = min(i, j), jj = max(i, j);
-            for (int sp = 0; sp < kMaxGramSplit; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)ii * w + jj];
+            for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)ii * w + jj];
         }
         a[e] = s;
         v[e] = (i == j) ? 1.0 : 0.0;
@@ -437,7 +350,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
         for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
         if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
         __syncthreads();
-        const bool done = red[0] <= 1e-26 * red[1];
+        const bool done = red[0] <= 1e-22 * red[1];
         __syncthreads();
         if (done) break;
         for (int rd = 0; rd < n - 1; ++rd) {
