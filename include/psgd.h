@@ -68,8 +68,9 @@ typedef struct {
 
 typedef struct {
     int32_t refresh_iters;      /* subspace iterations of the SVD refresh; 0 = default (8)            */
-    int32_t refresh_oversample; /* extra block columns beyond r; negative = default (at least 8,
-                                   block width rounded up to a multiple of 32)                        */
+    int32_t refresh_oversample; /* extra block columns beyond r; negative = default max(8, r/4); the
+                                   block width r + oversample is rounded up to a multiple of 8 and
+                                   capped at n                                                       */
     int32_t refresh_warm_start; /* 1: psgd_compress_refresh starts from span(Q_{t-1}) plus random
                                    columns; 0: random start.  Default 1.                             */
     uint32_t seed;              /* seed of the counter-based generator for the random start      */

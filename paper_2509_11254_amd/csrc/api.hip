@@ -63,7 +63,9 @@ struct psgd_ctx {
     Lists lists;
     int rmax = 0;
     int cpc = 0;     // packed width of the compress step: 32 * ceil(rmax / 32)
-    int wz = 0;      // block width of the subspace iteration
+    int wz = 0;      // block width of the subspace iteration (r + oversampling, multiple of 8)
+    int cpz = 0;     // its packed width: wz rounded up to a multiple of 32
+    int cpmax = 0;   // max(cpc, cpz)
     int planes = 2;  // bf16 planes per fp32 operand of the MFMA products (2: 3 products, 3: 6 products)
     // batched splits
     int split_row_b = 1, split_col_b = 1;
@@ -115,7 +117,7 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     const int split[2] = {c->split_row_b, c->split_col_b};
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
-        for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->wz * sizeof(bf16_t));
+        for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
     for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
     const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
@@ -130,9 +132,21 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     return R;
 }
 
+// PSGD_TARGET_TILES (environment, tuning knob): workgroups a product launch should reach
+int target_tiles() {
+    static int v = 0;
+    if (v == 0) {
+        const char* e = std::getenv("PSGD_TARGET_TILES");
+        v = e ? std::atoi(e) : kTargetTiles;
+        if (v < 1) v = kTargetTiles;
+    }
+    return v;
+}
+
 int choose_split(int64_t base_tiles, int min_chunks) {
-    if (base_tiles >= kTargetTiles) return 1;
-    int64_t s = (kTargetTiles + base_tiles - 1) / base_tiles;
+    const int target = target_tiles();
+    if (base_tiles >= target) return 1;
+    int64_t s = (target + base_tiles - 1) / base_tiles;
     if (s > kMaxSplit) s = kMaxSplit;
     if (s > min_chunks) s = min_chunks;
     if (s < 1) s = 1;
@@ -307,18 +321,18 @@ double tol2_of(const psgd_ctx* c) {
 // Block subspace iteration + Rayleigh-Ritz for the layers of `L`: leaves P~ (Ritz vectors of the r
 // largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
 void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp) {
-    const int wz = ctx->wz, nbz = wz / 32;
+    const int wz = ctx->wz, cpz = ctx->cpz, nbz = cpz / 32;
     const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 8;
     const double tol2 = tol2_of(ctx);
     L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
                              ctx->opt.seed, L.st));
-    L.pack(ROLE_ZQ, wz);
+    L.pack(ROLE_ZQ, cpz);
     for (int it = 0; it < iters; ++it) {
         L.prod(true, form_first && it == 0, nbz, ROLE_ZP, EPI_GRAM);     // Z = M Y
-        L.orth(ROLE_ZP, wz, tol2, wz);
+        L.orth(ROLE_ZP, wz, tol2, cpz);
         L.prod(false, false, nbz, ROLE_ZQ, EPI_GRAM);                    // Y = M^T Z
-        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2, wz);
+        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2, cpz);
     }
     // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
@@ -377,11 +391,14 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         c->cpc = (int)round_up(rmax, 32);
         int over = c->opt.refresh_oversample;
         if (over < 0) over = 8;
-        c->wz = (int)round_up(rmax + over, 32);
+        if (c->opt.refresh_oversample < 0) over = rmax / 4 > 8 ? rmax / 4 : 8;
+        c->wz = (int)round_up(rmax + over, 8);
         int nmin = c->plan[0].n;
         for (auto& p : c->plan) if (p.n < nmin) nmin = p.n;
-        while (c->wz > 32 && c->wz > nmin && c->wz - 32 >= rmax) c->wz -= 32;   // block no wider than the matrix
-        if (c->wz > kMaxWidth || c->cpc > kMaxWidth) rc = PSGD_E_SHAPE;
+        if (c->wz > nmin) c->wz = nmin;                                         // block no wider than the matrix
+        c->cpz = (int)round_up(c->wz, 32);
+        c->cpmax = c->cpz > c->cpc ? c->cpz : c->cpc;
+        if (c->cpmax > kMaxWidth) rc = PSGD_E_SHAPE;
     }
     if (rc != PSGD_OK) { delete c; return rc; }
     // reduction splits of the batched launches

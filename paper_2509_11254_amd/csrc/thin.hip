@@ -59,11 +59,23 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 // --------------------------------------------------------------------------------------------
 constexpr double kSecondPassPivot = 1e-6;
 
+// Barrier of the threads that work on a small matrix: the whole workgroup, or, when a single
+// wavefront does the work, nothing but an ordering point (LDS accesses of one wave execute in order).
+__device__ inline void sync_group(bool single_wave) {
+    if (single_wave) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    } else {
+        __syncthreads();
+    }
+}
+
 __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)) / 2 + (j - i); }   // i <= j
 
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows) {
+                                                        int pass, int slot_rows, int inv_in_lds) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (pass == 2 && L.status[1] == 0) return;
     const int side = side_of_role(L.transposed, role);
@@ -72,7 +84,8 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
     extern __shared__ __align__(16) unsigned char smem[];
     double* a = reinterpret_cast<double*>(smem);          // packed upper triangle, w(w+1)/2
     double* dsc = a + (w * (w + 1)) / 2;                  // [w] scaling
-    int* bad = reinterpret_cast<int*>(dsc + w);           // [w] dependent-column flags
+    double* rdiag = dsc + w;                              // [w] diagonal of the factor
+    int* bad = reinterpret_cast<int*>(rdiag + w);         // [w] dependent-column flags
     const int t = threadIdx.x;
     for (int e = t; e < w * w; e += kThreads) {
         const int i = e / w, j = e % w;
@@ -101,46 +114,52 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
         if (i <= j) a[tri_idx(i, j, w)] *= dsc[i] * dsc[j];
     }
     __syncthreads();
-    // right-looking Cholesky, A = R^T R, R overwrites the upper triangle
+    // right-looking Cholesky, A = R^T R, R overwrites the upper triangle.  The trailing update walks
+    // the threads as a 16 x 16 grid over (row, column) so that no integer division is needed.
+    const int tx = t & 15, ty = t >> 4;
     double min_piv = 1.0;
     for (int k = 0; k < w; ++k) {
+        // every thread reads the pivot itself; the diagonal of R goes to rdiag, so the pivot entry is
+        // never overwritten and two barriers per step are enough
         const double piv = a[tri_idx(k, k, w)];
         const bool dep = bad[k] || !(piv > tol2);
         if (!dep && piv < min_piv) min_piv = piv;
-        __syncthreads();
+        const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
         if (dep) {
-            if (t == 0) bad[k] = 1;
-            for (int j = k + t; j < w; j += kThreads) a[tri_idx(k, j, w)] = (j == k) ? 1.0 : 0.0;
+            if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
+            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
         } else {
-            const double rkk = sqrt(piv);
-            for (int j = k + t; j < w; j += kThreads) a[tri_idx(k, j, w)] = (j == k) ? rkk : a[tri_idx(k, j, w)] / rkk;
+            const double rinv = 1.0 / sqrt(piv);
+            if (t == 0) rdiag[k] = sqrt(piv);
+            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
         }
         __syncthreads();
         if (!dep) {
-            const int nrem = w - k - 1;
-            for (int e = t; e < nrem * nrem; e += kThreads) {
-                const int i = k + 1 + e / nrem, j = k + 1 + e % nrem;
-                if (i <= j) a[tri_idx(i, j, w)] -= a[tri_idx(k, i, w)] * a[tri_idx(k, j, w)];
+            for (int i = k + 1 + ty; i < w; i += 16) {
+                const double rki = a[kbase + i];
+                const int base = tri_idx(i, i, w) - i;
+                for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
             }
         }
         __syncthreads();
     }
-    // inverse of the upper-triangular factor, one column per thread: T = R^{-1}
-    double* __restrict__ tm = L.tmat;
+    // inverse of the upper-triangular factor, one column per thread, built in LDS (packed upper):
+    // T = R^{-1}; then tmat = D T with the dependent columns zeroed
+    // (for blocks too wide for a second triangle in LDS the scratch matrix evec in global memory is used)
+    double* ti = inv_in_lds ? reinterpret_cast<double*>(bad + w + (w & 1)) : L.evec;
     for (int j = t; j < w; j += kThreads) {
-        for (int i = w - 1; i > j; --i) tm[(int64_t)i * w + j] = 0.0;
-        tm[(int64_t)j * w + j] = 1.0 / a[tri_idx(j, j, w)];
+        ti[tri_idx(j, j, w)] = 1.0 / rdiag[j];
         for (int i = j - 1; i >= 0; --i) {
             double s = 0.0;
-            for (int l = i + 1; l <= j; ++l) s += a[tri_idx(i, l, w)] * tm[(int64_t)l * w + j];
-            tm[(int64_t)i * w + j] = -s / a[tri_idx(i, i, w)];
+            for (int l = i + 1; l <= j; ++l) s += a[tri_idx(i, l, w)] * ti[tri_idx(l, j, w)];
+            ti[tri_idx(i, j, w)] = -s / rdiag[i];
         }
     }
     __syncthreads();
-    // tmat = D T with the dependent columns zeroed
+    double* __restrict__ tm = L.tmat;
     for (int e = t; e < w * w; e += kThreads) {
         const int i = e / w, j = e % w;
-        tm[e] = bad[j] ? 0.0 : tm[e] * dsc[i];
+        tm[e] = (i <= j && !bad[j]) ? ti[tri_idx(i, j, w)] * dsc[i] : 0.0;
     }
     if (t == 0) {
         int nbad = 0;
@@ -158,13 +177,14 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
                        int slot_rows, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
-    const size_t lds = (size_t)((w * (w + 1)) / 2 + w) * sizeof(double) + (size_t)w * sizeof(int);
+    const int inv_in_lds = w <= 128 ? 1 : 0;
+    const size_t lds = (size_t)((inv_in_lds ? 2 : 1) * (w * (w + 1)) / 2 + 2 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chol_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, inv_in_lds);
     return hipGetLastError();
 }
 
@@ -323,8 +343,10 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
     double* a = use_lds ? red + 2 : L.jwork;           // n x n working copy of H
     double* v = use_lds ? a + n * n : L.evec;          // n x n accumulated rotations
     const int t = threadIdx.x;
+    const int nt = kJacobiThreads;
+    const int tx = t & 15, ty = t >> 4;     // threads as a 16 x 16 grid: loops over pairs need no division
     // H (symmetric) = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue
-    for (int e = t; e < n * n; e += kJacobiThreads) {
+    for (int e = t; e < n * n; e += nt) {
         const int i = e / n, j = e % n;
         double s = 0.0;
         if (i < w && j < w) {
@@ -342,18 +364,19 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
         if (t < 2) red[t] = 0.0;
         __syncthreads();
         double off = 0.0, dia = 0.0;
-        for (int e = t; e < n * n; e += kJacobiThreads) {
-            const int i = e / n, j = e % n;
-            const double x = a[e];
-            if (i == j) dia += x * x; else off += x * x;
-        }
+        for (int i = ty; i < n; i += 16)
+            for (int j = tx; j < n; j += 16) {
+                const double x = a[i * n + j];
+                if (i == j) dia += x * x; else off += x * x;
+            }
         for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
         if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
         __syncthreads();
-        const bool done = red[0] <= 1e-22 * red[1];
+        const bool done = red[0] <= 1e-20 * red[1];
         __syncthreads();
         if (done) break;
         for (int rd = 0; rd < n - 1; ++rd) {
+            // the half disjoint pairs (p, q) of this round and their rotations, from the current A
             if (t < half) {
                 int p, q;
                 if (t == 0) { p = n - 1; q = rd; }
@@ -370,24 +393,26 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
                 cs[t] = c; cs[half + t] = s; pq[t] = p; pq[half + t] = q;
             }
             __syncthreads();
-            // rows: A <- J^T A
-            for (int e = t; e < half * n; e += kJacobiThreads) {
-                const int k = e / n, j = e % n;
-                const int p = pq[k], q = pq[half + k];
-                const double c = cs[k], s = cs[half + k];
-                const double x = a[p * n + j], y = a[q * n + j];
-                a[p * n + j] = c * x - s * y;
-                a[q * n + j] = s * x + c * y;
+            // A <- J^T A J in place: the 2x2 block (pair k1 rows) x (pair k2 columns) only depends on itself
+            for (int k1 = ty; k1 < half; k1 += 16)
+              for (int k2 = tx; k2 < half; k2 += 16) {
+                const int p1 = pq[k1], q1 = pq[half + k1], p2 = pq[k2], q2 = pq[half + k2];
+                const double c1 = cs[k1], s1 = cs[half + k1], c2 = cs[k2], s2 = cs[half + k2];
+                const double app = a[p1 * n + p2], apq = a[p1 * n + q2], aqp = a[q1 * n + p2], aqq = a[q1 * n + q2];
+                // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
+                const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
+                const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
+                // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
+                a[p1 * n + p2] = c2 * rpp - s2 * rpq;
+                a[p1 * n + q2] = s2 * rpp + c2 * rpq;
+                a[q1 * n + p2] = c2 * rqp - s2 * rqq;
+                a[q1 * n + q2] = s2 * rqp + c2 * rqq;
             }
-            __syncthreads();
-            // columns: A <- A J, V <- V J
-            for (int e = t; e < half * n; e += kJacobiThreads) {
-                const int k = e / n, i = e % n;
+            // V <- V J
+            for (int k = ty; k < half; k += 16)
+              for (int i = tx; i < n; i += 16) {
                 const int p = pq[k], q = pq[half + k];
                 const double c = cs[k], s = cs[half + k];
-                const double x = a[i * n + p], y = a[i * n + q];
-                a[i * n + p] = c * x - s * y;
-                a[i * n + q] = s * x + c * y;
                 const double vx = v[i * n + p], vy = v[i * n + q];
                 v[i * n + p] = c * vx - s * vy;
                 v[i * n + q] = s * vx + c * vy;
@@ -397,7 +422,7 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
     }
     // sort: rank of eigenvalue j = number of eigenvalues that come before it (ties by index)
     double* __restrict__ tm = L.tmat;
-    for (int j = t; j < w; j += kJacobiThreads) {
+    for (int j = t; j < w; j += nt) {
         const double lj = a[j * n + j];
         int rank = 0;
         for (int k = 0; k < w; ++k) {
@@ -408,14 +433,14 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
         L.eval[rank] = lj;
     }
     __syncthreads();
-    for (int e = t; e < w * w; e += kJacobiThreads) {
+    for (int e = t; e < w * w; e += nt) {
         const int i = e / w, j = e % w;
         tm[(int64_t)i * w + pq[j]] = v[i * n + j];
     }
     __syncthreads();
     __threadfence_block();
     const int r = L.r;
-    for (int k = t; k < r; k += kJacobiThreads) {
+    for (int k = t; k < r; k += nt) {
         const float sg = (float)sqrt(fmax(L.eval[k], 0.0));
         if (sigma_out) sigma_out[k] = sg;
         if (k == 0) L.status[2] = __float_as_int(sg);

@@ -281,6 +281,17 @@ def test_abi_rejects_misaligned_pointers():
     assert ei.value.code == psgd.PSGD_E_ALIGN
 
 
+# ------------------------------------------------------------------ full-size layer shapes of configs 3 and 4
+@pytest.mark.parametrize("cfg,rows,cols", [("c3", 2048, 2048), ("c3", 5632, 2048), ("c3", 2048, 5632),
+                                           ("c4", 4096, 4096), ("c4", 11008, 4096)])
+def test_llm_layer_shapes_full_size_ssp_step(cfg, rows, cols):
+    """One matrix of each distinct shape of the 1B-style (bf16, r = 32, N = 4) and 7B-shaped
+    (bf16, r = 64, N = 1) layer sets, at full size, against the oracle element by element."""
+    base = synth.config3() if cfg == "c3" else synth.config4()
+    wl = synth.scaled_down(base, rows, cols)
+    print(cfg, rows, cols, _run_case(wl))
+
+
 # ------------------------------------------------------------------ full size (config 2), bench launch configuration
 def test_config2_full_size_ssp_step():
     wl = synth.config2()
