@@ -33,6 +33,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decompress", action="store_true")
     ap.add_argument("--rank", type=int, default=0, help="override the compression rank (sweep r = 8..64)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also launch the library's plain copy kernel on 256 MiB three times (counter calibration)")
     return ap.parse_args()
 
 
@@ -158,6 +160,13 @@ def main():
         if not args.no_decompress:
             comp.decompress(P, Q, OUT)
 
+    if args.calibrate_copy:
+        a = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            psgd.copy_bytes(b, a, a.numel())
+        torch.cuda.synchronize()
+        del a, b
     t = 0
     for _ in range(args.warmup):
         step(t)

@@ -76,6 +76,7 @@ struct psgd_ctx {
     size_t max_part_single[2] = {0, 0};
     // cached tables
     void* bound_ws = nullptr;
+    void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs
     bool tables_valid = false;
     std::vector<const void*> hG;
     std::vector<float*> hE, hQ, hP;
@@ -207,24 +208,30 @@ int check_table(const void* const* tab, size_t n) {
     return PSGD_OK;
 }
 
-// Upload descriptors, id lists and pointer tables when anything they hold has changed.
-int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool force) {
+// Upload what has changed: the layer descriptors and id lists (new workspace, or new E/Q/P
+// pointers) and/or the table of gradient pointers.  Stream-ordered, so launches already queued keep
+// seeing the old tables.
+int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_changed, bool g_changed) {
     char* ws = reinterpret_cast<char*>(workspace);
-    if (!force && ctx->tables_valid && ctx->bound_ws == workspace) return PSGD_OK;
+    const bool fresh = !ctx->tables_valid || ctx->bound_ws != workspace;
     const int nl = ctx->n_layers;
-    ctx->hLayers.resize(nl + 1);
-    for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, &ctx->hLayers[l]);
-    ctx->hLayers[nl] = ctx->hLayers[0];
-    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers, ctx->hLayers.data(), (size_t)(nl + 1) * sizeof(LayerDev),
-                            hipMemcpyHostToDevice, st));
-    std::vector<int>& ids = ctx->hIds;
-    ids.assign(3 * (size_t)nl + 1, 0);
-    for (int l = 0; l < nl; ++l) ids[l] = l;
-    for (size_t i = 0; i < ctx->lists.norm.size(); ++i) ids[nl + i] = ctx->lists.norm[i];
-    for (size_t i = 0; i < ctx->lists.tr.size(); ++i) ids[2 * (size_t)nl + i] = ctx->lists.tr[i];
-    ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
-    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), hipMemcpyHostToDevice, st));
-    if (!ctx->hG.empty())
+    if (fresh || desc_changed) {
+        ctx->hLayers.resize(nl + 1);
+        for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, &ctx->hLayers[l]);
+        ctx->hLayers[nl] = ctx->hLayers[0];
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers, ctx->hLayers.data(), (size_t)(nl + 1) * sizeof(LayerDev),
+                                hipMemcpyHostToDevice, st));
+    }
+    if (fresh) {
+        std::vector<int>& ids = ctx->hIds;
+        ids.assign(3 * (size_t)nl + 1, 0);
+        for (int l = 0; l < nl; ++l) ids[l] = l;
+        for (size_t i = 0; i < ctx->lists.norm.size(); ++i) ids[nl + i] = ctx->lists.norm[i];
+        for (size_t i = 0; i < ctx->lists.tr.size(); ++i) ids[2 * (size_t)nl + i] = ctx->lists.tr[i];
+        ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), hipMemcpyHostToDevice, st));
+    }
+    if ((fresh || g_changed) && !ctx->hG.empty())
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab, ctx->hG.data(), ctx->hG.size() * sizeof(void*),
                                 hipMemcpyHostToDevice, st));
     ctx->bound_ws = workspace;
@@ -457,12 +464,12 @@ static int bind_common(psgd_ctx* ctx, void* workspace, hipStream_t st, const voi
     if (E && (rc = check_table(reinterpret_cast<const void* const*>(E), nl)) != PSGD_OK) return rc;
     if (Q && (rc = check_table(reinterpret_cast<const void* const*>(Q), nl)) != PSGD_OK) return rc;
     if (P && (rc = check_table(reinterpret_cast<const void* const*>(P), nl)) != PSGD_OK) return rc;
+    const bool g_changed = sync_table(ctx->hG, G, nl * ctx->n_workers);
     bool changed = false;
-    changed |= sync_table(ctx->hG, G, nl * ctx->n_workers);
     changed |= sync_table(ctx->hE, E, nl);
     changed |= sync_table(ctx->hQ, Q, nl);
     changed |= sync_table(ctx->hP, P, nl);
-    return upload_tables(ctx, workspace, st, changed);
+    return upload_tables(ctx, workspace, st, changed, g_changed);
 }
 
 int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* const* G, float* const* E,
@@ -541,9 +548,10 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
-    sync_table(ctx->hOut, out, (size_t)ctx->n_layers);
-    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*),
+    if (sync_table(ctx->hOut, out, (size_t)ctx->n_layers) || ctx->outs_ws != workspace)
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*),
                                 hipMemcpyHostToDevice, st));
+    ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_P, cp);

@@ -93,11 +93,11 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
         const double* __restrict__ g = L.gram + e;
         double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
         int sl = 0;
-        for (; sl + 4 <= n_slots; sl += 4) {      // independent loads in flight; order of the sum is fixed
-            s0 += g[(int64_t)(sl + 0) * w * w];
-            s1 += g[(int64_t)(sl + 1) * w * w];
-            s2 += g[(int64_t)(sl + 2) * w * w];
-            s3 += g[(int64_t)(sl + 3) * w * w];
+        for (; sl + 8 <= n_slots; sl += 8) {      // independent loads in flight; order of the sum is fixed
+            double x[8];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) x[d] = g[(int64_t)(sl + d) * w * w];
+            s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
         }
         for (; sl < n_slots; ++sl) s0 += g[(int64_t)sl * w * w];
         a[tri_idx(i, j, w)] = (s0 + s1) + (s2 + s3);
