@@ -31,62 +31,85 @@ __device__ inline float4 ld_bf16x4(const bf16_t* p) {
     return o;
 }
 
-// Eight 4-element pieces of M (or of S when !FORM), piece u at (row0 + u*row_step, col); zero outside
-// the matrix.  The loop over the workers is outermost so that the eight loads of one worker are in
-// flight together.  Addresses are clamped into the matrix and masked afterwards (no divergent loads).
-template <bool FORM>
-__device__ inline void load_m4x8(const LayerDev& L, int row0, int row_step, int col, float inv_n, float4 (&m)[8]) {
-    const bool col_ok = col < L.cols;
-    const int colc = col_ok ? col : 0;
+// A thread's share of one S tile: eight 4-element pieces, piece u at (row0 + u*row_step, col).
+// Addresses are clamped into the matrix and the values masked afterwards (no divergent loads); the
+// padding up to ld and rows past the end are not data.
+struct TileAddr {
     int64_t off[8];
     bool ok[8];
+    bool k1, k2, k3;
+};
+
+__device__ inline TileAddr tile_addr(const LayerDev& L, int row0, int row_step, int col) {
+    TileAddr a;
+    const bool col_ok = col < L.cols;
+    const int colc = col_ok ? col : 0;
 #pragma unroll
     for (int u = 0; u < 8; ++u) {
         const int row = row0 + u * row_step;
-        ok[u] = col_ok && row < L.rows;
-        off[u] = (int64_t)min(row, L.rows - 1) * L.ld + colc;
+        a.ok[u] = col_ok && row < L.rows;
+        a.off[u] = (int64_t)min(row, L.rows - 1) * L.ld + colc;
     }
+    a.k1 = col + 1 < L.cols; a.k2 = col + 2 < L.cols; a.k3 = col + 3 < L.cols;
+    return a;
+}
+
+__device__ inline void load_g8(const LayerDev& L, int w, const TileAddr& a, float4 (&x)[8]) {
+    if (L.gdt == 0) {
+        const float* __restrict__ g = reinterpret_cast<const float*>(L.G[w]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = ld_f32x4(g + a.off[u]);
+    } else {
+        const bf16_t* __restrict__ g = reinterpret_cast<const bf16_t*>(L.G[w]);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = ld_bf16x4(g + a.off[u]);
+    }
+}
+
+__device__ inline void add8(float4 (&m)[8], const float4 (&x)[8]) {
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { m[u].x += x[u].x; m[u].y += x[u].y; m[u].z += x[u].z; m[u].w += x[u].w; }
+}
+
+// First half of a tile load, issued before the MFMA phase of the previous chunk so that the loads
+// are in flight while the matrix cores work: the S tile itself (!FORM), or worker 0's gradient and E.
+template <bool FORM>
+__device__ inline void tile_prefetch(const LayerDev& L, const TileAddr& a, float4 (&p0)[8], float4 (&p1)[8]) {
     if (FORM) {
+        load_g8(L, 0, a, p0);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) m[u] = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (L.gdt == 0) {
-            for (int w = 0; w < L.n_workers; ++w) {
-                const float* __restrict__ g = reinterpret_cast<const float*>(L.G[w]);
-                float4 x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = ld_f32x4(g + off[u]);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) { m[u].x += x[u].x; m[u].y += x[u].y; m[u].z += x[u].z; m[u].w += x[u].w; }
-            }
-        } else {
-            for (int w = 0; w < L.n_workers; ++w) {
-                const bf16_t* __restrict__ g = reinterpret_cast<const bf16_t*>(L.G[w]);
-                float4 x[8];
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = ld_bf16x4(g + off[u]);
-#pragma unroll
-                for (int u = 0; u < 8; ++u) { m[u].x += x[u].x; m[u].y += x[u].y; m[u].z += x[u].z; m[u].w += x[u].w; }
-            }
-        }
-        float4 e[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) e[u] = ld_f32x4(L.S + off[u]);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            m[u].x = m[u].x * inv_n + e[u].x; m[u].y = m[u].y * inv_n + e[u].y;
-            m[u].z = m[u].z * inv_n + e[u].z; m[u].w = m[u].w * inv_n + e[u].w;
-        }
+        for (int u = 0; u < 8; ++u) p1[u] = ld_f32x4(L.S + a.off[u]);
     } else {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) m[u] = ld_f32x4(L.S + off[u]);
+        for (int u = 0; u < 8; ++u) p0[u] = ld_f32x4(L.S + a.off[u]);
     }
-    const bool k1 = col + 1 < L.cols, k2 = col + 2 < L.cols, k3 = col + 3 < L.cols;
+}
+
+// Second half: the remaining workers (eight loads in flight each), the mean, + E, the mask.
+// The sum over the workers runs in worker order.
+template <bool FORM>
+__device__ inline void tile_finish(const LayerDev& L, const TileAddr& a, float inv_n, const float4 (&p0)[8],
+                                   const float4 (&p1)[8], float4 (&m)[8]) {
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {   // ragged edges: padding up to ld and rows past the end are not data
-        m[u].x = ok[u] ? m[u].x : 0.f;
-        m[u].y = (ok[u] && k1) ? m[u].y : 0.f;
-        m[u].z = (ok[u] && k2) ? m[u].z : 0.f;
-        m[u].w = (ok[u] && k3) ? m[u].w : 0.f;
+    for (int u = 0; u < 8; ++u) m[u] = p0[u];
+    if (FORM) {
+        for (int w = 1; w < L.n_workers; ++w) {
+            float4 x[8];
+            load_g8(L, w, a, x);
+            add8(m, x);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            m[u].x = m[u].x * inv_n + p1[u].x; m[u].y = m[u].y * inv_n + p1[u].y;
+            m[u].z = m[u].z * inv_n + p1[u].z; m[u].w = m[u].w * inv_n + p1[u].w;
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        m[u].x = a.ok[u] ? m[u].x : 0.f;
+        m[u].y = (a.ok[u] && a.k1) ? m[u].y : 0.f;
+        m[u].z = (a.ok[u] && a.k2) ? m[u].z : 0.f;
+        m[u].w = (a.ok[u] && a.k3) ? m[u].w : 0.f;
     }
 }
 
@@ -130,10 +153,15 @@ __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int ou
 
 // MFMA products kept per pair of split operands: with two planes hi*hi + lo*hi + hi*lo, with three
 // planes also mid*mid and the two products with the third plane (everything down to 2^-24).
+// Column mode writes the A tile with 16-byte LDS stores whose lanes are 4 tile rows apart; with the
+// plain padded layout every other lane would hit the same banks.  The 16-byte chunk index within a
+// row is therefore XOR-ed with bits 3..5 of the row index (same function on the read side).
+template <bool COLMODE> __device__ inline int a_chunk(int row, int chunk) { return COLMODE ? (chunk ^ ((row >> 3) & 7)) : chunk; }
+
 template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL == 2 ? (ka + kb <= 1) : (ka + kb <= 2); }
 
 template <int NB, int PL, bool COLMODE, bool FORM>
-__global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
                                                         int epi) {
     const LayerDev& L = layers[ids[blockIdx.y]];
@@ -171,66 +199,76 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
 
+    // thread's position in the S tile: row mode 16 x 16 threads over (row, 4 columns), 8 rows 16 apart;
+    // column mode 8 x 32 threads over (8 consecutive rows, 4 columns)
+    const int c4 = COLMODE ? (t & 31) : (t & 15);
+    const int r0 = COLMODE ? (t >> 5) : (t >> 4);       // row group in column mode
+    auto addr_of = [&](int ch) {
+        const int k0 = ch * BK;
+        return COLMODE ? tile_addr(L, k0 + 8 * r0, 1, ob * BT + 4 * c4) : tile_addr(L, ob * BT + r0, 16, k0 + 4 * c4);
+    };
+    float4 p0[8], p1[8];
+    if (ch0 < ch1) tile_prefetch<FORM>(L, addr_of(ch0), p0, p1);
     for (int ch = ch0; ch < ch1; ++ch) {
         const int k0 = ch * BK;
-        // ---- S tile: global -> registers -> (store M) -> split -> LDS
-        if (!COLMODE) {
-            const int c4 = t & 15, r0 = t >> 4;
-            const int col = k0 + 4 * c4;
+        // ---- S tile: (prefetched) global -> registers -> (store M) -> split -> LDS
+        {
+            const TileAddr a = addr_of(ch);
             float4 m[8];
-            load_m4x8<FORM>(L, ob * BT + r0, 16, col, inv_n, m);
+            tile_finish<FORM>(L, a, inv_n, p0, p1, m);
+            if (!COLMODE) {
+                const int col = k0 + 4 * c4;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int row = r0 + 16 * u;
-                if (FORM) store_m4(L, ob * BT + row, col, m[u]);
-                bf16x4 o[PL];
-                bf16_t q[PL];
-                split_planes<PL>(m[u].x, q);
+                for (int u = 0; u < 8; ++u) {
+                    const int row = r0 + 16 * u;
+                    if (FORM) store_m4(L, ob * BT + row, col, m[u]);
+                    bf16x4 o[PL];
+                    bf16_t q[PL];
+                    split_planes<PL>(m[u].x, q);
 #pragma unroll
-                for (int k = 0; k < PL; ++k) o[k][0] = q[k];
-                split_planes<PL>(m[u].y, q);
+                    for (int k = 0; k < PL; ++k) o[k][0] = q[k];
+                    split_planes<PL>(m[u].y, q);
 #pragma unroll
-                for (int k = 0; k < PL; ++k) o[k][1] = q[k];
-                split_planes<PL>(m[u].z, q);
+                    for (int k = 0; k < PL; ++k) o[k][1] = q[k];
+                    split_planes<PL>(m[u].z, q);
 #pragma unroll
-                for (int k = 0; k < PL; ++k) o[k][2] = q[k];
-                split_planes<PL>(m[u].w, q);
+                    for (int k = 0; k < PL; ++k) o[k][2] = q[k];
+                    split_planes<PL>(m[u].w, q);
 #pragma unroll
-                for (int k = 0; k < PL; ++k) o[k][3] = q[k];
+                    for (int k = 0; k < PL; ++k) o[k][3] = q[k];
 #pragma unroll
-                for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_pl + k * APL + row * LDSW + 4 * c4) = o[k];
+                    for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_pl + k * APL + row * LDSW + 4 * c4) = o[k];
+                }
+            } else {
+                const int rg = r0;
+                const int col = ob * BT + 4 * c4;
+                if (FORM) {
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) store_m4(L, k0 + 8 * rg + u, col, m[u]);
+                }
+                bf16x8 o[4][PL];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    bf16_t q[PL];
+                    split_planes<PL>(m[u].x, q);
+#pragma unroll
+                    for (int k = 0; k < PL; ++k) o[0][k][u] = q[k];
+                    split_planes<PL>(m[u].y, q);
+#pragma unroll
+                    for (int k = 0; k < PL; ++k) o[1][k][u] = q[k];
+                    split_planes<PL>(m[u].z, q);
+#pragma unroll
+                    for (int k = 0; k < PL; ++k) o[2][k][u] = q[k];
+                    split_planes<PL>(m[u].w, q);
+#pragma unroll
+                    for (int k = 0; k < PL; ++k) o[3][k][u] = q[k];
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int k = 0; k < PL; ++k)
+                        *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * a_chunk<true>(4 * c4 + q, rg)) = o[q][k];
             }
-        } else {
-            const int c4 = t & 31, rg = t >> 5;
-            const int col = ob * BT + 4 * c4;
-            float4 m[8];
-            load_m4x8<FORM>(L, k0 + 8 * rg, 1, col, inv_n, m);
-            if (FORM) {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) store_m4(L, k0 + 8 * rg + u, col, m[u]);
-            }
-            bf16x8 o[4][PL];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                bf16_t q[PL];
-                split_planes<PL>(m[u].x, q);
-#pragma unroll
-                for (int k = 0; k < PL; ++k) o[0][k][u] = q[k];
-                split_planes<PL>(m[u].y, q);
-#pragma unroll
-                for (int k = 0; k < PL; ++k) o[1][k][u] = q[k];
-                split_planes<PL>(m[u].z, q);
-#pragma unroll
-                for (int k = 0; k < PL; ++k) o[2][k][u] = q[k];
-                split_planes<PL>(m[u].w, q);
-#pragma unroll
-                for (int k = 0; k < PL; ++k) o[3][k][u] = q[k];
-            }
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int k = 0; k < PL; ++k)
-                    *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * rg) = o[q][k];
         }
         // ---- thin operand chunk: pre-split, transposed [cp][lenP] -> LDS [cp][LDSW]
 #pragma unroll
@@ -244,10 +282,12 @@ __global__ __launch_bounds__(kThreads) void prod_kernel(const LayerDev* __restri
                     *reinterpret_cast<const uint4*>(XK.t[k] + goff);
         }
         __syncthreads();
+        // ---- next tile's first loads go out now and stay in flight during the MFMA phase
+        if (ch + 1 < ch1) tile_prefetch<FORM>(L, addr_of(ch + 1), p0, p1);
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
-            const int aoff = (32 * wv + li) * LDSW + 16 * ks + 8 * lg;
+            const int aoff = (32 * wv + li) * LDSW + 8 * a_chunk<COLMODE>(32 * wv + li, 2 * ks + lg);
             bf16x8 av[PL];
 #pragma unroll
             for (int k = 0; k < PL; ++k) av[k] = *reinterpret_cast<const bf16x8*>(a_pl + k * APL + aoff);

@@ -88,13 +88,30 @@ __device__ inline void split_planes(float x, bf16_t (&p)[PL]) {
     }
 }
 
+// v / d and v % d for the small divisors that occur as cp/8 or nrows/8 (4..24 in steps of 4): constant
+// divisors compile to a multiply and a shift instead of the long generic division sequence.
+__device__ inline void divmod_small(int v, int d, int& q, int& r) {
+    switch (d) {
+        case 4: q = v / 4; break;
+        case 8: q = v / 8; break;
+        case 12: q = v / 12; break;
+        case 16: q = v / 16; break;
+        case 20: q = v / 20; break;
+        case 24: q = v / 24; break;
+        default: q = v / d; break;
+    }
+    r = v - q * d;
+}
+
 // Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
 // nrows a multiple of 8); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
 __device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
                                    int nrows, int lenP) {
     const int t = threadIdx.x;
     for (int v = t; v < nrows * (cp / 8); v += kThreads) {
-        const int row = v / (cp / 8), c0 = 8 * (v % (cp / 8));
+        int row, g8;
+        divmod_small(v, cp / 8, row, g8);
+        const int c0 = 8 * g8;
         bf16x8 o[kMaxPlanes];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -109,7 +126,9 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
             if (k < planes) *reinterpret_cast<bf16x8*>(K.n[k] + off) = o[k];
     }
     for (int v = t; v < cp * (nrows / 8); v += kThreads) {
-        const int c = v / (nrows / 8), ib = 8 * (v % (nrows / 8));
+        int c, g8;
+        divmod_small(v, nrows / 8, c, g8);
+        const int ib = 8 * g8;
         bf16x8 o[kMaxPlanes];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {

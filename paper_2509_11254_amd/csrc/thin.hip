@@ -200,6 +200,8 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
 // --------------------------------------------------------------------------------------------
 enum ApplyMode { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
 
+typedef __attribute__((__vector_size__(4 * sizeof(double)))) double doublex4;
+
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
                                                          int mode, int cp) {
@@ -217,31 +219,87 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     const int w_in = X.width, w_out = Y.width;
     const bool upper = mode != APPLY_RITZ;
     const int ow = (cp > w_out ? cp : w_out) + 1;     // stride of the output tile (zero padded to cp)
+    // The product runs on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): wave v owns rows 16v..16v+15
+    // of the 64-row tile and walks the 16-column tiles of the result.  A operand = x (fp32 in LDS,
+    // widened per use), B operand = a block of tmat columns staged in LDS.
+    const int xs = w_in + 1;                                         // row stride of the x tile
+    const int kpad = (w_in + 3) & ~3;                                // reduction length padded to the MFMA k
+    const int cbw = 32;                                              // output columns per pass
     extern __shared__ __align__(16) unsigned char smem[];
-    float* sx = reinterpret_cast<float*>(smem);     // [64][w_in + 1]
-    float* so = sx + kGramRows2 * (w_in + 1);       // [64][ow]
+    double* st = reinterpret_cast<double*>(smem);                    // [kpad][cbw] block of tmat columns
+    float* sx = reinterpret_cast<float*>(st + (size_t)kpad * cbw);    // [64][xs]  x tile
+    float* so = sx + (size_t)kGramRows2 * xs;                        // [64][ow]  result tile
     const int t = threadIdx.x;
-    for (int e = t; e < kGramRows2 * w_in; e += kThreads) {
-        const int i = e / w_in, c = e % w_in;
-        sx[i * (w_in + 1) + c] = (i0 + i < len) ? X.ptr[(int64_t)(i0 + i) * X.ld + c] : 0.f;
-    }
-    for (int e = t; e < kGramRows2 * ow; e += kThreads) so[e] = 0.f;
-    __syncthreads();
+    const int tx = t & 63, ty = t >> 6;
     {
-        const int i = t & 63;
-        const int wv = __builtin_amdgcn_readfirstlane(t >> 6);
-        const double* __restrict__ tm = L.tmat;
-        for (int c = wv; c < w_out; c += 4) {
-            double s = 0.0;
-            const int jmax = upper ? min(c + 1, w_in) : w_in;
-            for (int j = 0; j < jmax; ++j) s += (double)sx[i * (w_in + 1) + j] * tm[(int64_t)j * w_in + c];
-            so[i * ow + c] = (float)s;
+        // the 64 x w_in tile is one contiguous block of the thin matrix when ld == width (always the
+        // case for the library's own buffers and for P, Q): 16-byte loads over the flat range
+        const int64_t base = (int64_t)i0 * X.ld;
+        const int n_valid = (min(len, i0 + kGramRows2) - i0) * w_in;          // elements that exist
+        const float inv_w = 1.0f / (float)w_in;
+        if (X.ld == w_in && (w_in & 3) == 0) {
+            for (int f = 4 * t; f < kGramRows2 * w_in; f += 4 * kThreads) {
+                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (f < n_valid) x = *reinterpret_cast<const float4*>(X.ptr + base + f);
+                int row = (int)(((float)f + 0.5f) * inv_w);
+                int c = f - row * w_in;
+                if (c < 0) { --row; c += w_in; } else if (c >= w_in) { ++row; c -= w_in; }
+                float* d = sx + row * xs + c;
+                d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+            }
+        } else {
+            for (int i = ty; i < kGramRows2; i += 4) {
+                const bool in = i0 + i < len;
+                const float* __restrict__ xr = X.ptr + (int64_t)(in ? i0 + i : 0) * X.ld;
+                for (int c = tx; c < w_in; c += 64) sx[i * xs + c] = in ? xr[c] : 0.f;
+            }
+        }
+        for (int e = t; e < kGramRows2 * ow; e += kThreads) so[e] = 0.f;
+    }
+    const double* __restrict__ tm = L.tmat;
+    const int li = tx & 15, lk = tx >> 4;                             // MFMA lane: row/column index, k index
+    for (int cb = 0; cb < w_out; cb += cbw) {
+        __syncthreads();
+        const int jmax = upper ? min(cb + cbw, w_in) : w_in;          // below-diagonal entries of tmat are zero
+        const int jpad = (jmax + 3) & ~3;
+        for (int j = ty; j < jpad; j += 4)
+            if (tx < cbw) st[j * cbw + tx] = (j < w_in && cb + tx < w_in) ? tm[(int64_t)j * w_in + cb + tx] : 0.0;
+        __syncthreads();
+        const float* __restrict__ xa = sx + (16 * ty + li) * xs + lk;
+        for (int ct = 0; ct < cbw / 16 && cb + 16 * ct < w_out; ++ct) {
+            doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+            const int kend = upper ? min(jpad, (cb + 16 * ct + 16 + 3) & ~3) : jpad;
+            const double* __restrict__ sb = st + lk * cbw + 16 * ct + li;
+            for (int k = 0; k < kend; k += 4) {
+                const double a = (k + lk < w_in) ? (double)xa[k] : 0.0;
+                const double b = sb[k * cbw];
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, acc, 0, 0, 0);
+            }
+            const int col = cb + 16 * ct + li;
+            if (col < w_out) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) so[(16 * ty + 4 * v + lk) * ow + col] = (float)acc[v];
+            }
         }
     }
     __syncthreads();
-    for (int e = t; e < kGramRows2 * w_out; e += kThreads) {
-        const int ii = e / w_out, c = e % w_out;
-        if (i0 + ii < len) Y.ptr[(int64_t)(i0 + ii) * Y.ld + c] = so[ii * ow + c];
+    if (Y.ld == w_out && (w_out & 3) == 0) {
+        // contiguous result block: 16-byte stores (rows past the end are cut off)
+        const int n_valid = (min(len, i0 + kGramRows2) - i0) * w_out;
+        const float inv_w = 1.0f / (float)w_out;
+        for (int f = 4 * t; f < n_valid; f += 4 * kThreads) {
+            int row = (int)(((float)f + 0.5f) * inv_w);
+            int c = f - row * w_out;
+            if (c < 0) { --row; c += w_out; } else if (c >= w_out) { ++row; c -= w_out; }
+            const float* __restrict__ sr = so + row * ow + c;
+            *reinterpret_cast<float4*>(Y.ptr + (int64_t)i0 * Y.ld + f) = make_float4(sr[0], sr[1], sr[2], sr[3]);
+        }
+    } else {
+        for (int i = ty; i < kGramRows2; i += 4) {
+            if (i0 + i >= len) break;
+            float* __restrict__ yr = Y.ptr + (int64_t)(i0 + i) * Y.ld;
+            for (int c = tx; c < w_out; c += 64) yr[c] = so[i * ow + c];
+        }
     }
     if (do_gram) {
         double* __restrict__ g = L.gram + (int64_t)blockIdx.x * w_out * w_out;
@@ -264,7 +322,9 @@ hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int m
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
     const int ow = (cp > w_out ? cp : w_out) + 1;
-    const size_t lds = (size_t)kGramRows2 * (w_in + 1 + ow) * sizeof(float);
+    const int kpad = (w_in + 3) & ~3;
+    const int st_elems = kpad * 32;                      // tmat block [kpad][32]
+    const size_t lds = (size_t)kGramRows2 * (ow + w_in + 1) * sizeof(float) + (size_t)st_elems * sizeof(double);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(apply_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
