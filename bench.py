@@ -33,6 +33,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decompress", action="store_true")
     ap.add_argument("--rank", type=int, default=0, help="override the compression rank (sweep r = 8..64)")
+    ap.add_argument("--no-qr", action="store_true",
+                    help="signal factors = scaled Gaussian columns (orthonormal up to O(sqrt(k/rows))) instead of a "
+                         "QR: keeps rocsolver out of counter-collection runs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel on 256 MiB three times (counter calibration)")
     return ap.parse_args()
@@ -47,7 +50,7 @@ def make_workload(name, rank):
     return wl
 
 
-def device_gradients(wl, n_sets, torch):
+def device_gradients(wl, n_sets, torch, no_qr=False):
     """Same recipe as synth.worker_gradient (shared low-rank signal + fresh iid noise per worker),
     drawn on the device with torch's generator: the full-size sets are throughput inputs only."""
     from paper_2509_11254_amd import synth
@@ -61,8 +64,12 @@ def device_gradients(wl, n_sets, torch):
     for l, spec in enumerate(wl.layers):
         key = (spec.rows, spec.cols)
         k = wl.signal_rank
-        u, _ = torch.linalg.qr(torch.randn((spec.rows, k), generator=gen, device="cuda"))
-        v, _ = torch.linalg.qr(torch.randn((spec.cols, k), generator=gen, device="cuda"))
+        u = torch.randn((spec.rows, k), generator=gen, device="cuda")
+        v = torch.randn((spec.cols, k), generator=gen, device="cuda")
+        if no_qr:
+            u, v = u / spec.rows ** 0.5, v / spec.cols ** 0.5
+        else:
+            u, v = torch.linalg.qr(u)[0], torch.linalg.qr(v)[0]
         signal = (u * spectrum[None, :]) @ v.T
         sigma = synth.noise_sigma(spec, wl)
         for s in range(n_sets):
@@ -146,7 +153,7 @@ def main():
     sg = 2 if wl.grad_dtype == synth.BF16 else 4
     layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
     comp = psgd.Compressor(layers, wl.n_workers)
-    sets, E, Q, P, OUT = device_gradients(wl, args.sets, torch)
+    sets, E, Q, P, OUT = device_gradients(wl, args.sets, torch, args.no_qr)
     elems = sum(s.rows * s.cols for s in wl.layers)
     grad_bytes = elems * wl.n_workers * sg
     tau = wl.tau

@@ -13,17 +13,17 @@
 
 namespace psgd {
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
-                       int n_ids, int max_tiles, int out_role, int epi, hipStream_t st);
+                       int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_outer(int nb, int planes, bool decomp, const LayerDev* layers, const int* ids, int n_ids,
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, hipStream_t st);
+                         int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
                        hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, hipStream_t st);
+                       int slot_rows, int gate, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
-                        int src_role, int dst_role, int mode, int cp, hipStream_t st);
+                        int src_role, int dst_role, int mode, int cp, int gate, hipStream_t st);
 hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
                              int src_role, int warm, uint32_t seed, hipStream_t st);
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
@@ -128,7 +128,7 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     R.evec = take(w2 * sizeof(double));
     R.jwork = take(w2 * sizeof(double));
     R.eval = take((size_t)(c->wz + 2) * sizeof(double));
-    R.status = take(4 * sizeof(int));
+    R.status = take(8 * sizeof(int));
     R.end = o;
     return R;
 }
@@ -234,6 +234,13 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
     if ((fresh || g_changed) && !ctx->hG.empty())
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab, ctx->hG.data(), ctx->hG.size() * sizeof(void*),
                                 hipMemcpyHostToDevice, st));
+    if (fresh) {
+        // status words of a new workspace start at zero ("iterations the next refresh needs" = unknown)
+        for (int l = 0; l < nl; ++l) {
+            const LayerRegion R = layer_region(ctx, ctx->plan[l]);
+            PSGD_TRY(hipMemsetAsync(ws + ctx->off_layer[l] + R.status, 0, 8 * sizeof(int), st));
+        }
+    }
     ctx->bound_ws = workspace;
     ctx->tables_valid = true;
     return PSGD_OK;
@@ -252,6 +259,7 @@ struct Launcher {
     int split_row = 1, split_col = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
+    int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -271,22 +279,23 @@ struct Launcher {
     void prod(bool p_like, bool form, int nb, int out_role, int epi) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
-        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, epi, st));
-        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, epi, st));
+        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, epi, gate, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, epi, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch
         const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, st));
-        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, st));
+        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, st));
+        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, st));
     }
     // CholeskyQR2 on thin[role], whose partial Gram matrices the producing product has just written;
     // the result is final after pass 1 unless the conditioning asks for pass 2 (decided on the device);
     // cp > 0: also leave the split-bf16 operand copies of the result
-    void orth(int role, int w, double tol2, int cp) {
-        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 1, kGramRows1, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS1, cp, st));
-        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 2, kGramRows2, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS2, cp, st));
+    void orth(int role, int w, double tol2, int cp, int kind = 0) {
+        const int g = gate < 0 ? -1 : (gate | kind << 8);
+        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 1, kGramRows1, g, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS1, cp, g, st));
+        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 2, kGramRows2, g, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS2, cp, g, st));
     }
     void residual(int nb) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
@@ -336,17 +345,21 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
                              ctx->opt.seed, L.st));
     L.pack(ROLE_ZQ, cpz);
     for (int it = 0; it < iters; ++it) {
+        // every layer runs its own number of iterations (decided on the device from the Ritz values of
+        // its previous refresh); launches past that number find their gate closed and exit at once
+        L.gate = it | (iters << 16);
         L.prod(true, form_first && it == 0, nbz, ROLE_ZP, EPI_GRAM);     // Z = M Y
         L.orth(ROLE_ZP, wz, tol2, cpz);
         L.prod(false, false, nbz, ROLE_ZQ, EPI_GRAM);                    // Y = M^T Z
-        if (it + 1 < iters) L.orth(ROLE_ZQ, wz, tol2, cpz);
+        L.orth(ROLE_ZQ, wz, tol2, cpz, 1);                               // not in a layer's last iteration
     }
+    L.gate = -1;
     // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZP, ROLE_P, APPLY_RITZ,
-                        final_cp, L.st));
+                        final_cp, -1, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, APPLY_RITZ,
-                        final_cp, L.st));
+                        final_cp, -1, L.st));
     L.prof_mute = false;
 }
 
@@ -568,10 +581,10 @@ int psgd_status(psgd_ctx* ctx, void* workspace, void* stream, int layer, psgd_la
     PSGD_TRY(hipStreamSynchronize(st));
     char* ws = reinterpret_cast<char*>(workspace);
     const LayerRegion R = layer_region(ctx, ctx->plan[layer]);
-    int raw[4] = {0, 0, 0, 0};
+    int raw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     PSGD_TRY(hipMemcpy(raw, ws + ctx->off_layer[layer] + R.status, sizeof(raw), hipMemcpyDeviceToHost));
     out->rank_deficient = raw[0];
-    out->reserved = 0;
+    out->refresh_iters_next = raw[4];
     std::memcpy(&out->sigma_max, &raw[2], sizeof(float));
     std::memcpy(&out->sigma_r, &raw[3], sizeof(float));
     return PSGD_OK;

@@ -163,8 +163,9 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 template <int NB, int PL, bool COLMODE, bool FORM>
 __global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
-                                                        int epi) {
+                                                        int epi, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
     const int out_side = COLMODE ? SIDE_W : SIDE_L;
     const int src_side = COLMODE ? SIDE_L : SIDE_W;
     const int out_len = COLMODE ? L.cols : L.rows;
@@ -349,8 +350,9 @@ __global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __res
 // output block; the partials are added in split order, so the result is deterministic.
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
-                                                          int out_role, int epi) {
+                                                          int out_role, int epi, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
     const int n_split = colmode ? L.split_col : L.split_row;
@@ -392,7 +394,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
 }
 
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, hipStream_t st) {
+                         int out_role, int epi, int gate, hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
     dim3 grid(max_blocks, n_ids), block(kThreads);
     const size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
@@ -401,7 +403,7 @@ hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, i
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi);
+    hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate);
     return hipGetLastError();
 }
 
@@ -413,7 +415,7 @@ size_t prod_lds_bytes(int nb, int planes) {
 
 template <int NB, int PL>
 static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                            int max_tiles, int out_role, int epi, hipStream_t st) {
+                            int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = prod_lds_bytes(NB, PL);
@@ -426,7 +428,7 @@ static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, con
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
             if (e != hipSuccess) return e;                                                             \
         }                                                                                              \
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, out_role, epi);                 \
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, out_role, epi, gate);           \
     } while (0)
     if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
     else         { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
@@ -436,11 +438,11 @@ static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, con
 
 // nb = width / 32 of the thin operand (1..6); planes = 2 or 3 bf16 planes per operand.
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
-                       int n_ids, int max_tiles, int out_role, int epi, hipStream_t st) {
+                       int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
 #define PSGD_CASE(N)                                                                                          \
     case N:                                                                                                   \
-        return planes == 2 ? launch_nb<N, 2>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, st) \
-                           : launch_nb<N, 3>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, st);
+        return planes == 2 ? launch_nb<N, 2>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, gate, st) \
+                           : launch_nb<N, 3>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, gate, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;

@@ -68,7 +68,8 @@ struct LayerDev {
     double* evec;           // [wmax*wmax] accumulated Jacobi rotations
     double* jwork;          // [wmax*wmax] Jacobi working copy of the projected Gram matrix
     double* eval;           // [wmax]
-    int* status;            // [4] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits
+    int* status;            // [8] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits,
+                            //       iterations the next refresh needs (0 = not known yet), 3 spare
 };
 
 __host__ __device__ inline int side_of_role(int transposed, int role) {
@@ -142,6 +143,18 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         for (int k = 0; k < kMaxPlanes; ++k)
             if (k < planes) *reinterpret_cast<bf16x8*>(K.t[k] + off) = o[k];
     }
+}
+
+// Launches inside the subspace iteration carry a gate = iteration | kind << 8 | max_iterations << 16
+// (-1 outside it).  A layer runs k iterations, k = status[4] clamped to max_iterations (all of them
+// while status[4] is still 0); kind 1 marks the orthonormalisation of Y, which the last executed
+// iteration skips because the Rayleigh-Ritz step wants Y = M^T Z itself.
+__device__ inline bool gate_open(const LayerDev& L, int gate) {
+    if (gate < 0) return true;
+    const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
+    int k = L.status[4];
+    if (k <= 0 || k > mx) k = mx;
+    return it < k - kind;
 }
 
 __device__ inline int side_len(const LayerDev& L, int side) { return side == SIDE_L ? L.rows : L.cols; }

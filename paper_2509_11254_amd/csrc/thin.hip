@@ -75,8 +75,9 @@ __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)
 
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows, int inv_in_lds) {
+                                                        int pass, int slot_rows, int inv_in_lds, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
     const int side = side_of_role(L.transposed, role);
     const int n_slots = (side_len(L, side) + slot_rows - 1) / slot_rows;
@@ -174,7 +175,7 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
 }
 
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, hipStream_t st) {
+                       int slot_rows, int gate, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
     const int inv_in_lds = w <= 128 ? 1 : 0;
@@ -184,7 +185,7 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, inv_in_lds);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, inv_in_lds, gate);
     return hipGetLastError();
 }
 
@@ -204,8 +205,9 @@ typedef __attribute__((__vector_size__(4 * sizeof(double)))) double doublex4;
 
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
-                                                         int mode, int cp) {
+                                                         int mode, int cp, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
     const int need2 = L.status[1];
     if (mode == APPLY_PASS2 && !need2) return;
     const int side = side_of_role(L.transposed, src_role);
@@ -318,7 +320,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
-                        int src_role, int dst_role, int mode, int cp, hipStream_t st) {
+                        int src_role, int dst_role, int mode, int cp, int gate, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
     const int ow = (cp > w_out ? cp : w_out) + 1;
@@ -330,7 +332,7 @@ hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int m
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp);
+    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate);
     return hipGetLastError();
 }
 
@@ -505,6 +507,18 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
         if (sigma_out) sigma_out[k] = sg;
         if (k == 0) L.status[2] = __float_as_int(sg);
         if (k == r - 1) L.status[3] = __float_as_int(sg);
+    }
+    if (t == 0) {
+        // The iteration contracts the error of the leading r-dimensional subspace by about
+        // rho = (theta_b / theta_r)^2 per step (theta = Ritz values, the smallest one of the block standing
+        // in for sigma_{b+1}); the next refresh of this layer runs as many steps as 1e-6 needs, plus one.
+        int k_next = 255;
+        const double lr = L.eval[r - 1], lb = L.eval[w - 1];
+        if (w > r && lr > 0.0 && lb >= 0.0) {
+            const double rho = lb / lr;
+            if (rho < 0.999) k_next = (rho <= 1e-12) ? 2 : (int)ceil(log(1e-6) / log(rho)) + 1;
+        }
+        L.status[4] = max(2, min(255, k_next));
     }
 }
 

@@ -37,7 +37,7 @@ class Options(C.Structure):
 
 
 class LayerStatus(C.Structure):
-    _fields_ = [("rank_deficient", C.c_int32), ("reserved", C.c_int32), ("sigma_max", C.c_float),
+    _fields_ = [("rank_deficient", C.c_int32), ("refresh_iters_next", C.c_int32), ("sigma_max", C.c_float),
                 ("sigma_r", C.c_float)]
 
 

@@ -196,6 +196,14 @@ def test_refresh_prescribed_svd():
     assert st.rank_deficient == 0
     assert st.sigma_max == pytest.approx(out.sigma[0], rel=1e-4)
     assert st.sigma_r == pytest.approx(out.sigma[r - 1], rel=1e-4)
+    # the first refresh ran the maximum (8) and left the count its spectrum needs: block width 24,
+    # (sigma_24 / sigma_16)^2 ~ 0.057 per iteration -> ceil(log 1e-6 / log 0.057) + 1 = 6
+    assert 4 <= st.refresh_iters_next <= 7
+    P.fill_(float("nan")); Q.fill_(float("nan"))
+    comp.refresh(0, M, P, Q, S)                      # second refresh: fewer iterations, same bar
+    torch.cuda.synchronize()
+    assert orc.sin_theta_max(out.p_tilde, back(P)) <= 1e-4
+    assert orc.rel_fro(back(P) @ back(Q).T, out.delta_hat) <= 1e-4
 
 
 def test_refresh_step_config2_shape_small_and_transposed():
