@@ -106,7 +106,7 @@ int fail_hip(psgd_ctx* c, hipError_t e) {
     } while (0)
 
 struct LayerRegion {
-    size_t part[2], pack[2][6], z[2], gram, tmat, evec, jwork, eval, status, end;
+    size_t part[2], pack[2][6], z[2], gram, tmat, eval, status, end;
 };
 
 // byte layout of one layer's private workspace region, relative to its start
@@ -125,8 +125,6 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     const int max_lenP = lenP[0] > lenP[1] ? lenP[0] : lenP[1];
     R.gram = take((size_t)(max_lenP / kGramRows2) * w2 * sizeof(double));
     R.tmat = take(w2 * sizeof(double));
-    R.evec = take(w2 * sizeof(double));
-    R.jwork = take(w2 * sizeof(double));
     R.eval = take((size_t)(c->wz + 2) * sizeof(double));
     R.status = take(8 * sizeof(int));
     R.end = o;
@@ -179,8 +177,6 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
     }
     L.gram = reinterpret_cast<double*>(base + R.gram);
     L.tmat = reinterpret_cast<double*>(base + R.tmat);
-    L.evec = reinterpret_cast<double*>(base + R.evec);
-    L.jwork = reinterpret_cast<double*>(base + R.jwork);
     L.eval = reinterpret_cast<double*>(base + R.eval);
     L.status = reinterpret_cast<int*>(base + R.status);
     *out = L;

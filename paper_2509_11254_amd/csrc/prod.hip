@@ -137,15 +137,7 @@ __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int ou
         if (ob * BT + row < out_len) T.ptr[(int64_t)(ob * BT + row) * T.ld + col] = otile[row * tw + col];
     }
     if (epi == EPI_GRAM) {
-        double* __restrict__ g = L.gram + (int64_t)ob * w * w;
-        for (int e = t; e < w * w; e += kThreads) {
-            const int i = e / w, j = e % w;
-            if (i > j) continue;
-            double s = 0.0;
-#pragma unroll 8
-            for (int row = 0; row < BT; ++row) s += (double)otile[row * tw + i] * (double)otile[row * tw + j];
-            g[e] = s;
-        }
+        gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * w * w);
     } else if (epi == EPI_PACK) {
         write_packs(L.pack[out_side], L.planes, otile, tw, cp, ob * BT, BT, out_lenP);
     }

@@ -65,11 +65,10 @@ struct LayerDev {
     PackRef pack[2];        // per side
     double* gram;           // [slots][w*w] partial Gram matrices, one slot per row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right
-    double* evec;           // [wmax*wmax] accumulated Jacobi rotations
-    double* jwork;          // [wmax*wmax] Jacobi working copy of the projected Gram matrix
     double* eval;           // [wmax]
     int* status;            // [8] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits,
-                            //       iterations the next refresh needs (0 = not known yet), 3 spare
+                            //       iterations the next refresh needs (0 = not known yet), Jacobi sweeps of the last
+                            //       refresh, 2 spare
 };
 
 __host__ __device__ inline int side_of_role(int transposed, int role) {
@@ -155,6 +154,35 @@ __device__ inline bool gate_open(const LayerDev& L, int gate) {
     int k = L.status[4];
     if (k <= 0 || k > mx) k = mx;
     return it < k - kind;
+}
+
+typedef __attribute__((__vector_size__(4 * sizeof(double)))) double doublex4;
+
+// Partial Gram matrix of a tile of finished rows on the fp64 matrix cores:
+//   g[i*w + j] = sum_rows tile[row][i] * tile[row][j]   for i <= j < w   (upper triangle only)
+// tile is fp32 in LDS, [nrows][tw], nrows a multiple of 4, columns up to the next multiple of 16 of w
+// readable (zero padded).  The 16 x 16 blocks (bi <= bj) are dealt to the four waves of the workgroup;
+// v_mfma_f64_16x16x4_f64 takes A = tile^T (lane: column, k: row) and B = tile.
+__device__ inline void gram_tile_f64(const float* tile, int tw, int nrows, int w, double* __restrict__ g) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int li = lane & 15, lk = lane >> 4;
+    const int nt = (w + 15) / 16;
+    int p = 0;
+    for (int bi = 0; bi < nt; ++bi)
+        for (int bj = bi; bj < nt; ++bj, ++p) {
+            if ((p & 3) != wv) continue;
+            doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+            const float* __restrict__ pa = tile + lk * tw + 16 * bi + li;
+            const float* __restrict__ pb = tile + lk * tw + 16 * bj + li;
+            for (int k0 = 0; k0 < nrows; k0 += 4)
+                acc = __builtin_amdgcn_mfma_f64_16x16x4f64((double)pa[k0 * tw], (double)pb[k0 * tw], acc, 0, 0, 0);
+            const int j = 16 * bj + li;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                const int i = 16 * bi + 4 * v + lk;
+                if (i <= j && j < w) g[(int64_t)i * w + j] = acc[v];
+            }
+        }
 }
 
 __device__ inline int side_len(const LayerDev& L, int side) { return side == SIDE_L ? L.rows : L.cols; }

@@ -75,7 +75,7 @@ __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)
 
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows, int inv_in_lds, int gate) {
+                                                        int pass, int slot_rows, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
@@ -85,8 +85,8 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
     extern __shared__ __align__(16) unsigned char smem[];
     double* a = reinterpret_cast<double*>(smem);          // packed upper triangle, w(w+1)/2
     double* dsc = a + (w * (w + 1)) / 2;                  // [w] scaling
-    double* rdiag = dsc + w;                              // [w] diagonal of the factor
-    int* bad = reinterpret_cast<int*>(rdiag + w);         // [w] dependent-column flags
+    double* rdiag = dsc + w;                              // [w] diagonal of the factor (then of its inverse)
+    int* bad = reinterpret_cast<int*>(rdiag + 2 * w);     // [w] dependent-column flags (after the column copy)
     const int t = threadIdx.x;
     for (int e = t; e < w * w; e += kThreads) {
         const int i = e / w, j = e % w;
@@ -144,23 +144,32 @@ __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restri
         }
         __syncthreads();
     }
-    // inverse of the upper-triangular factor, one column per thread, built in LDS (packed upper):
-    // T = R^{-1}; then tmat = D T with the dependent columns zeroed
-    // (for blocks too wide for a second triangle in LDS the scratch matrix evec in global memory is used)
-    double* ti = inv_in_lds ? reinterpret_cast<double*>(bad + w + (w & 1)) : L.evec;
-    for (int j = t; j < w; j += kThreads) {
-        ti[tri_idx(j, j, w)] = 1.0 / rdiag[j];
-        for (int i = j - 1; i >= 0; --i) {
-            double s = 0.0;
-            for (int l = i + 1; l <= j; ++l) s += a[tri_idx(i, l, w)] * ti[tri_idx(l, j, w)];
-            ti[tri_idx(i, j, w)] = -s / rdiag[i];
-        }
-    }
+    // inverse of the upper-triangular factor, in place in the packed triangle, column by column:
+    //   T_jj = 1 / R_jj,   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
+    // one thread per row i of the new column; then tmat = D T with the dependent columns zeroed
+    double* tcol = rdiag + w;            // [w] copy of the column of R that is being replaced
+    for (int i = t; i < w; i += kThreads) rdiag[i] = 1.0 / rdiag[i];          // rdiag now holds T_ii
     __syncthreads();
+    for (int j = 1; j < w; ++j) {
+        for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
+        __syncthreads();
+        const double tjj = rdiag[j];
+        for (int i = t; i < j; i += kThreads) {
+            const int base = tri_idx(i, i, w) - i;
+            double sacc = rdiag[i] * tcol[i];
+            for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
+            a[base + j] = -tjj * sacc;
+        }
+        __syncthreads();
+    }
     double* __restrict__ tm = L.tmat;
-    for (int e = t; e < w * w; e += kThreads) {
-        const int i = e / w, j = e % w;
-        tm[e] = (i <= j && !bad[j]) ? ti[tri_idx(i, j, w)] * dsc[i] : 0.0;
+    for (int i = ty; i < w; i += 16) {
+        const int base = tri_idx(i, i, w) - i;
+        for (int j = tx; j < w; j += 16) {
+            double v = 0.0;
+            if (!bad[j]) v = (i < j) ? a[base + j] : (i == j ? rdiag[i] : 0.0);
+            tm[(int64_t)i * w + j] = v * dsc[i];
+        }
     }
     if (t == 0) {
         int nbad = 0;
@@ -178,14 +187,13 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
                        int slot_rows, int gate, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
-    const int inv_in_lds = w <= 128 ? 1 : 0;
-    const size_t lds = (size_t)((inv_in_lds ? 2 : 1) * (w * (w + 1)) / 2 + 2 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
+    const size_t lds = (size_t)((w * (w + 1)) / 2 + 3 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chol_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, inv_in_lds, gate);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate);
     return hipGetLastError();
 }
 
@@ -200,8 +208,6 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
 //   APPLY_RITZ   (full tmat)            : final + operand copies if cp > 0
 // --------------------------------------------------------------------------------------------
 enum ApplyMode { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
-
-typedef __attribute__((__vector_size__(4 * sizeof(double)))) double doublex4;
 
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
@@ -304,15 +310,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
         }
     }
     if (do_gram) {
-        double* __restrict__ g = L.gram + (int64_t)blockIdx.x * w_out * w_out;
-        for (int e = t; e < w_out * w_out; e += kThreads) {
-            const int i = e / w_out, j = e % w_out;
-            if (i > j) continue;
-            double s = 0.0;
-#pragma unroll 8
-            for (int row = 0; row < kGramRows2; ++row) s += (double)so[row * ow + i] * (double)so[row * ow + j];
-            g[e] = s;
-        }
+        gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)blockIdx.x * w_out * w_out);
     } else if (do_pack) {
         write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP);
     }
@@ -384,123 +382,161 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 // --------------------------------------------------------------------------------------------
 // Rayleigh-Ritz: eigen-decomposition of the w x w Gram matrix H = Y^T Y (Y = M^T Z, Z orthonormal)
 // by cyclic two-sided Jacobi in fp64 with a round-robin ordering (w/2 disjoint rotations per round).
-// One workgroup per layer.  On exit tmat[:, k] is the eigenvector of the k-th largest eigenvalue,
-// so that P~ = Z tmat[:, :r] are the leading left singular vectors (Definition 3) and
-// Q = Y tmat[:, :r] = M^T P~.  status gets sigma_1 and sigma_r = sqrt(eigenvalue).
+// One workgroup per layer.  H is kept as a packed upper triangle in LDS; in a round the 2 x 2 blocks
+// (pair k1 rows) x (pair k2 columns), k1 <= k2, are independent of each other and are rotated in
+// place.  The accumulated rotations V live in LDS when they fit, else in the layer's scratch matrix.
+// On exit tmat[:, k] is the eigenvector of the k-th largest eigenvalue, so that P~ = Z tmat[:, :r] are
+// the leading left singular vectors (Definition 3) and Q = Y tmat[:, :r] = M^T P~.  status gets
+// sigma_1 and sigma_r = sqrt(eigenvalue), and the iteration count the next refresh needs.
 // --------------------------------------------------------------------------------------------
-constexpr int kJacobiThreads = 256;
 constexpr int kJacobiMaxSweeps = 30;
 
-__global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* __restrict__ layers,
-                                                                const int* __restrict__ ids, int role,
-                                                                int use_lds, float* __restrict__ sigma_out) {
+__device__ inline int sym_idx(int i, int j, int n) {          // packed upper triangle, any order of (i, j)
+    const int a = min(i, j), b = max(i, j);
+    return a * n - (a * (a - 1)) / 2 + (b - a);
+}
+
+// Rotation that annihilates H[p][q] for the pair number k of round rd (round-robin tournament on n players).
+__device__ inline void jacobi_rotation(const double* a, int n, int rd, int k, double* cs, int* pq) {
+    const int half = n / 2;
+    int p, q;
+    if (k == 0) { p = n - 1; q = rd; }
+    else {
+        p = rd + k; if (p >= n - 1) p -= n - 1;
+        q = rd - k; if (q < 0) q += n - 1;
+    }
+    if (p > q) { const int tmp = p; p = q; q = tmp; }
+    const double app = a[sym_idx(p, p, n)], aqq = a[sym_idx(q, q, n)], apq = a[sym_idx(p, q, n)];
+    double c = 1.0, sn = 0.0;
+    if (fabs(apq) > 1e-300 && apq * apq > 1e-36 * fabs(app * aqq)) {
+        // t = sgn(tau) / (|tau| + sqrt(1 + tau^2)), tau = (aqq - app) / (2 apq), written with one division
+        const double d = aqq - app, b = 2.0 * apq;
+        const double tt = (d >= 0.0 ? b : -b) / (fabs(d) + sqrt(d * d + b * b));
+        c = rsqrt(1.0 + tt * tt);
+        sn = tt * c;
+    }
+    cs[k] = c; cs[half + k] = sn; pq[k] = p; pq[half + k] = q;
+}
+
+// grid = (slices, layers): every workgroup of a layer repeats the (deterministic) iteration on H and
+// accumulates the rotations into its own slice of v_rows rows of V, which is independent of the other rows.
+__global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict__ layers,
+                                                      const int* __restrict__ ids, int role, int v_rows,
+                                                      float* __restrict__ sigma_out) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int w = L.thin[role].width;
     const int n_slots = (side_len(L, side_of_role(L.transposed, role)) + kGramRows1 - 1) / kGramRows1;
     const int n = (w + 1) & ~1;      // even size for the round-robin schedule (a zero row/column is added)
-    extern __shared__ __align__(16) unsigned char smem[];
-    double* cs = reinterpret_cast<double*>(smem);      // [n/2] cos, [n/2] sin
-    int* pq = reinterpret_cast<int*>(cs + n);          // [n/2] p, [n/2] q
-    double* red = reinterpret_cast<double*>(pq + n);   // [2] reduction scratch
-    double* a = use_lds ? red + 2 : L.jwork;           // n x n working copy of H
-    double* v = use_lds ? a + n * n : L.evec;          // n x n accumulated rotations
-    const int t = threadIdx.x;
-    const int nt = kJacobiThreads;
-    const int tx = t & 15, ty = t >> 4;     // threads as a 16 x 16 grid: loops over pairs need no division
-    // H (symmetric) = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue
-    for (int e = t; e < n * n; e += nt) {
-        const int i = e / n, j = e % n;
-        double s = 0.0;
-        if (i < w && j < w) {
-            const int ii = min(i, j), jj = max(i, j);
-            for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)ii * w + jj];
-        }
-        a[e] = s;
-        v[e] = (i == j) ? 1.0 : 0.0;
-    }
-    __syncthreads();
-
     const int half = n / 2;
+    const int row0 = blockIdx.x * v_rows;
+    const int nv = min(v_rows, n - row0);              // rows of V kept by this workgroup
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* csb = reinterpret_cast<double*>(smem);     // two buffers of [half] cos, [half] sin
+    double* red = csb + 2 * n;                         // [2] reduction scratch
+    double* a = red + 2;                               // packed upper triangle of H, n(n+1)/2
+    double* v = a + (n * (n + 1)) / 2;                 // v_rows x n slice of the accumulated rotations
+    int* pqb = reinterpret_cast<int*>(v + v_rows * n); // two buffers of [half] p, [half] q
+    const int t = threadIdx.x;
+    const int nt = blockDim.x;
+    const int tw = nt >= 1024 ? 32 : 16;               // threads as a tw x tw grid: no integer division
+    const int tx = t & (tw - 1), ty = t / tw;
+    // H = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue
+    for (int i = ty; i < n; i += tw)
+        for (int j = i + tx; j < n; j += tw) {
+            double s = 0.0;
+            if (j < w)
+                for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)i * w + j];
+            a[sym_idx(i, j, n)] = s;
+        }
+    for (int i = ty; i < nv; i += tw)
+        for (int j = tx; j < n; j += tw) v[i * n + j] = (row0 + i == j) ? 1.0 : 0.0;
+    __syncthreads();
+    int cur = 0, sweeps = 0;
     for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
         // convergence: off-diagonal mass relative to the diagonal
         if (t < 2) red[t] = 0.0;
         __syncthreads();
         double off = 0.0, dia = 0.0;
-        for (int i = ty; i < n; i += 16)
-            for (int j = tx; j < n; j += 16) {
-                const double x = a[i * n + j];
-                if (i == j) dia += x * x; else off += x * x;
+        for (int i = ty; i < n; i += tw) {
+            const int base = sym_idx(i, i, n) - i;
+            for (int j = i + tx; j < n; j += tw) {
+                const double x = a[base + j];
+                if (i == j) dia += x * x; else off += 2.0 * x * x;
             }
+        }
         for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
         if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
         __syncthreads();
         const bool done = red[0] <= 1e-20 * red[1];
-        __syncthreads();
         if (done) break;
+        sweeps = sweep + 1;
+        if (t < half) jacobi_rotation(a, n, 0, t, csb + cur * n, pqb + cur * n);
+        __syncthreads();
         for (int rd = 0; rd < n - 1; ++rd) {
-            // the half disjoint pairs (p, q) of this round and their rotations, from the current A
-            if (t < half) {
-                int p, q;
-                if (t == 0) { p = n - 1; q = rd; }
-                else { p = (rd + t) % (n - 1); q = (rd - t + (n - 1)) % (n - 1); }
-                if (p > q) { const int tmp = p; p = q; q = tmp; }
-                const double app = a[p * n + p], aqq = a[q * n + q], apq = a[p * n + q];
-                double c = 1.0, s = 0.0;
-                if (fabs(apq) > 1e-300 && fabs(apq) > 1e-18 * sqrt(fabs(app * aqq))) {
-                    const double tau = (aqq - app) / (2.0 * apq);
-                    const double tt = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
-                    c = 1.0 / sqrt(1.0 + tt * tt);
-                    s = tt * c;
+            const double* cs = csb + cur * n;
+            const int* pq = pqb + cur * n;
+            // H <- J^T H J on the 2 x 2 blocks k1 <= k2 (the others are their transposes)
+            for (int k1 = ty; k1 < half; k1 += tw) {
+                const int p1 = pq[k1], q1 = pq[half + k1];
+                const double c1 = cs[k1], s1 = cs[half + k1];
+                for (int k2 = k1 + tx; k2 < half; k2 += tw) {
+                    if (k1 == k2) {
+                        const int ipp = sym_idx(p1, p1, n), ipq = sym_idx(p1, q1, n), iqq = sym_idx(q1, q1, n);
+                        const double app = a[ipp], apq = a[ipq], aqq = a[iqq];
+                        a[ipp] = c1 * c1 * app - 2.0 * c1 * s1 * apq + s1 * s1 * aqq;
+                        a[iqq] = s1 * s1 * app + 2.0 * c1 * s1 * apq + c1 * c1 * aqq;
+                        a[ipq] = (c1 * c1 - s1 * s1) * apq + c1 * s1 * (app - aqq);
+                    } else {
+                        const int p2 = pq[k2], q2 = pq[half + k2];
+                        const double c2 = cs[k2], s2 = cs[half + k2];
+                        const int i00 = sym_idx(p1, p2, n), i01 = sym_idx(p1, q2, n);
+                        const int i10 = sym_idx(q1, p2, n), i11 = sym_idx(q1, q2, n);
+                        const double app = a[i00], apq = a[i01], aqp = a[i10], aqq = a[i11];
+                        // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
+                        const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
+                        const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
+                        // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
+                        a[i00] = c2 * rpp - s2 * rpq;
+                        a[i01] = s2 * rpp + c2 * rpq;
+                        a[i10] = c2 * rqp - s2 * rqq;
+                        a[i11] = s2 * rqp + c2 * rqq;
+                    }
                 }
-                cs[t] = c; cs[half + t] = s; pq[t] = p; pq[half + t] = q;
             }
             __syncthreads();
-            // A <- J^T A J in place: the 2x2 block (pair k1 rows) x (pair k2 columns) only depends on itself
-            for (int k1 = ty; k1 < half; k1 += 16)
-              for (int k2 = tx; k2 < half; k2 += 16) {
-                const int p1 = pq[k1], q1 = pq[half + k1], p2 = pq[k2], q2 = pq[half + k2];
-                const double c1 = cs[k1], s1 = cs[half + k1], c2 = cs[k2], s2 = cs[half + k2];
-                const double app = a[p1 * n + p2], apq = a[p1 * n + q2], aqp = a[q1 * n + p2], aqq = a[q1 * n + q2];
-                // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
-                const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
-                const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
-                // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
-                a[p1 * n + p2] = c2 * rpp - s2 * rpq;
-                a[p1 * n + q2] = s2 * rpp + c2 * rpq;
-                a[q1 * n + p2] = c2 * rqp - s2 * rqq;
-                a[q1 * n + q2] = s2 * rqp + c2 * rqq;
-            }
-            // V <- V J
-            for (int k = ty; k < half; k += 16)
-              for (int i = tx; i < n; i += 16) {
-                const int p = pq[k], q = pq[half + k];
-                const double c = cs[k], s = cs[half + k];
-                const double vx = v[i * n + p], vy = v[i * n + q];
-                v[i * n + p] = c * vx - s * vy;
-                v[i * n + q] = s * vx + c * vy;
-            }
+            // the next round's rotations (from the updated H) while the other waves finish V <- V J
+            if (rd + 1 < n - 1 && t < half) jacobi_rotation(a, n, rd + 1, t, csb + (cur ^ 1) * n, pqb + (cur ^ 1) * n);
+            for (int i = ty; i < nv; i += tw)
+                for (int k = tx; k < half; k += tw) {
+                    const int p = pq[k], q = pq[half + k];
+                    const double c = cs[k], sn = cs[half + k];
+                    const double vx = v[i * n + p], vy = v[i * n + q];
+                    v[i * n + p] = c * vx - sn * vy;
+                    v[i * n + q] = sn * vx + c * vy;
+                }
             __syncthreads();
+            cur ^= 1;
         }
     }
+    __syncthreads();
     // sort: rank of eigenvalue j = number of eigenvalues that come before it (ties by index)
+    int* rank_of = pqb;
     double* __restrict__ tm = L.tmat;
     for (int j = t; j < w; j += nt) {
-        const double lj = a[j * n + j];
+        const double lj = a[sym_idx(j, j, n)];
         int rank = 0;
         for (int k = 0; k < w; ++k) {
-            const double lk = a[k * n + k];
+            const double lk = a[sym_idx(k, k, n)];
             rank += (lk > lj || (lk == lj && k < j)) ? 1 : 0;
         }
-        pq[j] = rank;     // w <= n entries available
-        L.eval[rank] = lj;
+        rank_of[j] = rank;     // 2n entries available
+        if (blockIdx.x == 0) L.eval[rank] = lj;
     }
     __syncthreads();
-    for (int e = t; e < w * w; e += nt) {
-        const int i = e / w, j = e % w;
-        tm[(int64_t)i * w + pq[j]] = v[i * n + j];
-    }
-    __syncthreads();
-    __threadfence_block();
+    for (int i = ty; i < nv; i += tw)
+        if (row0 + i < w)
+            for (int j = tx; j < w; j += tw) tm[(int64_t)(row0 + i) * w + rank_of[j]] = v[i * n + j];
+    if (blockIdx.x != 0) return;
     const int r = L.r;
     for (int k = t; k < r; k += nt) {
         const float sg = (float)sqrt(fmax(L.eval[k], 0.0));
@@ -519,28 +555,35 @@ __global__ __launch_bounds__(kJacobiThreads) void jacobi_kernel(const LayerDev* 
             if (rho < 0.999) k_next = (rho <= 1e-12) ? 2 : (int)ceil(log(1e-6) / log(rho)) + 1;
         }
         L.status[4] = max(2, min(255, k_next));
+        L.status[5] = sweeps;
     }
 }
 
-size_t jacobi_lds_bytes(int w, int use_lds) {
+size_t jacobi_lds_bytes(int w, int v_rows) {
     const int n = (w + 1) & ~1;
-    size_t b = (size_t)n * sizeof(double) + (size_t)n * sizeof(int) + 2 * sizeof(double);
-    if (use_lds) b += (size_t)2 * n * n * sizeof(double);
-    return b;
+    return (size_t)(2 * n + 2 + (n * (n + 1)) / 2 + v_rows * n) * sizeof(double) + (size_t)2 * n * sizeof(int);
 }
 
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
                          hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
-    const int use_lds = jacobi_lds_bytes(w, 1) <= 150 * 1024 ? 1 : 0;
-    const size_t lds = jacobi_lds_bytes(w, use_lds);
-    dim3 grid(1, n_ids), block(kJacobiThreads);
+    const int n = (w + 1) & ~1;
+    // rows of V per workgroup: as few as 8 while the chip has idle compute units, and no more than fit in LDS
+    int slices = 256 / n_ids;
+    slices = slices < 1 ? 1 : slices;
+    int v_rows = (n + slices - 1) / slices;
+    v_rows = v_rows < 8 ? 8 : v_rows;
+    while (v_rows > 1 && jacobi_lds_bytes(w, v_rows) > 150 * 1024) --v_rows;
+    if (jacobi_lds_bytes(w, v_rows) > 150 * 1024) return hipErrorInvalidValue;
+    v_rows = v_rows > n ? n : v_rows;
+    const size_t lds = jacobi_lds_bytes(w, v_rows);
+    dim3 grid((n + v_rows - 1) / v_rows, n_ids), block(w > 48 ? 1024 : 256);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(jacobi_kernel, grid, block, lds, st, layers, ids, role, use_lds, sigma_out);
+    hipLaunchKernelGGL(jacobi_kernel, grid, block, lds, st, layers, ids, role, v_rows, sigma_out);
     return hipGetLastError();
 }
 
