@@ -17,13 +17,15 @@ hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerD
 hipError_t launch_outer(int nb, int planes, bool decomp, const LayerDev* layers, const int* ids, int n_ids,
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, int gate, hipStream_t st);
-hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
-                       hipStream_t st);
+                         int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
+                         hipStream_t st);
+hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
+                       int cp, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, hipStream_t st);
+                       int slot_rows, int gate, int a2gate, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
-                        int src_role, int dst_role, int mode, int cp, int gate, hipStream_t st);
+                        int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
+                        hipStream_t st);
 hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
                              int src_role, int warm, uint32_t seed, hipStream_t st);
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
@@ -270,28 +272,39 @@ struct Launcher {
     int max_len() const { return max_rows > max_cols ? max_rows : max_cols; }
     int max_lenP() const { return max_rowsP > max_colsP ? max_rowsP : max_colsP; }
 
-    void pack(int role, int cp) { note(launch_pack(layers, ids_all, n_all, max_lenP(), role, cp, st)); }
-    // product whose result is P-like (lives on the long side) or Q-like, stored in thin[out_role]
-    void prod(bool p_like, bool form, int nb, int out_role, int epi) {
+    void pack(int role, int cp, int role_b = -1) { note(launch_pack(layers, ids_all, n_all, max_lenP(), role, role_b, cp, st)); }
+    // product whose result is P-like (lives on the long side) or Q-like, stored in thin[out_role];
+    // chol_gate >= -1: the first CholeskyQR pass on the result follows at once (see prod_orth)
+    void prod(bool p_like, bool form, int nb, int out_role, int epi, int chol_gate = -2, int a2gate = -2,
+              double tol2 = 0.0, int w = 0) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, epi, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, epi, gate, st));
         prof_end(k);
-        // split reductions are completed (and the epilogue run) by a second, small launch
+        // split reductions are completed (and the epilogue run) by a second, small launch, whose last
+        // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
         const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, st));
-        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, st));
+        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, st));
+        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, st));
+        if (chol_gate >= -1) {
+            if (!split_n) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, st));
+            if (!split_t) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, st));
+        }
     }
-    // CholeskyQR2 on thin[role], whose partial Gram matrices the producing product has just written;
-    // the result is final after pass 1 unless the conditioning asks for pass 2 (decided on the device);
-    // cp > 0: also leave the split-bf16 operand copies of the result
-    void orth(int role, int w, double tol2, int cp, int kind = 0) {
+    // thin[out_role] = product as in prod(), then CholeskyQR2 on it: the first pass always, the second
+    // when the first one's pivots ask for it (decided on the device) and `pass2` allows it.  Inside the
+    // subspace iteration the second pass is only wanted where exact orthonormality matters: on Z in a
+    // layer's last iteration.  cp > 0: also leave the split-bf16 operand copies of the result.
+    enum Pass2 { PASS2_NEVER = 0, PASS2_ALWAYS = 1, PASS2_LAST_ITERATION = 2 };
+    void prod_orth(bool p_like, bool form, int nb, int out_role, int w, double tol2, int cp, int kind, Pass2 pass2) {
         const int g = gate < 0 ? -1 : (gate | kind << 8);
-        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 1, kGramRows1, g, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS1, cp, g, st));
-        note(launch_chol(layers, ids_all, n_all, w, role, tol2, 2, kGramRows2, g, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, role, role, APPLY_PASS2, cp, g, st));
+        const int a2 = pass2 == PASS2_ALWAYS ? -1 : (pass2 == PASS2_NEVER || gate < 0) ? -2 : (gate | 2 << 8);
+        prod(p_like, form, nb, out_role, EPI_GRAM, g, a2, tol2, w);
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, st));
+        if (a2 != -2)
+            note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp,
+                              a2 == -1 ? g : a2, a2, tol2, st));
     }
     void residual(int nb) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
@@ -344,18 +357,17 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
         // every layer runs its own number of iterations (decided on the device from the Ritz values of
         // its previous refresh); launches past that number find their gate closed and exit at once
         L.gate = it | (iters << 16);
-        L.prod(true, form_first && it == 0, nbz, ROLE_ZP, EPI_GRAM);     // Z = M Y
-        L.orth(ROLE_ZP, wz, tol2, cpz);
-        L.prod(false, false, nbz, ROLE_ZQ, EPI_GRAM);                    // Y = M^T Z
-        L.orth(ROLE_ZQ, wz, tol2, cpz, 1);                               // not in a layer's last iteration
+        // Z = orth(M Y);  Y = M^T Z, orthonormalised except in a layer's last iteration
+        L.prod_orth(true, form_first && it == 0, nbz, ROLE_ZP, wz, tol2, cpz, 0, Launcher::PASS2_LAST_ITERATION);
+        L.prod_orth(false, false, nbz, ROLE_ZQ, wz, tol2, cpz, 1, Launcher::PASS2_NEVER);
     }
     L.gate = -1;
     // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZP, ROLE_P, APPLY_RITZ,
-                        final_cp, -1, L.st));
+                        final_cp, -1, -2, 0.0, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, APPLY_RITZ,
-                        final_cp, -1, L.st));
+                        final_cp, -1, -2, 0.0, L.st));
     L.prof_mute = false;
 }
 
@@ -490,8 +502,8 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp);
-    L.prod(true, true, nb, ROLE_P, EPI_GRAM);      // P = M Q_{t-1}; M formed and stored on the way
-    L.orth(ROLE_P, ctx->rmax, tol2_of(ctx), cp);   // P~ = QR(P), operand copies of P~
+    // P = M Q_{t-1} (M formed and stored on the way); P~ = QR(P), operand copies of P~
+    L.prod_orth(true, true, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
     L.prod(false, false, nb, ROLE_Q, EPI_PACK);    // Q_t = M^T P~, operand copies of Q_t
     L.residual(nb);                                // E <- M - P~ Q_t^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
@@ -563,8 +575,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp);
-    L.pack(ROLE_Q, cp);
+    L.pack(ROLE_P, cp, ROLE_Q);
     L.note(launch_outer(nb, ctx->planes, true, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);

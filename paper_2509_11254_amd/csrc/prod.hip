@@ -11,7 +11,7 @@
 // and the product is accumulated in fp32 as hi*hi + lo*hi + hi*lo with v_mfma_f32_32x32x16_bf16.
 // The S tile goes global -> registers (coalesced 16-byte loads, summed over workers) -> LDS in the
 // k-contiguous layout the MFMA A operand wants; the thin operand arrives pre-split and transposed.
-#include "psgd_dev.h"
+#include "thin_dev.h"
 
 namespace psgd {
 
@@ -137,7 +137,7 @@ __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int ou
         if (ob * BT + row < out_len) T.ptr[(int64_t)(ob * BT + row) * T.ld + col] = otile[row * tw + col];
     }
     if (epi == EPI_GRAM) {
-        gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * w * w);
+        gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * ((w * (w + 1)) / 2));
     } else if (epi == EPI_PACK) {
         write_packs(L.pack[out_side], L.planes, otile, tw, cp, ob * BT, BT, out_lenP);
     }
@@ -340,9 +340,14 @@ __global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __res
 
 // Sum of the partial products of a split launch + the same epilogue.  One workgroup per 128-row
 // output block; the partials are added in split order, so the result is deterministic.
+// chol_gate >= -1: the last workgroup to finish a layer goes on to factorise the sum of the partial Gram
+// matrices (first CholeskyQR pass) if that gate is open, unless the layer is one where the apply kernel
+// does that for itself; -2: no factorisation follows.
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
-                                                          int out_role, int epi, int gate) {
+                                                          int out_role, int epi, int gate, int chol_gate,
+                                                          int a2gate, double tol2) {
+    __shared__ int s_last;
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     const int out_side = colmode ? SIDE_W : SIDE_L;
@@ -383,19 +388,27 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     }
     __syncthreads();
     tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
+    if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role) && gate_open(L, chol_gate)) {
+        const int n_wg = (out_len + BT - 1) / BT;
+        if (last_to_arrive(&L.status[6], n_wg, &s_last))
+            chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat);
+    }
 }
 
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, int gate, hipStream_t st) {
+                         int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
+                         hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
     dim3 grid(max_blocks, n_ids), block(kThreads);
-    const size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
+    size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
+    if (chol_gate >= -1 && chol_lds_bytes_upto(w) > lds) lds = chol_lds_bytes_upto(w);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(finish_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate);
+    hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate,
+                       chol_gate, a2gate, tol2);
     return hipGetLastError();
 }
 

@@ -63,12 +63,14 @@ struct LayerDev {
     ThinRef thin[ROLE_COUNT];
     float* part[2];         // per side: [split][width][lenP] fp32 partial products of a split reduction
     PackRef pack[2];        // per side
-    double* gram;           // [slots][w*w] partial Gram matrices, one slot per row block of the producer
+    double* gram;           // [slots][w(w+1)/2] partial Gram matrices (packed upper triangles), one slot per
+                            // row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right
     double* eval;           // [wmax]
     int* status;            // [8] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits,
                             //       iterations the next refresh needs (0 = not known yet), Jacobi sweeps of the last
-                            //       refresh, 2 spare
+                            //       refresh, arrival counters of the two
+                            //       kernels that hand over to the factorisation
 };
 
 __host__ __device__ inline int side_of_role(int transposed, int role) {
@@ -147,19 +149,24 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 // Launches inside the subspace iteration carry a gate = iteration | kind << 8 | max_iterations << 16
 // (-1 outside it).  A layer runs k iterations, k = status[4] clamped to max_iterations (all of them
 // while status[4] is still 0); kind 1 marks the orthonormalisation of Y, which the last executed
-// iteration skips because the Rayleigh-Ritz step wants Y = M^T Z itself.
+// iteration skips because the Rayleigh-Ritz step wants Y = M^T Z itself; kind 2 is open in the last
+// executed iteration only (the second CholeskyQR pass on Z, which the Rayleigh-Ritz step needs exact).
 __device__ inline bool gate_open(const LayerDev& L, int gate) {
     if (gate < 0) return true;
     const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
     int k = L.status[4];
     if (k <= 0 || k > mx) k = mx;
+    if (kind == 2) return it == k - 1;
     return it < k - kind;
 }
 
 typedef __attribute__((__vector_size__(4 * sizeof(double)))) double doublex4;
 
+// index of (i, j), i <= j, in a packed upper triangle of order w stored row by row
+__host__ __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)) / 2 + (j - i); }
+
 // Partial Gram matrix of a tile of finished rows on the fp64 matrix cores:
-//   g[i*w + j] = sum_rows tile[row][i] * tile[row][j]   for i <= j < w   (upper triangle only)
+//   g[tri_idx(i, j, w)] = sum_rows tile[row][i] * tile[row][j]   for i <= j < w   (packed upper triangle)
 // tile is fp32 in LDS, [nrows][tw], nrows a multiple of 4, columns up to the next multiple of 16 of w
 // readable (zero padded).  The 16 x 16 blocks (bi <= bj) are dealt to the four waves of the workgroup;
 // v_mfma_f64_16x16x4_f64 takes A = tile^T (lane: column, k: row) and B = tile.
@@ -180,7 +187,7 @@ __device__ inline void gram_tile_f64(const float* tile, int tw, int nrows, int w
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int i = 16 * bi + 4 * v + lk;
-                if (i <= j && j < w) g[(int64_t)i * w + j] = acc[v];
+                if (i <= j && j < w) g[tri_idx(i, j, w)] = acc[v];
             }
         }
 }

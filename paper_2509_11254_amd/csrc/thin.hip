@@ -1,22 +1,20 @@
 // Kernels on the thin (len x w) matrices of the compressor: operand packing, reduction of the
 // split products, the orthonormaliser, the Rayleigh-Ritz step of the refresh, random start blocks.
 //
-// Orthonormalisation (Section 2, "QR decomposition": Q-factor of the economic QR) is CholeskyQR2:
-//   G = X^T X (fp64, exact products of the fp32 entries);  G_s = D G D with D = diag(G)^{-1/2};
-//   G_s = R_s^T R_s (Cholesky, fp64);  X <- X (D R_s^{-1});  then the same once more on the result.
-// The Q-factor it converges to is the one with a positive diagonal of R.  A pivot of the scaled
-// Cholesky at step k equals (norm of column k's part orthogonal to the earlier columns / norm of
-// column k)^2; if it is <= rank_tol^2 the column is declared dependent and its P~ column is zero.
-#include "psgd_dev.h"
+// The small factorisation of the orthonormaliser (CholeskyQR2) is in thin_dev.h.
+#include "thin_dev.h"
 
 namespace psgd {
 
 // --------------------------------------------------------------------------------------------
 // pack: thin fp32 (len x width, ld) -> split-bf16 operand copies, row-major and transposed.
 // --------------------------------------------------------------------------------------------
+// grid.z walks the roles to pack (role_a, then role_b when two are asked for)
 __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restrict__ layers,
-                                                        const int* __restrict__ ids, int role, int cp) {
+                                                        const int* __restrict__ ids, int role_a, int role_b,
+                                                        int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    const int role = blockIdx.z == 0 ? role_a : role_b;
     const int side = side_of_role(L.transposed, role);
     const int len = side_len(L, side), lenP = side_lenP(L, side);
     const int i0 = blockIdx.x * 64;
@@ -35,165 +33,47 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restri
     write_packs(L.pack[side], L.planes, tile, tw, cp, i0, 64, lenP);
 }
 
-hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role, int cp,
-                       hipStream_t st) {
+// role_b < 0: one role
+hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
+                       int cp, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
-    dim3 grid(max_lenP / 64, n_ids), block(kThreads);
+    dim3 grid(max_lenP / 64, n_ids, role_b >= 0 ? 2 : 1), block(kThreads);
     const size_t lds = (size_t)64 * (cp + 1) * sizeof(float);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(pack_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(pack_kernel, grid, block, lds, st, layers, ids, role, cp);
+    hipLaunchKernelGGL(pack_kernel, grid, block, lds, st, layers, ids, role_a, role_b, cp);
     return hipGetLastError();
 }
 
 // --------------------------------------------------------------------------------------------
-// chol: one workgroup per layer.  Sums the partial Gram matrices (slots of `slot_rows` rows, fixed
-// order), scales to unit diagonal, Cholesky-factorises (upper, packed in LDS), inverts the factor
-// and writes tmat = D R_s^{-1}.  pass 1 also decides whether the second CholeskyQR pass is needed:
-// the smallest pivot of the scaled factorisation is about 1/cond^2 of the column-scaled matrix and
-// the first pass leaves an orthogonality error of about 1e-16/pivot; below kSecondPassPivot the
-// flag status[1] is set and the pass-2 kernels (which exit at once otherwise) do their work.
+// chol: one workgroup per layer runs the factorisation on the partial Gram matrices that the producing
+// kernel has left (used when that kernel cannot hand over to it itself).
 // --------------------------------------------------------------------------------------------
-constexpr double kSecondPassPivot = 1e-6;
-
-// Barrier of the threads that work on a small matrix: the whole workgroup, or, when a single
-// wavefront does the work, nothing but an ordering point (LDS accesses of one wave execute in order).
-__device__ inline void sync_group(bool single_wave) {
-    if (single_wave) {
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-    } else {
-        __syncthreads();
-    }
-}
-
-__device__ inline int tri_idx(int i, int j, int w) { return i * w - (i * (i - 1)) / 2 + (j - i); }   // i <= j
-
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows, int gate) {
+                                                        int pass, int slot_rows, int gate, int a2gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
-    const int side = side_of_role(L.transposed, role);
-    const int n_slots = (side_len(L, side) + slot_rows - 1) / slot_rows;
-    const int w = L.thin[role].width;
+    if (pass == 1 && local_chol(L, role)) return;       // the apply kernel factorises for itself
     extern __shared__ __align__(16) unsigned char smem[];
-    double* a = reinterpret_cast<double*>(smem);          // packed upper triangle, w(w+1)/2
-    double* dsc = a + (w * (w + 1)) / 2;                  // [w] scaling
-    double* rdiag = dsc + w;                              // [w] diagonal of the factor (then of its inverse)
-    int* bad = reinterpret_cast<int*>(rdiag + 2 * w);     // [w] dependent-column flags (after the column copy)
-    const int t = threadIdx.x;
-    for (int e = t; e < w * w; e += kThreads) {
-        const int i = e / w, j = e % w;
-        if (i > j) continue;
-        const double* __restrict__ g = L.gram + e;
-        double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-        int sl = 0;
-        for (; sl + 8 <= n_slots; sl += 8) {      // independent loads in flight; order of the sum is fixed
-            double x[8];
-#pragma unroll
-            for (int d = 0; d < 8; ++d) x[d] = g[(int64_t)(sl + d) * w * w];
-            s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
-        }
-        for (; sl < n_slots; ++sl) s0 += g[(int64_t)sl * w * w];
-        a[tri_idx(i, j, w)] = (s0 + s1) + (s2 + s3);
-    }
-    __syncthreads();
-    for (int i = t; i < w; i += kThreads) {
-        const double d = a[tri_idx(i, i, w)];
-        dsc[i] = d > 0.0 ? 1.0 / sqrt(d) : 0.0;
-        bad[i] = d > 0.0 ? 0 : 1;
-    }
-    __syncthreads();
-    for (int e = t; e < w * w; e += kThreads) {
-        const int i = e / w, j = e % w;
-        if (i <= j) a[tri_idx(i, j, w)] *= dsc[i] * dsc[j];
-    }
-    __syncthreads();
-    // right-looking Cholesky, A = R^T R, R overwrites the upper triangle.  The trailing update walks
-    // the threads as a 16 x 16 grid over (row, column) so that no integer division is needed.
-    const int tx = t & 15, ty = t >> 4;
-    double min_piv = 1.0;
-    for (int k = 0; k < w; ++k) {
-        // every thread reads the pivot itself; the diagonal of R goes to rdiag, so the pivot entry is
-        // never overwritten and two barriers per step are enough
-        const double piv = a[tri_idx(k, k, w)];
-        const bool dep = bad[k] || !(piv > tol2);
-        if (!dep && piv < min_piv) min_piv = piv;
-        const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
-        if (dep) {
-            if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
-            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
-        } else {
-            const double rinv = 1.0 / sqrt(piv);
-            if (t == 0) rdiag[k] = sqrt(piv);
-            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
-        }
-        __syncthreads();
-        if (!dep) {
-            for (int i = k + 1 + ty; i < w; i += 16) {
-                const double rki = a[kbase + i];
-                const int base = tri_idx(i, i, w) - i;
-                for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
-            }
-        }
-        __syncthreads();
-    }
-    // inverse of the upper-triangular factor, in place in the packed triangle, column by column:
-    //   T_jj = 1 / R_jj,   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
-    // one thread per row i of the new column; then tmat = D T with the dependent columns zeroed
-    double* tcol = rdiag + w;            // [w] copy of the column of R that is being replaced
-    for (int i = t; i < w; i += kThreads) rdiag[i] = 1.0 / rdiag[i];          // rdiag now holds T_ii
-    __syncthreads();
-    for (int j = 1; j < w; ++j) {
-        for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
-        __syncthreads();
-        const double tjj = rdiag[j];
-        for (int i = t; i < j; i += kThreads) {
-            const int base = tri_idx(i, i, w) - i;
-            double sacc = rdiag[i] * tcol[i];
-            for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
-            a[base + j] = -tjj * sacc;
-        }
-        __syncthreads();
-    }
-    double* __restrict__ tm = L.tmat;
-    for (int i = ty; i < w; i += 16) {
-        const int base = tri_idx(i, i, w) - i;
-        for (int j = tx; j < w; j += 16) {
-            double v = 0.0;
-            if (!bad[j]) v = (i < j) ? a[base + j] : (i == j ? rdiag[i] : 0.0);
-            tm[(int64_t)i * w + j] = v * dsc[i];
-        }
-    }
-    if (t == 0) {
-        int nbad = 0;
-        for (int i = 0; i < w; ++i) nbad += bad[i];
-        if (pass == 1) {
-            L.status[0] = nbad;
-            L.status[1] = (min_piv < kSecondPassPivot) ? 1 : 0;
-        } else {
-            L.status[0] = max(L.status[0], nbad);
-        }
-    }
+    chol_body(L, role, tol2, pass, slot_rows, allow2_of(L, a2gate), smem, L.tmat);
 }
 
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, hipStream_t st) {
+                       int slot_rows, int gate, int a2gate, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
-    const size_t lds = (size_t)((w * (w + 1)) / 2 + 3 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
+    const size_t lds = chol_lds_bytes_upto(w);
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chol_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate, a2gate);
     return hipGetLastError();
 }
 
@@ -202,29 +82,67 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
 // w_in and w_out are the widths of the two thin matrices, tmat is w_in x w_in row-major.
 // In place (dst == src) is allowed: a workgroup reads its 64 rows completely before writing them.
 // Fused follow-ups, chosen by `mode` and the layer's second-pass flag:
-//   APPLY_PASS1  (upper-triangular tmat): flag set   -> also the partial Gram matrix of the result
+//   APPLY_PASS1  (upper-triangular tmat): flag set   -> also the partial Gram matrix of the result, and the
+//                                                       last workgroup to finish factorises their sum
 //                                         flag clear -> result is final: operand copies if cp > 0
 //   APPLY_PASS2  (upper-triangular tmat): flag clear -> nothing to do; else final + operand copies
 //   APPLY_RITZ   (full tmat)            : final + operand copies if cp > 0
 // --------------------------------------------------------------------------------------------
 enum ApplyMode { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
 
+// LDS bytes of the tmat block, the x tile and the result tile (what every mode needs), 16-byte rounded
+__host__ __device__ inline size_t apply_main_lds(int w_in, int w_out, int cp) {
+    const int ow = (cp > w_out ? cp : w_out) + 1;
+    const int kpad = (w_in + 3) & ~3;
+    const size_t b = (size_t)kGramRows2 * (ow + w_in + 1) * sizeof(float) + (size_t)kpad * 32 * sizeof(double);
+    return (b + 15) & ~(size_t)15;
+}
+
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
-                                                         int mode, int cp, int gate) {
+                                                         int mode, int cp, int gate, int a2gate, double tol2) {
+    __shared__ int s_last;
+    __shared__ int s_need2;
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
-    const int need2 = L.status[1];
-    if (mode == APPLY_PASS2 && !need2) return;
     const int side = side_of_role(L.transposed, src_role);
     const int len = side_len(L, side), lenP = side_lenP(L, side);
     const int i0 = blockIdx.x * kGramRows2;
-    const bool do_gram = (mode == APPLY_PASS1) && need2;
-    const bool do_pack = !do_gram && cp > 0;
-    if (i0 >= (do_pack ? lenP : len)) return;
+    if (i0 >= lenP) return;
     const ThinRef X = L.thin[src_role];
     const ThinRef Y = L.thin[dst_role];
     const int w_in = X.width, w_out = Y.width;
+    extern __shared__ __align__(16) unsigned char smem[];
+    const size_t main_lds = apply_main_lds(w_in, w_out, cp);
+    const double* __restrict__ tm = L.tmat;
+    int need2;
+    // x tile (64 x w_in): one contiguous block of the thin matrix when ld == width (always the case for the
+    // library's own buffers and for P, Q), fetched with 16-byte loads over the flat range
+    const bool flat_x = X.ld == w_in && (w_in & 3) == 0;
+    const int64_t xbase = (int64_t)i0 * X.ld;
+    const int n_valid_x = (min(len, i0 + kGramRows2) - i0) * w_in;          // elements that exist
+    float4 xpre = make_float4(0.f, 0.f, 0.f, 0.f);
+    bool have_pre = false;
+    if (mode == APPLY_PASS1 && local_chol(L, src_role)) {
+        // small factorisation repeated by every workgroup; the first one records the outcome.  The
+        // workgroup's own rows are requested first so that their latency overlaps the factorisation.
+        if (flat_x) {
+            have_pre = true;
+            if (4 * (int)threadIdx.x < n_valid_x) xpre = *reinterpret_cast<const float4*>(X.ptr + xbase + 4 * threadIdx.x);
+        }
+        double* tml = reinterpret_cast<double*>(smem + main_lds);
+        chol_body(L, src_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem + main_lds + w_in * w_in * sizeof(double),
+                  tml, blockIdx.x == 0, &s_need2);
+        __syncthreads();
+        need2 = s_need2;
+        tm = tml;
+    } else {
+        need2 = L.status[1];
+    }
+    if (mode == APPLY_PASS2 && !need2) return;
+    const bool do_gram = (mode == APPLY_PASS1) && need2;
+    const bool do_pack = !do_gram && cp > 0;
+    if (i0 >= (do_pack ? lenP : len)) return;
     const bool upper = mode != APPLY_RITZ;
     const int ow = (cp > w_out ? cp : w_out) + 1;     // stride of the output tile (zero padded to cp)
     // The product runs on the fp64 matrix cores (v_mfma_f64_16x16x4_f64): wave v owns rows 16v..16v+15
@@ -233,22 +151,18 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     const int xs = w_in + 1;                                         // row stride of the x tile
     const int kpad = (w_in + 3) & ~3;                                // reduction length padded to the MFMA k
     const int cbw = 32;                                              // output columns per pass
-    extern __shared__ __align__(16) unsigned char smem[];
     double* st = reinterpret_cast<double*>(smem);                    // [kpad][cbw] block of tmat columns
     float* sx = reinterpret_cast<float*>(st + (size_t)kpad * cbw);    // [64][xs]  x tile
     float* so = sx + (size_t)kGramRows2 * xs;                        // [64][ow]  result tile
     const int t = threadIdx.x;
     const int tx = t & 63, ty = t >> 6;
     {
-        // the 64 x w_in tile is one contiguous block of the thin matrix when ld == width (always the
-        // case for the library's own buffers and for P, Q): 16-byte loads over the flat range
-        const int64_t base = (int64_t)i0 * X.ld;
-        const int n_valid = (min(len, i0 + kGramRows2) - i0) * w_in;          // elements that exist
         const float inv_w = 1.0f / (float)w_in;
-        if (X.ld == w_in && (w_in & 3) == 0) {
+        if (flat_x) {
             for (int f = 4 * t; f < kGramRows2 * w_in; f += 4 * kThreads) {
                 float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (f < n_valid) x = *reinterpret_cast<const float4*>(X.ptr + base + f);
+                if (have_pre && f == 4 * t) x = xpre;
+                else if (f < n_valid_x) x = *reinterpret_cast<const float4*>(X.ptr + xbase + f);
                 int row = (int)(((float)f + 0.5f) * inv_w);
                 int c = f - row * w_in;
                 if (c < 0) { --row; c += w_in; } else if (c >= w_in) { ++row; c -= w_in; }
@@ -264,7 +178,6 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
         }
         for (int e = t; e < kGramRows2 * ow; e += kThreads) so[e] = 0.f;
     }
-    const double* __restrict__ tm = L.tmat;
     const int li = tx & 15, lk = tx >> 4;                             // MFMA lane: row/column index, k index
     for (int cb = 0; cb < w_out; cb += cbw) {
         __syncthreads();
@@ -310,7 +223,9 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
         }
     }
     if (do_gram) {
-        gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)blockIdx.x * w_out * w_out);
+        gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)blockIdx.x * ((w_out * (w_out + 1)) / 2));
+        const int n_wg = (len + kGramRows2 - 1) / kGramRows2;
+        if (last_to_arrive(&L.status[7], n_wg, &s_last)) chol_body(L, dst_role, tol2, 2, kGramRows2, false, smem, L.tmat);
     } else if (do_pack) {
         write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP);
     }
@@ -318,19 +233,24 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
-                        int src_role, int dst_role, int mode, int cp, int gate, hipStream_t st) {
+                        int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
+                        hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
-    const int ow = (cp > w_out ? cp : w_out) + 1;
-    const int kpad = (w_in + 3) & ~3;
-    const int st_elems = kpad * 32;                      // tmat block [kpad][32]
-    const size_t lds = (size_t)kGramRows2 * (ow + w_in + 1) * sizeof(float) + (size_t)st_elems * sizeof(double);
+    // w_in / w_out are upper bounds over the layers: sizes that grow with them cover every layer
+    size_t lds = apply_main_lds(w_in, w_out, cp);
+    if (mode == APPLY_PASS1) {
+        if (chol_lds_bytes_upto(w_out) > lds) lds = chol_lds_bytes_upto(w_out);          // second-pass factorisation
+        const int wl = w_in < kCholRegWidth ? w_in : kCholRegWidth;             // per-workgroup factorisation
+        lds += (size_t)wl * wl * sizeof(double) + chol_lds_bytes_upto(wl);
+    }
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(apply_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate);
+    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate, a2gate,
+                       tol2);
     return hipGetLastError();
 }
 
@@ -445,7 +365,7 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         for (int j = i + tx; j < n; j += tw) {
             double s = 0.0;
             if (j < w)
-                for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * w * w + (int64_t)i * w + j];
+                for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * ((w * (w + 1)) / 2) + tri_idx(i, j, w)];
             a[sym_idx(i, j, n)] = s;
         }
     for (int i = ty; i < nv; i += tw)

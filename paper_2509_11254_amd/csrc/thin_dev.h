@@ -1,0 +1,317 @@
+// Device code of the small (w x w) factorisation behind the orthonormaliser, shared by the kernels
+// that can run it: the stand-alone chol kernel and, as the last workgroup to arrive, the kernel that
+// wrote the partial Gram matrices.
+//
+// Orthonormalisation (Section 2, "QR decomposition": Q-factor of the economic QR) is CholeskyQR2:
+//   G = X^T X (fp64, exact products of the fp32 entries);  G_s = D G D with D = diag(G)^{-1/2};
+//   G_s = R_s^T R_s (Cholesky, fp64);  X <- X (D R_s^{-1});  then the same once more on the result.
+// The Q-factor it converges to is the one with a positive diagonal of R.  A pivot of the scaled
+// Cholesky at step k equals (norm of column k's part orthogonal to the earlier columns / norm of
+// column k)^2; if it is <= rank_tol^2 the column is declared dependent and its P~ column is zero.
+#pragma once
+#include "psgd_dev.h"
+
+namespace psgd {
+
+// The first pass leaves an orthogonality error of about 1e-16/pivot (the smallest pivot of the scaled
+// factorisation is about 1/cond^2 of the column-scaled matrix); below kSecondPassPivot the flag
+// status[1] is set and the pass-2 code (which exits at once otherwise) does its work.
+constexpr double kSecondPassPivot = 1e-6;
+constexpr int kCholMaxGroups = 8;
+
+// slot groups that sum the partial Gram matrices side by side (all kThreads threads busy for small w)
+__host__ __device__ inline int chol_groups(int w) {
+    const int ntri = (w * (w + 1)) / 2;
+    int g = kThreads / ntri;
+    return g < 1 ? 1 : (g > kCholMaxGroups ? kCholMaxGroups : g);
+}
+// LDS bytes chol_body needs
+__host__ __device__ inline size_t chol_lds_bytes(int w) {
+    const int ntri = (w * (w + 1)) / 2;
+    const int g = chol_groups(w);
+    return (size_t)((g > 1 ? g + 1 : 1) * ntri + 3 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
+}
+
+// the same for a launch that serves layers of any width up to w (the need is not monotone in w)
+inline size_t chol_lds_bytes_upto(int w) {
+    size_t b = 0;
+    for (int v = 1; v <= w; ++v) b = chol_lds_bytes(v) > b ? chol_lds_bytes(v) : b;
+    return b;
+}
+
+// squared column norms at or below this count as zero (far below anything fp32 data can produce, and
+// keeps the reciprocal square root away from subnormal arguments)
+constexpr double kTinyNorm2 = 1e-280;
+
+// 1 / sqrt(x) for finite normal x > 0: hardware estimate refined by two Newton steps (full fp64 accuracy)
+__device__ inline double rsqrt_nr(double x) {
+    double y = __builtin_amdgcn_rsq(x);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) {
+        const double e = __builtin_fma(-(x * y), y, 1.0);
+        y = __builtin_fma(0.5 * y, e, y);
+    }
+    return y;
+}
+
+// Second-pass permission carried by a launch: -1 always, -2 never, else an iteration gate (kind 2).
+__device__ inline bool allow2_of(const LayerDev& L, int a2gate) {
+    if (a2gate == -1) return true;
+    if (a2gate == -2) return false;
+    return gate_open(L, a2gate);
+}
+
+// The factorisation for w <= 16 by one wavefront without LDS traffic or barriers: lane j < 16 holds column j
+// of the scaled matrix in registers, lane 16 + c holds column c of an identity matrix, and the steps
+// exchange values with cross-lane reads.  The row operations of the right-looking Cholesky A = R^T R turn
+// the identity columns into R^{-T}, so lane 16 + c ends up with row c of T = R^{-1} and no separate
+// inversion is needed.  g: the summed Gram matrix (packed upper triangle, LDS).  Same arithmetic and
+// outputs as the general path of chol_body.  W: compiled width (w <= W); rows and columns w .. W-1 are
+// those of an identity matrix.
+constexpr int kCholRegWidth = 16;
+template <int W>
+__device__ inline void chol_in_registers_w(const LayerDev& L, const double* g, int w, double tol2, int pass,
+                                           bool allow2, double* tm, bool write_status, int* need2_out) {
+    const int j = threadIdx.x & 63;
+    const bool aug = j >= 16;                          // identity column c = j - 16
+    const int c = (j - 16) & 15;
+    const int jc = j < w ? j : 0;                      // matrix lanes >= w hold identity columns
+    const double djj = g[tri_idx(jc, jc, w)];
+    const double dsc_own = djj > kTinyNorm2 ? rsqrt_nr(djj) : 0.0;
+    const double dsc_row = __shfl(dsc_own, c < w ? c : 0);    // scaling of row c (used by lane 16 + c)
+    // a[i]: entry (i, j) of the scaled matrix, later of R; on lane 16 + c entry (i, c) of R^{-T}
+    double a[W];
+    int badmask = 0;
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        const double dsi = __shfl(dsc_own, i < w ? i : 0);
+        if (i < w && !(dsi > 0.0)) badmask |= 1 << i;
+        double x = (i == (aug ? c : j)) ? 1.0 : 0.0;
+        if (!aug && i < w && j < w && i <= j) x = g[tri_idx(i, jc, w)] * dsi * dsc_own;
+        a[i] = x;
+    }
+    double min_piv = 1.0;
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        const double piv = __shfl(a[k], k);
+        const bool dep = ((badmask >> k) & 1) || !(piv > tol2);
+        if (k < w) {
+            if (dep) {
+                badmask |= 1 << k;                            // row k of R := row k of the identity
+                if (!aug) a[k] = (j == k) ? 1.0 : 0.0;
+            } else {
+                if (piv < min_piv) min_piv = piv;
+                const double rinv = rsqrt_nr(piv);
+                a[k] *= rinv;                                 // row k <- row k / R_kk
+#pragma unroll
+                for (int i = k + 1; i < W; ++i) {
+                    const double rki = __shfl(a[k], i);      // R[k][i]
+                    if (aug || j >= i) a[i] -= rki * a[k];    // row i <- row i - R[k][i] row k
+                }
+            }
+        }
+    }
+    // lane 16 + c: row c of tmat = D T with the dependent columns zeroed
+    if (aug && j < 16 + w) {
+#pragma unroll
+        for (int i = 0; i < W; ++i)
+            if (i < w) tm[(int64_t)c * w + i] = ((badmask >> i) & 1) ? 0.0 : a[i] * dsc_row;
+    }
+    if (j == 0) {
+        const int nbad = __popc(badmask & ((1 << w) - 1));
+        const int need2 = (allow2 && min_piv < kSecondPassPivot) ? 1 : 0;
+        if (need2_out) *need2_out = need2;
+        if (write_status) {
+            if (pass == 1) {
+                L.status[0] = nbad;
+                L.status[1] = need2;
+            } else {
+                L.status[0] = max(L.status[0], nbad);
+            }
+        }
+    }
+}
+
+__device__ inline void chol_in_registers(const LayerDev& L, const double* g, int w, double tol2, int pass,
+                                         bool allow2, double* tm, bool write_status, int* need2_out) {
+    if (w <= 4) chol_in_registers_w<4>(L, g, w, tol2, pass, allow2, tm, write_status, need2_out);
+    else if (w <= 8) chol_in_registers_w<8>(L, g, w, tol2, pass, allow2, tm, write_status, need2_out);
+    else if (w <= 12) chol_in_registers_w<12>(L, g, w, tol2, pass, allow2, tm, write_status, need2_out);
+    else chol_in_registers_w<16>(L, g, w, tol2, pass, allow2, tm, write_status, need2_out);
+}
+
+// Layers whose factorisation is cheap enough for every workgroup of the apply kernel to repeat it for
+// itself (one kernel boundary less): register path, and few partial Gram matrices to add up.
+constexpr int kLocalCholMaxSlots = 64;
+__device__ inline bool local_chol(const LayerDev& L, int role) {
+    const int len = side_len(L, side_of_role(L.transposed, role));
+    return L.thin[role].width <= kCholRegWidth && (len + kGramRows1 - 1) / kGramRows1 <= kLocalCholMaxSlots;
+}
+
+// Sums the partial Gram matrices of thin[role] (packed upper triangles, slots of `slot_rows` rows, fixed
+// order), scales to unit diagonal, Cholesky-factorises (upper, packed in LDS), inverts the factor in
+// place and writes tmat = D R_s^{-1}.  pass 1 also decides whether the second CholeskyQR pass runs.
+// Called by all kThreads threads of one workgroup per layer; smem: chol_lds_bytes(w), 8-byte aligned.
+// tm: where the w x w factor goes (the layer's tmat, or LDS of the caller); need2_out: optional LDS word
+// that receives the second-pass decision; write_status: whether this caller owns the layer's status words.
+__device__ inline void chol_body(const LayerDev& L, int role, double tol2, int pass, int slot_rows, bool allow2,
+                                 unsigned char* smem, double* tm, bool write_status = true,
+                                 int* need2_out = nullptr) {
+    const int side = side_of_role(L.transposed, role);
+    const int n_slots = (side_len(L, side) + slot_rows - 1) / slot_rows;
+    const int w = L.thin[role].width;
+    const int ntri = (w * (w + 1)) / 2;
+    const int G = chol_groups(w);
+    double* a = reinterpret_cast<double*>(smem);          // packed upper triangle
+    double* ps = a + ntri;                                // [G][ntri] partial slot sums (G > 1)
+    double* dsc = ps + (G > 1 ? G * ntri : 0);            // [w] scaling
+    double* rdiag = dsc + w;                              // [w] diagonal of the inverse factor
+    double* tcol = rdiag + w;                             // [w] copy of the column of R that is being replaced
+    int* bad = reinterpret_cast<int*>(tcol + w);          // [w] dependent-column flags
+    const int t = threadIdx.x;
+    const double* __restrict__ gram = L.gram;
+    if (G > 1) {
+        // thread (e, g): entries e of slots g, g + G, ...; eight loads in flight, those past the end
+        // re-read slot g and do not count
+        const int g = t / ntri, e = t - g * ntri;
+        if (g < G) {
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+            for (int sl = g; sl < n_slots; sl += 8 * G) {
+                double x[8];
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    const int sd = sl + d * G;
+                    x[d] = gram[(int64_t)(sd < n_slots ? sd : g) * ntri + e];
+                }
+#pragma unroll
+                for (int d = 0; d < 8; ++d)
+                    if (sl + d * G >= n_slots) x[d] = 0.0;
+                s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
+            }
+            ps[g * ntri + e] = (s0 + s1) + (s2 + s3);
+        }
+        __syncthreads();
+        if (t < ntri) {
+            double s = 0.0;
+            for (int g2 = 0; g2 < G; ++g2) s += ps[g2 * ntri + t];
+            a[t] = s;
+        }
+    } else {
+        for (int e = t; e < ntri; e += kThreads) {
+            const double* __restrict__ g = gram + e;
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+            int sl = 0;
+            for (; sl + 8 <= n_slots; sl += 8) {      // independent loads in flight; order of the sum is fixed
+                double x[8];
+#pragma unroll
+                for (int d = 0; d < 8; ++d) x[d] = g[(int64_t)(sl + d) * ntri];
+                s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
+            }
+            for (; sl < n_slots; ++sl) s0 += g[(int64_t)sl * ntri];
+            a[e] = (s0 + s1) + (s2 + s3);
+        }
+    }
+    __syncthreads();
+    if (w <= kCholRegWidth) {
+        if (t < 64) chol_in_registers(L, a, w, tol2, pass, allow2, tm, write_status, need2_out);
+        return;
+    }
+    for (int i = t; i < w; i += kThreads) {
+        const double d = a[tri_idx(i, i, w)];
+        dsc[i] = d > kTinyNorm2 ? rsqrt_nr(d) : 0.0;
+        bad[i] = d > kTinyNorm2 ? 0 : 1;
+    }
+    __syncthreads();
+    // threads as a 16 x 16 grid over (row, column): no integer division in the loops over the triangle
+    const int tx = t & 15, ty = t >> 4;
+    for (int i = ty; i < w; i += 16) {
+        const int base = tri_idx(i, i, w) - i;
+        for (int j = i + tx; j < w; j += 16) a[base + j] *= dsc[i] * dsc[j];
+    }
+    __syncthreads();
+    // right-looking Cholesky, A = R^T R, R overwrites the strict upper triangle
+    double min_piv = 1.0;
+    for (int k = 0; k < w; ++k) {
+        // every thread reads the pivot itself; 1 / R_kk goes to rdiag, so the pivot entry is never
+        // overwritten and two barriers per step are enough
+        const double piv = a[tri_idx(k, k, w)];
+        const bool dep = bad[k] || !(piv > tol2);
+        if (!dep && piv < min_piv) min_piv = piv;
+        const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
+        if (dep) {
+            if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
+            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
+        } else {
+            const double rinv = rsqrt_nr(piv);
+            if (t == 0) rdiag[k] = rinv;
+            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
+        }
+        __syncthreads();
+        if (!dep) {
+            for (int i = k + 1 + ty; i < w; i += 16) {
+                const double rki = a[kbase + i];
+                const int base = tri_idx(i, i, w) - i;
+                for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
+            }
+        }
+        __syncthreads();
+    }
+    // inverse of the upper-triangular factor, in place in the packed triangle, column by column:
+    //   T_jj = 1 / R_jj,   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
+    // one thread per row i of the new column; then tmat = D T with the dependent columns zeroed
+    for (int j = 1; j < w; ++j) {
+        for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
+        __syncthreads();
+        const double tjj = rdiag[j];
+        for (int i = t; i < j; i += kThreads) {
+            const int base = tri_idx(i, i, w) - i;
+            double sacc = rdiag[i] * tcol[i];
+            for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
+            a[base + j] = -tjj * sacc;
+        }
+        __syncthreads();
+    }
+    for (int i = ty; i < w; i += 16) {
+        const int base = tri_idx(i, i, w) - i;
+        for (int j = tx; j < w; j += 16) {
+            double v = 0.0;
+            if (!bad[j]) v = (i < j) ? a[base + j] : (i == j ? rdiag[i] : 0.0);
+            tm[(int64_t)i * w + j] = v * dsc[i];
+        }
+    }
+    if (t == 0) {
+        int nbad = 0;
+        for (int i = 0; i < w; ++i) nbad += bad[i];
+        const int need2 = (allow2 && min_piv < kSecondPassPivot) ? 1 : 0;
+        if (need2_out) *need2_out = need2;
+        if (write_status) {
+            if (pass == 1) {
+                L.status[0] = nbad;
+                L.status[1] = need2;
+            } else {
+                L.status[0] = max(L.status[0], nbad);
+            }
+        }
+    }
+}
+
+// True in exactly one workgroup of the `n_wg` that call it for a layer: the one that arrives last, after
+// which everything the others wrote before their call is visible to it.  `counter` starts at zero and is
+// zero again afterwards.  All threads of the workgroup must call it; flag points to an int in LDS.
+__device__ inline bool last_to_arrive(int* counter, int n_wg, int* flag) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int old = atomicAdd(counter, 1);
+        *flag = (old == n_wg - 1) ? 1 : 0;
+    }
+    __syncthreads();
+    const bool last = *flag != 0;
+    if (last) {
+        __threadfence();
+        if (threadIdx.x == 0) *counter = 0;
+    }
+    return last;
+}
+
+}  // namespace psgd
