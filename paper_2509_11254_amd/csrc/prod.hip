@@ -19,10 +19,13 @@ constexpr int BK = 64;          // reduction chunk
 constexpr int BT = 128;         // output rows per workgroup (4 waves x 32)
 constexpr int LDSW = BK + 8;    // LDS row stride in bf16 elements (144 bytes)
 
-__device__ inline float4 ld_f32x4(const float* p) { return *reinterpret_cast<const float4*>(p); }
+__device__ inline float4 ld_f32x4(const PSGD_GLOBAL float* p) {
+    const floatx4 v = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(p);
+    return make_float4(v.x, v.y, v.z, v.w);
+}
 
-__device__ inline float4 ld_bf16x4(const bf16_t* p) {
-    uint2 v = *reinterpret_cast<const uint2*>(p);
+__device__ inline float4 ld_bf16x4(const PSGD_GLOBAL bf16_t* p) {
+    const uintx2 v = *reinterpret_cast<const PSGD_GLOBAL uintx2*>(p);
     float4 o;
     o.x = __uint_as_float(v.x << 16);
     o.y = __uint_as_float(v.x & 0xffff0000u);
@@ -55,12 +58,13 @@ __device__ inline TileAddr tile_addr(const LayerDev& L, int row0, int row_step, 
 }
 
 __device__ inline void load_g8(const LayerDev& L, int w, const TileAddr& a, float4 (&x)[8]) {
+    const PSGD_GLOBAL void* gw = as_global(as_global(L.G)[w]);
     if (L.gdt == 0) {
-        const float* __restrict__ g = reinterpret_cast<const float*>(L.G[w]);
+        const PSGD_GLOBAL float* __restrict__ g = reinterpret_cast<const PSGD_GLOBAL float*>(gw);
 #pragma unroll
         for (int u = 0; u < 8; ++u) x[u] = ld_f32x4(g + a.off[u]);
     } else {
-        const bf16_t* __restrict__ g = reinterpret_cast<const bf16_t*>(L.G[w]);
+        const PSGD_GLOBAL bf16_t* __restrict__ g = reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw);
 #pragma unroll
         for (int u = 0; u < 8; ++u) x[u] = ld_bf16x4(g + a.off[u]);
     }
@@ -78,10 +82,10 @@ __device__ inline void tile_prefetch(const LayerDev& L, const TileAddr& a, float
     if (FORM) {
         load_g8(L, 0, a, p0);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) p1[u] = ld_f32x4(L.S + a.off[u]);
+        for (int u = 0; u < 8; ++u) p1[u] = ld_f32x4(as_global(L.S) + a.off[u]);
     } else {
 #pragma unroll
-        for (int u = 0; u < 8; ++u) p0[u] = ld_f32x4(L.S + a.off[u]);
+        for (int u = 0; u < 8; ++u) p0[u] = ld_f32x4(as_global(L.S) + a.off[u]);
     }
 }
 
@@ -115,9 +119,9 @@ __device__ inline void tile_finish(const LayerDev& L, const TileAddr& a, float i
 
 __device__ inline void store_m4(const LayerDev& L, int row, int col, float4 m) {
     if (row >= L.rows || col >= L.cols) return;
-    float* p = L.S + (int64_t)row * L.ld + col;
+    PSGD_GLOBAL float* p = as_global(L.S) + (int64_t)row * L.ld + col;
     if (col + 3 < L.cols) {
-        *reinterpret_cast<float4*>(p) = m;
+        *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = floatx4{m.x, m.y, m.z, m.w};
     } else {
         p[0] = m.x;
         if (col + 1 < L.cols) p[1] = m.y;
@@ -134,7 +138,7 @@ __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int ou
     const int w = T.width;
     for (int e = t; e < BT * w; e += kThreads) {
         const int row = e / w, col = e % w;
-        if (ob * BT + row < out_len) T.ptr[(int64_t)(ob * BT + row) * T.ld + col] = otile[row * tw + col];
+        if (ob * BT + row < out_len) as_global(T.ptr)[(int64_t)(ob * BT + row) * T.ld + col] = otile[row * tw + col];
     }
     if (epi == EPI_GRAM) {
         gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * ((w * (w + 1)) / 2));
@@ -152,8 +156,12 @@ template <bool COLMODE> __device__ inline int a_chunk(int row, int chunk) { retu
 
 template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL == 2 ? (ka + kb <= 1) : (ka + kb <= 2); }
 
+// Two workgroups share a compute unit when their operand buffers fit its 160 KB of LDS twice; the wide
+// variants run alone and may use the whole register file.
+constexpr int prod_min_blocks(int nb, int pl) { return 2 * pl * (BT + 32 * nb) * LDSW * 2 <= 160 * 1024 ? 2 : 1; }
+
 template <int NB, int PL, bool COLMODE, bool FORM>
-__global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
                                                         int epi, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
@@ -271,8 +279,8 @@ __global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __res
             const int64_t goff = (int64_t)c * src_lenP + k0 + 8 * part;
 #pragma unroll
             for (int k = 0; k < PL; ++k)
-                *reinterpret_cast<uint4*>(b_pl + k * BPL + c * LDSW + 8 * part) =
-                    *reinterpret_cast<const uint4*>(XK.t[k] + goff);
+                *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) =
+                    *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
         }
         __syncthreads();
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
@@ -310,15 +318,15 @@ __global__ __launch_bounds__(kThreads, 2) void prod_kernel(const LayerDev* __res
         // them up in split order.  Layout [split][column][row]: only the T.width real columns are
         // stored, and a lane's four consecutive accumulator rows go out as one 16-byte store.
         const int64_t plane = (int64_t)out_lenP * T.width;
-        float* __restrict__ dst = L.part[out_side] + sp * plane + (int64_t)ob * BT + 32 * wv + 4 * lg;
+        PSGD_GLOBAL float* __restrict__ dst = as_global(L.part[out_side]) + sp * plane + (int64_t)ob * BT + 32 * wv + 4 * lg;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int col = 32 * nb + li;
             if (col < T.width) {
 #pragma unroll
                 for (int vq = 0; vq < 4; ++vq)
-                    *reinterpret_cast<float4*>(dst + (int64_t)col * out_lenP + 8 * vq) =
-                        make_float4(acc[nb][4 * vq], acc[nb][4 * vq + 1], acc[nb][4 * vq + 2], acc[nb][4 * vq + 3]);
+                    *reinterpret_cast<PSGD_GLOBAL floatx4*>(dst + (int64_t)col * out_lenP + 8 * vq) =
+                        floatx4{acc[nb][4 * vq], acc[nb][4 * vq + 1], acc[nb][4 * vq + 2], acc[nb][4 * vq + 3]};
             }
         }
         return;
@@ -364,21 +372,21 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     for (int e = t; e < BT * cp; e += kThreads) otile[(e / cp) * tw + e % cp] = 0.f;
     __syncthreads();
     const int64_t plane = (int64_t)out_lenP * T.width;
-    const float* __restrict__ src = L.part[out_side] + (int64_t)ob * BT;
+    const PSGD_GLOBAL float* __restrict__ src = as_global(L.part[out_side]) + (int64_t)ob * BT;
     for (int item = t; item < T.width * (BT / 4); item += kThreads) {
         const int col = item / (BT / 4), r4 = 4 * (item % (BT / 4));
-        const float* __restrict__ sc = src + (int64_t)col * out_lenP + r4;
+        const PSGD_GLOBAL float* __restrict__ sc = src + (int64_t)col * out_lenP + r4;
         float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
         int s2 = 0;
         for (; s2 + 8 <= n_split; s2 += 8) {          // 8 independent 16-byte loads in flight
             float4 x[8];
 #pragma unroll
-            for (int d = 0; d < 8; ++d) x[d] = *reinterpret_cast<const float4*>(sc + (s2 + d) * plane);
+            for (int d = 0; d < 8; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
 #pragma unroll
             for (int d = 0; d < 8; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
         }
         for (; s2 < n_split; ++s2) {
-            const float4 x = *reinterpret_cast<const float4*>(sc + s2 * plane);
+            const float4 x = ld_f32x4(sc + s2 * plane);
             sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
         }
         otile[(r4 + 0) * tw + col] = sum.x;

@@ -16,6 +16,14 @@ typedef __bf16 bf16_t;
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16;
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx4 __attribute__((ext_vector_type(4)));
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+
+// Pointers read from a layer descriptor are generic to the compiler, which then emits flat memory
+// instructions (tied to the LDS counter as well); the kernels cast them to the global address space.
+#define PSGD_GLOBAL __attribute__((address_space(1)))
+template <class T> __device__ inline PSGD_GLOBAL T* as_global(T* p) { return (PSGD_GLOBAL T*)p; }
 
 constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kLenPad = 128;       // packed operand rows are padded (with zeros) to this multiple
@@ -125,7 +133,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         const int64_t off = (int64_t)(row0 + row) * cp + c0;
 #pragma unroll
         for (int k = 0; k < kMaxPlanes; ++k)
-            if (k < planes) *reinterpret_cast<bf16x8*>(K.n[k] + off) = o[k];
+            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.n[k]) + off) = o[k];
     }
     for (int v = t; v < cp * (nrows / 8); v += kThreads) {
         int c, g8;
@@ -142,7 +150,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         const int64_t off = (int64_t)c * lenP + row0 + ib;
 #pragma unroll
         for (int k = 0; k < kMaxPlanes; ++k)
-            if (k < planes) *reinterpret_cast<bf16x8*>(K.t[k] + off) = o[k];
+            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.t[k]) + off) = o[k];
     }
 }
 
@@ -170,7 +178,8 @@ __host__ __device__ inline int tri_idx(int i, int j, int w) { return i * w - (i 
 // tile is fp32 in LDS, [nrows][tw], nrows a multiple of 4, columns up to the next multiple of 16 of w
 // readable (zero padded).  The 16 x 16 blocks (bi <= bj) are dealt to the four waves of the workgroup;
 // v_mfma_f64_16x16x4_f64 takes A = tile^T (lane: column, k: row) and B = tile.
-__device__ inline void gram_tile_f64(const float* tile, int tw, int nrows, int w, double* __restrict__ g) {
+__device__ inline void gram_tile_f64(const float* tile, int tw, int nrows, int w, double* __restrict__ g_generic) {
+    PSGD_GLOBAL double* __restrict__ g = as_global(g_generic);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int li = lane & 15, lk = lane >> 4;
     const int nt = (w + 15) / 16;

@@ -25,8 +25,10 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
     const int li = lane & 31, lg = lane >> 5;
-    const PackRef WK = L.pack[SIDE_W];
-    const PackRef LK = L.pack[SIDE_L];
+    const PSGD_GLOBAL bf16_t* wk[PL];
+    const PSGD_GLOBAL bf16_t* lk[PL];
+#pragma unroll
+    for (int k = 0; k < PL; ++k) { wk[k] = as_global(L.pack[SIDE_W].n[k]); lk[k] = as_global(L.pack[SIDE_L].n[k]); }
     // stage the W-side tile: matrix column j = cb*128 + jj goes to LDS row (jj & 3) * 32 + (jj >> 2)
     for (int v = t; v < RT * NB * 4; v += kThreads) {
         const int jj = v / (NB * 4), part = v % (NB * 4);
@@ -34,8 +36,8 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
         const int64_t goff = (int64_t)(cb * RT + jj) * cp + 8 * part;
 #pragma unroll
         for (int k = 0; k < PL; ++k)
-            *reinterpret_cast<uint4*>(b_pl + k * BPL + lrow * CPW + 8 * part) =
-                *reinterpret_cast<const uint4*>(WK.n[k] + goff);
+            *reinterpret_cast<uintx4*>(b_pl + k * BPL + lrow * CPW + 8 * part) =
+                *reinterpret_cast<const PSGD_GLOBAL uintx4*>(wk[k] + goff);
     }
     __syncthreads();
     const int64_t aoff = (int64_t)(rb * RT + 32 * wv + li) * cp + 8 * lg;
@@ -47,7 +49,7 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     for (int ks = 0; ks < 2 * NB; ++ks) {
         bf16x8 av[PL];
 #pragma unroll
-        for (int k = 0; k < PL; ++k) av[k] = *reinterpret_cast<const bf16x8*>(LK.n[k] + aoff + 16 * ks);
+        for (int k = 0; k < PL; ++k) av[k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(lk[k] + aoff + 16 * ks);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int boff = (32 * q + li) * CPW + 16 * ks + 8 * lg;
@@ -67,7 +69,7 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
 }
 
 template <int NB, int PL>
-__global__ __launch_bounds__(kThreads) void residual_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, 3) void residual_kernel(const LayerDev* __restrict__ layers,
                                                             const int* __restrict__ ids, int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -80,15 +82,20 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(const LayerDev* __re
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const int col = cb * RT + 4 * li;
-    const int row_base = rb * RT + 32 * wv + 4 * lg;
     const bool col_ok = col < L.cols;
     // issue the 16 loads of M first; the operand staging and the MFMAs hide their latency
-    float4 m[16];
+    // addresses = uniform base of tile row 8*(v>>2) + (v&3) (scalar registers) + one per-lane offset
+    PSGD_GLOBAL float* tile0 = as_global(L.S) + (int64_t)(rb * RT) * L.ld + cb * RT;
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    const int row_lane = rb * RT + 32 * wv + 4 * lg;
+    floatx4 m[16];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const int row = row_base + 8 * (v >> 2) + (v & 3);
-        const int64_t off = (int64_t)min(row, L.rows - 1) * L.ld + (col_ok ? col : 0);
-        m[v] = *reinterpret_cast<const float4*>(L.S + off);
+        const int k = 8 * (v >> 2) + (v & 3);
+        m[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (col_ok && row_lane + k < L.rows)
+            m[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(
+                reinterpret_cast<const PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
     }
     floatx16 acc[4];
     outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
@@ -96,13 +103,14 @@ __global__ __launch_bounds__(kThreads) void residual_kernel(const LayerDev* __re
     const bool full = col + 3 < L.cols;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
-        const int row = row_base + 8 * (v >> 2) + (v & 3);
-        if (row >= L.rows) continue;
-        float4 e;
+        const int k = 8 * (v >> 2) + (v & 3);
+        if (row_lane + k >= L.rows) continue;
+        floatx4 e;
         e.x = m[v].x - acc[0][v]; e.y = m[v].y - acc[1][v]; e.z = m[v].z - acc[2][v]; e.w = m[v].w - acc[3][v];
-        float* p = L.S + (int64_t)row * L.ld + col;
+        PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(
+            reinterpret_cast<PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
         if (full) {
-            *reinterpret_cast<float4*>(p) = e;
+            *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = e;
         } else {
             p[0] = e.x;
             if (col + 1 < L.cols) p[1] = e.y;
@@ -138,18 +146,19 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
         const float d[4] = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
         const int64_t off = (int64_t)row * L.ld + col;
         if (out_bf16) {
-            bf16_t* p = reinterpret_cast<bf16_t*>(outs[lid]) + off;
+            PSGD_GLOBAL bf16_t* p = as_global(reinterpret_cast<bf16_t*>(outs[lid])) + off;
             if (full) {
                 bf16x4 o;
                 o[0] = (bf16_t)d[0]; o[1] = (bf16_t)d[1]; o[2] = (bf16_t)d[2]; o[3] = (bf16_t)d[3];
-                *reinterpret_cast<bf16x4*>(p) = o;
+                *reinterpret_cast<PSGD_GLOBAL bf16x4*>(p) = o;
             } else {
                 for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = (bf16_t)d[q];
             }
         } else {
-            float* p = reinterpret_cast<float*>(outs[lid]) + off;
+            PSGD_GLOBAL float* p = as_global(reinterpret_cast<float*>(outs[lid])) + off;
             if (full) {
-                *reinterpret_cast<float4*>(p) = make_float4(d[0], d[1], d[2], d[3]);
+                floatx4 o = {d[0], d[1], d[2], d[3]};
+                *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = o;
             } else {
                 for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = d[q];
             }
