@@ -25,13 +25,23 @@ __host__ __device__ inline int chol_groups(int w) {
     int g = kThreads / ntri;
     return g < 1 ? 1 : (g > kCholMaxGroups ? kCholMaxGroups : g);
 }
-// LDS bytes chol_body needs
-__host__ __device__ inline size_t chol_lds_bytes(int w) {
+// LDS doubles of chol_body besides the blocked inverse's panel, and whether the panel fits as well
+__host__ __device__ inline size_t chol_lds_doubles(int w) {
     const int ntri = (w * (w + 1)) / 2;
     const int g = chol_groups(w);
-    return (size_t)((g > 1 ? g + 1 : 1) * ntri + 3 * w) * sizeof(double) + (size_t)(w + 2) * sizeof(int);
+    const int wp = (w + 15) & ~15;
+    return (size_t)(g > 1 ? g + 1 : 1) * ntri + 2 * w + wp;
 }
-
+__host__ __device__ inline bool chol_blocked_inverse(int w) {
+    const int wp = (w + 15) & ~15;
+    return w > 32 && (chol_lds_doubles(w) + (size_t)wp * 16) * sizeof(double) + (w + 2) * sizeof(int) <= 150 * 1024;
+}
+// LDS bytes chol_body needs
+__host__ __device__ inline size_t chol_lds_bytes(int w) {
+    const int wp = (w + 15) & ~15;
+    return (chol_lds_doubles(w) + (chol_blocked_inverse(w) ? (size_t)wp * 16 : 0)) * sizeof(double) +
+           (size_t)(w + 2) * sizeof(int);
+}
 // the same for a launch that serves layers of any width up to w (the need is not monotone in w)
 inline size_t chol_lds_bytes_upto(int w) {
     size_t b = 0;
@@ -166,8 +176,11 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     double* ps = a + ntri;                                // [G][ntri] partial slot sums (G > 1)
     double* dsc = ps + (G > 1 ? G * ntri : 0);            // [w] scaling
     double* rdiag = dsc + w;                              // [w] diagonal of the inverse factor
-    double* tcol = rdiag + w;                             // [w] copy of the column of R that is being replaced
-    int* bad = reinterpret_cast<int*>(tcol + w);          // [w] dependent-column flags
+    double* tcol = rdiag + w;                             // [w up to 16] copy of the column of R being replaced
+    const int wp = (w + 15) & ~15;
+    const bool blocked = chol_blocked_inverse(w);
+    double* panel = tcol + wp;                            // [wp][16] original block column (blocked inverse)
+    int* bad = reinterpret_cast<int*>(panel + (blocked ? wp * 16 : 0));    // [w] dependent-column flags
     const int t = threadIdx.x;
     const double* __restrict__ gram = L.gram;
     if (G > 1) {
@@ -256,20 +269,81 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         }
         __syncthreads();
     }
-    // inverse of the upper-triangular factor, in place in the packed triangle, column by column:
-    //   T_jj = 1 / R_jj,   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
-    // one thread per row i of the new column; then tmat = D T with the dependent columns zeroed
-    for (int j = 1; j < w; ++j) {
-        for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
-        __syncthreads();
-        const double tjj = rdiag[j];
-        for (int i = t; i < j; i += kThreads) {
-            const int base = tri_idx(i, i, w) - i;
-            double sacc = rdiag[i] * tcol[i];
-            for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
-            a[base + j] = -tjj * sacc;
+    // inverse T of the upper-triangular factor, in place in the packed triangle (T_jj = 1 / R_jj is in rdiag):
+    //   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
+    if (!blocked) {
+        // column by column, one thread per row i of the new column
+        for (int j = 1; j < w; ++j) {
+            for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
+            __syncthreads();
+            const double tjj = rdiag[j];
+            for (int i = t; i < j; i += kThreads) {
+                const int base = tri_idx(i, i, w) - i;
+                double sacc = rdiag[i] * tcol[i];
+                for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
+                a[base + j] = -tjj * sacc;
+            }
+            __syncthreads();
         }
-        __syncthreads();
+    } else {
+        // 16 x 16 blocks.  First the diagonal blocks, all at once, by the column scheme above ...
+        const int nbk = wp / 16;
+        {
+            const int J = t >> 4, i = t & 15, r0 = 16 * J;
+            const int bw = J < nbk ? min(16, w - r0) : 0;
+            for (int j = 1; j < 16; ++j) {
+                const bool act = i < j && j < bw;
+                if (act) tcol[r0 + i] = a[tri_idx(r0 + i, r0 + j, w)];
+                __syncthreads();
+                if (act) {
+                    const int base = tri_idx(r0 + i, r0 + i, w) - i;          // a[base + c] = entry (r0 + i, r0 + c)
+                    double sacc = rdiag[r0 + i] * tcol[r0 + i];
+                    for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[r0 + l];
+                    a[base + j] = -rdiag[r0 + j] * sacc;
+                }
+                __syncthreads();
+            }
+        }
+        // ... then block column after block column, T_IJ = -(sum_{K=I}^{J-1} T_IK R_KJ) T_JJ on the fp64 matrix
+        // cores, the block rows I dealt to the waves.  The products are formed transposed,
+        // U^T = sum_K R_KJ^T T_IK^T and T_IJ^T = -T_JJ^T U^T, so that the accumulator of the first is the
+        // B operand of the second without a move.  R_KJ is read from a copy of the block column, T in place.
+        const int lane = t & 63, wv = t >> 6, li = lane & 15, lk = lane >> 4;
+        for (int J = 1; J < nbk; ++J) {
+            for (int e = t; e < 16 * J * 16; e += kThreads) {
+                const int row = e >> 4, col = 16 * J + (e & 15);
+                panel[e] = col < w ? a[tri_idx(row, col, w)] : 0.0;
+            }
+            __syncthreads();
+            for (int I = wv; I < J; I += kThreads / 64) {
+                doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+                const int trow = 16 * I + li;
+                const int tbase = tri_idx(trow, trow, w) - trow;               // a[tbase + c] = T[trow][c], c > trow
+                for (int K = I; K < J; ++K)
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int kk = 16 * K + 4 * c + lk;                     // < 16 J <= w
+                        const double av = panel[kk * 16 + li];                  // R[kk][16 J + li]
+                        const double bv = trow < kk ? a[tbase + kk] : (trow == kk ? rdiag[trow] : 0.0);   // T[trow][kk]
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                    }
+                doublex4 d2 = {0.0, 0.0, 0.0, 0.0};
+                const int jcol = 16 * J + li;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int jrow = 16 * J + 4 * c + lk;
+                    double av = 0.0;                                            // T_JJ[jrow][jcol]
+                    if (jcol < w) av = jrow < jcol ? a[tri_idx(jrow, jcol, w)] : (jrow == jcol ? rdiag[jrow] : 0.0);
+                    d2 = __builtin_amdgcn_mfma_f64_16x16x4f64(av, acc[c], d2, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int col = 16 * J + 4 * v + lk;
+                    if (col < w) a[tbase + col] = -d2[v];                       // T[trow][col]
+                }
+            }
+            __syncthreads();
+        }
     }
     for (int i = ty; i < w; i += 16) {
         const int base = tri_idx(i, i, w) - i;
