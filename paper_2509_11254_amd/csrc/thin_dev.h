@@ -64,6 +64,14 @@ __device__ inline double rsqrt_nr(double x) {
     return y;
 }
 
+// Ordering point for LDS traffic inside one wavefront (its LDS accesses execute in program order; this
+// keeps the compiler from moving them across).
+__device__ inline void wave_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
 // Second-pass permission carried by a launch: -1 always, -2 never, else an iteration gate (kind 2).
 __device__ inline bool allow2_of(const LayerDev& L, int a2gate) {
     if (a2gate == -1) return true;
@@ -150,6 +158,55 @@ __device__ inline void chol_in_registers(const LayerDev& L, const double* g, int
     else chol_in_registers_w<16>(L, g, w, tol2, pass, allow2, tm, write_status, need2_out);
 }
 
+// Diagonal 16 x 16 block of the blocked factorisation, by one wavefront in registers (same scheme as above):
+// factorises the block at rows/columns r0 .. r0 + bw - 1 of the packed triangle `a` (order w), leaves the
+// strict upper part of T_JJ = R_JJ^{-1} in its place, 1 / R_kk in rdiag, and updates the dependent-column
+// flags and the smallest accepted pivot.  All 64 lanes of the wave call it.
+__device__ inline void chol_block16(double* a, int w, int r0, int bw, double tol2, double* rdiag, int* bad,
+                                    double& min_piv) {
+    constexpr int W = 16;
+    const int j = threadIdx.x & 63;
+    const bool aug = j >= 16;
+    const int c = (j - 16) & 15;
+    double x[W];
+    int badmask = 0;
+#pragma unroll
+    for (int i = 0; i < W; ++i) {
+        if (i < bw && bad[r0 + i]) badmask |= 1 << i;
+        double v = (i == (aug ? c : j)) ? 1.0 : 0.0;
+        if (!aug && i <= j && j < bw) v = a[tri_idx(r0 + i, r0 + j, w)];
+        x[i] = v;
+    }
+#pragma unroll
+    for (int k = 0; k < W; ++k) {
+        const double piv = __shfl(x[k], k);
+        const bool dep = ((badmask >> k) & 1) || !(piv > tol2);
+        if (k < bw) {
+            if (dep) {
+                badmask |= 1 << k;
+                if (!aug) x[k] = (j == k) ? 1.0 : 0.0;
+            } else {
+                if (piv < min_piv) min_piv = piv;
+                const double rinv = rsqrt_nr(piv);
+                x[k] *= rinv;
+#pragma unroll
+                for (int i = k + 1; i < W; ++i) {
+                    const double rki = __shfl(x[k], i);
+                    if (aug || j >= i) x[i] -= rki * x[k];
+                }
+            }
+        }
+    }
+    // lane 16 + c holds row c of T_JJ
+    if (aug && j < 16 + bw) {
+        rdiag[r0 + c] = x[c];
+#pragma unroll
+        for (int i = 1; i < W; ++i)
+            if (i > c && i < bw) a[tri_idx(r0 + c, r0 + i, w)] = x[i];
+    }
+    if (j < bw) bad[r0 + j] = (badmask >> j) & 1;
+}
+
 // Layers whose factorisation is cheap enough for every workgroup of the apply kernel to repeat it for
 // itself (one kernel boundary less): register path, and few partial Gram matrices to add up.
 constexpr int kLocalCholMaxSlots = 64;
@@ -210,18 +267,30 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             a[t] = s;
         }
     } else {
-        for (int e = t; e < ntri; e += kThreads) {
-            const double* __restrict__ g = gram + e;
-            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+        // one workgroup adds up everything: keep many loads in flight (two entries x 16 slots per thread);
+        // the order of the sum is fixed
+        for (int e = t; e < ntri; e += 2 * kThreads) {
+            const bool two = e + kThreads < ntri;
+            const double* __restrict__ g0 = gram + e;
+            const double* __restrict__ g1 = gram + (two ? e + kThreads : e);
+            double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0, q0 = 0.0, q1 = 0.0, q2 = 0.0, q3 = 0.0;
             int sl = 0;
-            for (; sl + 8 <= n_slots; sl += 8) {      // independent loads in flight; order of the sum is fixed
-                double x[8];
+            for (; sl + 16 <= n_slots; sl += 16) {
+                double x[16], y[16];
 #pragma unroll
-                for (int d = 0; d < 8; ++d) x[d] = g[(int64_t)(sl + d) * ntri];
-                s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
+                for (int d = 0; d < 16; ++d) {
+                    x[d] = g0[(int64_t)(sl + d) * ntri];
+                    y[d] = g1[(int64_t)(sl + d) * ntri];
+                }
+#pragma unroll
+                for (int d = 0; d < 16; d += 4) {
+                    p0 += x[d]; p1 += x[d + 1]; p2 += x[d + 2]; p3 += x[d + 3];
+                    q0 += y[d]; q1 += y[d + 1]; q2 += y[d + 2]; q3 += y[d + 3];
+                }
             }
-            for (; sl < n_slots; ++sl) s0 += g[(int64_t)sl * ntri];
-            a[e] = (s0 + s1) + (s2 + s3);
+            for (; sl < n_slots; ++sl) { p0 += g0[(int64_t)sl * ntri]; q0 += g1[(int64_t)sl * ntri]; }
+            a[e] = (p0 + p1) + (p2 + p3);
+            if (two) a[e + kThreads] = (q0 + q1) + (q2 + q3);
         }
     }
     __syncthreads();
@@ -242,32 +311,85 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         for (int j = i + tx; j < w; j += 16) a[base + j] *= dsc[i] * dsc[j];
     }
     __syncthreads();
-    // right-looking Cholesky, A = R^T R, R overwrites the strict upper triangle
+    // right-looking Cholesky, A = R^T R, R overwrites the strict upper triangle; 1 / R_kk goes to rdiag
     double min_piv = 1.0;
-    for (int k = 0; k < w; ++k) {
-        // every thread reads the pivot itself; 1 / R_kk goes to rdiag, so the pivot entry is never
-        // overwritten and two barriers per step are enough
-        const double piv = a[tri_idx(k, k, w)];
-        const bool dep = bad[k] || !(piv > tol2);
-        if (!dep && piv < min_piv) min_piv = piv;
-        const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
-        if (dep) {
-            if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
-            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
-        } else {
-            const double rinv = rsqrt_nr(piv);
-            if (t == 0) rdiag[k] = rinv;
-            for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
-        }
-        __syncthreads();
-        if (!dep) {
-            for (int i = k + 1 + ty; i < w; i += 16) {
-                const double rki = a[kbase + i];
-                const int base = tri_idx(i, i, w) - i;
-                for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
+    const int lane = t & 63, wv = t >> 6, li = lane & 15, lk = lane >> 4;
+    if (!blocked) {
+        for (int k = 0; k < w; ++k) {
+            // every thread reads the pivot itself; the pivot entry is never overwritten, so two barriers
+            // per step are enough
+            const double piv = a[tri_idx(k, k, w)];
+            const bool dep = bad[k] || !(piv > tol2);
+            if (!dep && piv < min_piv) min_piv = piv;
+            const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
+            if (dep) {
+                if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
+                for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
+            } else {
+                const double rinv = rsqrt_nr(piv);
+                if (t == 0) rdiag[k] = rinv;
+                for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
             }
+            __syncthreads();
+            if (!dep) {
+                for (int i = k + 1 + ty; i < w; i += 16) {
+                    const double rki = a[kbase + i];
+                    const int base = tri_idx(i, i, w) - i;
+                    for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
+                }
+            }
+            __syncthreads();
         }
-        __syncthreads();
+    } else {
+        // The same in 16 x 16 blocks: per block row J, (1) one wave factorises the diagonal block and
+        // inverts its factor (needed below and by the inverse of R), (2) R_JK = T_JJ^T A_JK for K > J and
+        // (3) A_IK -= R_JI^T R_JK for J < I <= K run on the fp64 matrix cores, blocks dealt to the waves.
+        const int nbk = wp / 16;
+        for (int J = 0; J < nbk; ++J) {
+            const int r0 = 16 * J;
+            const int bw = min(16, w - r0);
+            if (t < 64) chol_block16(a, w, r0, bw, tol2, rdiag, bad, min_piv);
+            __syncthreads();
+            // (2) row panel; rows of dependent columns are zero.  (Block J is complete: K > J exists.)
+            for (int K = J + 1 + wv; K < nbk; K += kThreads / 64) {
+                doublex4 d = {0.0, 0.0, 0.0, 0.0};
+                const int col = 16 * K + li;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const int kk = r0 + 4 * c + lk, ii = r0 + li;
+                    const double av = kk < ii ? a[tri_idx(kk, ii, w)] : (kk == ii ? rdiag[ii] : 0.0);   // T_JJ[kk][ii]
+                    const double bv = col < w ? a[tri_idx(kk, col, w)] : 0.0;                           // A_JK[kk][col]
+                    d = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, d, 0, 0, 0);
+                }
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int row = r0 + 4 * v + lk;
+                    if (col < w) a[tri_idx(row, col, w)] = bad[row] ? 0.0 : d[v];
+                }
+            }
+            __syncthreads();
+            // (3) trailing update
+            int pair = 0;
+            for (int I = J + 1; I < nbk; ++I)
+                for (int K = I; K < nbk; ++K, ++pair) {
+                    if ((pair & 3) != wv) continue;
+                    doublex4 acc = {0.0, 0.0, 0.0, 0.0};
+                    const int ci = 16 * I + li, ck = 16 * K + li;
+#pragma unroll
+                    for (int c = 0; c < 4; ++c) {
+                        const int kk = r0 + 4 * c + lk;
+                        const double av = ci < w ? a[tri_idx(kk, ci, w)] : 0.0;     // R_JI[kk][ci]
+                        const double bv = ck < w ? a[tri_idx(kk, ck, w)] : 0.0;     // R_JK[kk][ck]
+                        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(av, bv, acc, 0, 0, 0);
+                    }
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int row = 16 * I + 4 * v + lk;
+                        if (row <= ck && ck < w) a[tri_idx(row, ck, w)] -= acc[v];
+                    }
+                }
+            __syncthreads();
+        }
     }
     // inverse T of the upper-triangular factor, in place in the packed triangle (T_jj = 1 / R_jj is in rdiag):
     //   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
@@ -286,29 +408,12 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     } else {
-        // 16 x 16 blocks.  First the diagonal blocks, all at once, by the column scheme above ...
+        // 16 x 16 blocks; the diagonal blocks of T were left by the factorisation,
         const int nbk = wp / 16;
-        {
-            const int J = t >> 4, i = t & 15, r0 = 16 * J;
-            const int bw = J < nbk ? min(16, w - r0) : 0;
-            for (int j = 1; j < 16; ++j) {
-                const bool act = i < j && j < bw;
-                if (act) tcol[r0 + i] = a[tri_idx(r0 + i, r0 + j, w)];
-                __syncthreads();
-                if (act) {
-                    const int base = tri_idx(r0 + i, r0 + i, w) - i;          // a[base + c] = entry (r0 + i, r0 + c)
-                    double sacc = rdiag[r0 + i] * tcol[r0 + i];
-                    for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[r0 + l];
-                    a[base + j] = -rdiag[r0 + j] * sacc;
-                }
-                __syncthreads();
-            }
-        }
-        // ... then block column after block column, T_IJ = -(sum_{K=I}^{J-1} T_IK R_KJ) T_JJ on the fp64 matrix
+        // then block column after block column, T_IJ = -(sum_{K=I}^{J-1} T_IK R_KJ) T_JJ on the fp64 matrix
         // cores, the block rows I dealt to the waves.  The products are formed transposed,
         // U^T = sum_K R_KJ^T T_IK^T and T_IJ^T = -T_JJ^T U^T, so that the accumulator of the first is the
         // B operand of the second without a move.  R_KJ is read from a copy of the block column, T in place.
-        const int lane = t & 63, wv = t >> 6, li = lane & 15, lk = lane >> 4;
         for (int J = 1; J < nbk; ++J) {
             for (int e = t; e < 16 * J * 16; e += kThreads) {
                 const int row = e >> 4, col = 16 * J + (e & 15);
