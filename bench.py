@@ -216,7 +216,7 @@ def main():
     # region held no SSP step)
     s1_ms, s1_n = prof["sweep1"] if prof["sweep1"][1] > 0 else prof_ssp["sweep1"]
     per_launch_ms = s1_ms / max(1, s1_n)
-    s1_bytes = elems * (wl.n_workers * sg + 8) + sum((s.rows + s.cols) * 4 * 32 * ((wl.r + 31) // 32) for s in wl.layers)
+    s1_bytes = comp.kernel_bytes("sweep1")
     achieved = s1_bytes / (per_launch_ms * 1e-3) / 1e9 if per_launch_ms > 0 else 0.0
     traffic = read_traffic(args.workload)
     kernels = {}

@@ -84,7 +84,11 @@ typedef struct {
                                    products per term (16 mantissa bits), 3 = six products (24 bits,
                                    fp32-faithful); 0 = default: 3 if any layer has fp32 gradients,
                                    else 2                                                            */
-    int32_t reserved[2];
+    int32_t m_policy;           /* where M = mean G + E lives between the passes of an SSP step: 1 = stored
+                                   over E by the first pass, 2 = formed again from G and E by every pass
+                                   (E is only written by the residual; fewer bytes never, equal bytes for
+                                   one bf16 worker, first pass read-only), 0 = default = 1                  */
+    int32_t reserved;
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */
@@ -139,6 +143,11 @@ int psgd_status(psgd_ctx *ctx, void *workspace, void *stream, int layer, psgd_la
  * rows*cols*min(N*sizeof(G) + 16, 2*N*sizeof(G) + 12) -- M stored between the two passes, or
  * formed twice -- plus 16*(rows + cols)*r for the thin matrices. */
 double psgd_algorithmic_bytes(const psgd_ctx *ctx);
+
+/* Algorithmic HBM bytes of one launch of a streaming kernel of psgd_compress over all layers, under the
+ * context's m_policy (tag = PSGD_PROF_SWEEP1 / _SWEEP2 / _RESIDUAL): matrix bytes read and written + the
+ * packed thin operands.  What a measured kernel duration is divided into for the roofline. */
+double psgd_kernel_bytes(const psgd_ctx *ctx, int tag);
 
 /* Plain device copy kernel (dst <- src, n_bytes multiple of 16) used to calibrate profiler counters
  * and to measure the attainable copy bandwidth with the same launch machinery. */

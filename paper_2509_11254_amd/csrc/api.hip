@@ -14,7 +14,7 @@
 namespace psgd {
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
                        int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
-hipError_t launch_outer(int nb, int planes, bool decomp, const LayerDev* layers, const int* ids, int n_ids,
+hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
                          int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
@@ -69,6 +69,8 @@ struct psgd_ctx {
     int cpz = 0;     // its packed width: wz rounded up to a multiple of 32
     int cpmax = 0;   // max(cpc, cpz)
     int planes = 2;  // bf16 planes per fp32 operand of the MFMA products (2: 3 products, 3: 6 products)
+    bool reform_m = false;   // SSP step forms M = mean G + E in every pass instead of storing it over E
+    double kernel_bytes[3] = {0.0, 0.0, 0.0};   // algorithmic bytes of the three streaming kernels of one SSP step
     // batched splits
     int split_row_b = 1, split_col_b = 1;
     // workspace layout (byte offsets)
@@ -258,6 +260,7 @@ struct Launcher {
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
+    bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -279,8 +282,9 @@ struct Launcher {
               double tol2 = 0.0, int w = 0) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
-        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, epi, gate, st));
-        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, epi, gate, st));
+        const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
+        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
@@ -306,9 +310,9 @@ struct Launcher {
             note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp,
                               a2 == -1 ? g : a2, a2, tol2, st));
     }
-    void residual(int nb) {
+    void residual(int nb, bool form = false) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
-        note(launch_outer(nb, ctx->planes, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        note(launch_outer(nb, ctx->planes, false, form, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
         prof_end(k);
     }
 };
@@ -413,6 +417,13 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         const int prec = c->opt.precision;
         if (prec != 0 && prec != 2 && prec != 3) rc = PSGD_E_INVALID_ARG;
         c->planes = prec ? prec : (any_f32 ? 3 : 2);
+        // M between the passes: stored over E (N*sg + 20 bytes per element over the three kernels) or formed
+        // again from G and E in every pass (3*N*sg + 16).  Equal bytes at N*sg = 2 (one bf16 worker), where
+        // forming again makes pass 1 read-only -- but the residual then merges three streams and is the slower
+        // by more than pass 1 gains (7B-shaped set: 35.4 against 31.6 ms per step), so storing is the default.
+        const int pol = c->opt.m_policy;
+        if (pol < 0 || pol > 2) rc = PSGD_E_INVALID_ARG;
+        c->reform_m = pol == 2;
     }
     if (rc == PSGD_OK) {
         c->rmax = rmax;
@@ -464,6 +475,11 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         const double a = n_workers * sg + 16.0, b = 2.0 * n_workers * sg + 12.0;
         bytes += (double)p.d.rows * (double)p.d.cols * (a < b ? a : b);
         bytes += 4.0 * 4.0 * (double)(p.d.rows + p.d.cols) * p.d.r;
+        const double e = (double)p.d.rows * (double)p.d.cols, nsg = n_workers * sg;
+        const double thin = 4.0 * (double)(p.d.rows + p.d.cols) * 32.0 * ((p.d.r + 31) / 32);
+        c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin;
+        c->kernel_bytes[1] += e * (c->reform_m ? nsg + 4.0 : 4.0) + thin;
+        c->kernel_bytes[2] += e * (c->reform_m ? nsg + 8.0 : 8.0) + thin;
     }
     c->ws_bytes = o;
     c->algo_bytes = bytes;
@@ -474,6 +490,10 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
 size_t psgd_workspace_bytes(const psgd_ctx* ctx) { return ctx ? ctx->ws_bytes : 0; }
 
 double psgd_algorithmic_bytes(const psgd_ctx* ctx) { return ctx ? ctx->algo_bytes : 0.0; }
+
+double psgd_kernel_bytes(const psgd_ctx* ctx, int tag) {
+    return (ctx && tag >= 0 && tag < 3) ? ctx->kernel_bytes[tag] : 0.0;
+}
 
 static int bind_common(psgd_ctx* ctx, void* workspace, hipStream_t st, const void* const* G, float* const* E,
                        float* const* Q, float* const* P) {
@@ -502,10 +522,14 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp);
-    // P = M Q_{t-1} (M formed and stored on the way); P~ = QR(P), operand copies of P~
+    // P = M Q_{t-1} (M formed on the way and, unless it is formed again below, stored over E);
+    // P~ = QR(P), operand copies of P~
+    const bool re = ctx->reform_m;
+    L.keep_e = re;
     L.prod_orth(true, true, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
-    L.prod(false, false, nb, ROLE_Q, EPI_PACK);    // Q_t = M^T P~, operand copies of Q_t
-    L.residual(nb);                                // E <- M - P~ Q_t^T
+    L.prod(false, re, nb, ROLE_Q, EPI_PACK);       // Q_t = M^T P~, operand copies of Q_t
+    L.keep_e = false;
+    L.residual(nb, re);                            // E <- M - P~ Q_t^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -576,7 +600,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_P, cp, ROLE_Q);
-    L.note(launch_outer(nb, ctx->planes, true, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+    L.note(launch_outer(nb, ctx->planes, true, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;

@@ -163,9 +163,11 @@ constexpr int prod_min_blocks(int nb, int pl) { return 2 * pl * (BT + 32 * nb) *
 template <int NB, int PL, bool COLMODE, bool FORM>
 __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
-                                                        int epi, int gate) {
+                                                        int epi_flags, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
+    const int epi = epi_flags & EPI_KIND_MASK;
+    const bool store_m = FORM && !(epi_flags & EPI_KEEP_E);
     const int out_side = COLMODE ? SIDE_W : SIDE_L;
     const int src_side = COLMODE ? SIDE_L : SIDE_W;
     const int out_len = COLMODE ? L.cols : L.rows;
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int row = r0 + 16 * u;
-                    if (FORM) store_m4(L, ob * BT + row, col, m[u]);
+                    if (store_m) store_m4(L, ob * BT + row, col, m[u]);
                     bf16x4 o[PL];
                     bf16_t q[PL];
                     split_planes<PL>(m[u].x, q);
@@ -243,7 +245,7 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
             } else {
                 const int rg = r0;
                 const int col = ob * BT + 4 * c4;
-                if (FORM) {
+                if (store_m) {
 #pragma unroll
                     for (int u = 0; u < 8; ++u) store_m4(L, k0 + 8 * rg + u, col, m[u]);
                 }
@@ -353,11 +355,12 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
 // does that for itself; -2: no factorisation follows.
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
-                                                          int out_role, int epi, int gate, int chol_gate,
+                                                          int out_role, int epi_flags, int gate, int chol_gate,
                                                           int a2gate, double tol2) {
     __shared__ int s_last;
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
+    const int epi = epi_flags & EPI_KIND_MASK;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
     const int n_split = colmode ? L.split_col : L.split_row;

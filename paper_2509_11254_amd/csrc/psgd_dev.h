@@ -34,7 +34,8 @@ enum Side { SIDE_L = 0, SIDE_W = 1 };
 // Roles: the paper's P~ and Q (user buffers, leading dimension r) and the two wide internal
 // blocks of the subspace iteration (leading dimension wz).
 // what a product's epilogue does besides storing the thin result
-enum Epilogue { EPI_NONE = 0, EPI_GRAM = 1, EPI_PACK = 2 };
+enum Epilogue { EPI_NONE = 0, EPI_GRAM = 1, EPI_PACK = 2, EPI_KIND_MASK = 3,
+                EPI_KEEP_E = 16 };   // flag: a FORM pass uses M but leaves E in place (M is formed again later)
 enum Role { ROLE_P = 0, ROLE_Q = 1, ROLE_ZP = 2, ROLE_ZQ = 3, ROLE_COUNT = 4 };
 
 struct ThinRef {

@@ -1,6 +1,7 @@
 // Rank-w outer product on MFMA fused with the error-feedback residual (gfx950).
 //
 //   residual    S <- S - X_L X_W^T     E_{t+1} = M - P~ Q_t^T        (Algorithm 2, error update)
+//               (FORM: S holds E_t, not M; M = mean G + E is formed again on the way, Eq. (7a))
 //   decompress  out <- X_L X_W^T       Delta_hat = P~ Q_t^T          (Algorithm 1, return value)
 //
 // Both thin operands arrive pre-split into two or three bf16 planes (row-major [len][cp]); the
@@ -68,9 +69,18 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     }
 }
 
-template <int NB, int PL>
-__global__ __launch_bounds__(kThreads, 3) void residual_kernel(const LayerDev* __restrict__ layers,
-                                                            const int* __restrict__ ids, int cp) {
+// 16 bytes of worker w's gradient at element offset off, widened to fp32
+__device__ inline floatx4 load_grad4(const LayerDev& L, int w, int64_t off) {
+    const PSGD_GLOBAL void* gw = as_global(as_global(L.G)[w]);
+    if (L.gdt == 0) return *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL float*>(gw) + off);
+    const uintx2 v = *reinterpret_cast<const PSGD_GLOBAL uintx2*>(reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw) + off);
+    return floatx4{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
+                   __uint_as_float(v.y & 0xffff0000u)};
+}
+
+template <int NB, int PL, bool FORM>
+__global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const LayerDev* __restrict__ layers,
+                                                                       const int* __restrict__ ids, int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
     const int tile = blockIdx.x;
@@ -93,9 +103,17 @@ __global__ __launch_bounds__(kThreads, 3) void residual_kernel(const LayerDev* _
     for (int v = 0; v < 16; ++v) {
         const int k = 8 * (v >> 2) + (v & 3);
         m[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (col_ok && row_lane + k < L.rows)
+        if (col_ok && row_lane + k < L.rows) {
             m[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(
                 reinterpret_cast<const PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
+            if (FORM) {
+                // same arithmetic and order as the product kernel's FORM path: (sum of workers) / N + E
+                const int64_t off = (int64_t)(rb * RT + k) * L.ld + cb * RT + (lane_byte >> 2);
+                floatx4 g = load_grad4(L, 0, off);
+                for (int w = 1; w < L.n_workers; ++w) g += load_grad4(L, w, off);
+                m[v] = g * (1.0f / (float)L.n_workers) + m[v];
+            }
+        }
     }
     floatx16 acc[4];
     outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
@@ -169,7 +187,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
 static size_t outer_lds_bytes(int nb, int planes) { return (size_t)planes * RT * (32 * nb + 8) * sizeof(bf16_t); }
 
 template <int NB, int PL>
-static hipError_t launch_outer_nb(bool decomp, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+static hipError_t launch_outer_nb(bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                                   void* const* outs, int out_bf16, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
@@ -182,8 +200,16 @@ static hipError_t launch_outer_nb(bool decomp, const LayerDev* layers, const int
             if (e != hipSuccess) return e;
         }
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16);
+    } else if (form) {
+        auto kfn = residual_kernel<NB, PL, true>;
+        if (lds > 48 * 1024) {
+            hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return e;
+        }
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
     } else {
-        auto kfn = residual_kernel<NB, PL>;
+        auto kfn = residual_kernel<NB, PL, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -194,13 +220,13 @@ static hipError_t launch_outer_nb(bool decomp, const LayerDev* layers, const int
     return hipGetLastError();
 }
 
-hipError_t launch_outer(int nb, int planes, bool decomp, const LayerDev* layers, const int* ids, int n_ids,
+hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
 #define PSGD_CASE(N)                                                                                              \
     case N:                                                                                                       \
-        return planes == 2 ? launch_outer_nb<N, 2>(decomp, layers, ids, n_ids, max_tiles, outs, out_bf16, st)     \
-                           : launch_outer_nb<N, 3>(decomp, layers, ids, n_ids, max_tiles, outs, out_bf16, st);
+        return planes == 2 ? launch_outer_nb<N, 2>(decomp, form, layers, ids, n_ids, max_tiles, outs, out_bf16, st)     \
+                           : launch_outer_nb<N, 3>(decomp, form, layers, ids, n_ids, max_tiles, outs, out_bf16, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;

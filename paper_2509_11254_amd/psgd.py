@@ -19,7 +19,8 @@ PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -
 
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_refresh",
-    "psgd_decompress", "psgd_status", "psgd_algorithmic_bytes", "psgd_copy_bytes", "psgd_last_hip_error",
+    "psgd_decompress", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
+    "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_read",
 ]
 PROF_TAGS = ("sweep1", "sweep2", "residual")
@@ -33,7 +34,7 @@ class LayerDesc(C.Structure):
 class Options(C.Structure):
     _fields_ = [("refresh_iters", C.c_int32), ("refresh_oversample", C.c_int32),
                 ("refresh_warm_start", C.c_int32), ("seed", C.c_uint32), ("rank_tol", C.c_float),
-                ("precision", C.c_int32), ("reserved", C.c_int32 * 2)]
+                ("precision", C.c_int32), ("m_policy", C.c_int32), ("reserved", C.c_int32)]
 
 
 class LayerStatus(C.Structure):
@@ -81,6 +82,8 @@ def load_library() -> C.CDLL:
     lib.psgd_status.restype = C.c_int
     lib.psgd_algorithmic_bytes.argtypes = [vp]
     lib.psgd_algorithmic_bytes.restype = C.c_double
+    lib.psgd_kernel_bytes.argtypes = [vp, C.c_int]
+    lib.psgd_kernel_bytes.restype = C.c_double
     lib.psgd_copy_bytes.argtypes = [vp, vp, vp, C.c_size_t]
     lib.psgd_copy_bytes.restype = C.c_int
     lib.psgd_last_hip_error.argtypes = [vp]
@@ -126,7 +129,8 @@ class Compressor:
 
     def __init__(self, layers: Sequence[Sequence[int]], n_workers: int, *, refresh_iters: int = 0,
                  refresh_oversample: int = -1, refresh_warm_start: bool = True, seed: int = 0x5EED5EED,
-                 rank_tol: float = 0.0, precision: int = 0, device: str = "cuda:0", allocate: bool = True):
+                 rank_tol: float = 0.0, precision: int = 0, m_policy: int = 0, device: str = "cuda:0",
+                 allocate: bool = True):
         self.lib = load_library()
         self.n_layers = len(layers)
         self.n_workers = int(n_workers)
@@ -135,7 +139,7 @@ class Compressor:
             descs[i].rows, descs[i].cols, descs[i].r, descs[i].grad_dtype = int(l[0]), int(l[1]), int(l[2]), int(l[3])
             descs[i].ld = int(l[4]) if len(l) > 4 else 0
         opt = Options(int(refresh_iters), int(refresh_oversample), 1 if refresh_warm_start else 0,
-                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision))
+                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), 0)
         self.ctx = C.c_void_p()
         rc = self.lib.psgd_init(C.byref(self.ctx), self.n_layers, descs, self.n_workers, C.byref(opt))
         _check(self.lib, None, rc)
@@ -159,6 +163,10 @@ class Compressor:
     @property
     def algorithmic_bytes(self) -> float:
         return float(self.lib.psgd_algorithmic_bytes(self.ctx))
+
+    def kernel_bytes(self, tag: str) -> float:
+        """Algorithmic bytes of one launch of the streaming kernel `tag` (one of PROF_TAGS) over all layers."""
+        return float(self.lib.psgd_kernel_bytes(self.ctx, PROF_TAGS.index(tag)))
 
     def _tables(self, G, E, Q, P):
         flat_g = [g for per_layer in G for g in per_layer] if G and isinstance(G[0], (list, tuple)) else list(G)

@@ -131,6 +131,29 @@ def test_ssp_step_batched_mixed_layers():
     print(_run_case(wl))
 
 
+@pytest.mark.parametrize("m_policy", [1, 2])
+@pytest.mark.parametrize("which", ["f32_n4", "bf16_n1", "bf16_n3_transposed", "batched"])
+def test_ssp_step_m_stored_or_formed_again(which, m_policy):
+    """M = mean G + E between the passes of an SSP step: stored over E by the first pass (policy 1) or
+    formed again from G and E by every pass (policy 2).  Same result."""
+    if which == "f32_n4":
+        wl = synth.scaled_down(synth.config1(), 333, 203)
+        lds = [208]
+    elif which == "bf16_n1":
+        wl = synth.scaled_down(synth.config4(), 700, 384)
+        lds = None
+    elif which == "bf16_n3_transposed":
+        wl = synth.scaled_down(synth.config3(), 384, 1024)
+        wl.n_workers = 3
+        lds = None
+    else:
+        wl = synth.scaled_down(synth.config4(), 256, 256)
+        wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c"),
+                     synth.LayerSpec(200, 136, "e")]
+        lds = None
+    print(which, m_policy, _run_case(wl, lds=lds, m_policy=m_policy))
+
+
 # ------------------------------------------------------------------ trajectory, teacher-forced (config 1)
 def test_config1_trajectory_teacher_forced():
     wl = synth.config1()
