@@ -18,14 +18,14 @@ hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerD
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
                          int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
-                         hipStream_t st);
+                         int local_ok, hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
                        int cp, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, int a2gate, hipStream_t st);
+                       int slot_rows, int gate, int a2gate, int local_ok, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
-                        hipStream_t st);
+                        bool small, hipStream_t st);
 hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
                              int src_role, int warm, uint32_t seed, hipStream_t st);
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
@@ -279,7 +279,7 @@ struct Launcher {
     // product whose result is P-like (lives on the long side) or Q-like, stored in thin[out_role];
     // chol_gate >= -1: the first CholeskyQR pass on the result follows at once (see prod_orth)
     void prod(bool p_like, bool form, int nb, int out_role, int epi, int chol_gate = -2, int a2gate = -2,
-              double tol2 = 0.0, int w = 0) {
+              double tol2 = 0.0, int w = 0, bool small = false) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
@@ -289,11 +289,11 @@ struct Launcher {
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
         const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, st));
-        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, st));
+        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (chol_gate >= -1) {
-            if (!split_n) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, st));
-            if (!split_t) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, st));
+            if (!split_n) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
+            if (!split_t) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
         }
     }
     // thin[out_role] = product as in prod(), then CholeskyQR2 on it: the first pass always, the second
@@ -304,11 +304,16 @@ struct Launcher {
     void prod_orth(bool p_like, bool form, int nb, int out_role, int w, double tol2, int cp, int kind, Pass2 pass2) {
         const int g = gate < 0 ? -1 : (gate | kind << 8);
         const int a2 = pass2 == PASS2_ALWAYS ? -1 : (pass2 == PASS2_NEVER || gate < 0) ? -2 : (gate | 2 << 8);
-        prod(p_like, form, nb, out_role, EPI_GRAM, g, a2, tol2, w);
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, st));
-        if (a2 != -2)
-            note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp,
-                              a2 == -1 ? g : a2, a2, tol2, st));
+        // narrow blocks everywhere: the apply kernel factorises per workgroup and hands over to the second
+        // factorisation itself; otherwise the second factorisation is a launch of its own
+        const bool small = w <= 16;
+        prod(p_like, form, nb, out_role, EPI_GRAM, g, a2, tol2, w, small);
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, small, st));
+        if (a2 != -2) {
+            const int g2 = a2 == -1 ? g : a2;
+            if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, g2, -2, 0, st));
+            note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, g2, a2, tol2, small, st));
+        }
     }
     void residual(int nb, bool form = false) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
@@ -369,9 +374,9 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZP, ROLE_P, APPLY_RITZ,
-                        final_cp, -1, -2, 0.0, L.st));
+                        final_cp, -1, -2, 0.0, false, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, APPLY_RITZ,
-                        final_cp, -1, -2, 0.0, L.st));
+                        final_cp, -1, -2, 0.0, false, L.st));
     L.prof_mute = false;
 }
 

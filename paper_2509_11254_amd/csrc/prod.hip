@@ -34,40 +34,64 @@ __device__ inline float4 ld_bf16x4(const PSGD_GLOBAL bf16_t* p) {
     return o;
 }
 
-// A thread's share of one S tile: eight 4-element pieces, piece u at (row0 + u*row_step, col).
-// Addresses are clamped into the matrix and the values masked afterwards (no divergent loads); the
-// padding up to ld and rows past the end are not data.
+// A thread's share of one S tile: eight 4-element pieces, piece u at (row0 + u*row_step, col).  The
+// address of piece u is (uniform part: tile origin + u * ustep) + (this thread's offset inside the tile),
+// so that the eight addresses cost one 32-bit register.  Tiles that lie inside the matrix (`full`, uniform)
+// take unpredicated loads; ragged ones load under a per-piece predicate and mask the column tail afterwards
+// (the padding up to ld and rows past the end are not data).
 struct TileAddr {
-    int64_t off[8];
-    bool ok[8];
-    bool k1, k2, k3;
+    int64_t origin;     // element offset of the tile's first element
+    int64_t ustep;      // elements between a thread's consecutive pieces (row_step * ld)
+    unsigned lane;      // element offset of this thread's piece 0 from the origin (< 2^30)
+    int row0, row_step, col;
+    bool full;
 };
 
-__device__ inline TileAddr tile_addr(const LayerDev& L, int row0, int row_step, int col) {
+__device__ inline TileAddr tile_addr(const LayerDev& L, int tile_row0, int tile_col0, int tile_rows, int tile_cols,
+                                     int lane_row, int row_step, int lane_col) {
     TileAddr a;
-    const bool col_ok = col < L.cols;
-    const int colc = col_ok ? col : 0;
-#pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        const int row = row0 + u * row_step;
-        a.ok[u] = col_ok && row < L.rows;
-        a.off[u] = (int64_t)min(row, L.rows - 1) * L.ld + colc;
-    }
-    a.k1 = col + 1 < L.cols; a.k2 = col + 2 < L.cols; a.k3 = col + 3 < L.cols;
+    a.origin = (int64_t)tile_row0 * L.ld + tile_col0;
+    a.ustep = (int64_t)row_step * L.ld;
+    a.lane = (unsigned)lane_row * (unsigned)L.ld + (unsigned)lane_col;
+    a.row0 = tile_row0 + lane_row;
+    a.row_step = row_step;
+    a.col = tile_col0 + lane_col;
+    a.full = tile_row0 + tile_rows <= L.rows && tile_col0 + tile_cols <= L.cols;
     return a;
+}
+
+__device__ inline bool piece_ok(const LayerDev& L, const TileAddr& a, int u) {
+    return a.col < L.cols && a.row0 + u * a.row_step < L.rows;
+}
+
+// eight pieces of a row-major matrix of T (float or bf16) with the layer's leading dimension, widened to fp32
+template <class T>
+__device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const TileAddr& a, float4 (&x)[8]) {
+    const PSGD_GLOBAL char* b = reinterpret_cast<const PSGD_GLOBAL char*>(base + a.origin);
+    const unsigned lb = a.lane * (unsigned)sizeof(T);
+    const int64_t sb = a.ustep * (int64_t)sizeof(T);
+    if (a.full) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
+            if constexpr (sizeof(T) == 4) x[u] = ld_f32x4(p); else x[u] = ld_bf16x4(p);
+        }
+    } else {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (piece_ok(L, a, u)) {
+                const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
+                if constexpr (sizeof(T) == 4) x[u] = ld_f32x4(p); else x[u] = ld_bf16x4(p);
+            }
+        }
+    }
 }
 
 __device__ inline void load_g8(const LayerDev& L, int w, const TileAddr& a, float4 (&x)[8]) {
     const PSGD_GLOBAL void* gw = as_global(as_global(L.G)[w]);
-    if (L.gdt == 0) {
-        const PSGD_GLOBAL float* __restrict__ g = reinterpret_cast<const PSGD_GLOBAL float*>(gw);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = ld_f32x4(g + a.off[u]);
-    } else {
-        const PSGD_GLOBAL bf16_t* __restrict__ g = reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) x[u] = ld_bf16x4(g + a.off[u]);
-    }
+    if (L.gdt == 0) load8(L, reinterpret_cast<const PSGD_GLOBAL float*>(gw), a, x);
+    else load8(L, reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw), a, x);
 }
 
 __device__ inline void add8(float4 (&m)[8], const float4 (&x)[8]) {
@@ -81,26 +105,39 @@ template <bool FORM>
 __device__ inline void tile_prefetch(const LayerDev& L, const TileAddr& a, float4 (&p0)[8], float4 (&p1)[8]) {
     if (FORM) {
         load_g8(L, 0, a, p0);
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p1[u] = ld_f32x4(as_global(L.S) + a.off[u]);
+        load8(L, as_global(L.S), a, p1);
     } else {
-#pragma unroll
-        for (int u = 0; u < 8; ++u) p0[u] = ld_f32x4(as_global(L.S) + a.off[u]);
+        load8(L, as_global(L.S), a, p0);
     }
 }
 
-// Second half: the remaining workers (eight loads in flight each), the mean, + E, the mask.
-// The sum over the workers runs in worker order.
-template <bool FORM>
+// Second half: the remaining workers, the mean, + E, the mask.  The sum over the workers runs in worker order.
+template <bool FORM, bool PIPE>
 __device__ inline void tile_finish(const LayerDev& L, const TileAddr& a, float inv_n, const float4 (&p0)[8],
                                    const float4 (&p1)[8], float4 (&m)[8]) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) m[u] = p0[u];
     if (FORM) {
-        for (int w = 1; w < L.n_workers; ++w) {
-            float4 x[8];
-            load_g8(L, w, a, x);
-            add8(m, x);
+        const int nw = L.n_workers;
+        if (PIPE) {
+            // two workers' loads in flight: the next worker is requested before the current one is added
+            // (where the registers allow it: narrow output blocks)
+            float4 xa[8], xb[8];
+            int w = 1;
+            if (w < nw) load_g8(L, w, a, xa);
+            for (; w + 1 < nw; w += 2) {
+                load_g8(L, w + 1, a, xb);
+                add8(m, xa);
+                if (w + 2 < nw) load_g8(L, w + 2, a, xa);
+                add8(m, xb);
+            }
+            if (w < nw) add8(m, xa);
+        } else {
+            for (int w = 1; w < nw; ++w) {
+                float4 x[8];
+                load_g8(L, w, a, x);
+                add8(m, x);
+            }
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -108,24 +145,41 @@ __device__ inline void tile_finish(const LayerDev& L, const TileAddr& a, float i
             m[u].z = m[u].z * inv_n + p1[u].z; m[u].w = m[u].w * inv_n + p1[u].w;
         }
     }
+    if (!a.full) {
+        // pieces outside the matrix were loaded as zero (and 0 * inv_n + 0 = 0); cut the column tail
+        const bool k1 = a.col + 1 < L.cols, k2 = a.col + 2 < L.cols, k3 = a.col + 3 < L.cols;
 #pragma unroll
-    for (int u = 0; u < 8; ++u) {
-        m[u].x = a.ok[u] ? m[u].x : 0.f;
-        m[u].y = (a.ok[u] && a.k1) ? m[u].y : 0.f;
-        m[u].z = (a.ok[u] && a.k2) ? m[u].z : 0.f;
-        m[u].w = (a.ok[u] && a.k3) ? m[u].w : 0.f;
+        for (int u = 0; u < 8; ++u) {
+            m[u].y = k1 ? m[u].y : 0.f;
+            m[u].z = k2 ? m[u].z : 0.f;
+            m[u].w = k3 ? m[u].w : 0.f;
+        }
     }
 }
 
-__device__ inline void store_m4(const LayerDev& L, int row, int col, float4 m) {
-    if (row >= L.rows || col >= L.cols) return;
-    PSGD_GLOBAL float* p = as_global(L.S) + (int64_t)row * L.ld + col;
-    if (col + 3 < L.cols) {
-        *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = floatx4{m.x, m.y, m.z, m.w};
+// M back in place of E, same addressing as the loads
+__device__ inline void store_m8(const LayerDev& L, const TileAddr& a, const float4 (&m)[8]) {
+    PSGD_GLOBAL char* b = reinterpret_cast<PSGD_GLOBAL char*>(as_global(L.S) + a.origin);
+    const unsigned lb = a.lane * 4u;
+    const int64_t sb = a.ustep * 4;
+    if (a.full) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            *reinterpret_cast<PSGD_GLOBAL floatx4*>(b + u * sb + lb) = floatx4{m[u].x, m[u].y, m[u].z, m[u].w};
     } else {
-        p[0] = m.x;
-        if (col + 1 < L.cols) p[1] = m.y;
-        if (col + 2 < L.cols) p[2] = m.z;
+        const bool k1 = a.col + 1 < L.cols, k2 = a.col + 2 < L.cols, k3 = a.col + 3 < L.cols;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (!piece_ok(L, a, u)) continue;
+            PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(b + u * sb + lb);
+            if (k3) {
+                *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = floatx4{m[u].x, m[u].y, m[u].z, m[u].w};
+            } else {
+                p[0] = m[u].x;
+                if (k1) p[1] = m[u].y;
+                if (k2) p[2] = m[u].z;
+            }
+        }
     }
 }
 
@@ -208,7 +262,7 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
     const int r0 = COLMODE ? (t >> 5) : (t >> 4);       // row group in column mode
     auto addr_of = [&](int ch) {
         const int k0 = ch * BK;
-        return COLMODE ? tile_addr(L, k0 + 8 * r0, 1, ob * BT + 4 * c4) : tile_addr(L, ob * BT + r0, 16, k0 + 4 * c4);
+        return COLMODE ? tile_addr(L, k0, ob * BT, BK, BT, 8 * r0, 1, 4 * c4) : tile_addr(L, ob * BT, k0, BT, BK, r0, 16, 4 * c4);
     };
     float4 p0[8], p1[8];
     if (ch0 < ch1) tile_prefetch<FORM>(L, addr_of(ch0), p0, p1);
@@ -218,13 +272,12 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
         {
             const TileAddr a = addr_of(ch);
             float4 m[8];
-            tile_finish<FORM>(L, a, inv_n, p0, p1, m);
+            tile_finish<FORM, (NB <= 2)>(L, a, inv_n, p0, p1, m);
+            if (store_m) store_m8(L, a, m);
             if (!COLMODE) {
-                const int col = k0 + 4 * c4;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     const int row = r0 + 16 * u;
-                    if (store_m) store_m4(L, ob * BT + row, col, m[u]);
                     bf16x4 o[PL];
                     bf16_t q[PL];
                     split_planes<PL>(m[u].x, q);
@@ -244,11 +297,6 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
                 }
             } else {
                 const int rg = r0;
-                const int col = ob * BT + 4 * c4;
-                if (store_m) {
-#pragma unroll
-                    for (int u = 0; u < 8; ++u) store_m4(L, k0 + 8 * rg + u, col, m[u]);
-                }
                 bf16x8 o[4][PL];
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
@@ -273,16 +321,27 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
                         *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * a_chunk<true>(4 * c4 + q, rg)) = o[q][k];
             }
         }
-        // ---- thin operand chunk: pre-split, transposed [cp][lenP] -> LDS [cp][LDSW]
+        // ---- thin operand chunk: pre-split, transposed [cp][lenP] -> LDS [cp][LDSW]; all loads are issued
+        // before the first LDS store so that they are in flight together
+        {
+            uintx4 bq[NB][PL];
 #pragma unroll
-        for (int it = 0; it < NB; ++it) {
-            const int v = t + it * kThreads;        // 0 .. 32*NB*8-1
-            const int c = v >> 3, part = v & 7;
-            const int64_t goff = (int64_t)c * src_lenP + k0 + 8 * part;
+            for (int it = 0; it < NB; ++it) {
+                const int v = t + it * kThreads;        // 0 .. 32*NB*8-1
+                const int c = v >> 3, part = v & 7;
+                const int64_t goff = (int64_t)c * src_lenP + k0 + 8 * part;
 #pragma unroll
-            for (int k = 0; k < PL; ++k)
-                *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) =
-                    *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
+                for (int k = 0; k < PL; ++k)
+                    bq[it][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
+            }
+#pragma unroll
+            for (int it = 0; it < NB; ++it) {
+                const int v = t + it * kThreads;
+                const int c = v >> 3, part = v & 7;
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) = bq[it][k];
+            }
         }
         __syncthreads();
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
@@ -356,7 +415,7 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
                                                           int out_role, int epi_flags, int gate, int chol_gate,
-                                                          int a2gate, double tol2) {
+                                                          int a2gate, double tol2, int local_ok) {
     __shared__ int s_last;
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
@@ -399,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     }
     __syncthreads();
     tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
-    if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role) && gate_open(L, chol_gate)) {
+    if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role, local_ok) && gate_open(L, chol_gate)) {
         const int n_wg = (out_len + BT - 1) / BT;
         if (last_to_arrive(&L.status[6], n_wg, &s_last))
             chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat);
@@ -408,7 +467,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
 
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
                          int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
-                         hipStream_t st) {
+                         int local_ok, hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
     dim3 grid(max_blocks, n_ids), block(kThreads);
     size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
@@ -419,7 +478,7 @@ hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, i
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate,
-                       chol_gate, a2gate, tol2);
+                       chol_gate, a2gate, tol2, local_ok);
     return hipGetLastError();
 }
 

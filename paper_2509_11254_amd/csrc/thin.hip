@@ -54,17 +54,18 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 // --------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows, int gate, int a2gate) {
+                                                        int pass, int slot_rows, int gate, int a2gate,
+                                                        int local_ok) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
-    if (pass == 1 && local_chol(L, role)) return;       // the apply kernel factorises for itself
+    if (pass == 1 && local_chol(L, role, local_ok)) return;       // the apply kernel factorises for itself
     extern __shared__ __align__(16) unsigned char smem[];
     chol_body(L, role, tol2, pass, slot_rows, allow2_of(L, a2gate), smem, L.tmat);
 }
 
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, int a2gate, hipStream_t st) {
+                       int slot_rows, int gate, int a2gate, int local_ok, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(1, n_ids), block(kThreads);
     const size_t lds = chol_lds_bytes_upto(w);
@@ -73,7 +74,8 @@ hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate, a2gate);
+    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate, a2gate,
+                       local_ok);
     return hipGetLastError();
 }
 
@@ -98,6 +100,11 @@ __host__ __device__ inline size_t apply_main_lds(int w_in, int w_out, int cp) {
     return (b + 15) & ~(size_t)15;
 }
 
+// SMALL: the variant for launches whose layers are all narrow (width <= 16) -- it carries the per-workgroup
+// factorisation and the hand-over to the second-pass factorisation, which cost registers the plain variant
+// (wide blocks, where the kernel is a streaming pass and wants occupancy) does without; there the
+// second-pass factorisation is a launch of its own.
+template <bool SMALL>
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
                                                          int mode, int cp, int gate, int a2gate, double tol2) {
@@ -123,7 +130,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     const int n_valid_x = (min(len, i0 + kGramRows2) - i0) * w_in;          // elements that exist
     float4 xpre = make_float4(0.f, 0.f, 0.f, 0.f);
     bool have_pre = false;
-    if (mode == APPLY_PASS1 && local_chol(L, src_role)) {
+    if (SMALL && mode == APPLY_PASS1 && local_chol(L, src_role, 1)) {
         // small factorisation repeated by every workgroup; the first one records the outcome.  The
         // workgroup's own rows are requested first so that their latency overlaps the factorisation.
         if (flat_x) {
@@ -131,7 +138,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
             if (4 * (int)threadIdx.x < n_valid_x) xpre = *reinterpret_cast<const float4*>(X.ptr + xbase + 4 * threadIdx.x);
         }
         double* tml = reinterpret_cast<double*>(smem + main_lds);
-        chol_body(L, src_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem + main_lds + w_in * w_in * sizeof(double),
+        chol_body<true>(L, src_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem + main_lds + w_in * w_in * sizeof(double),
                   tml, blockIdx.x == 0, &s_need2);
         __syncthreads();
         need2 = s_need2;
@@ -224,33 +231,36 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     }
     if (do_gram) {
         gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)blockIdx.x * ((w_out * (w_out + 1)) / 2));
-        const int n_wg = (len + kGramRows2 - 1) / kGramRows2;
-        if (last_to_arrive(&L.status[7], n_wg, &s_last)) chol_body(L, dst_role, tol2, 2, kGramRows2, false, smem, L.tmat);
+        if (SMALL) {
+            const int n_wg = (len + kGramRows2 - 1) / kGramRows2;
+            if (last_to_arrive(&L.status[7], n_wg, &s_last)) chol_body<true>(L, dst_role, tol2, 2, kGramRows2, false, smem, L.tmat);
+        }
     } else if (do_pack) {
         write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP);
     }
 }
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
+// small: every layer of the launch is narrow (w_in <= 16) and the chain runs the per-workgroup factorisation
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
-                        hipStream_t st) {
+                        bool small, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
     // w_in / w_out are upper bounds over the layers: sizes that grow with them cover every layer
     size_t lds = apply_main_lds(w_in, w_out, cp);
-    if (mode == APPLY_PASS1) {
+    if (small && mode == APPLY_PASS1) {
         if (chol_lds_bytes_upto(w_out) > lds) lds = chol_lds_bytes_upto(w_out);          // second-pass factorisation
         const int wl = w_in < kCholRegWidth ? w_in : kCholRegWidth;             // per-workgroup factorisation
         lds += (size_t)wl * wl * sizeof(double) + chol_lds_bytes_upto(wl);
     }
+    auto kfn = small ? apply_kernel<true> : apply_kernel<false>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(apply_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(apply_kernel, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate, a2gate,
-                       tol2);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate, a2gate, tol2);
     return hipGetLastError();
 }
 

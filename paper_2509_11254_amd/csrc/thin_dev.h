@@ -210,9 +210,11 @@ __device__ inline void chol_block16(double* a, int w, int r0, int bw, double tol
 // Layers whose factorisation is cheap enough for every workgroup of the apply kernel to repeat it for
 // itself (one kernel boundary less): register path, and few partial Gram matrices to add up.
 constexpr int kLocalCholMaxSlots = 64;
-__device__ inline bool local_chol(const LayerDev& L, int role) {
+// local_ok: launch-wide permission (all layers of the launch are narrow), the same in every kernel of the chain
+__device__ inline bool local_chol(const LayerDev& L, int role, int local_ok) {
     const int len = side_len(L, side_of_role(L.transposed, role));
-    return L.thin[role].width <= kCholRegWidth && (len + kGramRows1 - 1) / kGramRows1 <= kLocalCholMaxSlots;
+    return local_ok && L.thin[role].width <= kCholRegWidth &&
+           (len + kGramRows1 - 1) / kGramRows1 <= kLocalCholMaxSlots;
 }
 
 // Sums the partial Gram matrices of thin[role] (packed upper triangles, slots of `slot_rows` rows, fixed
@@ -221,6 +223,8 @@ __device__ inline bool local_chol(const LayerDev& L, int role) {
 // Called by all kThreads threads of one workgroup per layer; smem: chol_lds_bytes(w), 8-byte aligned.
 // tm: where the w x w factor goes (the layer's tmat, or LDS of the caller); need2_out: optional LDS word
 // that receives the second-pass decision; write_status: whether this caller owns the layer's status words.
+// NARROW: compiled for widths <= 16 only (the register path; nothing else is generated).
+template <bool NARROW = false>
 __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int pass, int slot_rows, bool allow2,
                                  unsigned char* smem, double* tm, bool write_status = true,
                                  int* need2_out = nullptr) {
@@ -240,7 +244,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     int* bad = reinterpret_cast<int*>(panel + (blocked ? wp * 16 : 0));    // [w] dependent-column flags
     const int t = threadIdx.x;
     const double* __restrict__ gram = L.gram;
-    if (G > 1) {
+    if (G > 1 || NARROW) {
         // thread (e, g): entries e of slots g, g + G, ...; eight loads in flight, those past the end
         // re-read slot g and do not count
         const int g = t / ntri, e = t - g * ntri;
@@ -258,13 +262,15 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
                     if (sl + d * G >= n_slots) x[d] = 0.0;
                 s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
             }
-            ps[g * ntri + e] = (s0 + s1) + (s2 + s3);
+            (G > 1 ? ps + g * ntri : a)[e] = (s0 + s1) + (s2 + s3);
         }
-        __syncthreads();
-        if (t < ntri) {
-            double s = 0.0;
-            for (int g2 = 0; g2 < G; ++g2) s += ps[g2 * ntri + t];
-            a[t] = s;
+        if (G > 1) {
+            __syncthreads();
+            if (t < ntri) {
+                double s = 0.0;
+                for (int g2 = 0; g2 < G; ++g2) s += ps[g2 * ntri + t];
+                a[t] = s;
+            }
         }
     } else {
         // one workgroup adds up everything: keep many loads in flight (two entries x 16 slots per thread);
@@ -298,6 +304,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         if (t < 64) chol_in_registers(L, a, w, tol2, pass, allow2, tm, write_status, need2_out);
         return;
     }
+    if constexpr (NARROW) return;
     for (int i = t; i < w; i += kThreads) {
         const double d = a[tri_idx(i, i, w)];
         dsc[i] = d > kTinyNorm2 ? rsqrt_nr(d) : 0.0;
