@@ -68,9 +68,11 @@ typedef struct {
 
 typedef struct {
     int32_t refresh_iters;      /* maximum number of subspace iterations of the SVD refresh; 0 = default
-                                   (8).  A layer's first refresh runs all of them; later ones run the
-                                   number that the convergence factor (theta_b/theta_r)^2 seen at its last
-                                   refresh needs for 1e-6, plus one (at least 2, at most the maximum)      */
+                                   (16).  A layer's first refresh runs all of them.  Later ones run the
+                                   number that the convergence factor rho = (theta_b/theta_r)^2 seen at its
+                                   last refresh needs for 1e-5, plus one, if that is within the maximum
+                                   (rho <= 0.46 for 16); if it is not -- no gap after sigma_r to converge
+                                   across in the budget -- they run 8 (or the maximum, if smaller)      */
     int32_t refresh_oversample; /* extra block columns beyond r; negative = default max(8, r/4); the
                                    block width r + oversample is rounded up to a multiple of 8 and
                                    capped at n                                                       */
@@ -94,8 +96,9 @@ typedef struct {
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */
 typedef struct {
     int32_t rank_deficient; /* number of columns of P~ zeroed by the rank test                  */
-    int32_t refresh_iters_next; /* iterations the layer's next refresh will run (0: not known yet, the
-                                   maximum is used): chosen from the Ritz values of the last refresh    */
+    int32_t refresh_iters_next; /* iterations the layer's next refresh needs to converge, from the Ritz
+                                   values of the last one (0: not known yet; above the maximum: it will
+                                   run 8, see refresh_iters)                                            */
     float sigma_max;        /* refresh only: largest and r-th Ritz value (singular value estimates) */
     float sigma_r;
 } psgd_layer_status;

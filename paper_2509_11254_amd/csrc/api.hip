@@ -356,7 +356,7 @@ double tol2_of(const psgd_ctx* c) {
 // largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
 void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp) {
     const int wz = ctx->wz, cpz = ctx->cpz, nbz = cpz / 32;
-    const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 8;
+    const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
     const double tol2 = tol2_of(ctx);
     L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,

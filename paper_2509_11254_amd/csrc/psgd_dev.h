@@ -156,15 +156,21 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 }
 
 // Launches inside the subspace iteration carry a gate = iteration | kind << 8 | max_iterations << 16
-// (-1 outside it).  A layer runs k iterations, k = status[4] clamped to max_iterations (all of them
-// while status[4] is still 0); kind 1 marks the orthonormalisation of Y, which the last executed
-// iteration skips because the Rayleigh-Ritz step wants Y = M^T Z itself; kind 2 is open in the last
-// executed iteration only (the second CholeskyQR pass on Z, which the Rayleigh-Ritz step needs exact).
+// (-1 outside it).  A layer runs k iterations: all max_iterations while status[4] is still 0 (first
+// refresh); status[4] itself (what its spectrum needs to converge, from the Ritz values of its last
+// refresh) when that is within the maximum; and kBudgetIterations when it is not -- the cut is then too
+// close to a cluster of singular values to converge across in the budget, and the members of such a
+// cluster compress almost equally well, so the budget is not burnt on it.  kind 1 marks the
+// orthonormalisation of Y, which the last executed iteration skips because the Rayleigh-Ritz step wants
+// Y = M^T Z itself; kind 2 is open in the last executed iteration only (the second CholeskyQR pass on Z,
+// which the Rayleigh-Ritz step needs exact).
+constexpr int kBudgetIterations = 8;
 __device__ inline bool gate_open(const LayerDev& L, int gate) {
     if (gate < 0) return true;
     const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
     int k = L.status[4];
-    if (k <= 0 || k > mx) k = mx;
+    if (k <= 0) k = mx;
+    else if (k > mx) k = mx < kBudgetIterations ? mx : kBudgetIterations;
     if (kind == 2) return it == k - 1;
     return it < k - kind;
 }

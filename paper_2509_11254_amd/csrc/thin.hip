@@ -477,12 +477,14 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     if (t == 0) {
         // The iteration contracts the error of the leading r-dimensional subspace by about
         // rho = (theta_b / theta_r)^2 per step (theta = Ritz values, the smallest one of the block standing
-        // in for sigma_{b+1}); the next refresh of this layer runs as many steps as 1e-6 needs, plus one.
+        // in for sigma_{b+1}); the next refresh of this layer needs as many steps as 1e-5 takes (a tenth of
+        // the 1e-4 bar on the subspace), plus one.  (Error feedback drives M towards rho = 1: what is not
+        // sent accumulates in E until it is as large as what is.  The launches cap the count, see gate_open.)
         int k_next = 255;
         const double lr = L.eval[r - 1], lb = L.eval[w - 1];
         if (w > r && lr > 0.0 && lb >= 0.0) {
             const double rho = lb / lr;
-            if (rho < 0.999) k_next = (rho <= 1e-12) ? 2 : (int)ceil(log(1e-6) / log(rho)) + 1;
+            if (rho < 0.999) k_next = (rho <= 1e-12) ? 2 : (int)ceil(log(1e-5) / log(rho)) + 1;
         }
         L.status[4] = max(2, min(255, k_next));
         L.status[5] = sweeps;

@@ -219,8 +219,8 @@ def test_refresh_prescribed_svd():
     assert st.rank_deficient == 0
     assert st.sigma_max == pytest.approx(out.sigma[0], rel=1e-4)
     assert st.sigma_r == pytest.approx(out.sigma[r - 1], rel=1e-4)
-    # the first refresh ran the maximum (8) and left the count its spectrum needs: block width 24,
-    # (sigma_24 / sigma_16)^2 ~ 0.057 per iteration -> ceil(log 1e-6 / log 0.057) + 1 = 6
+    # the first refresh ran the maximum (16) and left the count its spectrum needs: block width 24,
+    # (sigma_24 / sigma_16)^2 ~ 0.057 per iteration -> ceil(log 1e-5 / log 0.057) + 1 = 6
     assert 4 <= st.refresh_iters_next <= 7
     P.fill_(float("nan")); Q.fill_(float("nan"))
     comp.refresh(0, M, P, Q, S)                      # second refresh: fewer iterations, same bar
@@ -333,3 +333,52 @@ def test_config2_full_size_ssp_step():
     case.compress()
     w = _check_step(case, wl, grads, errs, qs, False, 1e-4)
     print("config2 full", w)
+
+
+def test_config2_full_size_refresh_step():
+    """SVD-Comp step at config 2's size and worker count, against the oracle's SVD of the 4096 x 4096 mean."""
+    wl = synth.config2()
+    spec = wl.layers[0]
+    grads, errs, qs = _workload_inputs(wl, err_scale=1.0)
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, errs, qs)
+    case.compress(refresh=True)
+    print("config2 full refresh", _check_step(case, wl, grads, errs, qs, True, 1e-4))
+
+
+def test_refresh_step_bf16_gradients():
+    """SVD-Comp with bf16 gradients (four workers, r = 32, normal and transposed storage): the oracle sees the
+    same bf16 values, so the subspace bar is the same 1e-4; E and Delta_hat are held to the bf16 bar."""
+    for rows, cols in ((640, 384), (384, 1024)):
+        wl = synth.scaled_down(synth.config3(), rows, cols)
+        print(rows, cols, _run_case(wl, refresh=True))
+
+
+def test_config5_full_size_refresh_known_factors():
+    """8192 x 8192 fp32, r = 128 (config 5's refresh at full size).  The matrix is built from prescribed
+    factors, M = U diag(s) V^T with a gap after s_128, so the answer is known without an SVD of this size:
+    span(P~) = span(U[:, :128]), sigma = s[:128], and E = M - P~ P~^T M has squared norm sum_{k>128} s_k^2
+    (Eq. (6))."""
+    torch = torch_mod()
+    m = n = 8192
+    r = 128
+    sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.6 * 0.97 ** np.arange(128)])
+    mat, u, v = synth.prescribed_svd_matrix(m, n, sigma, seed=21)
+    comp = psgd.Compressor([(m, n, r, psgd.PSGD_F32)], 1)
+    M = to_dev_f32(mat)
+    P = torch.empty((m, r), device="cuda")
+    Q = torch.empty((n, r), device="cuda")
+    S = torch.empty((r,), device="cuda")
+    comp.refresh(0, M, P, Q, S)
+    torch.cuda.synchronize()
+    p_gpu, q_gpu = back(P), back(Q)
+    assert np.abs(p_gpu.T @ p_gpu - np.eye(r)).max() < 2e-5
+    assert orc.sin_theta_max(u[:, :r], p_gpu) <= 1e-4
+    np.testing.assert_allclose(back(S), sigma[:r], rtol=1e-4)
+    # Q = M^T P~ and the residual norm, from the factors (fp64): M^T P~ = V diag(s) (U^T P~)
+    utp = u.T @ p_gpu
+    q_ref = (v * sigma[None, :]) @ utp
+    assert orc.rel_fro(q_gpu, q_ref) <= 1e-4
+    res2 = float(np.sum(sigma ** 2) - np.sum((sigma[:, None] * utp) ** 2))      # ||M||^2 - ||P~^T M||^2
+    assert abs(res2 - float(np.sum(sigma[r:] ** 2))) <= 1e-4 * float(np.sum(sigma[r:] ** 2))
+    assert comp.status(0).rank_deficient == 0
