@@ -4,11 +4,14 @@
 //   column mode Y_W = S^T X_L      (cols x w) = (cols x rows)(rows x w)     e.g. Q = M^T P~   (Algorithm 1)
 //
 // With FORM the pass also forms M = (1/N) sum_i G^(i) + E (Eq. (7a) averaged over the workers)
-// from the gradient buffers and the error buffer, uses it for the product and stores it in place
-// of E, so that the second pass and the residual read 4 bytes per element instead of N*sizeof(G)+4.
+// from the gradient buffers and the error buffer, uses it for the product and (unless the launch
+// carries EPI_KEEP_E) stores it in place of E, so that the second pass and the residual read 4 bytes
+// per element instead of N*sizeof(G)+4.
 //
-// Arithmetic: M and X are split into two bf16 halves each (x = hi + lo, |x - hi - lo| <= 2^-17 |x|)
-// and the product is accumulated in fp32 as hi*hi + lo*hi + hi*lo with v_mfma_f32_32x32x16_bf16.
+// Arithmetic: M and X are split into two or three bf16 planes each (x = p0 + p1 (+ p2), each plane the
+// rounded remainder of the ones before: 16 or 24 mantissa bits) and the product is accumulated in
+// fp32 from the plane products with plane-index sum <= 1 (three products) or <= 2 (six), smallest
+// first, with v_mfma_f32_32x32x16_bf16.
 // The S tile goes global -> registers (coalesced 16-byte loads, summed over workers) -> LDS in the
 // k-contiguous layout the MFMA A operand wants; the thin operand arrives pre-split and transposed.
 #include "thin_dev.h"
