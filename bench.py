@@ -38,7 +38,78 @@ def parse_args():
                          "QR: keeps rocsolver out of counter-collection runs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch the library's plain copy kernel on 256 MiB three times (counter calibration)")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="instead of the benchmark, run the plain streaming kernels of libpsgd_ceilings.so (the access "
+                         "patterns of the passes without the arithmetic) and print what HBM gives them, one JSON line")
     return ap.parse_args()
+
+
+def run_ceilings():
+    """Measured HBM ceilings for the access patterns of the three passes (GB/s), HIP-event timed."""
+    import ctypes as C
+    import torch
+    torch.cuda.set_device(0)
+    path = os.path.join(ROOT, "paper_2509_11254_amd", "libpsgd_ceilings.so")
+    if not os.path.exists(path):
+        raise FileNotFoundError(path + " is missing: run `python -m paper_2509_11254_amd.build`")
+    lib = C.CDLL(path)
+    vp = C.c_void_p
+    lib.ceil_flat_read.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
+    lib.ceil_flat_copy.argtypes = [vp, C.c_int, vp, vp, C.c_size_t]
+    lib.ceil_flat_rmw.argtypes = [vp, C.c_int, vp, C.c_size_t]
+    lib.ceil_flat_write.argtypes = [vp, C.c_int, vp, C.c_size_t]
+    lib.ceil_form.argtypes = [vp, C.c_int, C.POINTER(vp), C.c_int, vp, vp, C.c_size_t]
+    lib.ceil_tile_read.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, vp]
+    st = torch.cuda.current_stream().cuda_stream
+    sink = torch.zeros(16, device="cuda")
+
+    def timed(fn, reps=10):
+        for i in range(3):
+            rc = fn(i)
+            if rc != 0:
+                raise RuntimeError("ceilings kernel failed: HIP error %d" % rc)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for i in range(reps):
+            fn(i)
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps
+
+    out = {}
+    n = 512 * 1024 * 1024                                   # 2 GiB of fp32
+    big = torch.randn(n, device="cuda")
+    big2 = torch.empty_like(big)
+    for grid in (2048, 4096, 8192):
+        ms = timed(lambda i: lib.ceil_flat_read(st, grid, big.data_ptr(), n, sink.data_ptr()))
+        out["flat_read_2GiB_grid%d" % grid] = n * 4 / ms / 1e6
+        ms = timed(lambda i: lib.ceil_flat_copy(st, grid, big.data_ptr(), big2.data_ptr(), n))
+        out["flat_copy_2GiB_grid%d" % grid] = 2 * n * 4 / ms / 1e6
+        ms = timed(lambda i: lib.ceil_flat_write(st, grid, big2.data_ptr(), n))
+        out["flat_write_2GiB_grid%d" % grid] = n * 4 / ms / 1e6
+        ms = timed(lambda i: lib.ceil_flat_rmw(st, grid, big2.data_ptr(), n))
+        out["flat_rmw_in_place_2GiB_grid%d" % grid] = 2 * n * 4 / ms / 1e6
+    del big, big2
+    # pass 1 of config 2 without the product: 8 fp32 arrays of 4096^2 + E -> M, three rotating sets
+    m = 4096 * 4096
+    sets = [[torch.randn(m, device="cuda") for _ in range(8)] for _ in range(3)]
+    e = torch.randn(m, device="cuda")
+    o = torch.empty(m, device="cuda")
+    for grid in (1024, 2048, 4096):
+        def f(i):
+            tab = (vp * 8)(*[t.data_ptr() for t in sets[i % 3]])
+            return lib.ceil_form(st, grid, tab, 8, e.data_ptr(), o.data_ptr(), m)
+        out["form_8xf32_plus_E_store_4096sq_grid%d" % grid] = m * 40 / timed(f, 20) / 1e6
+    del sets
+    # tile-pattern reads of 96 matrices of 4096 x 4096 fp32 (6.4 GB), two workgroups per CU
+    mats = [torch.randn(4096, 4096, device="cuda") for _ in range(96)]
+    tab = torch.tensor([x.data_ptr() for x in mats], dtype=torch.int64, device="cuda")
+    for colmode, name in ((0, "tile_read_rowmode_128rows_x_256B"), (1, "tile_read_colmode_64rows_x_512B")):
+        ms = timed(lambda i: lib.ceil_tile_read(st, colmode, tab.data_ptr(), len(mats), 4096, 4096, sink.data_ptr()), 5)
+        out[name] = len(mats) * 4096 * 4096 * 4 / ms / 1e6
+    print(json.dumps({"metric": "measured HBM ceilings of plain streaming kernels", "unit": "GB/s",
+                      "peak_nominal": HBM_PEAK_GBPS, "values": {k: round(v, 1) for k, v in out.items()}}))
 
 
 def make_workload(name, rank):
@@ -144,6 +215,9 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    if args.ceilings:
+        run_ceilings()
+        return
     import torch
     from paper_2509_11254_amd import psgd, synth
 

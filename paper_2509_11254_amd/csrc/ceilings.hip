@@ -1,0 +1,149 @@
+// Plain streaming kernels with the access patterns of the compressor's passes and no arithmetic to speak of:
+// what HBM on this machine gives such patterns.  Not part of the library (built into its own shared
+// object); `bench.py --ceilings` runs them so that the roofline fractions of the real kernels can be read
+// against measured ceilings as well as against the nominal peak.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace {
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+#define GLOBAL_AS __attribute__((address_space(1)))
+constexpr int kT = 256;
+
+struct Ptrs { const float* g[8]; };
+
+// contiguous read of n4 16-byte words
+__global__ __launch_bounds__(kT) void flat_read(const float* src, size_t n4, float* sink) {
+    const GLOBAL_AS floatx4* s = (const GLOBAL_AS floatx4*)src;
+    floatx4 a = {0, 0, 0, 0};
+    for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n4; i += (size_t)gridDim.x * kT) a += s[i];
+    if (a.x + a.y + a.z + a.w == 12345.678f) sink[0] = a.x;
+}
+
+__global__ __launch_bounds__(kT) void flat_copy(const float* src, float* dst, size_t n4) {
+    const GLOBAL_AS floatx4* s = (const GLOBAL_AS floatx4*)src;
+    GLOBAL_AS floatx4* d = (GLOBAL_AS floatx4*)dst;
+    for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n4; i += (size_t)gridDim.x * kT) d[i] = s[i];
+}
+
+// write-only stream (decompress)
+__global__ __launch_bounds__(kT) void flat_write(float* dst, size_t n4) {
+    GLOBAL_AS floatx4* d = (GLOBAL_AS floatx4*)dst;
+    const floatx4 v = {1.0f, 2.0f, 3.0f, (float)blockIdx.x};
+    for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n4; i += (size_t)gridDim.x * kT) d[i] = v;
+}
+
+// in place x <- x + 1 (the residual's read-modify-write)
+__global__ __launch_bounds__(kT) void flat_rmw(float* buf, size_t n4) {
+    GLOBAL_AS floatx4* d = (GLOBAL_AS floatx4*)buf;
+    for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n4; i += (size_t)gridDim.x * kT) d[i] = d[i] + 1.0f;
+}
+
+// out = mean of nw arrays + e, elementwise (pass 1 without the product); 4 x 16 bytes per thread and array,
+// two arrays in flight
+__global__ __launch_bounds__(kT) void form_elementwise(Ptrs p, int nw, const float* e, float* out, size_t n4) {
+    constexpr int U = 4;
+    const size_t stride = (size_t)gridDim.x * kT;
+    const float inv = 1.0f / (float)nw;
+    for (size_t base = (size_t)blockIdx.x * kT * U + threadIdx.x; base < n4; base += stride * U) {
+        floatx4 acc[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) acc[u] = floatx4{0, 0, 0, 0};
+        for (int w = 0; w < nw; w += 2) {
+            floatx4 x[2][U];
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const size_t i = base + (size_t)u * kT;
+                    x[d][u] = (i < n4 && w + d < nw) ? ((const GLOBAL_AS floatx4*)p.g[w + d])[i] : floatx4{0, 0, 0, 0};
+                }
+#pragma unroll
+            for (int d = 0; d < 2; ++d)
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] += x[d][u];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t i = base + (size_t)u * kT;
+            if (i < n4) ((GLOBAL_AS floatx4*)out)[i] = acc[u] * inv + ((const GLOBAL_AS floatx4*)e)[i];
+        }
+    }
+}
+
+// Tile-pattern read of nmat matrices (rows x cols fp32, ld = cols, both multiples of 128), next tile requested
+// before the current one is consumed, two workgroups per compute unit like the product kernels.
+// COLMODE 0: a workgroup owns 128 rows and walks 64-column chunks along them (256 bytes per row and chunk);
+// COLMODE 1: it owns 128 columns and walks 64-row chunks down them (512 bytes per row).
+template <int COLMODE>
+__global__ __launch_bounds__(kT, 2) void tile_read(const float* const* mats, int rows, int cols, float* sink) {
+    const GLOBAL_AS float* m = (const GLOBAL_AS float*)mats[blockIdx.y];
+    const int t = threadIdx.x;
+    floatx4 acc = {0, 0, 0, 0};
+    floatx4 cur[8], nxt[8];
+    if (!COLMODE) {
+        const int ob = blockIdx.x, nch = cols / 64;
+        if (ob >= rows / 128) return;
+        const GLOBAL_AS float* base = m + (size_t)(ob * 128 + (t >> 4)) * cols + 4 * (t & 15);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cur[u] = *(const GLOBAL_AS floatx4*)(base + (size_t)u * 16 * cols);
+        for (int ch = 0; ch < nch; ++ch) {
+            if (ch + 1 < nch) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) nxt[u] = *(const GLOBAL_AS floatx4*)(base + (size_t)u * 16 * cols + (ch + 1) * 64);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc += cur[u]; cur[u] = nxt[u]; }
+        }
+    } else {
+        const int ob = blockIdx.x, nch = rows / 64;
+        if (ob >= cols / 128) return;
+        const GLOBAL_AS float* base = m + (size_t)(8 * (t >> 5)) * cols + ob * 128 + 4 * (t & 31);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) cur[u] = *(const GLOBAL_AS floatx4*)(base + (size_t)u * cols);
+        for (int ch = 0; ch < nch; ++ch) {
+            if (ch + 1 < nch) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) nxt[u] = *(const GLOBAL_AS floatx4*)(base + (size_t)((ch + 1) * 64 + u) * cols);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { acc += cur[u]; cur[u] = nxt[u]; }
+        }
+    }
+    if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;
+}
+}  // namespace
+
+// All pointers are device pointers; n = number of floats (multiple of 4); returns the HIP error code.
+extern "C" int ceil_flat_read(void* stream, int grid, const void* src, size_t n, void* sink) {
+    hipLaunchKernelGGL(flat_read, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (const float*)src, n / 4, (float*)sink);
+    return (int)hipGetLastError();
+}
+extern "C" int ceil_flat_copy(void* stream, int grid, const void* src, void* dst, size_t n) {
+    hipLaunchKernelGGL(flat_copy, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (const float*)src, (float*)dst, n / 4);
+    return (int)hipGetLastError();
+}
+extern "C" int ceil_flat_write(void* stream, int grid, void* dst, size_t n) {
+    hipLaunchKernelGGL(flat_write, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (float*)dst, n / 4);
+    return (int)hipGetLastError();
+}
+extern "C" int ceil_flat_rmw(void* stream, int grid, void* buf, size_t n) {
+    hipLaunchKernelGGL(flat_rmw, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (float*)buf, n / 4);
+    return (int)hipGetLastError();
+}
+// g: host array of nw (<= 8) device pointers
+extern "C" int ceil_form(void* stream, int grid, const void* const* g, int nw, const void* e, void* out, size_t n) {
+    if (nw < 1 || nw > 8) return (int)hipErrorInvalidValue;
+    Ptrs p;
+    for (int i = 0; i < 8; ++i) p.g[i] = (const float*)g[i < nw ? i : 0];
+    hipLaunchKernelGGL(form_elementwise, dim3(grid), dim3(kT), 0, (hipStream_t)stream, p, nw, (const float*)e, (float*)out, n / 4);
+    return (int)hipGetLastError();
+}
+// mats: device array of nmat device pointers; rows, cols multiples of 128
+extern "C" int ceil_tile_read(void* stream, int colmode, const void* const* mats, int nmat, int rows, int cols, void* sink) {
+    if (rows % 128 || cols % 128 || nmat < 1) return (int)hipErrorInvalidValue;
+    const float* const* m = (const float* const*)mats;
+    if (colmode) hipLaunchKernelGGL(tile_read<1>, dim3(cols / 128, nmat), dim3(kT), 0, (hipStream_t)stream, m, rows, cols, (float*)sink);
+    else hipLaunchKernelGGL(tile_read<0>, dim3(rows / 128, nmat), dim3(kT), 0, (hipStream_t)stream, m, rows, cols, (float*)sink);
+    return (int)hipGetLastError();
+}
