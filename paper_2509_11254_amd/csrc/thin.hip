@@ -190,8 +190,22 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
         __syncthreads();
         const int jmax = upper ? min(cb + cbw, w_in) : w_in;          // below-diagonal entries of tmat are zero
         const int jpad = (jmax + 3) & ~3;
-        for (int j = ty; j < jpad; j += 4)
-            if (tx < cbw) st[j * cbw + tx] = (j < w_in && cb + tx < w_in) ? tm[(int64_t)j * w_in + cb + tx] : 0.0;
+        // block of tmat -> LDS; eight loads per thread are issued before their LDS stores so that they are
+        // in flight together (a load-store-load-store chain costs a round trip to L2 per row)
+        for (int e0 = 0; e0 < jpad * cbw; e0 += 8 * kThreads) {
+            double tv[8];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                const int e = e0 + d * kThreads + t;
+                const int j = e / cbw, c = e % cbw;             // cbw is a power of two
+                tv[d] = (e < jpad * cbw && j < w_in && cb + c < w_in) ? tm[(int64_t)j * w_in + cb + c] : 0.0;
+            }
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+                const int e = e0 + d * kThreads + t;
+                if (e < jpad * cbw) st[e] = tv[d];
+            }
+        }
         __syncthreads();
         const float* __restrict__ xa = sx + (16 * ty + li) * xs + lk;
         for (int ct = 0; ct < cbw / 16 && cb + 16 * ct < w_out; ++ct) {
