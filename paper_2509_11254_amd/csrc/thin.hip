@@ -23,11 +23,21 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restri
     extern __shared__ __align__(16) unsigned char smem[];
     float* tile = reinterpret_cast<float*>(smem);      // [64][cp + 1]
     const int tw = cp + 1;
-    for (int e = threadIdx.x; e < 64 * cp; e += kThreads) {
-        const int i = e / cp, c = e % cp;
-        float v = 0.f;
-        if (i0 + i < len && c < T.width) v = T.ptr[(int64_t)(i0 + i) * T.ld + c];
-        tile[i * tw + c] = v;
+    // eight loads per thread are issued before their LDS stores
+    const PSGD_GLOBAL float* src = as_global(T.ptr);
+    for (int e0 = 0; e0 < 64 * cp; e0 += 8 * kThreads) {
+        float v[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int e = e0 + d * kThreads + threadIdx.x;
+            const int i = e / cp, c = e % cp;
+            v[d] = (e < 64 * cp && i0 + i < len && c < T.width) ? src[(int64_t)(i0 + i) * T.ld + c] : 0.f;
+        }
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int e = e0 + d * kThreads + threadIdx.x;
+            if (e < 64 * cp) tile[(e / cp) * tw + e % cp] = v[d];
+        }
     }
     __syncthreads();
     write_packs(L.pack[side], L.planes, tile, tw, cp, i0, 64, lenP);
@@ -166,15 +176,26 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     {
         const float inv_w = 1.0f / (float)w_in;
         if (flat_x) {
-            for (int f = 4 * t; f < kGramRows2 * w_in; f += 4 * kThreads) {
-                float4 x = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (have_pre && f == 4 * t) x = xpre;
-                else if (f < n_valid_x) x = *reinterpret_cast<const float4*>(X.ptr + xbase + f);
-                int row = (int)(((float)f + 0.5f) * inv_w);
-                int c = f - row * w_in;
-                if (c < 0) { --row; c += w_in; } else if (c >= w_in) { ++row; c -= w_in; }
-                float* d = sx + row * xs + c;
-                d[0] = x.x; d[1] = x.y; d[2] = x.z; d[3] = x.w;
+            // up to eight 16-byte loads per thread in flight before the first LDS store (w_in <= 128 in one go)
+            for (int f0 = 0; f0 < kGramRows2 * w_in; f0 += 32 * kThreads) {
+                floatx4 xv[8];
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    const int f = f0 + 4 * (d * kThreads + t);
+                    xv[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+                    if (have_pre && f == 4 * t) xv[d] = floatx4{xpre.x, xpre.y, xpre.z, xpre.w};
+                    else if (f < n_valid_x) xv[d] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(as_global(X.ptr) + xbase + f);
+                }
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    const int f = f0 + 4 * (d * kThreads + t);
+                    if (f >= kGramRows2 * w_in) continue;
+                    int row = (int)(((float)f + 0.5f) * inv_w);
+                    int c = f - row * w_in;
+                    if (c < 0) { --row; c += w_in; } else if (c >= w_in) { ++row; c -= w_in; }
+                    float* dd = sx + row * xs + c;
+                    dd[0] = xv[d].x; dd[1] = xv[d].y; dd[2] = xv[d].z; dd[3] = xv[d].w;
+                }
             }
         } else {
             for (int i = ty; i < kGramRows2; i += 4) {
