@@ -443,12 +443,19 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
         const PSGD_GLOBAL float* __restrict__ sc = src + (int64_t)col * out_lenP + r4;
         float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
         int s2 = 0;
-        for (; s2 + 8 <= n_split; s2 += 8) {          // 8 independent 16-byte loads in flight
-            float4 x[8];
+        for (; s2 + 16 <= n_split; s2 += 16) {        // 16 independent 16-byte loads in flight
+            float4 x[16];
 #pragma unroll
-            for (int d = 0; d < 8; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
+            for (int d = 0; d < 16; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
 #pragma unroll
-            for (int d = 0; d < 8; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
+            for (int d = 0; d < 16; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
+        }
+        for (; s2 + 4 <= n_split; s2 += 4) {
+            float4 x[4];
+#pragma unroll
+            for (int d = 0; d < 4; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
+#pragma unroll
+            for (int d = 0; d < 4; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
         }
         for (; s2 < n_split; ++s2) {
             const float4 x = ld_f32x4(sc + s2 * plane);

@@ -245,22 +245,23 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     const int t = threadIdx.x;
     const double* __restrict__ gram = L.gram;
     if (G > 1 || NARROW) {
-        // thread (e, g): entries e of slots g, g + G, ...; eight loads in flight, those past the end
+        // thread (e, g): entries e of slots g, g + G, ...; sixteen loads in flight, those past the end
         // re-read slot g and do not count
         const int g = t / ntri, e = t - g * ntri;
         if (g < G) {
             double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
-            for (int sl = g; sl < n_slots; sl += 8 * G) {
-                double x[8];
+            for (int sl = g; sl < n_slots; sl += 16 * G) {
+                double x[16];
 #pragma unroll
-                for (int d = 0; d < 8; ++d) {
+                for (int d = 0; d < 16; ++d) {
                     const int sd = sl + d * G;
                     x[d] = gram[(int64_t)(sd < n_slots ? sd : g) * ntri + e];
                 }
 #pragma unroll
-                for (int d = 0; d < 8; ++d)
+                for (int d = 0; d < 16; ++d)
                     if (sl + d * G >= n_slots) x[d] = 0.0;
-                s0 += x[0] + x[4]; s1 += x[1] + x[5]; s2 += x[2] + x[6]; s3 += x[3] + x[7];
+#pragma unroll
+                for (int d = 0; d < 16; d += 4) { s0 += x[d]; s1 += x[d + 1]; s2 += x[d + 2]; s3 += x[d + 3]; }
             }
             (G > 1 ? ps + g * ntri : a)[e] = (s0 + s1) + (s2 + s3);
         }
