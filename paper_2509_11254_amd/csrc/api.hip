@@ -77,7 +77,6 @@ struct psgd_ctx {
     size_t off_layers = 0, off_ids = 0, off_gtab = 0, off_outs = 0, off_single_part[2] = {0, 0};
     std::vector<size_t> off_layer;   // start of each layer's private region
     size_t ws_bytes = 0;
-    size_t max_part_single[2] = {0, 0};
     // cached tables
     void* bound_ws = nullptr;
     void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs

@@ -540,8 +540,9 @@ hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int 
     slices = slices < 1 ? 1 : slices;
     int v_rows = (n + slices - 1) / slices;
     v_rows = v_rows < 8 ? 8 : v_rows;
-    while (v_rows > 1 && jacobi_lds_bytes(w, v_rows) > 150 * 1024) --v_rows;
-    if (jacobi_lds_bytes(w, v_rows) > 150 * 1024) return hipErrorInvalidValue;
+    constexpr size_t kLdsCap = 159 * 1024;     // of the 160 KB a workgroup can have
+    while (v_rows > 1 && jacobi_lds_bytes(w, v_rows) > kLdsCap) --v_rows;
+    if (jacobi_lds_bytes(w, v_rows) > kLdsCap) return hipErrorInvalidValue;
     v_rows = v_rows > n ? n : v_rows;
     const size_t lds = jacobi_lds_bytes(w, v_rows);
     dim3 grid((n + v_rows - 1) / v_rows, n_ids), block(w > 48 ? 1024 : 256);

@@ -382,3 +382,34 @@ def test_config5_full_size_refresh_known_factors():
     res2 = float(np.sum(sigma ** 2) - np.sum((sigma[:, None] * utp) ** 2))      # ||M||^2 - ||P~^T M||^2
     assert abs(res2 - float(np.sum(sigma[r:] ** 2))) <= 1e-4 * float(np.sum(sigma[r:] ** 2))
     assert comp.status(0).rank_deficient == 0
+
+
+def test_widest_block_r150():
+    """r = 150: the subspace iteration's block is 192 wide, the widest the library plans for (six MFMA column
+    blocks, the unblocked fall-back of the factorisation, the largest Rayleigh-Ritz problem), and the SSP step
+    runs at 160 packed columns."""
+    torch = torch_mod()
+    m, n, r = 1024, 640, 150
+    sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.5 * 0.97 ** np.arange(100)])
+    mat, u, v = synth.prescribed_svd_matrix(m, n, sigma, seed=31)
+    comp = psgd.Compressor([(m, n, r, psgd.PSGD_F32)], 1)
+    M = to_dev_f32(mat)
+    P = torch.empty((m, r), device="cuda")
+    Q = torch.empty((n, r), device="cuda")
+    S = torch.empty((r,), device="cuda")
+    comp.refresh(0, M, P, Q, S)
+    torch.cuda.synchronize()
+    p_gpu, q_gpu = back(P), back(Q)
+    assert np.abs(p_gpu.T @ p_gpu - np.eye(r)).max() < 2e-5
+    assert orc.sin_theta_max(u[:, :r], p_gpu) <= 1e-4
+    np.testing.assert_allclose(back(S), sigma[:r], rtol=1e-4)
+    assert orc.rel_fro(q_gpu, mat.astype(np.float64).T @ p_gpu) <= 1e-4
+    # one SSP step from the refreshed Q against the oracle
+    case = Case([(m, n)], r, 1, synth.F32)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [q_gpu.astype(np.float32)])
+    case.compress()
+    out = orc.compress_step(1, None, r, q_gpu.astype(np.float32).astype(np.float64), [mat.astype(np.float64)],
+                            [np.zeros((m, n))])
+    p2, q2, e2 = case.outputs(0)
+    assert orc.rel_fro(p2, out.comp.p_tilde) <= 1e-4 and orc.rel_fro(q2, out.comp.q) <= 1e-4
+    assert orc.rel_fro(e2, out.e_mean) <= 1e-4
