@@ -413,3 +413,28 @@ def test_widest_block_r150():
     p2, q2, e2 = case.outputs(0)
     assert orc.rel_fro(p2, out.comp.p_tilde) <= 1e-4 and orc.rel_fro(q2, out.comp.q) <= 1e-4
     assert orc.rel_fro(e2, out.e_mean) <= 1e-4
+
+
+@pytest.mark.parametrize("r", [1, 2, 3, 5, 13, 16, 20, 24, 40, 70, 100])
+def test_rank_sweep_ssp_and_refresh(r):
+    """Every width path of the thin kernels: odd and tiny ranks (the register factorisation at compiled widths
+    4, 8, 12, 16, non-vectorised thin rows), the LDS path, the blocked one with a ragged last block."""
+    m, n = 640, 384
+    sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.4 * 0.9 ** np.arange(40)])
+    mat, u, v = synth.prescribed_svd_matrix(m, n, sigma, seed=100 + r, noise_std=1e-6)
+    q0 = synth.initial_q(n, r, 77)
+    g = [mat.astype(np.float64)]
+    e = [np.zeros((m, n))]
+    for refresh in (False, True):
+        case = Case([(m, n)], r, 1, synth.F32)
+        case.upload([[mat]], [np.zeros((m, n), np.float32)], [q0])
+        case.compress(refresh=refresh)
+        out = orc.compress_step(0 if refresh else 1, 1 if refresh else None, r, q0.astype(np.float64), g, e)
+        p_gpu, q_gpu, e_gpu = case.outputs(0)
+        assert np.abs(p_gpu.T @ p_gpu - np.eye(r)).max() < 2e-5
+        assert orc.rel_fro(e_gpu, out.e_mean) <= 1e-4, (r, refresh)
+        if refresh:
+            assert orc.sin_theta_max(out.comp.p_tilde, p_gpu) <= 1e-4, (r, refresh)
+            assert orc.rel_fro(p_gpu @ q_gpu.T, out.comp.delta_hat) <= 1e-4
+        else:
+            assert orc.rel_fro(p_gpu, out.comp.p_tilde) <= 1e-4 and orc.rel_fro(q_gpu, out.comp.q) <= 1e-4, (r, refresh)
