@@ -18,6 +18,7 @@ namespace psgd {
 // status[1] is set and the pass-2 code (which exits at once otherwise) does its work.
 constexpr double kSecondPassPivot = 1e-6;
 constexpr int kCholMaxGroups = 8;
+constexpr int kCholRegWidth = 16;      // widths up to this are factorised by one wavefront in registers
 
 // slot groups that sum the partial Gram matrices side by side (all kThreads threads busy for small w)
 __host__ __device__ inline int chol_groups(int w) {
@@ -34,7 +35,7 @@ __host__ __device__ inline size_t chol_lds_doubles(int w) {
 }
 __host__ __device__ inline bool chol_blocked_inverse(int w) {
     const int wp = (w + 15) & ~15;
-    return w > 32 && (chol_lds_doubles(w) + (size_t)wp * 16) * sizeof(double) + (w + 2) * sizeof(int) <= 150 * 1024;
+    return w > kCholRegWidth && (chol_lds_doubles(w) + (size_t)wp * 16) * sizeof(double) + (w + 2) * sizeof(int) <= 150 * 1024;
 }
 // LDS bytes chol_body needs
 __host__ __device__ inline size_t chol_lds_bytes(int w) {
@@ -86,7 +87,6 @@ __device__ inline bool allow2_of(const LayerDev& L, int a2gate) {
 // inversion is needed.  g: the summed Gram matrix (packed upper triangle, LDS).  Same arithmetic and
 // outputs as the general path of chol_body.  W: compiled width (w <= W); rows and columns w .. W-1 are
 // those of an identity matrix.
-constexpr int kCholRegWidth = 16;
 template <int W>
 __device__ inline void chol_in_registers_w(const LayerDev& L, const double* g, int w, double tol2, int pass,
                                            bool allow2, double* tm, bool write_status, int* need2_out) {
