@@ -284,6 +284,12 @@ def main():
     comp.profile_enable(0)
     refresh_ms = timed(lambda i: comp.compress_refresh(sets[i % args.sets], E, Q, P), max(2, min(5, n_b)))
     dec_ms = timed(lambda i: comp.decompress(P, Q, OUT), n_b)
+    # decompress fused with the momentum-SGD update (Eq. (7c)): reads and writes m and X, 16 bytes per element
+    MOM = [torch.zeros_like(e) for e in E]
+    XW = [torch.randn_like(e) for e in E]
+    msgd_ms = timed(lambda i: comp.decompress_msgd(P, Q, MOM, XW, 0.9, 1e-3), n_b)
+    msgd_gbps = (16.0 * elems) / (msgd_ms * 1e-3) / 1e9
+    del MOM, XW
 
     # ---- roofline of the dominant kernel: the first streaming pass (reads N gradients + E, writes M)
     # (event pairs recorded inside the timed region; the SSP-only loop is the fallback when the timed
@@ -318,6 +324,8 @@ def main():
                      "bytes_per_launch": s1_bytes, "ms_per_launch": per_launch_ms},
         "breakdown": dict(kernels, ssp_step_ms=ssp_ms, refresh_step_ms=refresh_ms,
                           refresh_ms_per_layer=refresh_ms / len(wl.layers), decompress_ms=dec_ms,
+                          decompress_msgd_ms=msgd_ms, decompress_msgd_GBps=msgd_gbps,
+                          decompress_msgd_frac_of_hbm_peak=msgd_gbps / HBM_PEAK_GBPS,
                           ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
                           ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
     }

@@ -139,6 +139,13 @@ int psgd_refresh(psgd_ctx *ctx, void *workspace, void *stream, int layer, const 
 int psgd_decompress(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
                     const float *const *Q, void *const *out, int out_dtype);
 
+/* psgd_decompress_msgd -- the step after the compressor, fused with the reconstruction (Eq. (7c), last lines
+ * of Algorithm 2): m[l] <- mu m[l] + P~[l] Q[l]^T;  X[l] <- X[l] - eta m[l].  Delta_hat is never written.
+ * mom, X: n_layers fp32 buffers rows x cols (ld) in the layer's storage orientation, updated in place.
+ * Errors: INVALID_ARG (null table or entry, mu outside [0, 1), eta not a number), ALIGN, HIP. */
+int psgd_decompress_msgd(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
+                         const float *const *Q, float *const *mom, float *const *X, float mu, float eta);
+
 /* Copy the per-layer diagnostics of the last call to the host.  Synchronises `stream`. */
 int psgd_status(psgd_ctx *ctx, void *workspace, void *stream, int layer, psgd_layer_status *out);
 

@@ -16,6 +16,8 @@ hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerD
                        int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,
                         int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                       float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
                          int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
@@ -74,16 +76,18 @@ struct psgd_ctx {
     // batched splits
     int split_row_b = 1, split_col_b = 1;
     // workspace layout (byte offsets)
-    size_t off_layers = 0, off_ids = 0, off_gtab = 0, off_outs = 0, off_single_part[2] = {0, 0};
+    size_t off_layers = 0, off_ids = 0, off_gtab = 0, off_outs = 0, off_moms = 0, off_xs = 0, off_single_part[2] = {0, 0};
     std::vector<size_t> off_layer;   // start of each layer's private region
     size_t ws_bytes = 0;
     // cached tables
     void* bound_ws = nullptr;
     void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs
+    void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd
     bool tables_valid = false;
     std::vector<const void*> hG;
     std::vector<float*> hE, hQ, hP;
     std::vector<void*> hOut;
+    std::vector<float*> hMom, hX;
     std::vector<int> hIds;
     std::vector<LayerDev> hLayers;   // n_layers + 1 (last = scratch descriptor of single-layer calls)
     int last_hip = 0;
@@ -463,6 +467,8 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
     c->off_gtab = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
+    c->off_moms = take((size_t)n_layers * sizeof(void*));
+    c->off_xs = take((size_t)n_layers * sizeof(void*));
     int max_rowsP = 0, max_colsP = 0;
     for (auto& p : c->plan) { if (p.rowsP > max_rowsP) max_rowsP = p.rowsP; if (p.colsP > max_colsP) max_colsP = p.colsP; }
     c->off_single_part[0] = take((size_t)kMaxSplit * max_rowsP * c->wz * sizeof(float));
@@ -606,6 +612,34 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     L.pack(ROLE_P, cp, ROLE_Q);
     L.note(launch_outer(nb, ctx->planes, true, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
+                         float* const* mom, float* const* X, float mu, float eta) {
+    if (!ctx || !P || !Q || !mom || !X) return PSGD_E_INVALID_ARG;
+    if (!(mu >= 0.f && mu < 1.f) || !(eta == eta)) return PSGD_E_INVALID_ARG;      // Algorithm 2: 0 <= mu < 1
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t nl = (size_t)ctx->n_layers;
+    int rc = check_table(reinterpret_cast<const void* const*>(mom), nl);
+    if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(X), nl);
+    if (rc != PSGD_OK) return rc;
+    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    if (rc != PSGD_OK) return rc;
+    char* ws = reinterpret_cast<char*>(workspace);
+    const bool changed = sync_table(ctx->hMom, mom, nl) | sync_table(ctx->hX, X, nl);
+    if (changed || ctx->msgd_ws != workspace) {
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+    }
+    ctx->msgd_ws = workspace;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_P, cp, ROLE_Q);
+    L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+                       reinterpret_cast<float* const*>(ws + ctx->off_moms),
+                       reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }

@@ -3,6 +3,7 @@
 //   residual    S <- S - X_L X_W^T     E_{t+1} = M - P~ Q_t^T        (Algorithm 2, error update)
 //               (FORM: S holds E_t, not M; M = mean G + E is formed again on the way, Eq. (7a))
 //   decompress  out <- X_L X_W^T       Delta_hat = P~ Q_t^T          (Algorithm 1, return value)
+//   msgd        m <- mu m + X_L X_W^T;  X <- X - eta m               (Eq. (7c): momentum SGD on Delta_hat)
 //
 // Both thin operands arrive pre-split into two or three bf16 planes (row-major [len][cp]); the
 // product keeps the 3 (two planes) or 6 (three planes) largest plane products, accumulated in fp32 by
@@ -184,6 +185,65 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
     }
 }
 
+// Decompress fused with the momentum-SGD update of Eq. (7c): Delta_hat never goes to memory.
+//   m_t = mu m_{t-1} + P~ Q^T,   X_{t+1} = X_t - eta m_t      (both rows x cols fp32 with the layer's ld, in place)
+template <int NB, int PL>
+__global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __restrict__ layers,
+                                                           const int* __restrict__ ids, int cp,
+                                                           float* const* __restrict__ moms,
+                                                           float* const* __restrict__ xs, float mu, float eta) {
+    const int lid = ids[blockIdx.y];
+    const LayerDev& L = layers[lid];
+    const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
+    const int tile = blockIdx.x;
+    if (tile >= n_rb * n_cb) return;
+    const int cb = tile % n_cb, rb = tile / n_cb;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* b_pl = reinterpret_cast<bf16_t*>(smem);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int col = cb * RT + 4 * li;
+    const bool col_ok = col < L.cols;
+    const int64_t tile_off = (int64_t)(rb * RT) * L.ld + cb * RT;
+    PSGD_GLOBAL float* m0 = as_global(moms[lid]) + tile_off;
+    PSGD_GLOBAL float* x0 = as_global(xs[lid]) + tile_off;
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    const int row_lane = rb * RT + 32 * wv + 4 * lg;
+    // momentum and weights of the tile are requested first; the operand staging and the MFMAs hide the latency
+    floatx4 mo[16], xo[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int k = 8 * (v >> 2) + (v & 3);
+        mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        xo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (col_ok && row_lane + k < L.rows) {
+            mo[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte);
+            xo[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte);
+        }
+    }
+    floatx16 acc[4];
+    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
+    if (!col_ok) return;
+    const bool full = col + 3 < L.cols;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int k = 8 * (v >> 2) + (v & 3);
+        if (row_lane + k >= L.rows) continue;
+        const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+        const floatx4 mn = mo[v] * mu + d;
+        const floatx4 xn = xo[v] - mn * eta;
+        PSGD_GLOBAL float* pm = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte);
+        PSGD_GLOBAL float* px = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte);
+        if (full) {
+            *reinterpret_cast<PSGD_GLOBAL floatx4*>(pm) = mn;
+            *reinterpret_cast<PSGD_GLOBAL floatx4*>(px) = xn;
+        } else {
+            for (int q = 0; q < 4; ++q)
+                if (col + q < L.cols) { pm[q] = mn[q]; px[q] = xn[q]; }
+        }
+    }
+}
+
 static size_t outer_lds_bytes(int nb, int planes) { return (size_t)planes * RT * (32 * nb + 8) * sizeof(bf16_t); }
 
 template <int NB, int PL>
@@ -218,6 +278,36 @@ static hipError_t launch_outer_nb(bool decomp, bool form, const LayerDev* layers
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
     }
     return hipGetLastError();
+}
+
+template <int NB, int PL>
+static hipError_t launch_msgd_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, float* const* moms,
+                                 float* const* xs, float mu, float eta, hipStream_t st) {
+    dim3 grid(max_tiles, n_ids), block(kThreads);
+    const size_t lds = outer_lds_bytes(NB, PL);
+    auto kfn = msgd_kernel<NB, PL>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, moms, xs, mu, eta);
+    return hipGetLastError();
+}
+
+// moms, xs: device arrays of per-layer device pointers
+hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                       float* const* moms, float* const* xs, float mu, float eta, hipStream_t st) {
+    if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
+#define PSGD_CASE(N)                                                                                       \
+    case N:                                                                                                \
+        return planes == 2 ? launch_msgd_nb<N, 2>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st)   \
+                           : launch_msgd_nb<N, 3>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st);
+    switch (nb) {
+        PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
+        default: return hipErrorInvalidValue;
+    }
+#undef PSGD_CASE
 }
 
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,

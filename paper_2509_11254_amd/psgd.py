@@ -19,7 +19,7 @@ PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -
 
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_refresh",
-    "psgd_decompress", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
+    "psgd_decompress", "psgd_decompress_msgd", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_read",
 ]
@@ -78,6 +78,8 @@ def load_library() -> C.CDLL:
     lib.psgd_refresh.restype = C.c_int
     lib.psgd_decompress.argtypes = [vp, vp, vp, pp, pp, pp, C.c_int]
     lib.psgd_decompress.restype = C.c_int
+    lib.psgd_decompress_msgd.argtypes = [vp, vp, vp, pp, pp, pp, pp, C.c_float, C.c_float]
+    lib.psgd_decompress_msgd.restype = C.c_int
     lib.psgd_status.argtypes = [vp, vp, vp, C.c_int, C.POINTER(LayerStatus)]
     lib.psgd_status.restype = C.c_int
     lib.psgd_algorithmic_bytes.argtypes = [vp]
@@ -194,6 +196,14 @@ class Compressor:
         self._keep = (tp, tq, to)
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, to, int(out_dtype)))
+
+    def decompress_msgd(self, P, Q, mom, X, mu: float, eta: float, stream=None) -> None:
+        """psgd_decompress_msgd: mom[l] <- mu mom[l] + P[l] Q[l]^T, X[l] <- X[l] - eta mom[l] (in place)."""
+        tp, tq, tm, tx = _ptr_table(P), _ptr_table(Q), _ptr_table(mom), _ptr_table(X)
+        self._keep = (tp, tq, tm, tx)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_decompress_msgd(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, tm, tx,
+                                             C.c_float(mu), C.c_float(eta)))
 
     def profile_enable(self, max_records: int) -> None:
         _check(self.lib, self.ctx, self.lib.psgd_profile_enable(self.ctx, int(max_records)))

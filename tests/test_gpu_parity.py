@@ -438,3 +438,31 @@ def test_rank_sweep_ssp_and_refresh(r):
             assert orc.rel_fro(p_gpu @ q_gpu.T, out.comp.delta_hat) <= 1e-4
         else:
             assert orc.rel_fro(p_gpu, out.comp.p_tilde) <= 1e-4 and orc.rel_fro(q_gpu, out.comp.q) <= 1e-4, (r, refresh)
+
+
+# ------------------------------------------------------------------ decompress fused with the momentum update
+@pytest.mark.parametrize("rows,cols,dtype", [(640, 384, synth.F32), (200, 328, synth.F32), (1000, 264, synth.BF16)])
+def test_decompress_msgd_matches_eq_7c(rows, cols, dtype):
+    """m <- mu m + P~ Q^T, X <- X - eta m (Eq. (7c)) against the oracle's update applied to the oracle's
+    Delta_hat, over two steps so that the momentum term is exercised (normal, transposed and ragged storage)."""
+    torch = torch_mod()
+    r, mu, eta = 12, 0.9, 0.05
+    m, n = max(rows, cols), min(rows, cols)
+    rng = np.random.default_rng(17)
+    case = Case([(rows, cols)], r, 1, dtype)
+    x_ref = rng.standard_normal((rows, cols))
+    mom_ref = np.zeros((rows, cols))
+    X = [to_dev_f32(x_ref.astype(np.float32))]
+    MOM = [to_dev_f32(mom_ref.astype(np.float32))]
+    x_ref = x_ref.astype(np.float32).astype(np.float64)
+    for step in range(2):
+        p = np.linalg.qr(rng.standard_normal((m, r)))[0].astype(np.float32)
+        q = rng.standard_normal((n, r)).astype(np.float32)
+        P, Q = [to_dev_f32(p)], [to_dev_f32(q)]
+        case.comp.decompress_msgd(P, Q, MOM, X, mu, eta)
+        torch.cuda.synchronize()
+        dhat = orc.decompress(p.astype(np.float64), q.astype(np.float64))          # logical m x n
+        dhat = dhat.T if rows < cols else dhat                                     # storage orientation
+        x_ref, mom_ref = orc.msgd_update(x_ref, mom_ref, dhat, eta, mu)
+        assert orc.rel_fro(back(MOM[0], cols), mom_ref) <= 1e-5, step
+        assert orc.rel_fro(back(X[0], cols), x_ref) <= 1e-5, step
