@@ -90,7 +90,10 @@ typedef struct {
                                    over E by the first pass, 2 = formed again from G and E by every pass
                                    (E is only written by the residual; fewer bytes never, equal bytes for
                                    one bf16 worker, first pass read-only), 0 = default = 1                  */
-    int32_t reserved;
+    int32_t power_iters;        /* K of the power iteration inside psgd_compress (Eq. (8)): P~_k = QR(M Q_{k-1}),
+                                   Q_k = M^T P~_k for k = 0..K-1, then the residual with (P~_{K-1}, Q_{K-1}).
+                                   0 = default = 1, the single-step compressor of Algorithm 1; each further
+                                   step costs two more passes over M                                      */
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */

@@ -431,6 +431,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         // by more than pass 1 gains (7B-shaped set: 35.4 against 31.6 ms per step), so storing is the default.
         const int pol = c->opt.m_policy;
         if (pol < 0 || pol > 2) rc = PSGD_E_INVALID_ARG;
+        if (c->opt.power_iters < 0 || c->opt.power_iters > 64) rc = PSGD_E_INVALID_ARG;
         c->reform_m = pol == 2;
     }
     if (rc == PSGD_OK) {
@@ -533,12 +534,15 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp);
     // P = M Q_{t-1} (M formed on the way and, unless it is formed again below, stored over E);
-    // P~ = QR(P), operand copies of P~
+    // P~ = QR(P), operand copies of P~;  Q_t = M^T P~, operand copies of Q_t;  K times (Eq. (8)), K = 1 by default
     const bool re = ctx->reform_m;
-    L.keep_e = re;
-    L.prod_orth(true, true, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
-    L.prod(false, re, nb, ROLE_Q, EPI_PACK);       // Q_t = M^T P~, operand copies of Q_t
-    L.keep_e = false;
+    const int K = ctx->opt.power_iters > 0 ? ctx->opt.power_iters : 1;
+    for (int k = 0; k < K; ++k) {
+        L.keep_e = re;
+        L.prod_orth(true, k == 0 || re, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
+        L.prod(false, re, nb, ROLE_Q, EPI_PACK);
+        L.keep_e = false;
+    }
     L.residual(nb, re);                            // E <- M - P~ Q_t^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;

@@ -34,7 +34,7 @@ class LayerDesc(C.Structure):
 class Options(C.Structure):
     _fields_ = [("refresh_iters", C.c_int32), ("refresh_oversample", C.c_int32),
                 ("refresh_warm_start", C.c_int32), ("seed", C.c_uint32), ("rank_tol", C.c_float),
-                ("precision", C.c_int32), ("m_policy", C.c_int32), ("reserved", C.c_int32)]
+                ("precision", C.c_int32), ("m_policy", C.c_int32), ("power_iters", C.c_int32)]
 
 
 class LayerStatus(C.Structure):
@@ -131,7 +131,8 @@ class Compressor:
 
     def __init__(self, layers: Sequence[Sequence[int]], n_workers: int, *, refresh_iters: int = 0,
                  refresh_oversample: int = -1, refresh_warm_start: bool = True, seed: int = 0x5EED5EED,
-                 rank_tol: float = 0.0, precision: int = 0, m_policy: int = 0, device: str = "cuda:0",
+                 rank_tol: float = 0.0, precision: int = 0, m_policy: int = 0, power_iters: int = 0,
+                 device: str = "cuda:0",
                  allocate: bool = True):
         self.lib = load_library()
         self.n_layers = len(layers)
@@ -141,7 +142,7 @@ class Compressor:
             descs[i].rows, descs[i].cols, descs[i].r, descs[i].grad_dtype = int(l[0]), int(l[1]), int(l[2]), int(l[3])
             descs[i].ld = int(l[4]) if len(l) > 4 else 0
         opt = Options(int(refresh_iters), int(refresh_oversample), 1 if refresh_warm_start else 0,
-                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), 0)
+                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), int(power_iters))
         self.ctx = C.c_void_p()
         rc = self.lib.psgd_init(C.byref(self.ctx), self.n_layers, descs, self.n_workers, C.byref(opt))
         _check(self.lib, None, rc)

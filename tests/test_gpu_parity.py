@@ -466,3 +466,26 @@ def test_decompress_msgd_matches_eq_7c(rows, cols, dtype):
         x_ref, mom_ref = orc.msgd_update(x_ref, mom_ref, dhat, eta, mu)
         assert orc.rel_fro(back(MOM[0], cols), mom_ref) <= 1e-5, step
         assert orc.rel_fro(back(X[0], cols), x_ref) <= 1e-5, step
+
+
+# ------------------------------------------------------------------ K-step power iteration (Eq. (8))
+@pytest.mark.parametrize("k_steps,m_policy", [(2, 0), (3, 0), (2, 2)])
+def test_k_step_power_iteration(k_steps, m_policy):
+    """psgd_options.power_iters = K: P~_k = QR(M Q_{k-1}), Q_k = M^T P~_k, K times, then E = M - P~ Q^T."""
+    wl = synth.scaled_down(synth.config1(), 640, 384)
+    wl.r = 8
+    grads, errs, qs = _workload_inputs(wl)
+    spec = wl.layers[0]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, power_iters=k_steps, m_policy=m_policy)
+    case.upload(grads, errs, qs)
+    case.compress()
+    g, e = oracle_inputs(grads[0], errs[0], spec.rows, spec.cols, wl.n_workers)
+    mat = orc.worker_mean([gi + ei for gi, ei in zip(g, e)])
+    p_ref, q_ref = orc.power_iteration(mat, qs[0].astype(np.float64), k_steps)
+    p_gpu, q_gpu, e_gpu = case.outputs(0)
+    assert orc.rel_fro(p_gpu, p_ref) <= 1e-4 and orc.rel_fro(q_gpu, q_ref) <= 1e-4
+    assert orc.rel_fro(e_gpu, mat - p_ref @ q_ref.T) <= 1e-4
+    # more steps never capture less (the projection onto span(P~_k) is the one of a power step)
+    if k_steps > 1:
+        p1, q1 = orc.power_iteration(mat, qs[0].astype(np.float64), 1)
+        assert np.linalg.norm(e_gpu) <= np.linalg.norm(mat - p1 @ q1.T) * (1 + 1e-6)
