@@ -76,7 +76,11 @@ struct psgd_ctx {
     // batched splits
     int split_row_b = 1, split_col_b = 1;
     // workspace layout (byte offsets)
-    size_t off_layers = 0, off_ids = 0, off_gtab = 0, off_outs = 0, off_moms = 0, off_xs = 0, off_single_part[2] = {0, 0};
+    // The gradient pointer table and the layer descriptors (which point into it) exist kGSlots times: a caller
+    // that rotates between a few sets of gradient buffers finds its table already on the device.
+    static constexpr int kGSlots = 4;
+    size_t off_layers_s[kGSlots] = {}, off_gtab_s[kGSlots] = {};
+    size_t off_ids = 0, off_outs = 0, off_moms = 0, off_xs = 0, off_single_part[2] = {0, 0};
     std::vector<size_t> off_layer;   // start of each layer's private region
     size_t ws_bytes = 0;
     // cached tables
@@ -84,7 +88,9 @@ struct psgd_ctx {
     void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs
     void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd
     bool tables_valid = false;
-    std::vector<const void*> hG;
+    std::vector<const void*> hG;                       // the caller's current table
+    std::vector<const void*> hGs[kGSlots];             // what each device slot holds (empty: nothing yet)
+    int cur_slot = 0, next_victim = 0;
     std::vector<float*> hE, hQ, hP;
     std::vector<void*> hOut;
     std::vector<float*> hMom, hX;
@@ -159,7 +165,7 @@ int choose_split(int64_t base_tiles, int min_chunks) {
     return (int)s;
 }
 
-void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
+void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
     const Plan& p = c->plan[l];
     const LayerRegion R = layer_region(c, p);
     char* base = ws + c->off_layer[l];
@@ -168,7 +174,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, LayerDev* out) {
     L.gdt = p.d.grad_dtype; L.n_workers = c->n_workers; L.transposed = p.transposed; L.planes = c->planes;
     L.rowsP = p.rowsP; L.colsP = p.colsP;
     L.split_row = c->split_row_b; L.split_col = c->split_col_b;
-    L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab) + (size_t)l * c->n_workers;
+    L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab_s[slot]) + (size_t)l * c->n_workers;
     L.S = c->hE.empty() ? nullptr : c->hE[l];
     const int side_p = side_of_role(p.transposed, ROLE_P), side_q = side_of_role(p.transposed, ROLE_Q);
     L.thin[ROLE_P] = ThinRef{c->hP.empty() ? nullptr : c->hP[l], p.d.r, p.d.r};
@@ -220,10 +226,12 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
     const int nl = ctx->n_layers;
     if (fresh || desc_changed) {
         ctx->hLayers.resize(nl + 1);
-        for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, &ctx->hLayers[l]);
-        ctx->hLayers[nl] = ctx->hLayers[0];
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers, ctx->hLayers.data(), (size_t)(nl + 1) * sizeof(LayerDev),
-                                hipMemcpyHostToDevice, st));
+        for (int slot = 0; slot < psgd_ctx::kGSlots; ++slot) {
+            for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, slot, &ctx->hLayers[l]);
+            ctx->hLayers[nl] = ctx->hLayers[0];
+            PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers_s[slot], ctx->hLayers.data(),
+                                    (size_t)(nl + 1) * sizeof(LayerDev), hipMemcpyHostToDevice, st));
+        }
     }
     if (fresh) {
         std::vector<int>& ids = ctx->hIds;
@@ -234,9 +242,22 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
         ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), hipMemcpyHostToDevice, st));
     }
-    if ((fresh || g_changed) && !ctx->hG.empty())
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab, ctx->hG.data(), ctx->hG.size() * sizeof(void*),
-                                hipMemcpyHostToDevice, st));
+    if (fresh)
+        for (auto& v : ctx->hGs) v.clear();
+    if ((fresh || g_changed) && !ctx->hG.empty()) {
+        // a slot that already holds this table, else the next one in turn
+        int slot = -1;
+        for (int k = 0; k < psgd_ctx::kGSlots; ++k)
+            if (ctx->hGs[k] == ctx->hG) slot = k;
+        if (slot < 0) {
+            slot = ctx->next_victim;
+            ctx->next_victim = (ctx->next_victim + 1) % psgd_ctx::kGSlots;
+            ctx->hGs[slot] = ctx->hG;
+            PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab_s[slot], ctx->hG.data(), ctx->hG.size() * sizeof(void*),
+                                    hipMemcpyHostToDevice, st));
+        }
+        ctx->cur_slot = slot;
+    }
     if (fresh) {
         // status words of a new workspace start at zero ("iterations the next refresh needs" = unknown)
         for (int l = 0; l < nl; ++l) {
@@ -341,7 +362,7 @@ void geometry(const psgd_ctx* c, int l, int split_row, int split_col, Launcher& 
 Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     Launcher L{};
     L.ctx = ctx; L.ws = reinterpret_cast<char*>(workspace); L.st = st;
-    L.layers = reinterpret_cast<const LayerDev*>(L.ws + ctx->off_layers);
+    L.layers = reinterpret_cast<const LayerDev*>(L.ws + ctx->off_layers_s[ctx->cur_slot]);
     const int nl = ctx->n_layers;
     const int* ids = reinterpret_cast<const int*>(L.ws + ctx->off_ids);
     L.ids_all = ids; L.ids_norm = ids + nl; L.ids_tr = ids + 2 * (size_t)nl;
@@ -464,9 +485,9 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     // workspace layout
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
-    c->off_layers = take((size_t)(n_layers + 1) * sizeof(LayerDev));
+    for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_layers_s[k] = take((size_t)(n_layers + 1) * sizeof(LayerDev));
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
-    c->off_gtab = take((size_t)n_layers * n_workers * sizeof(void*));
+    for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_gtab_s[k] = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));
     c->off_xs = take((size_t)n_layers * sizeof(void*));
@@ -573,7 +594,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     const Plan& p = ctx->plan[layer];
     // scratch descriptor: this layer's private regions, the caller's M/P/Q, splits sized for one layer
     LayerDev D;
-    build_layer_dev(ctx, ws, layer, &D);
+    build_layer_dev(ctx, ws, layer, ctx->cur_slot, &D);
     D.S = const_cast<float*>(M);
     D.thin[ROLE_P].ptr = P;
     D.thin[ROLE_Q].ptr = Q;
@@ -582,11 +603,11 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     D.part[0] = reinterpret_cast<float*>(ws + ctx->off_single_part[0]);
     D.part[1] = reinterpret_cast<float*>(ws + ctx->off_single_part[1]);
     ctx->hLayers[ctx->n_layers] = D;
-    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev),
+    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers_s[ctx->cur_slot] + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev),
                             hipMemcpyHostToDevice, st));
     Launcher L{};
     L.ctx = ctx; L.ws = ws; L.st = st;
-    L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers);
+    L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers_s[ctx->cur_slot]);
     const int* ids = reinterpret_cast<const int*>(ws + ctx->off_ids) + 3 * (size_t)ctx->n_layers;
     L.ids_all = ids; L.n_all = 1;
     L.ids_norm = ids; L.n_norm = p.transposed ? 0 : 1;

@@ -489,3 +489,26 @@ def test_k_step_power_iteration(k_steps, m_policy):
     if k_steps > 1:
         p1, q1 = orc.power_iteration(mat, qs[0].astype(np.float64), 1)
         assert np.linalg.norm(e_gpu) <= np.linalg.norm(mat - p1 @ q1.T) * (1 + 1e-6)
+
+
+def test_rotating_gradient_buffers_more_than_table_slots():
+    """The library keeps the last few gradient pointer tables on the device; six distinct buffer sets visited
+    twice in turn (more sets than slots, so tables are evicted and re-uploaded) must all give their own result."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config1(), 256, 128)
+    spec = wl.layers[0]
+    sig = synth.signal_matrix(spec, wl, 0)
+    sets = [[synth.worker_gradient(spec, wl, 0, w, 100 + s, sig) for w in range(wl.n_workers)] for s in range(6)]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    dev_sets = [[to_dev_grad(g, spec.cols) for g in gs] for gs in sets]
+    q0 = synth.initial_q(spec.n, wl.r, wl.seed, 0)
+    e0 = np.zeros((spec.rows, spec.cols), np.float32)
+    for visit in range(2):
+        for s in range(6):
+            case.upload([sets[s]], [e0], [q0])
+            case.G = [dev_sets[s]]                       # a different set of device buffers every call
+            case.compress()
+            g, e = oracle_inputs(sets[s], e0, spec.rows, spec.cols, wl.n_workers)
+            out = orc.compress_step(1, None, wl.r, q0.astype(np.float64), g, e)
+            p_gpu, q_gpu, e_gpu = case.outputs(0)
+            assert orc.rel_fro(e_gpu, out.e_mean) <= 1e-4 and orc.rel_fro(q_gpu, out.comp.q) <= 1e-4, (visit, s)
