@@ -9,7 +9,7 @@ import pytest
 
 from oracle import psgd_oracle as orc
 from paper_2509_11254_amd import psgd, synth
-from gpu_harness import Case, back, logical, oracle_inputs, to_dev_f32, torch_mod
+from gpu_harness import Case, back, logical, oracle_inputs, to_dev_f32, torch_mod, to_dev_grad
 
 pytestmark = pytest.mark.gpu
 
