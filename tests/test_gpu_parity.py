@@ -512,3 +512,26 @@ def test_rotating_gradient_buffers_more_than_table_slots():
             out = orc.compress_step(1, None, wl.r, q0.astype(np.float64), g, e)
             p_gpu, q_gpu, e_gpu = case.outputs(0)
             assert orc.rel_fro(e_gpu, out.e_mean) <= 1e-4 and orc.rel_fro(q_gpu, out.comp.q) <= 1e-4, (visit, s)
+
+
+def test_refresh_as_randomized_range_finder():
+    """refresh_iters = 1 with a random start is the randomized range finder (sketch Y = M Omega, orthonormalise,
+    project, small SVD): one pass captures the range of a matrix whose rank is within the block width exactly,
+    and on a decaying spectrum it is within a small factor of the optimal rank-r error (Eq. (6))."""
+    torch = torch_mod()
+    m, n, r = 768, 512, 8
+    mat, _, _ = synth.prescribed_svd_matrix(m, n, np.linspace(3, 1, 12), seed=9)      # rank 12 <= block width 16
+    case = Case([(m, n)], r, 1, synth.F32, refresh_iters=1, refresh_warm_start=False)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 1)])
+    case.compress(refresh=True)
+    p, q, e = case.outputs(0)
+    out = orc.svd_comp([mat.astype(np.float64)], r)
+    assert orc.sin_theta_max(out.p_tilde, p) <= 1e-4               # exact: the sketch spans the whole range
+    assert orc.rel_fro(e, mat.astype(np.float64) - out.delta_hat) <= 1e-4
+    sigma = 0.85 ** np.arange(64)
+    mat, _, _ = synth.prescribed_svd_matrix(m, n, sigma, seed=10)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 1)])
+    case.compress(refresh=True)
+    _, _, e = case.outputs(0)
+    opt = float(np.sum(sigma[r:] ** 2))
+    assert opt * (1 - 1e-6) <= float(np.sum(e ** 2)) <= 1.5 * opt      # never below the optimum, close above it
