@@ -274,30 +274,53 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             }
         }
     } else {
-        // one workgroup adds up everything: keep many loads in flight (two entries x 16 slots per thread);
-        // the order of the sum is fixed
-        for (int e = t; e < ntri; e += 2 * kThreads) {
-            const bool two = e + kThreads < ntri;
-            const double* __restrict__ g0 = gram + e;
-            const double* __restrict__ g1 = gram + (two ? e + kThreads : e);
-            double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0, q0 = 0.0, q1 = 0.0, q2 = 0.0, q3 = 0.0;
-            int sl = 0;
-            for (; sl + 16 <= n_slots; sl += 16) {
-                double x[16], y[16];
+        // one workgroup adds up everything: keep many loads in flight (four entries x 16 slots per thread, as
+        // 16-byte loads where the slot stride keeps them aligned); the order of the sum is fixed
+        typedef double doublex2 __attribute__((ext_vector_type(2)));
+        const PSGD_GLOBAL double* gg = as_global(gram);
+        if ((ntri & 1) == 0) {
+            for (int e = 2 * t; e < ntri; e += 4 * kThreads) {
+                const bool two = e + 2 * kThreads < ntri;
+                const PSGD_GLOBAL double* g0 = gg + e;
+                const PSGD_GLOBAL double* g1 = gg + (two ? e + 2 * kThreads : e);
+                doublex2 p0 = {0.0, 0.0}, p1 = p0, p2 = p0, p3 = p0, q0 = p0, q1 = p0, q2 = p0, q3 = p0;
+                int sl = 0;
+                for (; sl + 16 <= n_slots; sl += 16) {
+                    doublex2 x[16], y[16];
 #pragma unroll
-                for (int d = 0; d < 16; ++d) {
-                    x[d] = g0[(int64_t)(sl + d) * ntri];
-                    y[d] = g1[(int64_t)(sl + d) * ntri];
-                }
+                    for (int d = 0; d < 16; ++d) {
+                        x[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)(sl + d) * ntri);
+                        y[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)(sl + d) * ntri);
+                    }
 #pragma unroll
-                for (int d = 0; d < 16; d += 4) {
-                    p0 += x[d]; p1 += x[d + 1]; p2 += x[d + 2]; p3 += x[d + 3];
-                    q0 += y[d]; q1 += y[d + 1]; q2 += y[d + 2]; q3 += y[d + 3];
+                    for (int d = 0; d < 16; d += 4) {
+                        p0 += x[d]; p1 += x[d + 1]; p2 += x[d + 2]; p3 += x[d + 3];
+                        q0 += y[d]; q1 += y[d + 1]; q2 += y[d + 2]; q3 += y[d + 3];
+                    }
                 }
+                for (; sl < n_slots; ++sl) {
+                    p0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)sl * ntri);
+                    q0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)sl * ntri);
+                }
+                const doublex2 ps2 = (p0 + p1) + (p2 + p3), qs2 = (q0 + q1) + (q2 + q3);
+                a[e] = ps2.x; a[e + 1] = ps2.y;
+                if (two) { a[e + 2 * kThreads] = qs2.x; a[e + 2 * kThreads + 1] = qs2.y; }
             }
-            for (; sl < n_slots; ++sl) { p0 += g0[(int64_t)sl * ntri]; q0 += g1[(int64_t)sl * ntri]; }
-            a[e] = (p0 + p1) + (p2 + p3);
-            if (two) a[e + kThreads] = (q0 + q1) + (q2 + q3);
+        } else {
+            for (int e = t; e < ntri; e += kThreads) {
+                const PSGD_GLOBAL double* g0 = gg + e;
+                double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
+                int sl = 0;
+                for (; sl + 16 <= n_slots; sl += 16) {
+                    double x[16];
+#pragma unroll
+                    for (int d = 0; d < 16; ++d) x[d] = g0[(int64_t)(sl + d) * ntri];
+#pragma unroll
+                    for (int d = 0; d < 16; d += 4) { p0 += x[d]; p1 += x[d + 1]; p2 += x[d + 2]; p3 += x[d + 3]; }
+                }
+                for (; sl < n_slots; ++sl) p0 += g0[(int64_t)sl * ntri];
+                a[e] = (p0 + p1) + (p2 + p3);
+            }
         }
     }
     __syncthreads();
