@@ -22,13 +22,15 @@ constexpr int BK = 64;          // reduction chunk
 constexpr int BT = 128;         // output rows per workgroup (4 waves x 32)
 constexpr int LDSW = BK + 8;    // LDS row stride in bf16 elements (144 bytes)
 
+template <int NT = 0>
 __device__ inline float4 ld_f32x4(const PSGD_GLOBAL float* p) {
-    const floatx4 v = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(p);
+    const floatx4 v = ld_stream<NT>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(p));
     return make_float4(v.x, v.y, v.z, v.w);
 }
 
+template <int NT = 0>
 __device__ inline float4 ld_bf16x4(const PSGD_GLOBAL bf16_t* p) {
-    const uintx2 v = *reinterpret_cast<const PSGD_GLOBAL uintx2*>(p);
+    const uintx2 v = ld_stream<NT>(reinterpret_cast<const PSGD_GLOBAL uintx2*>(p));
     float4 o;
     o.x = __uint_as_float(v.x << 16);
     o.y = __uint_as_float(v.x & 0xffff0000u);
@@ -68,7 +70,7 @@ __device__ inline bool piece_ok(const LayerDev& L, const TileAddr& a, int u) {
 }
 
 // eight pieces of a row-major matrix of T (float or bf16) with the layer's leading dimension, widened to fp32
-template <class T>
+template <int NT, class T>
 __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const TileAddr& a, float4 (&x)[8]) {
     const PSGD_GLOBAL char* b = reinterpret_cast<const PSGD_GLOBAL char*>(base + a.origin);
     const unsigned lb = a.lane * (unsigned)sizeof(T);
@@ -77,7 +79,7 @@ __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
-            if constexpr (sizeof(T) == 4) x[u] = ld_f32x4(p); else x[u] = ld_bf16x4(p);
+            if constexpr (sizeof(T) == 4) x[u] = ld_f32x4<NT>(p); else x[u] = ld_bf16x4<NT>(p);
         }
     } else {
 #pragma unroll
@@ -85,7 +87,7 @@ __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const
             x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (piece_ok(L, a, u)) {
                 const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
-                if constexpr (sizeof(T) == 4) x[u] = ld_f32x4(p); else x[u] = ld_bf16x4(p);
+                if constexpr (sizeof(T) == 4) x[u] = ld_f32x4<NT>(p); else x[u] = ld_bf16x4<NT>(p);
             }
         }
     }
@@ -93,8 +95,8 @@ __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const
 
 __device__ inline void load_g8(const LayerDev& L, int w, const TileAddr& a, float4 (&x)[8]) {
     const PSGD_GLOBAL void* gw = as_global(as_global(L.G)[w]);
-    if (L.gdt == 0) load8(L, reinterpret_cast<const PSGD_GLOBAL float*>(gw), a, x);
-    else load8(L, reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw), a, x);
+    if (L.gdt == 0) load8<NT_G>(L, reinterpret_cast<const PSGD_GLOBAL float*>(gw), a, x);
+    else load8<NT_G>(L, reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw), a, x);
 }
 
 __device__ inline void add8(float4 (&m)[8], const float4 (&x)[8]) {
@@ -108,9 +110,9 @@ template <bool FORM>
 __device__ inline void tile_prefetch(const LayerDev& L, const TileAddr& a, float4 (&p0)[8], float4 (&p1)[8]) {
     if (FORM) {
         load_g8(L, 0, a, p0);
-        load8(L, as_global(L.S), a, p1);
+        load8<NT_E_IN>(L, as_global(L.S), a, p1);
     } else {
-        load8(L, as_global(L.S), a, p0);
+        load8<NT_S_PROD>(L, as_global(L.S), a, p0);
     }
 }
 
@@ -168,7 +170,7 @@ __device__ inline void store_m8(const LayerDev& L, const TileAddr& a, const floa
     if (a.full) {
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            *reinterpret_cast<PSGD_GLOBAL floatx4*>(b + u * sb + lb) = floatx4{m[u].x, m[u].y, m[u].z, m[u].w};
+            st_stream<NT_M_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(b + u * sb + lb), floatx4{m[u].x, m[u].y, m[u].z, m[u].w});
     } else {
         const bool k1 = a.col + 1 < L.cols, k2 = a.col + 2 < L.cols, k3 = a.col + 3 < L.cols;
 #pragma unroll
@@ -176,7 +178,7 @@ __device__ inline void store_m8(const LayerDev& L, const TileAddr& a, const floa
             if (!piece_ok(L, a, u)) continue;
             PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(b + u * sb + lb);
             if (k3) {
-                *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = floatx4{m[u].x, m[u].y, m[u].z, m[u].w};
+                st_stream<NT_M_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), floatx4{m[u].x, m[u].y, m[u].z, m[u].w});
             } else {
                 p[0] = m[u].x;
                 if (k1) p[1] = m[u].y;

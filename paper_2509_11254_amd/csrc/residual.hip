@@ -73,8 +73,8 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
 // 16 bytes of worker w's gradient at element offset off, widened to fp32
 __device__ inline floatx4 load_grad4(const LayerDev& L, int w, int64_t off) {
     const PSGD_GLOBAL void* gw = as_global(as_global(L.G)[w]);
-    if (L.gdt == 0) return *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL float*>(gw) + off);
-    const uintx2 v = *reinterpret_cast<const PSGD_GLOBAL uintx2*>(reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw) + off);
+    if (L.gdt == 0) return ld_stream<NT_G>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL float*>(gw) + off));
+    const uintx2 v = ld_stream<NT_G>(reinterpret_cast<const PSGD_GLOBAL uintx2*>(reinterpret_cast<const PSGD_GLOBAL bf16_t*>(gw) + off));
     return floatx4{__uint_as_float(v.x << 16), __uint_as_float(v.x & 0xffff0000u), __uint_as_float(v.y << 16),
                    __uint_as_float(v.y & 0xffff0000u)};
 }
@@ -105,8 +105,8 @@ __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const 
         const int k = 8 * (v >> 2) + (v & 3);
         m[v] = floatx4{0.f, 0.f, 0.f, 0.f};
         if (col_ok && row_lane + k < L.rows) {
-            m[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(
-                reinterpret_cast<const PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
+            m[v] = ld_stream<NT_M_RES>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(
+                reinterpret_cast<const PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte));
             if (FORM) {
                 // same arithmetic and order as the product kernel's FORM path: (sum of workers) / N + E
                 const int64_t off = (int64_t)(rb * RT + k) * L.ld + cb * RT + (lane_byte >> 2);
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const 
         PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(
             reinterpret_cast<PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
         if (full) {
-            *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = e;
+            st_stream<NT_E_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), e);
         } else {
             p[0] = e.x;
             if (col + 1 < L.cols) p[1] = e.y;
@@ -169,7 +169,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
             if (full) {
                 bf16x4 o;
                 o[0] = (bf16_t)d[0]; o[1] = (bf16_t)d[1]; o[2] = (bf16_t)d[2]; o[3] = (bf16_t)d[3];
-                *reinterpret_cast<PSGD_GLOBAL bf16x4*>(p) = o;
+                st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL bf16x4*>(p), o);
             } else {
                 for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = (bf16_t)d[q];
             }
@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
             PSGD_GLOBAL float* p = as_global(reinterpret_cast<float*>(outs[lid])) + off;
             if (full) {
                 floatx4 o = {d[0], d[1], d[2], d[3]};
-                *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = o;
+                st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), o);
             } else {
                 for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = d[q];
             }
@@ -217,8 +217,8 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
         mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
         xo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
         if (col_ok && row_lane + k < L.rows) {
-            mo[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte);
-            xo[v] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte);
+            mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte));
+            xo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte));
         }
     }
     floatx16 acc[4];
@@ -235,8 +235,8 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
         PSGD_GLOBAL float* pm = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte);
         PSGD_GLOBAL float* px = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte);
         if (full) {
-            *reinterpret_cast<PSGD_GLOBAL floatx4*>(pm) = mn;
-            *reinterpret_cast<PSGD_GLOBAL floatx4*>(px) = xn;
+            st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(pm), mn);
+            st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(px), xn);
         } else {
             for (int q = 0; q < 4; ++q)
                 if (col + q < L.cols) { pm[q] = mn[q]; px[q] = xn[q]; }
