@@ -33,6 +33,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decompress", action="store_true")
     ap.add_argument("--rank", type=int, default=0, help="override the compression rank (sweep r = 8..64)")
+    ap.add_argument("--lazy", action="store_true",
+                    help="deferred residual (psgd_options.lazy_residual): the residual of a step is applied by the "
+                         "next step's forming pass instead of a pass of its own")
     ap.add_argument("--no-qr", action="store_true",
                     help="signal factors = scaled Gaussian columns (orthonormal up to O(sqrt(k/rows))) instead of a "
                          "QR: keeps rocsolver out of counter-collection runs")
@@ -226,7 +229,7 @@ def main():
     gd = psgd.PSGD_BF16 if wl.grad_dtype == synth.BF16 else psgd.PSGD_F32
     sg = 2 if wl.grad_dtype == synth.BF16 else 4
     layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
-    comp = psgd.Compressor(layers, wl.n_workers)
+    comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=args.lazy)
     sets, E, Q, P, OUT = device_gradients(wl, args.sets, torch, args.no_qr)
     elems = sum(s.rows * s.cols for s in wl.layers)
     grad_bytes = elems * wl.n_workers * sg
@@ -317,7 +320,7 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": dict(wl.describe(), refresh_steps_in_timed_region=n_refresh, gradient_sets=args.sets,
-                       decompress_in_step=not args.no_decompress),
+                       decompress_in_step=not args.no_decompress, deferred_residual=bool(args.lazy)),
         "roofline": {"bound": "hbm", "kernel": "prod_kernel (M = mean G + E formed, stored, P = M Q)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,

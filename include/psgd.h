@@ -94,6 +94,15 @@ typedef struct {
                                    Q_k = M^T P~_k for k = 0..K-1, then the residual with (P~_{K-1}, Q_{K-1}).
                                    0 = default = 1, the single-step compressor of Algorithm 1; each further
                                    step costs two more passes over M                                      */
+    int32_t lazy_residual;      /* 1: deferred residual.  psgd_compress does not run the pass E <- M - P~ Q^T for the
+                                   layers stored with rows >= cols; it leaves M_t in their E buffers, puts the
+                                   operand copies of P~_t and Q_t aside in the workspace, and the forming pass of
+                                   the next psgd_compress subtracts their product on the way (same arithmetic:
+                                   E_{t+1} is rounded to fp32 before it enters M_{t+1}).  P~, Q and every later
+                                   result are those of the immediate form; the E buffers hold E_{t+1} only after
+                                   psgd_flush_residual (psgd_compress_refresh settles it by itself).  Saves the
+                                   8 bytes per element of the residual pass.  Not with m_policy = 2; r <= 128.
+                                   0 = default: immediate residual                                        */
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */
@@ -123,6 +132,13 @@ size_t psgd_workspace_bytes(const psgd_ctx *ctx);
  * P: m x r fp32, out.  Errors: INVALID_ARG (null table or entry), ALIGN (pointer alignment), HIP. */
 int psgd_compress(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
                   float *const *E, float *const *Q, float *const *P);
+
+/* psgd_flush_residual -- with lazy_residual = 1: run the residual that the last psgd_compress left owed,
+ * E[l] <- M_t - P~_t Q_t^T from the operand copies it put aside (Algorithm 2, error update), so that the E
+ * buffers hold E_{t+1}.  Needed before the caller reads, replaces or checkpoints E, or drops the workspace.
+ * A no-op when nothing is owed (and always with lazy_residual = 0).  E: the table given to psgd_compress.
+ * Errors: INVALID_ARG (null, or a workspace other than the one the owed operands live in), ALIGN, HIP. */
+int psgd_flush_residual(psgd_ctx *ctx, void *workspace, void *stream, float *const *E);
 
 /* psgd_compress_refresh -- one SVD-Comp step for every layer (Algorithm 1 SVD-Comp + Eq. (7a) +
  * residual): as psgd_compress, but P~ spans the top-r left singular subspace of M (Definition 3)

@@ -12,10 +12,11 @@
 #include "psgd_dev.h"
 
 namespace psgd {
-hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids,
                        int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
-hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                        int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
+                        int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st);
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                        float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
 hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
@@ -72,6 +73,8 @@ struct psgd_ctx {
     int cpmax = 0;   // max(cpc, cpz)
     int planes = 2;  // bf16 planes per fp32 operand of the MFMA products (2: 3 products, 3: 6 products)
     bool reform_m = false;   // SSP step forms M = mean G + E in every pass instead of storing it over E
+    bool lazy = false;       // deferred residual: E_{t+1} = M - P~ Q^T is applied by the next forming pass
+    bool pending = false;    // the E buffers of the row-major layers hold M_t, their residual is still owed
     double kernel_bytes[3] = {0.0, 0.0, 0.0};   // algorithmic bytes of the three streaming kernels of one SSP step
     // batched splits
     int split_row_b = 1, split_col_b = 1;
@@ -119,7 +122,7 @@ int fail_hip(psgd_ctx* c, hipError_t e) {
     } while (0)
 
 struct LayerRegion {
-    size_t part[2], pack[2][6], z[2], gram, tmat, eval, status, end;
+    size_t part[2], pack[2][6], lz[2][3], z[2], gram, tmat, eval, status, end;
 };
 
 // byte layout of one layer's private workspace region, relative to its start
@@ -132,6 +135,9 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
+    if (c->lazy && !p.transposed)
+        for (int s = 0; s < 2; ++s)
+            for (int k = 0; k < c->planes; ++k) R.lz[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
     for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
     const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
@@ -186,6 +192,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
         for (int k = 0; k < c->planes; ++k) {
             L.pack[s].n[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k]);
             L.pack[s].t[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k + 1]);
+            L.lz[s][k] = (c->lazy && !p.transposed) ? reinterpret_cast<bf16_t*>(base + R.lz[s][k]) : nullptr;
         }
     }
     L.gram = reinterpret_cast<double*>(base + R.gram);
@@ -285,6 +292,7 @@ struct Launcher {
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
+    bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -307,8 +315,8 @@ struct Launcher {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
-        note(launch_prod(nb, ctx->planes, !p_like, form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
-        note(launch_prod(nb, ctx->planes, p_like, form, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
+        note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, false, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
@@ -341,7 +349,20 @@ struct Launcher {
     }
     void residual(int nb, bool form = false) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
-        note(launch_outer(nb, ctx->planes, false, form, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        note(launch_outer(nb, ctx->planes, false, form, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        prof_end(k);
+    }
+    // deferred residual: the transposed layers take theirs at once, the row-major ones keep their operands
+    void residual_deferred(int nb, int cp) {
+        const int k = prof_begin(PSGD_PROF_RESIDUAL);
+        note(launch_outer(nb, ctx->planes, false, false, false, layers, ids_tr, n_tr, tiles_outer, nullptr, 0, st));
+        prof_end(k);
+        note(launch_keep(layers, ids_norm, n_norm, max_lenP(), cp, st));
+    }
+    // E <- M - (kept P~)(kept Q)^T for the row-major layers: what the deferred residual still owes
+    void residual_owed(int nb) {
+        const int k = prof_begin(PSGD_PROF_RESIDUAL);
+        note(launch_outer(nb, ctx->planes, false, false, true, layers, ids_norm, n_norm, tiles_outer, nullptr, 0, st));
         prof_end(k);
     }
 };
@@ -454,6 +475,9 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         if (pol < 0 || pol > 2) rc = PSGD_E_INVALID_ARG;
         if (c->opt.power_iters < 0 || c->opt.power_iters > 64) rc = PSGD_E_INVALID_ARG;
         c->reform_m = pol == 2;
+        if (c->opt.lazy_residual != 0 && c->opt.lazy_residual != 1) rc = PSGD_E_INVALID_ARG;
+        if (c->opt.lazy_residual && c->reform_m) rc = PSGD_E_INVALID_ARG;      // the deferred residual lives in the stored M
+        c->lazy = c->opt.lazy_residual == 1;
     }
     if (rc == PSGD_OK) {
         c->rmax = rmax;
@@ -468,6 +492,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         c->cpz = (int)round_up(c->wz, 32);
         c->cpmax = c->cpz > c->cpc ? c->cpz : c->cpc;
         if (c->cpmax > kMaxWidth) rc = PSGD_E_SHAPE;
+        if (c->lazy && c->cpc > 128) rc = PSGD_E_SHAPE;
     }
     if (rc != PSGD_OK) { delete c; return rc; }
     // reduction splits of the batched launches
@@ -509,9 +534,10 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         bytes += 4.0 * 4.0 * (double)(p.d.rows + p.d.cols) * p.d.r;
         const double e = (double)p.d.rows * (double)p.d.cols, nsg = n_workers * sg;
         const double thin = 4.0 * (double)(p.d.rows + p.d.cols) * 32.0 * ((p.d.r + 31) / 32);
-        c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin;
+        const bool deferred = c->lazy && !p.transposed;
+        c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin * (deferred ? 2.0 : 1.0);
         c->kernel_bytes[1] += e * (c->reform_m ? nsg + 4.0 : 4.0) + thin;
-        c->kernel_bytes[2] += e * (c->reform_m ? nsg + 8.0 : 8.0) + thin;
+        if (!deferred) c->kernel_bytes[2] += e * (c->reform_m ? nsg + 8.0 : 8.0) + thin;
     }
     c->ws_bytes = o;
     c->algo_bytes = bytes;
@@ -551,6 +577,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
+    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp);
@@ -560,11 +587,34 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     const int K = ctx->opt.power_iters > 0 ? ctx->opt.power_iters : 1;
     for (int k = 0; k < K; ++k) {
         L.keep_e = re;
+        L.lazy_form = ctx->pending;            // E of the row-major layers is M_{t-1} - (kept P~)(kept Q)^T
         L.prod_orth(true, k == 0 || re, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
+        if (k == 0) ctx->pending = false;      // the buffers hold M_t from here on
+        L.lazy_form = false;
         L.prod(false, re, nb, ROLE_Q, EPI_PACK);
         L.keep_e = false;
     }
-    L.residual(nb, re);                            // E <- M - P~ Q_t^T
+    if (ctx->lazy) {
+        L.residual_deferred(nb, cp);               // owed: E <- M - P~ Q_t^T, applied by the next forming pass
+        ctx->pending = L.n_norm > 0;
+    } else {
+        L.residual(nb, re);                        // E <- M - P~ Q_t^T
+    }
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_flush_residual(psgd_ctx* ctx, void* workspace, void* stream, float* const* E) {
+    if (!ctx || !E) return PSGD_E_INVALID_ARG;
+    if (!ctx->pending) return PSGD_OK;
+    if (ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, nullptr, E, nullptr, nullptr);
+    if (rc != PSGD_OK) return rc;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    L.prof_mute = true;
+    L.residual_owed(ctx->cpc / 32);
+    ctx->pending = false;
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -575,7 +625,15 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
+    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;
     Launcher L = batch_launcher(ctx, workspace, st);
+    if (ctx->pending) {
+        // the subspace iteration forms M from a materialised E: settle what the deferred residual owes first
+        L.prof_mute = true;
+        L.residual_owed(ctx->cpc / 32);
+        L.prof_mute = false;
+        ctx->pending = false;
+    }
     refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc);
     L.residual(ctx->cpc / 32);
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
@@ -635,7 +693,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_P, cp, ROLE_Q);
-    L.note(launch_outer(nb, ctx->planes, true, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+    L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;

@@ -50,7 +50,14 @@ struct TileAddr {
     unsigned lane;      // element offset of this thread's piece 0 from the origin (< 2^30)
     int row0, row_step, col;
     bool full;
+    bool quad;          // pieces at rows row0 + {0,1,2,3, 16,17,18,19} (rows of two 16 x 16 MFMA accumulator
+                        // blocks) instead of row0 + u * row_step
 };
+
+// multiple of ustep that leads to piece u
+__device__ inline int piece_mul(const TileAddr& a, int u) { return a.quad ? (u & 3) + 16 * (u >> 2) : u; }
+// row of piece u relative to row0
+__device__ inline int piece_row(const TileAddr& a, int u) { return a.quad ? (u & 3) + 16 * (u >> 2) : u * a.row_step; }
 
 __device__ inline TileAddr tile_addr(const LayerDev& L, int tile_row0, int tile_col0, int tile_rows, int tile_cols,
                                      int lane_row, int row_step, int lane_col) {
@@ -62,11 +69,21 @@ __device__ inline TileAddr tile_addr(const LayerDev& L, int tile_row0, int tile_
     a.row_step = row_step;
     a.col = tile_col0 + lane_col;
     a.full = tile_row0 + tile_rows <= L.rows && tile_col0 + tile_cols <= L.cols;
+    a.quad = false;
+    return a;
+}
+
+// the layout of the pass that also applies the pending rank-r correction: piece u of a thread sits at row
+// lane_row + (u & 3) + 16 * (u >> 2); ustep then holds one row
+__device__ inline TileAddr tile_addr_quad(const LayerDev& L, int tile_row0, int tile_col0, int tile_rows, int tile_cols,
+                                          int lane_row, int lane_col) {
+    TileAddr a = tile_addr(L, tile_row0, tile_col0, tile_rows, tile_cols, lane_row, 1, lane_col);
+    a.quad = true;
     return a;
 }
 
 __device__ inline bool piece_ok(const LayerDev& L, const TileAddr& a, int u) {
-    return a.col < L.cols && a.row0 + u * a.row_step < L.rows;
+    return a.col < L.cols && a.row0 + piece_row(a, u) < L.rows;
 }
 
 // eight pieces of a row-major matrix of T (float or bf16) with the layer's leading dimension, widened to fp32
@@ -78,7 +95,7 @@ __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const
     if (a.full) {
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
+            const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + piece_mul(a, u) * sb + lb);
             if constexpr (sizeof(T) == 4) x[u] = ld_f32x4<NT>(p); else x[u] = ld_bf16x4<NT>(p);
         }
     } else {
@@ -86,7 +103,7 @@ __device__ inline void load8(const LayerDev& L, const PSGD_GLOBAL T* base, const
         for (int u = 0; u < 8; ++u) {
             x[u] = make_float4(0.f, 0.f, 0.f, 0.f);
             if (piece_ok(L, a, u)) {
-                const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + u * sb + lb);
+                const PSGD_GLOBAL T* p = reinterpret_cast<const PSGD_GLOBAL T*>(b + piece_mul(a, u) * sb + lb);
                 if constexpr (sizeof(T) == 4) x[u] = ld_f32x4<NT>(p); else x[u] = ld_bf16x4<NT>(p);
             }
         }
@@ -170,13 +187,13 @@ __device__ inline void store_m8(const LayerDev& L, const TileAddr& a, const floa
     if (a.full) {
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            st_stream<NT_M_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(b + u * sb + lb), floatx4{m[u].x, m[u].y, m[u].z, m[u].w});
+            st_stream<NT_M_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(b + piece_mul(a, u) * sb + lb), floatx4{m[u].x, m[u].y, m[u].z, m[u].w});
     } else {
         const bool k1 = a.col + 1 < L.cols, k2 = a.col + 2 < L.cols, k3 = a.col + 3 < L.cols;
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             if (!piece_ok(L, a, u)) continue;
-            PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(b + u * sb + lb);
+            PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(b + piece_mul(a, u) * sb + lb);
             if (k3) {
                 st_stream<NT_M_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), floatx4{m[u].x, m[u].y, m[u].z, m[u].w});
             } else {
@@ -219,8 +236,18 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 // variants run alone and may use the whole register file.
 constexpr int prod_min_blocks(int nb, int pl) { return 2 * pl * (BT + 32 * nb) * LDSW * 2 <= 160 * 1024 ? 2 : 1; }
 
-template <int NB, int PL, bool COLMODE, bool FORM>
-__global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel(const LayerDev* __restrict__ layers,
+// LAZY (row mode, FORM): the buffer S holds M_{t-1} and the residual of the previous step is still owed,
+// E_t = M_{t-1} - P~_{t-1} Q_{t-1}^T (Algorithm 2, error update).  The pass applies it on the way: the rank-r
+// product for the tile comes from the kept operand copies of P~_{t-1} (this workgroup's 128 rows, in
+// registers for the whole pass) and Q_{t-1} (the chunk's 64 rows, staged in LDS) on v_mfma_f32_16x16x32_bf16,
+// whose accumulator layout -- lane (j, g) holds rows 4g..4g+3 of column j -- with block q bound to matrix
+// columns 4j + q gives every lane 4 consecutive columns of 8 rows: the layout the tile is loaded in.
+template <int NB, int PL> constexpr int prod_lds_elems(bool lazy) {
+    return PL * (BT + 32 * NB) * LDSW + (lazy ? PL * BK * (32 * NB + 8) : 0);
+}
+
+template <int NB, int PL, bool COLMODE, bool FORM, bool LAZY = false>
+__global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 * 1024 ? 2 : 1)) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
                                                         int epi_flags, int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
@@ -251,9 +278,14 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
     const int li = lane & 31, lg = lane >> 5;
+    const int lj = lane & 15, lq = lane >> 4;     // lane coordinates of the 16 x 16 MFMA blocks (LAZY)
     const float inv_n = 1.0f / (float)L.n_workers;
     const int src_lenP = side_lenP(L, src_side);
     const PackRef XK = L.pack[src_side];
+    static_assert(!LAZY || (FORM && !COLMODE), "the pending correction is applied by the row-mode forming pass");
+    constexpr int CPW = 32 * NB + 8;                         // LDS row stride of the correction's column operand
+    constexpr int CPL = BK * CPW;                            // one plane of it
+    bf16_t* c_pl = b_pl + PL * NB * 32 * LDSW;               // PL planes of [BK][CPW] (LAZY only)
 
     floatx16 acc[NB];
 #pragma unroll
@@ -263,26 +295,108 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
 
     // thread's position in the S tile: row mode 16 x 16 threads over (row, 4 columns), 8 rows 16 apart;
     // column mode 8 x 32 threads over (8 consecutive rows, 4 columns)
-    const int c4 = COLMODE ? (t & 31) : (t & 15);
-    const int r0 = COLMODE ? (t >> 5) : (t >> 4);       // row group in column mode
+    // (LAZY: wave v owns rows 32v..32v+31 as two 16-row accumulator blocks, lane (j, g) rows 4g..4g+3 of each)
+    const int c4 = COLMODE ? (t & 31) : LAZY ? lj : (t & 15);
+    const int r0 = COLMODE ? (t >> 5) : LAZY ? 32 * wv + 4 * lq : (t >> 4);       // row group in column mode
     auto addr_of = [&](int ch) {
         const int k0 = ch * BK;
-        return COLMODE ? tile_addr(L, k0, ob * BT, BK, BT, 8 * r0, 1, 4 * c4) : tile_addr(L, ob * BT, k0, BT, BK, r0, 16, 4 * c4);
+        return COLMODE ? tile_addr(L, k0, ob * BT, BK, BT, 8 * r0, 1, 4 * c4)
+               : LAZY  ? tile_addr_quad(L, ob * BT, k0, BT, BK, r0, 4 * c4)
+                       : tile_addr(L, ob * BT, k0, BT, BK, r0, 16, 4 * c4);
     };
+    // LAZY: this wave's 32 rows of the kept P~ operand copy stay in registers for the whole pass; the chunk's 64
+    // rows of the kept Q copy are requested one chunk ahead and staged in LDS, matrix column c at LDS row
+    // (c & 3) * 16 + (c >> 2) so that the 16 lanes of an MFMA block read 16 consecutive LDS rows
+    bf16x8 ap[LAZY ? 2 : 1][LAZY ? NB : 1][PL];
+    uintx4 cq[LAZY ? NB : 1][PL];
+    auto corr_prefetch = [&](int ch) {
+#pragma unroll
+        for (int it = 0; it < NB; ++it) {
+            const int v = t + it * kThreads;          // 0 .. 64 * 4 NB - 1
+            const int c = v / (4 * NB), part = v % (4 * NB);
+            const int64_t goff = (int64_t)(ch * BK + c) * cp + 8 * part;
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                cq[it][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[SIDE_W][k]) + goff);
+        }
+    };
+    auto load_ap = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    ap[h][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
+                        as_global(L.lz[SIDE_L][k]) + (int64_t)(ob * BT + 32 * wv + 16 * h + lj) * cp + 32 * ks + 8 * lq);
+    };
+#ifndef PSGD_LAZY_AP_RELOAD
+    if (LAZY) load_ap();
+#endif
     float4 p0[8], p1[8];
-    if (ch0 < ch1) tile_prefetch<FORM>(L, addr_of(ch0), p0, p1);
+    if (ch0 < ch1) {
+        tile_prefetch<FORM>(L, addr_of(ch0), p0, p1);
+        if (LAZY) corr_prefetch(ch0);
+    }
     for (int ch = ch0; ch < ch1; ++ch) {
         const int k0 = ch * BK;
+        // ---- LAZY: the rank-r product of the previous step for this tile, in the tile's register layout;
+        // E = M_{t-1} - product is rounded to fp32 here, as the residual kernel would have stored it
+        if (LAZY) {
+#pragma unroll
+            for (int it = 0; it < NB; ++it) {
+                const int v = t + it * kThreads;
+                const int c = v / (4 * NB), part = v % (4 * NB);
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + ((c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[it][k];
+            }
+#ifdef PSGD_LAZY_AP_RELOAD
+            load_ap();
+#endif
+            __syncthreads();
+            floatx4 d[2][4];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) d[h][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x8 bv[PL];
+#pragma unroll
+                    for (int k = 0; k < PL; ++k)
+                        bv[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (16 * q + lj) * CPW + 32 * ks + 8 * lq);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                            for (int ka = 0; ka < PL; ++ka) {
+                                const int kb = sum - ka;
+                                if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                                    d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap[h][ks][ka], bv[kb], d[h][q], 0, 0, 0);
+                            }
+                }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    float4& e = p1[4 * h + v];
+                    e.x -= d[h][0][v]; e.y -= d[h][1][v]; e.z -= d[h][2][v]; e.w -= d[h][3][v];
+                }
+        }
         // ---- S tile: (prefetched) global -> registers -> (store M) -> split -> LDS
         {
             const TileAddr a = addr_of(ch);
             float4 m[8];
-            tile_finish<FORM, (NB <= 2)>(L, a, inv_n, p0, p1, m);
+            tile_finish<FORM, (NB <= 2 && !LAZY)>(L, a, inv_n, p0, p1, m);
             if (store_m) store_m8(L, a, m);
             if (!COLMODE) {
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
-                    const int row = r0 + 16 * u;
+                    const int row = LAZY ? r0 + (u & 3) + 16 * (u >> 2) : r0 + 16 * u;
                     bf16x4 o[PL];
                     bf16_t q[PL];
                     split_planes<PL>(m[u].x, q);
@@ -350,7 +464,10 @@ __global__ __launch_bounds__(kThreads, prod_min_blocks(NB, PL)) void prod_kernel
         }
         __syncthreads();
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
-        if (ch + 1 < ch1) tile_prefetch<FORM>(L, addr_of(ch + 1), p0, p1);
+        if (ch + 1 < ch1) {
+            tile_prefetch<FORM>(L, addr_of(ch + 1), p0, p1);
+            if (LAZY) corr_prefetch(ch + 1);
+        }
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
 #pragma unroll
         for (int ks = 0; ks < BK / 16; ++ks) {
@@ -494,22 +611,22 @@ hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, i
     return hipGetLastError();
 }
 
-size_t prod_lds_bytes(int nb, int planes) {
-    const size_t operands = (size_t)planes * (BT * LDSW + nb * 32 * LDSW) * sizeof(bf16_t);
+size_t prod_lds_bytes(int nb, int planes, bool lazy = false) {
+    const size_t operands = (size_t)planes * (BT * LDSW + nb * 32 * LDSW + (lazy ? BK * (32 * nb + 8) : 0)) * sizeof(bf16_t);
     const size_t tile = (size_t)BT * (32 * nb + 1) * sizeof(float);
     return operands > tile ? operands : tile;
 }
 
 template <int NB, int PL>
-static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids,
+static hipError_t launch_nb(bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids, int n_ids,
                             int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
     dim3 grid(max_tiles, n_ids), block(kThreads);
-    const size_t lds = prod_lds_bytes(NB, PL);
+    const size_t lds = prod_lds_bytes(NB, PL, lazy);
     const int cp = 32 * NB;
-#define PSGD_LAUNCH(C, F)                                                                              \
+#define PSGD_LAUNCH(...)                                                                               \
     do {                                                                                               \
-        auto kfn = prod_kernel<NB, PL, C, F>;                                                          \
+        auto kfn = prod_kernel<NB, PL, __VA_ARGS__>;                                                   \
         if (lds > 48 * 1024) {                                                                         \
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),                     \
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);  \
@@ -517,19 +634,28 @@ static hipError_t launch_nb(bool colmode, bool form, const LayerDev* layers, con
         }                                                                                              \
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, out_role, epi, gate);           \
     } while (0)
-    if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
-    else         { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
+    if (lazy) {
+        // the forming pass that also applies the pending residual: row mode, compress-step widths only
+        if constexpr (NB <= 4) {
+            if (colmode || !form) return hipErrorInvalidValue;
+            PSGD_LAUNCH(false, true, true);
+        } else {
+            return hipErrorInvalidValue;
+        }
+    } else if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
+    else                { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
 #undef PSGD_LAUNCH
     return hipGetLastError();
 }
 
 // nb = width / 32 of the thin operand (1..6); planes = 2 or 3 bf16 planes per operand.
-hipError_t launch_prod(int nb, int planes, bool colmode, bool form, const LayerDev* layers, const int* ids,
+// lazy: the forming pass also applies the pending rank-r correction (row mode, form, nb <= 4).
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids,
                        int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
 #define PSGD_CASE(N)                                                                                          \
     case N:                                                                                                   \
-        return planes == 2 ? launch_nb<N, 2>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, gate, st) \
-                           : launch_nb<N, 3>(colmode, form, layers, ids, n_ids, max_tiles, out_role, epi, gate, st);
+        return planes == 2 ? launch_nb<N, 2>(colmode, form, lazy, layers, ids, n_ids, max_tiles, out_role, epi, gate, st) \
+                           : launch_nb<N, 3>(colmode, form, lazy, layers, ids, n_ids, max_tiles, out_role, epi, gate, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;

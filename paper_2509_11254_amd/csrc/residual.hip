@@ -21,7 +21,8 @@ constexpr int RT = 128;   // tile rows and columns
 template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL == 2 ? (ka + kb <= 1) : (ka + kb <= 2); }
 
 template <int NB, int PL>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
-__device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4]) {
+__device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4],
+                                  bool kept = false) {
     constexpr int CPW = 32 * NB + 8;   // LDS row stride (bf16)
     constexpr int BPL = RT * CPW;      // one plane
     const int t = threadIdx.x;
@@ -30,7 +31,11 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     const PSGD_GLOBAL bf16_t* wk[PL];
     const PSGD_GLOBAL bf16_t* lk[PL];
 #pragma unroll
-    for (int k = 0; k < PL; ++k) { wk[k] = as_global(L.pack[SIDE_W].n[k]); lk[k] = as_global(L.pack[SIDE_L].n[k]); }
+    for (int k = 0; k < PL; ++k) {
+        // kept: the operand copies put aside by the last compress step (deferred residual) instead of the current ones
+        wk[k] = as_global(kept ? L.lz[SIDE_W][k] : L.pack[SIDE_W].n[k]);
+        lk[k] = as_global(kept ? L.lz[SIDE_L][k] : L.pack[SIDE_L].n[k]);
+    }
     // stage the W-side tile: matrix column j = cb*128 + jj goes to LDS row (jj & 3) * 32 + (jj >> 2)
     for (int v = t; v < RT * NB * 4; v += kThreads) {
         const int jj = v / (NB * 4), part = v % (NB * 4);
@@ -81,7 +86,7 @@ __device__ inline floatx4 load_grad4(const LayerDev& L, int w, int64_t off) {
 
 template <int NB, int PL, bool FORM>
 __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const LayerDev* __restrict__ layers,
-                                                                       const int* __restrict__ ids, int cp) {
+                                                                       const int* __restrict__ ids, int cp, int kept) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
     const int tile = blockIdx.x;
@@ -117,7 +122,7 @@ __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const 
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -247,8 +252,8 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
 static size_t outer_lds_bytes(int nb, int planes) { return (size_t)planes * RT * (32 * nb + 8) * sizeof(bf16_t); }
 
 template <int NB, int PL>
-static hipError_t launch_outer_nb(bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                                  void* const* outs, int out_bf16, hipStream_t st) {
+static hipError_t launch_outer_nb(bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids, int n_ids,
+                                  int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
     const int cp = 32 * NB;
@@ -267,7 +272,7 @@ static hipError_t launch_outer_nb(bool decomp, bool form, const LayerDev* layers
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, kept ? 1 : 0);
     } else {
         auto kfn = residual_kernel<NB, PL, false>;
         if (lds > 48 * 1024) {
@@ -275,7 +280,7 @@ static hipError_t launch_outer_nb(bool decomp, bool form, const LayerDev* layers
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, kept ? 1 : 0);
     }
     return hipGetLastError();
 }
@@ -310,13 +315,14 @@ hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* id
 #undef PSGD_CASE
 }
 
-hipError_t launch_outer(int nb, int planes, bool decomp, bool form, const LayerDev* layers, const int* ids, int n_ids,
-                        int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
+// kept (residual only): subtract the product of the operand copies that the last compress step put aside
+hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
+                        int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
 #define PSGD_CASE(N)                                                                                              \
     case N:                                                                                                       \
-        return planes == 2 ? launch_outer_nb<N, 2>(decomp, form, layers, ids, n_ids, max_tiles, outs, out_bf16, st)     \
-                           : launch_outer_nb<N, 3>(decomp, form, layers, ids, n_ids, max_tiles, outs, out_bf16, st);
+        return planes == 2 ? launch_outer_nb<N, 2>(decomp, form, kept, layers, ids, n_ids, max_tiles, outs, out_bf16, st) \
+                           : launch_outer_nb<N, 3>(decomp, form, kept, layers, ids, n_ids, max_tiles, outs, out_bf16, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;

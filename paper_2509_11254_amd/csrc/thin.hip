@@ -59,6 +59,31 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 }
 
 // --------------------------------------------------------------------------------------------
+// keep: put the row-major operand copies of the compress step's P~ and Q aside (deferred residual): the next
+// forming pass subtracts their product on the way, whatever has happened to the current copies in between.
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void keep_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
+                                                        int cp) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int side = blockIdx.z;
+    const int64_t n16 = (int64_t)side_lenP(L, side) * cp / 8;       // 16-byte words per plane
+    for (int k = 0; k < L.planes; ++k) {
+        const PSGD_GLOBAL uintx4* src = reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.pack[side].n[k]));
+        PSGD_GLOBAL uintx4* dst = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lz[side][k]));
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads)
+            dst[i] = src[i];
+    }
+}
+
+hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    int blocks = (int)(((int64_t)max_lenP * cp / 8 + 4 * kThreads - 1) / (4 * kThreads));
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(keep_kernel, dim3(blocks, n_ids, 2), dim3(kThreads), 0, st, layers, ids, cp);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
 // chol: one workgroup per layer runs the factorisation on the partial Gram matrices that the producing
 // kernel has left (used when that kernel cannot hand over to it itself).
 // --------------------------------------------------------------------------------------------

@@ -18,7 +18,7 @@ PSGD_OK = 0
 PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -2, -3, -4, -5
 
 EXPORTS = [
-    "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_refresh",
+    "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
     "psgd_decompress", "psgd_decompress_msgd", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_read",
@@ -34,7 +34,8 @@ class LayerDesc(C.Structure):
 class Options(C.Structure):
     _fields_ = [("refresh_iters", C.c_int32), ("refresh_oversample", C.c_int32),
                 ("refresh_warm_start", C.c_int32), ("seed", C.c_uint32), ("rank_tol", C.c_float),
-                ("precision", C.c_int32), ("m_policy", C.c_int32), ("power_iters", C.c_int32)]
+                ("precision", C.c_int32), ("m_policy", C.c_int32), ("power_iters", C.c_int32),
+                ("lazy_residual", C.c_int32)]
 
 
 class LayerStatus(C.Structure):
@@ -74,6 +75,8 @@ def load_library() -> C.CDLL:
         fn = getattr(lib, name)
         fn.argtypes = [vp, vp, vp, pp, pp, pp, pp]
         fn.restype = C.c_int
+    lib.psgd_flush_residual.argtypes = [vp, vp, vp, pp]
+    lib.psgd_flush_residual.restype = C.c_int
     lib.psgd_refresh.argtypes = [vp, vp, vp, C.c_int, vp, vp, vp, vp]
     lib.psgd_refresh.restype = C.c_int
     lib.psgd_decompress.argtypes = [vp, vp, vp, pp, pp, pp, C.c_int]
@@ -132,7 +135,7 @@ class Compressor:
     def __init__(self, layers: Sequence[Sequence[int]], n_workers: int, *, refresh_iters: int = 0,
                  refresh_oversample: int = -1, refresh_warm_start: bool = True, seed: int = 0x5EED5EED,
                  rank_tol: float = 0.0, precision: int = 0, m_policy: int = 0, power_iters: int = 0,
-                 device: str = "cuda:0",
+                 lazy_residual: bool = False, device: str = "cuda:0",
                  allocate: bool = True):
         self.lib = load_library()
         self.n_layers = len(layers)
@@ -142,7 +145,8 @@ class Compressor:
             descs[i].rows, descs[i].cols, descs[i].r, descs[i].grad_dtype = int(l[0]), int(l[1]), int(l[2]), int(l[3])
             descs[i].ld = int(l[4]) if len(l) > 4 else 0
         opt = Options(int(refresh_iters), int(refresh_oversample), 1 if refresh_warm_start else 0,
-                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), int(power_iters))
+                      int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), int(power_iters),
+                      1 if lazy_residual else 0)
         self.ctx = C.c_void_p()
         rc = self.lib.psgd_init(C.byref(self.ctx), self.n_layers, descs, self.n_workers, C.byref(opt))
         _check(self.lib, None, rc)
@@ -186,6 +190,12 @@ class Compressor:
         tg, te, tq, tp = self._tables(G, E, Q, P)
         _check(self.lib, self.ctx,
                self.lib.psgd_compress_refresh(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def flush_residual(self, E, stream=None) -> None:
+        """psgd_flush_residual: settle the residual a lazy_residual compress step left owed (E[l] <- E_{t+1})."""
+        te = _ptr_table(E)
+        self._keep = (te,)
+        _check(self.lib, self.ctx, self.lib.psgd_flush_residual(self.ctx, self._ws_ptr, _stream_handle(stream), te))
 
     def refresh(self, layer: int, M, P, Q, sigma=None, stream=None) -> None:
         _check(self.lib, self.ctx,

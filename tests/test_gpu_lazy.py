@@ -1,0 +1,178 @@
+"""GPU parity of the deferred residual (psgd_options.lazy_residual = 1): free-running trajectories of
+psgd_compress against the fp64 oracle's own trajectory of Algorithm 2.
+
+With the option on, psgd_compress leaves M_t in the E buffers of the layers stored with rows >= cols and the next
+forming pass applies E_{t+1} = M_t - P~_t Q_t^T (Algorithm 2, error update) on the way; psgd_flush_residual
+materialises it.  Every step's P~ and Q, M_t as found in the E buffer before the flush, and E after it are compared.
+"""
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2509_11254_amd import psgd, synth
+from gpu_harness import Case, back, logical, to_dev_grad, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+
+
+def _layers_inputs(wl, step):
+    out = []
+    for l, spec in enumerate(wl.layers):
+        sig = synth.signal_matrix(spec, wl, l)
+        out.append([synth.worker_gradient(spec, wl, l, w, step, sig) for w in range(wl.n_workers)])
+    return out
+
+
+def _trajectory(wl, steps, lds=None, refresh_at=(), check_m=True, **opts):
+    """Free-running: the GPU keeps its own E and Q from step to step, and so does the oracle."""
+    torch = torch_mod()
+    tol = TOL[wl.grad_dtype]
+    case = Case([(s.rows, s.cols) for s in wl.layers], wl.r, wl.n_workers, wl.grad_dtype, lds=lds,
+                lazy_residual=True, **opts)
+    nl = len(wl.layers)
+    rng = np.random.default_rng([wl.seed, 4242])
+    errs0 = [(0.3 * synth.noise_sigma(s, wl) * rng.standard_normal((s.rows, s.cols))).astype(np.float32) for s in wl.layers]
+    qs0 = [synth.initial_q(s.n, wl.r, wl.seed, l) for l, s in enumerate(wl.layers)]
+    grads = _layers_inputs(wl, 0)
+    case.upload(grads, errs0, qs0)
+    # oracle state per layer: per-worker error buffers (all equal to E_0) and Q
+    e_w = [[logical(np.asarray(errs0[l], np.float64), s.rows, s.cols) for _ in range(wl.n_workers)]
+           for l, s in enumerate(wl.layers)]
+    q_or = [q.astype(np.float64) for q in qs0]
+    worst = {}
+    for t in range(steps):
+        if t > 0:
+            grads = _layers_inputs(wl, t)
+            case.G = [[to_dev_grad(g, case.lds[l]) for g in grads[l]] for l in range(nl)]
+        refresh = t in refresh_at
+        case.compress(refresh=refresh)
+        for l, spec in enumerate(wl.layers):
+            g = [logical(synth.gradient_as_f64(gw), spec.rows, spec.cols) for gw in grads[l]]
+            out = orc.compress_step(0 if refresh else 1, 1 if refresh else None, wl.r, q_or[l], g, e_w[l])
+            p_gpu, q_gpu, s_gpu = case.outputs(l)
+            s_gpu = logical(s_gpu, spec.rows, spec.cols)
+            errs = {}
+            if refresh:
+                errs["sin"] = orc.sin_theta_max(out.comp.p_tilde, p_gpu)
+                errs["dhat"] = orc.rel_fro(p_gpu @ q_gpu.T, out.comp.delta_hat)
+                assert errs["sin"] <= 1e-4, (t, l, errs)
+            else:
+                errs["P"] = orc.rel_fro(p_gpu, out.comp.p_tilde)
+                errs["Q"] = orc.rel_fro(q_gpu, out.comp.q)
+            deferred = spec.rows >= spec.cols and not refresh
+            if deferred and check_m:
+                # what the option documents: the buffer holds M_t = mean_i (G^(i) + e^(i)) until the flush
+                m_t = orc.worker_mean([gi + ei for gi, ei in zip(g, e_w[l])])
+                errs["M"] = orc.rel_fro(s_gpu, m_t)
+            elif not deferred:
+                errs["E"] = orc.rel_fro(s_gpu, out.e_mean)
+            for k, v in errs.items():
+                worst[k] = max(worst.get(k, 0.0), v)
+                if k != "sin":
+                    assert v <= tol, (t, l, spec, k, errs)
+            e_w[l], q_or[l] = out.e_next, out.comp.q
+            if refresh:
+                # Definition 3 fixes the subspace, not the signs of the Ritz vectors: the oracle carries on from
+                # the library's Q and E of this step
+                q_or[l] = q_gpu
+                e_w[l] = [s_gpu.copy() for _ in range(wl.n_workers)]
+    case.comp.flush_residual(case.E)
+    torch.cuda.synchronize()
+    for l, spec in enumerate(wl.layers):
+        e_gpu = logical(case.outputs(l)[2], spec.rows, spec.cols)
+        err = orc.rel_fro(e_gpu, orc.worker_mean(e_w[l]))
+        worst["E_flushed"] = max(worst.get("E_flushed", 0.0), err)
+        assert err <= tol, (l, spec, err)
+    return worst
+
+
+@pytest.mark.parametrize("which", ["f32_n4_ragged_r4", "bf16_n1_r64", "bf16_n4_r32", "f32_n2_r128", "f32_r40"])
+def test_deferred_residual_trajectory(which):
+    lds = None
+    if which == "f32_n4_ragged_r4":
+        wl = synth.scaled_down(synth.config1(), 333, 203)
+        lds = [208]
+    elif which == "bf16_n1_r64":
+        wl = synth.scaled_down(synth.config4(), 700, 384)
+    elif which == "bf16_n4_r32":
+        wl = synth.scaled_down(synth.config3(), 640, 256)
+    elif which == "f32_n2_r128":
+        wl = synth.scaled_down(synth.config5a(), 640, 512)
+        wl.n_workers = 2
+    else:
+        wl = synth.scaled_down(synth.config2(), 520, 328)
+        wl.r = 40
+    print(which, _trajectory(wl, 4, lds=lds))
+
+
+def test_deferred_residual_batched_with_transposed_layer():
+    """Layers stored with rows < cols take their residual at once; the others defer it: one batch holds both."""
+    wl = synth.scaled_down(synth.config3(), 256, 256)
+    wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c"),
+                 synth.LayerSpec(200, 136, "e")]
+    print(_trajectory(wl, 3))
+
+
+def test_deferred_residual_with_refresh_steps_in_between():
+    """psgd_compress_refresh settles what is owed before it forms M, and leaves nothing owed."""
+    wl = synth.scaled_down(synth.config2(), 512, 384)
+    print(_trajectory(wl, 5, refresh_at=(0, 3)))
+
+
+def test_deferred_residual_with_two_power_steps():
+    wl = synth.scaled_down(synth.config1(), 640, 384)
+    wl.r = 8
+    torch = torch_mod()
+    spec = wl.layers[0]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=True, power_iters=2)
+    e = np.zeros((spec.rows, spec.cols), np.float32)
+    q = synth.initial_q(spec.n, wl.r, wl.seed, 0)
+    e_or = np.zeros((spec.rows, spec.cols))
+    q_or = q.astype(np.float64)
+    for t in range(3):
+        grads = _layers_inputs(wl, t)
+        if t == 0:
+            case.upload(grads, [e], [q])
+        else:
+            case.G = [[to_dev_grad(g, spec.cols) for g in grads[0]]]
+        case.compress()
+        mat = orc.worker_mean([synth.gradient_as_f64(g) for g in grads[0]]) + e_or
+        p_ref, q_ref = orc.power_iteration(mat, q_or, 2)
+        p_gpu, q_gpu, _ = case.outputs(0)
+        assert orc.rel_fro(p_gpu, p_ref) <= 1e-4 and orc.rel_fro(q_gpu, q_ref) <= 1e-4, t
+        e_or, q_or = mat - p_ref @ q_ref.T, q_ref
+    case.comp.flush_residual(case.E)
+    torch.cuda.synchronize()
+    assert orc.rel_fro(case.outputs(0)[2], e_or) <= 1e-4
+
+
+def test_flush_without_anything_owed_is_a_no_op():
+    wl = synth.scaled_down(synth.config1(), 256, 128)
+    spec = wl.layers[0]
+    torch = torch_mod()
+    for lazy in (False, True):
+        case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=lazy)
+        grads = _layers_inputs(wl, 0)
+        e0 = np.zeros((spec.rows, spec.cols), np.float32)
+        case.upload(grads, [e0], [synth.initial_q(spec.n, wl.r, wl.seed, 0)])
+        case.comp.flush_residual(case.E)                 # nothing has run yet
+        case.compress()
+        case.comp.flush_residual(case.E)
+        torch.cuda.synchronize()
+        first = back(case.E[0]).copy()
+        case.comp.flush_residual(case.E)                 # settled already: must not subtract twice
+        torch.cuda.synchronize()
+        assert np.array_equal(first, back(case.E[0]))
+        g = [synth.gradient_as_f64(gw) for gw in grads[0]]
+        out = orc.compress_step(1, None, wl.r, synth.initial_q(spec.n, wl.r, wl.seed, 0).astype(np.float64), g,
+                                [e0.astype(np.float64)] * wl.n_workers)
+        assert orc.rel_fro(first, out.e_mean) <= 1e-4
+
+
+def test_lazy_option_rejects_unsupported_combinations():
+    with pytest.raises(psgd.PsgdError):
+        psgd.Compressor([(256, 128, 4, psgd.PSGD_F32)], 1, lazy_residual=True, m_policy=2, allocate=False)
+    with pytest.raises(psgd.PsgdError):
+        psgd.Compressor([(512, 512, 150, psgd.PSGD_F32)], 1, lazy_residual=True, allocate=False)
