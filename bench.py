@@ -134,9 +134,7 @@ def device_gradients(wl, n_sets, torch, no_qr=False):
     spectrum = torch.tensor(wl.spectrum, dtype=torch.float32, device="cuda")
     sets = [[] for _ in range(n_sets)]
     E, Q, P, OUT = [], [], [], []
-    sig_cache = {}
     for l, spec in enumerate(wl.layers):
-        key = (spec.rows, spec.cols)
         k = wl.signal_rank
         u = torch.randn((spec.rows, k), generator=gen, device="cuda")
         v = torch.randn((spec.cols, k), generator=gen, device="cuda")
@@ -156,9 +154,7 @@ def device_gradients(wl, n_sets, torch, no_qr=False):
         E.append(torch.zeros((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
         Q.append(torch.randn((spec.n, wl.r), generator=gen, device="cuda"))
         P.append(torch.zeros((spec.m, wl.r), dtype=torch.float32, device="cuda"))
-        if key not in sig_cache:
-            sig_cache[key] = torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda")
-        OUT.append(sig_cache[key])      # one reconstruction buffer per distinct shape (write-only output)
+        OUT.append(torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
     return sets, E, Q, P, OUT
 
 

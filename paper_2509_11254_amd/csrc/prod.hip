@@ -330,15 +330,22 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                     ap[h][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
                         as_global(L.lz[SIDE_L][k]) + (int64_t)(ob * BT + 32 * wv + 16 * h + lj) * cp + 32 * ks + 8 * lq);
     };
-#ifndef PSGD_LAZY_AP_RELOAD
     if (LAZY) load_ap();
-#endif
+    // Row mode: workgroups that run at the same time own different row blocks and would all be at the same
+    // column offset within their rows, i.e. on the same few memory channels (the row stride is a large power of
+    // two); each row block therefore starts its walk at a chunk of its own and wraps around.  Column mode needs
+    // nothing of the kind: there the workgroups running together cover whole rows.
+    const int n_loc = ch1 - ch0;
+    // (ob + ob / 8: consecutive row blocks go to different XCDs, so the blocks of one XCD differ by multiples of 8)
+    const int rot = (COLMODE || n_loc <= 0) ? 0 : (ob + (ob >> 3)) % n_loc;
+    auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
     float4 p0[8], p1[8];
-    if (ch0 < ch1) {
-        tile_prefetch<FORM>(L, addr_of(ch0), p0, p1);
-        if (LAZY) corr_prefetch(ch0);
+    if (n_loc > 0) {
+        tile_prefetch<FORM>(L, addr_of(chunk_at(0)), p0, p1);
+        if (LAZY) corr_prefetch(chunk_at(0));
     }
-    for (int ch = ch0; ch < ch1; ++ch) {
+    for (int it = 0; it < n_loc; ++it) {
+        const int ch = chunk_at(it);
         const int k0 = ch * BK;
         // ---- LAZY: the rank-r product of the previous step for this tile, in the tile's register layout;
         // E = M_{t-1} - product is rounded to fp32 here, as the residual kernel would have stored it
@@ -351,9 +358,6 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                 for (int k = 0; k < PL; ++k)
                     *reinterpret_cast<uintx4*>(c_pl + k * CPL + ((c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[it][k];
             }
-#ifdef PSGD_LAZY_AP_RELOAD
-            load_ap();
-#endif
             __syncthreads();
             floatx4 d[2][4];
 #pragma unroll
@@ -464,9 +468,9 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
         }
         __syncthreads();
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
-        if (ch + 1 < ch1) {
-            tile_prefetch<FORM>(L, addr_of(ch + 1), p0, p1);
-            if (LAZY) corr_prefetch(ch + 1);
+        if (it + 1 < n_loc) {
+            tile_prefetch<FORM>(L, addr_of(chunk_at(it + 1)), p0, p1);
+            if (LAZY) corr_prefetch(chunk_at(it + 1));
         }
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
 #pragma unroll

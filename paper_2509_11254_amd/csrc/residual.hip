@@ -20,11 +20,18 @@ constexpr int RT = 128;   // tile rows and columns
 
 template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL == 2 ? (ka + kb <= 1) : (ka + kb <= 2); }
 
-template <int NB, int PL>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
+// KGH = half the k-steps whose row operand is held in registers at a time with two planes (a quarter with three):
+// small for the kernels that also hold a tile of M or of the optimizer state, or that want more workgroups per CU
+template <int NB, int PL, int KGH = 2>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
 __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4],
                                   bool kept = false) {
     constexpr int CPW = 32 * NB + 8;   // LDS row stride (bf16)
     constexpr int BPL = RT * CPW;      // one plane
+    constexpr int KS = 2 * NB;         // k-steps of 16
+    constexpr int KG = (PL == 2 ? 2 * KGH : KGH) > 0 ? (PL == 2 ? 2 * KGH : KGH) : 1;
+    constexpr int NG = (KS + KG - 1) / KG;
+    constexpr int NI = 2 * NB;         // 16-byte pieces of the column operand per thread and plane
+    constexpr int SB = KGH < 2 ? 2 : (NI < 4 ? NI : 4);   // pieces requested together
     const int t = threadIdx.x;
     const int lane = t & 63, wv = t >> 6;
     const int li = lane & 31, lg = lane >> 5;
@@ -36,41 +43,71 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
         wk[k] = as_global(kept ? L.lz[SIDE_W][k] : L.pack[SIDE_W].n[k]);
         lk[k] = as_global(kept ? L.lz[SIDE_L][k] : L.pack[SIDE_L].n[k]);
     }
-    // stage the W-side tile: matrix column j = cb*128 + jj goes to LDS row (jj & 3) * 32 + (jj >> 2)
-    for (int v = t; v < RT * NB * 4; v += kThreads) {
-        const int jj = v / (NB * 4), part = v % (NB * 4);
-        const int lrow = (jj & 3) * 32 + (jj >> 2);
-        const int64_t goff = (int64_t)(cb * RT + jj) * cp + 8 * part;
+    // Every global round trip on the way to the first MFMA is a stretch in which this workgroup moves no
+    // matrix bytes, so the requests go out together: the first group of this wave's row operand, then the
+    // column operand of the tile in batches of SB pieces per thread.
+    const int64_t aoff = (int64_t)(rb * RT + 32 * wv + li) * cp + 8 * lg;
+    bf16x8 av[2][KG][PL];
+    auto load_rows = [&](int g, bf16x8 (&dst)[KG][PL]) {
 #pragma unroll
-        for (int k = 0; k < PL; ++k)
-            *reinterpret_cast<uintx4*>(b_pl + k * BPL + lrow * CPW + 8 * part) =
-                *reinterpret_cast<const PSGD_GLOBAL uintx4*>(wk[k] + goff);
+        for (int j = 0; j < KG; ++j)
+            if (g * KG + j < KS) {
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    dst[j][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(lk[k] + aoff + 16 * (g * KG + j));
+            }
+    };
+    load_rows(0, av[0]);
+    // stage the W-side tile: matrix column j = cb*128 + jj goes to LDS row (jj & 3) * 32 + (jj >> 2)
+#pragma unroll
+    for (int i0 = 0; i0 < NI; i0 += SB) {
+        uintx4 tmp[SB][PL];
+#pragma unroll
+        for (int i = 0; i < SB; ++i) {
+            const int v = t + (i0 + i) * kThreads;
+            const int jj = v / (NB * 4), part = v % (NB * 4);
+            const int64_t goff = (int64_t)(cb * RT + jj) * cp + 8 * part;
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                if (i0 + i < NI) tmp[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(wk[k] + goff);
+        }
+#pragma unroll
+        for (int i = 0; i < SB; ++i) {
+            const int v = t + (i0 + i) * kThreads;
+            const int jj = v / (NB * 4), part = v % (NB * 4);
+            const int lrow = (jj & 3) * 32 + (jj >> 2);
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                if (i0 + i < NI) *reinterpret_cast<uintx4*>(b_pl + k * BPL + lrow * CPW + 8 * part) = tmp[i][k];
+        }
     }
     __syncthreads();
-    const int64_t aoff = (int64_t)(rb * RT + 32 * wv + li) * cp + 8 * lg;
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 2 * NB; ++ks) {
-        bf16x8 av[PL];
+    for (int g = 0; g < NG; ++g) {
+        if (g + 1 < NG) load_rows(g + 1, av[(g + 1) & 1]);      // next group in flight during this one's MFMAs
 #pragma unroll
-        for (int k = 0; k < PL; ++k) av[k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(lk[k] + aoff + 16 * ks);
+        for (int j = 0; j < KG; ++j) {
+            const int ks = g * KG + j;
+            if (ks >= KS) continue;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int boff = (32 * q + li) * CPW + 16 * ks + 8 * lg;
-            bf16x8 bv[PL];
+            for (int q = 0; q < 4; ++q) {
+                const int boff = (32 * q + li) * CPW + 16 * ks + 8 * lg;
+                bf16x8 bv[PL];
 #pragma unroll
-            for (int k = 0; k < PL; ++k) bv[k] = *reinterpret_cast<const bf16x8*>(b_pl + k * BPL + boff);
+                for (int k = 0; k < PL; ++k) bv[k] = *reinterpret_cast<const bf16x8*>(b_pl + k * BPL + boff);
 #pragma unroll
-            for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+                for (int sum = 2 * (PL - 1); sum >= 0; --sum)
 #pragma unroll
-                for (int ka = 0; ka < PL; ++ka) {
-                    const int kb = sum - ka;
-                    if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
-                        acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bv[kb], acc[q], 0, 0, 0);
-                }
+                    for (int ka = 0; ka < PL; ++ka) {
+                        const int kb = sum - ka;
+                        if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                            acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[g & 1][j][ka], bv[kb], acc[q], 0, 0, 0);
+                    }
+            }
         }
     }
 }
@@ -85,7 +122,7 @@ __device__ inline floatx4 load_grad4(const LayerDev& L, int w, int64_t off) {
 }
 
 template <int NB, int PL, bool FORM>
-__global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* __restrict__ layers,
                                                                        const int* __restrict__ ids, int cp, int kept) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -122,7 +159,7 @@ __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const 
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -143,8 +180,10 @@ __global__ __launch_bounds__(kThreads, FORM ? 2 : 3) void residual_kernel(const 
     }
 }
 
+// Write-only: nothing but other workgroups' stores hides this one's operand round trip and MFMA phase, so as many
+// workgroups per compute unit as the operand tile in LDS allows (four at NB * PL <= 6).
 template <int NB, int PL>
-__global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_kernel(const LayerDev* __restrict__ layers,
                                                               const int* __restrict__ ids, int cp,
                                                               void* const* __restrict__ outs, int out_bf16) {
     const int lid = ids[blockIdx.y];
@@ -160,7 +199,7 @@ __global__ __launch_bounds__(kThreads) void decompress_kernel(const LayerDev* __
     const int col = cb * RT + 4 * li;
     const int row_base = rb * RT + 32 * wv + 4 * lg;
     floatx16 acc[4];
-    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL, 2>(L, rb, cb, cp, b_pl, acc);
     if (col >= L.cols) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -227,7 +266,7 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
