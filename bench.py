@@ -63,6 +63,10 @@ def run_ceilings():
     lib.ceil_flat_write.argtypes = [vp, C.c_int, vp, C.c_size_t]
     lib.ceil_form.argtypes = [vp, C.c_int, C.POINTER(vp), C.c_int, vp, vp, C.c_size_t]
     lib.ceil_tile_read.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, C.c_int, vp]
+    lib.ceil_flat_read_nt.argtypes = [vp, C.c_int, vp, C.c_size_t, vp]
+    lib.ceil_flat_rmw_nt.argtypes = [vp, C.c_int, vp, C.c_size_t]
+    lib.ceil_tile_write.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, C.c_int]
+    lib.ceil_form_tile.argtypes = [vp, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int]
     st = torch.cuda.current_stream().cuda_stream
     sink = torch.zeros(16, device="cuda")
 
@@ -93,6 +97,10 @@ def run_ceilings():
         out["flat_write_2GiB_grid%d" % grid] = n * 4 / ms / 1e6
         ms = timed(lambda i: lib.ceil_flat_rmw(st, grid, big2.data_ptr(), n))
         out["flat_rmw_in_place_2GiB_grid%d" % grid] = 2 * n * 4 / ms / 1e6
+        ms = timed(lambda i: lib.ceil_flat_read_nt(st, grid, big.data_ptr(), n, sink.data_ptr()))
+        out["flat_read_nontemporal_2GiB_grid%d" % grid] = n * 4 / ms / 1e6
+        ms = timed(lambda i: lib.ceil_flat_rmw_nt(st, grid, big2.data_ptr(), n))
+        out["flat_rmw_in_place_nontemporal_x4_2GiB_grid%d" % grid] = 2 * n * 4 / ms / 1e6
     del big, big2
     # pass 1 of config 2 without the product: 8 fp32 arrays of 4096^2 + E -> M, three rotating sets
     m = 4096 * 4096
@@ -111,6 +119,14 @@ def run_ceilings():
     for colmode, name in ((0, "tile_read_rowmode_128rows_x_256B"), (1, "tile_read_colmode_64rows_x_512B")):
         ms = timed(lambda i: lib.ceil_tile_read(st, colmode, tab.data_ptr(), len(mats), 4096, 4096, sink.data_ptr()), 5)
         out[name] = len(mats) * 4096 * 4096 * 4 / ms / 1e6
+    for pat, name in ((0, "tile_write_128x128_accumulator_layout"), (1, "tile_write_64x256_1KB_per_wave_store")):
+        ms = timed(lambda i: lib.ceil_tile_write(st, pat, tab.data_ptr(), len(mats), 4096, 4096), 5)
+        out[name] = len(mats) * 4096 * 4096 * 4 / ms / 1e6
+    gmats = [torch.randn(4096, 4096, device="cuda").bfloat16() for _ in range(48)]
+    gtab = torch.tensor([x.data_ptr() for x in gmats], dtype=torch.int64, device="cuda")
+    for rot, name in ((0, "form_tile_bf16_plus_E_in_place_rowmode_in_step"), (1, "form_tile_bf16_plus_E_in_place_rowmode_rotated")):
+        ms = timed(lambda i: lib.ceil_form_tile(st, rot, gtab.data_ptr(), tab.data_ptr(), len(gmats), 4096, 4096), 5)
+        out[name] = len(gmats) * 4096 * 4096 * 10 / ms / 1e6
     print(json.dumps({"metric": "measured HBM ceilings of plain streaming kernels", "unit": "GB/s",
                       "peak_nominal": HBM_PEAK_GBPS, "values": {k: round(v, 1) for k, v in out.items()}}))
 

@@ -112,6 +112,84 @@ __global__ __launch_bounds__(kT, 2) void tile_read(const float* const* mats, int
     }
     if (acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;
 }
+
+// ---- the same streams with the non-temporal hint (what the library's kernels use on data touched once)
+__global__ __launch_bounds__(kT) void flat_read_nt(const float* src, size_t n4, float* sink) {
+    const GLOBAL_AS floatx4* s = (const GLOBAL_AS floatx4*)src;
+    floatx4 a = {0, 0, 0, 0};
+    for (size_t i = (size_t)blockIdx.x * kT + threadIdx.x; i < n4; i += (size_t)gridDim.x * kT) a += __builtin_nontemporal_load(s + i);
+    if (a.x + a.y + a.z + a.w == 12345.678f) sink[0] = a.x;
+}
+
+// in place x <- x + 1, four 16-byte pieces per thread in flight, non-temporal loads and stores
+__global__ __launch_bounds__(kT) void flat_rmw_nt(float* buf, size_t n4) {
+    GLOBAL_AS floatx4* d = (GLOBAL_AS floatx4*)buf;
+    constexpr int U = 4;
+    const size_t stride = (size_t)gridDim.x * kT * U;
+    for (size_t b = (size_t)blockIdx.x * kT * U + threadIdx.x; b < n4; b += stride) {
+        floatx4 x[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) { const size_t i = b + (size_t)u * kT; x[u] = i < n4 ? __builtin_nontemporal_load(d + i) : floatx4{0, 0, 0, 0}; }
+#pragma unroll
+        for (int u = 0; u < U; ++u) { const size_t i = b + (size_t)u * kT; if (i < n4) __builtin_nontemporal_store(x[u] + 1.0f, d + i); }
+    }
+}
+
+// Write-only in tiles (decompress): a workgroup writes a 128 x 128 tile, consecutive workgroups consecutive column
+// blocks.  PAT 0: per store instruction a wave writes 2 rows x 512 B, rows 4 apart (the MFMA accumulator layout of the
+// outer-product kernels); PAT 1: tile 64 rows x 256 columns, per store a wave writes 1 row x 1 KB.
+template <int PAT>
+__global__ __launch_bounds__(kT) void tile_write(float* const* mats, int rows, int cols) {
+    GLOBAL_AS float* m = (GLOBAL_AS float*)mats[blockIdx.y];
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6, li = lane & 31, lg = lane >> 5;
+    const floatx4 val = {1.f, 2.f, 3.f, (float)blockIdx.x};
+    if (PAT == 1) {
+        const int n_cb = cols / 256, cb = blockIdx.x % n_cb, rb = blockIdx.x / n_cb;
+        if (rb >= rows / 64) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            *(GLOBAL_AS floatx4*)(m + (size_t)(rb * 64 + 16 * wv + v) * cols + cb * 256 + 4 * lane) = val;
+    } else {
+        const int n_cb = cols / 128, cb = blockIdx.x % n_cb, rb = blockIdx.x / n_cb;
+        if (rb >= rows / 128) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            *(GLOBAL_AS floatx4*)(m + (size_t)(rb * 128 + 32 * wv + 8 * (v >> 2) + (v & 3) + 4 * lg) * cols + cb * 128 + 4 * li) = val;
+    }
+}
+
+// Pass 1 of the one-worker bf16 case without the product: S <- widen(G) + S in place, a workgroup owns 128 rows and
+// walks 64-column chunks along them, next chunk requested before the current one is consumed.  ROT 1: every row
+// block starts its walk at a chunk of its own (ob + ob / 8) and wraps around, as the library's kernel does; ROT 0:
+// all row blocks walk in step from column 0 and meet on the same memory channels.
+typedef unsigned int uintx2 __attribute__((ext_vector_type(2)));
+template <int ROT>
+__global__ __launch_bounds__(kT, 2) void form_tile(const uint16_t* const* gs, float* const* ss, int rows, int cols) {
+    const GLOBAL_AS uint16_t* g = (const GLOBAL_AS uint16_t*)gs[blockIdx.y];
+    GLOBAL_AS float* s = (GLOBAL_AS float*)ss[blockIdx.y];
+    const int t = threadIdx.x, ob = blockIdx.x;
+    if (ob >= rows / 128) return;
+    const int nch = cols / 64, rot = ROT ? (ob + (ob >> 3)) % nch : 0;
+    const size_t base = (size_t)(ob * 128 + (t >> 4)) * cols + 4 * (t & 15);
+    floatx4 sv[8], sn[8];
+    uintx2 gv[8], gn[8];
+    auto off_of = [&](int it, int u) { int c = it + rot; if (c >= nch) c -= nch; return base + (size_t)u * 16 * cols + (size_t)c * 64; };
+#pragma unroll
+    for (int u = 0; u < 8; ++u) { sv[u] = __builtin_nontemporal_load((const GLOBAL_AS floatx4*)(s + off_of(0, u))); gv[u] = __builtin_nontemporal_load((const GLOBAL_AS uintx2*)(g + off_of(0, u))); }
+    for (int it = 0; it < nch; ++it) {
+        if (it + 1 < nch) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) { sn[u] = __builtin_nontemporal_load((const GLOBAL_AS floatx4*)(s + off_of(it + 1, u))); gn[u] = __builtin_nontemporal_load((const GLOBAL_AS uintx2*)(g + off_of(it + 1, u))); }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const floatx4 w = {__uint_as_float(gv[u].x << 16), __uint_as_float(gv[u].x & 0xffff0000u), __uint_as_float(gv[u].y << 16), __uint_as_float(gv[u].y & 0xffff0000u)};
+            *(GLOBAL_AS floatx4*)(s + off_of(it, u)) = w + sv[u];
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) { sv[u] = sn[u]; gv[u] = gn[u]; }
+    }
+}
 }  // namespace
 
 // All pointers are device pointers; n = number of floats (multiple of 4); returns the HIP error code.
@@ -145,5 +223,30 @@ extern "C" int ceil_tile_read(void* stream, int colmode, const void* const* mats
     const float* const* m = (const float* const*)mats;
     if (colmode) hipLaunchKernelGGL(tile_read<1>, dim3(cols / 128, nmat), dim3(kT), 0, (hipStream_t)stream, m, rows, cols, (float*)sink);
     else hipLaunchKernelGGL(tile_read<0>, dim3(rows / 128, nmat), dim3(kT), 0, (hipStream_t)stream, m, rows, cols, (float*)sink);
+    return (int)hipGetLastError();
+}
+extern "C" int ceil_flat_read_nt(void* stream, int grid, const void* src, size_t n, void* sink) {
+    hipLaunchKernelGGL(flat_read_nt, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (const float*)src, n / 4, (float*)sink);
+    return (int)hipGetLastError();
+}
+extern "C" int ceil_flat_rmw_nt(void* stream, int grid, void* buf, size_t n) {
+    hipLaunchKernelGGL(flat_rmw_nt, dim3(grid), dim3(kT), 0, (hipStream_t)stream, (float*)buf, n / 4);
+    return (int)hipGetLastError();
+}
+// mats: device array of nmat device pointers to rows x cols fp32 (rows multiple of 128, cols of 256)
+extern "C" int ceil_tile_write(void* stream, int pat, const void* const* mats, int nmat, int rows, int cols) {
+    if (rows % 128 || cols % 256 || nmat < 1) return (int)hipErrorInvalidValue;
+    dim3 grid((rows / 128) * (cols / 128), nmat);
+    float* const* m = (float* const*)mats;
+    if (pat) hipLaunchKernelGGL(tile_write<1>, grid, dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
+    else hipLaunchKernelGGL(tile_write<0>, grid, dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
+    return (int)hipGetLastError();
+}
+// gs, ss: device arrays of nmat device pointers (bf16 and fp32 matrices rows x cols, rows multiple of 128, cols of 64)
+extern "C" int ceil_form_tile(void* stream, int rot, const void* const* gs, const void* const* ss, int nmat, int rows, int cols) {
+    if (rows % 128 || cols % 64 || nmat < 1) return (int)hipErrorInvalidValue;
+    dim3 grid(rows / 128, nmat);
+    if (rot) hipLaunchKernelGGL(form_tile<1>, grid, dim3(kT), 0, (hipStream_t)stream, (const uint16_t* const*)gs, (float* const*)ss, rows, cols);
+    else hipLaunchKernelGGL(form_tile<0>, grid, dim3(kT), 0, (hipStream_t)stream, (const uint16_t* const*)gs, (float* const*)ss, rows, cols);
     return (int)hipGetLastError();
 }

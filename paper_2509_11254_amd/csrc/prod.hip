@@ -311,13 +311,13 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     uintx4 cq[LAZY ? NB : 1][PL];
     auto corr_prefetch = [&](int ch) {
 #pragma unroll
-        for (int it = 0; it < NB; ++it) {
-            const int v = t + it * kThreads;          // 0 .. 64 * 4 NB - 1
+        for (int i = 0; i < NB; ++i) {
+            const int v = t + i * kThreads;          // 0 .. 64 * 4 NB - 1
             const int c = v / (4 * NB), part = v % (4 * NB);
             const int64_t goff = (int64_t)(ch * BK + c) * cp + 8 * part;
 #pragma unroll
             for (int k = 0; k < PL; ++k)
-                cq[it][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[SIDE_W][k]) + goff);
+                cq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[SIDE_W][k]) + goff);
         }
     };
     auto load_ap = [&]() {
@@ -339,24 +339,53 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     // (ob + ob / 8: consecutive row blocks go to different XCDs, so the blocks of one XCD differ by multiples of 8)
     const int rot = (COLMODE || n_loc <= 0) ? 0 : (ob + (ob >> 3)) % n_loc;
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
+    // thin operand chunk: pre-split, transposed [cp][lenP]; requested one chunk ahead, before the tile's own loads
+    // (the wait counter is in issue order: waiting for the chunk then leaves the tile's loads in flight)
+    // (only where the registers allow it: the forming passes are at their limit and request it after the tile
+    // has been consumed instead)
+    constexpr bool BPRE = !FORM;
+    uintx4 bq[NB][PL];
+    auto b_prefetch = [&](int ch) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int v = t + i * kThreads;        // 0 .. 32*NB*8-1
+            const int c = v >> 3, part = v & 7;
+            const int64_t goff = (int64_t)c * src_lenP + ch * BK + 8 * part;
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                bq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
+        }
+    };
     float4 p0[8], p1[8];
     if (n_loc > 0) {
-        tile_prefetch<FORM>(L, addr_of(chunk_at(0)), p0, p1);
+        if (BPRE) b_prefetch(chunk_at(0));
         if (LAZY) corr_prefetch(chunk_at(0));
+        tile_prefetch<FORM>(L, addr_of(chunk_at(0)), p0, p1);
     }
     for (int it = 0; it < n_loc; ++it) {
         const int ch = chunk_at(it);
-        const int k0 = ch * BK;
+        // ---- thin operand chunk -> LDS [cp][LDSW] (its buffer is free: the last MFMA phase ended in a barrier)
+        auto b_to_lds = [&]() {
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int v = t + i * kThreads;
+                const int c = v >> 3, part = v & 7;
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) = bq[i][k];
+            }
+        };
+        if (BPRE) b_to_lds();
         // ---- LAZY: the rank-r product of the previous step for this tile, in the tile's register layout;
         // E = M_{t-1} - product is rounded to fp32 here, as the residual kernel would have stored it
         if (LAZY) {
 #pragma unroll
-            for (int it = 0; it < NB; ++it) {
-                const int v = t + it * kThreads;
+            for (int i = 0; i < NB; ++i) {
+                const int v = t + i * kThreads;
                 const int c = v / (4 * NB), part = v % (4 * NB);
 #pragma unroll
                 for (int k = 0; k < PL; ++k)
-                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + ((c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[it][k];
+                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + ((c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[i][k];
             }
             __syncthreads();
             floatx4 d[2][4];
@@ -443,34 +472,14 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                     for (int k = 0; k < PL; ++k)
                         *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * a_chunk<true>(4 * c4 + q, rg)) = o[q][k];
             }
-        }
-        // ---- thin operand chunk: pre-split, transposed [cp][lenP] -> LDS [cp][LDSW]; all loads are issued
-        // before the first LDS store so that they are in flight together
-        {
-            uintx4 bq[NB][PL];
-#pragma unroll
-            for (int it = 0; it < NB; ++it) {
-                const int v = t + it * kThreads;        // 0 .. 32*NB*8-1
-                const int c = v >> 3, part = v & 7;
-                const int64_t goff = (int64_t)c * src_lenP + k0 + 8 * part;
-#pragma unroll
-                for (int k = 0; k < PL; ++k)
-                    bq[it][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
-            }
-#pragma unroll
-            for (int it = 0; it < NB; ++it) {
-                const int v = t + it * kThreads;
-                const int c = v >> 3, part = v & 7;
-#pragma unroll
-                for (int k = 0; k < PL; ++k)
-                    *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) = bq[it][k];
-            }
-        }
+                }
+        if (!BPRE) { b_prefetch(ch); b_to_lds(); }
         __syncthreads();
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
         if (it + 1 < n_loc) {
-            tile_prefetch<FORM>(L, addr_of(chunk_at(it + 1)), p0, p1);
+            if (BPRE) b_prefetch(chunk_at(it + 1));
             if (LAZY) corr_prefetch(chunk_at(it + 1));
+            tile_prefetch<FORM>(L, addr_of(chunk_at(it + 1)), p0, p1);
         }
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
 #pragma unroll
