@@ -176,3 +176,12 @@ def test_lazy_option_rejects_unsupported_combinations():
         psgd.Compressor([(256, 128, 4, psgd.PSGD_F32)], 1, lazy_residual=True, m_policy=2, allocate=False)
     with pytest.raises(psgd.PsgdError):
         psgd.Compressor([(512, 512, 150, psgd.PSGD_F32)], 1, lazy_residual=True, allocate=False)
+
+
+@pytest.mark.parametrize("cfg,rows,cols", [("c4", 4096, 4096), ("c4", 11008, 4096), ("c3", 5632, 2048)])
+def test_deferred_residual_full_size_llm_shapes(cfg, rows, cols):
+    """Two free-running steps at the full size of a benchmark layer, so that the second forming pass applies the
+    first step's residual across many row blocks and rotated chunk walks, in the benchmark's launch configuration."""
+    base = synth.config3() if cfg == "c3" else synth.config4()
+    wl = synth.scaled_down(base, rows, cols)
+    print(cfg, rows, cols, _trajectory(wl, 2))
