@@ -28,7 +28,9 @@
  *     the transpose of the logical matrix and is used as is (no physical transpose).
  *     P~ is m x r and Q is n x r, both fp32, row-major, contiguous (leading dimension r).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default stream) and
- *     the call returns without waiting for it.  Nothing is read back to the host.
+ *     the call returns without waiting for it.  No result is read back to the host; the one exception is a
+ *     4-byte bookkeeping copy into pinned memory that psgd_compress_refresh enqueues behind its work (how many
+ *     subspace iterations the next refresh can need at most), which a later call looks at only if it has arrived.
  *   - Return value: PSGD_OK or a negative PSGD_E_* code.  On an argument error nothing is
  *     enqueued.  No exceptions, no aborts.
  *   - Calls that share a workspace must be stream-ordered; two calls running at the same time on

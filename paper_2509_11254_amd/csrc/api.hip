@@ -16,6 +16,7 @@ hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, c
                        int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
+hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
 hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st);
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                        float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
@@ -83,6 +84,7 @@ struct psgd_ctx {
     // that rotates between a few sets of gradient buffers finds its table already on the device.
     static constexpr int kGSlots = 4;
     size_t off_layers_s[kGSlots] = {}, off_gtab_s[kGSlots] = {};
+    size_t off_iters = 0;            // one int: most iterations any layer's next refresh will run
     size_t off_ids = 0, off_outs = 0, off_moms = 0, off_xs = 0, off_single_part[2] = {0, 0};
     std::vector<size_t> off_layer;   // start of each layer's private region
     size_t ws_bytes = 0;
@@ -101,6 +103,14 @@ struct psgd_ctx {
     std::vector<LayerDev> hLayers;   // n_layers + 1 (last = scratch descriptor of single-layer calls)
     int last_hip = 0;
     double algo_bytes = 0.0;
+    // The per-layer iteration counts of the next refresh are decided on the device.  Their maximum is copied to
+    // pinned host memory after every batched refresh (asynchronously, with an event behind it); a later refresh
+    // that finds the event complete launches only that many iterations instead of the whole budget.
+    int* h_iters = nullptr;          // pinned, one int
+    hipEvent_t iters_ev = nullptr;
+    bool iters_pending = false;      // a copy is under way
+    int iters_bound = 0;             // > 0: known bound for the next batched refresh on bound_ws
+    int iters_gen = 0, iters_gen_of_copy = 0;   // a copy made before something else changed the counts is ignored
     // optional timing of the three streaming kernels with event pairs on the caller's stream
     bool prof_on = false;
     std::vector<hipEvent_t> prof_ev;      // pairs (start, stop)
@@ -231,6 +241,11 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
     char* ws = reinterpret_cast<char*>(workspace);
     const bool fresh = !ctx->tables_valid || ctx->bound_ws != workspace;
     const int nl = ctx->n_layers;
+    if (fresh) {
+        // the iteration counts live in the workspace: a bound fetched from another one says nothing about this one
+        ctx->iters_gen++;
+        ctx->iters_bound = 0;
+    }
     if (fresh || desc_changed) {
         ctx->hLayers.resize(nl + 1);
         for (int slot = 0; slot < psgd_ctx::kGSlots; ++slot) {
@@ -399,15 +414,17 @@ double tol2_of(const psgd_ctx* c) {
 
 // Block subspace iteration + Rayleigh-Ritz for the layers of `L`: leaves P~ (Ritz vectors of the r
 // largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
-void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp) {
+void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp,
+                      int launch_iters = 0) {
     const int wz = ctx->wz, cpz = ctx->cpz, nbz = cpz / 32;
     const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
+    const int n_launch = launch_iters > 0 && launch_iters < iters ? launch_iters : iters;
     const double tol2 = tol2_of(ctx);
     L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
                              ctx->opt.seed, L.st));
     L.pack(ROLE_ZQ, cpz);
-    for (int it = 0; it < iters; ++it) {
+    for (int it = 0; it < n_launch; ++it) {
         // every layer runs its own number of iterations (decided on the device from the Ritz values of
         // its previous refresh); launches past that number find their gate closed and exit at once
         L.gate = it | (iters << 16);
@@ -512,6 +529,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_layers_s[k] = take((size_t)(n_layers + 1) * sizeof(LayerDev));
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
+    c->off_iters = take(sizeof(int));
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_gtab_s[k] = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));
@@ -634,8 +652,35 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
         L.prof_mute = false;
         ctx->pending = false;
     }
-    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc);
+    // how many iterations to launch: the bound fetched after the last refresh, if it has arrived
+    if (ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
+        ctx->iters_pending = false;
+        ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? ctx->h_iters[0] : 0;
+    }
+    const int iters_max = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
+    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc,
+                     ctx->iters_pending ? 0 : ctx->iters_bound);
     L.residual(ctx->cpc / 32);
+    // fetch the bound for the next one (pinned memory and the event are created on first use; without them
+    // every refresh simply launches the whole budget)
+    ctx->iters_bound = 0;
+    if (!ctx->h_iters) {
+        void* hp = nullptr;
+        if (hipHostMalloc(&hp, sizeof(int), hipHostMallocDefault) == hipSuccess) ctx->h_iters = static_cast<int*>(hp);
+        if (ctx->h_iters && hipEventCreateWithFlags(&ctx->iters_ev, hipEventDisableTiming) != hipSuccess) {
+            (void)hipHostFree(ctx->h_iters);
+            ctx->h_iters = nullptr;
+        }
+        (void)hipGetLastError();
+    }
+    if (ctx->h_iters && !ctx->iters_pending) {
+        int* d_it = reinterpret_cast<int*>(L.ws + ctx->off_iters);
+        L.note(launch_max_iterations(L.layers, L.ids_all, L.n_all, iters_max, d_it, st));
+        L.note(hipMemcpyAsync(ctx->h_iters, d_it, sizeof(int), hipMemcpyDeviceToHost, st));
+        L.note(hipEventRecord(ctx->iters_ev, st));
+        ctx->iters_pending = L.err == hipSuccess;
+        ctx->iters_gen_of_copy = ctx->iters_gen;
+    }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -663,6 +708,9 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     ctx->hLayers[ctx->n_layers] = D;
     PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers_s[ctx->cur_slot] + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev),
                             hipMemcpyHostToDevice, st));
+    // this call rewrites the layer's iteration count: what the host knows about the next batched refresh is void
+    ctx->iters_gen++;
+    ctx->iters_bound = 0;
     Launcher L{};
     L.ctx = ctx; L.ws = ws; L.st = st;
     L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers_s[ctx->cur_slot]);
@@ -793,6 +841,9 @@ int psgd_profile_read(psgd_ctx* ctx, double* total_ms, int* count, int n_tags) {
 
 void psgd_destroy(psgd_ctx* ctx) {
     if (!ctx) return;
+    if (ctx->iters_pending) (void)hipEventSynchronize(ctx->iters_ev);
+    if (ctx->iters_ev) (void)hipEventDestroy(ctx->iters_ev);
+    if (ctx->h_iters) (void)hipHostFree(ctx->h_iters);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     delete ctx;
 }

@@ -185,12 +185,17 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 // Y = M^T Z itself; kind 2 is open in the last executed iteration only (the second CholeskyQR pass on Z,
 // which the Rayleigh-Ritz step needs exact).
 constexpr int kBudgetIterations = 8;
-__device__ inline bool gate_open(const LayerDev& L, int gate) {
-    if (gate < 0) return true;
-    const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
+// iterations the layer's next refresh runs when at most mx are launched
+__device__ inline int refresh_iterations(const LayerDev& L, int mx) {
     int k = L.status[4];
     if (k <= 0) k = mx;
     else if (k > mx) k = mx < kBudgetIterations ? mx : kBudgetIterations;
+    return k;
+}
+__device__ inline bool gate_open(const LayerDev& L, int gate) {
+    if (gate < 0) return true;
+    const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
+    const int k = refresh_iterations(L, mx);
     if (kind == 2) return it == k - 1;
     return it < k - kind;
 }

@@ -59,6 +59,25 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 }
 
 // --------------------------------------------------------------------------------------------
+// iterations the next refresh of these layers will run, at most: the largest per-layer count.  The host fetches
+// the number asynchronously and stops launching iterations past it (they would find every gate closed).
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void max_iterations_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
+                                                            int n_ids, int mx, int* __restrict__ out) {
+    int k = 1;
+    for (int i = threadIdx.x; i < n_ids; i += 64) k = max(k, refresh_iterations(layers[ids[i]], mx));
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) k = max(k, __shfl_xor(k, off));
+    if (threadIdx.x == 0) out[0] = k;
+}
+
+hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    hipLaunchKernelGGL(max_iterations_kernel, dim3(1), dim3(64), 0, st, layers, ids, n_ids, mx, out);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
 // keep: put the row-major operand copies of the compress step's P~ and Q aside (deferred residual): the next
 // forming pass subtracts their product on the way, whatever has happened to the current copies in between.
 // --------------------------------------------------------------------------------------------
