@@ -652,19 +652,24 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
         L.prof_mute = false;
         ctx->pending = false;
     }
-    // how many iterations to launch: the bound fetched after the last refresh, if it has arrived
-    if (ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
+    // how many iterations to launch: the bound fetched after the last refresh, if it has arrived.  (None of this
+    // bookkeeping under stream capture: a captured refresh launches the whole budget and fetches nothing.)
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool capturing = hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+    (void)hipGetLastError();
+    if (!capturing && ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
         ctx->iters_pending = false;
         ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? ctx->h_iters[0] : 0;
     }
     const int iters_max = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
     refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc,
-                     ctx->iters_pending ? 0 : ctx->iters_bound);
+                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_bound);
     L.residual(ctx->cpc / 32);
     // fetch the bound for the next one (pinned memory and the event are created on first use; without them
     // every refresh simply launches the whole budget)
     ctx->iters_bound = 0;
-    if (!ctx->h_iters) {
+    if (capturing) { ctx->iters_gen++; }
+    else if (!ctx->h_iters) {
         void* hp = nullptr;
         if (hipHostMalloc(&hp, sizeof(int), hipHostMallocDefault) == hipSuccess) ctx->h_iters = static_cast<int*>(hp);
         if (ctx->h_iters && hipEventCreateWithFlags(&ctx->iters_ev, hipEventDisableTiming) != hipSuccess) {
@@ -673,7 +678,7 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
         }
         (void)hipGetLastError();
     }
-    if (ctx->h_iters && !ctx->iters_pending) {
+    if (!capturing && ctx->h_iters && !ctx->iters_pending) {
         int* d_it = reinterpret_cast<int*>(L.ws + ctx->off_iters);
         L.note(launch_max_iterations(L.layers, L.ids_all, L.n_all, iters_max, d_it, st));
         L.note(hipMemcpyAsync(ctx->h_iters, d_it, sizeof(int), hipMemcpyDeviceToHost, st));
