@@ -73,6 +73,15 @@ __device__ inline void wave_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Value of v on lane `lane`, the same lane for the whole wavefront (a constant or a uniform value): two scalar
+// lane reads instead of the LDS-routed general shuffle, whose latency would sit on the critical path of every
+// step of the in-register factorisations below.  All lanes of the wave must be active.
+__device__ inline double bcast_lane(double v, int lane) {
+    const int lo = __builtin_amdgcn_readlane(__double2loint(v), lane);
+    const int hi = __builtin_amdgcn_readlane(__double2hiint(v), lane);
+    return __hiloint2double(hi, lo);
+}
+
 // Second-pass permission carried by a launch: -1 always, -2 never, else an iteration gate (kind 2).
 __device__ inline bool allow2_of(const LayerDev& L, int a2gate) {
     if (a2gate == -1) return true;
@@ -102,32 +111,31 @@ __device__ inline void chol_in_registers_w(const LayerDev& L, const double* g, i
     int badmask = 0;
 #pragma unroll
     for (int i = 0; i < W; ++i) {
-        const double dsi = __shfl(dsc_own, i < w ? i : 0);
+        const double dsi = bcast_lane(dsc_own, i < w ? i : 0);
         if (i < w && !(dsi > 0.0)) badmask |= 1 << i;
         double x = (i == (aug ? c : j)) ? 1.0 : 0.0;
         if (!aug && i < w && j < w && i <= j) x = g[tri_idx(i, jc, w)] * dsi * dsc_own;
         a[i] = x;
     }
     double min_piv = 1.0;
+    // Written without branches (selects on the wave-uniform `dep`): with branches the compiler copies the whole
+    // register array at every merge point, which cost more than the arithmetic.  Rows k >= w are rows of the
+    // identity: pivot 1, multipliers 0, nothing changes.  A dependent column (pivot not above tol2) makes row k of
+    // R the k-th row of the identity and skips the update (multiplier 0).
 #pragma unroll
     for (int k = 0; k < W; ++k) {
-        const double piv = __shfl(a[k], k);
+        const double piv = bcast_lane(a[k], k);
         const bool dep = ((badmask >> k) & 1) || !(piv > tol2);
-        if (k < w) {
-            if (dep) {
-                badmask |= 1 << k;                            // row k of R := row k of the identity
-                if (!aug) a[k] = (j == k) ? 1.0 : 0.0;
-            } else {
-                if (piv < min_piv) min_piv = piv;
-                const double rinv = rsqrt_nr(piv);
-                a[k] *= rinv;                                 // row k <- row k / R_kk
+        badmask |= dep ? (1 << k) : 0;
+        min_piv = (!dep && piv < min_piv) ? piv : min_piv;
+        const double rinv = rsqrt_nr(dep ? 1.0 : piv);
+        const double ak = dep ? (aug ? a[k] : (j == k ? 1.0 : 0.0)) : a[k] * rinv;   // row k <- row k / R_kk
+        a[k] = ak;
+        const double mult = dep ? 0.0 : ak;
 #pragma unroll
-                for (int i = k + 1; i < W; ++i) {
-                    const double rki = __shfl(a[k], i);      // R[k][i]
-                    if (aug || j >= i) a[i] -= rki * a[k];    // row i <- row i - R[k][i] row k
-                }
-            }
-        }
+        for (int i = k + 1; i < W; ++i)
+            a[i] = __builtin_fma(-bcast_lane(ak, i), mult, a[i]);   // row i <- row i - R[k][i] row k  (on a matrix lane
+                                                                    // j < i an entry below the diagonal: never read)
     }
     // lane 16 + c: row c of tmat = D T with the dependent columns zeroed
     if (aug && j < 16 + w) {
@@ -177,25 +185,19 @@ __device__ inline void chol_block16(double* a, int w, int r0, int bw, double tol
         if (!aug && i <= j && j < bw) v = a[tri_idx(r0 + i, r0 + j, w)];
         x[i] = v;
     }
+    // (branch-free for the same reason as above; rows k >= bw are rows of the identity)
 #pragma unroll
     for (int k = 0; k < W; ++k) {
-        const double piv = __shfl(x[k], k);
+        const double piv = bcast_lane(x[k], k);
         const bool dep = ((badmask >> k) & 1) || !(piv > tol2);
-        if (k < bw) {
-            if (dep) {
-                badmask |= 1 << k;
-                if (!aug) x[k] = (j == k) ? 1.0 : 0.0;
-            } else {
-                if (piv < min_piv) min_piv = piv;
-                const double rinv = rsqrt_nr(piv);
-                x[k] *= rinv;
+        badmask |= dep ? (1 << k) : 0;
+        min_piv = (!dep && piv < min_piv) ? piv : min_piv;
+        const double rinv = rsqrt_nr(dep ? 1.0 : piv);
+        const double xk = dep ? (aug ? x[k] : (j == k ? 1.0 : 0.0)) : x[k] * rinv;
+        x[k] = xk;
+        const double mult = dep ? 0.0 : xk;
 #pragma unroll
-                for (int i = k + 1; i < W; ++i) {
-                    const double rki = __shfl(x[k], i);
-                    if (aug || j >= i) x[i] -= rki * x[k];
-                }
-            }
-        }
+        for (int i = k + 1; i < W; ++i) x[i] = __builtin_fma(-bcast_lane(xk, i), mult, x[i]);
     }
     // lane 16 + c holds row c of T_JJ
     if (aug && j < 16 + bw) {
