@@ -97,7 +97,8 @@ typedef struct {
                                    0 = default = 1, the single-step compressor of Algorithm 1; each further
                                    step costs two more passes over M                                      */
     int32_t lazy_residual;      /* 1: deferred residual.  psgd_compress does not run the pass E <- M - P~ Q^T for the
-                                   layers stored with rows >= cols; it leaves M_t in their E buffers, puts the
+                                   layers stored with rows >= cols (for every layer if no rank exceeds 32); it
+                                   leaves M_t in their E buffers, puts the
                                    operand copies of P~_t and Q_t aside in the workspace, and the forming pass of
                                    the next psgd_compress subtracts their product on the way (same arithmetic:
                                    E_{t+1} is rounded to fp32 before it enters M_{t+1}).  P~, Q and every later

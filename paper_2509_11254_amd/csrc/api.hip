@@ -75,6 +75,7 @@ struct psgd_ctx {
     int planes = 2;  // bf16 planes per fp32 operand of the MFMA products (2: 3 products, 3: 6 products)
     bool reform_m = false;   // SSP step forms M = mean G + E in every pass instead of storing it over E
     bool lazy = false;       // deferred residual: E_{t+1} = M - P~ Q^T is applied by the next forming pass
+    bool lazy_tr = false;    // ... also for the layers stored with rows < cols (column-mode forming pass: width 32 only)
     bool pending = false;    // the E buffers of the row-major layers hold M_t, their residual is still owed
     double kernel_bytes[3] = {0.0, 0.0, 0.0};   // algorithmic bytes of the three streaming kernels of one SSP step
     // batched splits
@@ -145,7 +146,7 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
-    if (c->lazy && !p.transposed)
+    if (c->lazy && (!p.transposed || c->lazy_tr))
         for (int s = 0; s < 2; ++s)
             for (int k = 0; k < c->planes; ++k) R.lz[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
@@ -202,7 +203,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
         for (int k = 0; k < c->planes; ++k) {
             L.pack[s].n[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k]);
             L.pack[s].t[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k + 1]);
-            L.lz[s][k] = (c->lazy && !p.transposed) ? reinterpret_cast<bf16_t*>(base + R.lz[s][k]) : nullptr;
+            L.lz[s][k] = (c->lazy && (!p.transposed || c->lazy_tr)) ? reinterpret_cast<bf16_t*>(base + R.lz[s][k]) : nullptr;
         }
     }
     L.gram = reinterpret_cast<double*>(base + R.gram);
@@ -331,7 +332,7 @@ struct Launcher {
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
         note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
-        note(launch_prod(nb, ctx->planes, p_like, form, false, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
@@ -367,17 +368,23 @@ struct Launcher {
         note(launch_outer(nb, ctx->planes, false, form, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
         prof_end(k);
     }
-    // deferred residual: the transposed layers take theirs at once, the row-major ones keep their operands
+    // deferred residual: the layers that defer keep their operands; the others (stored with rows < cols, at
+    // widths above 32) take their residual at once
     void residual_deferred(int nb, int cp) {
+        if (ctx->lazy_tr) {
+            note(launch_keep(layers, ids_all, n_all, max_lenP(), cp, st));
+            return;
+        }
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
         note(launch_outer(nb, ctx->planes, false, false, false, layers, ids_tr, n_tr, tiles_outer, nullptr, 0, st));
         prof_end(k);
         note(launch_keep(layers, ids_norm, n_norm, max_lenP(), cp, st));
     }
-    // E <- M - (kept P~)(kept Q)^T for the row-major layers: what the deferred residual still owes
+    // E <- M - (kept P~)(kept Q)^T for the layers that defer: what the deferred residual still owes
     void residual_owed(int nb) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
-        note(launch_outer(nb, ctx->planes, false, false, true, layers, ids_norm, n_norm, tiles_outer, nullptr, 0, st));
+        if (ctx->lazy_tr) note(launch_outer(nb, ctx->planes, false, false, true, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
+        else note(launch_outer(nb, ctx->planes, false, false, true, layers, ids_norm, n_norm, tiles_outer, nullptr, 0, st));
         prof_end(k);
     }
 };
@@ -510,6 +517,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         c->cpmax = c->cpz > c->cpc ? c->cpz : c->cpc;
         if (c->cpmax > kMaxWidth) rc = PSGD_E_SHAPE;
         if (c->lazy && c->cpc > 128) rc = PSGD_E_SHAPE;
+        c->lazy_tr = c->lazy && c->cpc == 32;
     }
     if (rc != PSGD_OK) { delete c; return rc; }
     // reduction splits of the batched launches
@@ -552,7 +560,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         bytes += 4.0 * 4.0 * (double)(p.d.rows + p.d.cols) * p.d.r;
         const double e = (double)p.d.rows * (double)p.d.cols, nsg = n_workers * sg;
         const double thin = 4.0 * (double)(p.d.rows + p.d.cols) * 32.0 * ((p.d.r + 31) / 32);
-        const bool deferred = c->lazy && !p.transposed;
+        const bool deferred = c->lazy && (!p.transposed || c->lazy_tr);
         c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin * (deferred ? 2.0 : 1.0);
         c->kernel_bytes[1] += e * (c->reform_m ? nsg + 4.0 : 4.0) + thin;
         if (!deferred) c->kernel_bytes[2] += e * (c->reform_m ? nsg + 8.0 : 8.0) + thin;
@@ -614,7 +622,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     }
     if (ctx->lazy) {
         L.residual_deferred(nb, cp);               // owed: E <- M - P~ Q_t^T, applied by the next forming pass
-        ctx->pending = L.n_norm > 0;
+        ctx->pending = L.n_norm > 0 || ctx->lazy_tr;
     } else {
         L.residual(nb, re);                        // E <- M - P~ Q_t^T
     }

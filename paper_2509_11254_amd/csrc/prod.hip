@@ -236,12 +236,14 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 // variants run alone and may use the whole register file.
 constexpr int prod_min_blocks(int nb, int pl) { return 2 * pl * (BT + 32 * nb) * LDSW * 2 <= 160 * 1024 ? 2 : 1; }
 
-// LAZY (row mode, FORM): the buffer S holds M_{t-1} and the residual of the previous step is still owed,
+// LAZY (FORM): the buffer S holds M_{t-1} and the residual of the previous step is still owed,
 // E_t = M_{t-1} - P~_{t-1} Q_{t-1}^T (Algorithm 2, error update).  The pass applies it on the way: the rank-r
-// product for the tile comes from the kept operand copies of P~_{t-1} (this workgroup's 128 rows, in
-// registers for the whole pass) and Q_{t-1} (the chunk's 64 rows, staged in LDS) on v_mfma_f32_16x16x32_bf16,
-// whose accumulator layout -- lane (j, g) holds rows 4g..4g+3 of column j -- with block q bound to matrix
-// columns 4j + q gives every lane 4 consecutive columns of 8 rows: the layout the tile is loaded in.
+// product for the tile comes from the kept operand copies of the two thin matrices -- the one on the side the
+// workgroup owns (its 128 rows in row mode, 128 columns in column mode) in registers for the whole pass, the
+// chunk's 64 rows of the other one staged in LDS -- on v_mfma_f32_16x16x32_bf16, whose accumulator layout
+// -- lane (j, g) holds rows 4g..4g+3 of column j -- with block q bound to matrix columns 4j + q gives every
+// lane 4 consecutive columns of 8 rows: the layout the tile is loaded in.  Column mode: width 32 only (the
+// resident operand is four blocks wide there, twice the registers of row mode).
 template <int NB, int PL> constexpr int prod_lds_elems(bool lazy) {
     return PL * (BT + 32 * NB) * LDSW + (lazy ? PL * BK * (32 * NB + 8) : 0);
 }
@@ -282,7 +284,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     const float inv_n = 1.0f / (float)L.n_workers;
     const int src_lenP = side_lenP(L, src_side);
     const PackRef XK = L.pack[src_side];
-    static_assert(!LAZY || (FORM && !COLMODE), "the pending correction is applied by the row-mode forming pass");
+    static_assert(!LAZY || (FORM && (!COLMODE || NB == 1)), "the pending correction is applied by a forming pass");
     constexpr int CPW = 32 * NB + 8;                         // LDS row stride of the correction's column operand
     constexpr int CPL = BK * CPW;                            // one plane of it
     bf16_t* c_pl = b_pl + PL * NB * 32 * LDSW;               // PL planes of [BK][CPW] (LAZY only)
@@ -296,18 +298,24 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     // thread's position in the S tile: row mode 16 x 16 threads over (row, 4 columns), 8 rows 16 apart;
     // column mode 8 x 32 threads over (8 consecutive rows, 4 columns)
     // (LAZY: wave v owns rows 32v..32v+31 as two 16-row accumulator blocks, lane (j, g) rows 4g..4g+3 of each)
-    const int c4 = COLMODE ? (t & 31) : LAZY ? lj : (t & 15);
-    const int r0 = COLMODE ? (t >> 5) : LAZY ? 32 * wv + 4 * lq : (t >> 4);       // row group in column mode
+    // (LAZY, column mode: wave v owns rows 32 (v & 1) .. +31 of the chunk and columns 64 (v >> 1) .. +63)
+    const int c4 = LAZY ? (COLMODE ? 16 * (wv >> 1) + lj : lj) : COLMODE ? (t & 31) : (t & 15);
+    const int r0 = LAZY ? (COLMODE ? 32 * (wv & 1) + 4 * lq : 32 * wv + 4 * lq)
+                        : COLMODE ? (t >> 5) : (t >> 4);       // row group in column mode
     auto addr_of = [&](int ch) {
         const int k0 = ch * BK;
+        if (LAZY) return COLMODE ? tile_addr_quad(L, k0, ob * BT, BK, BT, r0, 4 * c4)
+                                 : tile_addr_quad(L, ob * BT, k0, BT, BK, r0, 4 * c4);
         return COLMODE ? tile_addr(L, k0, ob * BT, BK, BT, 8 * r0, 1, 4 * c4)
-               : LAZY  ? tile_addr_quad(L, ob * BT, k0, BT, BK, r0, 4 * c4)
                        : tile_addr(L, ob * BT, k0, BT, BK, r0, 16, 4 * c4);
     };
-    // LAZY: this wave's 32 rows of the kept P~ operand copy stay in registers for the whole pass; the chunk's 64
-    // rows of the kept Q copy are requested one chunk ahead and staged in LDS, matrix column c at LDS row
-    // (c & 3) * 16 + (c >> 2) so that the 16 lanes of an MFMA block read 16 consecutive LDS rows
-    bf16x8 ap[LAZY ? 2 : 1][LAZY ? NB : 1][PL];
+    // LAZY: this wave's part of the kept operand copy on the side the workgroup owns stays in registers for the
+    // whole pass (row mode: 2 blocks of 16 rows; column mode: 4 blocks of 16 columns, block q = columns 4j + q);
+    // the chunk's 64 rows of the other kept copy are requested one chunk ahead and staged in LDS -- in row mode
+    // matrix column c at LDS row (c & 3) * 16 + (c >> 2), so that the 16 lanes of an MFMA block read 16
+    // consecutive LDS rows; in column mode matrix row by matrix row
+    constexpr int NRES = COLMODE ? 4 : 2;
+    bf16x8 ap[LAZY ? NRES : 1][LAZY ? NB : 1][PL];
     uintx4 cq[LAZY ? NB : 1][PL];
     auto corr_prefetch = [&](int ch) {
 #pragma unroll
@@ -317,18 +325,20 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
             const int64_t goff = (int64_t)(ch * BK + c) * cp + 8 * part;
 #pragma unroll
             for (int k = 0; k < PL; ++k)
-                cq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[SIDE_W][k]) + goff);
+                cq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[src_side][k]) + goff);
         }
     };
     auto load_ap = [&]() {
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+        for (int h = 0; h < NRES; ++h)
 #pragma unroll
             for (int ks = 0; ks < NB; ++ks)
 #pragma unroll
-                for (int k = 0; k < PL; ++k)
+                for (int k = 0; k < PL; ++k) {
+                    const int own = COLMODE ? 64 * (wv >> 1) + 4 * lj + h : 32 * wv + 16 * h + lj;   // row / column of the tile
                     ap[h][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                        as_global(L.lz[SIDE_L][k]) + (int64_t)(ob * BT + 32 * wv + 16 * h + lj) * cp + 32 * ks + 8 * lq);
+                        as_global(L.lz[out_side][k]) + (int64_t)(ob * BT + own) * cp + 32 * ks + 8 * lq);
+                }
     };
     if (LAZY) load_ap();
     // Row mode: workgroups that run at the same time own different row blocks and would all be at the same
@@ -385,7 +395,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                 const int c = v / (4 * NB), part = v % (4 * NB);
 #pragma unroll
                 for (int k = 0; k < PL; ++k)
-                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + ((c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[i][k];
+                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + (COLMODE ? c : (c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[i][k];
             }
             __syncthreads();
             floatx4 d[2][4];
@@ -393,25 +403,49 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
             for (int h = 0; h < 2; ++h)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) d[h][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (!COLMODE) {
+                // A operand = the resident rows (block h), B operand = the staged chunk (block q)
 #pragma unroll
-            for (int ks = 0; ks < NB; ++ks)
+                for (int ks = 0; ks < NB; ++ks)
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    bf16x8 bv[PL];
+                    for (int q = 0; q < 4; ++q) {
+                        bf16x8 bv[PL];
 #pragma unroll
-                    for (int k = 0; k < PL; ++k)
-                        bv[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (16 * q + lj) * CPW + 32 * ks + 8 * lq);
+                        for (int k = 0; k < PL; ++k)
+                            bv[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (16 * q + lj) * CPW + 32 * ks + 8 * lq);
 #pragma unroll
-                    for (int h = 0; h < 2; ++h)
+                        for (int h = 0; h < 2; ++h)
 #pragma unroll
-                        for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+                            for (int sum = 2 * (PL - 1); sum >= 0; --sum)
 #pragma unroll
-                            for (int ka = 0; ka < PL; ++ka) {
-                                const int kb = sum - ka;
-                                if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
-                                    d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap[h][ks][ka], bv[kb], d[h][q], 0, 0, 0);
-                            }
-                }
+                                for (int ka = 0; ka < PL; ++ka) {
+                                    const int kb = sum - ka;
+                                    if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                                        d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap[h][ks][ka], bv[kb], d[h][q], 0, 0, 0);
+                                }
+                    }
+            } else {
+                // A operand = the staged chunk rows (block h of this wave's 32), B operand = the resident columns (block q)
+#pragma unroll
+                for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        bf16x8 av[PL];
+#pragma unroll
+                        for (int k = 0; k < PL; ++k)
+                            av[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (32 * (wv & 1) + 16 * h + lj) * CPW + 32 * ks + 8 * lq);
+#pragma unroll
+                        for (int q = 0; q < 4; ++q)
+#pragma unroll
+                            for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                                for (int ka = 0; ka < PL; ++ka) {
+                                    const int kb = sum - ka;
+                                    if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                                        d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ka], ap[q][ks][kb], d[h][q], 0, 0, 0);
+                                }
+                    }
+            }
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -446,6 +480,34 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                     for (int k = 0; k < PL; ++k) o[k][3] = q[k];
 #pragma unroll
                     for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_pl + k * APL + row * LDSW + 4 * c4) = o[k];
+                }
+            } else if constexpr (LAZY) {
+                // piece u = 4h + v: rows 16h + v (+ this lane's 32 (wv & 1) + 4 lq), i.e. 4 consecutive k per column
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    bf16x4 o[4][PL];
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        bf16_t q[PL];
+                        split_planes<PL>(m[4 * h + v].x, q);
+#pragma unroll
+                        for (int k = 0; k < PL; ++k) o[0][k][v] = q[k];
+                        split_planes<PL>(m[4 * h + v].y, q);
+#pragma unroll
+                        for (int k = 0; k < PL; ++k) o[1][k][v] = q[k];
+                        split_planes<PL>(m[4 * h + v].z, q);
+#pragma unroll
+                        for (int k = 0; k < PL; ++k) o[2][k][v] = q[k];
+                        split_planes<PL>(m[4 * h + v].w, q);
+#pragma unroll
+                        for (int k = 0; k < PL; ++k) o[3][k][v] = q[k];
+                    }
+                    const int kk = r0 + 16 * h;                 // first of the 4 rows, a multiple of 4
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int k = 0; k < PL; ++k)
+                            *reinterpret_cast<bf16x4*>(a_pl + k * APL + (4 * c4 + q) * LDSW + 8 * a_chunk<true>(4 * c4 + q, kk >> 3) + (kk & 4)) = o[q][k];
                 }
             } else {
                 const int rg = r0;
@@ -648,9 +710,12 @@ static hipError_t launch_nb(bool colmode, bool form, bool lazy, const LayerDev* 
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, out_role, epi, gate);           \
     } while (0)
     if (lazy) {
-        // the forming pass that also applies the pending residual: row mode, compress-step widths only
-        if constexpr (NB <= 4) {
-            if (colmode || !form) return hipErrorInvalidValue;
+        // the forming pass that also applies the pending residual: compress-step widths only, column mode at width 32
+        if (!form) return hipErrorInvalidValue;
+        if constexpr (NB == 1) {
+            if (colmode) PSGD_LAUNCH(true, true, true); else PSGD_LAUNCH(false, true, true);
+        } else if constexpr (NB <= 4) {
+            if (colmode) return hipErrorInvalidValue;
             PSGD_LAUNCH(false, true, true);
         } else {
             return hipErrorInvalidValue;

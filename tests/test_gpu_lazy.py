@@ -61,7 +61,8 @@ def _trajectory(wl, steps, lds=None, refresh_at=(), check_m=True, **opts):
             else:
                 errs["P"] = orc.rel_fro(p_gpu, out.comp.p_tilde)
                 errs["Q"] = orc.rel_fro(q_gpu, out.comp.q)
-            deferred = spec.rows >= spec.cols and not refresh
+            # layers stored with rows < cols defer too when no rank exceeds 32 (column-mode forming pass)
+            deferred = (spec.rows >= spec.cols or wl.r <= 32) and not refresh
             if deferred and check_m:
                 # what the option documents: the buffer holds M_t = mean_i (G^(i) + e^(i)) until the flush
                 m_t = orc.worker_mean([gi + ei for gi, ei in zip(g, e_w[l])])
@@ -107,12 +108,21 @@ def test_deferred_residual_trajectory(which):
     print(which, _trajectory(wl, 4, lds=lds))
 
 
-def test_deferred_residual_batched_with_transposed_layer():
-    """Layers stored with rows < cols take their residual at once; the others defer it: one batch holds both."""
+@pytest.mark.parametrize("r", [32, 40, 5])
+def test_deferred_residual_batched_with_transposed_layers(r):
+    """Layers stored with rows < cols defer their residual only up to rank 32 (column-mode forming pass) and take it
+    at once above; one batch holds both kinds of storage, ragged shapes included."""
     wl = synth.scaled_down(synth.config3(), 256, 256)
+    wl.r = r
     wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c"),
-                 synth.LayerSpec(200, 136, "e")]
-    print(_trajectory(wl, 3))
+                 synth.LayerSpec(200, 136, "e"), synth.LayerSpec(136, 333, "f")]
+    print(r, _trajectory(wl, 3, lds=[256, 256, 704, 136, 336]))
+
+
+def test_deferred_residual_transposed_full_size():
+    """The 2048 x 5632 layer of the 1B-style set (stored with rows < cols, rank 32, 4 workers), two free-running steps."""
+    wl = synth.scaled_down(synth.config3(), 2048, 5632)
+    print(_trajectory(wl, 2))
 
 
 def test_deferred_residual_with_refresh_steps_in_between():
