@@ -12,8 +12,8 @@
 #include "psgd_dev.h"
 
 namespace psgd {
-hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids,
-                       int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers,
+                       const int* ids, int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
@@ -331,8 +331,9 @@ struct Launcher {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
-        note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
-        note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
+        const bool onew = ctx->n_workers == 1;
+        note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that

@@ -134,14 +134,16 @@ __device__ inline void tile_prefetch(const LayerDev& L, const TileAddr& a, float
 }
 
 // Second half: the remaining workers, the mean, + E, the mask.  The sum over the workers runs in worker order.
-template <bool FORM, bool PIPE>
+// ONEW: compiled for a single worker (no loop over further gradient buffers, and no registers kept for them)
+template <bool FORM, bool PIPE, bool ONEW = false>
 __device__ inline void tile_finish(const LayerDev& L, const TileAddr& a, float inv_n, const float4 (&p0)[8],
                                    const float4 (&p1)[8], float4 (&m)[8]) {
 #pragma unroll
     for (int u = 0; u < 8; ++u) m[u] = p0[u];
     if (FORM) {
-        const int nw = L.n_workers;
-        if (PIPE) {
+        const int nw = ONEW ? 1 : L.n_workers;
+        if (ONEW) {
+        } else if (PIPE) {
             // two workers' loads in flight: the next worker is requested before the current one is added
             // (where the registers allow it: narrow output blocks)
             float4 xa[8], xb[8];
@@ -248,7 +250,7 @@ template <int NB, int PL> constexpr int prod_lds_elems(bool lazy) {
     return PL * (BT + 32 * NB) * LDSW + (lazy ? PL * BK * (32 * NB + 8) : 0);
 }
 
-template <int NB, int PL, bool COLMODE, bool FORM, bool LAZY = false>
+template <int NB, int PL, bool COLMODE, bool FORM, bool LAZY = false, bool ONEW = false>
 __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 * 1024 ? 2 : 1)) void prod_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int cp, int out_role,
                                                         int epi_flags, int gate) {
@@ -281,7 +283,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     const int lane = t & 63, wv = t >> 6;
     const int li = lane & 31, lg = lane >> 5;
     const int lj = lane & 15, lq = lane >> 4;     // lane coordinates of the 16 x 16 MFMA blocks (LAZY)
-    const float inv_n = 1.0f / (float)L.n_workers;
+    static_assert(!ONEW || FORM, "the single-worker variants are forming passes");
+    const float inv_n = ONEW ? 1.0f : 1.0f / (float)L.n_workers;
     const int src_lenP = side_lenP(L, src_side);
     const PackRef XK = L.pack[src_side];
     static_assert(!LAZY || (FORM && (!COLMODE || NB == 1)), "the pending correction is applied by a forming pass");
@@ -351,9 +354,9 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
     // thin operand chunk: pre-split, transposed [cp][lenP]; requested one chunk ahead, before the tile's own loads
     // (the wait counter is in issue order: waiting for the chunk then leaves the tile's loads in flight)
-    // (only where the registers allow it: the forming passes are at their limit and request it after the tile
-    // has been consumed instead)
-    constexpr bool BPRE = !FORM;
+    // (only where the registers allow it: the forming passes for several workers are at their limit and request it
+    // after the tile has been consumed instead)
+    constexpr bool BPRE = !FORM || ONEW;
     uintx4 bq[NB][PL];
     auto b_prefetch = [&](int ch) {
 #pragma unroll
@@ -366,10 +369,79 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                 bq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
         }
     };
+    floatx4 d[LAZY ? 2 : 1][4];
+    auto corr_to_lds = [&]() {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int v = t + i * kThreads;
+            const int c = v / (4 * NB), part = v % (4 * NB);
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                *reinterpret_cast<uintx4*>(c_pl + k * CPL + (COLMODE ? c : (c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[i][k];
+        }
+    };
+    // the rank-r product for the chunk whose kept rows are in LDS, in the tile's register layout
+    auto corr_mfma = [&]() {
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) d[h][q] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if constexpr (!COLMODE) {
+            // A operand = the resident rows (block h), B operand = the staged chunk (block q)
+#pragma unroll
+            for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    bf16x8 bv[PL];
+#pragma unroll
+                    for (int k = 0; k < PL; ++k)
+                        bv[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (16 * q + lj) * CPW + 32 * ks + 8 * lq);
+#pragma unroll
+                    for (int h = 0; h < 2; ++h)
+#pragma unroll
+                        for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                            for (int ka = 0; ka < PL; ++ka) {
+                                const int kb = sum - ka;
+                                if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                                    d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap[h][ks][ka], bv[kb], d[h][q], 0, 0, 0);
+                            }
+                }
+        } else {
+            // A operand = the staged chunk rows (block h of this wave's 32), B operand = the resident columns (block q)
+#pragma unroll
+            for (int ks = 0; ks < NB; ++ks)
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    bf16x8 av[PL];
+#pragma unroll
+                    for (int k = 0; k < PL; ++k)
+                        av[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (32 * (wv & 1) + 16 * h + lj) * CPW + 32 * ks + 8 * lq);
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+#pragma unroll
+                        for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                            for (int ka = 0; ka < PL; ++ka) {
+                                const int kb = sum - ka;
+                                if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
+                                    d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ka], ap[q][ks][kb], d[h][q], 0, 0, 0);
+                            }
+                }
+        }
+    };
     float4 p0[8], p1[8];
     if (n_loc > 0) {
+        if (LAZY) {
+            // the first chunk's product has no MFMA phase before it to hide in
+            corr_prefetch(chunk_at(0));
+            corr_to_lds();
+            __syncthreads();
+            corr_mfma();
+            __syncthreads();
+            if (n_loc > 1) corr_prefetch(chunk_at(1));
+        }
         if (BPRE) b_prefetch(chunk_at(0));
-        if (LAZY) corr_prefetch(chunk_at(0));
         tile_prefetch<FORM>(L, addr_of(chunk_at(0)), p0, p1);
     }
     for (int it = 0; it < n_loc; ++it) {
@@ -386,66 +458,10 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
             }
         };
         if (BPRE) b_to_lds();
-        // ---- LAZY: the rank-r product of the previous step for this tile, in the tile's register layout;
-        // E = M_{t-1} - product is rounded to fp32 here, as the residual kernel would have stored it
+        // ---- LAZY: E = M_{t-1} - (rank-r product of the previous step), rounded to fp32 here as the residual kernel
+        // would have stored it; the product for this tile was formed during the previous MFMA phase.  The next
+        // chunk's rows of the kept operand go to LDS now (their buffer was last read before the last barrier).
         if (LAZY) {
-#pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int v = t + i * kThreads;
-                const int c = v / (4 * NB), part = v % (4 * NB);
-#pragma unroll
-                for (int k = 0; k < PL; ++k)
-                    *reinterpret_cast<uintx4*>(c_pl + k * CPL + (COLMODE ? c : (c & 3) * 16 + (c >> 2)) * CPW + 8 * part) = cq[i][k];
-            }
-            __syncthreads();
-            floatx4 d[2][4];
-#pragma unroll
-            for (int h = 0; h < 2; ++h)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) d[h][q] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if constexpr (!COLMODE) {
-                // A operand = the resident rows (block h), B operand = the staged chunk (block q)
-#pragma unroll
-                for (int ks = 0; ks < NB; ++ks)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        bf16x8 bv[PL];
-#pragma unroll
-                        for (int k = 0; k < PL; ++k)
-                            bv[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (16 * q + lj) * CPW + 32 * ks + 8 * lq);
-#pragma unroll
-                        for (int h = 0; h < 2; ++h)
-#pragma unroll
-                            for (int sum = 2 * (PL - 1); sum >= 0; --sum)
-#pragma unroll
-                                for (int ka = 0; ka < PL; ++ka) {
-                                    const int kb = sum - ka;
-                                    if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
-                                        d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ap[h][ks][ka], bv[kb], d[h][q], 0, 0, 0);
-                                }
-                    }
-            } else {
-                // A operand = the staged chunk rows (block h of this wave's 32), B operand = the resident columns (block q)
-#pragma unroll
-                for (int ks = 0; ks < NB; ++ks)
-#pragma unroll
-                    for (int h = 0; h < 2; ++h) {
-                        bf16x8 av[PL];
-#pragma unroll
-                        for (int k = 0; k < PL; ++k)
-                            av[k] = *reinterpret_cast<const bf16x8*>(c_pl + k * CPL + (32 * (wv & 1) + 16 * h + lj) * CPW + 32 * ks + 8 * lq);
-#pragma unroll
-                        for (int q = 0; q < 4; ++q)
-#pragma unroll
-                            for (int sum = 2 * (PL - 1); sum >= 0; --sum)
-#pragma unroll
-                                for (int ka = 0; ka < PL; ++ka) {
-                                    const int kb = sum - ka;
-                                    if (kb >= 0 && kb < PL && keep_term<PL>(ka, kb))
-                                        d[h][q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[ka], ap[q][ks][kb], d[h][q], 0, 0, 0);
-                                }
-                    }
-            }
 #pragma unroll
             for (int h = 0; h < 2; ++h)
 #pragma unroll
@@ -453,12 +469,13 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                     float4& e = p1[4 * h + v];
                     e.x -= d[h][0][v]; e.y -= d[h][1][v]; e.z -= d[h][2][v]; e.w -= d[h][3][v];
                 }
+            if (it + 1 < n_loc) corr_to_lds();
         }
         // ---- S tile: (prefetched) global -> registers -> (store M) -> split -> LDS
         {
             const TileAddr a = addr_of(ch);
             float4 m[8];
-            tile_finish<FORM, (NB <= 2 && !LAZY)>(L, a, inv_n, p0, p1, m);
+            tile_finish<FORM, (NB <= 2 && !LAZY), ONEW>(L, a, inv_n, p0, p1, m);
             if (store_m) store_m8(L, a, m);
             if (!COLMODE) {
 #pragma unroll
@@ -540,7 +557,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
         // ---- next tile's first loads go out now and stay in flight during the MFMA phase
         if (it + 1 < n_loc) {
             if (BPRE) b_prefetch(chunk_at(it + 1));
-            if (LAZY) corr_prefetch(chunk_at(it + 1));
+            if (LAZY && it + 2 < n_loc) corr_prefetch(chunk_at(it + 2));
             tile_prefetch<FORM>(L, addr_of(chunk_at(it + 1)), p0, p1);
         }
         // ---- MFMA: 32 output rows per wave, NB blocks of 32 columns, 4 k-steps of 16
@@ -567,6 +584,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                     }
             }
         }
+        // ---- LAZY: the next chunk's rank-r product, in the same MFMA phase (its rows went to LDS before the barrier)
+        if (LAZY && it + 1 < n_loc) corr_mfma();
         __syncthreads();
     }
     const int out_lenP = side_lenP(L, out_side);
@@ -693,8 +712,8 @@ size_t prod_lds_bytes(int nb, int planes, bool lazy = false) {
 }
 
 template <int NB, int PL>
-static hipError_t launch_nb(bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids, int n_ids,
-                            int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
+static hipError_t launch_nb(bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers, const int* ids,
+                            int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = prod_lds_bytes(NB, PL, lazy);
@@ -713,27 +732,30 @@ static hipError_t launch_nb(bool colmode, bool form, bool lazy, const LayerDev* 
         // the forming pass that also applies the pending residual: compress-step widths only, column mode at width 32
         if (!form) return hipErrorInvalidValue;
         if constexpr (NB == 1) {
-            if (colmode) PSGD_LAUNCH(true, true, true); else PSGD_LAUNCH(false, true, true);
+            if (colmode) { if (onew) PSGD_LAUNCH(true, true, true, true); else PSGD_LAUNCH(true, true, true); }
+            else         { if (onew) PSGD_LAUNCH(false, true, true, true); else PSGD_LAUNCH(false, true, true); }
         } else if constexpr (NB <= 4) {
             if (colmode) return hipErrorInvalidValue;
-            PSGD_LAUNCH(false, true, true);
+            if (onew) PSGD_LAUNCH(false, true, true, true); else PSGD_LAUNCH(false, true, true);
         } else {
             return hipErrorInvalidValue;
         }
-    } else if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
-    else                { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
+    } else if (form && onew) { if (colmode) PSGD_LAUNCH(true, true, false, true); else PSGD_LAUNCH(false, true, false, true); }
+    else if (colmode) { if (form) PSGD_LAUNCH(true, true); else PSGD_LAUNCH(true, false); }
+    else              { if (form) PSGD_LAUNCH(false, true); else PSGD_LAUNCH(false, false); }
 #undef PSGD_LAUNCH
     return hipGetLastError();
 }
 
 // nb = width / 32 of the thin operand (1..6); planes = 2 or 3 bf16 planes per operand.
 // lazy: the forming pass also applies the pending rank-r correction (row mode, form, nb <= 4).
-hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, const LayerDev* layers, const int* ids,
-                       int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
+// onew: every layer of the launch has one worker (forming passes only; ignored otherwise).
+hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers,
+                       const int* ids, int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st) {
 #define PSGD_CASE(N)                                                                                          \
     case N:                                                                                                   \
-        return planes == 2 ? launch_nb<N, 2>(colmode, form, lazy, layers, ids, n_ids, max_tiles, out_role, epi, gate, st) \
-                           : launch_nb<N, 3>(colmode, form, lazy, layers, ids, n_ids, max_tiles, out_role, epi, gate, st);
+        return planes == 2 ? launch_nb<N, 2>(colmode, form, lazy, onew, layers, ids, n_ids, max_tiles, out_role, epi, gate, st) \
+                           : launch_nb<N, 3>(colmode, form, lazy, onew, layers, ids, n_ids, max_tiles, out_role, epi, gate, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;
