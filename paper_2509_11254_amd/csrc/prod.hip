@@ -355,7 +355,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     // spread over the channels, while the blocks of one layer on one XCD read nearby chunks of the thin operands
     // at any time and find in the L2 what a neighbour fetched a little earlier.  (With every block on an unrelated
     // walk the operands of the ~16 layers in flight do not fit the L2 and come from memory again and again: the
-    // deferred residual's operand alone costs 1.4 ms of a 13.7 ms pass; this order takes 0.3-0.4 ms off it.)
+    // deferred residual's operand alone costs 1.4 ms of a 13.7 ms pass.  What this order takes off it, 0.3 ms or
+    // so, is within the run-to-run spread of the pass.)
     const int rot = (COLMODE || n_loc <= 0) ? 0
                     : ((ob & 7) * (n_loc >> 3) + 2 * (ob >> 3) + (int)blockIdx.y) % n_loc;
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
