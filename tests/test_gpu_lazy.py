@@ -195,3 +195,36 @@ def test_deferred_residual_full_size_llm_shapes(cfg, rows, cols):
     base = synth.config3() if cfg == "c3" else synth.config4()
     wl = synth.scaled_down(base, rows, cols)
     print(cfg, rows, cols, _trajectory(wl, 2))
+
+
+@pytest.mark.parametrize("rows,cols,dtype,r", [(328, 520, synth.F32, 8), (264, 1000, synth.BF16, 32), (1000, 264, synth.F32, 96)])
+def test_deferred_residual_single_worker(rows, cols, dtype, r):
+    """N = 1 with the deferred residual: the single-worker forming kernels in row and column mode."""
+    base = synth.config4() if dtype == synth.BF16 else synth.config2()
+    wl = synth.scaled_down(base, rows, cols)
+    wl.n_workers = 1
+    wl.r = r
+    print(_trajectory(wl, 3))
+
+
+def test_flush_on_another_workspace_is_rejected():
+    """The owed operands live in the workspace of the compress call: settling them from another one is an error."""
+    import ctypes as C
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config1(), 256, 128)
+    spec = wl.layers[0]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=True)
+    grads = _layers_inputs(wl, 0)
+    case.upload(grads, [np.zeros((spec.rows, spec.cols), np.float32)], [synth.initial_q(spec.n, wl.r, wl.seed, 0)])
+    case.compress()
+    other = torch.empty(case.comp.workspace_bytes + 256, dtype=torch.uint8, device="cuda")
+    other_ptr = (other.data_ptr() + 255) // 256 * 256
+    te = (C.c_void_p * 1)(case.E[0].data_ptr())
+    rc = case.comp.lib.psgd_flush_residual(case.comp.ctx, other_ptr, 0, te)
+    assert rc == psgd.PSGD_E_INVALID_ARG
+    case.comp.flush_residual(case.E)                      # the right one still settles it
+    torch.cuda.synchronize()
+    g = [synth.gradient_as_f64(gw) for gw in grads[0]]
+    out = orc.compress_step(1, None, wl.r, synth.initial_q(spec.n, wl.r, wl.seed, 0).astype(np.float64), g,
+                            [np.zeros((spec.rows, spec.cols))] * wl.n_workers)
+    assert orc.rel_fro(back(case.E[0]), out.e_mean) <= 1e-4

@@ -535,3 +535,19 @@ def test_refresh_as_randomized_range_finder():
     _, _, e = case.outputs(0)
     opt = float(np.sum(sigma[r:] ** 2))
     assert opt * (1 - 1e-6) <= float(np.sum(e ** 2)) <= 1.5 * opt      # never below the optimum, close above it
+
+
+# ------------------------------------------------------------------ single-worker variants of the forming passes
+@pytest.mark.parametrize("rows,cols,dtype,r", [(520, 328, synth.F32, 8), (328, 520, synth.F32, 8), (333, 203, synth.BF16, 40),
+                                               (264, 1000, synth.BF16, 64), (640, 512, synth.F32, 128)])
+def test_single_worker_forming_passes(rows, cols, dtype, r):
+    """N = 1 selects kernels compiled without the loop over further gradient buffers (row and column mode, both
+    operand precisions): one SSP step and one SVD-Comp step against the oracle."""
+    base = synth.config4() if dtype == synth.BF16 else synth.config2()
+    wl = synth.scaled_down(base, rows, cols)
+    wl.n_workers = 1
+    wl.r = r
+    lds = [(cols + 7) // 8 * 8]
+    print("ssp", _run_case(wl, lds=lds))
+    if r <= 40:      # at these small shapes a wider cut lies inside the noise bulk: no gap, no subspace to compare
+        print("refresh", _run_case(wl, refresh=True, lds=lds))
