@@ -114,6 +114,7 @@ struct psgd_ctx {
     int iters_gen = 0, iters_gen_of_copy = 0;   // a copy made before something else changed the counts is ignored
     // optional timing of the three streaming kernels with event pairs on the caller's stream
     bool prof_on = false;
+    int prof_mask = (1 << PSGD_PROF_TAGS) - 1;   // which of the tagged launches are timed
     std::vector<hipEvent_t> prof_ev;      // pairs (start, stop)
     std::vector<int> prof_tag;            // tag of each pair
     size_t prof_used = 0;                 // pairs recorded so far
@@ -313,7 +314,7 @@ struct Launcher {
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
     int prof_begin(int tag) {
-        if (prof_mute || !ctx->prof_on || ctx->prof_used >= ctx->prof_ev.size() / 2) return -1;
+        if (prof_mute || !ctx->prof_on || !((ctx->prof_mask >> tag) & 1) || ctx->prof_used >= ctx->prof_ev.size() / 2) return -1;
         const int k = (int)ctx->prof_used++;
         ctx->prof_tag[k] = tag;
         note(hipEventRecord(ctx->prof_ev[2 * k], st));
@@ -836,6 +837,12 @@ int psgd_profile_enable(psgd_ctx* ctx, int max_records) {
         PSGD_TRY(hipEventCreate(&e));
         ctx->prof_ev.push_back(e);
     }
+    return PSGD_OK;
+}
+
+int psgd_profile_select(psgd_ctx* ctx, int tag_mask) {
+    if (!ctx || tag_mask < 0 || tag_mask >= (1 << PSGD_PROF_TAGS)) return PSGD_E_INVALID_ARG;
+    ctx->prof_mask = tag_mask;
     return PSGD_OK;
 }
 

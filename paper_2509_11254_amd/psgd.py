@@ -21,7 +21,7 @@ EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
     "psgd_decompress", "psgd_decompress_msgd", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
-    "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_read",
+    "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_select", "psgd_profile_read",
 ]
 PROF_TAGS = ("sweep1", "sweep2", "residual")
 
@@ -97,6 +97,8 @@ def load_library() -> C.CDLL:
     lib.psgd_strerror.restype = C.c_char_p
     lib.psgd_profile_enable.argtypes = [vp, C.c_int]
     lib.psgd_profile_enable.restype = C.c_int
+    lib.psgd_profile_select.argtypes = [vp, C.c_int]
+    lib.psgd_profile_select.restype = C.c_int
     lib.psgd_profile_read.argtypes = [vp, C.POINTER(C.c_double), C.POINTER(C.c_int), C.c_int]
     lib.psgd_profile_read.restype = C.c_int
     lib.psgd_destroy.argtypes = [vp]
@@ -218,6 +220,13 @@ class Compressor:
 
     def profile_enable(self, max_records: int) -> None:
         _check(self.lib, self.ctx, self.lib.psgd_profile_enable(self.ctx, int(max_records)))
+
+    def profile_select(self, tags: Sequence[str]) -> None:
+        """Time only the launches with these tags (each timed launch costs two event records on the stream)."""
+        mask = 0
+        for t in tags:
+            mask |= 1 << PROF_TAGS.index(t)
+        _check(self.lib, self.ctx, self.lib.psgd_profile_select(self.ctx, mask))
 
     def profile_read(self) -> dict:
         """{tag: (total_ms, count)} of the event pairs recorded since the last read."""
