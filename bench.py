@@ -302,7 +302,10 @@ def main():
     torch.cuda.synchronize()
     prof_ssp = comp.profile_read()
     comp.profile_enable(0)
-    refresh_ms = timed(lambda i: comp.compress_refresh(sets[i % args.sets], E, Q, P), max(2, min(5, n_b)))
+    # (one call per synchronised interval, as in a schedule with tau > 1: the library looks at the iteration bound it
+    # fetched after the previous refresh only if that copy has arrived)
+    n_r = max(2, min(5, n_b))
+    refresh_ms = sum(timed(lambda i: comp.compress_refresh(sets[i % args.sets], E, Q, P), 1) for _ in range(n_r)) / n_r
     dec_ms = timed(lambda i: comp.decompress(P, Q, OUT), n_b)
     # decompress fused with the momentum-SGD update (Eq. (7c)): reads and writes m and X, 16 bytes per element
     MOM = [torch.zeros_like(e) for e in E]
