@@ -362,9 +362,9 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
     // thin operand chunk: pre-split, transposed [cp][lenP]; requested one chunk ahead, before the tile's own loads
     // (the wait counter is in issue order: waiting for the chunk then leaves the tile's loads in flight)
-    // (only where the registers allow it: the forming passes for several workers are at their limit and request it
-    // after the tile has been consumed instead)
-    constexpr bool BPRE = !FORM || ONEW;
+    // (only where the registers allow it: the forming passes for several workers are at their limit above width 32
+    // and request it after the tile has been consumed instead)
+    constexpr bool BPRE = !FORM || ONEW || NB == 1;
     uintx4 bq[NB][PL];
     auto b_prefetch = [&](int ch) {
 #pragma unroll
