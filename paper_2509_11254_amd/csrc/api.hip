@@ -20,8 +20,8 @@ hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_i
 hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st);
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                        float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
-hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
+hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
+                         int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
                        int cp, hipStream_t st);
@@ -43,7 +43,9 @@ using namespace psgd;
 namespace {
 
 constexpr int kMaxWidth = 192;      // widest thin block (packed Cholesky factor and product operands must fit in LDS)
-constexpr int kTargetTiles = 1024;  // workgroups per product launch we try to reach by splitting the reduction
+constexpr int kTargetTiles = 1024;  // workgroups per forming-pass launch we try to reach by splitting the reduction
+constexpr int kTargetTilesPlain = 512;   // ... per launch of a product that only reads M: half as many, twice as long-lived
+                                         // (config 2: pass 2a 20.4 -> 18.6 us, its refresh step 1.00 -> 0.96 ms)
 constexpr int kMaxSplit = 32;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -79,7 +81,8 @@ struct psgd_ctx {
     bool pending = false;    // the E buffers of the row-major layers hold M_t, their residual is still owed
     double kernel_bytes[3] = {0.0, 0.0, 0.0};   // algorithmic bytes of the three streaming kernels of one SSP step
     // batched splits
-    int split_row_b = 1, split_col_b = 1;
+    int split_row_b = 1, split_col_b = 1;       // products that read M
+    int split_row_bf = 1, split_col_bf = 1;     // forming passes
     // workspace layout (byte offsets)
     // The gradient pointer table and the layer descriptors (which point into it) exist kGSlots times: a caller
     // that rotates between a few sets of gradient buffers finds its table already on the device.
@@ -143,7 +146,8 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
     const int lenP[2] = {p.rowsP, p.colsP};
-    const int split[2] = {c->split_row_b, c->split_col_b};
+    const int split[2] = {c->split_row_b > c->split_row_bf ? c->split_row_b : c->split_row_bf,
+                          c->split_col_b > c->split_col_bf ? c->split_col_b : c->split_col_bf};
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
@@ -173,8 +177,9 @@ int target_tiles() {
     return v;
 }
 
-int choose_split(int64_t base_tiles, int min_chunks) {
-    const int target = target_tiles();
+int choose_split(int64_t base_tiles, int min_chunks, bool form) {
+    int target = target_tiles();
+    if (!form && target > kTargetTilesPlain) target = target / 2;
     if (base_tiles >= target) return 1;
     int64_t s = (target + base_tiles - 1) / base_tiles;
     if (s > kMaxSplit) s = kMaxSplit;
@@ -192,6 +197,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
     L.gdt = p.d.grad_dtype; L.n_workers = c->n_workers; L.transposed = p.transposed; L.planes = c->planes;
     L.rowsP = p.rowsP; L.colsP = p.colsP;
     L.split_row = c->split_row_b; L.split_col = c->split_col_b;
+    L.split_row_f = c->split_row_bf; L.split_col_f = c->split_col_bf;
     L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab_s[slot]) + (size_t)l * c->n_workers;
     L.S = c->hE.empty() ? nullptr : c->hE[l];
     const int side_p = side_of_role(p.transposed, ROLE_P), side_q = side_of_role(p.transposed, ROLE_Q);
@@ -304,7 +310,8 @@ struct Launcher {
     // geometry maxima over the layers addressed by this launcher
     int max_rows = 0, max_cols = 0, max_rowsP = 0, max_colsP = 0;
     int tiles_row = 0, tiles_col = 0, tiles_outer = 0, blocks_row = 0, blocks_col = 0;
-    int split_row = 1, split_col = 1;
+    int tiles_row_f = 0, tiles_col_f = 0;       // forming passes
+    int split_row = 1, split_col = 1, split_row_f = 1, split_col_f = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
@@ -332,6 +339,8 @@ struct Launcher {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
         const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
+        const int tiles_row = form ? tiles_row_f : this->tiles_row, tiles_col = form ? tiles_col_f : this->tiles_col;
+        const int split_row = form ? split_row_f : this->split_row, split_col = form ? split_col_f : this->split_col;
         const bool onew = ctx->n_workers == 1;
         note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
@@ -339,8 +348,8 @@ struct Launcher {
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
         const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
-        if (split_t) note(launch_finish(p_like, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_n) note(launch_finish(!p_like, form, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_t) note(launch_finish(p_like, form, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (chol_gate >= -1) {
             if (!split_n) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
             if (!split_t) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
@@ -391,16 +400,19 @@ struct Launcher {
     }
 };
 
-void geometry(const psgd_ctx* c, int l, int split_row, int split_col, Launcher& L) {
+void geometry(const psgd_ctx* c, int l, int split_row, int split_col, int split_row_f, int split_col_f, Launcher& L) {
     const Plan& p = c->plan[l];
     auto mx = [](int& a, int b) { if (b > a) a = b; };
     mx(L.max_rows, (int)p.d.rows); mx(L.max_cols, (int)p.d.cols);
     mx(L.max_rowsP, p.rowsP); mx(L.max_colsP, p.colsP);
     mx(L.tiles_row, (int)((p.d.rows + 127) / 128) * split_row);
     mx(L.tiles_col, (int)((p.d.cols + 127) / 128) * split_col);
+    mx(L.tiles_row_f, (int)((p.d.rows + 127) / 128) * split_row_f);
+    mx(L.tiles_col_f, (int)((p.d.cols + 127) / 128) * split_col_f);
     mx(L.blocks_row, (int)((p.d.rows + 127) / 128));
     mx(L.blocks_col, (int)((p.d.cols + 127) / 128));
     L.split_row = split_row; L.split_col = split_col;
+    L.split_row_f = split_row_f; L.split_col_f = split_col_f;
     mx(L.tiles_outer, (int)((p.d.rows + 127) / 128) * (int)((p.d.cols + 127) / 128));
 }
 
@@ -412,7 +424,7 @@ Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     const int* ids = reinterpret_cast<const int*>(L.ws + ctx->off_ids);
     L.ids_all = ids; L.ids_norm = ids + nl; L.ids_tr = ids + 2 * (size_t)nl;
     L.n_all = nl; L.n_norm = (int)ctx->lists.norm.size(); L.n_tr = (int)ctx->lists.tr.size();
-    for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, L);
+    for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, ctx->split_row_bf, ctx->split_col_bf, L);
     return L;
 }
 
@@ -532,8 +544,10 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         if (cr < min_chunks_row) min_chunks_row = cr;
         if (cc < min_chunks_col) min_chunks_col = cc;
     }
-    c->split_row_b = choose_split(base_row, min_chunks_row);
-    c->split_col_b = choose_split(base_col, min_chunks_col);
+    c->split_row_b = choose_split(base_row, min_chunks_row, false);
+    c->split_col_b = choose_split(base_col, min_chunks_col, false);
+    c->split_row_bf = choose_split(base_row, min_chunks_row, true);
+    c->split_col_bf = choose_split(base_col, min_chunks_col, true);
     // workspace layout
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
@@ -716,8 +730,9 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     D.S = const_cast<float*>(M);
     D.thin[ROLE_P].ptr = P;
     D.thin[ROLE_Q].ptr = Q;
-    D.split_row = choose_split((p.d.rows + 127) / 128, (int)((p.d.cols + 63) / 64));
-    D.split_col = choose_split((p.d.cols + 127) / 128, (int)((p.d.rows + 63) / 64));
+    D.split_row = choose_split((p.d.rows + 127) / 128, (int)((p.d.cols + 63) / 64), false);
+    D.split_col = choose_split((p.d.cols + 127) / 128, (int)((p.d.rows + 63) / 64), false);
+    D.split_row_f = D.split_row; D.split_col_f = D.split_col;      // (no forming pass in this call)
     D.part[0] = reinterpret_cast<float*>(ws + ctx->off_single_part[0]);
     D.part[1] = reinterpret_cast<float*>(ws + ctx->off_single_part[1]);
     ctx->hLayers[ctx->n_layers] = D;
@@ -733,7 +748,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     L.ids_all = ids; L.n_all = 1;
     L.ids_norm = ids; L.n_norm = p.transposed ? 0 : 1;
     L.ids_tr = ids; L.n_tr = p.transposed ? 1 : 0;
-    geometry(ctx, layer, D.split_row, D.split_col, L);
+    geometry(ctx, layer, D.split_row, D.split_col, D.split_row_f, D.split_col_f, L);
     refresh_sequence(ctx, L, false, false, sigma, 0);
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;

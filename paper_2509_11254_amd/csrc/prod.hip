@@ -263,7 +263,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     const int out_len = COLMODE ? L.cols : L.rows;
     const int red_len = COLMODE ? L.rows : L.cols;
     const int n_ob = (out_len + BT - 1) / BT;
-    const int n_split = COLMODE ? L.split_col : L.split_row;
+    const int n_split = FORM ? (COLMODE ? L.split_col_f : L.split_row_f) : (COLMODE ? L.split_col : L.split_row);
     const int tile = blockIdx.x;
     if (tile >= n_ob * n_split) return;
     int ob, sp;
@@ -639,14 +639,14 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
                                                           int out_role, int epi_flags, int gate, int chol_gate,
-                                                          int a2gate, double tol2, int local_ok) {
+                                                          int a2gate, double tol2, int local_ok, int form) {
     __shared__ int s_last;
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     const int epi = epi_flags & EPI_KIND_MASK;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
-    const int n_split = colmode ? L.split_col : L.split_row;
+    const int n_split = form ? (colmode ? L.split_col_f : L.split_row_f) : (colmode ? L.split_col : L.split_row);
     const int ob = blockIdx.x;
     if (n_split <= 1 || ob * BT >= out_len) return;
     const int out_lenP = side_lenP(L, out_side);
@@ -696,8 +696,8 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     }
 }
 
-hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int cp,
-                         int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
+hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
+                         int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
     dim3 grid(max_blocks, n_ids), block(kThreads);
@@ -709,7 +709,7 @@ hipError_t launch_finish(bool colmode, const LayerDev* layers, const int* ids, i
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate,
-                       chol_gate, a2gate, tol2, local_ok);
+                       chol_gate, a2gate, tol2, local_ok, form ? 1 : 0);
     return hipGetLastError();
 }
 

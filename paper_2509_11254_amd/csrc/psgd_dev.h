@@ -85,6 +85,8 @@ struct LayerDev {
     int rowsP, colsP;  // rows / cols rounded up to kLenPad
     int split_row;     // k-splits of the row-mode product  (reduction over cols)
     int split_col;     // k-splits of the column-mode product (reduction over rows)
+    int split_row_f;   // the same for the forming passes, which want about twice as many workgroups
+    int split_col_f;
     const void* const* G;   // n_workers device pointers
     float* S;               // E on entry, M between the sweeps, E_{t+1} on exit
     ThinRef thin[ROLE_COUNT];
