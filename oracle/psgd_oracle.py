@@ -176,6 +176,23 @@ def msgd_update(x: np.ndarray, mom: np.ndarray, delta_hat: np.ndarray, eta: floa
 
 
 # ----------------------------------------------------------------------------------------
+# Adam as the base optimizer (Section 3, Claim 1 and Figure 1 name it next to MSGD; the pre-training runs of
+# Section 5 / Appendix C use Adam and the fine-tuning runs AdamW with betas (0.9, 0.999)).  The paper does not
+# print the update; this is the published one (Kingma & Ba, Algorithm 1) applied to the compressed update
+# Delta_hat in place of the gradient, with the decoupled weight decay of AdamW (Loshchilov & Hutter,
+# Algorithm 2 with schedule multiplier 1); weight_decay = 0 is plain Adam.  `step` counts from 1.
+# ----------------------------------------------------------------------------------------
+def adam_update(x: np.ndarray, m1: np.ndarray, m2: np.ndarray, delta_hat: np.ndarray, step: int, eta: float,
+                beta1: float, beta2: float, eps: float, weight_decay: float = 0.0):
+    m1 = beta1 * m1 + (1.0 - beta1) * delta_hat
+    m2 = beta2 * m2 + (1.0 - beta2) * delta_hat * delta_hat
+    m1_hat = m1 / (1.0 - beta1 ** step)
+    m2_hat = m2 / (1.0 - beta2 ** step)
+    x = x - eta * (m1_hat / (np.sqrt(m2_hat) + eps) + weight_decay * x)
+    return x, m1, m2
+
+
+# ----------------------------------------------------------------------------------------
 # Section 3 / Appendix A: the 2x2 problem on which PowerSGD stalls.
 # ----------------------------------------------------------------------------------------
 A_MAT = np.array([[1.0, -1.0], [-1.0, 1.0]])

@@ -346,6 +346,40 @@ def test_config2_full_size_refresh_step():
     print("config2 full refresh", _check_step(case, wl, grads, errs, qs, True, 1e-4))
 
 
+def test_config2_full_size_refresh_schedule_adaptive_count():
+    """Error-feedback schedule at config 2's size with a refresh at t = 0, 2, 4 and SSP steps in between, the
+    library keeping its own E and Q.  The later refreshes run the iteration count the layer chose from its own
+    Ritz values (fewer than the budget of 16); each is compared with the oracle's SVD-Comp of the same
+    M = mean G_t + E_t, E_t read back from the device before the step."""
+    wl = synth.config2()
+    spec = wl.layers[0]
+    sig = synth.signal_matrix(spec, wl, 0)
+    grads, errs, qs = _workload_inputs(wl, err_scale=0.3)
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, errs, qs)
+    worst = 0.0
+    for t in range(5):
+        if t > 0:
+            grads = [[synth.worker_gradient(spec, wl, 0, w, t, sig) for w in range(wl.n_workers)]]
+            case.G = [[to_dev_grad(g, case.lds[0]) for g in grads[0]]]
+        refresh = t % 2 == 0
+        if refresh and t > 0:
+            e_before = back(case.E[0], spec.cols)
+            k_used = case.comp.status(0).refresh_iters_next
+            assert 2 <= k_used < 16, k_used
+        case.compress(refresh=refresh)
+        if refresh and t > 0:
+            g, e = oracle_inputs(grads[0], e_before, spec.rows, spec.cols, wl.n_workers)
+            out = orc.compress_step(0, 1, wl.r, back(case.Q[0]), g, e)
+            p_gpu, q_gpu, e_gpu = case.outputs(0)
+            sn = orc.sin_theta_max(out.comp.p_tilde, p_gpu)
+            worst = max(worst, sn)
+            assert sn <= 1e-4, (t, k_used, sn)
+            assert orc.rel_fro(p_gpu @ q_gpu.T, out.comp.delta_hat) <= 1e-4
+            assert orc.rel_fro(e_gpu, out.e_mean) <= 1e-4
+    print("config2 refresh schedule, worst sin", worst)
+
+
 def test_refresh_step_bf16_gradients():
     """SVD-Comp with bf16 gradients (four workers, r = 32, normal and transposed storage): the oracle sees the
     same bf16 values, so the subspace bar is the same 1e-4; E and Delta_hat are held to the bf16 bar."""

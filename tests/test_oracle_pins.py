@@ -415,3 +415,51 @@ def test_mean_error_trajectory_equals_single_aggregated_buffer():
         np.testing.assert_allclose(ow.e_mean, oa.e_next[0], atol=1e-12)
         np.testing.assert_allclose(ow.comp.delta_hat, oa.comp.delta_hat, atol=1e-12)
         e_w, e_agg, q_w, q_a = ow.e_next, oa.e_next, ow.comp.q, oa.comp.q
+
+
+# ------------------------------------------------------------------ Adam / AdamW on the compressed update
+def test_adam_first_step_and_constant_gradient_closed_form():
+    """From zero moments the bias-corrected moments of step 1 are g and g^2, so the step is
+    -eta g / (|g| + eps); with the same g at every step the bias corrections cancel the (1 - beta^t) factors
+    exactly and every step is that same step."""
+    rng = np.random.default_rng(3)
+    g = rng.standard_normal((5, 3))
+    x0 = rng.standard_normal((5, 3))
+    eta, eps = 0.01, 1e-8
+    x, m1, m2 = x0, np.zeros_like(g), np.zeros_like(g)
+    for t in range(1, 8):
+        x, m1, m2 = orc.adam_update(x, m1, m2, g, t, eta, 0.9, 0.999, eps)
+        np.testing.assert_allclose(x, x0 - t * eta * g / (np.abs(g) + eps), rtol=0, atol=1e-14)
+    np.testing.assert_allclose(m1, (1 - 0.9 ** 7) * g, atol=1e-15)
+    np.testing.assert_allclose(m2, (1 - 0.999 ** 7) * g * g, atol=1e-15)
+
+
+def test_adam_two_steps_by_hand():
+    """g_1 = 1, g_2 = -1, beta = (0.9, 0.999), eps = 0: m = 0.1 then -0.01, v = 0.001 then 0.001999;
+    at step 2 m^ = -0.01 / 0.19 and v^ = 0.001999 / (1 - 0.998001) = 1, so x_2 = x_1 + eta / 19."""
+    x, m1, m2 = np.array([2.0]), np.zeros(1), np.zeros(1)
+    x, m1, m2 = orc.adam_update(x, m1, m2, np.array([1.0]), 1, 0.5, 0.9, 0.999, 0.0)
+    assert x[0] == pytest.approx(1.5, abs=1e-15) and m1[0] == pytest.approx(0.1) and m2[0] == pytest.approx(0.001)
+    x, m1, m2 = orc.adam_update(x, m1, m2, np.array([-1.0]), 2, 0.5, 0.9, 0.999, 0.0)
+    assert m1[0] == pytest.approx(-0.01, abs=1e-15) and m2[0] == pytest.approx(0.001999, abs=1e-15)
+    assert x[0] == pytest.approx(1.5 + 0.5 / 19.0, abs=1e-13)
+
+
+def test_adam_scale_invariance_and_decoupled_weight_decay():
+    rng = np.random.default_rng(4)
+    gs = [rng.standard_normal((4, 4)) for _ in range(5)]
+    x0 = rng.standard_normal((4, 4))
+    def run(scale, wd):
+        x, m1, m2 = x0, np.zeros((4, 4)), np.zeros((4, 4))
+        for t, g in enumerate(gs, 1):
+            x, m1, m2 = orc.adam_update(x, m1, m2, scale * g, t, 0.02, 0.8, 0.95, 0.0, wd)
+        return x
+    # with eps = 0 the step does not see the scale of the gradients
+    np.testing.assert_allclose(run(1.0, 0.0), run(37.5, 0.0), atol=1e-13)
+    # zero gradient (eps > 0 so that 0 / (0 + eps) = 0): only the decay acts, x_t = (1 - eta lambda)^t x_0,
+    # and it does not enter the moments
+    x, m1, m2 = x0, np.zeros((4, 4)), np.zeros((4, 4))
+    for t in range(1, 4):
+        x, m1, m2 = orc.adam_update(x, m1, m2, np.zeros((4, 4)), t, 0.02, 0.9, 0.999, 1e-8, 0.1)
+    np.testing.assert_allclose(x, (1 - 0.02 * 0.1) ** 3 * x0, atol=1e-15)
+    assert not m1.any() and not m2.any()
