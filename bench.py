@@ -312,7 +312,11 @@ def main():
     XW = [torch.randn_like(e) for e in E]
     msgd_ms = timed(lambda i: comp.decompress_msgd(P, Q, MOM, XW, 0.9, 1e-3), n_b)
     msgd_gbps = (16.0 * elems) / (msgd_ms * 1e-3) / 1e9
-    del MOM, XW
+    # ... and with Adam (second moment as well: 24 bytes per element); the step counter advances as in a run
+    M2 = [torch.zeros_like(e) for e in E]
+    adam_ms = timed(lambda i: comp.decompress_adam(P, Q, MOM, M2, XW, i + 1, 1e-3), n_b)
+    adam_gbps = (24.0 * elems) / (adam_ms * 1e-3) / 1e9
+    del MOM, M2, XW
     # the same SSP steps with the deferred residual (psgd_options.lazy_residual): the residual of a step is applied by
     # the next step's forming pass; the flush that settles the last one is inside the timed region
     lazy_ms = None
@@ -364,6 +368,8 @@ def main():
                           refresh_ms_per_layer=refresh_ms / len(wl.layers), decompress_ms=dec_ms,
                           decompress_msgd_ms=msgd_ms, decompress_msgd_GBps=msgd_gbps,
                           decompress_msgd_frac_of_hbm_peak=msgd_gbps / HBM_PEAK_GBPS,
+                          decompress_adam_ms=adam_ms, decompress_adam_GBps=adam_gbps,
+                          decompress_adam_frac_of_hbm_peak=adam_gbps / HBM_PEAK_GBPS,
                           ssp_step_deferred_residual_ms=lazy_ms,
                           ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
                           ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),

@@ -168,6 +168,18 @@ int psgd_decompress(psgd_ctx *ctx, void *workspace, void *stream, const float *c
 int psgd_decompress_msgd(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
                          const float *const *Q, float *const *mom, float *const *X, float mu, float eta);
 
+/* psgd_decompress_adam -- the same step with Adam as the base optimizer (the paper's pre-training and fine-tuning
+ * runs, Section 5 and Appendix C, use Adam / AdamW on the compressed update; Claim 1 names it next to MSGD).  The
+ * update is the published one with bias correction and decoupled weight decay, on D = P~[l] Q[l]^T:
+ *   m1 <- beta1 m1 + (1 - beta1) D;   m2 <- beta2 m2 + (1 - beta2) D.D   (elementwise)
+ *   X  <- X - eta ( (m1 / (1 - beta1^step)) / (sqrt(m2 / (1 - beta2^step)) + eps) + weight_decay X )
+ * step counts from 1 (the caller increments it); weight_decay = 0 is plain Adam.  Delta_hat is never written.
+ * m1, m2, X: n_layers fp32 buffers rows x cols (ld) in the layer's storage orientation, updated in place.
+ * Errors: INVALID_ARG (null table or entry, step < 1, a beta outside [0, 1), eps < 0, a NaN), ALIGN, HIP. */
+int psgd_decompress_adam(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
+                         const float *const *Q, float *const *m1, float *const *m2, float *const *X, int step,
+                         float eta, float beta1, float beta2, float eps, float weight_decay);
+
 /* Copy the per-layer diagnostics of the last call to the host.  Synchronises `stream`. */
 int psgd_status(psgd_ctx *ctx, void *workspace, void *stream, int layer, psgd_layer_status *out);
 

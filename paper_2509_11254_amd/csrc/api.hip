@@ -3,6 +3,7 @@
 // step, one SVD-Comp step (Algorithm 1) and the reconstruction.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <cstdlib>
 #include <cstring>
 #include <new>
@@ -20,6 +21,8 @@ hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_i
 hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st);
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                        float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
+hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, hipStream_t st);
 hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
@@ -89,20 +92,21 @@ struct psgd_ctx {
     static constexpr int kGSlots = 4;
     size_t off_layers_s[kGSlots] = {}, off_gtab_s[kGSlots] = {};
     size_t off_iters = 0;            // one int: most iterations any layer's next refresh will run
-    size_t off_ids = 0, off_outs = 0, off_moms = 0, off_xs = 0, off_single_part[2] = {0, 0};
+    size_t off_ids = 0, off_outs = 0, off_moms = 0, off_m2s = 0, off_xs = 0, off_single_part[2] = {0, 0};
     std::vector<size_t> off_layer;   // start of each layer's private region
     size_t ws_bytes = 0;
     // cached tables
     void* bound_ws = nullptr;
     void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs
-    void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd
+    void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd / _adam
+    void* m2_ws = nullptr;       // ... and of the second-moment buffers of psgd_decompress_adam
     bool tables_valid = false;
     std::vector<const void*> hG;                       // the caller's current table
     std::vector<const void*> hGs[kGSlots];             // what each device slot holds (empty: nothing yet)
     int cur_slot = 0, next_victim = 0;
     std::vector<float*> hE, hQ, hP;
     std::vector<void*> hOut;
-    std::vector<float*> hMom, hX;
+    std::vector<float*> hMom, hM2, hX;
     std::vector<int> hIds;
     std::vector<LayerDev> hLayers;   // n_layers + 1 (last = scratch descriptor of single-layer calls)
     int last_hip = 0;
@@ -558,6 +562,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));
     c->off_xs = take((size_t)n_layers * sizeof(void*));
+    c->off_m2s = take((size_t)n_layers * sizeof(void*));
     int max_rowsP = 0, max_colsP = 0;
     for (auto& p : c->plan) { if (p.rowsP > max_rowsP) max_rowsP = p.rowsP; if (p.colsP > max_colsP) max_colsP = p.colsP; }
     c->off_single_part[0] = take((size_t)kMaxSplit * max_rowsP * c->wz * sizeof(float));
@@ -801,6 +806,47 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, st));
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
+                         float* const* m1, float* const* m2, float* const* X, int step, float eta, float beta1,
+                         float beta2, float eps, float weight_decay) {
+    if (!ctx || !P || !Q || !m1 || !m2 || !X) return PSGD_E_INVALID_ARG;
+    if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) ||
+        !(eta == eta) || !(weight_decay == weight_decay))
+        return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const size_t nl = (size_t)ctx->n_layers;
+    int rc = check_table(reinterpret_cast<const void* const*>(m1), nl);
+    if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(m2), nl);
+    if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(X), nl);
+    if (rc != PSGD_OK) return rc;
+    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    if (rc != PSGD_OK) return rc;
+    char* ws = reinterpret_cast<char*>(workspace);
+    const bool changed = sync_table(ctx->hMom, m1, nl) | sync_table(ctx->hX, X, nl);
+    if (changed || ctx->msgd_ws != workspace) {
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+    }
+    ctx->msgd_ws = workspace;
+    if (sync_table(ctx->hM2, m2, nl) || ctx->m2_ws != workspace)
+        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_m2s, ctx->hM2.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+    ctx->m2_ws = workspace;
+    // bias corrections in double: 1 - beta^t loses nothing for beta close to 1 and small t
+    const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
+    const float coef[8] = {beta1, beta2, (float)(1.0 - (double)beta1), (float)(1.0 - (double)beta2),
+                           (float)((double)eta / bc1), (float)(1.0 / std::sqrt(bc2)), eps,
+                           (float)((double)eta * (double)weight_decay)};
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_P, cp, ROLE_Q);
+    L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+                       reinterpret_cast<float* const*>(ws + ctx->off_moms),
+                       reinterpret_cast<float* const*>(ws + ctx->off_m2s),
+                       reinterpret_cast<float* const*>(ws + ctx->off_xs), coef, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }

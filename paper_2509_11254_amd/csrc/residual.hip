@@ -4,6 +4,7 @@
 //               (FORM: S holds E_t, not M; M = mean G + E is formed again on the way, Eq. (7a))
 //   decompress  out <- X_L X_W^T       Delta_hat = P~ Q_t^T          (Algorithm 1, return value)
 //   msgd        m <- mu m + X_L X_W^T;  X <- X - eta m               (Eq. (7c): momentum SGD on Delta_hat)
+//   adam        Adam / AdamW moments and weights from X_L X_W^T      (the base optimizer of Section 5's runs)
 //
 // Both thin operands arrive pre-split into two or three bf16 planes (row-major [len][cp]); the
 // product keeps the 3 (two planes) or 6 (three planes) largest plane products, accumulated in fp32 by
@@ -288,6 +289,94 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
     }
 }
 
+// Decompress fused with Adam on Delta_hat (the base optimizer of the paper's pre-training and fine-tuning runs,
+// Section 5 and Appendix C; the update itself is the published one, with decoupled weight decay):
+//   m <- b1 m + (1 - b1) D,  v <- b2 v + (1 - b2) D^2,  X <- X - step m / (sqrt(v) rs2 + eps) - decay X
+// with step = eta / (1 - b1^t), rs2 = 1 / sqrt(1 - b2^t), decay = eta lambda folded by the host.
+struct AdamArgs { float b1, b2, c1, c2, step, rs2, eps, decay; };
+
+template <int NB, int PL>
+__global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __restrict__ layers,
+                                                           const int* __restrict__ ids, int cp,
+                                                           float* const* __restrict__ m1s,
+                                                           float* const* __restrict__ m2s,
+                                                           float* const* __restrict__ xs, AdamArgs a) {
+    const int lid = ids[blockIdx.y];
+    const LayerDev& L = layers[lid];
+    const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
+    const int tile = blockIdx.x;
+    if (tile >= n_rb * n_cb) return;
+    const int cb = tile % n_cb, rb = tile / n_cb;
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* b_pl = reinterpret_cast<bf16_t*>(smem);
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int li = lane & 31, lg = lane >> 5;
+    const int col = cb * RT + 4 * li;
+    const bool col_ok = col < L.cols;
+    const int64_t tile_off = (int64_t)(rb * RT) * L.ld + cb * RT;
+    PSGD_GLOBAL float* m0 = as_global(m1s[lid]) + tile_off;
+    PSGD_GLOBAL float* v0 = as_global(m2s[lid]) + tile_off;
+    PSGD_GLOBAL float* x0 = as_global(xs[lid]) + tile_off;
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    const int row_lane = rb * RT + 32 * wv + 4 * lg;
+    auto at = [&](PSGD_GLOBAL float* base, int k) {
+        return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(base + (int64_t)k * L.ld) + lane_byte);
+    };
+    // the two moments of the tile are requested before the product (its staging and MFMAs hide their latency);
+    // the weights, needed last, are read in the epilogue
+    floatx4 mo[16], vo[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const int k = 8 * (v >> 2) + (v & 3);
+        mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        vo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+        if (col_ok && row_lane + k < L.rows) {
+            mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(m0, k)));
+            vo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(v0, k)));
+        }
+    }
+    floatx16 acc[4];
+    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc);
+    if (!col_ok) return;
+    const bool full = col + 3 < L.cols;
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+        floatx4 xo[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int k = 8 * g + u;
+            xo[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (row_lane + k < L.rows) {
+                if (full) xo[u] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(x0, k)));
+                else for (int q = 0; q < 4; ++q) if (col + q < L.cols) xo[u][q] = at(x0, k)[q];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int v = 4 * g + u, k = 8 * g + u;
+            if (row_lane + k >= L.rows) continue;
+            const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+            const floatx4 mn = mo[v] * a.b1 + d * a.c1;
+            const floatx4 vn = vo[v] * a.b2 + (d * d) * a.c2;
+            floatx4 xn;
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                xn[q] = xo[u][q] - a.step * (mn[q] / (sqrtf(vn[q]) * a.rs2 + a.eps)) - a.decay * xo[u][q];
+            PSGD_GLOBAL float* pm = at(m0, k);
+            PSGD_GLOBAL float* pv = at(v0, k);
+            PSGD_GLOBAL float* px = at(x0, k);
+            if (full) {
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(pm), mn);
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(pv), vn);
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(px), xn);
+            } else {
+                for (int q = 0; q < 4; ++q)
+                    if (col + q < L.cols) { pm[q] = mn[q]; pv[q] = vn[q]; px[q] = xn[q]; }
+            }
+        }
+    }
+}
+
 static size_t outer_lds_bytes(int nb, int planes) { return (size_t)planes * RT * (32 * nb + 8) * sizeof(bf16_t); }
 
 template <int NB, int PL>
@@ -347,6 +436,38 @@ hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* id
     case N:                                                                                                \
         return planes == 2 ? launch_msgd_nb<N, 2>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st)   \
                            : launch_msgd_nb<N, 3>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st);
+    switch (nb) {
+        PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
+        default: return hipErrorInvalidValue;
+    }
+#undef PSGD_CASE
+}
+
+template <int NB, int PL>
+static hipError_t launch_adam_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, float* const* m1s,
+                                 float* const* m2s, float* const* xs, const AdamArgs& a, hipStream_t st) {
+    dim3 grid(max_tiles, n_ids), block(kThreads);
+    const size_t lds = outer_lds_bytes(NB, PL);
+    auto kfn = adam_kernel<NB, PL>;
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, m1s, m2s, xs, a);
+    return hipGetLastError();
+}
+
+// m1s, m2s, xs: device arrays of per-layer device pointers; coef = {b1, b2, 1 - b1, 1 - b2, eta / (1 - b1^t),
+// 1 / sqrt(1 - b2^t), eps, eta * weight decay}
+hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, hipStream_t st) {
+    if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
+    const AdamArgs a = {coef[0], coef[1], coef[2], coef[3], coef[4], coef[5], coef[6], coef[7]};
+#define PSGD_CASE(N)                                                                                       \
+    case N:                                                                                                \
+        return planes == 2 ? launch_adam_nb<N, 2>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, st)     \
+                           : launch_adam_nb<N, 3>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;

@@ -19,7 +19,7 @@ PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -
 
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
-    "psgd_decompress", "psgd_decompress_msgd", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
+    "psgd_decompress", "psgd_decompress_msgd", "psgd_decompress_adam", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_select", "psgd_profile_read",
 ]
@@ -83,6 +83,9 @@ def load_library() -> C.CDLL:
     lib.psgd_decompress.restype = C.c_int
     lib.psgd_decompress_msgd.argtypes = [vp, vp, vp, pp, pp, pp, pp, C.c_float, C.c_float]
     lib.psgd_decompress_msgd.restype = C.c_int
+    lib.psgd_decompress_adam.argtypes = [vp, vp, vp, pp, pp, pp, pp, pp, C.c_int, C.c_float, C.c_float, C.c_float,
+                                         C.c_float, C.c_float]
+    lib.psgd_decompress_adam.restype = C.c_int
     lib.psgd_status.argtypes = [vp, vp, vp, C.c_int, C.POINTER(LayerStatus)]
     lib.psgd_status.restype = C.c_int
     lib.psgd_algorithmic_bytes.argtypes = [vp]
@@ -217,6 +220,16 @@ class Compressor:
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress_msgd(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, tm, tx,
                                              C.c_float(mu), C.c_float(eta)))
+
+    def decompress_adam(self, P, Q, m1, m2, X, step: int, eta: float, beta1: float = 0.9, beta2: float = 0.999,
+                        eps: float = 1e-8, weight_decay: float = 0.0, stream=None) -> None:
+        """psgd_decompress_adam: Adam / AdamW moments m1[l], m2[l] and weights X[l] from P[l] Q[l]^T (in place)."""
+        tp, tq, t1, t2, tx = _ptr_table(P), _ptr_table(Q), _ptr_table(m1), _ptr_table(m2), _ptr_table(X)
+        self._keep = (tp, tq, t1, t2, tx)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_decompress_adam(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, t1, t2, tx,
+                                             int(step), C.c_float(eta), C.c_float(beta1), C.c_float(beta2),
+                                             C.c_float(eps), C.c_float(weight_decay)))
 
     def profile_enable(self, max_records: int) -> None:
         _check(self.lib, self.ctx, self.lib.psgd_profile_enable(self.ctx, int(max_records)))

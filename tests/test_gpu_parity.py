@@ -502,6 +502,83 @@ def test_decompress_msgd_matches_eq_7c(rows, cols, dtype):
         assert orc.rel_fro(back(X[0], cols), x_ref) <= 1e-5, step
 
 
+# ------------------------------------------------------------------ decompress fused with Adam / AdamW
+@pytest.mark.parametrize("rows,cols,dtype,r,wd", [(640, 384, synth.F32, 12, 0.0), (200, 328, synth.F32, 12, 0.05),
+                                                  (1000, 264, synth.BF16, 40, 0.01), (384, 512, synth.BF16, 64, 0.0)])
+def test_decompress_adam_matches_published_update(rows, cols, dtype, r, wd):
+    """Adam moments and weights from Delta_hat = P~ Q^T over three steps (bias corrections of steps 1..3, both
+    moments carried over), against the oracle's update applied to the oracle's Delta_hat.  The step itself,
+    X_t - X_{t-1}, is compared as well: relative to X it would pass even if it were wrong by a factor."""
+    torch = torch_mod()
+    eta, b1, b2, eps = 0.01, 0.9, 0.999, 1e-8
+    m, n = max(rows, cols), min(rows, cols)
+    rng = np.random.default_rng(23)
+    case = Case([(rows, cols)], r, 1, dtype)
+    x_ref = rng.standard_normal((rows, cols)).astype(np.float32).astype(np.float64)
+    m1_ref, m2_ref = np.zeros((rows, cols)), np.zeros((rows, cols))
+    X, M1, M2 = [to_dev_f32(x_ref.astype(np.float32))], [to_dev_f32(m1_ref.astype(np.float32))], [to_dev_f32(m2_ref.astype(np.float32))]
+    posed = np.ones((rows, cols), dtype=bool)
+    for step in range(1, 4):
+        p = np.linalg.qr(rng.standard_normal((m, r)))[0].astype(np.float32)
+        q = (rng.standard_normal((n, r)) * 0.9 ** np.arange(r)).astype(np.float32)
+        P, Q = [to_dev_f32(p)], [to_dev_f32(q)]
+        x_before = back(X[0], cols)
+        case.comp.decompress_adam(P, Q, M1, M2, X, step, eta, b1, b2, eps, wd)
+        torch.cuda.synchronize()
+        dhat = orc.decompress(p.astype(np.float64), q.astype(np.float64))          # logical m x n
+        dhat = dhat.T if rows < cols else dhat                                     # storage orientation
+        x_new, m1_ref, m2_ref = orc.adam_update(x_ref, m1_ref, m2_ref, dhat, step, eta, b1, b2, eps, wd)
+        assert orc.rel_fro(back(M1[0], cols), m1_ref) <= 1e-5, step
+        assert orc.rel_fro(back(M2[0], cols), m2_ref) <= 3e-5, step      # D.D carries twice D's relative error
+        # Adam's step m^ / (sqrt(v^) + eps) is sign(D) at step 1 and stays discontinuous wherever the D's seen so
+        # far vanish together: an entry of D smaller than D's own error bar (split-bf16 operands, 2^-16 of
+        # |P~||Q| with two planes) has no well-defined step.  Those few entries are only held to Adam's bound
+        # on a step; all others are compared.
+        posed &= np.abs(dhat) > 1e-3 * np.sqrt(np.mean(dhat * dhat))
+        assert posed.mean() > 0.99
+        x_gpu = back(X[0], cols)
+        assert np.linalg.norm((x_gpu - x_new)[posed]) <= 1e-6 * np.linalg.norm(x_new[posed]), step
+        # fp32 weights: the step is known to about ulp(X) / |step| ~ 6e-8 / 1e-2 per entry
+        assert np.linalg.norm(((x_gpu - x_before) - (x_new - x_ref))[posed]) <= 1e-4 * np.linalg.norm((x_new - x_ref)[posed]), step
+        assert np.abs(x_gpu - x_new).max() <= 10 * eta * step
+        x_ref = x_new
+
+
+def test_decompress_adam_batched_and_rejected_arguments():
+    """All layers of a mixed batch in one call; the argument checks of the entry point."""
+    torch = torch_mod()
+    shapes = [(256, 256), (704, 256), (256, 704), (200, 136)]
+    r = 32
+    rng = np.random.default_rng(29)
+    case = Case(shapes, r, 1, synth.BF16)
+    P, Q, X, M1, M2, refs = [], [], [], [], [], []
+    for rows, cols in shapes:
+        m, n = max(rows, cols), min(rows, cols)
+        p = np.linalg.qr(rng.standard_normal((m, r)))[0].astype(np.float32)
+        q = rng.standard_normal((n, r)).astype(np.float32)
+        x = rng.standard_normal((rows, cols)).astype(np.float32)
+        m1 = (0.1 * rng.standard_normal((rows, cols))).astype(np.float32)
+        # second moment bounded away from zero: where it and D both vanish the step m^ / sqrt(v^) is ill-conditioned
+        m2 = (0.01 + 0.1 * rng.standard_normal((rows, cols)) ** 2).astype(np.float32)
+        P.append(to_dev_f32(p)); Q.append(to_dev_f32(q)); X.append(to_dev_f32(x)); M1.append(to_dev_f32(m1)); M2.append(to_dev_f32(m2))
+        dhat = orc.decompress(p.astype(np.float64), q.astype(np.float64))
+        dhat = dhat.T if rows < cols else dhat
+        refs.append(orc.adam_update(x.astype(np.float64), m1.astype(np.float64), m2.astype(np.float64), dhat, 7, 0.003,
+                                    0.9, 0.95, 1e-6, 0.1))
+    case.comp.decompress_adam(P, Q, M1, M2, X, 7, 0.003, 0.9, 0.95, 1e-6, 0.1)
+    torch.cuda.synchronize()
+    for l, (rows, cols) in enumerate(shapes):
+        x_ref, m1_ref, m2_ref = refs[l]
+        assert orc.rel_fro(back(M1[l], cols), m1_ref) <= 1e-5, l
+        assert orc.rel_fro(back(M2[l], cols), m2_ref) <= 3e-5, l
+        assert orc.rel_fro(back(X[l], cols), x_ref) <= 1e-6, l
+    for bad in (dict(step=0), dict(beta1=1.0), dict(beta2=-0.1), dict(eps=-1.0), dict(eta=float("nan"))):
+        args = dict(step=1, eta=0.01, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0)
+        args.update(bad)
+        with pytest.raises(psgd.PsgdError):
+            case.comp.decompress_adam(P, Q, M1, M2, X, **args)
+
+
 # ------------------------------------------------------------------ K-step power iteration (Eq. (8))
 @pytest.mark.parametrize("k_steps,m_policy", [(2, 0), (3, 0), (2, 2)])
 def test_k_step_power_iteration(k_steps, m_policy):
