@@ -165,7 +165,7 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     R.gram = take((size_t)(max_lenP / kGramRows2) * w2 * sizeof(double));
     R.tmat = take(w2 * sizeof(double));
     R.eval = take((size_t)(c->wz + 2) * sizeof(double));
-    R.status = take(8 * sizeof(int));
+    R.status = take(kStatusWords * sizeof(int));
     R.end = o;
     return R;
 }
@@ -296,7 +296,7 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
         // status words of a new workspace start at zero ("iterations the next refresh needs" = unknown)
         for (int l = 0; l < nl; ++l) {
             const LayerRegion R = layer_region(ctx, ctx->plan[l]);
-            PSGD_TRY(hipMemsetAsync(ws + ctx->off_layer[l] + R.status, 0, 8 * sizeof(int), st));
+            PSGD_TRY(hipMemsetAsync(ws + ctx->off_layer[l] + R.status, 0, kStatusWords * sizeof(int), st));
         }
     }
     ctx->bound_ws = workspace;

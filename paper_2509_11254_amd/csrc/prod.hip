@@ -14,6 +14,8 @@
 // first, with v_mfma_f32_32x32x16_bf16.
 // The S tile goes global -> registers (coalesced 16-byte loads, summed over workers) -> LDS in the
 // k-contiguous layout the MFMA A operand wants; the thin operand arrives pre-split and transposed.
+#include <type_traits>
+
 #include "thin_dev.h"
 
 namespace psgd {
@@ -636,6 +638,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
 // chol_gate >= -1: the last workgroup to finish a layer goes on to factorise the sum of the partial Gram
 // matrices (first CholeskyQR pass) if that gate is open, unless the layer is one where the apply kernel
 // does that for itself; -2: no factorisation follows.
+static_assert(BT == kGramRows1, "one partial Gram matrix per output block of a product");
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
                                                           int out_role, int epi_flags, int gate, int chol_gate,
@@ -655,44 +658,88 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     float* otile = reinterpret_cast<float*>(smem);    // [BT][cp + 1]
     const int tw = cp + 1;
     const int t = threadIdx.x;
+    PSGD_MARK(0);
     for (int e = t; e < BT * cp; e += kThreads) otile[(e / cp) * tw + e % cp] = 0.f;
     __syncthreads();
     const int64_t plane = (int64_t)out_lenP * T.width;
     const PSGD_GLOBAL float* __restrict__ src = as_global(L.part[out_side]) + (int64_t)ob * BT;
-    for (int item = t; item < T.width * (BT / 4); item += kThreads) {
-        const int col = item / (BT / 4), r4 = 4 * (item % (BT / 4));
-        const PSGD_GLOBAL float* __restrict__ sc = src + (int64_t)col * out_lenP + r4;
-        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
-        int s2 = 0;
-        for (; s2 + 16 <= n_split; s2 += 16) {        // 16 independent 16-byte loads in flight
-            float4 x[16];
+    // U items per thread at a time (two where a thread has several: 16 loads of 16 bytes in flight at a split of 8;
+    // four spill), eight splits per batch.  Every sum runs in split order.
+    auto reduce_items = [&](auto u_tag, int first, int last) {
+        constexpr int U = decltype(u_tag)::value;
+        for (int item0 = first + t; item0 < last; item0 += U * kThreads) {
+            const PSGD_GLOBAL float* sc[U];
+            float4 sum[U];
 #pragma unroll
-            for (int d = 0; d < 16; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
+            for (int u = 0; u < U; ++u) {
+                const int item = item0 + u * kThreads < last ? item0 + u * kThreads : item0;     // (clamped: a valid address)
+                sc[u] = src + (int64_t)(item / (BT / 4)) * out_lenP + 4 * (item % (BT / 4));
+                sum[u] = make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+            int s2 = 0;
+            for (; s2 + 8 <= n_split; s2 += 8) {
+                float4 x[U][8];
 #pragma unroll
-            for (int d = 0; d < 16; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) x[u][d] = ld_f32x4(sc[u] + (s2 + d) * plane);
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) { sum[u].x += x[u][d].x; sum[u].y += x[u][d].y; sum[u].z += x[u][d].z; sum[u].w += x[u][d].w; }
+            }
+            for (; s2 < n_split; ++s2) {
+                float4 x[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) x[u] = ld_f32x4(sc[u] + s2 * plane);
+#pragma unroll
+                for (int u = 0; u < U; ++u) { sum[u].x += x[u].x; sum[u].y += x[u].y; sum[u].z += x[u].z; sum[u].w += x[u].w; }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int item = item0 + u * kThreads;
+                if (item >= last) continue;
+                const int col = item / (BT / 4), r4 = 4 * (item % (BT / 4));
+                otile[(r4 + 0) * tw + col] = sum[u].x;
+                otile[(r4 + 1) * tw + col] = sum[u].y;
+                otile[(r4 + 2) * tw + col] = sum[u].z;
+                otile[(r4 + 3) * tw + col] = sum[u].w;
+            }
         }
-        for (; s2 + 4 <= n_split; s2 += 4) {
-            float4 x[4];
-#pragma unroll
-            for (int d = 0; d < 4; ++d) x[d] = ld_f32x4(sc + (s2 + d) * plane);
-#pragma unroll
-            for (int d = 0; d < 4; ++d) { sum.x += x[d].x; sum.y += x[d].y; sum.z += x[d].z; sum.w += x[d].w; }
-        }
-        for (; s2 < n_split; ++s2) {
-            const float4 x = ld_f32x4(sc + s2 * plane);
-            sum.x += x.x; sum.y += x.y; sum.z += x.z; sum.w += x.w;
-        }
-        otile[(r4 + 0) * tw + col] = sum.x;
-        otile[(r4 + 1) * tw + col] = sum.y;
-        otile[(r4 + 2) * tw + col] = sum.z;
-        otile[(r4 + 3) * tw + col] = sum.w;
+    };
+    {
+        const int n_items = T.width * (BT / 4);
+        if (n_items >= 2 * kThreads) reduce_items(std::integral_constant<int, 2>{}, 0, n_items);
+        else reduce_items(std::integral_constant<int, 1>{}, 0, n_items);
     }
     __syncthreads();
+    PSGD_MARK(1);
     tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
+    PSGD_MARK(2);
     if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role, local_ok) && gate_open(L, chol_gate)) {
-        const int n_wg = (out_len + BT - 1) / BT;
-        if (last_to_arrive(&L.status[6], n_wg, &s_last))
+        const int n_wg = (out_len + BT - 1) / BT;      // = number of Gram slots (BT == kGramRows1)
+        if (grouped_slot_sum(T.width, n_wg)) {
+            const int grp = ob / kSlotGroup;
+            const int in_grp = min(kSlotGroup, n_wg - grp * kSlotGroup);
+            if (last_to_arrive(&L.status[8 + grp], in_grp, &s_last)) {
+                PSGD_MARK(3);
+                sum_slot_group(L.gram, T.width, n_wg, grp);
+                if (last_to_arrive(&L.status[6], (n_wg + kSlotGroup - 1) / kSlotGroup, &s_last)) {
+                    PSGD_MARK(4);
+                    chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat, true, nullptr,
+                              kSlotGroup);
+#ifdef PSGD_MARKS
+                    PSGD_MARK(8);
+                    if (threadIdx.x == 0)
+                        printf("finish marks w=%d (10 ns): reduce %lld epilogue %lld arrive %lld groupsum+arrive %lld slotsum %lld factor %lld inverse %lld write %lld\n",
+                               T.width, g_marks[1] - g_marks[0], g_marks[2] - g_marks[1], g_marks[3] - g_marks[2], g_marks[4] - g_marks[3],
+                               g_marks[5] - g_marks[4], g_marks[6] - g_marks[5], g_marks[7] - g_marks[6], g_marks[8] - g_marks[7]);
+#endif
+                }
+            }
+        } else if (last_to_arrive(&L.status[6], n_wg, &s_last)) {
             chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat);
+        }
     }
 }
 

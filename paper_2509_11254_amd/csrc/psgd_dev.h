@@ -43,6 +43,7 @@ template <int BIT, class V> __device__ inline void st_stream(PSGD_GLOBAL V* p, V
     if constexpr ((PSGD_NT_MASK & BIT) != 0) __builtin_nontemporal_store(v, p); else *p = v;
 }
 
+constexpr int kStatusWords = 8 + 16; // per layer: 8 diagnostics and counters + one counter per Gram slot group
 constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kLenPad = 128;       // packed operand rows are padded (with zeros) to this multiple
 constexpr int kGramRows1 = 128;    // rows per partial Gram matrix written by a product's epilogue
@@ -98,10 +99,10 @@ struct LayerDev {
                             // row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right
     double* eval;           // [wmax]
-    int* status;            // [8] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits,
+    int* status;            // [kStatusWords] : rank_deficient, second-pass-needed flag, sigma_max bits, sigma_r bits,
                             //       iterations the next refresh needs (0 = not known yet), Jacobi sweeps of the last
-                            //       refresh, arrival counters of the two
-                            //       kernels that hand over to the factorisation
+                            //       refresh, arrival counters of the two kernels that hand over to the
+                            //       factorisation, then the arrival counters of the Gram slot groups
 };
 
 __host__ __device__ inline int side_of_role(int transposed, int role) {

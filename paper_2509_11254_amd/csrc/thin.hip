@@ -391,7 +391,7 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 // --------------------------------------------------------------------------------------------
 // Rayleigh-Ritz: eigen-decomposition of the w x w Gram matrix H = Y^T Y (Y = M^T Z, Z orthonormal)
 // by cyclic two-sided Jacobi in fp64 with a round-robin ordering (w/2 disjoint rotations per round).
-// One workgroup per layer.  H is kept as a packed upper triangle in LDS; in a round the 2 x 2 blocks
+// One workgroup per layer.  One copy of each entry of the symmetric H is kept in LDS (layout: sym_idx); in a round the 2 x 2 blocks
 // (pair k1 rows) x (pair k2 columns), k1 <= k2, are independent of each other and are rotated in
 // place.  The accumulated rotations V live in LDS when they fit, else in the layer's scratch matrix.
 // On exit tmat[:, k] is the eigenvector of the k-th largest eigenvalue, so that P~ = Z tmat[:, :r] are
@@ -399,10 +399,21 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 // sigma_1 and sigma_r = sqrt(eigenvalue), and the iteration count the next refresh needs.
 // --------------------------------------------------------------------------------------------
 constexpr int kJacobiMaxSweeps = 30;
+constexpr int kJacobiBlocksPerThread = 5;     // 2 x 2 blocks of H per thread: (w/2)(w/2 + 1)/2 blocks over the workgroup
 
-__device__ inline int sym_idx(int i, int j, int n) {          // packed upper triangle, any order of (i, j)
-    const int a = min(i, j), b = max(i, j);
-    return a * n - (a * (a - 1)) / 2 + (b - a);
+// Storage of the symmetric matrix H of even order n in LDS: n rows of S doubles, S the odd one of n / 2 + 1 and
+// n / 2 + 2; entry (i, j) lives in row i at column d = (j - i) mod n if d <= n / 2 (for d = n / 2 in the row of the
+// smaller index), otherwise it is entry (j, i) of row j.  About as many doubles as a packed triangle.  The lanes
+// of a rotation step hold neighbouring rotation pairs at a fixed distance, so the entries they touch together
+// move along a diagonal: by +-1 in both indices (address stride S) or by +1 and -1 (stride S - 2).  Both are
+// odd, so 32 lanes reading doubles fall on 32 different even banks; the packed triangle's strides vary with the
+// row and collide.
+__host__ __device__ inline int sym_stride(int n) { return (n / 2 + 1) | 1; }
+__device__ inline int sym_idx(int i, int j, int n) {
+    int d = j - i;
+    d += d < 0 ? n : 0;
+    const bool own = 2 * d < n || (2 * d == n && i < j);
+    return own ? i * sym_stride(n) + d : j * sym_stride(n) + (n - d);
 }
 
 // Rotation that annihilates H[p][q] for the pair number k of round rd (round-robin tournament on n players).
@@ -442,8 +453,8 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     extern __shared__ __align__(16) unsigned char smem[];
     double* csb = reinterpret_cast<double*>(smem);     // two buffers of [half] cos, [half] sin
     double* red = csb + 2 * n;                         // [2] reduction scratch
-    double* a = red + 2;                               // packed upper triangle of H, n(n+1)/2
-    double* v = a + (n * (n + 1)) / 2;                 // v_rows x n slice of the accumulated rotations
+    double* a = red + 2;                               // H, n rows of sym_stride(n) (see sym_idx)
+    double* v = a + n * sym_stride(n);                 // v_rows x n slice of the accumulated rotations
     int* pqb = reinterpret_cast<int*>(v + v_rows * n); // two buffers of [half] p, [half] q
     const int t = threadIdx.x;
     const int nt = blockDim.x;
@@ -460,19 +471,40 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     for (int i = ty; i < nv; i += tw)
         for (int j = tx; j < n; j += tw) v[i * n + j] = (row0 + i == j) ? 1.0 : 0.0;
     __syncthreads();
+    // The unordered pairs {k1, k2} of rotation pairs (k1 = k2 included), i.e. the 2 x 2 blocks of H that hold one
+    // stored copy each, dealt evenly to the threads once: block e is k1 = e mod half, k2 = k1 + e / half (mod half);
+    // the distances e / half = 0 .. half / 2 reach every pair once (the last distance, for even half, only from
+    // the lower k1).  A thread keeps its blocks for all rounds; which matrix rows they are changes with the round.
+    int bk1[kJacobiBlocksPerThread], bk2[kJacobiBlocksPerThread], n_blk = 0;
+    {
+        const int total = (half * (half + 1)) / 2;
+#pragma unroll
+        for (int b = 0; b < kJacobiBlocksPerThread; ++b) {
+            const int e = t + b * nt;
+            bk1[b] = 0; bk2[b] = 0;
+            if (e < total) {
+                const int dk = e / half, k1 = e - dk * half;
+                int k2 = k1 + dk;
+                k2 -= k2 >= half ? half : 0;
+                bk1[b] = k1; bk2[b] = k2;
+                n_blk = b + 1;
+            }
+        }
+    }
     int cur = 0, sweeps = 0;
+#ifdef PSGD_MARKS
+    const long long jt0 = wall_clock64();
+#endif
     for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
         // convergence: off-diagonal mass relative to the diagonal
         if (t < 2) red[t] = 0.0;
         __syncthreads();
         double off = 0.0, dia = 0.0;
-        for (int i = ty; i < n; i += tw) {
-            const int base = sym_idx(i, i, n) - i;
+        for (int i = ty; i < n; i += tw)
             for (int j = i + tx; j < n; j += tw) {
-                const double x = a[base + j];
+                const double x = a[sym_idx(i, j, n)];
                 if (i == j) dia += x * x; else off += 2.0 * x * x;
             }
-        }
         for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
         if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
         __syncthreads();
@@ -484,32 +516,33 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         for (int rd = 0; rd < n - 1; ++rd) {
             const double* cs = csb + cur * n;
             const int* pq = pqb + cur * n;
-            // H <- J^T H J on the 2 x 2 blocks k1 <= k2 (the others are their transposes)
-            for (int k1 = ty; k1 < half; k1 += tw) {
+            // H <- J^T H J on this thread's 2 x 2 blocks (pair k1 rows) x (pair k2 columns)
+#pragma unroll
+            for (int b = 0; b < kJacobiBlocksPerThread; ++b) {
+                if (b >= n_blk) break;
+                const int k1 = bk1[b], k2 = bk2[b];
                 const int p1 = pq[k1], q1 = pq[half + k1];
                 const double c1 = cs[k1], s1 = cs[half + k1];
-                for (int k2 = k1 + tx; k2 < half; k2 += tw) {
-                    if (k1 == k2) {
-                        const int ipp = sym_idx(p1, p1, n), ipq = sym_idx(p1, q1, n), iqq = sym_idx(q1, q1, n);
-                        const double app = a[ipp], apq = a[ipq], aqq = a[iqq];
-                        a[ipp] = c1 * c1 * app - 2.0 * c1 * s1 * apq + s1 * s1 * aqq;
-                        a[iqq] = s1 * s1 * app + 2.0 * c1 * s1 * apq + c1 * c1 * aqq;
-                        a[ipq] = (c1 * c1 - s1 * s1) * apq + c1 * s1 * (app - aqq);
-                    } else {
-                        const int p2 = pq[k2], q2 = pq[half + k2];
-                        const double c2 = cs[k2], s2 = cs[half + k2];
-                        const int i00 = sym_idx(p1, p2, n), i01 = sym_idx(p1, q2, n);
-                        const int i10 = sym_idx(q1, p2, n), i11 = sym_idx(q1, q2, n);
-                        const double app = a[i00], apq = a[i01], aqp = a[i10], aqq = a[i11];
-                        // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
-                        const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
-                        const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
-                        // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
-                        a[i00] = c2 * rpp - s2 * rpq;
-                        a[i01] = s2 * rpp + c2 * rpq;
-                        a[i10] = c2 * rqp - s2 * rqq;
-                        a[i11] = s2 * rqp + c2 * rqq;
-                    }
+                if (k1 == k2) {
+                    const int ipp = sym_idx(p1, p1, n), ipq = sym_idx(p1, q1, n), iqq = sym_idx(q1, q1, n);
+                    const double app = a[ipp], apq = a[ipq], aqq = a[iqq];
+                    a[ipp] = c1 * c1 * app - 2.0 * c1 * s1 * apq + s1 * s1 * aqq;
+                    a[iqq] = s1 * s1 * app + 2.0 * c1 * s1 * apq + c1 * c1 * aqq;
+                    a[ipq] = (c1 * c1 - s1 * s1) * apq + c1 * s1 * (app - aqq);
+                } else {
+                    const int p2 = pq[k2], q2 = pq[half + k2];
+                    const double c2 = cs[k2], s2 = cs[half + k2];
+                    const int i00 = sym_idx(p1, p2, n), i01 = sym_idx(p1, q2, n);
+                    const int i10 = sym_idx(q1, p2, n), i11 = sym_idx(q1, q2, n);
+                    const double app = a[i00], apq = a[i01], aqp = a[i10], aqq = a[i11];
+                    // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
+                    const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
+                    const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
+                    // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
+                    a[i00] = c2 * rpp - s2 * rpq;
+                    a[i01] = s2 * rpp + c2 * rpq;
+                    a[i10] = c2 * rqp - s2 * rqq;
+                    a[i11] = s2 * rqp + c2 * rqq;
                 }
             }
             __syncthreads();
@@ -528,6 +561,9 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         }
     }
     __syncthreads();
+#ifdef PSGD_MARKS
+    if (t == 0 && blockIdx.x == 0) printf("jacobi marks n=%d sweeps=%d loop %lld (10 ns) nv=%d threads=%d\n", n, sweeps, wall_clock64() - jt0, nv, nt);
+#endif
     // sort: rank of eigenvalue j = number of eigenvalues that come before it (ties by index)
     int* rank_of = pqb;
     double* __restrict__ tm = L.tmat;
@@ -572,7 +608,7 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
 
 size_t jacobi_lds_bytes(int w, int v_rows) {
     const int n = (w + 1) & ~1;
-    return (size_t)(2 * n + 2 + (n * (n + 1)) / 2 + v_rows * n) * sizeof(double) + (size_t)2 * n * sizeof(int);
+    return (size_t)(2 * n + 2 + n * sym_stride(n) + v_rows * n) * sizeof(double) + (size_t)2 * n * sizeof(int);
 }
 
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
@@ -590,6 +626,8 @@ hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int 
     v_rows = v_rows > n ? n : v_rows;
     const size_t lds = jacobi_lds_bytes(w, v_rows);
     dim3 grid((n + v_rows - 1) / v_rows, n_ids), block(w > 48 ? 1024 : 256);
+    const int n_blocks = ((n / 2) * (n / 2 + 1)) / 2;
+    if ((n_blocks + (int)block.x - 1) / (int)block.x > kJacobiBlocksPerThread) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);

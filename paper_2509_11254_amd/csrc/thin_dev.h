@@ -18,6 +18,12 @@ namespace psgd {
 // status[1] is set and the pass-2 code (which exits at once otherwise) does its work.
 constexpr double kSecondPassPivot = 1e-6;
 constexpr int kCholMaxGroups = 8;
+#ifdef PSGD_MARKS
+static __device__ long long g_marks[16];
+#define PSGD_MARK(i) do { __syncthreads(); if (threadIdx.x == 0) g_marks[i] = wall_clock64(); } while (0)
+#else
+#define PSGD_MARK(i) do { } while (0)
+#endif
 constexpr int kCholRegWidth = 16;      // widths up to this are factorised by one wavefront in registers
 
 // slot groups that sum the partial Gram matrices side by side (all kThreads threads busy for small w)
@@ -229,11 +235,14 @@ __device__ inline bool local_chol(const LayerDev& L, int role, int local_ok) {
 template <bool NARROW = false>
 __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int pass, int slot_rows, bool allow2,
                                  unsigned char* smem, double* tm, bool write_status = true,
-                                 int* need2_out = nullptr) {
+                                 int* need2_out = nullptr, int slot_stride = 1) {
     const int side = side_of_role(L.transposed, role);
-    const int n_slots = (side_len(L, side) + slot_rows - 1) / slot_rows;
+    // slot_stride > 1: the slots were already added up in groups of that many, each sum left in its group's
+    // first slot (sum_slot_groups); what remains is one matrix per group
+    const int n_slots = (side_len(L, side) + slot_rows * slot_stride - 1) / (slot_rows * slot_stride);
     const int w = L.thin[role].width;
     const int ntri = (w * (w + 1)) / 2;
+    const int64_t sstr = (int64_t)slot_stride * ntri;      // distance between the matrices to add
     const int G = chol_groups(w);
     double* a = reinterpret_cast<double*>(smem);          // packed upper triangle
     double* ps = a + ntri;                                // [G][ntri] partial slot sums (G > 1)
@@ -257,7 +266,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
 #pragma unroll
                 for (int d = 0; d < 16; ++d) {
                     const int sd = sl + d * G;
-                    x[d] = gram[(int64_t)(sd < n_slots ? sd : g) * ntri + e];
+                    x[d] = gram[(int64_t)(sd < n_slots ? sd : g) * sstr + e];
                 }
 #pragma unroll
                 for (int d = 0; d < 16; ++d)
@@ -291,8 +300,8 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
                     doublex2 x[16], y[16];
 #pragma unroll
                     for (int d = 0; d < 16; ++d) {
-                        x[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)(sl + d) * ntri);
-                        y[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)(sl + d) * ntri);
+                        x[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)(sl + d) * sstr);
+                        y[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)(sl + d) * sstr);
                     }
 #pragma unroll
                     for (int d = 0; d < 16; d += 4) {
@@ -301,8 +310,8 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
                     }
                 }
                 for (; sl < n_slots; ++sl) {
-                    p0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)sl * ntri);
-                    q0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)sl * ntri);
+                    p0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)sl * sstr);
+                    q0 += *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g1 + (int64_t)sl * sstr);
                 }
                 const doublex2 ps2 = (p0 + p1) + (p2 + p3), qs2 = (q0 + q1) + (q2 + q3);
                 a[e] = ps2.x; a[e + 1] = ps2.y;
@@ -316,16 +325,17 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
                 for (; sl + 16 <= n_slots; sl += 16) {
                     double x[16];
 #pragma unroll
-                    for (int d = 0; d < 16; ++d) x[d] = g0[(int64_t)(sl + d) * ntri];
+                    for (int d = 0; d < 16; ++d) x[d] = g0[(int64_t)(sl + d) * sstr];
 #pragma unroll
                     for (int d = 0; d < 16; d += 4) { p0 += x[d]; p1 += x[d + 1]; p2 += x[d + 2]; p3 += x[d + 3]; }
                 }
-                for (; sl < n_slots; ++sl) p0 += g0[(int64_t)sl * ntri];
+                for (; sl < n_slots; ++sl) p0 += g0[(int64_t)sl * sstr];
                 a[e] = (p0 + p1) + (p2 + p3);
             }
         }
     }
     __syncthreads();
+    PSGD_MARK(5);
     if (w <= kCholRegWidth) {
         if (t < 64) chol_in_registers(L, a, w, tol2, pass, allow2, tm, write_status, need2_out);
         return;
@@ -424,6 +434,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     }
+    PSGD_MARK(6);
     // inverse T of the upper-triangular factor, in place in the packed triangle (T_jj = 1 / R_jj is in rdiag):
     //   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
     if (!blocked) {
@@ -483,6 +494,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     }
+    PSGD_MARK(7);
     for (int i = ty; i < w; i += 16) {
         const int base = tri_idx(i, i, w) - i;
         for (int j = tx; j < w; j += 16) {
@@ -524,6 +536,49 @@ __device__ inline bool last_to_arrive(int* counter, int n_wg, int* flag) {
         if (threadIdx.x == 0) *counter = 0;
     }
     return last;
+}
+
+// Partial Gram matrices added up in two levels, so that no workgroup has to read all of them: the slots form
+// groups of kSlotGroup; the workgroup that completes a group adds the group's slots into the first one (fixed
+// order), and the one that completes the last group goes on with one matrix per group.  Used where one
+// workgroup per slot runs anyway and the matrices are large (width above the register path, many slots).
+constexpr int kSlotGroup = 8;
+constexpr int kMaxSlotGroups = 16;      // arrival counters per layer
+__device__ inline bool grouped_slot_sum(int w, int n_slots) {
+    return w > kCholRegWidth && n_slots >= 2 * kSlotGroup && n_slots <= kSlotGroup * kMaxSlotGroups;
+}
+// Called by all threads of the workgroup that completed group `grp`: slot first <- sum of the group's slots.
+__device__ inline void sum_slot_group(double* gram, int w, int n_slots, int grp) {
+    typedef double doublex2 __attribute__((ext_vector_type(2)));
+    const int ntri = (w * (w + 1)) / 2;
+    const int first = grp * kSlotGroup;
+    const int cnt = min(kSlotGroup, n_slots - first);
+    PSGD_GLOBAL double* g0 = as_global(gram) + (int64_t)first * ntri;
+    const int t = threadIdx.x, nt = blockDim.x;
+    if ((ntri & 1) == 0 && cnt == kSlotGroup) {
+        // two 16-byte entries x 8 slots in flight per thread
+        for (int e = 2 * t; e < ntri; e += 4 * nt) {
+            const bool two = e + 2 * nt < ntri;
+            const int e2 = two ? e + 2 * nt : e;
+            doublex2 x[kSlotGroup], y[kSlotGroup];
+#pragma unroll
+            for (int d = 0; d < kSlotGroup; ++d) {
+                x[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)d * ntri + e);
+                y[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)d * ntri + e2);
+            }
+            doublex2 sx = x[0], sy = y[0];
+#pragma unroll
+            for (int d = 1; d < kSlotGroup; ++d) { sx += x[d]; sy += y[d]; }
+            *reinterpret_cast<PSGD_GLOBAL doublex2*>(g0 + e) = sx;
+            if (two) *reinterpret_cast<PSGD_GLOBAL doublex2*>(g0 + e2) = sy;
+        }
+    } else {
+        for (int e = t; e < ntri; e += nt) {
+            double sacc = g0[e];
+            for (int d = 1; d < cnt; ++d) sacc += g0[(int64_t)d * ntri + e];
+            g0[e] = sacc;
+        }
+    }
 }
 
 }  // namespace psgd
