@@ -399,7 +399,6 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 // sigma_1 and sigma_r = sqrt(eigenvalue), and the iteration count the next refresh needs.
 // --------------------------------------------------------------------------------------------
 constexpr int kJacobiMaxSweeps = 30;
-constexpr int kJacobiBlocksPerThread = 5;     // 2 x 2 blocks of H per thread: (w/2)(w/2 + 1)/2 blocks over the workgroup
 
 // Storage of the symmetric matrix H of even order n in LDS: n rows of S doubles, S the odd one of n / 2 + 1 and
 // n / 2 + 2; entry (i, j) lives in row i at column d = (j - i) mod n if d <= n / 2 (for d = n / 2 in the row of the
@@ -413,33 +412,70 @@ __device__ inline int sym_idx(int i, int j, int n) {
     int d = j - i;
     d += d < 0 ? n : 0;
     const bool own = 2 * d < n || (2 * d == n && i < j);
-    return own ? i * sym_stride(n) + d : j * sym_stride(n) + (n - d);
+    return own ? __mul24(i, sym_stride(n)) + d : __mul24(j, sym_stride(n)) + (n - d);      // (24-bit multiply: full rate)
 }
 
-// Rotation that annihilates H[p][q] for the pair number k of round rd (round-robin tournament on n players).
+// The round-robin tournament on n players (n even): n / 2 slots, slot k pairs the players at positions 2k ("top")
+// and 2k + 1 ("bottom").  Position 0 keeps its player; after every round the others move one place round the ring
+// top[1] -> bottom[0] -> bottom[1] -> ... -> bottom[n/2 - 1] -> top[n/2 - 1] -> ... -> top[2] -> top[1].
+// In round rd the players (matrix indices) in slot k are
+//   top: n - 1 for k = 0, else (rd + k) mod (n - 1);   bottom: (rd - k) mod (n - 1),
+// and after n - 1 rounds everybody is back where round 0 had them.
+__device__ inline int jacobi_next_pos(int x, int n) {
+    const int half = n / 2, k = x >> 1;
+    if (x == 0 || n <= 2) return x;
+    if ((x & 1) == 0) return k == 1 ? 1 : x - 2;            // top[k] -> top[k - 1], top[1] -> bottom[0]
+    return k == half - 1 ? n - 2 : x + 2;                   // bottom[k] -> bottom[k + 1], the last one -> top[half - 1]
+}
+__device__ inline int jacobi_top(int k, int rd, int n) {
+    if (k == 0) return n - 1;
+    const int p = rd + k;
+    return p >= n - 1 ? p - (n - 1) : p;
+}
+__device__ inline int jacobi_bottom(int k, int rd, int n) {
+    const int q = rd - k;
+    return q < 0 ? q + (n - 1) : q;
+}
+// position in round 0 of matrix index j (inverse of jacobi_top / jacobi_bottom at rd = 0)
+__device__ inline int jacobi_pos0(int j, int n) {
+    const int half = n / 2;
+    if (j == n - 1) return 0;
+    if (j == 0) return 1;
+    return j < half ? 2 * j : 2 * (n - 1 - j) + 1;
+}
+
+// Rotation that annihilates the off-diagonal entry of slot k's 2 x 2 diagonal block (H is stored by position);
+// also notes which columns of V the slot holds in round rd.
 __device__ inline void jacobi_rotation(const double* a, int n, int rd, int k, double* cs, int* pq) {
     const int half = n / 2;
-    int p, q;
-    if (k == 0) { p = n - 1; q = rd; }
-    else {
-        p = rd + k; if (p >= n - 1) p -= n - 1;
-        q = rd - k; if (q < 0) q += n - 1;
-    }
-    if (p > q) { const int tmp = p; p = q; q = tmp; }
-    const double app = a[sym_idx(p, p, n)], aqq = a[sym_idx(q, q, n)], apq = a[sym_idx(p, q, n)];
+    const double app = a[sym_idx(2 * k, 2 * k, n)], aqq = a[sym_idx(2 * k + 1, 2 * k + 1, n)];
+    const double apq = a[sym_idx(2 * k, 2 * k + 1, n)];
     double c = 1.0, sn = 0.0;
     if (fabs(apq) > 1e-300 && apq * apq > 1e-36 * fabs(app * aqq)) {
         // t = sgn(tau) / (|tau| + sqrt(1 + tau^2)), tau = (aqq - app) / (2 apq), written with one division
+        // (square root and quotient from the hardware estimates with Newton steps: this sits on the critical path
+        // of every round.  b^2 is a normal number by the test above.)
         const double d = aqq - app, b = 2.0 * apq;
-        const double tt = (d >= 0.0 ? b : -b) / (fabs(d) + sqrt(d * d + b * b));
-        c = rsqrt(1.0 + tt * tt);
+        const double h2 = __builtin_fma(d, d, b * b);
+        const double tt = (d >= 0.0 ? b : -b) * rcp_nr(fabs(d) + h2 * rsqrt_nr(h2));
+        c = rsqrt_nr(__builtin_fma(tt, tt, 1.0));
         sn = tt * c;
     }
-    cs[k] = c; cs[half + k] = sn; pq[k] = p; pq[half + k] = q;
+    cs[k] = c; cs[half + k] = sn;
+    pq[k] = jacobi_top(k, rd, n); pq[half + k] = jacobi_bottom(k, rd, n);
 }
 
 // grid = (slices, layers): every workgroup of a layer repeats the (deterministic) iteration on H and
 // accumulates the rotations into its own slice of v_rows rows of V, which is independent of the other rows.
+//
+// H is stored by POSITION in the tournament, not by matrix index: the 2 x 2 block (slot k1) x (slot k2) sits at
+// the same LDS addresses in every round, is rotated by the two slots' rotations, and its four entries are written
+// to where the tournament moves their row and column players.  Source and destination addresses of a thread's
+// blocks are therefore computed once; a round is: read and rotate (registers) | barrier | write | barrier | the
+// next rotations from the diagonal blocks, and V <- V J on the columns the slots hold | barrier.
+// V stays indexed by matrix index.
+// NBLK: 2 x 2 blocks of H per thread, at least (w/2)(w/2 + 1)/2 over the workgroup's threads.
+template <int NBLK>
 __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict__ layers,
                                                       const int* __restrict__ ids, int role, int v_rows,
                                                       float* __restrict__ sigma_out) {
@@ -455,53 +491,77 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     double* red = csb + 2 * n;                         // [2] reduction scratch
     double* a = red + 2;                               // H, n rows of sym_stride(n) (see sym_idx)
     double* v = a + n * sym_stride(n);                 // v_rows x n slice of the accumulated rotations
-    int* pqb = reinterpret_cast<int*>(v + v_rows * n); // two buffers of [half] p, [half] q
+    int* pqb = reinterpret_cast<int*>(v + v_rows * n); // two buffers of [half] top, [half] bottom matrix indices
     const int t = threadIdx.x;
     const int nt = blockDim.x;
-    const int tw = nt >= 1024 ? 32 : 16;               // threads as a tw x tw grid: no integer division
-    const int tx = t & (tw - 1), ty = t / tw;
-    // H = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue
-    for (int i = ty; i < n; i += tw)
-        for (int j = i + tx; j < n; j += tw) {
-            double s = 0.0;
-            if (j < w)
-                for (int sp = 0; sp < n_slots; ++sp) s += L.gram[(int64_t)sp * ((w * (w + 1)) / 2) + tri_idx(i, j, w)];
-            a[sym_idx(i, j, n)] = s;
+    const int txw = nt >= 512 ? 32 : 16, tyw = nt / txw;   // threads as a tyw x txw grid: no integer division
+    const int tx = t & (txw - 1), ty = t / txw;
+    // H = sum of the partial Gram matrices (upper triangle) left by the last product's epilogue, entry
+    // (position x, position y) = H of the matrix indices that round 0 puts there
+    const int ntri = (w * (w + 1)) / 2;
+    for (int x = ty; x < n; x += tyw) {
+        const int k = x >> 1, i = (x & 1) ? jacobi_bottom(k, 0, n) : jacobi_top(k, 0, n);
+        for (int y = x + tx; y < n; y += txw) {
+            const int ky = y >> 1, j = (y & 1) ? jacobi_bottom(ky, 0, n) : jacobi_top(ky, 0, n);
+            double s0 = 0.0, s1 = 0.0, s2 = 0.0, s3 = 0.0;
+            if (i < w && j < w) {
+                const double* g = L.gram + tri_idx(min(i, j), max(i, j), w);
+                int sp = 0;
+                for (; sp + 4 <= n_slots; sp += 4) {
+                    s0 += g[(int64_t)sp * ntri]; s1 += g[(int64_t)(sp + 1) * ntri];
+                    s2 += g[(int64_t)(sp + 2) * ntri]; s3 += g[(int64_t)(sp + 3) * ntri];
+                }
+                for (; sp < n_slots; ++sp) s0 += g[(int64_t)sp * ntri];
+            }
+            a[sym_idx(x, y, n)] = (s0 + s1) + (s2 + s3);
         }
-    for (int i = ty; i < nv; i += tw)
-        for (int j = tx; j < n; j += tw) v[i * n + j] = (row0 + i == j) ? 1.0 : 0.0;
-    __syncthreads();
-    // The unordered pairs {k1, k2} of rotation pairs (k1 = k2 included), i.e. the 2 x 2 blocks of H that hold one
-    // stored copy each, dealt evenly to the threads once: block e is k1 = e mod half, k2 = k1 + e / half (mod half);
-    // the distances e / half = 0 .. half / 2 reach every pair once (the last distance, for even half, only from
-    // the lower k1).  A thread keeps its blocks for all rounds; which matrix rows they are changes with the round.
-    int bk1[kJacobiBlocksPerThread], bk2[kJacobiBlocksPerThread], n_blk = 0;
+    }
+    for (int i = ty; i < nv; i += tyw)
+        for (int j = tx; j < n; j += txw) v[i * n + j] = (row0 + i == j) ? 1.0 : 0.0;
+    // The unordered pairs {k1, k2} of slots (k1 = k2 included), i.e. the 2 x 2 blocks of H that hold one stored
+    // copy each, dealt evenly to the threads once: block e is k1 = e mod half, k2 = k1 + e / half (mod half); the
+    // distances e / half = 0 .. half / 2 reach every pair once (the last distance, for even half, only from the
+    // lower k1).  Per entry: source address | destination address << 16 (both below 2^16 doubles).
+    int bk[NBLK], n_blk = 0;                                   // k1 | k2 << 8
+    unsigned adr[NBLK][4];
     {
         const int total = (half * (half + 1)) / 2;
 #pragma unroll
-        for (int b = 0; b < kJacobiBlocksPerThread; ++b) {
+        for (int b = 0; b < NBLK; ++b) {
             const int e = t + b * nt;
-            bk1[b] = 0; bk2[b] = 0;
+            bk[b] = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) adr[b][q] = 0;
             if (e < total) {
                 const int dk = e / half, k1 = e - dk * half;
                 int k2 = k1 + dk;
                 k2 -= k2 >= half ? half : 0;
-                bk1[b] = k1; bk2[b] = k2;
+                bk[b] = k1 | (k2 << 8);
                 n_blk = b + 1;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    // entry q of the block: row 2 k1 + (q >> 1), column 2 k2 + (q & 1); a diagonal block's entry 2
+                    // (bottom, top) is the stored entry 1 again and is left out when the block is written
+                    const int x = 2 * k1 + (q >> 1), y = 2 * k2 + (q & 1);
+                    adr[b][q] = (unsigned)sym_idx(x, y, n) |
+                                ((unsigned)sym_idx(jacobi_next_pos(x, n), jacobi_next_pos(y, n), n) << 16);
+                }
             }
         }
     }
+    __syncthreads();
     int cur = 0, sweeps = 0;
 #ifdef PSGD_MARKS
     const long long jt0 = wall_clock64();
+    long long jph1 = 0, jph2 = 0;
 #endif
     for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
         // convergence: off-diagonal mass relative to the diagonal
         if (t < 2) red[t] = 0.0;
         __syncthreads();
         double off = 0.0, dia = 0.0;
-        for (int i = ty; i < n; i += tw)
-            for (int j = i + tx; j < n; j += tw) {
+        for (int i = ty; i < n; i += tyw)
+            for (int j = i + tx; j < n; j += txw) {
                 const double x = a[sym_idx(i, j, n)];
                 if (i == j) dia += x * x; else off += 2.0 * x * x;
             }
@@ -514,42 +574,56 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         if (t < half) jacobi_rotation(a, n, 0, t, csb + cur * n, pqb + cur * n);
         __syncthreads();
         for (int rd = 0; rd < n - 1; ++rd) {
+#ifdef PSGD_MARKS
+            const long long jt00 = wall_clock64();
+#endif
             const double* cs = csb + cur * n;
             const int* pq = pqb + cur * n;
-            // H <- J^T H J on this thread's 2 x 2 blocks (pair k1 rows) x (pair k2 columns)
+            // H <- J^T H J on this thread's blocks: rows by slot k1's rotation, columns by slot k2's
+            double o[NBLK][4];
 #pragma unroll
-            for (int b = 0; b < kJacobiBlocksPerThread; ++b) {
+            for (int b = 0; b < NBLK; ++b) {
                 if (b >= n_blk) break;
-                const int k1 = bk1[b], k2 = bk2[b];
-                const int p1 = pq[k1], q1 = pq[half + k1];
+                const int k1 = bk[b] & 0xff, k2 = bk[b] >> 8;
                 const double c1 = cs[k1], s1 = cs[half + k1];
+                const double app = a[adr[b][0] & 0xffffu], apq = a[adr[b][1] & 0xffffu];
+                const double aqp = a[adr[b][2] & 0xffffu], aqq = a[adr[b][3] & 0xffffu];
                 if (k1 == k2) {
-                    const int ipp = sym_idx(p1, p1, n), ipq = sym_idx(p1, q1, n), iqq = sym_idx(q1, q1, n);
-                    const double app = a[ipp], apq = a[ipq], aqq = a[iqq];
-                    a[ipp] = c1 * c1 * app - 2.0 * c1 * s1 * apq + s1 * s1 * aqq;
-                    a[iqq] = s1 * s1 * app + 2.0 * c1 * s1 * apq + c1 * c1 * aqq;
-                    a[ipq] = (c1 * c1 - s1 * s1) * apq + c1 * s1 * (app - aqq);
+                    // (aqp is apq here)
+                    o[b][0] = c1 * c1 * app - 2.0 * c1 * s1 * apq + s1 * s1 * aqq;
+                    o[b][1] = (c1 * c1 - s1 * s1) * apq + c1 * s1 * (app - aqq);
+                    o[b][2] = 0.0;
+                    o[b][3] = s1 * s1 * app + 2.0 * c1 * s1 * apq + c1 * c1 * aqq;
                 } else {
-                    const int p2 = pq[k2], q2 = pq[half + k2];
                     const double c2 = cs[k2], s2 = cs[half + k2];
-                    const int i00 = sym_idx(p1, p2, n), i01 = sym_idx(p1, q2, n);
-                    const int i10 = sym_idx(q1, p2, n), i11 = sym_idx(q1, q2, n);
-                    const double app = a[i00], apq = a[i01], aqp = a[i10], aqq = a[i11];
-                    // rows: (p1, q1) <- (c1 p1 - s1 q1, s1 p1 + c1 q1)
+                    // rows: (top, bottom) <- (c1 top - s1 bottom, s1 top + c1 bottom)
                     const double rpp = c1 * app - s1 * aqp, rpq = c1 * apq - s1 * aqq;
                     const double rqp = s1 * app + c1 * aqp, rqq = s1 * apq + c1 * aqq;
-                    // columns: (p2, q2) <- (c2 p2 - s2 q2, s2 p2 + c2 q2)
-                    a[i00] = c2 * rpp - s2 * rpq;
-                    a[i01] = s2 * rpp + c2 * rpq;
-                    a[i10] = c2 * rqp - s2 * rqq;
-                    a[i11] = s2 * rqp + c2 * rqq;
+                    // columns: likewise with slot k2's rotation
+                    o[b][0] = c2 * rpp - s2 * rpq;
+                    o[b][1] = s2 * rpp + c2 * rpq;
+                    o[b][2] = c2 * rqp - s2 * rqq;
+                    o[b][3] = s2 * rqp + c2 * rqq;
                 }
             }
             __syncthreads();
+#pragma unroll
+            for (int b = 0; b < NBLK; ++b) {
+                if (b >= n_blk) break;
+                const bool diag = (bk[b] & 0xff) == (bk[b] >> 8);
+                a[adr[b][0] >> 16] = o[b][0];
+                a[adr[b][1] >> 16] = o[b][1];
+                if (!diag) a[adr[b][2] >> 16] = o[b][2];
+                a[adr[b][3] >> 16] = o[b][3];
+            }
+            __syncthreads();
+#ifdef PSGD_MARKS
+            const long long jt1 = wall_clock64();
+#endif
             // the next round's rotations (from the updated H) while the other waves finish V <- V J
             if (rd + 1 < n - 1 && t < half) jacobi_rotation(a, n, rd + 1, t, csb + (cur ^ 1) * n, pqb + (cur ^ 1) * n);
-            for (int i = ty; i < nv; i += tw)
-                for (int k = tx; k < half; k += tw) {
+            for (int i = ty; i < nv; i += tyw)
+                for (int k = tx; k < half; k += txw) {
                     const int p = pq[k], q = pq[half + k];
                     const double c = cs[k], sn = cs[half + k];
                     const double vx = v[i * n + p], vy = v[i * n + q];
@@ -557,30 +631,38 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
                     v[i * n + q] = sn * vx + c * vy;
                 }
             __syncthreads();
+#ifdef PSGD_MARKS
+            jph1 += jt1 - jt00; jph2 += wall_clock64() - jt1;
+#endif
             cur ^= 1;
         }
     }
     __syncthreads();
 #ifdef PSGD_MARKS
-    if (t == 0 && blockIdx.x == 0) printf("jacobi marks n=%d sweeps=%d loop %lld (10 ns) nv=%d threads=%d\n", n, sweeps, wall_clock64() - jt0, nv, nt);
+    if (t == 0 && blockIdx.x == 0) printf("jacobi marks n=%d sweeps=%d loop %lld (10 ns) nv=%d threads=%d phase1 %lld phase2 %lld\n", n, sweeps, wall_clock64() - jt0, nv, nt, jph1, jph2);
 #endif
+    // eigenvalue of matrix index j (= column j of V): the diagonal entry at the position round 0 gives j, where
+    // every sweep ends
+    double* lam = csb;                                 // [n], the rotation buffers are free now
+    for (int j = t; j < n; j += nt) { const int x = jacobi_pos0(j, n); lam[j] = a[sym_idx(x, x, n)]; }
+    __syncthreads();
     // sort: rank of eigenvalue j = number of eigenvalues that come before it (ties by index)
     int* rank_of = pqb;
     double* __restrict__ tm = L.tmat;
     for (int j = t; j < w; j += nt) {
-        const double lj = a[sym_idx(j, j, n)];
+        const double lj = lam[j];
         int rank = 0;
         for (int k = 0; k < w; ++k) {
-            const double lk = a[sym_idx(k, k, n)];
+            const double lk = lam[k];
             rank += (lk > lj || (lk == lj && k < j)) ? 1 : 0;
         }
         rank_of[j] = rank;     // 2n entries available
         if (blockIdx.x == 0) L.eval[rank] = lj;
     }
     __syncthreads();
-    for (int i = ty; i < nv; i += tw)
+    for (int i = ty; i < nv; i += tyw)
         if (row0 + i < w)
-            for (int j = tx; j < w; j += tw) tm[(int64_t)(row0 + i) * w + rank_of[j]] = v[i * n + j];
+            for (int j = tx; j < w; j += txw) tm[(int64_t)(row0 + i) * w + rank_of[j]] = v[i * n + j];
     if (blockIdx.x != 0) return;
     const int r = L.r;
     for (int k = t; k < r; k += nt) {
@@ -625,15 +707,28 @@ hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int 
     if (jacobi_lds_bytes(w, v_rows) > kLdsCap) return hipErrorInvalidValue;
     v_rows = v_rows > n ? n : v_rows;
     const size_t lds = jacobi_lds_bytes(w, v_rows);
-    dim3 grid((n + v_rows - 1) / v_rows, n_ids), block(w > 48 ? 1024 : 256);
     const int n_blocks = ((n / 2) * (n / 2 + 1)) / 2;
-    if ((n_blocks + (int)block.x - 1) / (int)block.x > kJacobiBlocksPerThread) return hipErrorInvalidValue;
+    // 256 threads for narrow blocks (the rounds are latency-bound there), else 1024.  (With three to five blocks
+    // per thread the kernel spills a few registers; 512 threads with twice the registers measured slower.)
+    const int threads = w <= 48 ? 256 : 1024;
+    dim3 grid((n + v_rows - 1) / v_rows, n_ids), block(threads);
+    const int per_thread = (n_blocks + threads - 1) / threads;
+    void (*kfn)(const LayerDev*, const int*, int, int, float*) = nullptr;
+    switch (per_thread) {
+        case 1: kfn = jacobi_kernel<1>; break;
+        case 2: kfn = jacobi_kernel<2>; break;
+        case 3: kfn = jacobi_kernel<3>; break;
+        case 4: kfn = jacobi_kernel<4>; break;
+        case 5: kfn = jacobi_kernel<5>; break;
+        default: break;
+    }
+    if (!kfn) return hipErrorInvalidValue;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(jacobi_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(jacobi_kernel, grid, block, lds, st, layers, ids, role, v_rows, sigma_out);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, role, v_rows, sigma_out);
     return hipGetLastError();
 }
 

@@ -71,6 +71,14 @@ __device__ inline double rsqrt_nr(double x) {
     return y;
 }
 
+// 1 / x for finite normal x: hardware estimate refined by two Newton steps (full fp64 accuracy)
+__device__ inline double rcp_nr(double x) {
+    double y = __builtin_amdgcn_rcp(x);
+#pragma unroll
+    for (int it = 0; it < 2; ++it) y = __builtin_fma(__builtin_fma(-x, y, 1.0), y, y);
+    return y;
+}
+
 // Ordering point for LDS traffic inside one wavefront (its LDS accesses execute in program order; this
 // keeps the compiler from moving them across).
 __device__ inline void wave_sync() {
