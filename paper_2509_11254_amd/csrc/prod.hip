@@ -658,7 +658,6 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     float* otile = reinterpret_cast<float*>(smem);    // [BT][cp + 1]
     const int tw = cp + 1;
     const int t = threadIdx.x;
-    PSGD_MARK(0);
     for (int e = t; e < BT * cp; e += kThreads) otile[(e / cp) * tw + e % cp] = 0.f;
     __syncthreads();
     const int64_t plane = (int64_t)out_lenP * T.width;
@@ -713,28 +712,17 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
         else reduce_items(std::integral_constant<int, 1>{}, 0, n_items);
     }
     __syncthreads();
-    PSGD_MARK(1);
     tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
-    PSGD_MARK(2);
     if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role, local_ok) && gate_open(L, chol_gate)) {
         const int n_wg = (out_len + BT - 1) / BT;      // = number of Gram slots (BT == kGramRows1)
         if (grouped_slot_sum(T.width, n_wg)) {
             const int grp = ob / kSlotGroup;
             const int in_grp = min(kSlotGroup, n_wg - grp * kSlotGroup);
             if (last_to_arrive(&L.status[8 + grp], in_grp, &s_last)) {
-                PSGD_MARK(3);
                 sum_slot_group(L.gram, T.width, n_wg, grp);
                 if (last_to_arrive(&L.status[6], (n_wg + kSlotGroup - 1) / kSlotGroup, &s_last)) {
-                    PSGD_MARK(4);
                     chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat, true, nullptr,
                               kSlotGroup);
-#ifdef PSGD_MARKS
-                    PSGD_MARK(8);
-                    if (threadIdx.x == 0)
-                        printf("finish marks w=%d (10 ns): reduce %lld epilogue %lld arrive %lld groupsum+arrive %lld slotsum %lld factor %lld inverse %lld write %lld\n",
-                               T.width, g_marks[1] - g_marks[0], g_marks[2] - g_marks[1], g_marks[3] - g_marks[2], g_marks[4] - g_marks[3],
-                               g_marks[5] - g_marks[4], g_marks[6] - g_marks[5], g_marks[7] - g_marks[6], g_marks[8] - g_marks[7]);
-#endif
                 }
             }
         } else if (last_to_arrive(&L.status[6], n_wg, &s_last)) {

@@ -551,10 +551,6 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     }
     __syncthreads();
     int cur = 0, sweeps = 0;
-#ifdef PSGD_MARKS
-    const long long jt0 = wall_clock64();
-    long long jph1 = 0, jph2 = 0;
-#endif
     for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
         // convergence: off-diagonal mass relative to the diagonal
         if (t < 2) red[t] = 0.0;
@@ -574,9 +570,6 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         if (t < half) jacobi_rotation(a, n, 0, t, csb + cur * n, pqb + cur * n);
         __syncthreads();
         for (int rd = 0; rd < n - 1; ++rd) {
-#ifdef PSGD_MARKS
-            const long long jt00 = wall_clock64();
-#endif
             const double* cs = csb + cur * n;
             const int* pq = pqb + cur * n;
             // H <- J^T H J on this thread's blocks: rows by slot k1's rotation, columns by slot k2's
@@ -617,9 +610,6 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
                 a[adr[b][3] >> 16] = o[b][3];
             }
             __syncthreads();
-#ifdef PSGD_MARKS
-            const long long jt1 = wall_clock64();
-#endif
             // the next round's rotations (from the updated H) while the other waves finish V <- V J
             if (rd + 1 < n - 1 && t < half) jacobi_rotation(a, n, rd + 1, t, csb + (cur ^ 1) * n, pqb + (cur ^ 1) * n);
             for (int i = ty; i < nv; i += tyw)
@@ -631,16 +621,10 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
                     v[i * n + q] = sn * vx + c * vy;
                 }
             __syncthreads();
-#ifdef PSGD_MARKS
-            jph1 += jt1 - jt00; jph2 += wall_clock64() - jt1;
-#endif
             cur ^= 1;
         }
     }
     __syncthreads();
-#ifdef PSGD_MARKS
-    if (t == 0 && blockIdx.x == 0) printf("jacobi marks n=%d sweeps=%d loop %lld (10 ns) nv=%d threads=%d phase1 %lld phase2 %lld\n", n, sweeps, wall_clock64() - jt0, nv, nt, jph1, jph2);
-#endif
     // eigenvalue of matrix index j (= column j of V): the diagonal entry at the position round 0 gives j, where
     // every sweep ends
     double* lam = csb;                                 // [n], the rotation buffers are free now

@@ -18,12 +18,6 @@ namespace psgd {
 // status[1] is set and the pass-2 code (which exits at once otherwise) does its work.
 constexpr double kSecondPassPivot = 1e-6;
 constexpr int kCholMaxGroups = 8;
-#ifdef PSGD_MARKS
-static __device__ long long g_marks[16];
-#define PSGD_MARK(i) do { __syncthreads(); if (threadIdx.x == 0) g_marks[i] = wall_clock64(); } while (0)
-#else
-#define PSGD_MARK(i) do { } while (0)
-#endif
 constexpr int kCholRegWidth = 16;      // widths up to this are factorised by one wavefront in registers
 
 // slot groups that sum the partial Gram matrices side by side (all kThreads threads busy for small w)
@@ -343,7 +337,6 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         }
     }
     __syncthreads();
-    PSGD_MARK(5);
     if (w <= kCholRegWidth) {
         if (t < 64) chol_in_registers(L, a, w, tol2, pass, allow2, tm, write_status, need2_out);
         return;
@@ -442,7 +435,6 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     }
-    PSGD_MARK(6);
     // inverse T of the upper-triangular factor, in place in the packed triangle (T_jj = 1 / R_jj is in rdiag):
     //   T_ij = -T_jj * sum_{l=i}^{j-1} T_il R_lj   (i < j; T_il already in place)
     if (!blocked) {
@@ -502,7 +494,6 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     }
-    PSGD_MARK(7);
     for (int i = ty; i < w; i += 16) {
         const int base = tri_idx(i, i, w) - i;
         for (int j = tx; j < w; j += 16) {
