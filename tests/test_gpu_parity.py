@@ -449,10 +449,11 @@ def test_widest_block_r150():
     assert orc.rel_fro(e2, out.e_mean) <= 1e-4
 
 
-@pytest.mark.parametrize("r", [1, 2, 3, 5, 13, 16, 20, 24, 40, 70, 100])
+@pytest.mark.parametrize("r", [1, 2, 3, 5, 13, 16, 20, 24, 40, 70, 84, 100, 128, 150])
 def test_rank_sweep_ssp_and_refresh(r):
     """Every width path of the thin kernels: odd and tiny ranks (the register factorisation at compiled widths
-    4, 8, 12, 16, non-vectorised thin rows), the LDS path, the blocked one with a ragged last block."""
+    4, 8, 12, 16, non-vectorised thin rows), the LDS path, the blocked one with a ragged last block; refresh block
+    widths 88, 112, 128, 160 and 192 take the Jacobi kernel through one to five 2 x 2 blocks per thread."""
     m, n = 640, 384
     sigma = np.concatenate([np.linspace(2.0, 1.0, r), 0.4 * 0.9 ** np.arange(40)])
     mat, u, v = synth.prescribed_svd_matrix(m, n, sigma, seed=100 + r, noise_std=1e-6)
