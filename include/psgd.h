@@ -136,6 +136,20 @@ size_t psgd_workspace_bytes(const psgd_ctx *ctx);
 int psgd_compress(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
                   float *const *E, float *const *Q, float *const *P);
 
+/* psgd_compress_project / psgd_compress_finish -- psgd_compress in the two halves between which a data-parallel job
+ * exchanges P (Algorithm 1, SSP-Comp: "P = mean of P^(i)" between the projection and the QR; Algorithm 2 keeps one
+ * error buffer e^(i) per node).  Each worker owns a context with n_workers = 1, its gradient and its e^(i):
+ *   project: M^(i) = G^(i) + e^(i) is stored over E;  P[l] <- M^(i) Q[l]  (m x r, not orthonormalised).
+ *   -- the caller averages P over the workers (an all-reduce) and hands every worker the mean --
+ *   finish:  P[l] <- P~ = QR(P[l]);  Q[l] <- M^(i)T P~;  E[l] <- e^(i)_{t+1} = M^(i) - P~ Q[l]^T.
+ *   -- the caller averages Q over the workers: Q_t --
+ * With one worker, project followed by finish is psgd_compress.  Same buffers, layouts and errors as psgd_compress;
+ * INVALID_ARG with lazy_residual, m_policy = 2 or power_iters > 1 (the halves assume M stored over E once). */
+int psgd_compress_project(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
+                          float *const *E, float *const *Q, float *const *P);
+int psgd_compress_finish(psgd_ctx *ctx, void *workspace, void *stream, float *const *E, float *const *Q,
+                         float *const *P);
+
 /* psgd_flush_residual -- with lazy_residual = 1: run the residual that the last psgd_compress left owed,
  * E[l] <- M_t - P~_t Q_t^T from the operand copies it put aside (Algorithm 2, error update), so that the E
  * buffers hold E_{t+1}.  Needed before the caller reads, replaces or checkpoints E, or drops the workspace.

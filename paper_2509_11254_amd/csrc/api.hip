@@ -26,6 +26,8 @@ hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* id
 hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
+hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
+                            hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
                        int cp, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
@@ -378,6 +380,16 @@ struct Launcher {
             note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, g2, a2, tol2, small, st));
         }
     }
+    // the same CholeskyQR2 on a thin[out_role] that the caller supplied: its Gram slots come from a pass of their own
+    void orth_given(int out_role, int w, double tol2, int cp) {
+        const bool small = w <= 16;
+        const int blocks = (max_lenP() + 127) / 128;
+        note(launch_thin_gram(layers, ids_all, n_all, blocks, out_role, cp, st));
+        note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 1, kGramRows1, -1, -1, small ? 1 : 0, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, -1, -1, tol2, small, st));
+        if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, -1, -2, 0, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, -1, -1, tol2, small, st));
+    }
     void residual(int nb, bool form = false) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
         note(launch_outer(nb, ctx->planes, false, form, false, layers, ids_all, n_all, tiles_outer, nullptr, 0, st));
@@ -647,6 +659,39 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     } else {
         L.residual(nb, re);                        // E <- M - P~ Q_t^T
     }
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+// The two halves of psgd_compress between which a data-parallel job averages P over its workers (and after which
+// it averages Q): each worker runs them on its own gradient and error buffer.
+int psgd_compress_project(psgd_ctx* ctx, void* workspace, void* stream, const void* const* G, float* const* E,
+                          float* const* Q, float* const* P) {
+    if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
+    if (ctx->lazy || ctx->reform_m || ctx->opt.power_iters > 1) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, G, E, Q, P);
+    if (rc != PSGD_OK) return rc;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.pack(ROLE_Q, cp);
+    L.prod(true, true, nb, ROLE_P, EPI_NONE);          // M = mean G + E stored over E;  P = M Q_{t-1}, as it is
+    if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    return PSGD_OK;
+}
+
+int psgd_compress_finish(psgd_ctx* ctx, void* workspace, void* stream, float* const* E, float* const* Q,
+                         float* const* P) {
+    if (!ctx || !E || !Q || !P) return PSGD_E_INVALID_ARG;
+    if (ctx->lazy || ctx->reform_m || ctx->opt.power_iters > 1) return PSGD_E_INVALID_ARG;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    int rc = bind_common(ctx, workspace, st, nullptr, E, Q, P);
+    if (rc != PSGD_OK) return rc;
+    Launcher L = batch_launcher(ctx, workspace, st);
+    const int cp = ctx->cpc, nb = cp / 32;
+    L.orth_given(ROLE_P, ctx->rmax, tol2_of(ctx), cp);  // P~ = QR(P), operand copies of P~
+    L.prod(false, false, nb, ROLE_Q, EPI_PACK);         // Q = M^T P~ (this worker's M), operand copies
+    L.residual(nb, false);                              // E <- M - P~ Q^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }

@@ -731,6 +731,45 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     }
 }
 
+// Partial Gram matrices of a thin matrix that did not come out of one of these products (the averaged P of a
+// data-parallel step, handed back by the caller): one workgroup per 128 rows fills the slot a product's epilogue
+// would have filled.
+__global__ __launch_bounds__(kThreads) void thin_gram_kernel(const LayerDev* __restrict__ layers,
+                                                             const int* __restrict__ ids, int role, int cp) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int len = side_len(L, side_of_role(L.transposed, role));
+    const int ob = blockIdx.x;
+    if (ob * BT >= len) return;
+    const ThinRef T = L.thin[role];
+    const int w = T.width;
+    extern __shared__ __align__(16) unsigned char smem[];
+    float* otile = reinterpret_cast<float*>(smem);    // [BT][cp + 1]
+    const int tw = cp + 1;
+    const int t = threadIdx.x;
+    for (int e = t; e < BT * cp; e += kThreads) otile[(e / cp) * tw + e % cp] = 0.f;
+    __syncthreads();
+    for (int e = t; e < BT * w; e += kThreads) {
+        const int row = e / w, col = e % w;
+        if (ob * BT + row < len) otile[row * tw + col] = as_global(T.ptr)[(int64_t)(ob * BT + row) * T.ld + col];
+    }
+    __syncthreads();
+    gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * ((w * (w + 1)) / 2));
+}
+
+hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
+                            hipStream_t st) {
+    if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
+    dim3 grid(max_blocks, n_ids), block(kThreads);
+    const size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(thin_gram_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(thin_gram_kernel, grid, block, lds, st, layers, ids, role, cp);
+    return hipGetLastError();
+}
+
 hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st) {

@@ -19,7 +19,7 @@ PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -
 
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
-    "psgd_decompress", "psgd_decompress_msgd", "psgd_decompress_adam", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
+    "psgd_decompress", "psgd_decompress_msgd", "psgd_decompress_adam", "psgd_compress_project", "psgd_compress_finish", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_select", "psgd_profile_read",
 ]
@@ -71,10 +71,12 @@ def load_library() -> C.CDLL:
     lib.psgd_init.restype = C.c_int
     lib.psgd_workspace_bytes.argtypes = [vp]
     lib.psgd_workspace_bytes.restype = C.c_size_t
-    for name in ("psgd_compress", "psgd_compress_refresh"):
+    for name in ("psgd_compress", "psgd_compress_refresh", "psgd_compress_project"):
         fn = getattr(lib, name)
         fn.argtypes = [vp, vp, vp, pp, pp, pp, pp]
         fn.restype = C.c_int
+    lib.psgd_compress_finish.argtypes = [vp, vp, vp, pp, pp, pp]
+    lib.psgd_compress_finish.restype = C.c_int
     lib.psgd_flush_residual.argtypes = [vp, vp, vp, pp]
     lib.psgd_flush_residual.restype = C.c_int
     lib.psgd_refresh.argtypes = [vp, vp, vp, C.c_int, vp, vp, vp, vp]
@@ -195,6 +197,19 @@ class Compressor:
         tg, te, tq, tp = self._tables(G, E, Q, P)
         _check(self.lib, self.ctx,
                self.lib.psgd_compress_refresh(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def compress_project(self, G, E, Q, P, stream=None) -> None:
+        """psgd_compress_project: E[l] <- M = G[l] + E[l]; P[l] <- M Q[l] (first half of a data-parallel step)."""
+        tg, te, tq, tp = self._tables(G, E, Q, P)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_compress_project(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def compress_finish(self, E, Q, P, stream=None) -> None:
+        """psgd_compress_finish: P[l] <- QR(P[l]) (the averaged P); Q[l] <- M^T P~; E[l] <- M - P~ Q[l]^T."""
+        te, tq, tp = _ptr_table(E), _ptr_table(Q), _ptr_table(P)
+        self._keep = (te, tq, tp)
+        _check(self.lib, self.ctx,
+               self.lib.psgd_compress_finish(self.ctx, self._ws_ptr, _stream_handle(stream), te, tq, tp))
 
     def flush_residual(self, E, stream=None) -> None:
         """psgd_flush_residual: settle the residual a lazy_residual compress step left owed (E[l] <- E_{t+1})."""

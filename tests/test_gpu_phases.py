@@ -1,0 +1,123 @@
+"""GPU parity of the two halves of psgd_compress (psgd_compress_project, psgd_compress_finish) that a data-parallel
+job runs on every worker, with the exchange of P and Q between and after them.
+
+Here the workers are N contexts (n_workers = 1 each, own workspace, own error buffer e^(i)) on the one GPU, run one
+after the other; the two all-reduce-means of Algorithm 1 (P after the projection, Q after the back-projection) are
+torch means over the workers' buffers -- plumbing that stands in for the collective.  The oracle runs the literal
+per-worker form of Algorithm 1 / Algorithm 2, so every worker's e^(i)_{t+1} is compared, not only their mean.
+"""
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2509_11254_amd import psgd, synth
+from gpu_harness import Case, back, logical, to_dev_f32, to_dev_grad, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+TOL = {synth.F32: 1e-4, synth.BF16: 2e-2}
+
+
+def _worker_inputs(wl, seed):
+    """Per layer and worker: gradient (stored dtype) and a distinct error buffer e^(i); per layer Q_{t-1}."""
+    grads, errs, qs = [], [], []
+    for l, spec in enumerate(wl.layers):
+        sig = synth.signal_matrix(spec, wl, l)
+        grads.append([synth.worker_gradient(spec, wl, l, w, 0, sig) for w in range(wl.n_workers)])
+        rng = np.random.default_rng([wl.seed, seed, l])
+        errs.append([(0.3 * synth.noise_sigma(spec, wl) * rng.standard_normal((spec.rows, spec.cols))).astype(np.float32)
+                     for _ in range(wl.n_workers)])
+        qs.append(synth.initial_q(spec.n, wl.r, wl.seed, l))
+    return grads, errs, qs
+
+
+def _data_parallel_step(wl, grads, errs, qs):
+    """Returns per layer (P~, Q_t, [e^(i)]) from N single-worker contexts and two device-side means."""
+    torch = torch_mod()
+    nl, nw = len(wl.layers), wl.n_workers
+    shapes = [(s.rows, s.cols) for s in wl.layers]
+    workers = []
+    for i in range(nw):
+        c = Case(shapes, wl.r, 1, wl.grad_dtype)
+        c.upload([[grads[l][i]] for l in range(nl)], [errs[l][i] for l in range(nl)], qs)
+        workers.append(c)
+    for c in workers:
+        c.comp.compress_project(c.G, c.E, c.Q, c.P)
+    torch.cuda.synchronize()
+    for l in range(nl):                                     # all-reduce-mean of P
+        mean_p = torch.stack([c.P[l] for c in workers]).mean(dim=0)
+        for c in workers:
+            c.P[l].copy_(mean_p)
+    for c in workers:
+        c.comp.compress_finish(c.E, c.Q, c.P)
+    torch.cuda.synchronize()
+    out = []
+    for l in range(nl):
+        q_t = torch.stack([c.Q[l] for c in workers]).mean(dim=0)          # all-reduce-mean of Q
+        for c in workers[1:]:
+            assert torch.equal(c.P[l], workers[0].P[l])                   # every worker holds the same P~
+        out.append((back(workers[0].P[l]), back(q_t), [back(c.E[l], shapes[l][1]) for c in workers]))
+    return out
+
+
+@pytest.mark.parametrize("which", ["f32_n3", "bf16_n4_transposed", "bf16_r64_n2", "batched_n2"])
+def test_data_parallel_step_matches_per_worker_oracle(which):
+    if which == "f32_n3":
+        wl = synth.scaled_down(synth.config2(), 640, 384); wl.n_workers = 3
+    elif which == "bf16_n4_transposed":
+        wl = synth.scaled_down(synth.config3(), 384, 1024)
+    elif which == "bf16_r64_n2":
+        wl = synth.scaled_down(synth.config4(), 1100, 512); wl.n_workers = 2
+    else:
+        wl = synth.scaled_down(synth.config3(), 256, 256); wl.n_workers = 2
+        wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c"),
+                     synth.LayerSpec(200, 136, "e")]
+    tol = TOL[wl.grad_dtype]
+    grads, errs, qs = _worker_inputs(wl, 31)
+    got = _data_parallel_step(wl, grads, errs, qs)
+    worst = {}
+    for l, spec in enumerate(wl.layers):
+        g = [logical(synth.gradient_as_f64(gw), spec.rows, spec.cols) for gw in grads[l]]
+        e = [logical(np.asarray(ew, np.float64), spec.rows, spec.cols) for ew in errs[l]]
+        ref = orc.compress_step(1, None, wl.r, qs[l].astype(np.float64), g, e)
+        p_gpu, q_gpu, e_gpu = got[l]
+        errs_l = {"P": orc.rel_fro(p_gpu, ref.comp.p_tilde), "Q": orc.rel_fro(q_gpu, ref.comp.q),
+                  "orth": float(np.abs(p_gpu.T @ p_gpu - np.eye(wl.r)).max())}
+        for i in range(wl.n_workers):
+            errs_l["e%d" % i] = orc.rel_fro(logical(e_gpu[i], spec.rows, spec.cols), ref.e_next[i])
+        assert errs_l.pop("orth") < 2e-5, (l, errs_l)
+        for k, v in errs_l.items():
+            assert v <= tol, (which, l, k, errs_l)
+            worst[k[0]] = max(worst.get(k[0], 0.0), v)
+    print(which, worst)
+
+
+def test_one_worker_halves_equal_the_whole_step():
+    """project followed by finish on one worker with all N gradients is psgd_compress."""
+    wl = synth.scaled_down(synth.config1(), 333, 203)
+    spec = wl.layers[0]
+    grads, errs, qs = _worker_inputs(wl, 5)
+    e0 = [errs[0][0]]
+    whole = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lds=[208])
+    whole.upload(grads, e0, qs)
+    whole.compress()
+    halves = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lds=[208])
+    halves.upload(grads, e0, qs)
+    halves.comp.compress_project(halves.G, halves.E, halves.Q, halves.P)
+    halves.comp.compress_finish(halves.E, halves.Q, halves.P)
+    torch_mod().cuda.synchronize()
+    for a, b in zip(whole.outputs(0), halves.outputs(0)):
+        assert orc.rel_fro(b, a) <= 2e-6
+
+
+def test_halves_rejected_with_options_they_do_not_support():
+    wl = synth.scaled_down(synth.config1(), 256, 128)
+    spec = wl.layers[0]
+    grads, errs, qs = _worker_inputs(wl, 6)
+    for opts in (dict(lazy_residual=True), dict(m_policy=2), dict(power_iters=2)):
+        case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, **opts)
+        case.upload(grads, [errs[0][0]], qs)
+        with pytest.raises(psgd.PsgdError):
+            case.comp.compress_project(case.G, case.E, case.Q, case.P)
+        with pytest.raises(psgd.PsgdError):
+            case.comp.compress_finish(case.E, case.Q, case.P)
