@@ -121,3 +121,42 @@ def test_halves_rejected_with_options_they_do_not_support():
             case.comp.compress_project(case.G, case.E, case.Q, case.P)
         with pytest.raises(psgd.PsgdError):
             case.comp.compress_finish(case.E, case.Q, case.P)
+
+
+def test_data_parallel_refresh_step_from_the_same_entry_points():
+    """The SVD-Comp step of a data-parallel job (Algorithm 1: the averaged Delta is decomposed, then every node
+    projects its own Delta^(i)): project stores M^(i), the mean of the M^(i) stands in for the full-gradient
+    all-reduce, psgd_refresh gives P~ = U_r of it, and finish (whose QR leaves an orthonormal P~ as it is) gives
+    every worker its Q^(i) and e^(i)."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config2(), 768, 512)
+    wl.n_workers = 3
+    spec = wl.layers[0]
+    grads, errs, qs = _worker_inputs(wl, 41)
+    workers = []
+    for i in range(wl.n_workers):
+        c = Case([(spec.rows, spec.cols)], wl.r, 1, wl.grad_dtype)
+        c.upload([[grads[0][i]]], [errs[0][i]], qs)
+        c.comp.compress_project(c.G, c.E, c.Q, c.P)
+        workers.append(c)
+    torch.cuda.synchronize()
+    m_bar = torch.stack([c.E[0] for c in workers]).mean(dim=0).contiguous()
+    w0 = workers[0]
+    q_tmp = torch.empty_like(w0.Q[0])
+    w0.comp.refresh(0, m_bar, w0.P[0], q_tmp)
+    torch.cuda.synchronize()
+    for c in workers[1:]:
+        c.P[0].copy_(w0.P[0])
+    for c in workers:
+        c.comp.compress_finish(c.E, c.Q, c.P)
+    torch.cuda.synchronize()
+    g = [synth.gradient_as_f64(gw) for gw in grads[0]]
+    e = [np.asarray(ew, np.float64) for ew in errs[0]]
+    ref = orc.compress_step(0, 1, wl.r, qs[0].astype(np.float64), g, e)
+    p_gpu = back(w0.P[0])
+    assert orc.sin_theta_max(ref.comp.p_tilde, p_gpu) <= 1e-4
+    assert np.abs(p_gpu.T @ p_gpu - np.eye(wl.r)).max() < 2e-5
+    q_t = back(torch.stack([c.Q[0] for c in workers]).mean(dim=0))
+    assert orc.rel_fro(p_gpu @ q_t.T, ref.comp.delta_hat) <= 1e-4
+    for i, c in enumerate(workers):
+        assert orc.rel_fro(back(c.E[0], spec.cols), ref.e_next[i]) <= 1e-4, i
