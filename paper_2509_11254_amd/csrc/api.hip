@@ -29,7 +29,7 @@ hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const 
 hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
                             hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
-                       int cp, hipStream_t st);
+                       int cp, int which, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
                        int slot_rows, int gate, int a2gate, int local_ok, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
@@ -337,7 +337,12 @@ struct Launcher {
     int max_len() const { return max_rows > max_cols ? max_rows : max_cols; }
     int max_lenP() const { return max_rowsP > max_colsP ? max_rowsP : max_colsP; }
 
-    void pack(int role, int cp, int role_b = -1) { note(launch_pack(layers, ids_all, n_all, max_lenP(), role, role_b, cp, st)); }
+    // operand copies of caller-supplied thin matrices: the transposed ones for a product, the row-major ones for an
+    // outer-product kernel
+    enum { PACK_ROWMAJOR = 1, PACK_TRANSPOSED = 2 };
+    void pack(int role, int cp, int which, int role_b = -1) {
+        note(launch_pack(layers, ids_all, n_all, max_lenP(), role, role_b, cp, which, st));
+    }
     // product whose result is P-like (lives on the long side) or Q-like, stored in thin[out_role];
     // chol_gate >= -1: the first CholeskyQR pass on the result follows at once (see prod_orth)
     void prod(bool p_like, bool form, int nb, int out_role, int epi, int chol_gate = -2, int a2gate = -2,
@@ -460,7 +465,7 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     L.prof_mute = true;
     L.note(launch_init_block(L.layers, L.ids_all, L.n_all, L.max_len(), wz, ROLE_ZQ, ROLE_Q, warm ? 1 : 0,
                              ctx->opt.seed, L.st));
-    L.pack(ROLE_ZQ, cpz);
+    L.pack(ROLE_ZQ, cpz, Launcher::PACK_TRANSPOSED);
     for (int it = 0; it < n_launch; ++it) {
         // every layer runs its own number of iterations (decided on the device from the Ritz values of
         // its previous refresh); launches past that number find their gate closed and exit at once
@@ -639,7 +644,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_Q, cp);
+    L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
     // P = M Q_{t-1} (M formed on the way and, unless it is formed again below, stored over E);
     // P~ = QR(P), operand copies of P~;  Q_t = M^T P~, operand copies of Q_t;  K times (Eq. (8)), K = 1 by default
     const bool re = ctx->reform_m;
@@ -674,7 +679,7 @@ int psgd_compress_project(psgd_ctx* ctx, void* workspace, void* stream, const vo
     if (rc != PSGD_OK) return rc;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_Q, cp);
+    L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
     L.prod(true, true, nb, ROLE_P, EPI_NONE);          // M = mean G + E stored over E;  P = M Q_{t-1}, as it is
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
@@ -820,7 +825,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, ROLE_Q);
+    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
@@ -847,7 +852,7 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     ctx->msgd_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, ROLE_Q);
+    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, st));
@@ -887,7 +892,7 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
                            (float)((double)eta * (double)weight_decay)};
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, ROLE_Q);
+    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_m2s),

@@ -139,10 +139,11 @@ __device__ inline void divmod_small(int v, int d, int& q, int& r) {
 
 // Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
 // nrows a multiple of 8); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
+// which: 1 = the row-major copies only, 2 = the transposed ones only, 3 = both.
 __device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
-                                   int nrows, int lenP) {
+                                   int nrows, int lenP, int which = 3) {
     const int t = threadIdx.x;
-    for (int v = t; v < nrows * (cp / 8); v += kThreads) {
+    for (int v = t; (which & 1) && v < nrows * (cp / 8); v += kThreads) {
         int row, g8;
         divmod_small(v, cp / 8, row, g8);
         const int c0 = 8 * g8;
@@ -159,7 +160,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         for (int k = 0; k < kMaxPlanes; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.n[k]) + off) = o[k];
     }
-    for (int v = t; v < cp * (nrows / 8); v += kThreads) {
+    for (int v = t; (which & 2) && v < cp * (nrows / 8); v += kThreads) {
         int c, g8;
         divmod_small(v, nrows / 8, c, g8);
         const int ib = 8 * g8;

@@ -9,10 +9,11 @@ namespace psgd {
 // --------------------------------------------------------------------------------------------
 // pack: thin fp32 (len x width, ld) -> split-bf16 operand copies, row-major and transposed.
 // --------------------------------------------------------------------------------------------
-// grid.z walks the roles to pack (role_a, then role_b when two are asked for)
+// grid.z walks the roles to pack (role_a, then role_b when two are asked for); which: 1 = row-major copies (what
+// the outer-product kernels read), 2 = transposed copies (what the products read), 3 = both
 __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restrict__ layers,
                                                         const int* __restrict__ ids, int role_a, int role_b,
-                                                        int cp) {
+                                                        int cp, int which) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int role = blockIdx.z == 0 ? role_a : role_b;
     const int side = side_of_role(L.transposed, role);
@@ -40,12 +41,12 @@ __global__ __launch_bounds__(kThreads) void pack_kernel(const LayerDev* __restri
         }
     }
     __syncthreads();
-    write_packs(L.pack[side], L.planes, tile, tw, cp, i0, 64, lenP);
+    write_packs(L.pack[side], L.planes, tile, tw, cp, i0, 64, lenP, which);
 }
 
 // role_b < 0: one role
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
-                       int cp, hipStream_t st) {
+                       int cp, int which, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / 64, n_ids, role_b >= 0 ? 2 : 1), block(kThreads);
     const size_t lds = (size_t)64 * (cp + 1) * sizeof(float);
@@ -54,7 +55,7 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(pack_kernel, grid, block, lds, st, layers, ids, role_a, role_b, cp);
+    hipLaunchKernelGGL(pack_kernel, grid, block, lds, st, layers, ids, role_a, role_b, cp, which);
     return hipGetLastError();
 }
 
