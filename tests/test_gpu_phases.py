@@ -160,3 +160,31 @@ def test_data_parallel_refresh_step_from_the_same_entry_points():
     assert orc.rel_fro(p_gpu @ q_t.T, ref.comp.delta_hat) <= 1e-4
     for i, c in enumerate(workers):
         assert orc.rel_fro(back(c.E[0], spec.cols), ref.e_next[i]) <= 1e-4, i
+
+
+def test_halves_on_degenerate_inputs():
+    """Zero gradient and zero error: the supplied P is zero, every column is flagged, all outputs are zero.  A
+    rank-deficient P (rank 2 < r) keeps a valid projector, as in the whole step."""
+    torch = torch_mod()
+    m, n, r = 256, 128, 4
+    z = np.zeros((m, n), np.float32)
+    case = Case([(m, n)], r, 1, synth.F32)
+    case.upload([[z]], [z], [synth.initial_q(n, r, 3)])
+    case.comp.compress_project(case.G, case.E, case.Q, case.P)
+    case.comp.compress_finish(case.E, case.Q, case.P)
+    torch.cuda.synchronize()
+    p, q, e = case.outputs(0)
+    assert np.all(p == 0) and np.all(q == 0) and np.all(e == 0)
+    assert case.comp.status(0).rank_deficient == r
+    m, n = 384, 256
+    mat, _, _ = synth.prescribed_svd_matrix(m, n, [2.0, 1.0], seed=9)
+    case = Case([(m, n)], r, 1, synth.F32)
+    case.upload([[mat]], [np.zeros((m, n), np.float32)], [synth.initial_q(n, r, 2)])
+    case.comp.compress_project(case.G, case.E, case.Q, case.P)
+    case.comp.compress_finish(case.E, case.Q, case.P)
+    torch.cuda.synchronize()
+    p, q, e = case.outputs(0)
+    assert case.comp.status(0).rank_deficient == 2
+    assert np.all(p[:, 2:] == 0)
+    np.testing.assert_allclose(p[:, :2].T @ p[:, :2], np.eye(2), atol=2e-5)
+    assert np.linalg.norm(e - (mat - p @ (p.T @ mat))) <= 1e-4 * np.linalg.norm(mat)
