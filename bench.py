@@ -295,6 +295,15 @@ def main():
 
     n_b = max(3, min(20, args.steps))
     ssp_ms = timed(lambda i: comp.compress(sets[i % args.sets], E, Q, P), n_b)
+    # the same step as the two halves a data-parallel job runs per worker (P averaged between them): what the split
+    # costs on one GPU (the orthonormaliser finds P in memory, not in the product's epilogue)
+    halves_ms = None
+    if not args.lazy:
+        def halves(i):
+            comp.compress_project(sets[i % args.sets], E, Q, P)
+            comp.compress_finish(E, Q, P)
+        halves(0)
+        halves_ms = timed(halves, n_b)
     comp.profile_select(list(psgd.PROF_TAGS))
     comp.profile_enable(4 * n_b + 8)
     for i in range(n_b):
@@ -370,7 +379,7 @@ def main():
                           decompress_msgd_frac_of_hbm_peak=msgd_gbps / HBM_PEAK_GBPS,
                           decompress_adam_ms=adam_ms, decompress_adam_GBps=adam_gbps,
                           decompress_adam_frac_of_hbm_peak=adam_gbps / HBM_PEAK_GBPS,
-                          ssp_step_deferred_residual_ms=lazy_ms,
+                          ssp_step_deferred_residual_ms=lazy_ms, ssp_step_two_halves_ms=halves_ms,
                           ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
                           ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
     }
