@@ -31,7 +31,7 @@ hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, i
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
                        int cp, int which, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, int a2gate, int local_ok, hipStream_t st);
+                       int slot_rows, int gate, int a2gate, int local_ok, int after_finish, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
                         bool small, hipStream_t st);
@@ -361,9 +361,11 @@ struct Launcher {
         const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
         if (split_n) note(launch_finish(!p_like, form, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (split_t) note(launch_finish(p_like, form, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        // (after a split product only the layers finish_kernel leaves to it -- wide, many Gram slots -- and none at
+        // widths where there are no such layers)
         if (chol_gate >= -1) {
-            if (!split_n) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
-            if (!split_t) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, st));
+            if (!split_n || w > 16) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, split_n ? 1 : 0, st));
+            if (!split_t || w > 16) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, split_t ? 1 : 0, st));
         }
     }
     // thin[out_role] = product as in prod(), then CholeskyQR2 on it: the first pass always, the second
@@ -381,7 +383,7 @@ struct Launcher {
         note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, small, st));
         if (a2 != -2) {
             const int g2 = a2 == -1 ? g : a2;
-            if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, g2, -2, 0, st));
+            if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, g2, -2, 0, 0, st));
             note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, g2, a2, tol2, small, st));
         }
     }
@@ -390,9 +392,9 @@ struct Launcher {
         const bool small = w <= 16;
         const int blocks = (max_lenP() + 127) / 128;
         note(launch_thin_gram(layers, ids_all, n_all, blocks, out_role, cp, st));
-        note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 1, kGramRows1, -1, -1, small ? 1 : 0, st));
+        note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 1, kGramRows1, -1, -1, small ? 1 : 0, 0, st));
         note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, -1, -1, tol2, small, st));
-        if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, -1, -2, 0, st));
+        if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, -1, -2, 0, 0, st));
         note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, -1, -1, tol2, small, st));
     }
     void residual(int nb, bool form = false) {

@@ -637,7 +637,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
 // output block; the partials are added in split order, so the result is deterministic.
 // chol_gate >= -1: the last workgroup to finish a layer goes on to factorise the sum of the partial Gram
 // matrices (first CholeskyQR pass) if that gate is open, unless the layer is one where the apply kernel
-// does that for itself; -2: no factorisation follows.
+// does that for itself or one that is left to the chol_kernel launch that follows (see there); -2: no
+// factorisation follows.
 static_assert(BT == kGramRows1, "one partial Gram matrix per output block of a product");
 __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __restrict__ layers,
                                                           const int* __restrict__ ids, int colmode, int cp,
@@ -716,15 +717,11 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role, local_ok) && gate_open(L, chol_gate)) {
         const int n_wg = (out_len + BT - 1) / BT;      // = number of Gram slots (BT == kGramRows1)
         if (grouped_slot_sum(T.width, n_wg)) {
+            // wide block, many slots: add the slots up in groups here, side by side; a launch of chol_kernel with
+            // twice the threads does the rest
             const int grp = ob / kSlotGroup;
             const int in_grp = min(kSlotGroup, n_wg - grp * kSlotGroup);
-            if (last_to_arrive(&L.status[8 + grp], in_grp, &s_last)) {
-                sum_slot_group(L.gram, T.width, n_wg, grp);
-                if (last_to_arrive(&L.status[6], (n_wg + kSlotGroup - 1) / kSlotGroup, &s_last)) {
-                    chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat, true, nullptr,
-                              kSlotGroup);
-                }
-            }
+            if (last_to_arrive(&L.status[8 + grp], in_grp, &s_last)) sum_slot_group(L.gram, T.width, n_wg, grp);
         } else if (last_to_arrive(&L.status[6], n_wg, &s_last)) {
             chol_body(L, out_role, tol2, 1, kGramRows1, allow2_of(L, a2gate), smem, L.tmat);
         }

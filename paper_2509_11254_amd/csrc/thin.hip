@@ -107,30 +107,44 @@ hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int ma
 // chol: one workgroup per layer runs the factorisation on the partial Gram matrices that the producing
 // kernel has left (used when that kernel cannot hand over to it itself).
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void chol_kernel(const LayerDev* __restrict__ layers,
-                                                        const int* __restrict__ ids, int role, double tol2,
-                                                        int pass, int slot_rows, int gate, int a2gate,
-                                                        int local_ok) {
+// after_finish: the launch follows a split product's finish_kernel, which has factorised every layer itself except
+// the wide ones with many Gram slots: those it has only added up in groups (grouped_slot_sum) and left to this
+// kernel, which brings 512 threads to the serial part instead of the 256 of a finish workgroup.
+template <int NT>
+__global__ __launch_bounds__(NT) void chol_kernel(const LayerDev* __restrict__ layers,
+                                                  const int* __restrict__ ids, int role, double tol2,
+                                                  int pass, int slot_rows, int gate, int a2gate,
+                                                  int local_ok, int after_finish) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
     if (pass == 1 && local_chol(L, role, local_ok)) return;       // the apply kernel factorises for itself
+    int stride = 1;
+    if (after_finish) {
+        const int n_slots = (side_len(L, side_of_role(L.transposed, role)) + slot_rows - 1) / slot_rows;
+        if (!grouped_slot_sum(L.thin[role].width, n_slots)) return;
+        stride = kSlotGroup;
+    }
     extern __shared__ __align__(16) unsigned char smem[];
-    chol_body(L, role, tol2, pass, slot_rows, allow2_of(L, a2gate), smem, L.tmat);
+    chol_body(L, role, tol2, pass, slot_rows, allow2_of(L, a2gate), smem, L.tmat, true, nullptr, stride);
 }
 
+// Widths that take the blocked factorisation get 512 threads: its panels, trailing updates, the blocked inverse and
+// the slot sum are dealt to the waves (1024 threads halve the registers a thread may hold, and measured slower).
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
-                       int slot_rows, int gate, int a2gate, int local_ok, hipStream_t st) {
+                       int slot_rows, int gate, int a2gate, int local_ok, int after_finish, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
-    dim3 grid(1, n_ids), block(kThreads);
+    const bool wide = w > 32;
+    dim3 grid(1, n_ids), block(wide ? 512 : kThreads);
     const size_t lds = chol_lds_bytes_upto(w);
+    auto kfn = wide ? chol_kernel<512> : chol_kernel<kThreads>;
     if (lds > 48 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(chol_kernel),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(chol_kernel, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate, a2gate,
-                       local_ok);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, role, tol2, pass, slot_rows, gate, a2gate,
+                       local_ok, after_finish);
     return hipGetLastError();
 }
 

@@ -230,7 +230,8 @@ __device__ inline bool local_chol(const LayerDev& L, int role, int local_ok) {
 // Sums the partial Gram matrices of thin[role] (packed upper triangles, slots of `slot_rows` rows, fixed
 // order), scales to unit diagonal, Cholesky-factorises (upper, packed in LDS), inverts the factor in
 // place and writes tmat = D R_s^{-1}.  pass 1 also decides whether the second CholeskyQR pass runs.
-// Called by all kThreads threads of one workgroup per layer; smem: chol_lds_bytes(w), 8-byte aligned.
+// Called by all threads of one workgroup per layer (256 or 1024: a multiple of 256 and a power of two); smem:
+// chol_lds_bytes(w), 8-byte aligned.
 // tm: where the w x w factor goes (the layer's tmat, or LDS of the caller); need2_out: optional LDS word
 // that receives the second-pass decision; write_status: whether this caller owns the layer's status words.
 // NARROW: compiled for widths <= 16 only (the register path; nothing else is generated).
@@ -256,6 +257,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     double* panel = tcol + wp;                            // [wp][16] original block column (blocked inverse)
     int* bad = reinterpret_cast<int*>(panel + (blocked ? wp * 16 : 0));    // [w] dependent-column flags
     const int t = threadIdx.x;
+    const int nt = blockDim.x, nw = nt >> 6, nty = nt >> 4;      // threads, wavefronts, rows of the 16-wide thread grid
     const double* __restrict__ gram = L.gram;
     if (G > 1 || NARROW) {
         // thread (e, g): entries e of slots g, g + G, ...; sixteen loads in flight, those past the end
@@ -292,10 +294,10 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         typedef double doublex2 __attribute__((ext_vector_type(2)));
         const PSGD_GLOBAL double* gg = as_global(gram);
         if ((ntri & 1) == 0) {
-            for (int e = 2 * t; e < ntri; e += 4 * kThreads) {
-                const bool two = e + 2 * kThreads < ntri;
+            for (int e = 2 * t; e < ntri; e += 4 * nt) {
+                const bool two = e + 2 * nt < ntri;
                 const PSGD_GLOBAL double* g0 = gg + e;
-                const PSGD_GLOBAL double* g1 = gg + (two ? e + 2 * kThreads : e);
+                const PSGD_GLOBAL double* g1 = gg + (two ? e + 2 * nt : e);
                 doublex2 p0 = {0.0, 0.0}, p1 = p0, p2 = p0, p3 = p0, q0 = p0, q1 = p0, q2 = p0, q3 = p0;
                 int sl = 0;
                 for (; sl + 16 <= n_slots; sl += 16) {
@@ -317,10 +319,10 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
                 }
                 const doublex2 ps2 = (p0 + p1) + (p2 + p3), qs2 = (q0 + q1) + (q2 + q3);
                 a[e] = ps2.x; a[e + 1] = ps2.y;
-                if (two) { a[e + 2 * kThreads] = qs2.x; a[e + 2 * kThreads + 1] = qs2.y; }
+                if (two) { a[e + 2 * nt] = qs2.x; a[e + 2 * nt + 1] = qs2.y; }
             }
         } else {
-            for (int e = t; e < ntri; e += kThreads) {
+            for (int e = t; e < ntri; e += nt) {
                 const PSGD_GLOBAL double* g0 = gg + e;
                 double p0 = 0.0, p1 = 0.0, p2 = 0.0, p3 = 0.0;
                 int sl = 0;
@@ -342,7 +344,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         return;
     }
     if constexpr (NARROW) return;
-    for (int i = t; i < w; i += kThreads) {
+    for (int i = t; i < w; i += nt) {
         const double d = a[tri_idx(i, i, w)];
         dsc[i] = d > kTinyNorm2 ? rsqrt_nr(d) : 0.0;
         bad[i] = d > kTinyNorm2 ? 0 : 1;
@@ -350,7 +352,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     __syncthreads();
     // threads as a 16 x 16 grid over (row, column): no integer division in the loops over the triangle
     const int tx = t & 15, ty = t >> 4;
-    for (int i = ty; i < w; i += 16) {
+    for (int i = ty; i < w; i += nty) {
         const int base = tri_idx(i, i, w) - i;
         for (int j = i + tx; j < w; j += 16) a[base + j] *= dsc[i] * dsc[j];
     }
@@ -368,15 +370,15 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             const int kbase = tri_idx(k, k, w) - k;             // a[tri_idx(k, j)] = a[kbase + j]
             if (dep) {
                 if (t == 0) { bad[k] = 1; rdiag[k] = 1.0; }
-                for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] = 0.0;
+                for (int j = k + 1 + t; j < w; j += nt) a[kbase + j] = 0.0;
             } else {
                 const double rinv = rsqrt_nr(piv);
                 if (t == 0) rdiag[k] = rinv;
-                for (int j = k + 1 + t; j < w; j += kThreads) a[kbase + j] *= rinv;
+                for (int j = k + 1 + t; j < w; j += nt) a[kbase + j] *= rinv;
             }
             __syncthreads();
             if (!dep) {
-                for (int i = k + 1 + ty; i < w; i += 16) {
+                for (int i = k + 1 + ty; i < w; i += nty) {
                     const double rki = a[kbase + i];
                     const int base = tri_idx(i, i, w) - i;
                     for (int j = i + tx; j < w; j += 16) a[base + j] -= rki * a[kbase + j];
@@ -395,7 +397,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             if (t < 64) chol_block16(a, w, r0, bw, tol2, rdiag, bad, min_piv);
             __syncthreads();
             // (2) row panel; rows of dependent columns are zero.  (Block J is complete: K > J exists.)
-            for (int K = J + 1 + wv; K < nbk; K += kThreads / 64) {
+            for (int K = J + 1 + wv; K < nbk; K += nw) {
                 doublex4 d = {0.0, 0.0, 0.0, 0.0};
                 const int col = 16 * K + li;
 #pragma unroll
@@ -416,7 +418,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             int pair = 0;
             for (int I = J + 1; I < nbk; ++I)
                 for (int K = I; K < nbk; ++K, ++pair) {
-                    if ((pair & 3) != wv) continue;
+                    if ((pair & (nw - 1)) != wv) continue;
                     doublex4 acc = {0.0, 0.0, 0.0, 0.0};
                     const int ci = 16 * I + li, ck = 16 * K + li;
 #pragma unroll
@@ -440,10 +442,10 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
     if (!blocked) {
         // column by column, one thread per row i of the new column
         for (int j = 1; j < w; ++j) {
-            for (int i = t; i < j; i += kThreads) tcol[i] = a[tri_idx(i, j, w)];
+            for (int i = t; i < j; i += nt) tcol[i] = a[tri_idx(i, j, w)];
             __syncthreads();
             const double tjj = rdiag[j];
-            for (int i = t; i < j; i += kThreads) {
+            for (int i = t; i < j; i += nt) {
                 const int base = tri_idx(i, i, w) - i;
                 double sacc = rdiag[i] * tcol[i];
                 for (int l = i + 1; l < j; ++l) sacc += a[base + l] * tcol[l];
@@ -459,12 +461,12 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
         // U^T = sum_K R_KJ^T T_IK^T and T_IJ^T = -T_JJ^T U^T, so that the accumulator of the first is the
         // B operand of the second without a move.  R_KJ is read from a copy of the block column, T in place.
         for (int J = 1; J < nbk; ++J) {
-            for (int e = t; e < 16 * J * 16; e += kThreads) {
+            for (int e = t; e < 16 * J * 16; e += nt) {
                 const int row = e >> 4, col = 16 * J + (e & 15);
                 panel[e] = col < w ? a[tri_idx(row, col, w)] : 0.0;
             }
             __syncthreads();
-            for (int I = wv; I < J; I += kThreads / 64) {
+            for (int I = wv; I < J; I += nw) {
                 doublex4 acc = {0.0, 0.0, 0.0, 0.0};
                 const int trow = 16 * I + li;
                 const int tbase = tri_idx(trow, trow, w) - trow;               // a[tbase + c] = T[trow][c], c > trow
@@ -494,7 +496,7 @@ __device__ inline void chol_body(const LayerDev& L, int role, double tol2, int p
             __syncthreads();
         }
     }
-    for (int i = ty; i < w; i += 16) {
+    for (int i = ty; i < w; i += nty) {
         const int base = tri_idx(i, i, w) - i;
         for (int j = tx; j < w; j += 16) {
             double v = 0.0;
