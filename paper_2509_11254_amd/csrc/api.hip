@@ -51,6 +51,7 @@ constexpr int kMaxWidth = 192;      // widest thin block (packed Cholesky factor
 constexpr int kTargetTiles = 1024;  // workgroups per forming-pass launch we try to reach by splitting the reduction
 constexpr int kTargetTilesPlain = 512;   // ... per launch of a product that only reads M: half as many, twice as long-lived
                                          // (config 2: pass 2a 20.4 -> 18.6 us, its refresh step 1.00 -> 0.96 ms)
+constexpr int kTargetTilesWide = 256;    // ... at thin widths of 64 and more (see choose_split)
 constexpr int kMaxSplit = 32;
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -172,20 +173,26 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     return R;
 }
 
-// PSGD_TARGET_TILES (environment, tuning knob): workgroups a product launch should reach
-int target_tiles() {
-    static int v = 0;
-    if (v == 0) {
+// PSGD_TARGET_TILES (environment, tuning knob): workgroups a product launch should reach; 0 = not set
+int target_tiles_env() {
+    static int v = -1;
+    if (v < 0) {
         const char* e = std::getenv("PSGD_TARGET_TILES");
-        v = e ? std::atoi(e) : kTargetTiles;
-        if (v < 1) v = kTargetTiles;
+        v = e ? std::atoi(e) : 0;
+        if (v < 1) v = 0;
     }
     return v;
 }
 
-int choose_split(int64_t base_tiles, int min_chunks, bool form) {
-    int target = target_tiles();
-    if (!form && target > kTargetTilesPlain) target = target / 2;
+// Reduction split of a launch with `base_tiles` output blocks.  cp: packed width of the thin operand.  At widths
+// of 64 and more one workgroup per compute unit is the target: the partial products that finish_kernel has to add
+// up grow with the width, and the wide product kernels do not gain from more workgroups (4096 x 4096: the step at
+// r = 64 takes 0.325 ms with 1024 workgroups, 0.302 with 256; at r = 128 0.514 and 0.473; at r = 16 and 32 it is
+// the other way round).
+int choose_split(int64_t base_tiles, int min_chunks, bool form, int cp) {
+    int target = target_tiles_env();
+    if (target == 0) target = cp >= 64 ? kTargetTilesWide : (form ? kTargetTiles : kTargetTilesPlain);
+    else if (!form && target > kTargetTilesPlain) target = target / 2;
     if (base_tiles >= target) return 1;
     int64_t s = (target + base_tiles - 1) / base_tiles;
     if (s > kMaxSplit) s = kMaxSplit;
@@ -567,10 +574,10 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         if (cr < min_chunks_row) min_chunks_row = cr;
         if (cc < min_chunks_col) min_chunks_col = cc;
     }
-    c->split_row_b = choose_split(base_row, min_chunks_row, false);
-    c->split_col_b = choose_split(base_col, min_chunks_col, false);
-    c->split_row_bf = choose_split(base_row, min_chunks_row, true);
-    c->split_col_bf = choose_split(base_col, min_chunks_col, true);
+    c->split_row_b = choose_split(base_row, min_chunks_row, false, c->cpc);
+    c->split_col_b = choose_split(base_col, min_chunks_col, false, c->cpc);
+    c->split_row_bf = choose_split(base_row, min_chunks_row, true, c->cpc);
+    c->split_col_bf = choose_split(base_col, min_chunks_col, true, c->cpc);
     // workspace layout
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
@@ -787,8 +794,8 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     D.S = const_cast<float*>(M);
     D.thin[ROLE_P].ptr = P;
     D.thin[ROLE_Q].ptr = Q;
-    D.split_row = choose_split((p.d.rows + 127) / 128, (int)((p.d.cols + 63) / 64), false);
-    D.split_col = choose_split((p.d.cols + 127) / 128, (int)((p.d.rows + 63) / 64), false);
+    D.split_row = choose_split((p.d.rows + 127) / 128, (int)((p.d.cols + 63) / 64), false, ctx->cpz);
+    D.split_col = choose_split((p.d.cols + 127) / 128, (int)((p.d.rows + 63) / 64), false, ctx->cpz);
     D.split_row_f = D.split_row; D.split_col_f = D.split_col;      // (no forming pass in this call)
     D.part[0] = reinterpret_cast<float*>(ws + ctx->off_single_part[0]);
     D.part[1] = reinterpret_cast<float*>(ws + ctx->off_single_part[1]);
