@@ -304,6 +304,17 @@ def main():
             comp.compress_finish(E, Q, P)
         halves(0)
         halves_ms = timed(halves, n_b)
+    # the same step recorded into a HIP graph once and replayed (kernel launches only; see psgd.h on capture)
+    graph_ms = None
+    if not args.lazy:
+        comp.compress(sets[0], E, Q, P)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            comp.compress(sets[0], E, Q, P)
+        gr.replay()
+        graph_ms = timed(lambda i: gr.replay(), n_b)
+        del gr
     comp.profile_select(list(psgd.PROF_TAGS))
     comp.profile_enable(4 * n_b + 8)
     for i in range(n_b):
@@ -379,7 +390,7 @@ def main():
                           decompress_msgd_frac_of_hbm_peak=msgd_gbps / HBM_PEAK_GBPS,
                           decompress_adam_ms=adam_ms, decompress_adam_GBps=adam_gbps,
                           decompress_adam_frac_of_hbm_peak=adam_gbps / HBM_PEAK_GBPS,
-                          ssp_step_deferred_residual_ms=lazy_ms, ssp_step_two_halves_ms=halves_ms,
+                          ssp_step_deferred_residual_ms=lazy_ms, ssp_step_two_halves_ms=halves_ms, ssp_step_graph_replay_ms=graph_ms,
                           ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
                           ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
     }

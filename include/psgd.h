@@ -35,6 +35,13 @@
  *     enqueued.  No exceptions, no aborts.
  *   - Calls that share a workspace must be stream-ordered; two calls running at the same time on
  *     one workspace race.
+ *   - HIP graphs: psgd_compress, psgd_compress_project / _finish, psgd_compress_refresh, psgd_flush_residual and the
+ *     psgd_decompress* calls may be recorded by a capturing stream once the same call has been made eagerly with
+ *     the same workspace and the same pointer tables (their contents, not the host arrays): the library then has
+ *     nothing to upload and the recorded work is kernel launches only (no copy and no memset nodes).  A call that
+ *     would have to upload returns PSGD_E_CAPTURE and records nothing; the next eager call uploads everything.  A
+ *     captured psgd_compress_refresh launches the whole iteration budget and skips its bookkeeping copy; per-kernel
+ *     profiling records nothing under capture.  psgd_refresh and psgd_status cannot be captured.
  */
 #ifndef PSGD_H_
 #define PSGD_H_
@@ -56,7 +63,8 @@ enum {
     PSGD_E_SHAPE = -2,       /* rows/cols < 1, r < 1, r > min(rows, cols), r + oversampling too large */
     PSGD_E_ALIGN = -3,       /* ld < cols, ld not a multiple of 8, pointer not 16-byte aligned */
     PSGD_E_HIP = -4,         /* a HIP runtime call failed (psgd_last_hip_error gives its code) */
-    PSGD_E_NOMEM = -5        /* host allocation failed                                      */
+    PSGD_E_NOMEM = -5,       /* host allocation failed                                      */
+    PSGD_E_CAPTURE = -6      /* the stream is capturing and the call would have to upload pointer tables */
 };
 
 /* One matrix variable.  G^(i) and E of this layer all share rows, cols and ld. */

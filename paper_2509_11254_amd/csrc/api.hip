@@ -255,6 +255,14 @@ int check_table(const void* const* tab, size_t n) {
     return PSGD_OK;
 }
 
+// Whether work put on `st` is being recorded into a graph instead of executed.
+static bool is_capturing(hipStream_t st) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    const bool yes = hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
+    (void)hipGetLastError();
+    return yes;
+}
+
 // Upload what has changed: the layer descriptors and id lists (new workspace, or new E/Q/P
 // pointers) and/or the table of gradient pointers.  Stream-ordered, so launches already queued keep
 // seeing the old tables.
@@ -262,6 +270,19 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
     char* ws = reinterpret_cast<char*>(workspace);
     const bool fresh = !ctx->tables_valid || ctx->bound_ws != workspace;
     const int nl = ctx->n_layers;
+    if (fresh || desc_changed || g_changed) {
+        // Under stream capture nothing may be uploaded: a copy node would read this context's host arrays again at
+        // every replay, and the clearing of a new workspace's status words would become a memset node.  The one
+        // thing that is allowed to differ from the last eager call is which of the gradient tables already on the
+        // device is used.
+        bool slot_known = false;
+        for (int k = 0; k < psgd_ctx::kGSlots; ++k) slot_known |= !ctx->hG.empty() && ctx->hGs[k] == ctx->hG;
+        const bool upload = fresh || desc_changed || (g_changed && !ctx->hG.empty() && !slot_known);
+        if (upload && is_capturing(st)) {
+            ctx->tables_valid = false;      // the host copies are ahead of the device now: upload all next time
+            return PSGD_E_CAPTURE;
+        }
+    }
     if (fresh) {
         // the iteration counts live in the workspace: a bound fetched from another one says nothing about this one
         ctx->iters_gen++;
@@ -327,6 +348,7 @@ struct Launcher {
     int split_row = 1, split_col = 1, split_row_f = 1, split_col_f = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
+    bool capturing = false;   // the stream records into a graph: no event records
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
     bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
@@ -334,7 +356,7 @@ struct Launcher {
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
     int prof_begin(int tag) {
-        if (prof_mute || !ctx->prof_on || !((ctx->prof_mask >> tag) & 1) || ctx->prof_used >= ctx->prof_ev.size() / 2) return -1;
+        if (prof_mute || capturing || !ctx->prof_on || !((ctx->prof_mask >> tag) & 1) || ctx->prof_used >= ctx->prof_ev.size() / 2) return -1;
         const int k = (int)ctx->prof_used++;
         ctx->prof_tag[k] = tag;
         note(hipEventRecord(ctx->prof_ev[2 * k], st));
@@ -449,6 +471,7 @@ void geometry(const psgd_ctx* c, int l, int split_row, int split_col, int split_
 Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     Launcher L{};
     L.ctx = ctx; L.ws = reinterpret_cast<char*>(workspace); L.st = st;
+    L.capturing = ctx->prof_on && is_capturing(st);
     L.layers = reinterpret_cast<const LayerDev*>(L.ws + ctx->off_layers_s[ctx->cur_slot]);
     const int nl = ctx->n_layers;
     const int* ids = reinterpret_cast<const int*>(L.ws + ctx->off_ids);
@@ -742,9 +765,7 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     }
     // how many iterations to launch: the bound fetched after the last refresh, if it has arrived.  (None of this
     // bookkeeping under stream capture: a captured refresh launches the whole budget and fetches nothing.)
-    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
-    const bool capturing = hipStreamIsCapturing(st, &cap) != hipSuccess || cap != hipStreamCaptureStatusNone;
-    (void)hipGetLastError();
+    const bool capturing = is_capturing(st);
     if (!capturing && ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
         ctx->iters_pending = false;
         ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? ctx->h_iters[0] : 0;
@@ -787,6 +808,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     int rc = bind_common(ctx, workspace, st, nullptr, nullptr, nullptr, nullptr);
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
+    if (is_capturing(st)) return PSGD_E_CAPTURE;       // (every call uploads a descriptor from the host)
     const Plan& p = ctx->plan[layer];
     // scratch descriptor: this layer's private regions, the caller's M/P/Q, splits sized for one layer
     LayerDev D;
@@ -828,9 +850,11 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
-    if (sync_table(ctx->hOut, out, (size_t)ctx->n_layers) || ctx->outs_ws != workspace)
+    if (sync_table(ctx->hOut, out, (size_t)ctx->n_layers) || ctx->outs_ws != workspace) {
+        if (is_capturing(st)) { ctx->outs_ws = nullptr; return PSGD_E_CAPTURE; }
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*),
                                 hipMemcpyHostToDevice, st));
+    }
     ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
@@ -855,6 +879,7 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     char* ws = reinterpret_cast<char*>(workspace);
     const bool changed = sync_table(ctx->hMom, mom, nl) | sync_table(ctx->hX, X, nl);
     if (changed || ctx->msgd_ws != workspace) {
+        if (is_capturing(st)) { ctx->msgd_ws = nullptr; return PSGD_E_CAPTURE; }
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
     }
@@ -887,12 +912,15 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
     char* ws = reinterpret_cast<char*>(workspace);
     const bool changed = sync_table(ctx->hMom, m1, nl) | sync_table(ctx->hX, X, nl);
     if (changed || ctx->msgd_ws != workspace) {
+        if (is_capturing(st)) { ctx->msgd_ws = nullptr; return PSGD_E_CAPTURE; }
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
     }
     ctx->msgd_ws = workspace;
-    if (sync_table(ctx->hM2, m2, nl) || ctx->m2_ws != workspace)
+    if (sync_table(ctx->hM2, m2, nl) || ctx->m2_ws != workspace) {
+        if (is_capturing(st)) { ctx->m2_ws = nullptr; return PSGD_E_CAPTURE; }
         PSGD_TRY(hipMemcpyAsync(ws + ctx->off_m2s, ctx->hM2.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+    }
     ctx->m2_ws = workspace;
     // bias corrections in double: 1 - beta^t loses nothing for beta close to 1 and small t
     const double bc1 = 1.0 - std::pow((double)beta1, (double)step), bc2 = 1.0 - std::pow((double)beta2, (double)step);
@@ -941,6 +969,7 @@ const char* psgd_strerror(int code) {
         case PSGD_E_ALIGN: return "leading dimension or pointer alignment";
         case PSGD_E_HIP: return "HIP runtime error";
         case PSGD_E_NOMEM: return "out of host memory";
+        case PSGD_E_CAPTURE: return "stream capture: pointer tables not on the device yet (make the same call eagerly once first)";
         default: return "unknown error";
     }
 }

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(HERE, "libpsgd.so")
 
 PSGD_F32, PSGD_BF16 = 0, 1
 PSGD_OK = 0
-PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM = -1, -2, -3, -4, -5
+PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM, PSGD_E_CAPTURE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
     "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
