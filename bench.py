@@ -140,40 +140,6 @@ def make_workload(name, rank):
     return wl
 
 
-def device_gradients(wl, n_sets, torch, no_qr=False):
-    """Same recipe as synth.worker_gradient (shared low-rank signal + fresh iid noise per worker),
-    drawn on the device with torch's generator: the full-size sets are throughput inputs only."""
-    from paper_2509_11254_amd import synth
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(wl.seed)
-    gdt = torch.bfloat16 if wl.grad_dtype == synth.BF16 else torch.float32
-    spectrum = torch.tensor(wl.spectrum, dtype=torch.float32, device="cuda")
-    sets = [[] for _ in range(n_sets)]
-    E, Q, P, OUT = [], [], [], []
-    for l, spec in enumerate(wl.layers):
-        k = wl.signal_rank
-        u = torch.randn((spec.rows, k), generator=gen, device="cuda")
-        v = torch.randn((spec.cols, k), generator=gen, device="cuda")
-        if no_qr:
-            u, v = u / spec.rows ** 0.5, v / spec.cols ** 0.5
-        else:
-            u, v = torch.linalg.qr(u)[0], torch.linalg.qr(v)[0]
-        signal = (u * spectrum[None, :]) @ v.T
-        sigma = synth.noise_sigma(spec, wl)
-        for s in range(n_sets):
-            per_worker = []
-            for w in range(wl.n_workers):
-                g = signal + sigma * torch.randn((spec.rows, spec.cols), generator=gen, device="cuda")
-                per_worker.append(g.to(gdt).contiguous())
-            sets[s].append(per_worker)
-        del signal, u, v
-        E.append(torch.zeros((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
-        Q.append(torch.randn((spec.n, wl.r), generator=gen, device="cuda"))
-        P.append(torch.zeros((spec.m, wl.r), dtype=torch.float32, device="cuda"))
-        OUT.append(torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
-    return sets, E, Q, P, OUT
-
-
 def cpu_baseline(wl, sets, E, Q, torch):
     """The fp64 NumPy oracle, as it stands, on a bounded sample of the same workload."""
     import numpy as np
@@ -242,7 +208,7 @@ def main():
     sg = 2 if wl.grad_dtype == synth.BF16 else 4
     layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
     comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=args.lazy)
-    sets, E, Q, P, OUT = device_gradients(wl, args.sets, torch, args.no_qr)
+    sets, E, Q, P, OUT = synth.device_gradients(wl, args.sets, torch, args.no_qr)
     elems = sum(s.rows * s.cols for s in wl.layers)
     grad_bytes = elems * wl.n_workers * sg
     tau = wl.tau

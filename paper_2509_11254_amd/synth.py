@@ -225,3 +225,37 @@ def scaled_down(wl: Workload, rows: int, cols: int, n_layers: int = 1) -> Worklo
                     r=min(wl.r, min(rows, cols)), n_workers=wl.n_workers, grad_dtype=wl.grad_dtype,
                     signal_rank=k, spectrum=wl.spectrum[:k], noise_std=wl.noise_std, noise_rel=wl.noise_rel,
                     tau=wl.tau, steps=wl.steps, seed=wl.seed)
+
+
+def device_gradients(wl, n_sets, torch, no_qr=False):
+    """Same recipe as worker_gradient (shared low-rank signal + fresh iid noise per worker), drawn on the device
+    with torch's generator (passed in: this module does not import torch): the full-size batches of the benchmark
+    and of the parity tests that sample layers of them.  Returns (sets[s][l][w], E[l] zeros, Q[l], P[l], OUT[l])."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(wl.seed)
+    gdt = torch.bfloat16 if wl.grad_dtype == BF16 else torch.float32
+    spectrum = torch.tensor(wl.spectrum, dtype=torch.float32, device="cuda")
+    sets = [[] for _ in range(n_sets)]
+    E, Q, P, OUT = [], [], [], []
+    for l, spec in enumerate(wl.layers):
+        k = wl.signal_rank
+        u = torch.randn((spec.rows, k), generator=gen, device="cuda")
+        v = torch.randn((spec.cols, k), generator=gen, device="cuda")
+        if no_qr:
+            u, v = u / spec.rows ** 0.5, v / spec.cols ** 0.5
+        else:
+            u, v = torch.linalg.qr(u)[0], torch.linalg.qr(v)[0]
+        signal = (u * spectrum[None, :]) @ v.T
+        sigma = noise_sigma(spec, wl)
+        for s in range(n_sets):
+            per_worker = []
+            for w in range(wl.n_workers):
+                g = signal + sigma * torch.randn((spec.rows, spec.cols), generator=gen, device="cuda")
+                per_worker.append(g.to(gdt).contiguous())
+            sets[s].append(per_worker)
+        del signal, u, v
+        E.append(torch.zeros((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
+        Q.append(torch.randn((spec.n, wl.r), generator=gen, device="cuda"))
+        P.append(torch.zeros((spec.m, wl.r), dtype=torch.float32, device="cuda"))
+        OUT.append(torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
+    return sets, E, Q, P, OUT
