@@ -179,7 +179,12 @@ int psgd_refresh(psgd_ctx *ctx, void *workspace, void *stream, int layer, const 
                  float *Q, float *sigma);
 
 /* psgd_decompress -- Delta_hat[l] = P~[l] Q[l]^T in the layer's storage orientation (Algorithm 1,
- * return value).  out[l]: rows x cols (ld), element type out_dtype (PSGD_F32 or PSGD_BF16). */
+ * return value).  out[l]: rows x cols (ld), element type out_dtype (PSGD_F32 or PSGD_BF16).
+ * P and Q both NULL: the factors of the last psgd_compress / psgd_compress_refresh / psgd_compress_finish call on
+ * this workspace, taken from the operand copies that call left there (nothing is read from the P and Q buffers and
+ * nothing is re-packed: one launch less); INVALID_ARG if no such call was the last to write them (any other call
+ * with explicit P and Q, or psgd_refresh, comes in between).  The same holds for psgd_decompress_msgd and
+ * psgd_decompress_adam.  After psgd_compress_finish the copies hold the worker's own Q, not the averaged one. */
 int psgd_decompress(psgd_ctx *ctx, void *workspace, void *stream, const float *const *P,
                     const float *const *Q, void *const *out, int out_dtype);
 

@@ -103,6 +103,7 @@ struct psgd_ctx {
     void* outs_ws = nullptr;     // workspace that holds the current table of decompress outputs
     void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd / _adam
     void* m2_ws = nullptr;       // ... and of the second-moment buffers of psgd_decompress_adam
+    void* factors_ws = nullptr;  // workspace whose row-major operand copies are the P~, Q of the last compress call
     bool tables_valid = false;
     std::vector<const void*> hG;                       // the caller's current table
     std::vector<const void*> hGs[kGSlots];             // what each device slot holds (empty: nothing yet)
@@ -674,6 +675,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
     if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
+    ctx->factors_ws = nullptr;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
@@ -697,6 +699,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
         L.residual(nb, re);                        // E <- M - P~ Q_t^T
     }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    ctx->factors_ws = workspace;                   // the operand copies of P~_t and Q_t are in place
     return PSGD_OK;
 }
 
@@ -709,6 +712,7 @@ int psgd_compress_project(psgd_ctx* ctx, void* workspace, void* stream, const vo
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
+    ctx->factors_ws = nullptr;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
@@ -730,6 +734,7 @@ int psgd_compress_finish(psgd_ctx* ctx, void* workspace, void* stream, float* co
     L.prod(false, false, nb, ROLE_Q, EPI_PACK);         // Q = M^T P~ (this worker's M), operand copies
     L.residual(nb, false);                              // E <- M - P~ Q^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    ctx->factors_ws = workspace;                        // (copies of P~ and of this worker's Q)
     return PSGD_OK;
 }
 
@@ -755,6 +760,7 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
     if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;
+    ctx->factors_ws = nullptr;
     Launcher L = batch_launcher(ctx, workspace, st);
     if (ctx->pending) {
         // the subspace iteration forms M from a materialised E: settle what the deferred residual owes first
@@ -796,6 +802,7 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
         ctx->iters_gen_of_copy = ctx->iters_gen;
     }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
+    ctx->factors_ws = workspace;
     return PSGD_OK;
 }
 
@@ -809,6 +816,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
     if (is_capturing(st)) return PSGD_E_CAPTURE;       // (every call uploads a descriptor from the host)
+    ctx->factors_ws = nullptr;                         // (it rewrites operand copies of this layer)
     const Plan& p = ctx->plan[layer];
     // scratch descriptor: this layer's private regions, the caller's M/P/Q, splits sized for one layer
     LayerDev D;
@@ -840,14 +848,29 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     return PSGD_OK;
 }
 
+// Factors of a decompress-type call: the caller's P and Q (packed by the call), or, with both tables null, the
+// operand copies the last compress-type call left in this workspace.  *packed: whether the copies are in place.
+static int bind_factors(psgd_ctx* ctx, void* workspace, hipStream_t st, const float* const* P, const float* const* Q,
+                        bool* packed) {
+    *packed = !P && !Q;
+    if (*packed) {
+        if (!workspace || ctx->factors_ws != workspace) return PSGD_E_INVALID_ARG;
+        return bind_common(ctx, workspace, st, nullptr, nullptr, nullptr, nullptr);
+    }
+    if (!P || !Q) return PSGD_E_INVALID_ARG;
+    ctx->factors_ws = nullptr;          // the copies will be the caller's P and Q
+    return bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+}
+
 int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
                     void* const* out, int out_dtype) {
-    if (!ctx || !P || !Q || !out) return PSGD_E_INVALID_ARG;
+    if (!ctx || !out) return PSGD_E_INVALID_ARG;
     if (out_dtype != PSGD_F32 && out_dtype != PSGD_BF16) return PSGD_E_INVALID_ARG;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     int rc = check_table(reinterpret_cast<const void* const*>(out), (size_t)ctx->n_layers);
     if (rc != PSGD_OK) return rc;
-    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    bool packed = false;
+    rc = bind_factors(ctx, workspace, st, P, Q, &packed);
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
     if (sync_table(ctx->hOut, out, (size_t)ctx->n_layers) || ctx->outs_ws != workspace) {
@@ -858,7 +881,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
+    if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
@@ -867,14 +890,15 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
 
 int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
                          float* const* mom, float* const* X, float mu, float eta) {
-    if (!ctx || !P || !Q || !mom || !X) return PSGD_E_INVALID_ARG;
+    if (!ctx || !mom || !X) return PSGD_E_INVALID_ARG;
     if (!(mu >= 0.f && mu < 1.f) || !(eta == eta)) return PSGD_E_INVALID_ARG;      // Algorithm 2: 0 <= mu < 1
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
     const size_t nl = (size_t)ctx->n_layers;
     int rc = check_table(reinterpret_cast<const void* const*>(mom), nl);
     if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(X), nl);
     if (rc != PSGD_OK) return rc;
-    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    bool packed = false;
+    rc = bind_factors(ctx, workspace, st, P, Q, &packed);
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
     const bool changed = sync_table(ctx->hMom, mom, nl) | sync_table(ctx->hX, X, nl);
@@ -886,7 +910,7 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     ctx->msgd_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
+    if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, st));
@@ -897,7 +921,7 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
 int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const float* const* P, const float* const* Q,
                          float* const* m1, float* const* m2, float* const* X, int step, float eta, float beta1,
                          float beta2, float eps, float weight_decay) {
-    if (!ctx || !P || !Q || !m1 || !m2 || !X) return PSGD_E_INVALID_ARG;
+    if (!ctx || !m1 || !m2 || !X) return PSGD_E_INVALID_ARG;
     if (step < 1 || !(beta1 >= 0.f && beta1 < 1.f) || !(beta2 >= 0.f && beta2 < 1.f) || !(eps >= 0.f) ||
         !(eta == eta) || !(weight_decay == weight_decay))
         return PSGD_E_INVALID_ARG;
@@ -907,7 +931,8 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
     if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(m2), nl);
     if (rc == PSGD_OK) rc = check_table(reinterpret_cast<const void* const*>(X), nl);
     if (rc != PSGD_OK) return rc;
-    rc = bind_common(ctx, workspace, st, nullptr, nullptr, const_cast<float* const*>(Q), const_cast<float* const*>(P));
+    bool packed = false;
+    rc = bind_factors(ctx, workspace, st, P, Q, &packed);
     if (rc != PSGD_OK) return rc;
     char* ws = reinterpret_cast<char*>(workspace);
     const bool changed = sync_table(ctx->hMom, m1, nl) | sync_table(ctx->hX, X, nl);
@@ -929,7 +954,7 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
                            (float)((double)eta * (double)weight_decay)};
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
+    if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_m2s),

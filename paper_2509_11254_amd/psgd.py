@@ -127,6 +127,11 @@ def _ptr_table(tensors: Sequence) -> C.Array:
     return arr
 
 
+def _opt_table(tensors):
+    """Pointer table, or a null pointer for None (where the ABI gives NULL a meaning)."""
+    return _ptr_table(tensors) if tensors is not None else None
+
+
 def _stream_handle(stream) -> int:
     import torch
     s = stream if stream is not None else torch.cuda.current_stream()
@@ -223,14 +228,15 @@ class Compressor:
                                      P.data_ptr(), Q.data_ptr(), sigma.data_ptr() if sigma is not None else None))
 
     def decompress(self, P, Q, out, out_dtype: int = PSGD_F32, stream=None) -> None:
-        tp, tq, to = _ptr_table(P), _ptr_table(Q), _ptr_table(out)
+        """psgd_decompress: out[l] <- P[l] Q[l]^T; P = Q = None: the factors of the last compress call."""
+        tp, tq, to = _opt_table(P), _opt_table(Q), _ptr_table(out)
         self._keep = (tp, tq, to)
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, to, int(out_dtype)))
 
     def decompress_msgd(self, P, Q, mom, X, mu: float, eta: float, stream=None) -> None:
         """psgd_decompress_msgd: mom[l] <- mu mom[l] + P[l] Q[l]^T, X[l] <- X[l] - eta mom[l] (in place)."""
-        tp, tq, tm, tx = _ptr_table(P), _ptr_table(Q), _ptr_table(mom), _ptr_table(X)
+        tp, tq, tm, tx = _opt_table(P), _opt_table(Q), _ptr_table(mom), _ptr_table(X)
         self._keep = (tp, tq, tm, tx)
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress_msgd(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, tm, tx,
@@ -239,7 +245,7 @@ class Compressor:
     def decompress_adam(self, P, Q, m1, m2, X, step: int, eta: float, beta1: float = 0.9, beta2: float = 0.999,
                         eps: float = 1e-8, weight_decay: float = 0.0, stream=None) -> None:
         """psgd_decompress_adam: Adam / AdamW moments m1[l], m2[l] and weights X[l] from P[l] Q[l]^T (in place)."""
-        tp, tq, t1, t2, tx = _ptr_table(P), _ptr_table(Q), _ptr_table(m1), _ptr_table(m2), _ptr_table(X)
+        tp, tq, t1, t2, tx = _opt_table(P), _opt_table(Q), _ptr_table(m1), _ptr_table(m2), _ptr_table(X)
         self._keep = (tp, tq, t1, t2, tx)
         _check(self.lib, self.ctx,
                self.lib.psgd_decompress_adam(self.ctx, self._ws_ptr, _stream_handle(stream), tp, tq, t1, t2, tx,

@@ -188,3 +188,44 @@ def test_halves_on_degenerate_inputs():
     assert np.all(p[:, 2:] == 0)
     np.testing.assert_allclose(p[:, :2].T @ p[:, :2], np.eye(2), atol=2e-5)
     assert np.linalg.norm(e - (mat - p @ (p.T @ mat))) <= 1e-4 * np.linalg.norm(mat)
+
+
+def test_decompress_from_the_factors_of_the_last_compress_call():
+    """P = Q = NULL in the decompress-type calls: the operand copies the last compress call left in the workspace.
+    Same bits as with the factors passed explicitly; refused when some other call wrote the copies last."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config3(), 256, 256)
+    wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c")]
+    grads, errs, qs = _worker_inputs(wl, 51)
+    case = Case([(s.rows, s.cols) for s in wl.layers], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload(grads, [errs[l][0] for l in range(3)], qs)
+    out_a = [torch.zeros_like(e) for e in case.E]
+    out_b = [torch.zeros_like(e) for e in case.E]
+    with pytest.raises(psgd.PsgdError):
+        case.comp.decompress(None, None, out_a)                 # nothing compressed on this workspace yet
+    for refresh in (False, True):
+        case.compress(refresh=refresh)
+        case.comp.decompress(None, None, out_a)
+        case.comp.decompress(case.P, case.Q, out_b)
+        torch.cuda.synchronize()
+        for a, b in zip(out_a, out_b):
+            assert torch.equal(a, b), refresh
+        with pytest.raises(psgd.PsgdError):
+            case.comp.decompress(None, None, out_a)             # the explicit call above re-packed the copies
+    # the fused optimizer passes take the same convention
+    case.compress()
+    mom_a, x_a = [torch.zeros_like(e) for e in case.E], [torch.ones_like(e) for e in case.E]
+    mom_b, x_b = [torch.zeros_like(e) for e in case.E], [torch.ones_like(e) for e in case.E]
+    case.comp.decompress_msgd(None, None, mom_a, x_a, 0.9, 0.1)
+    case.comp.decompress_msgd(case.P, case.Q, mom_b, x_b, 0.9, 0.1)
+    torch.cuda.synchronize()
+    for a, b in zip(x_a + mom_a, x_b + mom_b):
+        assert torch.equal(a, b)
+    case.compress()
+    m1_a, m2_a = [torch.zeros_like(e) for e in case.E], [torch.zeros_like(e) for e in case.E]
+    m1_b, m2_b = [torch.zeros_like(e) for e in case.E], [torch.zeros_like(e) for e in case.E]
+    case.comp.decompress_adam(None, None, m1_a, m2_a, x_a, 1, 0.01)
+    case.comp.decompress_adam(case.P, case.Q, m1_b, m2_b, x_b, 1, 0.01)
+    torch.cuda.synchronize()
+    for a, b in zip(x_a + m1_a + m2_a, x_b + m1_b + m2_b):
+        assert torch.equal(a, b)
