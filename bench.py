@@ -207,7 +207,8 @@ def main():
     gd = psgd.PSGD_BF16 if wl.grad_dtype == synth.BF16 else psgd.PSGD_F32
     sg = 2 if wl.grad_dtype == synth.BF16 else 4
     layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
-    comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=args.lazy)
+    # (q_resident: this loop never writes the Q buffers between the library's calls)
+    comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=args.lazy, q_resident=True)
     sets, E, Q, P, OUT = synth.device_gradients(wl, args.sets, torch, args.no_qr)
     elems = sum(s.rows * s.cols for s in wl.layers)
     grad_bytes = elems * wl.n_workers * sg
@@ -314,7 +315,7 @@ def main():
     # the next step's forming pass; the flush that settles the last one is inside the timed region
     lazy_ms = None
     if not args.lazy:
-        comp_l = psgd.Compressor(layers, wl.n_workers, lazy_residual=True)
+        comp_l = psgd.Compressor(layers, wl.n_workers, lazy_residual=True, q_resident=True)
         for i in range(2):
             comp_l.compress(sets[i % args.sets], E, Q, P)
 

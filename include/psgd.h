@@ -114,6 +114,12 @@ typedef struct {
                                    psgd_flush_residual (psgd_compress_refresh settles it by itself).  Saves the
                                    8 bytes per element of the residual pass.  Not with m_policy = 2; r <= 128.
                                    0 = default: immediate residual                                        */
+    int32_t q_resident;         /* 1: the caller promises not to write the Q buffers between one compress-type call
+                                   on a workspace and the next psgd_compress on it (a single-GPU loop; not a
+                                   data-parallel one, which averages Q).  psgd_compress then takes Q_{t-1} from
+                                   the operand copies the previous call left in the workspace instead of packing
+                                   the Q buffers again (one launch less); the first call, and any call after
+                                   one that re-packed the copies, packs as usual.  0 = default: always pack    */
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */

@@ -568,6 +568,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         if (c->opt.power_iters < 0 || c->opt.power_iters > 64) rc = PSGD_E_INVALID_ARG;
         c->reform_m = pol == 2;
         if (c->opt.lazy_residual != 0 && c->opt.lazy_residual != 1) rc = PSGD_E_INVALID_ARG;
+        if (c->opt.q_resident != 0 && c->opt.q_resident != 1) rc = PSGD_E_INVALID_ARG;
         if (c->opt.lazy_residual && c->reform_m) rc = PSGD_E_INVALID_ARG;      // the deferred residual lives in the stored M
         c->lazy = c->opt.lazy_residual == 1;
     }
@@ -675,10 +676,13 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
     if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
+    // Q_{t-1} as a product operand: packed from the caller's buffers, unless they are promised to be what the last
+    // call wrote there, whose operand copies are still in place
+    const bool q_in_place = ctx->opt.q_resident == 1 && ctx->factors_ws == workspace;
     ctx->factors_ws = nullptr;
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
-    L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
+    if (!q_in_place) L.pack(ROLE_Q, cp, Launcher::PACK_TRANSPOSED);
     // P = M Q_{t-1} (M formed on the way and, unless it is formed again below, stored over E);
     // P~ = QR(P), operand copies of P~;  Q_t = M^T P~, operand copies of Q_t;  K times (Eq. (8)), K = 1 by default
     const bool re = ctx->reform_m;

@@ -35,7 +35,7 @@ class Options(C.Structure):
     _fields_ = [("refresh_iters", C.c_int32), ("refresh_oversample", C.c_int32),
                 ("refresh_warm_start", C.c_int32), ("seed", C.c_uint32), ("rank_tol", C.c_float),
                 ("precision", C.c_int32), ("m_policy", C.c_int32), ("power_iters", C.c_int32),
-                ("lazy_residual", C.c_int32)]
+                ("lazy_residual", C.c_int32), ("q_resident", C.c_int32)]
 
 
 class LayerStatus(C.Structure):
@@ -147,7 +147,7 @@ class Compressor:
     def __init__(self, layers: Sequence[Sequence[int]], n_workers: int, *, refresh_iters: int = 0,
                  refresh_oversample: int = -1, refresh_warm_start: bool = True, seed: int = 0x5EED5EED,
                  rank_tol: float = 0.0, precision: int = 0, m_policy: int = 0, power_iters: int = 0,
-                 lazy_residual: bool = False, device: str = "cuda:0",
+                 lazy_residual: bool = False, q_resident: bool = False, device: str = "cuda:0",
                  allocate: bool = True):
         self.lib = load_library()
         self.n_layers = len(layers)
@@ -158,7 +158,7 @@ class Compressor:
             descs[i].ld = int(l[4]) if len(l) > 4 else 0
         opt = Options(int(refresh_iters), int(refresh_oversample), 1 if refresh_warm_start else 0,
                       int(seed) & 0xFFFFFFFF, float(rank_tol), int(precision), int(m_policy), int(power_iters),
-                      1 if lazy_residual else 0)
+                      1 if lazy_residual else 0, 1 if q_resident else 0)
         self.ctx = C.c_void_p()
         rc = self.lib.psgd_init(C.byref(self.ctx), self.n_layers, descs, self.n_workers, C.byref(opt))
         _check(self.lib, None, rc)

@@ -229,3 +229,40 @@ def test_decompress_from_the_factors_of_the_last_compress_call():
     torch.cuda.synchronize()
     for a, b in zip(x_a + m1_a + m2_a, x_b + m1_b + m2_b):
         assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("lazy", [False, True])
+def test_q_resident_gives_the_same_steps(lazy):
+    """psgd_options.q_resident: Q_{t-1} taken from the operand copies of the previous call instead of packing the Q
+    buffers again.  Same bits as the default over a schedule with refresh steps, the fused decompress in between
+    (NULL factors: the copies stay), and an explicit decompress (which re-packs: the next step packs Q again)."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config3(), 256, 256)
+    wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c")]
+    shapes = [(s.rows, s.cols) for s in wl.layers]
+    grads0, errs, qs = _worker_inputs(wl, 61)
+    a = Case(shapes, wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=lazy)
+    b = Case(shapes, wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=lazy, q_resident=True)
+    for c in (a, b):
+        c.upload(grads0, [errs[l][0] for l in range(3)], qs)
+        c.OUT = [torch.zeros_like(e) for e in c.E]
+    for t in range(7):
+        for c in (a, b):
+            if t > 0:
+                sig = [synth.signal_matrix(s, wl, l) for l, s in enumerate(wl.layers)]
+                for l, s in enumerate(wl.layers):
+                    for w in range(wl.n_workers):
+                        c.G[l][w].copy_(to_dev_grad(synth.worker_gradient(s, wl, l, w, t, sig[l]), c.lds[l]))
+            c.compress(refresh=(t in (0, 3)))
+            if t == 4:
+                c.comp.decompress(c.P, c.Q, c.OUT)       # explicit factors: re-packs the copies
+            else:
+                c.comp.decompress(None, None, c.OUT)
+        torch.cuda.synchronize()
+        for l in range(3):
+            assert torch.equal(a.P[l], b.P[l]) and torch.equal(a.Q[l], b.Q[l]) and torch.equal(a.OUT[l], b.OUT[l]), (t, l)
+    if lazy:
+        a.comp.flush_residual(a.E); b.comp.flush_residual(b.E)
+        torch.cuda.synchronize()
+    for l in range(3):
+        assert torch.equal(a.E[l], b.E[l])
