@@ -353,7 +353,8 @@ def main():
         "dtype": "f32",
         "data": "synthetic",
         "config": dict(wl.describe(), refresh_steps_in_timed_region=n_refresh, gradient_sets=args.sets,
-                       decompress_in_step=not args.no_decompress, deferred_residual=bool(args.lazy)),
+                       decompress_in_step=not args.no_decompress, deferred_residual=bool(args.lazy),
+                       factors_from_workspace=True),    # q_resident = 1, decompress with P = Q = NULL
         "roofline": {"bound": "hbm", "kernel": "prod_kernel (M = mean G + E formed, stored, P = M Q)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
