@@ -87,3 +87,32 @@ def test_workspace_and_algorithmic_bytes(lib):
     assert lib.psgd_workspace_bytes(c2) > lib.psgd_workspace_bytes(c1)
     lib.psgd_destroy(c1)
     lib.psgd_destroy(c2)
+
+
+def test_struct_layouts_match_the_header(tmp_path):
+    """The ctypes mirrors of the ABI structs against the C compiler's view of include/psgd.h: sizes and the offset
+    of every field, and the error codes the binding names."""
+    import subprocess
+    fields = {"psgd_layer_desc": [f[0] for f in psgd.LayerDesc._fields_],
+              "psgd_options": [f[0] for f in psgd.Options._fields_],
+              "psgd_layer_status": [f[0] for f in psgd.LayerStatus._fields_]}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "psgd.h"', 'int main(void) {']
+    for s, fs in fields.items():
+        lines.append('printf("%s %%zu\\n", sizeof(%s));' % (s, s))
+        for f in fs:
+            lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (s, f, s, f))
+    lines.append('printf("codes %d %d %d %d %d %d\\n", PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, '
+                 'PSGD_E_NOMEM, PSGD_E_CAPTURE);')
+    lines += ['return 0; }']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)], check=True)
+    out = dict(l.split(" ", 1) for l in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    mirrors = {"psgd_layer_desc": psgd.LayerDesc, "psgd_options": psgd.Options, "psgd_layer_status": psgd.LayerStatus}
+    for s, cls in mirrors.items():
+        assert int(out[s]) == C.sizeof(cls), s
+        for f in fields[s]:
+            assert int(out["%s.%s" % (s, f)]) == getattr(cls, f).offset, (s, f)
+    assert [int(x) for x in out["codes"].split()] == [psgd.PSGD_E_INVALID_ARG, psgd.PSGD_E_SHAPE, psgd.PSGD_E_ALIGN,
+                                                      psgd.PSGD_E_HIP, psgd.PSGD_E_NOMEM, psgd.PSGD_E_CAPTURE]
