@@ -23,6 +23,10 @@
  *     beyond the call.  Pointer tables (G, E, Q, P arrays of pointers) are HOST arrays of device
  *     pointers.  The library owns only the host-side psgd_ctx and works inside the device
  *     workspace the caller passes (psgd_workspace_bytes bytes, 256-byte aligned, device memory).
+ *     The workspace carries state from call to call (pointer tables, per-layer iteration counts and diagnostics,
+ *     operand copies of the factors): between calls with the same context the caller leaves its contents alone.  A
+ *     context may be used with another workspace at any time (everything is uploaded again); a workspace that was
+ *     freed, or written by someone else, must not come back under the same address without psgd_workspace_reset.
  *   - Storage: row-major, `rows x cols` with leading dimension `ld` (elements).  The logical
  *     matrix has m = max(rows, cols), n = min(rows, cols); when rows < cols the stored buffer is
  *     the transpose of the logical matrix and is used as is (no physical transpose).
@@ -140,6 +144,11 @@ int psgd_init(psgd_ctx **out, int n_layers, const psgd_layer_desc *layers, int n
 
 /* Bytes of device workspace every compute call needs (partials, packed operands, small factors). */
 size_t psgd_workspace_bytes(const psgd_ctx *ctx);
+
+/* Forget what the context knows about the contents of any workspace: the next call uploads its tables again, clears the
+ * per-layer state (the next refresh of every layer runs its full iteration budget) and packs its operands.  For a
+ * caller that recycles workspace memory.  Host only.  Not while a deferred residual is owed (flush first): INVALID_ARG. */
+int psgd_workspace_reset(psgd_ctx *ctx);
 
 /* psgd_compress -- one SSP-Comp step for every layer (Algorithm 1 SSP-Comp + Eq. (7a) + residual):
  *   M = mean_i G[l*N + i] + E[l];  P = M Q[l];  P~ = QR(P) (R_ii > 0);  Q[l] <- M^T P~;

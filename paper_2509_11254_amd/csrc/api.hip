@@ -669,6 +669,19 @@ static int bind_common(psgd_ctx* ctx, void* workspace, hipStream_t st, const voi
     return upload_tables(ctx, workspace, st, changed, g_changed);
 }
 
+int psgd_workspace_reset(psgd_ctx* ctx) {
+    if (!ctx || ctx->pending) return PSGD_E_INVALID_ARG;
+    ctx->tables_valid = false;
+    ctx->bound_ws = nullptr;
+    ctx->outs_ws = nullptr;
+    ctx->msgd_ws = nullptr;
+    ctx->m2_ws = nullptr;
+    ctx->factors_ws = nullptr;
+    ctx->iters_gen++;
+    ctx->iters_bound = 0;
+    return PSGD_OK;
+}
+
 int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* const* G, float* const* E,
                   float* const* Q, float* const* P) {
     if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;

@@ -18,7 +18,7 @@ PSGD_OK = 0
 PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM, PSGD_E_CAPTURE = -1, -2, -3, -4, -5, -6
 
 EXPORTS = [
-    "psgd_init", "psgd_workspace_bytes", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
+    "psgd_init", "psgd_workspace_bytes", "psgd_workspace_reset", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
     "psgd_decompress", "psgd_decompress_msgd", "psgd_decompress_adam", "psgd_compress_project", "psgd_compress_finish", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_select", "psgd_profile_read",
@@ -71,6 +71,8 @@ def load_library() -> C.CDLL:
     lib.psgd_init.restype = C.c_int
     lib.psgd_workspace_bytes.argtypes = [vp]
     lib.psgd_workspace_bytes.restype = C.c_size_t
+    lib.psgd_workspace_reset.argtypes = [vp]
+    lib.psgd_workspace_reset.restype = C.c_int
     for name in ("psgd_compress", "psgd_compress_refresh", "psgd_compress_project"):
         fn = getattr(lib, name)
         fn.argtypes = [vp, vp, vp, pp, pp, pp, pp]
@@ -215,6 +217,10 @@ class Compressor:
         self._keep = (te, tq, tp)
         _check(self.lib, self.ctx,
                self.lib.psgd_compress_finish(self.ctx, self._ws_ptr, _stream_handle(stream), te, tq, tp))
+
+    def workspace_reset(self) -> None:
+        """psgd_workspace_reset: treat the workspace as new (its contents were lost or recycled)."""
+        _check(self.lib, self.ctx, self.lib.psgd_workspace_reset(self.ctx))
 
     def flush_residual(self, E, stream=None) -> None:
         """psgd_flush_residual: settle the residual a lazy_residual compress step left owed (E[l] <- E_{t+1})."""

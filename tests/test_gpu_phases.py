@@ -266,3 +266,25 @@ def test_q_resident_gives_the_same_steps(lazy):
         torch.cuda.synchronize()
     for l in range(3):
         assert torch.equal(a.E[l], b.E[l])
+
+
+def test_workspace_reset_after_the_workspace_was_overwritten():
+    """A workspace whose contents were lost: psgd_workspace_reset makes the next call treat it as new (tables
+    uploaded, per-layer state cleared, operands packed), and the steps go on as those of an undisturbed twin."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config3(), 640, 384)
+    grads, errs, qs = _worker_inputs(wl, 71)
+    a = Case([(640, 384)], wl.r, wl.n_workers, wl.grad_dtype, q_resident=True)
+    b = Case([(640, 384)], wl.r, wl.n_workers, wl.grad_dtype, q_resident=True)
+    for c in (a, b):
+        c.upload(grads, [errs[0][0]], qs)
+        c.compress()
+    b.comp.workspace.fill_(0xA5)                                # everything the library kept there is gone
+    b.comp.workspace_reset()
+    out = [torch.zeros_like(b.E[0])]
+    with pytest.raises(psgd.PsgdError):
+        b.comp.decompress(None, None, out)                      # no factors known in this workspace any more
+    for c in (a, b):
+        c.compress()
+    torch.cuda.synchronize()
+    assert torch.equal(a.P[0], b.P[0]) and torch.equal(a.Q[0], b.Q[0]) and torch.equal(a.E[0], b.E[0])
