@@ -122,6 +122,7 @@ struct psgd_ctx {
     hipEvent_t iters_ev = nullptr;
     bool iters_pending = false;      // a copy is under way
     int iters_bound = 0;             // > 0: known bound for the next batched refresh on bound_ws
+    int iters_least = 0;             // ... and the smallest per-layer count (0: not known)
     int iters_gen = 0, iters_gen_of_copy = 0;   // a copy made before something else changed the counts is ignored
     // optional timing of the three streaming kernels with event pairs on the caller's stream
     bool prof_on = false;
@@ -287,7 +288,7 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
     if (fresh) {
         // the iteration counts live in the workspace: a bound fetched from another one says nothing about this one
         ctx->iters_gen++;
-        ctx->iters_bound = 0;
+        ctx->iters_bound = 0; ctx->iters_least = 0;
     }
     if (fresh || desc_changed) {
         ctx->hLayers.resize(nl + 1);
@@ -490,7 +491,7 @@ double tol2_of(const psgd_ctx* c) {
 // Block subspace iteration + Rayleigh-Ritz for the layers of `L`: leaves P~ (Ritz vectors of the r
 // largest singular values) in thin[ROLE_P] and Q = M^T P~ in thin[ROLE_Q].
 void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, float* sigma_out, int final_cp,
-                      int launch_iters = 0) {
+                      int launch_iters = 0, int least_iters = 0) {
     const int wz = ctx->wz, cpz = ctx->cpz, nbz = cpz / 32;
     const int iters = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
     const int n_launch = launch_iters > 0 && launch_iters < iters ? launch_iters : iters;
@@ -504,7 +505,11 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
         // its previous refresh); launches past that number find their gate closed and exit at once
         L.gate = it | (iters << 16);
         // Z = orth(M Y);  Y = M^T Z, orthonormalised except in a layer's last iteration
-        L.prod_orth(true, form_first && it == 0, nbz, ROLE_ZP, wz, tol2, cpz, 0, Launcher::PASS2_LAST_ITERATION);
+        // (the second CholeskyQR pass on Z belongs to a layer's last iteration: where the smallest count among the
+        // layers is known, the iterations before it need no launch for it)
+        const bool may_be_last = least_iters <= 0 || it + 1 >= least_iters;
+        L.prod_orth(true, form_first && it == 0, nbz, ROLE_ZP, wz, tol2, cpz, 0,
+                    may_be_last ? Launcher::PASS2_LAST_ITERATION : Launcher::PASS2_NEVER);
         L.prod_orth(false, false, nbz, ROLE_ZQ, wz, tol2, cpz, 1, Launcher::PASS2_NEVER);
     }
     L.gate = -1;
@@ -678,7 +683,7 @@ int psgd_workspace_reset(psgd_ctx* ctx) {
     ctx->m2_ws = nullptr;
     ctx->factors_ws = nullptr;
     ctx->iters_gen++;
-    ctx->iters_bound = 0;
+    ctx->iters_bound = 0; ctx->iters_least = 0;
     return PSGD_OK;
 }
 
@@ -791,15 +796,17 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     const bool capturing = is_capturing(st);
     if (!capturing && ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
         ctx->iters_pending = false;
-        ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? ctx->h_iters[0] : 0;
+        ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? (ctx->h_iters[0] & 0xffff) : 0;
+        ctx->iters_least = ctx->iters_bound > 0 ? (ctx->h_iters[0] >> 16) : 0;
     }
     const int iters_max = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
     refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc,
-                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_bound);
+                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_bound,
+                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_least);
     L.residual(ctx->cpc / 32);
     // fetch the bound for the next one (pinned memory and the event are created on first use; without them
     // every refresh simply launches the whole budget)
-    ctx->iters_bound = 0;
+    ctx->iters_bound = 0; ctx->iters_least = 0;
     if (capturing) { ctx->iters_gen++; }
     else if (!ctx->h_iters) {
         void* hp = nullptr;
@@ -851,7 +858,7 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
                             hipMemcpyHostToDevice, st));
     // this call rewrites the layer's iteration count: what the host knows about the next batched refresh is void
     ctx->iters_gen++;
-    ctx->iters_bound = 0;
+    ctx->iters_bound = 0; ctx->iters_least = 0;
     Launcher L{};
     L.ctx = ctx; L.ws = ws; L.st = st;
     L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers_s[ctx->cur_slot]);

@@ -60,16 +60,21 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
 }
 
 // --------------------------------------------------------------------------------------------
-// iterations the next refresh of these layers will run, at most: the largest per-layer count.  The host fetches
-// the number asynchronously and stops launching iterations past it (they would find every gate closed).
+// iterations the next refresh of these layers will run: the largest and the smallest per-layer count.  The host
+// fetches them asynchronously, stops launching iterations past the largest (they would find every gate closed) and
+// leaves out the second-pass launches of the iterations before the smallest (no layer has its last one there).
 // --------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(64) void max_iterations_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
                                                             int n_ids, int mx, int* __restrict__ out) {
-    int k = 1;
-    for (int i = threadIdx.x; i < n_ids; i += 64) k = max(k, refresh_iterations(layers[ids[i]], mx));
+    int k = 1, kmin = 255;
+    for (int i = threadIdx.x; i < n_ids; i += 64) {
+        const int ki = refresh_iterations(layers[ids[i]], mx);
+        k = max(k, ki);
+        kmin = min(kmin, ki);
+    }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) k = max(k, __shfl_xor(k, off));
-    if (threadIdx.x == 0) out[0] = k;
+    for (int off = 32; off > 0; off >>= 1) { k = max(k, __shfl_xor(k, off)); kmin = min(kmin, __shfl_xor(kmin, off)); }
+    if (threadIdx.x == 0) out[0] = k | (min(kmin, k) << 16);     // largest count, and the smallest in the high half
 }
 
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st) {
