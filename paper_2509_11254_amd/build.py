@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpsgd.so")
 CEIL_LIB = os.path.join(HERE, "libpsgd_ceilings.so")      # plain streaming kernels for `bench.py --ceilings`
-SOURCES = ["api.hip", "prod.hip", "residual.hip", "thin.hip"]
+SOURCES = ["api.hip", "prod.hip", "form.hip", "residual.hip", "thin.hip"]
 CEIL_SOURCE = "ceilings.hip"
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-sanitize",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -26,7 +26,7 @@ def _compile(src: str) -> str:
 
 
 def build(verbose: bool = True) -> str:
-    with ThreadPoolExecutor(max_workers=5) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         objs = list(ex.map(_compile, SOURCES + [CEIL_SOURCE]))
     for lib, parts in ((LIB, objs[:-1]), (CEIL_LIB, objs[-1:])):
         cmd = ["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *parts]

@@ -15,6 +15,9 @@
 namespace psgd {
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers,
                        const int* ids, int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
+hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids,
+                           int n_ids, int max_tiles, int out_role, int epi, int nt_m, hipStream_t st);
+bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
@@ -23,7 +26,7 @@ hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* id
                        float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
 hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                        float* const* m1s, float* const* m2s, float* const* xs, const float* coef, hipStream_t st);
-hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
+hipError_t launch_finish(bool colmode, int form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
 hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
@@ -40,6 +43,8 @@ hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, 
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
                          hipStream_t st);
 hipError_t launch_copy(void* dst, const void* src, size_t n_bytes, hipStream_t st);
+hipError_t launch_put(void* dst, const void* src_host, size_t bytes, hipStream_t st);
+hipError_t launch_clear_status(const LayerDev* layers, const int* ids, int n_ids, hipStream_t st);
 enum ApplyModeHost { APPLY_PASS1 = 1, APPLY_PASS2 = 2, APPLY_RITZ = 3 };
 }  // namespace psgd
 
@@ -53,6 +58,7 @@ constexpr int kTargetTilesPlain = 512;   // ... per launch of a product that onl
                                          // (config 2: pass 2a 20.4 -> 18.6 us, its refresh step 1.00 -> 0.96 ms)
 constexpr int kTargetTilesWide = 256;    // ... at thin widths of 64 and more (see choose_split)
 constexpr int kMaxSplit = 32;
+constexpr int64_t kMaxLd = (int64_t)1 << 23;   // largest leading dimension (elements)
 
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
@@ -89,6 +95,9 @@ struct psgd_ctx {
     // batched splits
     int split_row_b = 1, split_col_b = 1;       // products that read M
     int split_row_bf = 1, split_col_bf = 1;     // forming passes
+    int split_row_v2 = 1;                       // forming pass on 32 x 256 tiles (form_row_kernel)
+    int grad_kind = 0;                          // 1: every layer has fp32 gradients, 2: every layer bf16, 0: mixed
+    bool nt_m = false;                          // the row-major layers' M is too large to be found in a cache again
     // workspace layout (byte offsets)
     // The gradient pointer table and the layer descriptors (which point into it) exist kGSlots times: a caller
     // that rotates between a few sets of gradient buffers finds its table already on the device.
@@ -118,12 +127,20 @@ struct psgd_ctx {
     // The per-layer iteration counts of the next refresh are decided on the device.  Their maximum is copied to
     // pinned host memory after every batched refresh (asynchronously, with an event behind it); a later refresh
     // that finds the event complete launches only that many iterations instead of the whole budget.
-    int* h_iters = nullptr;          // pinned, one int
-    hipEvent_t iters_ev = nullptr;
-    bool iters_pending = false;      // a copy is under way
-    int iters_bound = 0;             // > 0: known bound for the next batched refresh on bound_ws
-    int iters_least = 0;             // ... and the smallest per-layer count (0: not known)
-    int iters_gen = 0, iters_gen_of_copy = 0;   // a copy made before something else changed the counts is ignored
+    // A copy describes the counts as the refresh it was enqueued behind left them: it is used by the very next
+    // batched refresh on the same workspace and by no other (refresh_seq), and not at all if something else has
+    // changed the counts in between (iters_gen: a single-layer psgd_refresh, another workspace, a reset).  The
+    // copies go through a small ring of pinned words, so that a loop that runs ahead of the GPU (tau = 1) still
+    // has a free word for every refresh; when none is free the next refresh launches the whole budget.  Whatever
+    // the host launches, the device never runs an iteration that was not launched (see gate_open).
+    static constexpr int kIterSlots = 4;
+    struct IterFetch { int* h = nullptr; hipEvent_t ev = nullptr; bool pending = false; int gen = 0; uint64_t seq = 0; };
+    IterFetch fetch[kIterSlots];
+    bool fetch_ready = false;        // pinned words and events exist
+    bool fetch_failed = false;       // ... could not be created: every refresh launches the whole budget
+    int fetch_last = -1;             // slot of the copy enqueued behind the last batched refresh (-1: none)
+    uint64_t refresh_seq = 0;        // batched refreshes run so far
+    int iters_gen = 0;
     // optional timing of the three streaming kernels with event pairs on the caller's stream
     bool prof_on = false;
     int prof_mask = (1 << PSGD_PROF_TAGS) - 1;   // which of the tagged launches are timed
@@ -155,8 +172,9 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
     const int lenP[2] = {p.rowsP, p.colsP};
-    const int split[2] = {c->split_row_b > c->split_row_bf ? c->split_row_b : c->split_row_bf,
-                          c->split_col_b > c->split_col_bf ? c->split_col_b : c->split_col_bf};
+    int split[2] = {c->split_row_b > c->split_row_bf ? c->split_row_b : c->split_row_bf,
+                    c->split_col_b > c->split_col_bf ? c->split_col_b : c->split_col_bf};
+    if (c->split_row_v2 > split[0]) split[0] = c->split_row_v2;
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
@@ -186,6 +204,16 @@ int target_tiles_env() {
     return v;
 }
 
+// PSGD_FORM_ROW=0 (environment, measurement knob): forming passes use the 128 x 64 kernel everywhere
+bool form_row_env() {
+    static int v = -1;
+    if (v < 0) {
+        const char* e = std::getenv("PSGD_FORM_ROW");
+        v = (e && e[0] == '0') ? 0 : 1;
+    }
+    return v == 1;
+}
+
 // Reduction split of a launch with `base_tiles` output blocks.  cp: packed width of the thin operand.  At widths
 // of 64 and more one workgroup per compute unit is the target: the partial products that finish_kernel has to add
 // up grow with the width, and the wide product kernels do not gain from more workgroups (4096 x 4096: the step at
@@ -213,6 +241,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
     L.rowsP = p.rowsP; L.colsP = p.colsP;
     L.split_row = c->split_row_b; L.split_col = c->split_col_b;
     L.split_row_f = c->split_row_bf; L.split_col_f = c->split_col_bf;
+    L.split_row_v2 = c->split_row_v2;
     L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab_s[slot]) + (size_t)l * c->n_workers;
     L.S = c->hE.empty() ? nullptr : c->hE[l];
     const int side_p = side_of_role(p.transposed, ROLE_P), side_q = side_of_role(p.transposed, ROLE_Q);
@@ -285,18 +314,14 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
             return PSGD_E_CAPTURE;
         }
     }
-    if (fresh) {
-        // the iteration counts live in the workspace: a bound fetched from another one says nothing about this one
-        ctx->iters_gen++;
-        ctx->iters_bound = 0; ctx->iters_least = 0;
-    }
+    // (tables go to the device as kernel arguments, launch_put: the host arrays are free again when it returns)
+    if (fresh) ctx->iters_gen++;   // the iteration counts live in the workspace: a bound fetched from another one is void
     if (fresh || desc_changed) {
         ctx->hLayers.resize(nl + 1);
         for (int slot = 0; slot < psgd_ctx::kGSlots; ++slot) {
             for (int l = 0; l < nl; ++l) build_layer_dev(ctx, ws, l, slot, &ctx->hLayers[l]);
             ctx->hLayers[nl] = ctx->hLayers[0];
-            PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers_s[slot], ctx->hLayers.data(),
-                                    (size_t)(nl + 1) * sizeof(LayerDev), hipMemcpyHostToDevice, st));
+            PSGD_TRY(launch_put(ws + ctx->off_layers_s[slot], ctx->hLayers.data(), (size_t)(nl + 1) * sizeof(LayerDev), st));
         }
     }
     if (fresh) {
@@ -306,7 +331,7 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
         for (size_t i = 0; i < ctx->lists.norm.size(); ++i) ids[nl + i] = ctx->lists.norm[i];
         for (size_t i = 0; i < ctx->lists.tr.size(); ++i) ids[2 * (size_t)nl + i] = ctx->lists.tr[i];
         ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), hipMemcpyHostToDevice, st));
+        PSGD_TRY(launch_put(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), st));
     }
     if (fresh)
         for (auto& v : ctx->hGs) v.clear();
@@ -319,17 +344,15 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
             slot = ctx->next_victim;
             ctx->next_victim = (ctx->next_victim + 1) % psgd_ctx::kGSlots;
             ctx->hGs[slot] = ctx->hG;
-            PSGD_TRY(hipMemcpyAsync(ws + ctx->off_gtab_s[slot], ctx->hG.data(), ctx->hG.size() * sizeof(void*),
-                                    hipMemcpyHostToDevice, st));
+            PSGD_TRY(launch_put(ws + ctx->off_gtab_s[slot], ctx->hG.data(), ctx->hG.size() * sizeof(void*), st));
         }
         ctx->cur_slot = slot;
     }
     if (fresh) {
-        // status words of a new workspace start at zero ("iterations the next refresh needs" = unknown)
-        for (int l = 0; l < nl; ++l) {
-            const LayerRegion R = layer_region(ctx, ctx->plan[l]);
-            PSGD_TRY(hipMemsetAsync(ws + ctx->off_layer[l] + R.status, 0, kStatusWords * sizeof(int), st));
-        }
+        // status words of a new workspace start at zero ("iterations the next refresh needs" = unknown); a fill
+        // kernel, not a memset, so that nothing on this path would ever become a memset node of a graph
+        PSGD_TRY(launch_clear_status(reinterpret_cast<const LayerDev*>(ws + ctx->off_layers_s[0]),
+                                     reinterpret_cast<const int*>(ws + ctx->off_ids), nl, st));
     }
     ctx->bound_ws = workspace;
     ctx->tables_valid = true;
@@ -347,6 +370,7 @@ struct Launcher {
     int max_rows = 0, max_cols = 0, max_rowsP = 0, max_colsP = 0;
     int tiles_row = 0, tiles_col = 0, tiles_outer = 0, blocks_row = 0, blocks_col = 0;
     int tiles_row_f = 0, tiles_col_f = 0;       // forming passes
+    int tiles_row_v2 = 0, split_row_v2 = 1;     // the forming pass on 32 x 256 tiles
     int split_row = 1, split_col = 1, split_row_f = 1, split_col_f = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
@@ -354,6 +378,7 @@ struct Launcher {
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
     bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
+    bool use_form_row = true; // PSGD_FORM_ROW=0 (environment, measurement knob): the older 128 x 64 forming pass
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -384,14 +409,23 @@ struct Launcher {
         const int tiles_row = form ? tiles_row_f : this->tiles_row, tiles_col = form ? tiles_col_f : this->tiles_col;
         const int split_row = form ? split_row_f : this->split_row, split_col = form ? split_col_f : this->split_col;
         const bool onew = ctx->n_workers == 1;
-        note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        // forming pass on row-major layers at compress-step widths: the kernel built on 32 x 256 tiles
+        // (never inside the gated part of the subspace iteration: its first product carries gate iteration 0,
+        // which is open for every layer)
+        const bool v2 = form && p_like && n_norm > 0 && ctx->grad_kind != 0 && use_form_row &&
+                        form_row_supported(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form);
+        if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, ef, ctx->nt_m ? 1 : 0, st));
+        else note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
-        const bool split_n = p_like ? split_row > 1 : split_col > 1, split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, form, layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
-        if (split_t) note(launch_finish(p_like, form, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        const bool split_n = v2 ? split_row_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
+        if (split_n) note(launch_finish(!p_like, v2 ? 2 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        // (the 32-row blocks of that kernel leave the partial Gram matrices of an unsplit launch, one per 128 rows,
+        // to a small pass over the result)
+        if (v2 && !split_n && epi == EPI_GRAM) note(launch_thin_gram(layers, ids_norm, n_norm, blocks_row, out_role, 32 * nb, st));
         // (after a split product only the layers finish_kernel leaves to it -- wide, many Gram slots -- and none at
         // widths where there are no such layers)
         if (chol_gate >= -1) {
@@ -405,8 +439,8 @@ struct Launcher {
     // layer's last iteration.  cp > 0: also leave the split-bf16 operand copies of the result.
     enum Pass2 { PASS2_NEVER = 0, PASS2_ALWAYS = 1, PASS2_LAST_ITERATION = 2 };
     void prod_orth(bool p_like, bool form, int nb, int out_role, int w, double tol2, int cp, int kind, Pass2 pass2) {
-        const int g = gate < 0 ? -1 : (gate | kind << 8);
-        const int a2 = pass2 == PASS2_ALWAYS ? -1 : (pass2 == PASS2_NEVER || gate < 0) ? -2 : (gate | 2 << 8);
+        const int g = gate < 0 ? -1 : gate_with_kind(gate, kind);
+        const int a2 = pass2 == PASS2_ALWAYS ? -1 : (pass2 == PASS2_NEVER || gate < 0) ? -2 : gate_with_kind(gate, 2);
         // narrow blocks everywhere: the apply kernel factorises per workgroup and hands over to the second
         // factorisation itself; otherwise the second factorisation is a launch of its own
         const bool small = w <= 16;
@@ -467,6 +501,8 @@ void geometry(const psgd_ctx* c, int l, int split_row, int split_col, int split_
     mx(L.blocks_col, (int)((p.d.cols + 127) / 128));
     L.split_row = split_row; L.split_col = split_col;
     L.split_row_f = split_row_f; L.split_col_f = split_col_f;
+    L.split_row_v2 = c->split_row_v2;
+    mx(L.tiles_row_v2, (p.rowsP / 32) * c->split_row_v2);
     mx(L.tiles_outer, (int)((p.d.rows + 127) / 128) * (int)((p.d.cols + 127) / 128));
 }
 
@@ -480,6 +516,7 @@ Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     L.ids_all = ids; L.ids_norm = ids + nl; L.ids_tr = ids + 2 * (size_t)nl;
     L.n_all = nl; L.n_norm = (int)ctx->lists.norm.size(); L.n_tr = (int)ctx->lists.tr.size();
     for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, ctx->split_row_bf, ctx->split_col_bf, L);
+    L.use_form_row = form_row_env();
     return L;
 }
 
@@ -503,7 +540,7 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     for (int it = 0; it < n_launch; ++it) {
         // every layer runs its own number of iterations (decided on the device from the Ritz values of
         // its previous refresh); launches past that number find their gate closed and exit at once
-        L.gate = it | (iters << 16);
+        L.gate = make_gate(it, 0, iters, n_launch);
         // Z = orth(M Y);  Y = M^T Z, orthonormalised except in a layer's last iteration
         // (the second CholeskyQR pass on Z belongs to a layer's last iteration: where the smallest count among the
         // layers is known, the iterations before it need no launch for it)
@@ -546,6 +583,8 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         if (d.grad_dtype != PSGD_F32 && d.grad_dtype != PSGD_BF16) { rc = PSGD_E_INVALID_ARG; break; }
         if (d.ld == 0) d.ld = d.cols;
         if (d.ld < d.cols || d.ld % 8 != 0) { rc = PSGD_E_ALIGN; break; }
+        // the kernels address a lane's pieces of a 128-row tile with 32-bit byte offsets: 127 * ld * 4 < 2^32
+        if (d.ld > kMaxLd) { rc = PSGD_E_SHAPE; break; }
         Plan& p = c->plan[l];
         p.d = d;
         p.transposed = d.rows < d.cols ? 1 : 0;
@@ -571,6 +610,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         const int pol = c->opt.m_policy;
         if (pol < 0 || pol > 2) rc = PSGD_E_INVALID_ARG;
         if (c->opt.power_iters < 0 || c->opt.power_iters > 64) rc = PSGD_E_INVALID_ARG;
+        if (c->opt.refresh_iters < 0 || c->opt.refresh_iters > kMaxRefreshIterations) rc = PSGD_E_INVALID_ARG;
         c->reform_m = pol == 2;
         if (c->opt.lazy_residual != 0 && c->opt.lazy_residual != 1) rc = PSGD_E_INVALID_ARG;
         if (c->opt.q_resident != 0 && c->opt.q_resident != 1) rc = PSGD_E_INVALID_ARG;
@@ -608,12 +648,30 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     c->split_col_b = choose_split(base_col, min_chunks_col, false, c->cpc);
     c->split_row_bf = choose_split(base_row, min_chunks_row, true, c->cpc);
     c->split_col_bf = choose_split(base_col, min_chunks_col, true, c->cpc);
+    {
+        // the forming pass on 32 x 256 tiles: row-major layers only
+        int64_t base = 0, m_bytes = 0;
+        int min_chunks = 1 << 30;
+        bool f32 = false, b16 = false;
+        for (auto& p : c->plan) {
+            (p.d.grad_dtype == PSGD_F32 ? f32 : b16) = true;
+            if (p.transposed) continue;
+            base += p.rowsP / 32;
+            m_bytes += p.d.rows * p.d.cols * 4;
+            const int ch = (int)((p.d.cols + 255) / 256);
+            if (ch < min_chunks) min_chunks = ch;
+        }
+        c->split_row_v2 = base > 0 ? choose_split(base, min_chunks, true, 32) : 1;
+        c->grad_kind = f32 && b16 ? 0 : (f32 ? 1 : 2);
+        // M that the second pass can find in the 256 MB memory-side cache is stored with plain stores
+        c->nt_m = m_bytes > ((int64_t)96 << 20);
+    }
     // workspace layout
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t at = o; o = (size_t)round_up((int64_t)(o + bytes), 256); return at; };
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_layers_s[k] = take((size_t)(n_layers + 1) * sizeof(LayerDev));
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
-    c->off_iters = take(sizeof(int));
+    c->off_iters = take(psgd_ctx::kIterSlots * sizeof(int));
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_gtab_s[k] = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));
@@ -683,7 +741,6 @@ int psgd_workspace_reset(psgd_ctx* ctx) {
     ctx->m2_ws = nullptr;
     ctx->factors_ws = nullptr;
     ctx->iters_gen++;
-    ctx->iters_bound = 0; ctx->iters_least = 0;
     return PSGD_OK;
 }
 
@@ -691,9 +748,9 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
                   float* const* Q, float* const* P) {
     if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
-    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
     // Q_{t-1} as a product operand: packed from the caller's buffers, unless they are promised to be what the last
     // call wrote there, whose operand copies are still in place
     const bool q_in_place = ctx->opt.q_resident == 1 && ctx->factors_ws == workspace;
@@ -779,9 +836,9 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
                           float* const* Q, float* const* P) {
     if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
     hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;   // the kept operands live in the old one
     int rc = bind_common(ctx, workspace, st, G, E, Q, P);
     if (rc != PSGD_OK) return rc;
-    if (ctx->pending && ctx->bound_ws != workspace) return PSGD_E_INVALID_ARG;
     ctx->factors_ws = nullptr;
     Launcher L = batch_launcher(ctx, workspace, st);
     if (ctx->pending) {
@@ -791,39 +848,65 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
         L.prof_mute = false;
         ctx->pending = false;
     }
-    // how many iterations to launch: the bound fetched after the last refresh, if it has arrived.  (None of this
-    // bookkeeping under stream capture: a captured refresh launches the whole budget and fetches nothing.)
+    // how many iterations to launch: the bound fetched behind the last refresh, if that copy has arrived and nothing
+    // else has changed the counts since.  (None of this bookkeeping under stream capture: a captured refresh
+    // launches the whole budget and fetches nothing.)
     const bool capturing = is_capturing(st);
-    if (!capturing && ctx->iters_pending && hipEventQuery(ctx->iters_ev) == hipSuccess) {
-        ctx->iters_pending = false;
-        ctx->iters_bound = ctx->iters_gen_of_copy == ctx->iters_gen ? (ctx->h_iters[0] & 0xffff) : 0;
-        ctx->iters_least = ctx->iters_bound > 0 ? (ctx->h_iters[0] >> 16) : 0;
+    int bound = 0, least = 0;
+    if (!capturing && ctx->fetch_last >= 0) {
+        psgd_ctx::IterFetch& F = ctx->fetch[ctx->fetch_last];
+        if (F.pending && hipEventQuery(F.ev) == hipSuccess) {
+            F.pending = false;
+            if (F.gen == ctx->iters_gen && F.seq == ctx->refresh_seq) {
+                bound = F.h[0] & 0xffff;
+                least = bound > 0 ? (F.h[0] >> 16) : 0;
+            }
+        }
+        (void)hipGetLastError();      // (hipErrorNotReady of the query is not an error)
     }
     const int iters_max = ctx->opt.refresh_iters > 0 ? ctx->opt.refresh_iters : 16;
-    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc,
-                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_bound,
-                     (capturing || ctx->iters_pending) ? 0 : ctx->iters_least);
+    refresh_sequence(ctx, L, true, ctx->opt.refresh_warm_start != 0, nullptr, ctx->cpc, bound, least);
     L.residual(ctx->cpc / 32);
-    // fetch the bound for the next one (pinned memory and the event are created on first use; without them
-    // every refresh simply launches the whole budget)
-    ctx->iters_bound = 0; ctx->iters_least = 0;
-    if (capturing) { ctx->iters_gen++; }
-    else if (!ctx->h_iters) {
+    ctx->refresh_seq++;
+    ctx->fetch_last = -1;
+    if (capturing) ctx->iters_gen++;
+    // fetch the bound for the next one (pinned words and events are created on first use; without them every
+    // refresh simply launches the whole budget)
+    if (!capturing && !ctx->fetch_ready && !ctx->fetch_failed) {
         void* hp = nullptr;
-        if (hipHostMalloc(&hp, sizeof(int), hipHostMallocDefault) == hipSuccess) ctx->h_iters = static_cast<int*>(hp);
-        if (ctx->h_iters && hipEventCreateWithFlags(&ctx->iters_ev, hipEventDisableTiming) != hipSuccess) {
-            (void)hipHostFree(ctx->h_iters);
-            ctx->h_iters = nullptr;
+        bool ok = hipHostMalloc(&hp, psgd_ctx::kIterSlots * sizeof(int), hipHostMallocDefault) == hipSuccess;
+        for (int k = 0; ok && k < psgd_ctx::kIterSlots; ++k) {
+            ctx->fetch[k].h = static_cast<int*>(hp) + k;
+            ok = hipEventCreateWithFlags(&ctx->fetch[k].ev, hipEventDisableTiming) == hipSuccess;
+            if (!ok) ctx->fetch[k].ev = nullptr;
         }
+        if (!ok) {
+            for (auto& F : ctx->fetch) { if (F.ev) (void)hipEventDestroy(F.ev); F.ev = nullptr; F.h = nullptr; }
+            if (hp) (void)hipHostFree(hp);
+            ctx->fetch_failed = true;
+        }
+        ctx->fetch_ready = ok;
         (void)hipGetLastError();
     }
-    if (!capturing && ctx->h_iters && !ctx->iters_pending) {
-        int* d_it = reinterpret_cast<int*>(L.ws + ctx->off_iters);
-        L.note(launch_max_iterations(L.layers, L.ids_all, L.n_all, iters_max, d_it, st));
-        L.note(hipMemcpyAsync(ctx->h_iters, d_it, sizeof(int), hipMemcpyDeviceToHost, st));
-        L.note(hipEventRecord(ctx->iters_ev, st));
-        ctx->iters_pending = L.err == hipSuccess;
-        ctx->iters_gen_of_copy = ctx->iters_gen;
+    if (!capturing && ctx->fetch_ready) {
+        int slot = -1;
+        for (int k = 0; k < psgd_ctx::kIterSlots && slot < 0; ++k) {
+            psgd_ctx::IterFetch& F = ctx->fetch[k];
+            if (F.pending && hipEventQuery(F.ev) == hipSuccess) F.pending = false;
+            if (!F.pending) slot = k;
+        }
+        (void)hipGetLastError();
+        if (slot >= 0) {
+            psgd_ctx::IterFetch& F = ctx->fetch[slot];
+            int* d_it = reinterpret_cast<int*>(L.ws + ctx->off_iters) + slot;
+            L.note(launch_max_iterations(L.layers, L.ids_all, L.n_all, iters_max, d_it, st));
+            L.note(hipMemcpyAsync(F.h, d_it, sizeof(int), hipMemcpyDeviceToHost, st));
+            L.note(hipEventRecord(F.ev, st));
+            if (L.err == hipSuccess) {
+                F.pending = true; F.gen = ctx->iters_gen; F.seq = ctx->refresh_seq;
+                ctx->fetch_last = slot;
+            }
+        }
     }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     ctx->factors_ws = workspace;
@@ -854,11 +937,9 @@ int psgd_refresh(psgd_ctx* ctx, void* workspace, void* stream, int layer, const 
     D.part[0] = reinterpret_cast<float*>(ws + ctx->off_single_part[0]);
     D.part[1] = reinterpret_cast<float*>(ws + ctx->off_single_part[1]);
     ctx->hLayers[ctx->n_layers] = D;
-    PSGD_TRY(hipMemcpyAsync(ws + ctx->off_layers_s[ctx->cur_slot] + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev),
-                            hipMemcpyHostToDevice, st));
+    PSGD_TRY(launch_put(ws + ctx->off_layers_s[ctx->cur_slot] + (size_t)ctx->n_layers * sizeof(LayerDev), &D, sizeof(LayerDev), st));
     // this call rewrites the layer's iteration count: what the host knows about the next batched refresh is void
     ctx->iters_gen++;
-    ctx->iters_bound = 0; ctx->iters_least = 0;
     Launcher L{};
     L.ctx = ctx; L.ws = ws; L.st = st;
     L.layers = reinterpret_cast<const LayerDev*>(ws + ctx->off_layers_s[ctx->cur_slot]);
@@ -899,8 +980,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     char* ws = reinterpret_cast<char*>(workspace);
     if (sync_table(ctx->hOut, out, (size_t)ctx->n_layers) || ctx->outs_ws != workspace) {
         if (is_capturing(st)) { ctx->outs_ws = nullptr; return PSGD_E_CAPTURE; }
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*),
-                                hipMemcpyHostToDevice, st));
+        PSGD_TRY(launch_put(ws + ctx->off_outs, ctx->hOut.data(), ctx->hOut.size() * sizeof(void*), st));
     }
     ctx->outs_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
@@ -928,8 +1008,8 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     const bool changed = sync_table(ctx->hMom, mom, nl) | sync_table(ctx->hX, X, nl);
     if (changed || ctx->msgd_ws != workspace) {
         if (is_capturing(st)) { ctx->msgd_ws = nullptr; return PSGD_E_CAPTURE; }
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+        PSGD_TRY(launch_put(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), st));
+        PSGD_TRY(launch_put(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), st));
     }
     ctx->msgd_ws = workspace;
     Launcher L = batch_launcher(ctx, workspace, st);
@@ -962,13 +1042,13 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
     const bool changed = sync_table(ctx->hMom, m1, nl) | sync_table(ctx->hX, X, nl);
     if (changed || ctx->msgd_ws != workspace) {
         if (is_capturing(st)) { ctx->msgd_ws = nullptr; return PSGD_E_CAPTURE; }
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+        PSGD_TRY(launch_put(ws + ctx->off_moms, ctx->hMom.data(), nl * sizeof(void*), st));
+        PSGD_TRY(launch_put(ws + ctx->off_xs, ctx->hX.data(), nl * sizeof(void*), st));
     }
     ctx->msgd_ws = workspace;
     if (sync_table(ctx->hM2, m2, nl) || ctx->m2_ws != workspace) {
         if (is_capturing(st)) { ctx->m2_ws = nullptr; return PSGD_E_CAPTURE; }
-        PSGD_TRY(hipMemcpyAsync(ws + ctx->off_m2s, ctx->hM2.data(), nl * sizeof(void*), hipMemcpyHostToDevice, st));
+        PSGD_TRY(launch_put(ws + ctx->off_m2s, ctx->hM2.data(), nl * sizeof(void*), st));
     }
     ctx->m2_ws = workspace;
     // bias corrections in double: 1 - beta^t loses nothing for beta close to 1 and small t
@@ -1060,9 +1140,11 @@ int psgd_profile_read(psgd_ctx* ctx, double* total_ms, int* count, int n_tags) {
 
 void psgd_destroy(psgd_ctx* ctx) {
     if (!ctx) return;
-    if (ctx->iters_pending) (void)hipEventSynchronize(ctx->iters_ev);
-    if (ctx->iters_ev) (void)hipEventDestroy(ctx->iters_ev);
-    if (ctx->h_iters) (void)hipHostFree(ctx->h_iters);
+    for (auto& F : ctx->fetch) {
+        if (F.pending) (void)hipEventSynchronize(F.ev);
+        if (F.ev) (void)hipEventDestroy(F.ev);
+    }
+    if (ctx->fetch[0].h) (void)hipHostFree(ctx->fetch[0].h);
     for (hipEvent_t e : ctx->prof_ev) (void)hipEventDestroy(e);
     delete ctx;
 }

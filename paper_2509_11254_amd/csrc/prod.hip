@@ -287,7 +287,6 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     const int lj = lane & 15, lq = lane >> 4;     // lane coordinates of the 16 x 16 MFMA blocks (LAZY)
     static_assert(!ONEW || FORM, "the single-worker variants are forming passes");
     const float inv_n = ONEW ? 1.0f : 1.0f / (float)L.n_workers;
-    const int src_lenP = side_lenP(L, src_side);
     const PackRef XK = L.pack[src_side];
     static_assert(!LAZY || (FORM && (!COLMODE || NB == 1)), "the pending correction is applied by a forming pass");
     constexpr int CPW = 32 * NB + 8;                         // LDS row stride of the correction's column operand
@@ -362,7 +361,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     const int rot = (COLMODE || n_loc <= 0) ? 0
                     : ((ob & 7) * (n_loc >> 3) + 2 * (ob >> 3) + (int)blockIdx.y) % n_loc;
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
-    // thin operand chunk: pre-split, transposed [cp][lenP]; requested one chunk ahead, before the tile's own loads
+    // thin operand chunk: pre-split, in MFMA fragment order (PackRef::t: a 64-row chunk is one run of 64 cp elements);
+    // requested one chunk ahead, before the tile's own loads
     // (the wait counter is in issue order: waiting for the chunk then leaves the tile's loads in flight)
     // (only where the registers allow it: the forming passes for several workers are at their limit above width 32
     // and request it after the tile has been consumed instead)
@@ -371,9 +371,8 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
     auto b_prefetch = [&](int ch) {
 #pragma unroll
         for (int i = 0; i < NB; ++i) {
-            const int v = t + i * kThreads;        // 0 .. 32*NB*8-1
-            const int c = v >> 3, part = v & 7;
-            const int64_t goff = (int64_t)c * src_lenP + ch * BK + 8 * part;
+            const int v = t + i * kThreads;        // 0 .. 32*NB*8-1: 16-byte piece of the chunk
+            const int64_t goff = ((int64_t)ch * (BK / 16) * NB * 64 + v) * 8;
 #pragma unroll
             for (int k = 0; k < PL; ++k)
                 bq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(XK.t[k]) + goff);
@@ -460,8 +459,10 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
         auto b_to_lds = [&]() {
 #pragma unroll
             for (int i = 0; i < NB; ++i) {
+                // piece v = (k16, nb, lane): column 32 nb + (lane & 31), rows 16 k16 + 8 (lane >> 5) .. + 7 of the chunk
                 const int v = t + i * kThreads;
-                const int c = v >> 3, part = v & 7;
+                const int k16 = v / (64 * NB), rem = v - k16 * (64 * NB);
+                const int c = 32 * (rem >> 6) + (rem & 31), part = 2 * k16 + ((rem >> 5) & 1);
 #pragma unroll
                 for (int k = 0; k < PL; ++k)
                     *reinterpret_cast<uintx4*>(b_pl + k * BPL + c * LDSW + 8 * part) = bq[i][k];
@@ -650,7 +651,9 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     const int epi = epi_flags & EPI_KIND_MASK;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
-    const int n_split = form ? (colmode ? L.split_col_f : L.split_row_f) : (colmode ? L.split_col : L.split_row);
+    // form: 0 = a product that reads M, 1 = a forming pass of prod_kernel, 2 = the forming pass on 32 x 256 tiles
+    const int n_split = form == 2 ? L.split_row_v2
+                        : form ? (colmode ? L.split_col_f : L.split_row_f) : (colmode ? L.split_col : L.split_row);
     const int ob = blockIdx.x;
     if (n_split <= 1 || ob * BT >= out_len) return;
     const int out_lenP = side_lenP(L, out_side);
@@ -767,7 +770,7 @@ hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, i
     return hipGetLastError();
 }
 
-hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
+hipError_t launch_finish(bool colmode, int form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
@@ -780,7 +783,7 @@ hipError_t launch_finish(bool colmode, bool form, const LayerDev* layers, const 
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(finish_kernel, grid, block, lds, st, layers, ids, colmode ? 1 : 0, cp, out_role, epi, gate,
-                       chol_gate, a2gate, tol2, local_ok, form ? 1 : 0);
+                       chol_gate, a2gate, tol2, local_ok, form);
     return hipGetLastError();
 }
 

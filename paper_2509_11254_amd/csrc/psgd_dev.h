@@ -67,8 +67,14 @@ struct ThinRef {
 // X is written as a sum of `planes` bf16 numbers, plane 0 the rounded value and each further plane
 // the rounded remainder: two planes carry 16 mantissa bits (|error| <= 2^-17 |x|), three carry 24.
 //   n[k] : [lenP][cp]   row-major      (A/B operand of the rank-r outer product)
-//   t[k] : [cp][lenP]   transposed     (B operand of the tall-skinny products)
+//   t[k] : the B operand of the tall-skinny products (reduction over len) in the register layout of
+//          v_mfma_f32_32x32x16_bf16: [lenP / 16][cp / 32][64 lanes][8], lane li + 32 lg of block (k16, nb) holding
+//          X[16 k16 + 8 lg .. + 7][32 nb + li].  One MFMA B fragment of a wavefront is 1 KB of consecutive memory,
+//          so a kernel can load it straight into registers, and a 64-row chunk of all columns is one run of 4 cp bytes.
 constexpr int kMaxPlanes = 3;
+__host__ __device__ inline int64_t pack_t_offset(int k, int c, int cp) {
+    return ((((int64_t)(k >> 4) * (cp >> 5) + (c >> 5)) * 64 + (c & 31) + 32 * ((k >> 3) & 1)) << 3) + (k & 7);
+}
 struct PackRef {
     bf16_t* n[kMaxPlanes];
     bf16_t* t[kMaxPlanes];
@@ -88,6 +94,8 @@ struct LayerDev {
     int split_col;     // k-splits of the column-mode product (reduction over rows)
     int split_row_f;   // the same for the forming passes, which want about twice as many workgroups
     int split_col_f;
+    int split_row_v2;  // k-splits of the row-mode forming pass on 32 x 256 tiles (form_row_kernel)
+    int pad_[3];
     const void* const* G;   // n_workers device pointers
     float* S;               // E on entry, M between the sweeps, E_{t+1} on exit
     ThinRef thin[ROLE_COUNT];
@@ -172,24 +180,31 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 #pragma unroll
             for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
         }
-        const int64_t off = (int64_t)c * lenP + row0 + ib;
+        const int64_t off = pack_t_offset(row0 + ib, c, cp);      // (row0 + ib is a multiple of 8)
 #pragma unroll
         for (int k = 0; k < kMaxPlanes; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.t[k]) + off) = o[k];
     }
 }
 
-// Launches inside the subspace iteration carry a gate = iteration | kind << 8 | max_iterations << 16
-// (-1 outside it).  A layer runs k iterations: all max_iterations while status[4] is still 0 (first
-// refresh); status[4] itself (what its spectrum needs to converge, from the Ritz values of its last
-// refresh) when that is within the maximum; and kBudgetIterations when it is not -- the cut is then too
-// close to a cluster of singular values to converge across in the budget, and the members of such a
-// cluster compress almost equally well, so the budget is not burnt on it.  kind 1 marks the
-// orthonormalisation of Y, which the last executed iteration skips because the Rayleigh-Ritz step wants
-// Y = M^T Z itself; kind 2 is open in the last executed iteration only (the second CholeskyQR pass on Z,
-// which the Rayleigh-Ritz step needs exact).
+// Launches inside the subspace iteration carry a gate (-1 outside it), see make_gate: the iteration the launch
+// belongs to, its kind, the iteration budget and the number of iterations the host launches this time.
+// A layer runs k iterations: the whole budget while status[4] is still 0 (first refresh); status[4] itself (what
+// its spectrum needs to converge, from the Ritz values of its last refresh) when that is within the budget; and
+// kBudgetIterations when it is not -- the cut is then too close to a cluster of singular values to converge
+// across in the budget, and the members of such a cluster compress almost equally well, so the budget is not
+// burnt on it.  k never exceeds the number of launched iterations (the host may launch fewer than the budget when
+// it knows an upper bound of the counts; should that bound be out of date, a layer's last iteration is still one
+// that was launched).  kind 1 marks the orthonormalisation of Y, which the last executed iteration skips because
+// the Rayleigh-Ritz step wants Y = M^T Z itself; kind 2 is open in the last executed iteration only (the second
+// CholeskyQR pass on Z, which the Rayleigh-Ritz step needs exact).
 constexpr int kBudgetIterations = 8;
-// iterations the layer's next refresh runs when at most mx are launched
+constexpr int kMaxRefreshIterations = 255;
+__host__ __device__ inline int make_gate(int iteration, int kind, int budget, int launched) {
+    return iteration | kind << 8 | budget << 10 | launched << 18;
+}
+__host__ __device__ inline int gate_with_kind(int gate, int kind) { return (gate & ~(3 << 8)) | kind << 8; }
+// iterations the layer's next refresh runs when the budget is mx
 __device__ inline int refresh_iterations(const LayerDev& L, int mx) {
     int k = L.status[4];
     if (k <= 0) k = mx;
@@ -198,8 +213,9 @@ __device__ inline int refresh_iterations(const LayerDev& L, int mx) {
 }
 __device__ inline bool gate_open(const LayerDev& L, int gate) {
     if (gate < 0) return true;
-    const int it = gate & 0xff, kind = (gate >> 8) & 0xff, mx = gate >> 16;
-    const int k = refresh_iterations(L, mx);
+    const int it = gate & 0xff, kind = (gate >> 8) & 3, mx = (gate >> 10) & 0xff, launched = (gate >> 18) & 0xff;
+    int k = refresh_iterations(L, mx);
+    k = k < launched ? k : launched;
     if (kind == 2) return it == k - 1;
     return it < k - kind;
 }
@@ -236,6 +252,8 @@ __device__ inline void gram_tile_f64(const float* tile, int tw, int nrows, int w
             }
         }
 }
+
+static_assert(sizeof(LayerDev) % 16 == 0, "descriptor tables are written in 16-byte words");
 
 __device__ inline int side_len(const LayerDev& L, int side) { return side == SIDE_L ? L.rows : L.cols; }
 __device__ inline int side_lenP(const LayerDev& L, int side) { return side == SIDE_L ? L.rowsP : L.colsP; }

@@ -2,6 +2,8 @@
 // split products, the orthonormaliser, the Rayleigh-Ritz step of the refresh, random start blocks.
 //
 // The small factorisation of the orthonormaliser (CholeskyQR2) is in thin_dev.h.
+#include <string.h>
+
 #include "thin_dev.h"
 
 namespace psgd {
@@ -733,6 +735,49 @@ hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int 
         if (e != hipSuccess) return e;
     }
     hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, role, v_rows, sigma_out);
+    return hipGetLastError();
+}
+
+// --------------------------------------------------------------------------------------------
+// Host tables (layer descriptors, pointer tables, id lists) reach the workspace as kernel arguments: the runtime
+// copies a launch's arguments before the launch call returns, so the host arrays may be rewritten or go out of
+// scope at once, nothing depends on how the runtime stages copies from pageable memory, and no copy node ever
+// re-reads a host array.  One launch carries kPutBytes bytes.
+// --------------------------------------------------------------------------------------------
+constexpr int kPutBytes = 2048;
+struct PutChunk { uint4 w[kPutBytes / 16]; };
+
+__global__ __launch_bounds__(kPutBytes / 16) void put_kernel(uint4* __restrict__ dst, PutChunk c, int n16) {
+    if ((int)threadIdx.x < n16) dst[threadIdx.x] = c.w[threadIdx.x];
+}
+
+// dst: device, 16-byte aligned, with room for `bytes` rounded up to 16 (the tail is written as zeros)
+hipError_t launch_put(void* dst, const void* src_host, size_t bytes, hipStream_t st) {
+    const unsigned char* src = static_cast<const unsigned char*>(src_host);
+    unsigned char* d = static_cast<unsigned char*>(dst);
+    for (size_t o = 0; o < bytes; o += kPutBytes) {
+        const size_t n = bytes - o < (size_t)kPutBytes ? bytes - o : (size_t)kPutBytes;
+        PutChunk c;
+        memset(&c, 0, sizeof(c));
+        memcpy(&c, src + o, n);
+        hipLaunchKernelGGL(put_kernel, dim3(1), dim3(kPutBytes / 16), 0, st, reinterpret_cast<uint4*>(d + o), c,
+                           (int)((n + 15) / 16));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// status words of the addressed layers <- 0 (a workspace seen for the first time: "iterations the next refresh
+// needs" = unknown, arrival counters at rest)
+__global__ __launch_bounds__(64) void clear_status_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids) {
+    const LayerDev& L = layers[ids[blockIdx.x]];
+    if (threadIdx.x < kStatusWords) as_global(L.status)[threadIdx.x] = 0;
+}
+
+hipError_t launch_clear_status(const LayerDev* layers, const int* ids, int n_ids, hipStream_t st) {
+    if (n_ids <= 0) return hipSuccess;
+    hipLaunchKernelGGL(clear_status_kernel, dim3(n_ids), dim3(64), 0, st, layers, ids);
     return hipGetLastError();
 }
 
