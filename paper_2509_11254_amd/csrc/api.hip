@@ -3,6 +3,7 @@
 // step, one SVD-Comp step (Algorithm 1) and the reconstruction.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -16,8 +17,12 @@ namespace psgd {
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers,
                        const int* ids, int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
 hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids,
-                           int n_ids, int max_tiles, int out_role, int epi, int nt_m, hipStream_t st);
+                           int n_ids, int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
+                           int xtiles, hipStream_t st);
 bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy);
+hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                           int out_role, int epi, int gate, int nt_s, hipStream_t st);
+bool col_prod_supported(int nb);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
@@ -96,8 +101,14 @@ struct psgd_ctx {
     int split_row_b = 1, split_col_b = 1;       // products that read M
     int split_row_bf = 1, split_col_bf = 1;     // forming passes
     int split_row_v2 = 1;                       // forming pass on 32 x 256 tiles (form_row_kernel)
+    int split_col_v2 = 1;                       // column-mode product on 32 x 256 tiles (col_prod_kernel)
     int grad_kind = 0;                          // 1: every layer has fp32 gradients, 2: every layer bf16, 0: mixed
     bool nt_m = false;                          // the row-major layers' M is too large to be found in a cache again
+    // XCD table of the forming pass on 32 x 256 tiles (see form_row_kernel): 16 rows of xstride ints; built when the
+    // row-major layers are many enough to be dealt evenly to the 8 XCDs
+    std::vector<int> hXtab;
+    int xstride = 0, xtiles = 0;
+    size_t off_xtab = 0;
     // workspace layout (byte offsets)
     // The gradient pointer table and the layer descriptors (which point into it) exist kGSlots times: a caller
     // that rotates between a few sets of gradient buffers finds its table already on the device.
@@ -163,7 +174,7 @@ int fail_hip(psgd_ctx* c, hipError_t e) {
     } while (0)
 
 struct LayerRegion {
-    size_t part[2], pack[2][6], lz[2][3], z[2], gram, tmat, eval, status, end;
+    size_t part[2], pack[2][6], lz[2][3], lzf[2][3], z[2], gram, tmat, eval, status, end;
 };
 
 // byte layout of one layer's private workspace region, relative to its start
@@ -175,12 +186,16 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
     int split[2] = {c->split_row_b > c->split_row_bf ? c->split_row_b : c->split_row_bf,
                     c->split_col_b > c->split_col_bf ? c->split_col_b : c->split_col_bf};
     if (c->split_row_v2 > split[0]) split[0] = c->split_row_v2;
+    if (c->split_col_v2 > split[1]) split[1] = c->split_col_v2;
     for (int s = 0; s < 2; ++s) R.part[s] = take((size_t)split[s] * lenP[s] * c->wz * sizeof(float));
     for (int s = 0; s < 2; ++s)
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
     if (c->lazy && (!p.transposed || c->lazy_tr))
         for (int s = 0; s < 2; ++s)
-            for (int k = 0; k < c->planes; ++k) R.lz[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
+            for (int k = 0; k < c->planes; ++k) {
+                R.lz[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
+                R.lzf[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
+            }
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
     for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
     const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
@@ -242,6 +257,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
     L.split_row = c->split_row_b; L.split_col = c->split_col_b;
     L.split_row_f = c->split_row_bf; L.split_col_f = c->split_col_bf;
     L.split_row_v2 = c->split_row_v2;
+    L.split_col_v2 = c->split_col_v2;
     L.G = reinterpret_cast<const void* const*>(ws + c->off_gtab_s[slot]) + (size_t)l * c->n_workers;
     L.S = c->hE.empty() ? nullptr : c->hE[l];
     const int side_p = side_of_role(p.transposed, ROLE_P), side_q = side_of_role(p.transposed, ROLE_Q);
@@ -255,6 +271,7 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
             L.pack[s].n[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k]);
             L.pack[s].t[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k + 1]);
             L.lz[s][k] = (c->lazy && (!p.transposed || c->lazy_tr)) ? reinterpret_cast<bf16_t*>(base + R.lz[s][k]) : nullptr;
+            L.lzf[s][k] = (c->lazy && (!p.transposed || c->lazy_tr)) ? reinterpret_cast<bf16_t*>(base + R.lzf[s][k]) : nullptr;
         }
     }
     L.gram = reinterpret_cast<double*>(base + R.gram);
@@ -332,6 +349,7 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
         for (size_t i = 0; i < ctx->lists.tr.size(); ++i) ids[2 * (size_t)nl + i] = ctx->lists.tr[i];
         ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
         PSGD_TRY(launch_put(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), st));
+        if (!ctx->hXtab.empty()) PSGD_TRY(launch_put(ws + ctx->off_xtab, ctx->hXtab.data(), ctx->hXtab.size() * sizeof(int), st));
     }
     if (fresh)
         for (auto& v : ctx->hGs) v.clear();
@@ -371,6 +389,7 @@ struct Launcher {
     int tiles_row = 0, tiles_col = 0, tiles_outer = 0, blocks_row = 0, blocks_col = 0;
     int tiles_row_f = 0, tiles_col_f = 0;       // forming passes
     int tiles_row_v2 = 0, split_row_v2 = 1;     // the forming pass on 32 x 256 tiles
+    int tiles_col_v2 = 0, split_col_v2 = 1;     // the column-mode product on 32 x 256 tiles
     int split_row = 1, split_col = 1, split_row_f = 1, split_col_f = 1;
     hipError_t err = hipSuccess;
     bool prof_mute = false;   // the refresh's products are not part of the per-kernel timing
@@ -379,6 +398,7 @@ struct Launcher {
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
     bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
     bool use_form_row = true; // PSGD_FORM_ROW=0 (environment, measurement knob): the older 128 x 64 forming pass
+    bool use_xtab = true;     // PSGD_XTAB=0 (environment, measurement knob): plain layer-by-layer launch order
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -414,14 +434,20 @@ struct Launcher {
         // which is open for every layer)
         const bool v2 = form && p_like && n_norm > 0 && ctx->grad_kind != 0 && use_form_row &&
                         form_row_supported(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form);
-        if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, ef, ctx->nt_m ? 1 : 0, st));
-        else note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        // (the XCD table pays where the thin operands are a large part of what a workgroup reads: width 64)
+        const int* xtab = (ctx->xstride > 0 && use_xtab && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
+                              ? reinterpret_cast<const int*>(ws + ctx->off_xtab) : nullptr;
+        // the second product on row-major layers at those widths likewise
+        const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb);
+        if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, st));
+        else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, ef, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
+        else if (!c2) note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
-        const bool split_n = v2 ? split_row_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, v2 ? 2 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        const bool split_n = v2 ? split_row_v2 > 1 : c2 ? split_col_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
+        if (split_n) note(launch_finish(!p_like, v2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         // (the 32-row blocks of that kernel leave the partial Gram matrices of an unsplit launch, one per 128 rows,
         // to a small pass over the result)
@@ -503,6 +529,8 @@ void geometry(const psgd_ctx* c, int l, int split_row, int split_col, int split_
     L.split_row_f = split_row_f; L.split_col_f = split_col_f;
     L.split_row_v2 = c->split_row_v2;
     mx(L.tiles_row_v2, (p.rowsP / 32) * c->split_row_v2);
+    L.split_col_v2 = c->split_col_v2;
+    mx(L.tiles_col_v2, ((p.colsP + 255) / 256) * c->split_col_v2);
     mx(L.tiles_outer, (int)((p.d.rows + 127) / 128) * (int)((p.d.cols + 127) / 128));
 }
 
@@ -517,6 +545,7 @@ Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     L.n_all = nl; L.n_norm = (int)ctx->lists.norm.size(); L.n_tr = (int)ctx->lists.tr.size();
     for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, ctx->split_row_bf, ctx->split_col_bf, L);
     L.use_form_row = form_row_env();
+    { static int v = -1; if (v < 0) { const char* e = std::getenv("PSGD_XTAB"); v = (e && e[0] == '0') ? 0 : 1; } L.use_xtab = v == 1; }
     return L;
 }
 
@@ -595,6 +624,14 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         (p.transposed ? c->lists.tr : c->lists.norm).push_back(l);
         if (d.r > rmax) rmax = d.r;
     }
+    // launch order: the largest layers first (a launch ends with its shortest-lived workgroups)
+    auto by_size = [&](int a, int b) {
+        return c->plan[a].d.rows * c->plan[a].d.cols > c->plan[b].d.rows * c->plan[b].d.cols;
+    };
+    if (rc == PSGD_OK) {
+        std::stable_sort(c->lists.norm.begin(), c->lists.norm.end(), by_size);
+        std::stable_sort(c->lists.tr.begin(), c->lists.tr.end(), by_size);
+    }
     if (rc == PSGD_OK) {
         // operand planes: bf16 gradients are compared at 2e-2, two planes (2^-17) are ample; fp32
         // gradients are held to 1e-4 of ||E||, which can be 100x smaller than ||M||: three planes
@@ -650,21 +687,48 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     c->split_col_bf = choose_split(base_col, min_chunks_col, true, c->cpc);
     {
         // the forming pass on 32 x 256 tiles: row-major layers only
-        int64_t base = 0, m_bytes = 0;
-        int min_chunks = 1 << 30;
+        int64_t base = 0, base_c = 0, m_bytes = 0;
+        int min_chunks = 1 << 30, min_chunks_c = 1 << 30;
         bool f32 = false, b16 = false;
         for (auto& p : c->plan) {
             (p.d.grad_dtype == PSGD_F32 ? f32 : b16) = true;
             if (p.transposed) continue;
             base += p.rowsP / 32;
+            base_c += (p.colsP + 255) / 256;
             m_bytes += p.d.rows * p.d.cols * 4;
-            const int ch = (int)((p.d.cols + 255) / 256);
+            const int ch = (int)((p.d.cols + 255) / 256), chc = (int)((p.d.rows + 31) / 32);
             if (ch < min_chunks) min_chunks = ch;
+            if (chc < min_chunks_c) min_chunks_c = chc;
         }
         c->split_row_v2 = base > 0 ? choose_split(base, min_chunks, true, 32) : 1;
+        c->split_col_v2 = base_c > 0 ? choose_split(base_c, min_chunks_c, false, 32) : 1;
         c->grad_kind = f32 && b16 ? 0 : (f32 ? 1 : 2);
         // M that the second pass can find in the 256 MB memory-side cache is stored with plain stores
         c->nt_m = m_bytes > ((int64_t)96 << 20);
+        // XCD table: the row-major layers (positions in the id list `norm`), largest first, each to the XCD with the
+        // least work so far
+        const int n_norm = (int)c->lists.norm.size();
+        if (n_norm >= 32) {
+            c->xstride = n_norm + 2;
+            c->hXtab.assign((size_t)16 * c->xstride, 0);
+            std::vector<int> order(n_norm);
+            for (int i = 0; i < n_norm; ++i) order[i] = i;
+            auto tiles_of = [&](int pos) { return (c->plan[c->lists.norm[pos]].rowsP / 32) * c->split_row_v2; };
+            std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tiles_of(a) > tiles_of(b); });
+            int total[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int pos : order) {
+                int x = 0;
+                for (int k = 1; k < 8; ++k) if (total[k] < total[x]) x = k;
+                c->hXtab[(size_t)(8 + x) * c->xstride + count[x]] = pos;
+                total[x] += tiles_of(pos);
+                count[x] += 1;
+                c->hXtab[(size_t)x * c->xstride + count[x]] = total[x];
+            }
+            for (int x = 0; x < 8; ++x) {
+                c->hXtab[(size_t)x * c->xstride + c->xstride - 1] = count[x];
+                if (total[x] > c->xtiles) c->xtiles = total[x];
+            }
+        }
     }
     // workspace layout
     size_t o = 0;
@@ -672,6 +736,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_layers_s[k] = take((size_t)(n_layers + 1) * sizeof(LayerDev));
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
     c->off_iters = take(psgd_ctx::kIterSlots * sizeof(int));
+    c->off_xtab = take(c->hXtab.size() * sizeof(int) + 16);
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_gtab_s[k] = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));

@@ -37,7 +37,7 @@ __device__ inline floatx4 widen4(floatx4 v) { return v; }
 template <int NB, int PL, bool LAZY> constexpr int form_abuf() { return (PL == 2 && !LAZY) ? 2 : 1; }
 template <int NB, int PL, bool LAZY> constexpr size_t form_lds_bytes() {
     const size_t a = (size_t)form_abuf<NB, PL, LAZY>() * PL * FR * FLD * sizeof(bf16_t);
-    const size_t d = LAZY ? (size_t)FR * FDW * sizeof(float) : 0;
+    const size_t d = LAZY ? (size_t)FR * FDW * sizeof(float) + (size_t)2 * NB * PL * 64 * 8 * sizeof(bf16_t) : 0;
     const size_t red = (size_t)4 * FR * (32 * NB + 1) * sizeof(float);
     return a + d > red ? a + d : red;
 }
@@ -47,17 +47,32 @@ template <int NB, int PL, bool LAZY> constexpr size_t form_lds_bytes() {
 template <int NB, int PL, bool GBF, bool ONEW, bool LAZY>
 __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* __restrict__ layers,
                                                                 const int* __restrict__ ids, int out_role,
-                                                                int epi_flags, int nt_m) {
+                                                                int epi_flags, int nt_m,
+                                                                const int* __restrict__ xtab, int xstride) {
     using GV = typename std::conditional<GBF, uintx2, floatx4>::type;
     using GT = typename std::conditional<GBF, bf16_t, float>::type;
     constexpr int cp = 32 * NB;
     constexpr int ABUF = form_abuf<NB, PL, LAZY>();
     constexpr int APL = FR * FLD;
-    const LayerDev& L = layers[ids[blockIdx.y]];
+    // Which layer and tile.  Plain launches: blockIdx.y = layer, blockIdx.x = tile.  With an XCD table (many layers):
+    // consecutive workgroup ids go to consecutive XCDs, and XCD x works through the layers dealt to it one after the
+    // other -- xtab row x holds the prefix sums of their tile counts, row 8 + x their positions in `ids` -- so that
+    // the workgroups that share an L2 at any time read the thin operands of one or two layers, which fit it.
+    int layer_pos = blockIdx.y, tile = blockIdx.x;
+    if (xtab) {
+        const int x = blockIdx.x & 7, s = blockIdx.x >> 3;
+        const int* pre = xtab + x * xstride;
+        const int n_mine = pre[xstride - 1];               // layers of this XCD (last word of the row)
+        if (n_mine == 0 || s >= pre[n_mine]) return;
+        int j = 0;
+        while (s >= pre[j + 1]) ++j;
+        layer_pos = xtab[(8 + x) * xstride + j];
+        tile = s - pre[j];
+    }
+    const LayerDev& L = layers[ids[layer_pos]];
     const bool store_m = !(epi_flags & EPI_KEEP_E);
     const int n_ob = L.rowsP / FR;                       // (row blocks past the end write the zeros of the padding)
     const int n_split = L.split_row_v2;
-    const int tile = blockIdx.x;
     if (tile >= n_ob * n_split) return;
     const int sp = tile % n_split, ob = tile / n_split;
     const int row0 = ob * FR;
@@ -69,9 +84,11 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* a_pl = reinterpret_cast<bf16_t*>(smem);                              // ABUF x PL planes of [FR][FLD]
     float* d_lds = reinterpret_cast<float*>(a_pl + ABUF * PL * APL);             // [FR][FDW] (LAZY)
+    bf16_t* p_lds = reinterpret_cast<bf16_t*>(d_lds + FR * FDW);                 // [2 NB][PL][64][8] (LAZY)
 
     const int t = threadIdx.x;
-    const int lane = t & 63, wv = t >> 6;
+    // (the wave index as a scalar: addresses are then a uniform base in scalar registers plus one 32-bit lane offset)
+    const int lane = t & 63, wv = __builtin_amdgcn_readfirstlane(t >> 6);
     const int li = lane & 31, lg = lane >> 5;
     const float inv_n = ONEW ? 1.0f : 1.0f / (float)L.n_workers;
     const int nw = ONEW ? 1 : L.n_workers;
@@ -79,41 +96,49 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     const int colsP = L.colsP;
     PSGD_GLOBAL float* S = as_global(L.S);
     // this thread's pieces of a tile: piece u at row row0 + 4 u + wv, columns ch * FK + 4 lane .. + 3
-    const int64_t lane_off = (int64_t)(row0 + wv) * ld + 4 * lane;
+    const int64_t wave_off = (int64_t)(row0 + wv) * ld;       // (uniform)
     const int64_t ustep = 4 * ld;
+    const unsigned lane_e = 16u * (unsigned)lane, lane_g = (unsigned)sizeof(GV) * (unsigned)lane, lane_f = 16u * (unsigned)lane;
     auto grad_ptr = [&](int w) { return reinterpret_cast<const PSGD_GLOBAL GT*>(as_global(as_global(L.G)[w])); };
     auto tile_full = [&](int ch) { return row0 + FR <= L.rows && ch * FK + FK <= L.cols; };
     auto piece_ok = [&](int ch, int u) { return row0 + 4 * u + wv < L.rows && ch * FK + 4 * lane < L.cols; };
     auto load_g = [&](int w, int ch, GV (&x)[8]) {
-        const PSGD_GLOBAL GT* gp = grad_ptr(w) + lane_off + (int64_t)ch * FK;
+        const PSGD_GLOBAL GT* gp = grad_ptr(w) + wave_off + (int64_t)ch * FK;
+        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL GV*>(reinterpret_cast<const PSGD_GLOBAL char*>(gp + u * ustep) + lane_g); };
         if (tile_full(ch)) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = ld_stream<NT_G>(reinterpret_cast<const PSGD_GLOBAL GV*>(gp + u * ustep));
+            for (int u = 0; u < 8; ++u) x[u] = ld_stream<NT_G>(at(u));
         } else {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 x[u] = GV{};
-                if (piece_ok(ch, u)) x[u] = ld_stream<NT_G>(reinterpret_cast<const PSGD_GLOBAL GV*>(gp + u * ustep));
+                if (piece_ok(ch, u)) x[u] = ld_stream<NT_G>(at(u));
             }
         }
     };
     auto load_e = [&](int ch, floatx4 (&x)[8]) {
-        const PSGD_GLOBAL float* ep = S + lane_off + (int64_t)ch * FK;
+        const PSGD_GLOBAL float* ep = S + wave_off + (int64_t)ch * FK;
+        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(ep + u * ustep) + lane_e); };
         if (tile_full(ch)) {
 #pragma unroll
-            for (int u = 0; u < 8; ++u) x[u] = ld_stream<NT_E_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(ep + u * ustep));
+            for (int u = 0; u < 8; ++u) x[u] = ld_stream<NT_E_IN>(at(u));
         } else {
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 x[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (piece_ok(ch, u)) x[u] = ld_stream<NT_E_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(ep + u * ustep));
+                if (piece_ok(ch, u)) x[u] = ld_stream<NT_E_IN>(at(u));
             }
         }
     };
-    // Each row block starts its walk at a step of its own and wraps around (consecutive blocks go to different XCDs,
-    // the blocks of one XCD start near each other, every layer adds a phase): blocks walking in step would all be on
-    // the same few memory channels, and this order keeps the thin operand chunks of the blocks that share an L2 close.
-    const int rot = n_loc > 0 ? ((ob & 7) * (n_loc >> 3) + 2 * (ob >> 3) + (int)blockIdx.y) % n_loc : 0;
+    // Each row block starts its walk at a step of its own and wraps around: blocks walking in step would all be on
+    // the same few memory channels (4.9 against 5.6 TB/s for the bare access pattern).  Plain launches: consecutive
+    // blocks go to different XCDs, XCD x starts an eighth of the walk after XCD x - 1, block j of an XCD two steps
+    // after block 0, every layer adds a phase.  With the XCD table the blocks of an XCD are consecutive blocks of one
+    // layer, which are spread over the whole walk.  (Keeping the blocks of an XCD within two steps of each other
+    // instead helps the L2 hit rate of the thin operands and hurts the channel spread by more: 12.6 against 11.05 ms
+    // on the 7B-shaped set without the table.)
+    int rot = 0;
+    if (n_loc > 0) rot = xtab ? (ob + layer_pos) % n_loc : ((ob & 7) * (n_loc >> 3) + 2 * (ob >> 3) + layer_pos) % n_loc;
     auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
 
     // thin operand: this wave's fragments for its 64 columns of the step, four k-steps of 16
@@ -122,55 +147,53 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     auto load_b = [&](int ch) {
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            const int kg = ch * (FK / 16) + 4 * wv + ks;
-            const bool ok = 16 * kg < colsP;                  // (uniform; past the padded length M is zero anyway)
+            // (past the padded length the fragment of the last k-step is read instead: M is zero there, and the
+            // operand copies hold finite numbers)
+            const int kg = min(ch * (FK / 16) + 4 * wv + ks, colsP / 16 - 1);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int k = 0; k < PL; ++k) {
-                    bfrag[ks][nb][k] = bf16x8{};
-                    if (ok) bfrag[ks][nb][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                                as_global(XK.t[k]) + (((int64_t)kg * NB + nb) * 64 + lane) * 8);
-                }
+                for (int k = 0; k < PL; ++k)
+                    bfrag[ks][nb][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
+                        reinterpret_cast<const PSGD_GLOBAL char*>(as_global(XK.t[k]) + ((int64_t)kg * NB + nb) * 512) + lane_f);
         }
     };
-    // LAZY: the rows of the kept P~ copy this workgroup owns stay in registers (A operand of the correction, all
-    // k-steps); the kept Q rows of a step's columns are the B operand, loaded per step like the thin operand above.
-    // Wave v forms the correction for columns 64 v .. 64 v + 63 of the step.
-    bf16x8 pres[LAZY ? 2 * NB : 1][PL];
-    if (LAZY) {
+    // LAZY: the correction d_lds[row][col] = sum_k P~[row0 + row][k] Q[ch * FK + col][k] of a step; wave v forms it
+    // for columns 64 v .. 64 v + 63.  The workgroup's 32 rows of the kept P~ copy (A operand, all k-steps) sit in
+    // LDS in fragment order; the kept Q rows of the step's columns (B operand) are requested one step ahead, before
+    // the next tile's own loads (the wait counter is in issue order: fragments requested after the tile could only be
+    // used once the tile had arrived).
+    bf16x8 qv[LAZY ? 2 : 1][LAZY ? 2 * NB : 1][PL];
+    auto load_q = [&](int ch, int q) {
+        {
+            // 32-column block of the kept Q copy; past the padded length the last block, whose product lands on
+            // columns that are outside the matrix and masked
+            const int cblk = min(ch * (FK / 32) + 2 * wv + q, colsP / 32 - 1);
 #pragma unroll
-        for (int ks = 0; ks < 2 * NB; ++ks)
+            for (int ks = 0; ks < 2 * NB; ++ks)
 #pragma unroll
-            for (int k = 0; k < PL; ++k)
-                pres[ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                    as_global(L.lz[SIDE_L][k]) + (int64_t)(row0 + li) * cp + 16 * ks + 8 * lg);
-    }
-    auto correction = [&](int ch) {
-        // d_lds[row][col] = sum_k P~[row0 + row][k] Q[ch * FK + col][k] for this wave's 64 columns
-#pragma unroll
-        for (int q = 0; q < 2; ++q) {
+                for (int k = 0; k < PL; ++k)
+                    qv[q][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
+                        reinterpret_cast<const PSGD_GLOBAL char*>(as_global(L.lzf[SIDE_W][k]) + ((int64_t)cblk * (2 * NB) + ks) * 512) + lane_f);
+        }
+    };
+    auto correction = [&](int q) {
+        {
             floatx16 d;
 #pragma unroll
             for (int v = 0; v < 16; ++v) d[v] = 0.f;
-            const int col = ch * FK + 64 * wv + 32 * q + li;
-            const bool ok = col < colsP;
 #pragma unroll
             for (int ks = 0; ks < 2 * NB; ++ks) {
-                bf16x8 qv[PL];
+                bf16x8 pv[PL];
 #pragma unroll
-                for (int k = 0; k < PL; ++k) {
-                    qv[k] = bf16x8{};
-                    if (ok) qv[k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                                as_global(L.lz[SIDE_W][k]) + (int64_t)col * cp + 16 * ks + 8 * lg);
-                }
+                for (int k = 0; k < PL; ++k) pv[k] = *reinterpret_cast<const bf16x8*>(p_lds + ((ks * PL + k) * 64 + lane) * 8);
 #pragma unroll
                 for (int sum = 2 * (PL - 1); sum >= 0; --sum)
 #pragma unroll
                     for (int ka = 0; ka < PL; ++ka) {
                         const int kb = sum - ka;
                         if (kb >= 0 && kb < PL && form_keep_term<PL>(ka, kb))
-                            d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pres[ks][ka], qv[kb], d, 0, 0, 0);
+                            d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv[ka], qv[q][ks][kb], d, 0, 0, 0);
                     }
             }
 #pragma unroll
@@ -192,7 +215,16 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         load_g(0, chunk_at(0), g);
         load_b(chunk_at(0));
         if (LAZY) {
-            correction(chunk_at(0));
+            for (int i = t; i < 2 * NB * PL * 64; i += kThreads) {
+                const int ks = i / (PL * 64), k = (i / 64) % PL, ln = i & 63;
+                *reinterpret_cast<uintx4*>(p_lds + i * 8) = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(
+                    as_global(L.lzf[SIDE_L][k]) + (((int64_t)ob * (2 * NB) + ks) * 64 + ln) * 8);
+            }
+            load_q(chunk_at(0), 0);
+            load_q(chunk_at(0), 1);
+            __syncthreads();
+            correction(0);
+            correction(1);
             __syncthreads();                 // (later steps: the barrier that ends the step before)
         }
     }
@@ -244,9 +276,10 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         if (!full) {
             // pieces outside the matrix were loaded as zero; cut the column tail (the padding up to ld is not data)
             const int c = ch * FK + 4 * lane;
-            const bool k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
+            const bool k0 = c < L.cols, k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
+                m[u].x = k0 ? m[u].x : 0.f;           // (LAZY: the correction is not zero there)
                 m[u].y = k1 ? m[u].y : 0.f;
                 m[u].z = k2 ? m[u].z : 0.f;
                 m[u].w = k3 ? m[u].w : 0.f;
@@ -254,21 +287,22 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         }
         // ---- M back in place of E
         if (store_m) {
-            PSGD_GLOBAL float* mp = S + lane_off + (int64_t)ch * FK;
+            PSGD_GLOBAL float* mp = S + wave_off + (int64_t)ch * FK;
+            auto at = [&](int u) { return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(mp + u * ustep) + lane_e); };
             if (full) {
                 if (nt_m) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(m[u], reinterpret_cast<PSGD_GLOBAL floatx4*>(mp + u * ustep));
+                    for (int u = 0; u < 8; ++u) __builtin_nontemporal_store(m[u], reinterpret_cast<PSGD_GLOBAL floatx4*>(at(u)));
                 } else {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) *reinterpret_cast<PSGD_GLOBAL floatx4*>(mp + u * ustep) = m[u];
+                    for (int u = 0; u < 8; ++u) *reinterpret_cast<PSGD_GLOBAL floatx4*>(at(u)) = m[u];
                 }
             } else {
                 const int c = ch * FK + 4 * lane;
 #pragma unroll
                 for (int u = 0; u < 8; ++u) {
                     if (!piece_ok(ch, u)) continue;
-                    PSGD_GLOBAL float* p = mp + u * ustep;
+                    PSGD_GLOBAL float* p = at(u);
                     if (c + 3 < L.cols) {
                         *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = m[u];
                     } else {
@@ -300,10 +334,16 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
             for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_cur + k * APL + (4 * u + wv) * FLD + 4 * lane) = o[k];
         }
         __syncthreads();
-        // ---- the next step's tile goes out now and is in flight during the MFMA phase
+        // ---- the next step's tile goes out now and is in flight during the MFMA phase.  (LAZY: half of the kept Q
+        // fragments of the next step go out first, the other half and the tile after this step's product: the
+        // registers do not hold the tile, both sets of fragments and the accumulators at once.)
         if (it + 1 < n_loc) {
-            load_e(chunk_at(it + 1), e);
-            load_g(0, chunk_at(it + 1), g);
+            if (LAZY) {
+                load_q(chunk_at(it + 1), 0);
+            } else {
+                load_e(chunk_at(it + 1), e);
+                load_g(0, chunk_at(it + 1), g);
+            }
         }
         // ---- MFMA: 32 rows x cp columns, this wave's 64 of the step's 256 reduction indices
 #pragma unroll
@@ -323,10 +363,17 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
                             acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bfrag[ks][nb][kb], acc[nb], 0, 0, 0);
                     }
         }
-        // ---- the next step's thin operand fragments (their registers are free now), and its correction
+        // ---- the next step's thin operand fragments (their registers are free now); LAZY: its tile and its
+        // correction first (d_lds was last read before this step's barrier)
         if (it + 1 < n_loc) {
+            if (LAZY) {
+                load_q(chunk_at(it + 1), 1);      // (before the tile: the wait counter is in issue order)
+                load_e(chunk_at(it + 1), e);
+                load_g(0, chunk_at(it + 1), g);
+                correction(0);
+                correction(1);
+            }
             load_b(chunk_at(it + 1));
-            if (LAZY) correction(chunk_at(it + 1));       // (d_lds was last read before this step's barrier)
         }
         if (ABUF == 1) __syncthreads();
     }
@@ -360,10 +407,225 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------------
+// The second product on the same tiles:  Q = M^T P~  (Algorithm 1; also Y = M^T Z of the refresh's iteration) for
+// layers stored with rows >= cols, at widths up to 64.  Reads S only (4 bytes per element).
+//
+// A workgroup owns 256 columns of S -- 256 rows of the result -- and walks down the rows 32 at a time; a load
+// instruction of a wavefront covers 1 KB of one row.  A thread holds 8 consecutive rows of 4 columns, so the tile goes to
+// LDS transposed with 16-byte writes ([column][32 rows], the 16-byte chunk index XOR-ed with bits of the column so
+// that neither the writes nor the MFMA reads collide on banks).  Wave v owns result rows 64 v .. 64 v + 63; all four
+// waves use the same fragments of the thin operand, which come straight from memory in MFMA order (PackRef::t).
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int CW = 256;         // columns of S per workgroup
+constexpr int CKR = 32;         // rows of S per step
+constexpr int CLD = CKR + 8;    // LDS row stride of the transposed tile (bf16 elements, 80 bytes)
+
+template <int NB, int PL> constexpr size_t colprod_lds_bytes() {
+    const size_t a = (size_t)PL * CW * CLD * sizeof(bf16_t);
+    const size_t o = (size_t)128 * (32 * NB + 1) * sizeof(float);
+    return a > o ? a : o;
+}
+
+// (three workgroups per compute unit where LDS and registers allow it: one tile per workgroup in flight is not enough
+// to cover the memory latency with two)
+template <int NB, int PL>
+__global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(const LayerDev* __restrict__ layers,
+                                                                const int* __restrict__ ids, int out_role,
+                                                                int epi_flags, int gate, int nt_s) {
+    constexpr int cp = 32 * NB;
+    constexpr int APL = CW * CLD;
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
+    const int epi = epi_flags & EPI_KIND_MASK;
+    const int n_cb = (L.colsP + CW - 1) / CW;
+    const int n_split = L.split_col_v2;
+    const int tile = blockIdx.x;
+    if (tile >= n_cb * n_split) return;
+    const int ob = tile % n_cb, sp = tile / n_cb;
+    const int col0 = ob * CW;
+    const int n_chunks = (L.rows + CKR - 1) / CKR;
+    const int cps = (n_chunks + n_split - 1) / n_split;
+    const int ch0 = sp * cps;
+    const int n_loc = col0 < L.cols ? max(min(n_chunks, ch0 + cps) - ch0, 0) : 0;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* a_pl = reinterpret_cast<bf16_t*>(smem);          // PL planes of [CW][CLD]
+    const int t = threadIdx.x;
+    const int lane = t & 63, wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int64_t ld = L.ld;
+    const int rowsP = L.rowsP;
+    const PSGD_GLOBAL float* S = as_global(L.S);
+    const unsigned lane_e = 16u * (unsigned)lane;
+    // this thread's pieces of a tile: piece u at row ch * 32 + 8 wv + u, columns col0 + 4 lane .. + 3
+    auto tile_full = [&](int ch) { return ch * CKR + CKR <= L.rows && col0 + CW <= L.cols; };
+    auto load_tile = [&](int ch, floatx4 (&x)[8]) {
+        const PSGD_GLOBAL float* sp0 = S + (int64_t)(ch * CKR + 8 * wv) * ld + col0;
+        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(sp0 + u * ld) + lane_e); };
+        if (tile_full(ch)) {
+            if (nt_s) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(at(u));
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = *at(u);
+            }
+        } else {
+            const int c = col0 + 4 * lane;
+            const bool k0 = c < L.cols, k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                x[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (k0 && ch * CKR + 8 * wv + u < L.rows) {
+                    const floatx4 v = *at(u);                       // (the padding up to ld may be read, not used)
+                    x[u] = floatx4{v.x, k1 ? v.y : 0.f, k2 ? v.z : 0.f, k3 ? v.w : 0.f};
+                }
+            }
+        }
+    };
+    const PackRef XK = L.pack[SIDE_L];
+    const unsigned lane_f = 16u * (unsigned)lane;
+    auto load_b = [&](int ch, bf16x8 (&bf)[2][NB][PL]) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int kg = min(ch * (CKR / 16) + ks, rowsP / 16 - 1);     // (past the end M is zero)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    bf[ks][nb][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
+                        reinterpret_cast<const PSGD_GLOBAL char*>(as_global(XK.t[k]) + ((int64_t)kg * NB + nb) * 512) + lane_f);
+        }
+    };
+    floatx16 acc[2][NB];
+#pragma unroll
+    for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[rb][nb][v] = 0.f;
+    floatx4 x[8];
+    bf16x8 bfrag[2][NB][PL];
+    if (n_loc > 0) {
+        load_tile(ch0, x);
+        load_b(ch0, bfrag);
+    }
+    const int wsw = (lane >> 2) & 3;                  // write side: bits 4, 5 of this thread's columns 4 lane + q
+    for (int it = 0; it < n_loc; ++it) {
+        // ---- tile -> planes -> LDS, transposed: column 4 lane + q gets this thread's 8 rows as one 16-byte write
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            bf16x8 o[PL];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                bf16_t pq[PL];
+                split_planes<PL>(x[u][q], pq);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][u] = pq[k];
+            }
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * lane + q) * CLD + 8 * (wv ^ wsw)) = o[k];
+        }
+        __syncthreads();
+        if (it + 1 < n_loc) load_tile(ch0 + it + 1, x);       // in flight during the MFMA phase
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb) {
+                const int cl = 64 * wv + 32 * rb + li;
+                bf16x8 av[PL];
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    av[k] = *reinterpret_cast<const bf16x8*>(a_pl + k * APL + cl * CLD + 8 * ((2 * ks + lg) ^ ((cl >> 4) & 3)));
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                        for (int ka = 0; ka < PL; ++ka) {
+                            const int kb = sum - ka;
+                            if (kb >= 0 && kb < PL && form_keep_term<PL>(ka, kb))
+                                acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bfrag[ks][nb][kb], acc[rb][nb], 0, 0, 0);
+                        }
+            }
+        if (it + 1 < n_loc) load_b(ch0 + it + 1, bfrag);
+        __syncthreads();
+    }
+    // ---- the 256 x cp result tile goes out in two halves of 128 rows through LDS (the operand buffer is free: the
+    // loop ends in a barrier); half h holds the rows of waves 2 h and 2 h + 1
+    float* otile = reinterpret_cast<float*>(smem);            // [128][cp + 1]
+    constexpr int tw = cp + 1;
+    const ThinRef T = L.thin[out_role];
+    const int w = T.width;
+#pragma unroll 1
+    for (int h = 0; h < 2; ++h) {
+        if (h) __syncthreads();
+        if ((wv >> 1) == h) {
+#pragma unroll
+            for (int rb = 0; rb < 2; ++rb)
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        otile[(64 * (wv & 1) + 32 * rb + 8 * (v >> 2) + 4 * lg + (v & 3)) * tw + 32 * nb + li] = acc[rb][nb][v];
+        }
+        __syncthreads();
+        const int r0 = col0 + 128 * h;                        // first result row of this half
+        if (r0 >= L.colsP) break;                             // (uniform)
+        if (n_split > 1) {
+            // one of n_split partial sums, [split][column][row]; finish_kernel adds them in split order
+            PSGD_GLOBAL float* dst = as_global(L.part[SIDE_W]) + (int64_t)sp * L.colsP * w + r0;
+            for (int i = t; i < 128 * w; i += kThreads) {
+                const int row = i & 127, c = i >> 7;
+                dst[(int64_t)c * L.colsP + row] = otile[row * tw + c];
+            }
+            continue;
+        }
+        for (int i = t; i < 128 * w; i += kThreads) {
+            const int row = i / w, c = i - row * w;
+            if (r0 + row < L.cols) as_global(T.ptr)[(int64_t)(r0 + row) * T.ld + c] = otile[row * tw + c];
+        }
+        // the partial Gram matrix or the operand copies of the result, per 128 rows as the other kernels expect them
+        if (epi == EPI_GRAM) gram_tile_f64(otile, tw, 128, w, L.gram + (int64_t)(r0 / 128) * ((w * (w + 1)) / 2));
+        else if (epi == EPI_PACK) write_packs(L.pack[SIDE_W], L.planes, otile, tw, cp, r0, 128, L.colsP);
+    }
+}
+
+template <int NB, int PL>
+static hipError_t launch_colprod_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, int out_role,
+                                    int epi, int gate, int nt_s, hipStream_t st) {
+    dim3 grid(max_tiles, n_ids), block(kThreads);
+    auto kfn = col_prod_kernel<NB, PL>;
+    const size_t lds = colprod_lds_bytes<NB, PL>();
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, gate, nt_s);
+    return hipGetLastError();
+}
+
+bool col_prod_supported(int nb) { return nb == 1 || nb == 2; }
+
+// max_tiles: max over the layers of ceil(padded cols / 256) * split_col_v2; nt_s: read S with the non-temporal hint
+hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                           int out_role, int epi, int gate, int nt_s, hipStream_t st) {
+    if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
+    if (nb == 1) return planes == 2 ? launch_colprod_nb<1, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st)
+                                    : launch_colprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st);
+    if (nb == 2) return planes == 2 ? launch_colprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st)
+                                    : launch_colprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st);
+    return hipErrorInvalidValue;
+}
+
 template <int NB, int PL>
 static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids, int n_ids,
-                                 int max_tiles, int out_role, int epi, int nt_m, hipStream_t st) {
+                                 int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
+                                 int xtiles, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
+    if (xtab) grid = dim3(8 * xtiles, 1);
 #define PSGD_FORM(GBF, ONEW, LAZY)                                                                             \
     do {                                                                                                       \
         auto kfn = form_row_kernel<NB, PL, GBF, ONEW, LAZY>;                                                   \
@@ -373,7 +635,7 @@ static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev*
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
             if (e != hipSuccess) return e;                                                                     \
         }                                                                                                      \
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, nt_m);                       \
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, nt_m, xtab, xstride);        \
     } while (0)
     if (lazy) {
         if (gbf) { if (onew) PSGD_FORM(true, true, true); else PSGD_FORM(true, false, true); }
@@ -391,22 +653,24 @@ static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev*
 bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy) {
     if (nb < 1 || nb > 2) return false;
     const bool f32_multi = !gbf && !onew;
-    if (nb == 1) return !(planes == 3 && lazy && f32_multi);
-    if (planes == 2) return !f32_multi;
+    if (nb == 1) return true;
+    if (planes == 2) return !(lazy && f32_multi);
     return !lazy && !f32_multi;
 }
 
 // nb = width / 32 of the thin operand (1 or 2); gbf: every layer of the launch has bf16 gradients (else every layer
 // fp32); onew: one worker; lazy: apply the owed residual on the way in; nt_m: store M with the non-temporal hint
 // (matrices too large to be found in a cache by the second pass).  max_tiles: max over the layers of
-// (padded rows / 32) * split_row_v2.
+// (padded rows / 32) * split_row_v2.  xtab (device, nullable): the XCD table described in the kernel, 16 rows of
+// xstride ints; xtiles: the largest tile total of an XCD.
 hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids,
-                           int n_ids, int max_tiles, int out_role, int epi, int nt_m, hipStream_t st) {
+                           int n_ids, int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
+                           int xtiles, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
-    if (nb == 1) return planes == 2 ? launch_form_nb<1, 2>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, st)
-                                    : launch_form_nb<1, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, st);
-    if (nb == 2) return planes == 2 ? launch_form_nb<2, 2>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, st)
-                                    : launch_form_nb<2, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, st);
+    if (nb == 1) return planes == 2 ? launch_form_nb<1, 2>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st)
+                                    : launch_form_nb<1, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st);
+    if (nb == 2) return planes == 2 ? launch_form_nb<2, 2>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st)
+                                    : launch_form_nb<2, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st);
     return hipErrorInvalidValue;
 }
 

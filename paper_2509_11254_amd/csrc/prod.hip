@@ -651,8 +651,9 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     const int epi = epi_flags & EPI_KIND_MASK;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
-    // form: 0 = a product that reads M, 1 = a forming pass of prod_kernel, 2 = the forming pass on 32 x 256 tiles
-    const int n_split = form == 2 ? L.split_row_v2
+    // form: 0 = a product that reads M, 1 = a forming pass of prod_kernel, 2 = the forming pass on 32 x 256 tiles,
+    // 3 = the column-mode product on 32 x 256 tiles
+    const int n_split = form == 2 ? L.split_row_v2 : form == 3 ? L.split_col_v2
                         : form ? (colmode ? L.split_col_f : L.split_row_f) : (colmode ? L.split_col : L.split_row);
     const int ob = blockIdx.x;
     if (n_split <= 1 || ob * BT >= out_len) return;

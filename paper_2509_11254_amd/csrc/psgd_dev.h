@@ -72,6 +72,12 @@ struct ThinRef {
 //          X[16 k16 + 8 lg .. + 7][32 nb + li].  One MFMA B fragment of a wavefront is 1 KB of consecutive memory,
 //          so a kernel can load it straight into registers, and a 64-row chunk of all columns is one run of 4 cp bytes.
 constexpr int kMaxPlanes = 3;
+// Fragment order of a row-major thin matrix X (len x cp) as the A or B operand of an outer product (reduction over
+// the cp columns): [len / 32][cp / 16][64 lanes][8], lane li + 32 lg of fragment (row block, k-step) holding
+// X[32 block + li][16 kstep + 8 lg .. + 7].  Offset of the 16-byte piece (row, 8-column group g8):
+__host__ __device__ inline int64_t frag_piece(int row, int g8, int cp) {
+    return ((int64_t)(row >> 5) * (cp >> 4) + (g8 >> 1)) * 64 + (row & 31) + 32 * (g8 & 1);
+}
 __host__ __device__ inline int64_t pack_t_offset(int k, int c, int cp) {
     return ((((int64_t)(k >> 4) * (cp >> 5) + (c >> 5)) * 64 + (c & 31) + 32 * ((k >> 3) & 1)) << 3) + (k & 7);
 }
@@ -95,7 +101,8 @@ struct LayerDev {
     int split_row_f;   // the same for the forming passes, which want about twice as many workgroups
     int split_col_f;
     int split_row_v2;  // k-splits of the row-mode forming pass on 32 x 256 tiles (form_row_kernel)
-    int pad_[3];
+    int split_col_v2;  // k-splits of the column-mode product on 32 x 256 tiles (col_prod_kernel)
+    int pad_[2];
     const void* const* G;   // n_workers device pointers
     float* S;               // E on entry, M between the sweeps, E_{t+1} on exit
     ThinRef thin[ROLE_COUNT];
@@ -103,6 +110,7 @@ struct LayerDev {
     PackRef pack[2];        // per side
     bf16_t* lz[2][kMaxPlanes];   // per side: row-major [lenP][cp] copies of the compress step's P~ and Q operands,
                                  // kept while the residual of that step is still owed (deferred residual)
+    bf16_t* lzf[2][kMaxPlanes];  // the same operands in MFMA fragment order (frag_offset), what form_row_kernel reads
     double* gram;           // [slots][w(w+1)/2] partial Gram matrices (packed upper triangles), one slot per
                             // row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right

@@ -94,11 +94,17 @@ __global__ __launch_bounds__(kThreads) void keep_kernel(const LayerDev* __restri
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int side = blockIdx.z;
     const int64_t n16 = (int64_t)side_lenP(L, side) * cp / 8;       // 16-byte words per plane
+    const int g8n = cp / 8;                                          // 16-byte pieces per row
     for (int k = 0; k < L.planes; ++k) {
         const PSGD_GLOBAL uintx4* src = reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.pack[side].n[k]));
         PSGD_GLOBAL uintx4* dst = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lz[side][k]));
-        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads)
-            dst[i] = src[i];
+        PSGD_GLOBAL uintx4* dstf = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lzf[side][k]));
+        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads) {
+            const uintx4 v = src[i];
+            dst[i] = v;
+            const int row = (int)(i / g8n), g8 = (int)(i - (int64_t)row * g8n);
+            dstf[frag_piece(row, g8, cp)] = v;
+        }
     }
 }
 
