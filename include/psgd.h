@@ -68,7 +68,8 @@ enum {
     PSGD_E_ALIGN = -3,       /* ld < cols, ld not a multiple of 8, pointer not 16-byte aligned */
     PSGD_E_HIP = -4,         /* a HIP runtime call failed (psgd_last_hip_error gives its code) */
     PSGD_E_NOMEM = -5,       /* host allocation failed                                      */
-    PSGD_E_CAPTURE = -6      /* the stream is capturing and the call would have to upload pointer tables */
+    PSGD_E_CAPTURE = -6,     /* the stream is capturing and the call would have to upload pointer tables */
+    PSGD_E_TOO_LARGE = -7    /* psgd_compress_static: the context needs more workspace than the built-in buffer has */
 };
 
 /* One matrix variable.  G^(i) and E of this layer all share rows, cols and ld. */
@@ -158,6 +159,22 @@ int psgd_workspace_reset(psgd_ctx *ctx);
  * P: m x r fp32, out.  Errors: INVALID_ARG (null table or entry), ALIGN (pointer alignment), HIP. */
 int psgd_compress(psgd_ctx *ctx, void *workspace, void *stream, const void *const *G,
                   float *const *E, float *const *Q, float *const *P);
+
+/* psgd_compress_static -- psgd_compress for callers that cannot allocate device memory (code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc): the same step with the same kernels, but the
+ * workspace is a buffer built into the library, a static device array of PSGD_STATIC_WORKSPACE_BYTES that every GPU
+ * the library runs on holds from the first such call on it until the process ends.  The call allocates nothing
+ * (no hipMalloc, hipHostMalloc or hipFree; tables travel as kernel arguments); G, E, Q, P are the caller's as in
+ * psgd_compress.  All contexts and all calls on one GPU share that one buffer: calls that overlap on one GPU race, and
+ * the buffer keeps what the last call left, so a context that finds another context's contents there uploads its
+ * tables again and starts from cleared per-layer state (as after psgd_workspace_reset).  Mixing it with the
+ * workspace-taking calls on the same context is allowed; the buffer then counts as one more workspace.
+ * Errors: as psgd_compress; TOO_LARGE if psgd_workspace_bytes(ctx) exceeds the buffer (nothing is enqueued);
+ * INVALID_ARG if a deferred residual of this context is owed in another workspace, or was owed in the buffer and
+ * another context has used the buffer since; HIP if the buffer's address cannot be obtained. */
+#define PSGD_STATIC_WORKSPACE_BYTES (64u * 1024u * 1024u)
+int psgd_compress_static(psgd_ctx *ctx, void *stream, const void *const *G, float *const *E, float *const *Q,
+                         float *const *P);
 
 /* psgd_compress_project / psgd_compress_finish -- psgd_compress in the two halves between which a data-parallel job
  * exchanges P (Algorithm 1, SSP-Comp: "P = mean of P^(i)" between the projection and the QR; Algorithm 2 keeps one

@@ -4,9 +4,11 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -81,6 +83,7 @@ struct Lists {
 }  // namespace
 
 struct psgd_ctx {
+    uint64_t serial = 0;     // unique per context (the built-in workspace remembers whose contents it holds)
     int n_layers = 0;
     int n_workers = 0;
     psgd_options opt{};
@@ -598,6 +601,10 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     if (!layers || n_layers < 1 || n_layers > 65535 || n_workers < 1 || n_workers > 4096) return PSGD_E_INVALID_ARG;
     psgd_ctx* c = new (std::nothrow) psgd_ctx();
     if (!c) return PSGD_E_NOMEM;
+    {
+        static std::atomic<uint64_t> next_serial{1};
+        c->serial = next_serial.fetch_add(1);
+    }
     c->n_layers = n_layers;
     c->n_workers = n_workers;
     if (opt) c->opt = *opt;
@@ -767,6 +774,16 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     }
     c->ws_bytes = o;
     c->algo_bytes = bytes;
+    // host tables at their final capacity, so that no compute call allocates host memory either
+    {
+        const size_t nl = (size_t)n_layers, ng = nl * (size_t)n_workers;
+        c->hG.reserve(ng);
+        for (auto& v : c->hGs) v.reserve(ng);
+        c->hE.reserve(nl); c->hQ.reserve(nl); c->hP.reserve(nl);
+        c->hOut.reserve(nl); c->hMom.reserve(nl); c->hM2.reserve(nl); c->hX.reserve(nl);
+        c->hIds.reserve(3 * nl + 1);
+        c->hLayers.reserve(nl + 1);
+    }
     *out = c;
     return PSGD_OK;
 }
@@ -845,6 +862,49 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     ctx->factors_ws = workspace;                   // the operand copies of P~_t and Q_t are in place
     return PSGD_OK;
+}
+
+// The built-in workspace of psgd_compress_static: one array per GPU (every device that loads this code object holds its
+// own copy at its own address).  In host code the array's name is only a handle for hipGetSymbolAddress; the device
+// address it returns, looked up once per device with that device current, is what is passed on.
+static __device__ __align__(256) unsigned char g_static_workspace[PSGD_STATIC_WORKSPACE_BYTES];
+namespace {
+constexpr int kMaxDevices = 64;
+struct StaticWorkspace { void* ptr = nullptr; uint64_t owner = 0; };
+StaticWorkspace g_static_ws[kMaxDevices];
+std::mutex g_static_mutex;
+}  // namespace
+
+int psgd_compress_static(psgd_ctx* ctx, void* stream, const void* const* G, float* const* E, float* const* Q,
+                         float* const* P) {
+    if (!ctx || !G || !E || !Q || !P) return PSGD_E_INVALID_ARG;
+    if (ctx->ws_bytes > (size_t)PSGD_STATIC_WORKSPACE_BYTES) return PSGD_E_TOO_LARGE;
+    int dev = -1;
+    PSGD_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return PSGD_E_INVALID_ARG;
+    void* ws = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        StaticWorkspace& W = g_static_ws[dev];
+        if (!W.ptr) {
+            void* p = nullptr;
+            PSGD_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_workspace)));
+            if (!p) return fail_hip(ctx, hipErrorInvalidSymbol);
+            W.ptr = p;
+        }
+        ws = W.ptr;
+        if (W.owner != ctx->serial) {
+            // another context's tables, counters and operand copies are in the buffer (or nothing yet)
+            if (ctx->pending && ctx->bound_ws == ws) return PSGD_E_INVALID_ARG;      // its kept operands are gone
+            if (ctx->bound_ws == ws) { ctx->tables_valid = false; ctx->iters_gen++; }
+            if (ctx->outs_ws == ws) ctx->outs_ws = nullptr;
+            if (ctx->msgd_ws == ws) ctx->msgd_ws = nullptr;
+            if (ctx->m2_ws == ws) ctx->m2_ws = nullptr;
+            if (ctx->factors_ws == ws) ctx->factors_ws = nullptr;
+            W.owner = ctx->serial;
+        }
+    }
+    return psgd_compress(ctx, ws, stream, G, E, Q, P);
 }
 
 // The two halves of psgd_compress between which a data-parallel job averages P over its workers (and after which
@@ -1164,6 +1224,7 @@ const char* psgd_strerror(int code) {
         case PSGD_E_HIP: return "HIP runtime error";
         case PSGD_E_NOMEM: return "out of host memory";
         case PSGD_E_CAPTURE: return "stream capture: pointer tables not on the device yet (make the same call eagerly once first)";
+        case PSGD_E_TOO_LARGE: return "the context needs more workspace than the library's built-in buffer holds";
         default: return "unknown error";
     }
 }

@@ -16,9 +16,11 @@ LIB_PATH = os.path.join(HERE, "libpsgd.so")
 PSGD_F32, PSGD_BF16 = 0, 1
 PSGD_OK = 0
 PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, PSGD_E_NOMEM, PSGD_E_CAPTURE = -1, -2, -3, -4, -5, -6
+PSGD_E_TOO_LARGE = -7
+STATIC_WORKSPACE_BYTES = 64 * 1024 * 1024
 
 EXPORTS = [
-    "psgd_init", "psgd_workspace_bytes", "psgd_workspace_reset", "psgd_compress", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
+    "psgd_init", "psgd_workspace_bytes", "psgd_workspace_reset", "psgd_compress", "psgd_compress_static", "psgd_compress_refresh", "psgd_flush_residual", "psgd_refresh",
     "psgd_decompress", "psgd_decompress_msgd", "psgd_decompress_adam", "psgd_compress_project", "psgd_compress_finish", "psgd_status", "psgd_algorithmic_bytes", "psgd_kernel_bytes", "psgd_copy_bytes",
     "psgd_last_hip_error",
     "psgd_strerror", "psgd_destroy", "psgd_profile_enable", "psgd_profile_select", "psgd_profile_read",
@@ -77,6 +79,8 @@ def load_library() -> C.CDLL:
         fn = getattr(lib, name)
         fn.argtypes = [vp, vp, vp, pp, pp, pp, pp]
         fn.restype = C.c_int
+    lib.psgd_compress_static.argtypes = [vp, vp, pp, pp, pp, pp]
+    lib.psgd_compress_static.restype = C.c_int
     lib.psgd_compress_finish.argtypes = [vp, vp, vp, pp, pp, pp]
     lib.psgd_compress_finish.restype = C.c_int
     lib.psgd_flush_residual.argtypes = [vp, vp, vp, pp]
@@ -199,6 +203,11 @@ class Compressor:
         """psgd_compress: G[l][i] gradients, E[l] error buffers (in place), Q[l] in/out, P[l] out."""
         tg, te, tq, tp = self._tables(G, E, Q, P)
         _check(self.lib, self.ctx, self.lib.psgd_compress(self.ctx, self._ws_ptr, _stream_handle(stream), tg, te, tq, tp))
+
+    def compress_static(self, G, E, Q, P, stream=None) -> None:
+        """psgd_compress_static: psgd_compress in the library's built-in workspace (allocates nothing)."""
+        tg, te, tq, tp = self._tables(G, E, Q, P)
+        _check(self.lib, self.ctx, self.lib.psgd_compress_static(self.ctx, _stream_handle(stream), tg, te, tq, tp))
 
     def compress_refresh(self, G, E, Q, P, stream=None) -> None:
         tg, te, tq, tp = self._tables(G, E, Q, P)
