@@ -6,6 +6,12 @@ psgd_compress (or psgd_compress_refresh when step % tau == 0, Algorithm 2) follo
 psgd_decompress.  Inputs are resident in HBM before the timed region; three gradient sets are
 rotated so that a step never finds its gradients in the 256 MB memory-side cache.
 
+The headline workload is the largest single-GPU configuration: the 7B-shaped sweep (224 matrices,
+bf16 gradients, r = 64, one worker = one GPU's share of a data-parallel job), run with the deferred
+residual (psgd_options.lazy_residual; `--plain` runs the immediate form, which the line reports
+beside it either way).  The smaller configurations are run after it and reported as sub-objects
+(`--only` skips them).
+
 Prints ONE JSON line (see the fields below).  `value` is gigabytes of gradient compressed per
 second: N * sum_l rows_l*cols_l * sizeof(G) * steps / time.
 """
@@ -26,16 +32,17 @@ HBM_PEAK_GBPS = 8000.0
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5a"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c4", choices=["c1", "c2", "c3", "c4", "c5a", "c5a_bf16"])
+    ap.add_argument("--only", action="store_true", help="the named workload only, no sub-objects for the others")
+    ap.add_argument("--plain", action="store_true",
+                    help="time the immediate residual (E_{t+1} written by a pass of its own) instead of the deferred one")
     ap.add_argument("--sets", type=int, default=3, help="rotating gradient sets")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decompress", action="store_true")
     ap.add_argument("--rank", type=int, default=0, help="override the compression rank (sweep r = 8..64)")
-    ap.add_argument("--lazy", action="store_true",
-                    help="deferred residual (psgd_options.lazy_residual): the residual of a step is applied by the "
-                         "next step's forming pass instead of a pass of its own")
+    ap.add_argument("--lazy", action="store_true", help="(default now; kept for old command lines)")
     ap.add_argument("--no-qr", action="store_true",
                     help="signal factors = scaled Gaussian columns (orthonormal up to O(sqrt(k/rows))) instead of a "
                          "QR: keeps rocsolver out of counter-collection runs")
@@ -134,60 +141,290 @@ def run_ceilings():
 def make_workload(name, rank):
     from paper_2509_11254_amd import synth
     wl = {"c1": synth.config1, "c2": synth.config2, "c3": synth.config3, "c4": synth.config4,
-          "c5a": synth.config5a}[name]()
+          "c5a": synth.config5a, "c5a_bf16": lambda: synth.config5a(synth.BF16)}[name]()
     if rank > 0:
         wl.r = rank
     return wl
 
 
-def cpu_baseline(wl, sets, E, Q, torch):
-    """The fp64 NumPy oracle, as it stands, on a bounded sample of the same workload."""
+def host_info():
+    model = None
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"nproc": os.cpu_count(), "cpu_model": model}
+
+
+def cpu_baseline(wl, sets, E, Q, torch, seconds=12.0):
+    """The fp64 NumPy oracle, as it stands, on a bounded sample of the same workload: SSP-Comp steps on the first layer
+    of each distinct shape, round after round with the oracle's own E and Q carried along, until `seconds` are used."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import psgd_oracle as orc
-    # sample: the first layer of each distinct shape, one SSP step with all workers (largest first)
     seen, sample = set(), []
     for l, spec in enumerate(wl.layers):
         if (spec.rows, spec.cols) not in seen:
             seen.add((spec.rows, spec.cols))
             sample.append(l)
-    budget_elems = 160e6     # about 10-30 s of oracle work
-    chosen, used = [], 0.0
+    state = {}
     for l in sample:
-        ne = wl.layers[l].rows * wl.layers[l].cols * wl.n_workers
-        if chosen and used + ne > budget_elems:
-            continue
-        chosen.append(l)
-        used += ne
-    t_total, bytes_total = 0.0, 0.0
-    for l in chosen:
         spec = wl.layers[l]
         g = [x.float().cpu().numpy().astype(np.float64) for x in sets[0][l]]
         e = [E[l].cpu().numpy().astype(np.float64)] * wl.n_workers
-        q = Q[l].cpu().numpy().astype(np.float64)
         if spec.transposed:
             g = [x.T for x in g]
             e = [x.T for x in e]
-        t0 = time.perf_counter()
-        orc.compress_step(1, None, wl.r, q, g, e)
-        t_total += time.perf_counter() - t0
-        bytes_total += spec.rows * spec.cols * wl.n_workers * (2 if wl.grad_dtype == "bf16" else 4)
+        state[l] = (g, e, Q[l].cpu().numpy().astype(np.float64))
+    t_total, bytes_total, rounds = 0.0, 0.0, 0
+    while t_total < seconds:
+        for l in sample:
+            spec = wl.layers[l]
+            g, e, q = state[l]
+            t0 = time.perf_counter()
+            out = orc.compress_step(1, None, wl.r, q, g, e)
+            t_total += time.perf_counter() - t0
+            state[l] = (g, out.e_next, out.comp.q)
+            bytes_total += spec.rows * spec.cols * wl.n_workers * (2 if wl.grad_dtype == "bf16" else 4)
+        rounds += 1
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": bytes_total / t_total / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
-            "sample": "one SSP-Comp step (all %d workers, fp64 NumPy) on layers %s of %s: %.1f s" % (
-                wl.n_workers, [wl.layers[l].name or l for l in chosen], wl.name, t_total)}
+    out = {"value": bytes_total / t_total / 1e9, "unit": "GB/s", "cores": int(threads), "kind": "oracle",
+           "sample": "%d SSP-Comp steps (all %d workers, fp64 NumPy) on each of the layers %s of %s, one per distinct "
+                     "shape: %.1f s; the rate of the whole batch is this one extrapolated (same shapes)" % (
+                         rounds, wl.n_workers, [wl.layers[l].name or l for l in sample], wl.name, t_total)}
+    out.update(host_info())
+    return out
 
 
 def read_traffic(tag):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary, if any."""
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this workload, if there
+    is one (the counters are collected in a run of their own, not in this one)."""
     path = os.path.join(ROOT, "profiles", "sweep1_%s_pmc.txt" % tag)
     try:
         for line in open(path):
             if line.startswith("traffic_bytes_per_launch:"):
-                return float(line.split(":", 1)[1])
+                return float(line.split(":", 1)[1]), "profiles/sweep1_%s_pmc.txt" % tag
     except OSError:
         pass
-    return None
+    return None, None
+
+
+def run_workload(name, args, primary):
+    """Times one workload; returns (the fields of its bench line, objects the CPU baseline needs)."""
+    import torch
+    from paper_2509_11254_amd import psgd, synth
+
+    wl = make_workload(name, args.rank if primary else 0)
+    gd = psgd.PSGD_BF16 if wl.grad_dtype == synth.BF16 else psgd.PSGD_F32
+    sg = 2 if wl.grad_dtype == synth.BF16 else 4
+    layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
+    # the deferred residual pays where a step is bound by the bytes of the streaming passes (the batched bf16 sets);
+    # on a single small matrix the immediate form is the faster one
+    lazy = (not args.plain) and name in ("c3", "c4")
+    steps = args.steps if primary else max(5, min(args.steps, 20))
+    warmup = args.warmup if primary else max(2, min(args.warmup, 5))
+    # (q_resident: this loop never writes the Q buffers between the library's calls)
+    comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=lazy, q_resident=True)
+    comp_other = psgd.Compressor(layers, wl.n_workers, lazy_residual=not lazy, q_resident=True)
+    planes = 3 if wl.grad_dtype == synth.F32 else 2
+    sets, E, Q, P, OUT = synth.device_gradients(wl, args.sets, torch, args.no_qr)
+    elems = sum(s.rows * s.cols for s in wl.layers)
+    grad_bytes = elems * wl.n_workers * sg
+    tau = wl.tau
+
+    def step(c, t):
+        G = sets[t % args.sets]
+        if t % tau == 0:
+            c.compress_refresh(G, E, Q, P)
+        else:
+            c.compress(G, E, Q, P)
+        if not args.no_decompress:
+            # Delta_hat of the factors this step's compress call produced: the library reads its own operand copies
+            # of them (P = Q = NULL in the ABI) instead of packing the P and Q buffers again
+            c.decompress(None, None, OUT)
+
+    if args.calibrate_copy and primary:
+        a = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            psgd.copy_bytes(b, a, a.numel())
+        torch.cuda.synchronize()
+        del a, b
+    t = 0
+    for _ in range(warmup):
+        step(comp, t)
+        t += 1
+    torch.cuda.synchronize()
+    # only the dominant kernel (pass 1) is timed inside the measured region, and only on every fourth step: a timed
+    # launch costs two event records, about 6 microseconds of idle GPU each (3 % of a config-2 step); the other
+    # kernels are timed in the breakdown loop below
+    comp.profile_enable(steps + 64)
+    n_refresh = sum(1 for k in range(t, t + steps) if k % tau == 0)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(steps):
+        comp.profile_select(["sweep1"] if k % 4 == 0 else [])
+        step(comp, t)
+        t += 1
+    if lazy:
+        comp.flush_residual(E)          # E_{t+1} of the last step: the deferred form owes it until here
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = comp.profile_read()
+    comp.profile_enable(0)
+
+    # ---- breakdown outside the timed region
+    def timed(fn, n):
+        torch.cuda.synchronize()
+        a = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - a) / n * 1e3
+
+    n_b = max(3, min(20, steps))
+
+    def ssp_loop(c, is_lazy):
+        def body(_):
+            for i in range(n_b):
+                c.compress(sets[i % args.sets], E, Q, P)
+            if is_lazy:
+                c.flush_residual(E)
+        return body
+    def kernel_times(c, is_lazy):
+        c.profile_select(list(psgd.PROF_TAGS))
+        c.profile_enable(4 * n_b + 8)
+        for i in range(n_b):
+            c.compress(sets[i % args.sets], E, Q, P)
+        if is_lazy:
+            c.flush_residual(E)
+        torch.cuda.synchronize()
+        d = c.profile_read()
+        c.profile_enable(0)
+        return d
+    # (each context in one stretch: with q_resident the Q buffers must not be written by anyone else in between)
+    ssp_ms = timed(ssp_loop(comp, lazy), 1) / n_b
+    per_kernel = {"lazy" if lazy else "plain": kernel_times(comp, lazy)}
+    for i in range(2):
+        comp_other.compress(sets[i % args.sets], E, Q, P)
+    if not lazy:
+        comp_other.flush_residual(E)
+    ssp_other_ms = timed(ssp_loop(comp_other, not lazy), 1) / n_b
+    per_kernel["plain" if lazy else "lazy"] = kernel_times(comp_other, not lazy)
+    ssp_lazy_ms, ssp_plain_ms = (ssp_ms, ssp_other_ms) if lazy else (ssp_other_ms, ssp_ms)
+    comp_plain = comp_other if lazy else comp
+    comp_plain.workspace_reset()
+    extra = {}
+    if primary:
+        # the same step as the two halves a data-parallel job runs per worker (P averaged between them)
+        def halves(i):
+            comp_plain.compress_project(sets[i % args.sets], E, Q, P)
+            comp_plain.compress_finish(E, Q, P)
+        halves(0)
+        extra["ssp_step_two_halves_ms"] = timed(halves, n_b)
+        # the same step recorded into a HIP graph once and replayed (kernel launches only)
+        comp_plain.compress(sets[0], E, Q, P)
+        torch.cuda.synchronize()
+        gr = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(gr):
+            comp_plain.compress(sets[0], E, Q, P)
+        gr.replay()
+        extra["ssp_step_graph_replay_ms"] = timed(lambda i: gr.replay(), n_b)
+        del gr
+    # SVD-Comp steps, one call per synchronised interval as in a schedule with tau > 1 (the library looks at the
+    # iteration bound it fetched behind the previous refresh only if that copy has arrived)
+    n_r = max(2, min(4, n_b))
+    comp_plain.compress_refresh(sets[0], E, Q, P)      # (a layer's first refresh on a workspace runs the whole budget)
+    it_next = [comp_plain.status(l).refresh_iters_next for l in range(len(wl.layers))]
+    refresh_ms = sum(timed(lambda i: comp_plain.compress_refresh(sets[i % args.sets], E, Q, P), 1) for _ in range(n_r)) / n_r
+    # cheaper refresh (Remark 2): one subspace iteration from a random start = randomized range finder
+    comp_rf = psgd.Compressor(layers, wl.n_workers, refresh_iters=1, refresh_warm_start=False, q_resident=True)
+    comp_rf.compress_refresh(sets[0], E, Q, P)
+    rangefinder_ms = sum(timed(lambda i: comp_rf.compress_refresh(sets[i % args.sets], E, Q, P), 1) for _ in range(n_r)) / n_r
+    del comp_rf
+    # refresh arithmetic: block width b, k iterations of two products of 2 m n b flops each (+ the forming product)
+    b_w = min(wl.r + max(8, wl.r // 4) + 7 & ~7, min(s.n for s in wl.layers))
+    # iterations per layer as the device decides them: its own count if within the budget of 16, else 8
+    k_layers = [(k if 0 < k <= 16 else (16 if k <= 0 else 8)) for k in it_next]
+    k_run = sum(k_layers) / len(k_layers)
+    refresh_flops = sum(4.0 * s.rows * s.cols * b_w * k for s, k in zip(wl.layers, k_layers))
+    cp_w = (b_w + 31) // 32 * 32
+    plane_products = 3 if planes == 2 else 6
+    dec_ms = timed(lambda i: comp_plain.decompress(P, Q, OUT), n_b)
+    comp_plain.compress(sets[0], E, Q, P)
+    dec_last_ms = timed(lambda i: comp_plain.decompress(None, None, OUT), n_b)
+    if primary:
+        # decompress fused with the momentum-SGD update (Eq. (7c)): reads and writes m and X, 16 bytes per element
+        MOM = [torch.zeros_like(e) for e in E]
+        XW = [torch.randn_like(e) for e in E]
+        msgd_ms = timed(lambda i: comp_plain.decompress_msgd(P, Q, MOM, XW, 0.9, 1e-3), n_b)
+        extra.update(decompress_msgd_ms=msgd_ms, decompress_msgd_GBps=16.0 * elems / (msgd_ms * 1e-3) / 1e9,
+                     decompress_msgd_frac_of_hbm_peak=16.0 * elems / (msgd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS)
+        # ... and with Adam (second moment as well: 24 bytes per element); the step counter advances as in a run
+        M2 = [torch.zeros_like(e) for e in E]
+        adam_ms = timed(lambda i: comp_plain.decompress_adam(P, Q, MOM, M2, XW, i + 1, 1e-3), n_b)
+        extra.update(decompress_adam_ms=adam_ms, decompress_adam_GBps=24.0 * elems / (adam_ms * 1e-3) / 1e9,
+                     decompress_adam_frac_of_hbm_peak=24.0 * elems / (adam_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS)
+        del MOM, M2, XW
+
+    # ---- roofline of the dominant kernel: the first streaming pass (reads N gradients + E, writes M; with the
+    # deferred residual also the kept factors of the step before).  Event pairs recorded inside the timed region;
+    # the SSP-only loop is the fallback when the timed region held no SSP step.
+    mode = "lazy" if lazy else "plain"
+    s1_ms, s1_n = prof["sweep1"] if prof["sweep1"][1] > 0 else per_kernel[mode]["sweep1"]
+    per_launch_ms = s1_ms / max(1, s1_n)
+    s1_bytes = comp.kernel_bytes("sweep1")
+    achieved = s1_bytes / (per_launch_ms * 1e-3) / 1e9 if per_launch_ms > 0 else 0.0
+    traffic, traffic_src = read_traffic(name)
+    kernels = {}
+    for tag, d in per_kernel.items():
+        for kname, (ms, n) in d.items():
+            if n > 0:
+                kernels["%s_%s_ms" % (kname, tag)] = ms / n
+    algo = comp.algorithmic_bytes
+    out = {
+        "metric": "compress GB/s of gradient",
+        "value": grad_bytes * steps / elapsed / 1e9,
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": warmup,
+        "ms_per_step": elapsed / steps * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        # elementwise arithmetic (error feedback, residual) in fp32; the three m*n*r contractions on the bf16 matrix
+        # cores with operands split into `planes` bf16 planes and fp32 accumulation; r x r pieces in fp64
+        "dtype": "f32" if planes == 3 else "bf16x2",
+        "data": "synthetic",
+        "config": dict(wl.describe(), refresh_steps_in_timed_region=n_refresh, gradient_sets=args.sets,
+                       decompress_in_step=not args.no_decompress, deferred_residual=bool(lazy),
+                       mfma_operand_planes=planes, error_buffer_dtype="f32",
+                       factors_from_workspace=True),    # q_resident = 1, decompress with P = Q = NULL
+        "roofline": {"bound": "hbm",
+                     "kernel": "form_row_kernel / prod_kernel FORM (M = mean G + E formed and stored, P = M Q%s)" % (
+                         "; the owed residual of the step before applied on the way in" if lazy else ""),
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_src,
+                     "bytes_per_launch": s1_bytes, "ms_per_launch": per_launch_ms},
+        "breakdown": dict(kernels, ssp_step_ms=ssp_ms, ssp_step_deferred_residual_ms=ssp_lazy_ms,
+                          ssp_step_immediate_residual_ms=ssp_plain_ms,
+                          ssp_step_algorithmic_GBps=algo / (ssp_ms * 1e-3) / 1e9,
+                          ssp_step_frac_of_hbm_peak=algo / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                          refresh_step_ms=refresh_ms, refresh_ms_per_layer=refresh_ms / len(wl.layers),
+                          refresh_iterations_mean=k_run, refresh_iterations_max=max(k_layers), refresh_block_width=b_w,
+                          refresh_algorithmic_TFLOPs=refresh_flops / (refresh_ms * 1e-3) / 1e12,
+                          refresh_plane_product_TFLOPs=refresh_flops * plane_products * cp_w / b_w / (refresh_ms * 1e-3) / 1e12,
+                          refresh_plane_product_frac_of_bf16_mfma_peak=refresh_flops * plane_products * cp_w / b_w / (refresh_ms * 1e-3) / 1e12 / 2500.0,
+                          rangefinder_refresh_step_ms=rangefinder_ms,
+                          rangefinder_refresh_ms_per_layer=rangefinder_ms / len(wl.layers),
+                          decompress_ms=dec_ms, decompress_of_last_factors_ms=dec_last_ms,
+                          decompress_GBps=4.0 * elems / (dec_last_ms * 1e-3) / 1e9, **extra),
+    }
+    return out, (wl, sets, E, Q)
 
 
 def main():
@@ -199,178 +436,24 @@ def main():
     if args.ceilings:
         run_ceilings()
         return
+    import gc
     import torch
-    from paper_2509_11254_amd import psgd, synth
-
     torch.cuda.set_device(0)
-    wl = make_workload(args.workload, args.rank)
-    gd = psgd.PSGD_BF16 if wl.grad_dtype == synth.BF16 else psgd.PSGD_F32
-    sg = 2 if wl.grad_dtype == synth.BF16 else 4
-    layers = [(s.rows, s.cols, wl.r, gd) for s in wl.layers]
-    # (q_resident: this loop never writes the Q buffers between the library's calls)
-    comp = psgd.Compressor(layers, wl.n_workers, lazy_residual=args.lazy, q_resident=True)
-    sets, E, Q, P, OUT = synth.device_gradients(wl, args.sets, torch, args.no_qr)
-    elems = sum(s.rows * s.cols for s in wl.layers)
-    grad_bytes = elems * wl.n_workers * sg
-    tau = wl.tau
-
-    def step(t):
-        G = sets[t % args.sets]
-        if t % tau == 0:
-            comp.compress_refresh(G, E, Q, P)
-        else:
-            comp.compress(G, E, Q, P)
-        if not args.no_decompress:
-            # Delta_hat of the factors this step's compress call produced: the library reads its own operand copies
-            # of them (P = Q = NULL in the ABI) instead of packing the P and Q buffers again
-            comp.decompress(None, None, OUT)
-
-    if args.calibrate_copy:
-        a = torch.empty(256 * 1024 * 1024, dtype=torch.uint8, device="cuda")
-        b = torch.empty_like(a)
-        for _ in range(3):
-            psgd.copy_bytes(b, a, a.numel())
-        torch.cuda.synchronize()
-        del a, b
-    t = 0
-    for _ in range(args.warmup):
-        step(t)
-        t += 1
-    torch.cuda.synchronize()
-    # only the dominant kernel (pass 1) is timed inside the measured region, and only on every fourth step: a timed
-    # launch costs two event records, about 6 microseconds of idle GPU each (3 % of a config-2 step); the other
-    # kernels are timed in the breakdown loop below
-    comp.profile_enable(args.steps + 64)
-    n_refresh = sum(1 for k in range(t, t + args.steps) if k % tau == 0)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        comp.profile_select(["sweep1"] if k % 4 == 0 else [])
-        step(t)
-        t += 1
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    prof = comp.profile_read()
-    comp.profile_enable(0)
-
-    # ---- breakdown outside the timed region: SSP-only steps, refresh-only steps, decompress
-    def timed(fn, n):
-        torch.cuda.synchronize()
-        a = time.perf_counter()
-        for i in range(n):
-            fn(i)
-        torch.cuda.synchronize()
-        return (time.perf_counter() - a) / n * 1e3
-
-    n_b = max(3, min(20, args.steps))
-    ssp_ms = timed(lambda i: comp.compress(sets[i % args.sets], E, Q, P), n_b)
-    # the same step as the two halves a data-parallel job runs per worker (P averaged between them): what the split
-    # costs on one GPU (the orthonormaliser finds P in memory, not in the product's epilogue)
-    halves_ms = None
-    if not args.lazy:
-        def halves(i):
-            comp.compress_project(sets[i % args.sets], E, Q, P)
-            comp.compress_finish(E, Q, P)
-        halves(0)
-        halves_ms = timed(halves, n_b)
-    # the same step recorded into a HIP graph once and replayed (kernel launches only; see psgd.h on capture)
-    graph_ms = None
-    if not args.lazy:
-        comp.compress(sets[0], E, Q, P)
-        torch.cuda.synchronize()
-        gr = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(gr):
-            comp.compress(sets[0], E, Q, P)
-        gr.replay()
-        graph_ms = timed(lambda i: gr.replay(), n_b)
-        del gr
-    comp.profile_select(list(psgd.PROF_TAGS))
-    comp.profile_enable(4 * n_b + 8)
-    for i in range(n_b):
-        comp.compress(sets[i % args.sets], E, Q, P)
-    torch.cuda.synchronize()
-    prof_ssp = comp.profile_read()
-    comp.profile_enable(0)
-    # (one call per synchronised interval, as in a schedule with tau > 1: the library looks at the iteration bound it
-    # fetched after the previous refresh only if that copy has arrived)
-    n_r = max(2, min(5, n_b))
-    refresh_ms = sum(timed(lambda i: comp.compress_refresh(sets[i % args.sets], E, Q, P), 1) for _ in range(n_r)) / n_r
-    dec_ms = timed(lambda i: comp.decompress(P, Q, OUT), n_b)
-    comp.compress(sets[0], E, Q, P)
-
-    def dec_last(i):
-        comp.decompress(None, None, OUT)
-    dec_last_ms = timed(dec_last, n_b)
-    # decompress fused with the momentum-SGD update (Eq. (7c)): reads and writes m and X, 16 bytes per element
-    MOM = [torch.zeros_like(e) for e in E]
-    XW = [torch.randn_like(e) for e in E]
-    msgd_ms = timed(lambda i: comp.decompress_msgd(P, Q, MOM, XW, 0.9, 1e-3), n_b)
-    msgd_gbps = (16.0 * elems) / (msgd_ms * 1e-3) / 1e9
-    # ... and with Adam (second moment as well: 24 bytes per element); the step counter advances as in a run
-    M2 = [torch.zeros_like(e) for e in E]
-    adam_ms = timed(lambda i: comp.decompress_adam(P, Q, MOM, M2, XW, i + 1, 1e-3), n_b)
-    adam_gbps = (24.0 * elems) / (adam_ms * 1e-3) / 1e9
-    del MOM, M2, XW
-    # the same SSP steps with the deferred residual (psgd_options.lazy_residual): the residual of a step is applied by
-    # the next step's forming pass; the flush that settles the last one is inside the timed region
-    lazy_ms = None
-    if not args.lazy:
-        comp_l = psgd.Compressor(layers, wl.n_workers, lazy_residual=True, q_resident=True)
-        for i in range(2):
-            comp_l.compress(sets[i % args.sets], E, Q, P)
-
-        def lazy_steps(_):
-            for i in range(n_b):
-                comp_l.compress(sets[i % args.sets], E, Q, P)
-            comp_l.flush_residual(E)
-        lazy_ms = timed(lazy_steps, 1) / n_b
-        del comp_l
-
-    # ---- roofline of the dominant kernel: the first streaming pass (reads N gradients + E, writes M)
-    # (event pairs recorded inside the timed region; the SSP-only loop is the fallback when the timed
-    # region held no SSP step)
-    s1_ms, s1_n = prof["sweep1"] if prof["sweep1"][1] > 0 else prof_ssp["sweep1"]
-    per_launch_ms = s1_ms / max(1, s1_n)
-    s1_bytes = comp.kernel_bytes("sweep1")
-    achieved = s1_bytes / (per_launch_ms * 1e-3) / 1e9 if per_launch_ms > 0 else 0.0
-    traffic = read_traffic(args.workload)
-    kernels = {"sweep1_ms": per_launch_ms}
-    for tag, (ms, n) in prof_ssp.items():
-        if tag != "sweep1":
-            kernels[tag + "_ms"] = ms / max(1, n)
-
-    out = {
-        "metric": "compress GB/s of gradient",
-        "value": grad_bytes * args.steps / elapsed / 1e9,
-        "unit": "GB/s",
-        "n_gpus": 1,
-        "steps": args.steps,
-        "warmup": args.warmup,
-        "ms_per_step": elapsed / args.steps * 1e3,
-        "higher_is_better": True,
-        "scaling": "weak",
-        "vs_baseline": None,
-        "dtype": "f32",
-        "data": "synthetic",
-        "config": dict(wl.describe(), refresh_steps_in_timed_region=n_refresh, gradient_sets=args.sets,
-                       decompress_in_step=not args.no_decompress, deferred_residual=bool(args.lazy),
-                       factors_from_workspace=True),    # q_resident = 1, decompress with P = Q = NULL
-        "roofline": {"bound": "hbm", "kernel": "prod_kernel (M = mean G + E formed, stored, P = M Q)",
-                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "bytes_per_launch": s1_bytes, "ms_per_launch": per_launch_ms},
-        "breakdown": dict(kernels, ssp_step_ms=ssp_ms, refresh_step_ms=refresh_ms,
-                          refresh_ms_per_layer=refresh_ms / len(wl.layers), decompress_ms=dec_ms, decompress_of_last_factors_ms=dec_last_ms,
-                          decompress_msgd_ms=msgd_ms, decompress_msgd_GBps=msgd_gbps,
-                          decompress_msgd_frac_of_hbm_peak=msgd_gbps / HBM_PEAK_GBPS,
-                          decompress_adam_ms=adam_ms, decompress_adam_GBps=adam_gbps,
-                          decompress_adam_frac_of_hbm_peak=adam_gbps / HBM_PEAK_GBPS,
-                          ssp_step_deferred_residual_ms=lazy_ms, ssp_step_two_halves_ms=halves_ms, ssp_step_graph_replay_ms=graph_ms,
-                          ssp_step_algorithmic_GBps=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9,
-                          ssp_step_frac_of_hbm_peak=comp.algorithmic_bytes / (ssp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS),
-    }
+    out, (wl, sets, E, Q) = run_workload(args.workload, args, True)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, sets, E, Q, torch)
+    del wl, sets, E, Q
+    if not args.only:
+        others = {}
+        for name in ("c2", "c3", "c5a", "c5a_bf16"):
+            if name == args.workload:
+                continue
+            gc.collect()
+            torch.cuda.empty_cache()
+            sub, keep = run_workload(name, args, False)
+            del keep
+            others[name] = {k: sub[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "config", "roofline", "breakdown")}
+        out["other_workloads"] = others
     print(json.dumps(out))
 
 
