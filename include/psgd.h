@@ -82,8 +82,9 @@ typedef struct {
 } psgd_layer_desc;
 
 typedef struct {
-    int32_t refresh_iters;      /* maximum number of subspace iterations of the SVD refresh; 0 = default
-                                   (16).  A layer's first refresh runs all of them.  Later ones run the
+    int32_t refresh_iters;      /* maximum number of subspace iterations of the SVD refresh (at most 255); 0 = default
+                                   (16).  A layer's first two refreshes on a workspace run all of them (the second
+                                   is the first to meet the state error feedback builds up).  Later ones run the
                                    number that the convergence factor rho = (theta_b/theta_r)^2 seen at its
                                    last refresh needs for 1e-5, plus one, if that is within the maximum
                                    (rho <= 0.46 for 16); if it is not -- no gap after sigma_r to converge

@@ -11,7 +11,11 @@ What is written out here and what is a library step:
   * the economic QR (Section 2, "QR decomposition") is written out as classical Gram-Schmidt
     applied twice per column, which yields the Q-factor whose R has a positive diagonal;
   * the SVD of SVD-Comp (Definition 3, Algorithm 1) is `numpy.linalg.svd`, i.e. the plain
-    definition "first r left singular vectors", not an iteration towards it.
+    definition "first r left singular vectors", not an iteration towards it (`svd_comp_large`, for
+    matrices a dense SVD is too slow for in a test, is an fp64 iteration that returns its own
+    certificate and is pinned against `svd_comp`);
+  * `range_finder_comp` is this build's reading of the "lighter contractive compressor" the paper
+    allows in place of SVD-Comp without printing one (randomized range finder).
 
 Every input is widened exactly to fp64; nothing is blocked, fused or reordered relative to
 Algorithm 1 / Algorithm 2.  The literal per-worker form (one error buffer e^(i) per worker) is
@@ -111,6 +115,81 @@ def svd_comp(deltas: Sequence[np.ndarray], r: int) -> CompOut:
     q_i = [d.T @ p_tilde for d in deltas]
     q = worker_mean(q_i)
     return CompOut(q, p_tilde, [p_tilde @ qi.T for qi in q_i], p_tilde @ q.T, sigma=s)
+
+
+# ----------------------------------------------------------------------------------------
+# SVD-Comp on matrices too large for a dense SVD in a test (4096^2 takes seconds, 8192^2 minutes).
+# Definition 3 fixes the result, not an algorithm: the top-r left singular subspace.  This routine reaches it by
+# fp64 block subspace iteration with generous oversampling and Rayleigh-Ritz, and returns a certificate with it:
+# the residuals ||M^T u_k - s_k v_k|| and ||M v_k - s_k u_k|| of the r leading triplets, relative to s_1.  A caller
+# asserts the certificate; `tests/test_oracle_pins.py` checks the routine against `svd_comp` on sizes where both run.
+# ----------------------------------------------------------------------------------------
+def svd_comp_large(deltas: Sequence[np.ndarray], r: int, oversample: int = 64, iters: int = 40,
+                   tol: float = 1e-11, seed: int = 0) -> Tuple[CompOut, float]:
+    delta = worker_mean(deltas)
+    m, n = delta.shape
+    b = min(n, r + oversample)
+    y = np.random.default_rng(seed).standard_normal((n, b))
+    resid = np.inf
+    for _ in range(iters):
+        z, _ = np.linalg.qr(delta @ y)                 # orthonormal basis of M Y
+        y = delta.T @ z                                # Y = M^T Z
+        w, s, vt = np.linalg.svd(y.T, full_matrices=False)     # Z^T M = W S V^T  (b x n)
+        u = z @ w[:, :r]                               # Ritz vectors: leading left singular vectors
+        v = vt[:r].T
+        resid = max(float(np.linalg.norm(delta.T @ u - v * s[:r])), float(np.linalg.norm(delta @ v - u * s[:r]))) / s[0]
+        if resid <= tol:
+            break
+    p_tilde = u
+    q_i = [d.T @ p_tilde for d in deltas]
+    q = worker_mean(q_i)
+    return CompOut(q, p_tilde, [p_tilde @ qi.T for qi in q_i], p_tilde @ q.T, sigma=s[:r]), resid
+
+
+# ----------------------------------------------------------------------------------------
+# A lighter contractive compressor in place of SVD-Comp (the remark after Theorem 2 and the last row of Table 1
+# allow any contractive compressor there and name random projection and an approximate top-r; the paper prints no
+# algorithm for them).  Reading: the randomized range finder --
+#   sketch  Y = M Omega  (Omega: n x b random, b >= r);  Z = orthonormal basis of Y;  B = Z^T M  (b x n);
+#   B = W S V^T (small SVD);  P~ = Z W[:, :r];  then Q = M^T P~ and the residual as in SVD-Comp.
+# P~ P~^T is an orthogonal projector, so the compressor is contractive (||M - P~P~^T M|| <= ||M||), and it is exact
+# when rank(M) <= b.  Omega is an input: the GPU draws it from a counter-based generator (`counter_uniform` below is
+# the same generator written in NumPy), so both sides can be given the same one.
+# ----------------------------------------------------------------------------------------
+def range_finder_comp(deltas: Sequence[np.ndarray], r: int, omega: np.ndarray) -> CompOut:
+    delta = worker_mean(deltas)
+    z = qr_thin(delta @ np.asarray(omega, dtype=np.float64))
+    b_mat = z.T @ delta
+    w, s, _vt = np.linalg.svd(b_mat, full_matrices=False)
+    p_tilde = z @ w[:, :r]
+    q_i = [d.T @ p_tilde for d in deltas]
+    q = worker_mean(q_i)
+    return CompOut(q, p_tilde, [p_tilde @ qi.T for qi in q_i], p_tilde @ q.T, sigma=s)
+
+
+def _mix32(x: np.ndarray) -> np.ndarray:
+    """32-bit integer finaliser (xor-shift-multiply, two rounds), on uint32 arrays with wrap-around."""
+    x = x.astype(np.uint64)
+    x ^= x >> np.uint64(16)
+    x = (x * np.uint64(0x7FEB352D)) & np.uint64(0xFFFFFFFF)
+    x ^= x >> np.uint64(15)
+    x = (x * np.uint64(0x846CA68B)) & np.uint64(0xFFFFFFFF)
+    x ^= x >> np.uint64(16)
+    return x
+
+
+def counter_uniform(seed: int, layer: int, rows: int, cols: int) -> np.ndarray:
+    """rows x cols matrix of uniform numbers in [-1, 1) with 24 random bits each, a pure function of
+    (seed, layer, row, column): entry = (h >> 8) * 2^-23 - 1 with
+    h = mix(mix(seed ^ mix(layer * 0x9E3779B9 + 0x85EBCA6B)) ^ mix(row + 0x632BE5AB) ^ mix(column * 0xC2B2AE35 + 0x27D4EB2F)).
+    The library's random start block of the refresh is drawn by the same rule on the device."""
+    m32 = np.uint64(0xFFFFFFFF)
+    lay = _mix32(np.array([(layer * 0x9E3779B9 + 0x85EBCA6B) & 0xFFFFFFFF], dtype=np.uint64))
+    h0 = _mix32(np.uint64(seed & 0xFFFFFFFF) ^ lay)
+    ri = _mix32((np.arange(rows, dtype=np.uint64) + np.uint64(0x632BE5AB)) & m32)
+    ci = _mix32((np.arange(cols, dtype=np.uint64) * np.uint64(0xC2B2AE35) + np.uint64(0x27D4EB2F)) & m32)
+    h = _mix32(h0 ^ ri[:, None] ^ ci[None, :])
+    return (h >> np.uint64(8)).astype(np.float64) * (2.0 / 16777216.0) - 1.0
 
 
 # ----------------------------------------------------------------------------------------

@@ -697,6 +697,7 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
         }
         L.status[4] = max(2, min(255, k_next));
         L.status[5] = sweeps;
+        L.status[24] = min(L.status[24] + 1, 1 << 20);
     }
 }
 

@@ -51,7 +51,17 @@ def test_init_rejects_bad_arguments(lib):
     assert _init(lib, [(256, 130, 0, 4, psgd.PSGD_F32)])[0] == psgd.PSGD_E_ALIGN       # ld = cols not multiple of 8
     assert _init(lib, [(256, 130, 136, 4, psgd.PSGD_F32)])[0] == psgd.PSGD_OK          # padded ld is fine
     assert _init(lib, [(4096, 4096, 0, 190, psgd.PSGD_F32)])[0] == psgd.PSGD_E_SHAPE   # block wider than supported
-    for code in (0, -1, -2, -3, -4, -5, -99):
+    # leading dimensions beyond what the kernels' 32-bit lane offsets cover (127 rows * ld * 4 bytes < 2^32)
+    assert _init(lib, [(256, 128, (1 << 23) + 8, 4, psgd.PSGD_F32)])[0] == psgd.PSGD_E_SHAPE
+    assert _init(lib, [(256, 128, 1 << 23, 4, psgd.PSGD_F32)])[0] == psgd.PSGD_OK
+    # the refresh's iteration budget has eight bits in the launches' gate word
+    for iters, want in ((255, psgd.PSGD_OK), (256, psgd.PSGD_E_INVALID_ARG), (-1, psgd.PSGD_E_INVALID_ARG)):
+        opt = psgd.Options(iters, -1, 1, 1, 0.0, 0, 0, 0, 0, 0)
+        rc, ctx = _init(lib, [ok], opt=C.byref(opt))
+        assert rc == want, iters
+        if rc == psgd.PSGD_OK:
+            lib.psgd_destroy(ctx)
+    for code in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert lib.psgd_strerror(code)
 
 
@@ -59,6 +69,7 @@ def test_compute_calls_reject_null_without_touching_a_gpu(lib):
     rc, ctx = _init(lib, [(256, 128, 0, 4, psgd.PSGD_F32)])
     assert rc == 0
     assert lib.psgd_compress(ctx, None, None, None, None, None, None) == psgd.PSGD_E_INVALID_ARG
+    assert lib.psgd_compress_static(ctx, None, None, None, None, None) == psgd.PSGD_E_INVALID_ARG
     assert lib.psgd_compress_refresh(ctx, None, None, None, None, None, None) == psgd.PSGD_E_INVALID_ARG
     assert lib.psgd_refresh(ctx, None, None, 0, None, None, None, None) == psgd.PSGD_E_INVALID_ARG
     assert lib.psgd_decompress(ctx, None, None, None, None, None, 0) == psgd.PSGD_E_INVALID_ARG
@@ -101,8 +112,9 @@ def test_struct_layouts_match_the_header(tmp_path):
         lines.append('printf("%s %%zu\\n", sizeof(%s));' % (s, s))
         for f in fs:
             lines.append('printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (s, f, s, f))
-    lines.append('printf("codes %d %d %d %d %d %d\\n", PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, '
-                 'PSGD_E_NOMEM, PSGD_E_CAPTURE);')
+    lines.append('printf("codes %d %d %d %d %d %d %d\\n", PSGD_E_INVALID_ARG, PSGD_E_SHAPE, PSGD_E_ALIGN, PSGD_E_HIP, '
+                 'PSGD_E_NOMEM, PSGD_E_CAPTURE, PSGD_E_TOO_LARGE);')
+    lines.append('printf("static_ws %u\\n", (unsigned)PSGD_STATIC_WORKSPACE_BYTES);')
     lines += ['return 0; }']
     src = tmp_path / "layout.c"
     src.write_text("\n".join(lines))
@@ -115,4 +127,6 @@ def test_struct_layouts_match_the_header(tmp_path):
         for f in fields[s]:
             assert int(out["%s.%s" % (s, f)]) == getattr(cls, f).offset, (s, f)
     assert [int(x) for x in out["codes"].split()] == [psgd.PSGD_E_INVALID_ARG, psgd.PSGD_E_SHAPE, psgd.PSGD_E_ALIGN,
-                                                      psgd.PSGD_E_HIP, psgd.PSGD_E_NOMEM, psgd.PSGD_E_CAPTURE]
+                                                      psgd.PSGD_E_HIP, psgd.PSGD_E_NOMEM, psgd.PSGD_E_CAPTURE,
+                                                      psgd.PSGD_E_TOO_LARGE]
+    assert int(out["static_ws"]) == psgd.STATIC_WORKSPACE_BYTES

@@ -228,3 +228,36 @@ def test_flush_on_another_workspace_is_rejected():
     out = orc.compress_step(1, None, wl.r, synth.initial_q(spec.n, wl.r, wl.seed, 0).astype(np.float64), g,
                             [np.zeros((spec.rows, spec.cols))] * wl.n_workers)
     assert orc.rel_fro(back(case.E[0]), out.e_mean) <= 1e-4
+
+
+def test_compress_on_another_workspace_while_a_residual_is_owed_is_rejected():
+    """The same for the two compress calls: they would subtract the kept operands of a workspace that has none, so
+    they are refused before anything is uploaded or enqueued, and the step goes on in the right workspace."""
+    import ctypes as C
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config1(), 256, 128)
+    spec = wl.layers[0]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype, lazy_residual=True)
+    grads = _layers_inputs(wl, 0)
+    q0 = synth.initial_q(spec.n, wl.r, wl.seed, 0)
+    case.upload(grads, [np.zeros((spec.rows, spec.cols), np.float32)], [q0])
+    case.compress()                                       # leaves M_0 in E, the residual owed
+    other = torch.empty(case.comp.workspace_bytes + 256, dtype=torch.uint8, device="cuda")
+    other_ptr = (other.data_ptr() + 255) // 256 * 256
+    vp = C.c_void_p
+    tg = (vp * wl.n_workers)(*[g.data_ptr() for g in case.G[0]])
+    te, tq, tp = (vp * 1)(case.E[0].data_ptr()), (vp * 1)(case.Q[0].data_ptr()), (vp * 1)(case.P[0].data_ptr())
+    e_before, q_before = back(case.E[0]), back(case.Q[0])
+    for fn in (case.comp.lib.psgd_compress, case.comp.lib.psgd_compress_refresh):
+        assert fn(case.comp.ctx, other_ptr, 0, tg, te, tq, tp) == psgd.PSGD_E_INVALID_ARG
+    torch.cuda.synchronize()
+    assert np.array_equal(e_before, back(case.E[0])) and np.array_equal(q_before, back(case.Q[0]))   # nothing ran
+    # the run continues in its own workspace: step 1 of the oracle's trajectory
+    case.compress()
+    case.comp.flush_residual(case.E)
+    torch.cuda.synchronize()
+    g = [synth.gradient_as_f64(gw) for gw in grads[0]]
+    o0 = orc.compress_step(1, None, wl.r, q0.astype(np.float64), g, [np.zeros((spec.rows, spec.cols))] * wl.n_workers)
+    o1 = orc.compress_step(1, None, wl.r, o0.comp.q, g, o0.e_next)
+    assert orc.rel_fro(back(case.E[0]), o1.e_mean) <= 1e-4
+    assert orc.rel_fro(back(case.P[0]), o1.comp.p_tilde) <= 1e-4

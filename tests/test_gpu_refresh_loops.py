@@ -1,0 +1,101 @@
+"""SVD-Comp steps as they occur in runs: after a stretch of error feedback (tau = 10 at config 2's full size), and
+several in a row enqueued without the host ever waiting for the GPU (tau = 1, Algorithm 2 with the smallest period).
+
+Every refreshed step is compared with the oracle's SVD-Comp of the same M = mean G_t + E_t.  The subspace bar
+sin(theta_max) <= 1e-4 is asserted where the cut after sigma_r is a real gap ((sigma_r - sigma_{r+1}) / sigma_1 >= 1e-2);
+the gap-independent equality of Eq. (6), | ||E||^2 - sum_{i>r} sigma_i^2 | <= 1e-4 ||M||^2, and the exact relations
+Q = M^T P~, E = M - P~ Q^T, P~^T P~ = I are asserted always.
+"""
+import time
+
+import numpy as np
+import pytest
+
+from oracle import psgd_oracle as orc
+from paper_2509_11254_amd import psgd, synth
+from gpu_harness import Case, back, oracle_inputs, to_dev_grad, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_refreshed_step(mat, p, q, e, r, tag):
+    """mat: the matrix that was compressed (fp64); p, q, e: what the library returned for it."""
+    nm = np.linalg.norm(mat)
+    assert np.all(np.isfinite(p)) and np.all(np.isfinite(q)) and np.all(np.isfinite(e)), tag
+    assert np.abs(p.T @ p - np.eye(r)).max() < 2e-5, tag
+    assert np.linalg.norm(q - mat.T @ p) <= 2e-5 * nm, tag                      # Q = M^T P~
+    assert np.linalg.norm(e - (mat - p @ q.T)) <= 2e-5 * nm, tag                # E = M - P~ Q^T
+    u, s, _ = np.linalg.svd(mat, full_matrices=False)
+    tail = float(np.sum(s[r:] ** 2))
+    energy_gap = abs(float(np.sum(e ** 2)) - tail) / nm ** 2
+    assert energy_gap <= 1e-4, (tag, energy_gap)
+    gap = (s[r - 1] - s[r]) / s[0]
+    sn = orc.sin_theta_max(u[:, :r], p)
+    if gap >= 1e-2:
+        assert sn <= 1e-4, (tag, gap, sn)
+    return {"gap": float(gap), "sin": float(sn), "energy": float(energy_gap)}
+
+
+def test_config2_full_size_refreshes_in_an_error_feedback_run():
+    """t = 0 SVD-Comp, then tau = 10: SSP-Comp steps with SVD-Comp at t = 10 and t = 20, the library keeping its own E
+    and Q throughout -- the state a refresh meets in a run, where error feedback has filled E with what was not sent
+    and flattened the spectrum at the cut.  The refresh at t = 10 is the layer's second (whole iteration budget); the
+    one at t = 20 runs the count the layer chose from its own Ritz values at t = 10 (or the fixed eight if that
+    exceeds the budget).  Both are checked against the oracle's SVD of the same M."""
+    wl = synth.config2()
+    spec = wl.layers[0]
+    sig = synth.signal_matrix(spec, wl, 0)
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    grads = [[synth.worker_gradient(spec, wl, 0, w, 0, sig) for w in range(wl.n_workers)]]
+    case.upload(grads, [np.zeros((spec.rows, spec.cols), np.float32)], [synth.initial_q(spec.n, wl.r, wl.seed, 0)])
+    for t in range(21):
+        if t > 0:
+            grads = [[synth.worker_gradient(spec, wl, 0, w, t, sig) for w in range(wl.n_workers)]]
+            case.G = [[to_dev_grad(g, case.lds[0]) for g in grads[0]]]
+        refresh = t % wl.tau == 0
+        if refresh and t > 0:
+            e_before = back(case.E[0], spec.cols)
+            k_next = case.comp.status(0).refresh_iters_next
+        case.compress(refresh=refresh)
+        if refresh and t > 0:
+            g, e = oracle_inputs(grads[0], e_before, spec.rows, spec.cols, wl.n_workers)
+            mat = orc.worker_mean(orc.ef_accumulate(g, e))
+            p, q, e_after = case.outputs(0)
+            sv = np.linalg.svd(mat, compute_uv=False)
+            print("t", t, "iterations the layer asked for", k_next, "(t = 10 runs the budget; above 16: the fixed eight)",
+                  "sigma_{r+1}/sigma_r", sv[wl.r] / sv[wl.r - 1], "sigma_{b+1}/sigma_r", sv[16] / sv[wl.r - 1],
+                  "||E|| / ||M||", np.linalg.norm(e_before) / np.linalg.norm(mat), flush=True)
+            print(_check_refreshed_step(mat, p, q, e_after, wl.r, "t=%d" % t), flush=True)
+
+
+@pytest.mark.parametrize("pause", [0.0, 0.05])
+def test_refresh_steps_back_to_back_without_host_sync(pause):
+    """Six SVD-Comp steps enqueued one behind the other; the host never waits for the GPU in between (pause = 0), or
+    sleeps a little so that the iteration bound fetched behind one step has arrived when a later one is enqueued
+    (pause > 0) -- both orders of events a loop with tau = 1 produces.  Error feedback flattens the spectrum at the
+    cut from step to step, so the per-layer iteration counts move; whatever the host knew when it launched a step,
+    every step must be a complete SVD-Comp step.  Copies of E, P~, Q are taken on the stream after every call."""
+    torch = torch_mod()
+    wl = synth.scaled_down(synth.config2(), 1536, 1024)
+    wl.n_workers = 2
+    spec = wl.layers[0]
+    steps = 6
+    sig = synth.signal_matrix(spec, wl, 0)
+    grads = [[synth.worker_gradient(spec, wl, 0, w, t, sig) for w in range(wl.n_workers)] for t in range(steps)]
+    case = Case([(spec.rows, spec.cols)], wl.r, wl.n_workers, wl.grad_dtype)
+    case.upload([grads[0]], [np.zeros((spec.rows, spec.cols), np.float32)], [synth.initial_q(spec.n, wl.r, wl.seed, 0)])
+    G_dev = [[[to_dev_grad(g) for g in grads[t]]] for t in range(steps)]
+    torch.cuda.synchronize()
+    snaps = []
+    for t in range(steps):
+        e_in = case.E[0].clone()
+        case.comp.compress_refresh(G_dev[t], case.E, case.Q, case.P)
+        snaps.append((e_in, case.P[0].clone(), case.Q[0].clone(), case.E[0].clone()))
+        if pause:
+            time.sleep(pause)
+    torch.cuda.synchronize()
+    for t, (e_in, p, q, e_out) in enumerate(snaps):
+        g, e = oracle_inputs(grads[t], back(e_in), spec.rows, spec.cols, wl.n_workers)
+        mat = orc.worker_mean(orc.ef_accumulate(g, e))
+        print("step", t, _check_refreshed_step(mat, back(p), back(q), back(e_out), wl.r, "t=%d pause=%g" % (t, pause)))
+    assert 2 <= case.comp.status(0).refresh_iters_next <= 255

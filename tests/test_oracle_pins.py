@@ -463,3 +463,107 @@ def test_adam_scale_invariance_and_decoupled_weight_decay():
         x, m1, m2 = orc.adam_update(x, m1, m2, np.zeros((4, 4)), t, 0.02, 0.9, 0.999, 1e-8, 0.1)
     np.testing.assert_allclose(x, (1 - 0.02 * 0.1) ** 3 * x0, atol=1e-15)
     assert not m1.any() and not m2.any()
+
+
+# ---------------------------------------------------------------------------------------------------
+# Eq. (7c) over two steps, by hand: m_t = mu m_{t-1} + Delta_hat_t, X_{t+1} = X_t - eta m_t.
+# ---------------------------------------------------------------------------------------------------
+def test_msgd_update_two_steps_by_hand():
+    # scalar: Delta_hat = 1, then -1; mu = 0.5, eta = 0.1  ->  m = 1, -0.5;  x = x0 - 0.1, x0 - 0.1 + 0.05
+    x0 = np.array([[2.0]])
+    x1, m1 = orc.msgd_update(x0, np.zeros((1, 1)), np.array([[1.0]]), 0.1, 0.5)
+    assert m1[0, 0] == 1.0 and abs(x1[0, 0] - 1.9) < 1e-15
+    x2, m2 = orc.msgd_update(x1, m1, np.array([[-1.0]]), 0.1, 0.5)
+    assert m2[0, 0] == -0.5 and abs(x2[0, 0] - 1.95) < 1e-15          # (stepping with Delta_hat instead of m_t gives 2.0)
+    # a matrix, two steps, mu = 0.9, eta = 0.25: entries worked out one by one
+    d1 = np.array([[1.0, -2.0], [0.5, 4.0]])
+    d2 = np.array([[-3.0, 1.0], [2.0, 0.0]])
+    xa = np.array([[1.0, 1.0], [1.0, 1.0]])
+    xb, ma = orc.msgd_update(xa, np.zeros((2, 2)), d1, 0.25, 0.9)
+    xc, mb = orc.msgd_update(xb, ma, d2, 0.25, 0.9)
+    np.testing.assert_allclose(mb, [[0.9 - 3.0, -1.8 + 1.0], [0.45 + 2.0, 3.6]], atol=1e-15)
+    np.testing.assert_allclose(xc, [[1 - 0.25 + 0.525, 1 + 0.5 + 0.2], [1 - 0.125 - 0.6125, 1 - 1.0 - 0.9]], atol=1e-15)
+
+
+# ---------------------------------------------------------------------------------------------------
+# svd_comp_large (the iteration used where a dense SVD is too slow) against svd_comp (the definition).
+# ---------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("m,n,r,gap", [(300, 200, 20, True), (256, 128, 4, False), (160, 160, 33, True)])
+def test_svd_comp_large_matches_the_definition(m, n, r, gap):
+    rng = np.random.default_rng([m, n, r])
+    u, _ = np.linalg.qr(rng.standard_normal((m, min(m, n))))
+    v, _ = np.linalg.qr(rng.standard_normal((n, min(m, n))))
+    k = min(m, n)
+    s = np.concatenate([np.linspace(2.0, 1.0, r), (0.6 if gap else 0.97) * 0.95 ** np.arange(k - r)])
+    mats = [(u * s) @ v.T + 1e-3 * rng.standard_normal((m, n)) for _ in range(3)]
+    ref = orc.svd_comp(mats, r)
+    out, resid = orc.svd_comp_large(mats, r, oversample=48, iters=400)
+    assert resid <= 1e-10                                      # its own certificate
+    np.testing.assert_allclose(out.sigma, ref.sigma[:r], rtol=1e-10)
+    assert orc.sin_theta_max(ref.p_tilde, out.p_tilde) <= 1e-8
+    np.testing.assert_allclose(out.delta_hat, ref.delta_hat, atol=1e-8)
+    for a, b in zip(out.delta_hat_i, ref.delta_hat_i):
+        np.testing.assert_allclose(a, b, atol=1e-8)
+
+
+# ---------------------------------------------------------------------------------------------------
+# range_finder_comp (reading of the "lighter contractive compressor" the paper allows in place of SVD-Comp).
+# ---------------------------------------------------------------------------------------------------
+def test_range_finder_two_by_two_by_hand():
+    # M = diag(3, 1), Omega = (1, 1)^T, r = 1: Y = (3, 1), Z = (3, 1)/sqrt(10), Delta_hat = Z Z^T M
+    out = orc.range_finder_comp([np.diag([3.0, 1.0])], 1, np.array([[1.0], [1.0]]))
+    np.testing.assert_allclose(np.abs(out.p_tilde.ravel()), np.array([3.0, 1.0]) / np.sqrt(10.0), atol=1e-15)
+    np.testing.assert_allclose(out.delta_hat, np.array([[27.0, 3.0], [9.0, 1.0]]) / 10.0, atol=1e-14)
+    np.testing.assert_allclose(np.abs(out.q.ravel()), np.array([9.0, 1.0]) / np.sqrt(10.0), atol=1e-14)
+
+
+def test_range_finder_is_exact_within_the_block_and_bounded_by_eckart_young():
+    rng = np.random.default_rng(5)
+    m, n, r, b = 120, 80, 6, 10
+    # rank 9 <= b: the sketch spans the range, the result is SVD-Comp's
+    low = rng.standard_normal((m, 9)) @ rng.standard_normal((9, n))
+    mats = [low + 0.0 * rng.standard_normal((m, n)) for _ in range(2)]
+    om = rng.standard_normal((n, b))
+    out, ref = orc.range_finder_comp(mats, r, om), orc.svd_comp(mats, r)
+    assert orc.sin_theta_max(ref.p_tilde, out.p_tilde) <= 1e-9
+    np.testing.assert_allclose(out.delta_hat, ref.delta_hat, atol=1e-9)
+    np.testing.assert_allclose(out.sigma[:9], ref.sigma[:9], rtol=1e-9)
+    # full rank: a projector (Pythagoras, Eq. (4)), never better than the optimum (Eq. (6)), contractive
+    mats = [rng.standard_normal((m, n)) * (0.9 ** np.arange(n))[None, :] for _ in range(3)]
+    mean = orc.worker_mean(mats)
+    out, ref = orc.range_finder_comp(mats, r, om), orc.svd_comp(mats, r)
+    p = out.p_tilde
+    np.testing.assert_allclose(p.T @ p, np.eye(r), atol=1e-13)
+    np.testing.assert_allclose(out.delta_hat, p @ (p.T @ mean), atol=1e-12)
+    np.testing.assert_allclose(out.q, mean.T @ p, atol=1e-12)
+    err2 = np.linalg.norm(mean - out.delta_hat) ** 2
+    assert abs(err2 + np.linalg.norm(out.delta_hat) ** 2 - np.linalg.norm(mean) ** 2) <= 1e-10 * np.linalg.norm(mean) ** 2
+    assert float(np.sum(ref.sigma[r:] ** 2)) * (1 - 1e-12) <= err2 <= np.linalg.norm(mean) ** 2
+    # per-worker reconstructions average to the global one (linearity, Appendix B notations)
+    np.testing.assert_allclose(orc.worker_mean(out.delta_hat_i), out.delta_hat, atol=1e-12)
+    # a square non-singular Omega spans everything: SVD-Comp again
+    out = orc.range_finder_comp(mats, r, rng.standard_normal((n, n)))
+    assert orc.sin_theta_max(ref.p_tilde, out.p_tilde) <= 1e-8
+
+
+def _mix32_scalar(x):
+    x &= 0xFFFFFFFF
+    x ^= x >> 16
+    x = (x * 0x7FEB352D) & 0xFFFFFFFF
+    x ^= x >> 15
+    x = (x * 0x846CA68B) & 0xFFFFFFFF
+    x ^= x >> 16
+    return x
+
+
+def test_counter_uniform_against_a_scalar_loop():
+    seed, layer = 0x5EED5EED, 3
+    got = orc.counter_uniform(seed, layer, 5, 7)
+    h0 = _mix32_scalar(seed ^ _mix32_scalar(layer * 0x9E3779B9 + 0x85EBCA6B))
+    for i in range(5):
+        for c in range(7):
+            h = _mix32_scalar(h0 ^ _mix32_scalar(i + 0x632BE5AB) ^ _mix32_scalar(c * 0xC2B2AE35 + 0x27D4EB2F))
+            assert got[i, c] == (h >> 8) * (2.0 / 16777216.0) - 1.0
+    big = orc.counter_uniform(1, 0, 400, 300)
+    assert -1.0 <= big.min() and big.max() < 1.0 and abs(big.mean()) < 0.01 and abs(big.var() - 1.0 / 3.0) < 0.01
+    assert not np.array_equal(big, orc.counter_uniform(2, 0, 400, 300))
