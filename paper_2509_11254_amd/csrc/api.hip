@@ -23,7 +23,8 @@ hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, c
                            int xtiles, hipStream_t st);
 bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy);
 hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                           int out_role, int epi, int gate, int nt_s, hipStream_t st);
+                           int out_role, int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                           hipStream_t st);
 bool col_prod_supported(int nb);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
@@ -109,9 +110,9 @@ struct psgd_ctx {
     bool nt_m = false;                          // the row-major layers' M is too large to be found in a cache again
     // XCD table of the forming pass on 32 x 256 tiles (see form_row_kernel): 16 rows of xstride ints; built when the
     // row-major layers are many enough to be dealt evenly to the 8 XCDs
-    std::vector<int> hXtab;
-    int xstride = 0, xtiles = 0;
-    size_t off_xtab = 0;
+    std::vector<int> hXtab, hXtabC;             // (forming pass; column-mode product: other tile counts)
+    int xstride = 0, xtiles = 0, xtiles_c = 0;
+    size_t off_xtab = 0, off_xtab_c = 0;
     // workspace layout (byte offsets)
     // The gradient pointer table and the layer descriptors (which point into it) exist kGSlots times: a caller
     // that rotates between a few sets of gradient buffers finds its table already on the device.
@@ -353,6 +354,7 @@ int upload_tables(psgd_ctx* ctx, void* workspace, hipStream_t st, bool desc_chan
         ids[3 * (size_t)nl] = nl;   // id of the scratch descriptor
         PSGD_TRY(launch_put(ws + ctx->off_ids, ids.data(), ids.size() * sizeof(int), st));
         if (!ctx->hXtab.empty()) PSGD_TRY(launch_put(ws + ctx->off_xtab, ctx->hXtab.data(), ctx->hXtab.size() * sizeof(int), st));
+        if (!ctx->hXtabC.empty()) PSGD_TRY(launch_put(ws + ctx->off_xtab_c, ctx->hXtabC.data(), ctx->hXtabC.size() * sizeof(int), st));
     }
     if (fresh)
         for (auto& v : ctx->hGs) v.clear();
@@ -442,7 +444,9 @@ struct Launcher {
                               ? reinterpret_cast<const int*>(ws + ctx->off_xtab) : nullptr;
         // the second product on row-major layers at those widths likewise
         const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb);
-        if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, st));
+        const int* xtab_c = (ctx->xstride > 0 && use_xtab && nb >= 2 && gate < 0 && ids_norm == ids_all + ctx->n_layers)
+                                ? reinterpret_cast<const int*>(ws + ctx->off_xtab_c) : nullptr;
+        if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, xtab_c, ctx->xstride, ctx->xtiles_c, st));
         else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, ef, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
         else if (!c2) note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
@@ -712,29 +716,37 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         c->grad_kind = f32 && b16 ? 0 : (f32 ? 1 : 2);
         // M that the second pass can find in the 256 MB memory-side cache is stored with plain stores
         c->nt_m = m_bytes > ((int64_t)96 << 20);
+        if (const char* e = std::getenv("PSGD_NT_M")) c->nt_m = e[0] != '0';     // (measurement knob)
         // XCD table: the row-major layers (positions in the id list `norm`), largest first, each to the XCD with the
         // least work so far
         const int n_norm = (int)c->lists.norm.size();
         if (n_norm >= 32) {
             c->xstride = n_norm + 2;
-            c->hXtab.assign((size_t)16 * c->xstride, 0);
-            std::vector<int> order(n_norm);
-            for (int i = 0; i < n_norm; ++i) order[i] = i;
-            auto tiles_of = [&](int pos) { return (c->plan[c->lists.norm[pos]].rowsP / 32) * c->split_row_v2; };
-            std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return tiles_of(a) > tiles_of(b); });
-            int total[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            for (int pos : order) {
-                int x = 0;
-                for (int k = 1; k < 8; ++k) if (total[k] < total[x]) x = k;
-                c->hXtab[(size_t)(8 + x) * c->xstride + count[x]] = pos;
-                total[x] += tiles_of(pos);
-                count[x] += 1;
-                c->hXtab[(size_t)x * c->xstride + count[x]] = total[x];
-            }
-            for (int x = 0; x < 8; ++x) {
-                c->hXtab[(size_t)x * c->xstride + c->xstride - 1] = count[x];
-                if (total[x] > c->xtiles) c->xtiles = total[x];
-            }
+            // work = rows x cols decides the deal (the same for both kernels), tiles = what a layer launches
+            auto build = [&](std::vector<int>& tab, int& xtiles, auto tiles_of) {
+                tab.assign((size_t)16 * c->xstride, 0);
+                std::vector<int> order(n_norm);
+                for (int i = 0; i < n_norm; ++i) order[i] = i;
+                auto work_of = [&](int pos) { const Plan& p = c->plan[c->lists.norm[pos]]; return p.d.rows * p.d.cols; };
+                std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return work_of(a) > work_of(b); });
+                int64_t work[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                int total[8] = {0, 0, 0, 0, 0, 0, 0, 0}, count[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+                for (int pos : order) {
+                    int x = 0;
+                    for (int k = 1; k < 8; ++k) if (work[k] < work[x]) x = k;
+                    tab[(size_t)(8 + x) * c->xstride + count[x]] = pos;
+                    total[x] += tiles_of(pos);
+                    work[x] += work_of(pos);
+                    count[x] += 1;
+                    tab[(size_t)x * c->xstride + count[x]] = total[x];
+                }
+                for (int x = 0; x < 8; ++x) {
+                    tab[(size_t)x * c->xstride + c->xstride - 1] = count[x];
+                    if (total[x] > xtiles) xtiles = total[x];
+                }
+            };
+            build(c->hXtab, c->xtiles, [&](int pos) { return (c->plan[c->lists.norm[pos]].rowsP / 32) * c->split_row_v2; });
+            build(c->hXtabC, c->xtiles_c, [&](int pos) { return ((c->plan[c->lists.norm[pos]].colsP + 255) / 256) * c->split_col_v2; });
         }
     }
     // workspace layout
@@ -744,6 +756,7 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
     c->off_ids = take((3 * (size_t)n_layers + 1) * sizeof(int));
     c->off_iters = take(psgd_ctx::kIterSlots * sizeof(int));
     c->off_xtab = take(c->hXtab.size() * sizeof(int) + 16);
+    c->off_xtab_c = take(c->hXtabC.size() * sizeof(int) + 16);
     for (int k = 0; k < psgd_ctx::kGSlots; ++k) c->off_gtab_s[k] = take((size_t)n_layers * n_workers * sizeof(void*));
     c->off_outs = take((size_t)n_layers * sizeof(void*));
     c->off_moms = take((size_t)n_layers * sizeof(void*));

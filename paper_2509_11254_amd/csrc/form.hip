@@ -427,20 +427,31 @@ template <int NB, int PL> constexpr size_t colprod_lds_bytes() {
     return a > o ? a : o;
 }
 
-// (three workgroups per compute unit where LDS and registers allow it: one tile per workgroup in flight is not enough
-// to cover the memory latency with two)
 template <int NB, int PL>
-__global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(const LayerDev* __restrict__ layers,
+__global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_prod_kernel(const LayerDev* __restrict__ layers,
                                                                 const int* __restrict__ ids, int out_role,
-                                                                int epi_flags, int gate, int nt_s) {
+                                                                int epi_flags, int gate, int nt_s,
+                                                                const int* __restrict__ xtab, int xstride) {
     constexpr int cp = 32 * NB;
     constexpr int APL = CW * CLD;
-    const LayerDev& L = layers[ids[blockIdx.y]];
+    // (layer and tile: plain, or through an XCD table as in form_row_kernel -- all workgroups of a layer on one XCD
+    // fetch its thin operand into one L2 instead of eight)
+    int layer_pos = blockIdx.y, tile = blockIdx.x;
+    if (xtab) {
+        const int x = blockIdx.x & 7, s = blockIdx.x >> 3;
+        const int* pre = xtab + x * xstride;
+        const int n_mine = pre[xstride - 1];
+        if (n_mine == 0 || s >= pre[n_mine]) return;
+        int j = 0;
+        while (s >= pre[j + 1]) ++j;
+        layer_pos = xtab[(8 + x) * xstride + j];
+        tile = s - pre[j];
+    }
+    const LayerDev& L = layers[ids[layer_pos]];
     if (!gate_open(L, gate)) return;
     const int epi = epi_flags & EPI_KIND_MASK;
     const int n_cb = (L.colsP + CW - 1) / CW;
     const int n_split = L.split_col_v2;
-    const int tile = blockIdx.x;
     if (tile >= n_cb * n_split) return;
     const int ob = tile % n_cb, sp = tile / n_cb;
     const int col0 = ob * CW;
@@ -505,14 +516,19 @@ __global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(c
         for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[rb][nb][v] = 0.f;
-    floatx4 x[8];
+    // Two tiles in flight: step `it` consumes one tile buffer while the tile of step it + 1 (requested a step ago) is
+    // on its way in the other, and requests the tile of step it + 2 into the buffer it has just emptied -- after its
+    // MFMA phase and after the fragments of step it + 1 (the wait counter is in issue order: what the next MFMA phase
+    // waits for must be older than the tile that is to stay in flight through it).
+    floatx4 xa[8], xb[8];
     bf16x8 bfrag[2][NB][PL];
     if (n_loc > 0) {
-        load_tile(ch0, x);
+        load_tile(ch0, xa);
         load_b(ch0, bfrag);
+        if (n_loc > 1) load_tile(ch0 + 1, xb);
     }
     const int wsw = (lane >> 2) & 3;                  // write side: bits 4, 5 of this thread's columns 4 lane + q
-    for (int it = 0; it < n_loc; ++it) {
+    auto step = [&](int it, floatx4 (&x)[8]) {
         // ---- tile -> planes -> LDS, transposed: column 4 lane + q gets this thread's 8 rows as one 16-byte write
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -529,7 +545,6 @@ __global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(c
                 *reinterpret_cast<bf16x8*>(a_pl + k * APL + (4 * lane + q) * CLD + 8 * (wv ^ wsw)) = o[k];
         }
         __syncthreads();
-        if (it + 1 < n_loc) load_tile(ch0 + it + 1, x);       // in flight during the MFMA phase
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
@@ -551,7 +566,12 @@ __global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(c
                         }
             }
         if (it + 1 < n_loc) load_b(ch0 + it + 1, bfrag);
+        if (it + 2 < n_loc) load_tile(ch0 + it + 2, x);
         __syncthreads();
+    };
+    for (int it = 0; it < n_loc; it += 2) {
+        step(it, xa);
+        if (it + 1 < n_loc) step(it + 1, xb);
     }
     // ---- the 256 x cp result tile goes out in two halves of 128 rows through LDS (the operand buffer is free: the
     // loop ends in a barrier); half h holds the rows of waves 2 h and 2 h + 1
@@ -595,15 +615,17 @@ __global__ __launch_bounds__(kThreads, (PL == 2 ? 3 : 2)) void col_prod_kernel(c
 
 template <int NB, int PL>
 static hipError_t launch_colprod_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, int out_role,
-                                    int epi, int gate, int nt_s, hipStream_t st) {
+                                    int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                                    hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
+    if (xtab) grid = dim3(8 * xtiles, 1);
     auto kfn = col_prod_kernel<NB, PL>;
     const size_t lds = colprod_lds_bytes<NB, PL>();
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, gate, nt_s);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, gate, nt_s, xtab, xstride);
     return hipGetLastError();
 }
 
@@ -611,12 +633,13 @@ bool col_prod_supported(int nb) { return nb == 1 || nb == 2; }
 
 // max_tiles: max over the layers of ceil(padded cols / 256) * split_col_v2; nt_s: read S with the non-temporal hint
 hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                           int out_role, int epi, int gate, int nt_s, hipStream_t st) {
+                           int out_role, int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                           hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
-    if (nb == 1) return planes == 2 ? launch_colprod_nb<1, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st)
-                                    : launch_colprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st);
-    if (nb == 2) return planes == 2 ? launch_colprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st)
-                                    : launch_colprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, st);
+    if (nb == 1) return planes == 2 ? launch_colprod_nb<1, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
+                                    : launch_colprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
+    if (nb == 2) return planes == 2 ? launch_colprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
+                                    : launch_colprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
     return hipErrorInvalidValue;
 }
 

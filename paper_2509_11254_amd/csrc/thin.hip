@@ -516,8 +516,8 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     const int nv = min(v_rows, n - row0);              // rows of V kept by this workgroup
     extern __shared__ __align__(16) unsigned char smem[];
     double* csb = reinterpret_cast<double*>(smem);     // two buffers of [half] cos, [half] sin
-    double* red = csb + 2 * n;                         // [2] reduction scratch
-    double* a = red + 2;                               // H, n rows of sym_stride(n) (see sym_idx)
+    double* red = csb + 2 * n;                         // [2][16] per-wave partial sums of the convergence test
+    double* a = red + 32;                              // H, n rows of sym_stride(n) (see sym_idx)
     double* v = a + n * sym_stride(n);                 // v_rows x n slice of the accumulated rotations
     int* pqb = reinterpret_cast<int*>(v + v_rows * n); // two buffers of [half] top, [half] bottom matrix indices
     const int t = threadIdx.x;
@@ -580,9 +580,9 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
     __syncthreads();
     int cur = 0, sweeps = 0;
     for (int sweep = 0; sweep < kJacobiMaxSweeps; ++sweep) {
-        // convergence: off-diagonal mass relative to the diagonal
-        if (t < 2) red[t] = 0.0;
-        __syncthreads();
+        // convergence: off-diagonal mass relative to the diagonal.  The per-wave partial sums are added in wave order
+        // by every thread for itself: the same bits in every thread and in every workgroup of the layer, whose
+        // slices of V only fit together if all of them run the same number of sweeps.
         double off = 0.0, dia = 0.0;
         for (int i = ty; i < n; i += tyw)
             for (int j = i + tx; j < n; j += txw) {
@@ -590,9 +590,11 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
                 if (i == j) dia += x * x; else off += 2.0 * x * x;
             }
         for (int o = 32; o > 0; o >>= 1) { off += __shfl_down(off, o); dia += __shfl_down(dia, o); }
-        if ((t & 63) == 0) { atomicAdd(&red[0], off); atomicAdd(&red[1], dia); }
+        if ((t & 63) == 0) { red[t >> 6] = off; red[16 + (t >> 6)] = dia; }
         __syncthreads();
-        const bool done = red[0] <= 1e-20 * red[1];
+        double off_all = 0.0, dia_all = 0.0;
+        for (int wq = 0; wq < (nt >> 6); ++wq) { off_all += red[wq]; dia_all += red[16 + wq]; }
+        const bool done = off_all <= 1e-20 * dia_all;
         if (done) break;
         sweeps = sweep + 1;
         if (t < half) jacobi_rotation(a, n, 0, t, csb + cur * n, pqb + cur * n);
@@ -703,7 +705,7 @@ __global__ __launch_bounds__(1024) void jacobi_kernel(const LayerDev* __restrict
 
 size_t jacobi_lds_bytes(int w, int v_rows) {
     const int n = (w + 1) & ~1;
-    return (size_t)(2 * n + 2 + n * sym_stride(n) + v_rows * n) * sizeof(double) + (size_t)2 * n * sizeof(int);
+    return (size_t)(2 * n + 32 + n * sym_stride(n) + v_rows * n) * sizeof(double) + (size_t)2 * n * sizeof(int);
 }
 
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
