@@ -43,6 +43,8 @@ hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int ma
                        int cp, int which, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
                        int slot_rows, int gate, int a2gate, int local_ok, int after_finish, hipStream_t st);
+hipError_t launch_slot_sum(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int slot_rows,
+                           int group, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
                         bool small, hipStream_t st);
@@ -442,12 +444,13 @@ struct Launcher {
         // (the XCD table pays where the thin operands are a large part of what a workgroup reads: width 64)
         const int* xtab = (ctx->xstride > 0 && use_xtab && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
                               ? reinterpret_cast<const int*>(ws + ctx->off_xtab) : nullptr;
+        const bool gram32 = v2 && split_row_v2 == 1 && epi == EPI_GRAM && w > 16 && chol_gate >= -1;
         // the second product on row-major layers at those widths likewise
         const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb);
         const int* xtab_c = (ctx->xstride > 0 && use_xtab && nb >= 2 && gate < 0 && ids_norm == ids_all + ctx->n_layers)
                                 ? reinterpret_cast<const int*>(ws + ctx->off_xtab_c) : nullptr;
         if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, xtab_c, ctx->xstride, ctx->xtiles_c, st));
-        else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, ef, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
+        else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
         else if (!c2) note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
@@ -456,13 +459,17 @@ struct Launcher {
         const bool split_n = v2 ? split_row_v2 > 1 : c2 ? split_col_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
         if (split_n) note(launch_finish(!p_like, v2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
-        // (the 32-row blocks of that kernel leave the partial Gram matrices of an unsplit launch, one per 128 rows,
-        // to a small pass over the result)
-        if (v2 && !split_n && epi == EPI_GRAM) note(launch_thin_gram(layers, ids_norm, n_norm, blocks_row, out_role, 32 * nb, st));
+        // (an unsplit launch of that kernel writes one partial Gram matrix per 32-row block itself where the
+        // factorisation is a launch of its own -- widths above 16 --, and leaves them to a small pass over the result,
+        // one per 128 rows, where the apply kernel factorises for itself)
+        if (v2 && !split_n && epi == EPI_GRAM && !gram32) note(launch_thin_gram(layers, ids_norm, n_norm, blocks_row, out_role, 32 * nb, st));
         // (after a split product only the layers finish_kernel leaves to it -- wide, many Gram slots -- and none at
         // widths where there are no such layers)
         if (chol_gate >= -1) {
-            if (!split_n || w > 16) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, split_n ? 1 : 0, st));
+            // (32-row slots: added up in groups of 16 side by side first, the factorisation's one workgroup per layer
+            // would otherwise spend most of its time on that sum)
+            if (gram32) note(launch_slot_sum(layers, ids_norm, n_norm, max_rows, out_role, 32, 16, st));
+            if (!split_n || w > 16) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, gram32 ? 32 : kGramRows1, chol_gate, a2gate, small ? 1 : 0, gram32 ? 16 : (split_n ? 1 : 0), st));
             if (!split_t || w > 16) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, split_t ? 1 : 0, st));
         }
     }

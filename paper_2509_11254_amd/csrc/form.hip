@@ -400,9 +400,20 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
             dst[(int64_t)col * L.rowsP + row] = total(row, col);
         }
     } else {
-        for (int i = t; i < FR * T.width; i += kThreads) {
-            const int row = i / T.width, col = i - row * T.width;
-            if (row0 + row < L.rows) as_global(T.ptr)[(int64_t)(row0 + row) * T.ld + col] = total(row, col);
+        // the rows of the result; the totals also replace the first wave's slice in LDS (every entry is read and
+        // written by one thread), from where this row block's partial Gram matrix is formed if the launch asks for
+        // it: one slot per 32 rows here (epi_flags carries EPI_GRAM only where the factorisation that follows sums
+        // 32-row slots)
+        const bool gram = (epi_flags & EPI_KIND_MASK) == EPI_GRAM;
+        for (int i = t; i < FR * cp; i += kThreads) {
+            const int row = i / cp, col = i - row * cp;
+            const float v = total(row, col);
+            if (gram) red[row * RW + col] = v;
+            if (col < T.width && row0 + row < L.rows) as_global(T.ptr)[(int64_t)(row0 + row) * T.ld + col] = v;
+        }
+        if (gram) {
+            __syncthreads();
+            gram_tile_f64(red, RW, FR, T.width, L.gram + (int64_t)ob * ((T.width * (T.width + 1)) / 2));
         }
     }
 }

@@ -132,14 +132,61 @@ __global__ __launch_bounds__(NT) void chol_kernel(const LayerDev* __restrict__ l
     if (!gate_open(L, gate)) return;
     if (pass == 2 && L.status[1] == 0) return;
     if (pass == 1 && local_chol(L, role, local_ok)) return;       // the apply kernel factorises for itself
-    int stride = 1;
-    if (after_finish) {
+    int stride = after_finish > 1 ? after_finish : 1;     // (> 1: slot_sum_kernel has added the slots up in such groups)
+    if (after_finish == 1) {
         const int n_slots = (side_len(L, side_of_role(L.transposed, role)) + slot_rows - 1) / slot_rows;
         if (!grouped_slot_sum(L.thin[role].width, n_slots)) return;
         stride = kSlotGroup;
     }
     extern __shared__ __align__(16) unsigned char smem[];
     chol_body(L, role, tol2, pass, slot_rows, allow2_of(L, a2gate), smem, L.tmat, true, nullptr, stride);
+}
+
+// --------------------------------------------------------------------------------------------
+// slot sum: the partial Gram matrices of thin[role] added up in groups of `group` consecutive slots, each sum left in
+// its group's first slot (fixed order).  For producers that leave many small slots (one per 32 rows): the
+// factorisation's one workgroup per layer then adds up one matrix per group.
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void slot_sum_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
+                                                            int role, int slot_rows, int group) {
+    typedef double doublex2 __attribute__((ext_vector_type(2)));
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    const int len = side_len(L, side_of_role(L.transposed, role));
+    const int n_slots = (len + slot_rows - 1) / slot_rows;
+    const int first = blockIdx.x * group;
+    if (first >= n_slots) return;
+    const int cnt = min(group, n_slots - first);
+    const int w = L.thin[role].width;
+    const int ntri = (w * (w + 1)) / 2;
+    PSGD_GLOBAL double* g0 = as_global(L.gram) + (int64_t)first * ntri;
+    const int t = threadIdx.x;
+    if ((ntri & 1) == 0 && (((int64_t)first * ntri) & 1) == 0) {
+        for (int e = 2 * t; e < ntri; e += 2 * kThreads) {
+            doublex2 x[16];
+#pragma unroll
+            for (int d = 0; d < 16; ++d)
+                x[d] = *reinterpret_cast<const PSGD_GLOBAL doublex2*>(g0 + (int64_t)(d < cnt ? d : 0) * ntri + e);
+            doublex2 sacc = x[0];
+#pragma unroll
+            for (int d = 1; d < 16; ++d) if (d < cnt) sacc += x[d];
+            *reinterpret_cast<PSGD_GLOBAL doublex2*>(g0 + e) = sacc;
+        }
+    } else {
+        for (int e = t; e < ntri; e += kThreads) {
+            double sacc = g0[e];
+            for (int d = 1; d < cnt; ++d) sacc += g0[(int64_t)d * ntri + e];
+            g0[e] = sacc;
+        }
+    }
+}
+
+// group <= 16
+hipError_t launch_slot_sum(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int slot_rows,
+                           int group, hipStream_t st) {
+    if (n_ids <= 0 || group < 2 || group > 16) return n_ids <= 0 ? hipSuccess : hipErrorInvalidValue;
+    const int groups = ((max_len + slot_rows - 1) / slot_rows + group - 1) / group;
+    hipLaunchKernelGGL(slot_sum_kernel, dim3(groups, n_ids), dim3(kThreads), 0, st, layers, ids, role, slot_rows, group);
+    return hipGetLastError();
 }
 
 // Widths that take the blocked factorisation get 512 threads: its panels, trailing updates, the blocked inverse and
