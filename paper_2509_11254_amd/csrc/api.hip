@@ -25,7 +25,11 @@ bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy);
 hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
                            int out_role, int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
                            hipStream_t st);
-bool col_prod_supported(int nb);
+bool col_prod_supported(int nb, int planes);
+hipError_t launch_row_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                           int out_role, int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                           hipStream_t st);
+bool row_prod_supported(int nb, int planes);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
@@ -38,13 +42,13 @@ hipError_t launch_finish(bool colmode, int form, const LayerDev* layers, const i
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
 hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
-                            hipStream_t st);
+                            int gate, hipStream_t st);
 hipError_t launch_pack(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int role_a, int role_b,
                        int cp, int which, hipStream_t st);
 hipError_t launch_chol(const LayerDev* layers, const int* ids, int n_ids, int w, int role, double tol2, int pass,
                        int slot_rows, int gate, int a2gate, int local_ok, int after_finish, hipStream_t st);
 hipError_t launch_slot_sum(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int slot_rows,
-                           int group, hipStream_t st);
+                           int group, int gate, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
                         bool small, hipStream_t st);
@@ -444,31 +448,35 @@ struct Launcher {
         // (the XCD table pays where the thin operands are a large part of what a workgroup reads: width 64)
         const int* xtab = (ctx->xstride > 0 && use_xtab && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
                               ? reinterpret_cast<const int*>(ws + ctx->off_xtab) : nullptr;
-        const bool gram32 = v2 && split_row_v2 == 1 && epi == EPI_GRAM && w > 16 && chol_gate >= -1;
+        // the same product on a matrix that is already formed (the refresh's iteration, further power steps)
+        const bool r2 = !form && p_like && n_norm > 0 && use_form_row && row_prod_supported(nb, ctx->planes);
+        const bool gram32 = (v2 || r2) && split_row_v2 == 1 && epi == EPI_GRAM && w > 16 && chol_gate >= -1;
         // the second product on row-major layers at those widths likewise
-        const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb);
-        const int* xtab_c = (ctx->xstride > 0 && use_xtab && nb >= 2 && gate < 0 && ids_norm == ids_all + ctx->n_layers)
+        const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb, ctx->planes);
+        const int* xtab_c = (ctx->xstride > 0 && use_xtab && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
                                 ? reinterpret_cast<const int*>(ws + ctx->off_xtab_c) : nullptr;
         if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, xtab_c, ctx->xstride, ctx->xtiles_c, st));
+        else if (r2) note(launch_row_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), gate, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
         else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
-        else if (!c2) note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
+        else note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
         // split reductions are completed (and the epilogue run) by a second, small launch, whose last
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
-        const bool split_n = v2 ? split_row_v2 > 1 : c2 ? split_col_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, v2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        const bool rv2 = v2 || r2;
+        const bool split_n = rv2 ? split_row_v2 > 1 : c2 ? split_col_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
+        if (split_n) note(launch_finish(!p_like, rv2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         // (an unsplit launch of that kernel writes one partial Gram matrix per 32-row block itself where the
         // factorisation is a launch of its own -- widths above 16 --, and leaves them to a small pass over the result,
         // one per 128 rows, where the apply kernel factorises for itself)
-        if (v2 && !split_n && epi == EPI_GRAM && !gram32) note(launch_thin_gram(layers, ids_norm, n_norm, blocks_row, out_role, 32 * nb, st));
+        if (rv2 && !split_n && epi == EPI_GRAM && !gram32) note(launch_thin_gram(layers, ids_norm, n_norm, blocks_row, out_role, 32 * nb, gate, st));
         // (after a split product only the layers finish_kernel leaves to it -- wide, many Gram slots -- and none at
         // widths where there are no such layers)
         if (chol_gate >= -1) {
             // (32-row slots: added up in groups of 16 side by side first, the factorisation's one workgroup per layer
             // would otherwise spend most of its time on that sum)
-            if (gram32) note(launch_slot_sum(layers, ids_norm, n_norm, max_rows, out_role, 32, 16, st));
+            if (gram32) note(launch_slot_sum(layers, ids_norm, n_norm, max_rows, out_role, 32, 16, gate, st));
             if (!split_n || w > 16) note(launch_chol(layers, ids_norm, n_norm, w, out_role, tol2, 1, gram32 ? 32 : kGramRows1, chol_gate, a2gate, small ? 1 : 0, gram32 ? 16 : (split_n ? 1 : 0), st));
             if (!split_t || w > 16) note(launch_chol(layers, ids_tr, n_tr, w, out_role, tol2, 1, kGramRows1, chol_gate, a2gate, small ? 1 : 0, split_t ? 1 : 0, st));
         }
@@ -496,7 +504,7 @@ struct Launcher {
     void orth_given(int out_role, int w, double tol2, int cp) {
         const bool small = w <= 16;
         const int blocks = (max_lenP() + 127) / 128;
-        note(launch_thin_gram(layers, ids_all, n_all, blocks, out_role, cp, st));
+        note(launch_thin_gram(layers, ids_all, n_all, blocks, out_role, cp, -1, st));
         note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 1, kGramRows1, -1, -1, small ? 1 : 0, 0, st));
         note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, -1, -1, tol2, small, st));
         if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, -1, -2, 0, 0, st));

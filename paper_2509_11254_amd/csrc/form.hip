@@ -42,6 +42,58 @@ template <int NB, int PL, bool LAZY> constexpr size_t form_lds_bytes() {
     return a + d > red ? a + d : red;
 }
 
+// The end of a row-mode product on 32-row blocks: the four waves' partial results (each over its quarter of every
+// step's reduction range) are added through LDS, and the block's 32 x cp result goes out -- as one of n_split partial
+// sums for finish_kernel, or as rows of the result, then with the block's partial Gram matrix if the launch asks for
+// it (one slot per 32 rows).
+template <int NB>
+__device__ inline void row_epilogue(unsigned char* smem, const floatx16 (&acc)[NB], const LayerDev& L, int out_role,
+                                    int epi_flags, int sp, int ob, int n_split) {
+    constexpr int cp = 32 * NB;
+    const int t = threadIdx.x;
+    const int lane = t & 63, wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int row0 = ob * FR;
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);          // [4][FR][cp + 1]
+    constexpr int RW = cp + 1;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            red[(wv * FR + 8 * (v >> 2) + 4 * lg + (v & 3)) * RW + 32 * nb + li] = acc[nb][v];
+    __syncthreads();
+    const ThinRef T = L.thin[out_role];
+    auto total = [&](int row, int col) {
+        const float* r = red + row * RW + col;
+        return (r[0] + r[FR * RW]) + (r[2 * FR * RW] + r[3 * FR * RW]);
+    };
+    if (n_split > 1) {
+        // one of n_split partial sums: [split][column][row]; finish_kernel adds them up in split order
+        PSGD_GLOBAL float* dst = as_global(L.part[SIDE_L]) + (int64_t)sp * L.rowsP * T.width + row0;
+        for (int i = t; i < FR * T.width; i += kThreads) {
+            const int row = i & (FR - 1), col = i / FR;
+            dst[(int64_t)col * L.rowsP + row] = total(row, col);
+        }
+    } else {
+        // the rows of the result; the totals also replace the first wave's slice in LDS (every entry is read and
+        // written by one thread), from where this row block's partial Gram matrix is formed if the launch asks for
+        // it: one slot per 32 rows here (epi_flags carries EPI_GRAM only where the factorisation that follows sums
+        // 32-row slots)
+        const bool gram = (epi_flags & EPI_KIND_MASK) == EPI_GRAM;
+        for (int i = t; i < FR * cp; i += kThreads) {
+            const int row = i / cp, col = i - row * cp;
+            const float v = total(row, col);
+            if (gram) red[row * RW + col] = v;
+            if (col < T.width && row0 + row < L.rows) as_global(T.ptr)[(int64_t)(row0 + row) * T.ld + col] = v;
+        }
+        if (gram) {
+            __syncthreads();
+            gram_tile_f64(red, RW, FR, T.width, L.gram + (int64_t)ob * ((T.width * (T.width + 1)) / 2));
+        }
+    }
+}
+
 // GBF: the gradients are bf16 (else fp32); ONEW: one worker (no loop over further gradient buffers);
 // LAZY: the residual of the previous compress step is applied on the way in.
 template <int NB, int PL, bool GBF, bool ONEW, bool LAZY>
@@ -377,45 +429,164 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         }
         if (ABUF == 1) __syncthreads();
     }
-    // ---- add the four waves' partial results
-    __syncthreads();
-    float* red = reinterpret_cast<float*>(smem);          // [4][FR][cp + 1]
-    constexpr int RW = cp + 1;
+    row_epilogue<NB>(smem, acc, L, out_role, epi_flags, sp, ob, n_split);
+}
+
+// ---------------------------------------------------------------------------------------------------------------
+// The same product without the forming:  thin[out_role] = S X  for a matrix that is already in S (Z = M Y of the
+// refresh's iteration).  Reads S only; same geometry as form_row_kernel, two tiles in flight as in col_prod_kernel
+// below (see there for the issue order).
+// ---------------------------------------------------------------------------------------------------------------
+template <int NB, int PL> constexpr int rowprod_abuf() { return PL == 2 ? 2 : 1; }
+template <int NB, int PL> constexpr size_t rowprod_lds_bytes() {
+    const size_t a = (size_t)rowprod_abuf<NB, PL>() * PL * FR * FLD * sizeof(bf16_t);
+    const size_t red = (size_t)4 * FR * (32 * NB + 1) * sizeof(float);
+    return a > red ? a : red;
+}
+
+template <int NB, int PL>
+__global__ __launch_bounds__(kThreads, 2) void row_prod_kernel(const LayerDev* __restrict__ layers,
+                                                                const int* __restrict__ ids, int out_role,
+                                                                int epi_flags, int gate, int nt_s,
+                                                                const int* __restrict__ xtab, int xstride) {
+    constexpr int ABUF = rowprod_abuf<NB, PL>();
+    constexpr int APL = FR * FLD;
+    int layer_pos = blockIdx.y, tile = blockIdx.x;
+    if (xtab) {
+        const int x = blockIdx.x & 7, s = blockIdx.x >> 3;
+        const int* pre = xtab + x * xstride;
+        const int n_mine = pre[xstride - 1];
+        if (n_mine == 0 || s >= pre[n_mine]) return;
+        int j = 0;
+        while (s >= pre[j + 1]) ++j;
+        layer_pos = xtab[(8 + x) * xstride + j];
+        tile = s - pre[j];
+    }
+    const LayerDev& L = layers[ids[layer_pos]];
+    if (!gate_open(L, gate)) return;
+    const int n_ob = L.rowsP / FR;
+    const int n_split = L.split_row_v2;
+    if (tile >= n_ob * n_split) return;
+    const int sp = tile % n_split, ob = tile / n_split;
+    const int row0 = ob * FR;
+    const int n_chunks = (L.cols + FK - 1) / FK;
+    const int cps = (n_chunks + n_split - 1) / n_split;
+    const int ch0 = sp * cps;
+    const int n_loc = row0 < L.rows ? max(min(n_chunks, ch0 + cps) - ch0, 0) : 0;
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    bf16_t* a_pl = reinterpret_cast<bf16_t*>(smem);                              // ABUF x PL planes of [FR][FLD]
+    const int t = threadIdx.x;
+    const int lane = t & 63, wv = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int li = lane & 31, lg = lane >> 5;
+    const int64_t ld = L.ld;
+    const int colsP = L.colsP;
+    const PSGD_GLOBAL float* S = as_global(L.S);
+    const int64_t wave_off = (int64_t)(row0 + wv) * ld;
+    const int64_t ustep = 4 * ld;
+    const unsigned lane_e = 16u * (unsigned)lane, lane_f = 16u * (unsigned)lane;
+    // this thread's pieces of a tile: piece u at row row0 + 4 u + wv, columns ch * FK + 4 lane .. + 3
+    auto tile_full = [&](int ch) { return row0 + FR <= L.rows && ch * FK + FK <= L.cols; };
+    auto load_tile = [&](int ch, floatx4 (&x)[8]) {
+        const PSGD_GLOBAL float* ep = S + wave_off + (int64_t)ch * FK;
+        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(ep + u * ustep) + lane_e); };
+        if (tile_full(ch)) {
+            if (nt_s) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(at(u));
+            } else {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) x[u] = *at(u);
+            }
+        } else {
+            const int c = ch * FK + 4 * lane;
+            const bool k0 = c < L.cols, k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                x[u] = floatx4{0.f, 0.f, 0.f, 0.f};
+                if (k0 && row0 + 4 * u + wv < L.rows) {
+                    const floatx4 v = *at(u);                       // (the padding up to ld may be read, not used)
+                    x[u] = floatx4{v.x, k1 ? v.y : 0.f, k2 ? v.z : 0.f, k3 ? v.w : 0.f};
+                }
+            }
+        }
+    };
+    int rot = 0;
+    if (n_loc > 0) rot = xtab ? (ob + layer_pos) % n_loc : ((ob & 7) * (n_loc >> 3) + 2 * (ob >> 3) + layer_pos) % n_loc;
+    auto chunk_at = [&](int it) { const int c = it + rot; return ch0 + (c >= n_loc ? c - n_loc : c); };
+    const PackRef XK = L.pack[SIDE_W];
+    bf16x8 bfrag[4][NB][PL];
+    auto load_b = [&](int ch) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const int kg = min(ch * (FK / 16) + 4 * wv + ks, colsP / 16 - 1);     // (past the end M is zero)
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int k = 0; k < PL; ++k)
+                    bfrag[ks][nb][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
+                        reinterpret_cast<const PSGD_GLOBAL char*>(as_global(XK.t[k]) + ((int64_t)kg * NB + nb) * 512) + lane_f);
+        }
+    };
+    floatx16 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            red[(wv * FR + 8 * (v >> 2) + 4 * lg + (v & 3)) * RW + 32 * nb + li] = acc[nb][v];
-    __syncthreads();
-    const ThinRef T = L.thin[out_role];
-    auto total = [&](int row, int col) {
-        const float* r = red + row * RW + col;
-        return (r[0] + r[FR * RW]) + (r[2 * FR * RW] + r[3 * FR * RW]);
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+    // (two tiles in flight where the registers hold them beside the fragments, else one)
+    constexpr int AHEAD = (PL == 2 || NB == 1) ? 2 : 1;
+    floatx4 xa[8], xb[AHEAD == 2 ? 8 : 1];
+    if (n_loc > 0) {
+        load_tile(chunk_at(0), xa);
+        load_b(chunk_at(0));
+        if constexpr (AHEAD == 2) { if (n_loc > 1) load_tile(chunk_at(1), xb); }
+    }
+    auto step = [&](int it, floatx4 (&x)[8]) {
+        bf16_t* a_cur = a_pl + (ABUF == 2 ? (it & 1) * PL * APL : 0);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            bf16x4 o[PL];
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                bf16_t pq[PL];
+                split_planes<PL>(x[u][q], pq);
+#pragma unroll
+                for (int k = 0; k < PL; ++k) o[k][q] = pq[k];
+            }
+#pragma unroll
+            for (int k = 0; k < PL; ++k) *reinterpret_cast<bf16x4*>(a_cur + k * APL + (4 * u + wv) * FLD + 4 * lane) = o[k];
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 av[PL];
+#pragma unroll
+            for (int k = 0; k < PL; ++k)
+                av[k] = *reinterpret_cast<const bf16x8*>(a_cur + k * APL + li * FLD + 64 * wv + 16 * ks + 8 * lg);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int sum = 2 * (PL - 1); sum >= 0; --sum)
+#pragma unroll
+                    for (int ka = 0; ka < PL; ++ka) {
+                        const int kb = sum - ka;
+                        if (kb >= 0 && kb < PL && form_keep_term<PL>(ka, kb))
+                            acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bfrag[ks][nb][kb], acc[nb], 0, 0, 0);
+                    }
+        }
+        if (it + 1 < n_loc) load_b(chunk_at(it + 1));
+        if (it + AHEAD < n_loc) load_tile(chunk_at(it + AHEAD), x);
+        if (ABUF == 1) __syncthreads();
     };
-    if (n_split > 1) {
-        // one of n_split partial sums: [split][column][row]; finish_kernel adds them up in split order
-        PSGD_GLOBAL float* dst = as_global(L.part[SIDE_L]) + (int64_t)sp * L.rowsP * T.width + row0;
-        for (int i = t; i < FR * T.width; i += kThreads) {
-            const int row = i & (FR - 1), col = i / FR;
-            dst[(int64_t)col * L.rowsP + row] = total(row, col);
+    if constexpr (AHEAD == 2) {
+        for (int it = 0; it < n_loc; it += 2) {
+            step(it, xa);
+            if (it + 1 < n_loc) step(it + 1, xb);
         }
     } else {
-        // the rows of the result; the totals also replace the first wave's slice in LDS (every entry is read and
-        // written by one thread), from where this row block's partial Gram matrix is formed if the launch asks for
-        // it: one slot per 32 rows here (epi_flags carries EPI_GRAM only where the factorisation that follows sums
-        // 32-row slots)
-        const bool gram = (epi_flags & EPI_KIND_MASK) == EPI_GRAM;
-        for (int i = t; i < FR * cp; i += kThreads) {
-            const int row = i / cp, col = i - row * cp;
-            const float v = total(row, col);
-            if (gram) red[row * RW + col] = v;
-            if (col < T.width && row0 + row < L.rows) as_global(T.ptr)[(int64_t)(row0 + row) * T.ld + col] = v;
-        }
-        if (gram) {
-            __syncthreads();
-            gram_tile_f64(red, RW, FR, T.width, L.gram + (int64_t)ob * ((T.width * (T.width + 1)) / 2));
-        }
+        for (int it = 0; it < n_loc; ++it) step(it, xa);
     }
+    row_epilogue<NB>(smem, acc, L, out_role, epi_flags, sp, ob, n_split);
 }
 
 // ---------------------------------------------------------------------------------------------------------------
@@ -531,12 +702,14 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
     // on its way in the other, and requests the tile of step it + 2 into the buffer it has just emptied -- after its
     // MFMA phase and after the fragments of step it + 1 (the wait counter is in issue order: what the next MFMA phase
     // waits for must be older than the tile that is to stay in flight through it).
-    floatx4 xa[8], xb[8];
+    // (width 96: one tile in flight, the registers do not hold two beside the accumulators)
+    constexpr int AHEAD = NB <= 2 ? 2 : 1;
+    floatx4 xa[8], xb[AHEAD == 2 ? 8 : 1];
     bf16x8 bfrag[2][NB][PL];
     if (n_loc > 0) {
         load_tile(ch0, xa);
         load_b(ch0, bfrag);
-        if (n_loc > 1) load_tile(ch0 + 1, xb);
+        if constexpr (AHEAD == 2) { if (n_loc > 1) load_tile(ch0 + 1, xb); }
     }
     const int wsw = (lane >> 2) & 3;                  // write side: bits 4, 5 of this thread's columns 4 lane + q
     auto step = [&](int it, floatx4 (&x)[8]) {
@@ -577,12 +750,16 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
                         }
             }
         if (it + 1 < n_loc) load_b(ch0 + it + 1, bfrag);
-        if (it + 2 < n_loc) load_tile(ch0 + it + 2, x);
+        if (it + AHEAD < n_loc) load_tile(ch0 + it + AHEAD, x);
         __syncthreads();
     };
-    for (int it = 0; it < n_loc; it += 2) {
-        step(it, xa);
-        if (it + 1 < n_loc) step(it + 1, xb);
+    if constexpr (AHEAD == 2) {
+        for (int it = 0; it < n_loc; it += 2) {
+            step(it, xa);
+            if (it + 1 < n_loc) step(it + 1, xb);
+        }
+    } else {
+        for (int it = 0; it < n_loc; ++it) step(it, xa);
     }
     // ---- the 256 x cp result tile goes out in two halves of 128 rows through LDS (the operand buffer is free: the
     // loop ends in a barrier); half h holds the rows of waves 2 h and 2 h + 1
@@ -640,7 +817,8 @@ static hipError_t launch_colprod_nb(const LayerDev* layers, const int* ids, int 
     return hipGetLastError();
 }
 
-bool col_prod_supported(int nb) { return nb == 1 || nb == 2; }
+// (width 96 with three planes: the fragments of a step and two tiles do not fit the registers)
+bool col_prod_supported(int nb, int planes) { return nb == 1 || nb == 2 || (nb == 3 && planes == 2); }
 
 // max_tiles: max over the layers of ceil(padded cols / 256) * split_col_v2; nt_s: read S with the non-temporal hint
 hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
@@ -651,6 +829,41 @@ hipError_t launch_col_prod(int nb, int planes, const LayerDev* layers, const int
                                     : launch_colprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
     if (nb == 2) return planes == 2 ? launch_colprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
                                     : launch_colprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
+    if (nb == 3 && planes == 2) return launch_colprod_nb<3, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
+    return hipErrorInvalidValue;
+}
+
+template <int NB, int PL>
+static hipError_t launch_rowprod_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, int out_role,
+                                    int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                                    hipStream_t st) {
+    dim3 grid(max_tiles, n_ids), block(kThreads);
+    if (xtab) grid = dim3(8 * xtiles, 1);
+    auto kfn = row_prod_kernel<NB, PL>;
+    const size_t lds = rowprod_lds_bytes<NB, PL>();
+    if (lds > 48 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+    }
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, gate, nt_s, xtab, xstride);
+    return hipGetLastError();
+}
+
+// (width 96 is built but not chosen: every 32 rows fetch the thin operand again, 12 bytes from L2 per 4 bytes of S
+// with two planes, and the pass is L2-bound: 7.1 ms on the 7B-shaped set against 6.4 for prod_kernel's 128-row tiles)
+bool row_prod_supported(int nb, int planes) { (void)planes; return nb == 1 || nb == 2; }
+
+// thin[out_role] = S X on row-major layers, S read only.  max_tiles, xtab, xstride, xtiles as for launch_form_row;
+// gate: iteration gate of the refresh (-1: none)
+hipError_t launch_row_prod(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
+                           int out_role, int epi, int gate, int nt_s, const int* xtab, int xstride, int xtiles,
+                           hipStream_t st) {
+    if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
+    if (nb == 1) return planes == 2 ? launch_rowprod_nb<1, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
+                                    : launch_rowprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
+    if (nb == 2) return planes == 2 ? launch_rowprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
+                                    : launch_rowprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
+    if (nb == 3 && planes == 2) return launch_rowprod_nb<3, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
     return hipErrorInvalidValue;
 }
 
@@ -685,9 +898,10 @@ static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev*
 // Variants this kernel is built for: the thin operand fragments of a whole step live in registers next to the tile,
 // which the wider and the several-fp32-worker variants cannot afford without spilling.
 bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy) {
-    if (nb < 1 || nb > 2) return false;
+    if (nb < 1 || nb > 3) return false;
     const bool f32_multi = !gbf && !onew;
     if (nb == 1) return true;
+    if (nb == 3) return planes == 2 && gbf && onew && !lazy;
     if (planes == 2) return !(lazy && f32_multi);
     return !lazy && !f32_multi;
 }
@@ -705,6 +919,16 @@ hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, c
                                     : launch_form_nb<1, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st);
     if (nb == 2) return planes == 2 ? launch_form_nb<2, 2>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st)
                                     : launch_form_nb<2, 3>(gbf, onew, lazy, layers, ids, n_ids, max_tiles, out_role, epi, nt_m, xtab, xstride, xtiles, st);
+    if (nb == 3 && planes == 2 && gbf && onew && !lazy) {
+        dim3 grid(max_tiles, n_ids), block(kThreads);
+        if (xtab) grid = dim3(8 * xtiles, 1);
+        auto kfn = form_row_kernel<3, 2, true, true, false>;
+        const size_t lds = form_lds_bytes<3, 2, false>();
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, nt_m, xtab, xstride);
+        return hipGetLastError();
+    }
     return hipErrorInvalidValue;
 }
 

@@ -651,8 +651,8 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
     const int epi = epi_flags & EPI_KIND_MASK;
     const int out_side = colmode ? SIDE_W : SIDE_L;
     const int out_len = colmode ? L.cols : L.rows;
-    // form: 0 = a product that reads M, 1 = a forming pass of prod_kernel, 2 = the forming pass on 32 x 256 tiles,
-    // 3 = the column-mode product on 32 x 256 tiles
+    // form (whose partial sums): 0 = a product of prod_kernel that reads M, 1 = a forming pass of prod_kernel,
+    // 2 = a row-mode pass on 32 x 256 tiles (form_row_kernel, row_prod_kernel), 3 = col_prod_kernel
     const int n_split = form == 2 ? L.split_row_v2 : form == 3 ? L.split_col_v2
                         : form ? (colmode ? L.split_col_f : L.split_row_f) : (colmode ? L.split_col : L.split_row);
     const int ob = blockIdx.x;
@@ -736,8 +736,10 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
 // data-parallel step, handed back by the caller): one workgroup per 128 rows fills the slot a product's epilogue
 // would have filled.
 __global__ __launch_bounds__(kThreads) void thin_gram_kernel(const LayerDev* __restrict__ layers,
-                                                             const int* __restrict__ ids, int role, int cp) {
+                                                             const int* __restrict__ ids, int role, int cp,
+                                                             int gate) {
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
     const int len = side_len(L, side_of_role(L.transposed, role));
     const int ob = blockIdx.x;
     if (ob * BT >= len) return;
@@ -757,8 +759,9 @@ __global__ __launch_bounds__(kThreads) void thin_gram_kernel(const LayerDev* __r
     gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * ((w * (w + 1)) / 2));
 }
 
+// gate: iteration gate of the refresh (-1: none)
 hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, int max_blocks, int role, int cp,
-                            hipStream_t st) {
+                            int gate, hipStream_t st) {
     if (n_ids <= 0 || max_blocks <= 0) return hipSuccess;
     dim3 grid(max_blocks, n_ids), block(kThreads);
     const size_t lds = (size_t)BT * (cp + 1) * sizeof(float);
@@ -767,7 +770,7 @@ hipError_t launch_thin_gram(const LayerDev* layers, const int* ids, int n_ids, i
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(thin_gram_kernel, grid, block, lds, st, layers, ids, role, cp);
+    hipLaunchKernelGGL(thin_gram_kernel, grid, block, lds, st, layers, ids, role, cp, gate);
     return hipGetLastError();
 }
 

@@ -148,9 +148,10 @@ __global__ __launch_bounds__(NT) void chol_kernel(const LayerDev* __restrict__ l
 // factorisation's one workgroup per layer then adds up one matrix per group.
 // --------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void slot_sum_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
-                                                            int role, int slot_rows, int group) {
+                                                            int role, int slot_rows, int group, int gate) {
     typedef double doublex2 __attribute__((ext_vector_type(2)));
     const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;       // (the slots of a layer whose iteration is over hold what its Ritz step needs)
     const int len = side_len(L, side_of_role(L.transposed, role));
     const int n_slots = (len + slot_rows - 1) / slot_rows;
     const int first = blockIdx.x * group;
@@ -180,12 +181,12 @@ __global__ __launch_bounds__(kThreads) void slot_sum_kernel(const LayerDev* __re
     }
 }
 
-// group <= 16
+// group <= 16; gate: iteration gate of the refresh (-1: none)
 hipError_t launch_slot_sum(const LayerDev* layers, const int* ids, int n_ids, int max_len, int role, int slot_rows,
-                           int group, hipStream_t st) {
+                           int group, int gate, hipStream_t st) {
     if (n_ids <= 0 || group < 2 || group > 16) return n_ids <= 0 ? hipSuccess : hipErrorInvalidValue;
     const int groups = ((max_len + slot_rows - 1) / slot_rows + group - 1) / group;
-    hipLaunchKernelGGL(slot_sum_kernel, dim3(groups, n_ids), dim3(kThreads), 0, st, layers, ids, role, slot_rows, group);
+    hipLaunchKernelGGL(slot_sum_kernel, dim3(groups, n_ids), dim3(kThreads), 0, st, layers, ids, role, slot_rows, group, gate);
     return hipGetLastError();
 }
 
