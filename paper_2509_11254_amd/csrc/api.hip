@@ -51,7 +51,7 @@ hipError_t launch_slot_sum(const LayerDev* layers, const int* ids, int n_ids, in
                            int group, int gate, hipStream_t st);
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
-                        bool small, hipStream_t st);
+                        bool small, int which, hipStream_t st);
 hipError_t launch_init_block(const LayerDev* layers, const int* ids, int n_ids, int max_len, int w, int dst_role,
                              int src_role, int warm, uint32_t seed, hipStream_t st);
 hipError_t launch_jacobi(const LayerDev* layers, const int* ids, int n_ids, int w, int role, float* sigma_out,
@@ -492,12 +492,14 @@ struct Launcher {
         // narrow blocks everywhere: the apply kernel factorises per workgroup and hands over to the second
         // factorisation itself; otherwise the second factorisation is a launch of its own
         const bool small = w <= 16;
+        // (inside the iteration only products read the result: no row-major operand copies)
+        const int wh = gate >= 0 ? PACK_TRANSPOSED : (PACK_ROWMAJOR | PACK_TRANSPOSED);
         prod(p_like, form, nb, out_role, EPI_GRAM, g, a2, tol2, w, small);
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, small, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, small, wh, st));
         if (a2 != -2) {
             const int g2 = a2 == -1 ? g : a2;
             if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, g2, -2, 0, 0, st));
-            note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, g2, a2, tol2, small, st));
+            note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, g2, a2, tol2, small, wh, st));
         }
     }
     // the same CholeskyQR2 on a thin[out_role] that the caller supplied: its Gram slots come from a pass of their own
@@ -506,9 +508,9 @@ struct Launcher {
         const int blocks = (max_lenP() + 127) / 128;
         note(launch_thin_gram(layers, ids_all, n_all, blocks, out_role, cp, -1, st));
         note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 1, kGramRows1, -1, -1, small ? 1 : 0, 0, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, -1, -1, tol2, small, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, -1, -1, tol2, small, 3, st));
         if (!small) note(launch_chol(layers, ids_all, n_all, w, out_role, tol2, 2, kGramRows2, -1, -2, 0, 0, st));
-        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, -1, -1, tol2, small, st));
+        note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS2, cp, -1, -1, tol2, small, 3, st));
     }
     void residual(int nb, bool form = false) {
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
@@ -604,9 +606,9 @@ void refresh_sequence(psgd_ctx* ctx, Launcher& L, bool form_first, bool warm, fl
     // Rayleigh-Ritz on H = Y^T Y (its partial Gram matrices are the last product's)
     L.note(launch_jacobi(L.layers, L.ids_all, L.n_all, wz, ROLE_ZQ, sigma_out, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZP, ROLE_P, APPLY_RITZ,
-                        final_cp, -1, -2, 0.0, false, L.st));
+                        final_cp, -1, -2, 0.0, false, 3, L.st));
     L.note(launch_apply(L.layers, L.ids_all, L.n_all, L.max_lenP(), wz, ctx->rmax, ROLE_ZQ, ROLE_Q, APPLY_RITZ,
-                        final_cp, -1, -2, 0.0, false, L.st));
+                        final_cp, -1, -2, 0.0, false, 3, L.st));
     L.prof_mute = false;
 }
 

@@ -237,7 +237,8 @@ __host__ __device__ inline size_t apply_main_lds(int w_in, int w_out, int cp) {
 template <bool SMALL>
 __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restrict__ layers,
                                                          const int* __restrict__ ids, int src_role, int dst_role,
-                                                         int mode, int cp, int gate, int a2gate, double tol2) {
+                                                         int mode, int cp, int gate, int a2gate, double tol2,
+                                                         int which) {
     __shared__ int s_last;
     __shared__ int s_need2;
     const LayerDev& L = layers[ids[blockIdx.y]];
@@ -391,15 +392,16 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
             if (last_to_arrive(&L.status[7], n_wg, &s_last)) chol_body<true>(L, dst_role, tol2, 2, kGramRows2, false, smem, L.tmat);
         }
     } else if (do_pack) {
-        write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP);
+        write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which);
     }
 }
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
 // small: every layer of the launch is narrow (w_in <= 16) and the chain runs the per-workgroup factorisation
+// which: operand copies to leave when cp > 0 (1 = row-major, 2 = transposed, 3 = both)
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
-                        bool small, hipStream_t st) {
+                        bool small, int which, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
     // w_in / w_out are upper bounds over the layers: sizes that grow with them cover every layer
@@ -415,7 +417,7 @@ hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int m
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate, a2gate, tol2);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, src_role, dst_role, mode, cp, gate, a2gate, tol2, which);
     return hipGetLastError();
 }
 
