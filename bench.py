@@ -74,6 +74,7 @@ def run_ceilings():
     lib.ceil_flat_rmw_nt.argtypes = [vp, C.c_int, vp, C.c_size_t]
     lib.ceil_tile_write.argtypes = [vp, C.c_int, vp, C.c_int, C.c_int, C.c_int]
     lib.ceil_form_tile.argtypes = [vp, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int]
+    lib.ceil_walk_32x256.argtypes = [vp, C.c_int, vp, vp, C.c_int, C.c_int, C.c_int, vp]
     st = torch.cuda.current_stream().cuda_stream
     sink = torch.zeros(16, device="cuda")
 
@@ -134,6 +135,10 @@ def run_ceilings():
     for rot, name in ((0, "form_tile_bf16_plus_E_in_place_rowmode_in_step"), (1, "form_tile_bf16_plus_E_in_place_rowmode_rotated")):
         ms = timed(lambda i: lib.ceil_form_tile(st, rot, gtab.data_ptr(), tab.data_ptr(), len(gmats), 4096, 4096), 5)
         out[name] = len(gmats) * 4096 * 4096 * 10 / ms / 1e6
+    for which, name, bpe in ((0, "walk_32x256_bf16_plus_E_in_place_rotated", 10), (1, "walk_32x256_bf16_plus_E_in_place_rotated_nt_store", 10),
+                             (2, "walk_256cols_down_32rows_read_only", 4), (3, "walk_256cols_down_32rows_read_only_2_in_flight", 4)):
+        ms = timed(lambda i: lib.ceil_walk_32x256(st, which, gtab.data_ptr(), tab.data_ptr(), len(gmats), 4096, 4096, sink.data_ptr()), 5)
+        out[name] = len(gmats) * 4096 * 4096 * bpe / ms / 1e6
     print(json.dumps({"metric": "measured HBM ceilings of plain streaming kernels", "unit": "GB/s",
                       "peak_nominal": HBM_PEAK_GBPS, "values": {k: round(v, 1) for k, v in out.items()}}))
 
@@ -379,7 +384,8 @@ def run_workload(name, args, primary):
     per_launch_ms = s1_ms / max(1, s1_n)
     s1_bytes = comp.kernel_bytes("sweep1")
     achieved = s1_bytes / (per_launch_ms * 1e-3) / 1e9 if per_launch_ms > 0 else 0.0
-    traffic, traffic_src = read_traffic(name)
+    # (the counter files were taken on the default form of each workload: deferred residual where it applies)
+    traffic, traffic_src = read_traffic(name) if lazy == (name in ("c3", "c4")) else (None, None)
     kernels = {}
     for tag, d in per_kernel.items():
         for kname, (ms, n) in d.items():

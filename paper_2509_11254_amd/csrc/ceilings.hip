@@ -190,6 +190,59 @@ __global__ __launch_bounds__(kT, 2) void form_tile(const uint16_t* const* gs, fl
         for (int u = 0; u < 8; ++u) { sv[u] = sn[u]; gv[u] = gn[u]; }
     }
 }
+// The walks of the kernels built on 32 x 256 tiles, without the products: every load and store instruction of a
+// wavefront covers 1 KB of one row.
+//   MODE 0 (form_row_kernel, one bf16 worker): a workgroup owns 32 rows and walks them 256 columns at a time,
+//          S <- widen(G) + S in place, next step requested before the current one is consumed; every row block starts
+//          at a step of its own.  NTS: non-temporal stores.
+//   MODE 1 (col_prod_kernel): a workgroup owns 256 columns and walks down the rows 32 at a time, read only, DEPTH
+//          steps in flight.
+template <int MODE, int NTS, int DEPTH>
+__global__ __launch_bounds__(kT, 2) void walk_32x256(const uint16_t* const* gs, float* const* ss, int rows, int cols, float* sink) {
+    const GLOBAL_AS uint16_t* g = MODE == 0 ? (const GLOBAL_AS uint16_t*)gs[blockIdx.y] : nullptr;
+    GLOBAL_AS float* s = (GLOBAL_AS float*)ss[blockIdx.y];
+    const int t = threadIdx.x, lane = t & 63, wv = t >> 6, ob = blockIdx.x;
+    const int nstrip = MODE == 0 ? rows / 32 : cols / 256;
+    if (ob >= nstrip) return;
+    const int nch = MODE == 0 ? cols / 256 : rows / 32;
+    const int rot = MODE == 0 ? ((ob & 7) * (nch >> 3) + 2 * (ob >> 3) + (int)blockIdx.y) % nch : 0;
+    auto off_of = [&](int it, int u) -> size_t {
+        int ch = it + rot; if (ch >= nch) ch -= nch;
+        const int row = (MODE == 0 ? ob * 32 + 4 * u + wv : ch * 32 + 8 * wv + u);
+        const int col = (MODE == 0 ? ch * 256 : ob * 256) + 4 * lane;
+        return (size_t)row * cols + col;
+    };
+    floatx4 sv[DEPTH + 1][8];
+    uintx2 gv[DEPTH + 1][8];
+    auto ld = [&](int it, int slot) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            sv[slot][u] = __builtin_nontemporal_load((const GLOBAL_AS floatx4*)(s + off_of(it, u)));
+            if (MODE == 0) gv[slot][u] = __builtin_nontemporal_load((const GLOBAL_AS uintx2*)(g + off_of(it, u)));
+        }
+    };
+    floatx4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int d = 0; d < DEPTH; ++d) if (d < nch) ld(d, d);
+    for (int it0 = 0; it0 < nch; it0 += DEPTH + 1) {
+#pragma unroll
+        for (int k = 0; k <= DEPTH; ++k) {
+            const int it = it0 + k;
+            if (it >= nch) break;
+            if (it + DEPTH < nch) ld(it + DEPTH, (k + DEPTH) % (DEPTH + 1));
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (MODE == 1) { acc += sv[k][u]; continue; }
+                const uintx2 b = gv[k][u];
+                const floatx4 w = {__uint_as_float(b.x << 16), __uint_as_float(b.x & 0xffff0000u), __uint_as_float(b.y << 16), __uint_as_float(b.y & 0xffff0000u)};
+                const floatx4 o = w + sv[k][u];
+                if (NTS) __builtin_nontemporal_store(o, (GLOBAL_AS floatx4*)(s + off_of(it, u)));
+                else *(GLOBAL_AS floatx4*)(s + off_of(it, u)) = o;
+            }
+        }
+    }
+    if (MODE == 1 && acc.x + acc.y + acc.z + acc.w == 12345.678f) sink[0] = acc.x;
+}
 }  // namespace
 
 // All pointers are device pointers; n = number of floats (multiple of 4); returns the HIP error code.
@@ -248,5 +301,20 @@ extern "C" int ceil_form_tile(void* stream, int rot, const void* const* gs, cons
     dim3 grid(rows / 128, nmat);
     if (rot) hipLaunchKernelGGL(form_tile<1>, grid, dim3(kT), 0, (hipStream_t)stream, (const uint16_t* const*)gs, (float* const*)ss, rows, cols);
     else hipLaunchKernelGGL(form_tile<0>, grid, dim3(kT), 0, (hipStream_t)stream, (const uint16_t* const*)gs, (float* const*)ss, rows, cols);
+    return (int)hipGetLastError();
+}
+// which: 0 = form walk, plain stores; 1 = form walk, non-temporal stores; 2 = read-only walk down the rows, one step in
+// flight; 3 = two steps in flight.  gs (which < 2), ss: device arrays of nmat device pointers to bf16 / fp32 matrices
+// rows x cols (rows multiple of 32, cols of 256)
+extern "C" int ceil_walk_32x256(void* stream, int which, const void* const* gs, const void* const* ss, int nmat, int rows,
+                                int cols, void* sink) {
+    if (rows % 32 || cols % 256 || nmat < 1 || which < 0 || which > 3) return (int)hipErrorInvalidValue;
+    const uint16_t* const* g = (const uint16_t* const*)gs;
+    float* const* s = (float* const*)ss;
+    hipStream_t st = (hipStream_t)stream;
+    if (which == 0) hipLaunchKernelGGL((walk_32x256<0, 0, 1>), dim3(rows / 32, nmat), dim3(kT), 0, st, g, s, rows, cols, (float*)sink);
+    else if (which == 1) hipLaunchKernelGGL((walk_32x256<0, 1, 1>), dim3(rows / 32, nmat), dim3(kT), 0, st, g, s, rows, cols, (float*)sink);
+    else if (which == 2) hipLaunchKernelGGL((walk_32x256<1, 0, 1>), dim3(cols / 256, nmat), dim3(kT), 0, st, g, s, rows, cols, (float*)sink);
+    else hipLaunchKernelGGL((walk_32x256<1, 0, 2>), dim3(cols / 256, nmat), dim3(kT), 0, st, g, s, rows, cols, (float*)sink);
     return (int)hipGetLastError();
 }
