@@ -139,10 +139,15 @@ __device__ inline void split_planes(float x, bf16_t (&p)[PL]) {
     }
 }
 
-// v / d and v % d for the small divisors that occur as cp/8 or nrows/8 (4..24 in steps of 4): constant
+// v / d and v % d for the small divisors that occur as cp/32, cp/8 or nrows/8 (1..6; 4..24 in steps of 4): constant
 // divisors compile to a multiply and a shift instead of the long generic division sequence.
 __device__ inline void divmod_small(int v, int d, int& q, int& r) {
     switch (d) {
+        case 1: q = v; break;
+        case 2: q = v / 2; break;
+        case 3: q = v / 3; break;
+        case 5: q = v / 5; break;
+        case 6: q = v / 6; break;
         case 4: q = v / 4; break;
         case 8: q = v / 8; break;
         case 12: q = v / 12; break;
@@ -155,7 +160,7 @@ __device__ inline void divmod_small(int v, int d, int& q, int& r) {
 }
 
 // Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
-// nrows a multiple of 8); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
+// nrows and row0 multiples of 16); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
 // which: 1 = the row-major copies only, 2 = the transposed ones only, 3 = both.
 __device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
                                    int nrows, int lenP, int which = 3) {
@@ -177,10 +182,13 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         for (int k = 0; k < kMaxPlanes; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.n[k]) + off) = o[k];
     }
+    // fragment-order copy: the tile's rows are (nrows / 16) * (cp / 32) whole fragments, one run of consecutive memory
+    // per plane; thread v writes the v-th 16-byte piece of that run (row0 and nrows are multiples of 16)
     for (int v = t; (which & 2) && v < cp * (nrows / 8); v += kThreads) {
-        int c, g8;
-        divmod_small(v, nrows / 8, c, g8);
-        const int ib = 8 * g8;
+        const int ln = v & 63, frag = v >> 6;
+        int k16, nb;
+        divmod_small(frag, cp >> 5, k16, nb);
+        const int c = 32 * nb + (ln & 31), ib = 16 * k16 + 8 * (ln >> 5);
         bf16x8 o[kMaxPlanes];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
@@ -189,7 +197,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 #pragma unroll
             for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
         }
-        const int64_t off = pack_t_offset(row0 + ib, c, cp);      // (row0 + ib is a multiple of 8)
+        const int64_t off = pack_t_offset(row0 + ib, c, cp);      // (= 8 * (first piece of the tile + v))
 #pragma unroll
         for (int k = 0; k < kMaxPlanes; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.t[k]) + off) = o[k];

@@ -396,6 +396,223 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
     }
 }
 
+// --------------------------------------------------------------------------------------------
+// The same product for blocks up to 96 wide that are not `small`, as a streaming pass: at these widths the kernel above
+// spends its time on latency, not bytes -- a workgroup stages a block of tmat per 32 output columns from L2 behind
+// barriers, and its 66 KB of LDS let two workgroups run per compute unit (config 4, 1.58 M rows of width 64: 0.70 ms
+// for 1.6 GB of traffic).  Here a workgroup keeps the part of tmat it needs in LDS for its whole life -- per
+// 16-column tile of the result only the rows above the diagonal block when tmat is triangular -- and walks over
+// many 64-row tiles of its layer; the rows of the next tile are requested before the MFMA phase of the current one.
+// --------------------------------------------------------------------------------------------
+constexpr int kApplyStreamMaxWidth = 96;
+constexpr int kTmStride = 17;        // doubles per row of a 16-column tile of tmat in LDS
+
+__host__ __device__ inline int apply_tm_rows(int ct, int kpad, bool upper) {
+    const int k = 16 * (ct + 1);
+    return (upper && k < kpad) ? k : kpad;
+}
+// kp16 > 0: the variant with tmat in registers (reduction length padded to 16 kp16, no tmat in LDS)
+__host__ __device__ inline size_t apply_stream_lds(int w_in, int w_out, int cp, bool upper, int kp16) {
+    const int kpad = kp16 > 0 ? 16 * kp16 : ((w_in + 3) & ~3), n_ct = (w_out + 15) / 16;
+    size_t rows = 0;
+    for (int ct = 0; ct < n_ct && kp16 == 0; ++ct) rows += (size_t)apply_tm_rows(ct, kpad, upper);
+    const int ow = (cp > 16 * n_ct ? cp : 16 * n_ct) + 1;
+    return rows * kTmStride * sizeof(double) + (size_t)kGramRows2 * (kpad + 1 + ow) * sizeof(float);
+}
+
+// KP16 > 0: for a triangular tmat of width <= 16 KP16 the wave's fragments of it (tile ct: 4 (ct + 1) steps of the
+// reduction) stay in registers for the workgroup's whole life and the MFMA phase reads nothing but them and the rows:
+// with the fragments in LDS every MFMA waits on two LDS reads, and the phase ran at a third of the matrix cores' rate.
+// KP16 = 0: fragments from LDS (a full tmat, the Ritz step, or widths whose fragments do not fit the registers).
+template <int KP16>
+__global__ __launch_bounds__(kThreads) void apply_stream_kernel(const LayerDev* __restrict__ layers,
+                                                                const int* __restrict__ ids, int src_role, int dst_role,
+                                                                int mode, int cp, int gate, int w_out_max, int which) {
+    const LayerDev& L = layers[ids[blockIdx.y]];
+    if (!gate_open(L, gate)) return;
+    const int need2 = L.status[1];
+    if (mode == APPLY_PASS2 && !need2) return;
+    const bool do_gram = (mode == APPLY_PASS1) && need2;
+    const bool do_pack = !do_gram && cp > 0;
+    const int side = side_of_role(L.transposed, src_role);
+    const int len = side_len(L, side), lenP = side_lenP(L, side);
+    const int n_tiles = ((do_pack ? lenP : len) + kGramRows2 - 1) / kGramRows2;
+    if ((int)blockIdx.x >= n_tiles) return;
+    const ThinRef X = L.thin[src_role];
+    const ThinRef Y = L.thin[dst_role];
+    const int w_in = X.width, w_out = Y.width;
+    const bool upper = mode != APPLY_RITZ;
+    const int kpad = KP16 > 0 ? 16 * KP16 : ((w_in + 3) & ~3);
+    const int n_ct = (w_out + 15) / 16;
+    const int n_ct_max = (w_out_max + 15) / 16;
+    const int ow = (cp > 16 * n_ct_max ? cp : 16 * n_ct_max) + 1;    // stride of the result tile (zero padded to cp)
+    const int xs = kpad + 1;
+    extern __shared__ __align__(16) unsigned char smem[];
+    double* tl = reinterpret_cast<double*>(smem);                    // tiles of tmat, tile ct: apply_tm_rows x 17
+    int tm_rows_all = 0;
+    int tm_rows[kApplyStreamMaxWidth / 16], tm_off[kApplyStreamMaxWidth / 16];     // (uniform)
+#pragma unroll
+    for (int ct = 0; ct < kApplyStreamMaxWidth / 16; ++ct) {
+        tm_rows[ct] = (KP16 == 0 && ct < n_ct) ? apply_tm_rows(ct, kpad, upper) : 0;
+        tm_off[ct] = tm_rows_all;
+        tm_rows_all += tm_rows[ct];
+    }
+    float* sx = reinterpret_cast<float*>(tl + (size_t)tm_rows_all * kTmStride);   // [64][xs]  x tile
+    float* so = sx + (size_t)kGramRows2 * xs;                                     // [64][ow]  result tile
+    const int t = threadIdx.x;
+    const int lane = t & 63, wv = t >> 6;
+    const int li = lane & 15, lk = lane >> 4;
+    // ---- tmat -> LDS (eight loads per thread in flight), zero where the matrix ends
+    {
+        const double* __restrict__ tm = L.tmat;
+        const int tcols = min(w_out, w_in);
+        int off = 0;
+        for (int ct = 0; ct < n_ct && KP16 == 0; ++ct) {
+            const int rows = apply_tm_rows(ct, kpad, upper);
+            for (int e0 = 0; e0 < rows * 16; e0 += 8 * kThreads) {
+                double tv[8];
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    const int e = e0 + d * kThreads + t;
+                    const int k = e >> 4, c = 16 * ct + (e & 15);
+                    tv[d] = (e < rows * 16 && k < w_in && c < tcols) ? tm[(int64_t)k * w_in + c] : 0.0;
+                }
+#pragma unroll
+                for (int d = 0; d < 8; ++d) {
+                    const int e = e0 + d * kThreads + t;
+                    if (e < rows * 16) tl[(off + (e >> 4)) * kTmStride + (e & 15)] = tv[d];
+                }
+            }
+            off += rows;
+        }
+        for (int e = t; e < kGramRows2 * ow; e += kThreads) so[e] = 0.f;
+    }
+    constexpr int NTB = KP16 > 0 ? 2 * KP16 * (KP16 + 1) : 1;
+    double tb[NTB];                                              // tile ct, step ks at 2 ct (ct + 1) + ks
+    if (KP16 > 0) {
+        const double* __restrict__ tm = L.tmat;
+        const int tcols = min(w_out, w_in);
+#pragma unroll
+        for (int ct = 0; ct < KP16; ++ct)
+#pragma unroll
+            for (int ks = 0; ks < 4 * (ct + 1); ++ks) {
+                const int k = 4 * ks + lk, c = 16 * ct + li;
+                tb[2 * ct * (ct + 1) + ks] = (k < w_in && c < tcols) ? tm[(int64_t)k * w_in + c] : 0.0;
+            }
+    }
+    // ---- the rows of a tile: one contiguous block of the thin matrix when ld == width, fetched with 16-byte loads
+    const bool flat_x = X.ld == w_in && (w_in & 3) == 0;
+    const bool flat_y = Y.ld == w_out && (w_out & 3) == 0;
+    const float inv_wi = 1.0f / (float)w_in, inv_wo = 1.0f / (float)w_out;
+    constexpr int XP = kApplyStreamMaxWidth / 16;          // 16-byte pieces per thread at the widest
+    floatx4 xr[XP];
+    auto load_x = [&](int tile) {
+        const int i0 = tile * kGramRows2;
+        const int n_valid = (min(len, i0 + kGramRows2) - i0) * w_in;
+        const PSGD_GLOBAL float* xp = as_global(X.ptr) + (int64_t)i0 * X.ld;
+#pragma unroll
+        for (int d = 0; d < XP; ++d) {
+            const int f = 4 * (d * kThreads + t);
+            xr[d] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (f < n_valid) xr[d] = *reinterpret_cast<const PSGD_GLOBAL floatx4*>(xp + f);
+        }
+    };
+    int tile = blockIdx.x;
+    if (flat_x) load_x(tile);
+    for (; tile < n_tiles; tile += gridDim.x) {
+        const int i0 = tile * kGramRows2;
+        // ---- x tile -> LDS (zero beyond the matrix and in the columns up to the padded reduction length)
+        if (flat_x) {
+#pragma unroll
+            for (int d = 0; d < XP; ++d) {
+                const int f = 4 * (d * kThreads + t);
+                if (f >= kGramRows2 * w_in) continue;
+                int row = (int)(((float)f + 0.5f) * inv_wi);
+                int c = f - row * w_in;
+                if (c < 0) { --row; c += w_in; } else if (c >= w_in) { ++row; c -= w_in; }
+                float* dd = sx + row * xs + c;
+                dd[0] = xr[d].x; dd[1] = xr[d].y; dd[2] = xr[d].z; dd[3] = xr[d].w;
+            }
+            if (kpad > w_in)
+                for (int e = t; e < kGramRows2 * (kpad - w_in); e += kThreads)
+                    sx[(e / (kpad - w_in)) * xs + w_in + e % (kpad - w_in)] = 0.f;        // (uniform widths: rarely)
+        } else {
+            for (int i = wv; i < kGramRows2; i += 4) {
+                const bool in = i0 + i < len;
+                const float* __restrict__ xrow = X.ptr + (int64_t)(in ? i0 + i : 0) * X.ld;
+                for (int c = lane; c < kpad; c += 64) sx[i * xs + c] = (in && c < w_in) ? xrow[c] : 0.f;
+            }
+        }
+        __syncthreads();
+        if (flat_x && tile + (int)gridDim.x < n_tiles) load_x(tile + gridDim.x);
+        // ---- wave v: rows 16 v .. 16 v + 15 of the tile (fp64 matrix cores).  All column tiles advance together along
+        // the reduction index: one read of the row operand serves them all, and their accumulators are independent
+        // chains (a tile by itself is a chain of dependent MFMAs, each behind two LDS reads).
+        if constexpr (KP16 > 0) {
+            const float* __restrict__ xa = sx + (16 * wv + li) * xs + lk;
+            double a[4 * KP16];
+#pragma unroll
+            for (int ks = 0; ks < 4 * KP16; ++ks) a[ks] = (double)xa[4 * ks];
+            doublex4 acc[KP16];
+#pragma unroll
+            for (int ct = 0; ct < KP16; ++ct) acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int ks = 0; ks < 4 * KP16; ++ks)
+#pragma unroll
+                for (int ct = ks / 4; ct < KP16; ++ct)
+                    acc[ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a[ks], tb[2 * ct * (ct + 1) + ks], acc[ct], 0, 0, 0);
+#pragma unroll
+            for (int ct = 0; ct < KP16; ++ct)
+                if (ct < n_ct) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) so[(16 * wv + 4 * v + lk) * ow + 16 * ct + li] = (float)acc[ct][v];
+                }
+        } else {
+            const float* __restrict__ xa = sx + (16 * wv + li) * xs + lk;
+            const double* __restrict__ sb = tl + lk * kTmStride + li;
+            doublex4 acc[kApplyStreamMaxWidth / 16];
+#pragma unroll
+            for (int ct = 0; ct < kApplyStreamMaxWidth / 16; ++ct) acc[ct] = doublex4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll 2
+            for (int k = 0; k < kpad; k += 4) {
+                const double a = (double)xa[k];
+#pragma unroll
+                for (int ct = 0; ct < kApplyStreamMaxWidth / 16; ++ct)
+                    if (ct < n_ct && k < tm_rows[ct])
+                        acc[ct] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, sb[(tm_off[ct] + k) * kTmStride], acc[ct], 0, 0, 0);
+            }
+#pragma unroll
+            for (int ct = 0; ct < kApplyStreamMaxWidth / 16; ++ct)
+                if (ct < n_ct) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) so[(16 * wv + 4 * v + lk) * ow + 16 * ct + li] = (float)acc[ct][v];
+                }
+        }
+        __syncthreads();
+        // ---- rows of the result
+        const int rows_valid = min(len, i0 + kGramRows2) - i0;
+        if (flat_y) {
+            const int n_valid = rows_valid * w_out;
+            PSGD_GLOBAL float* yp = as_global(Y.ptr) + (int64_t)i0 * Y.ld;
+            for (int f = 4 * t; f < n_valid; f += 4 * kThreads) {
+                int row = (int)(((float)f + 0.5f) * inv_wo);
+                int c = f - row * w_out;
+                if (c < 0) { --row; c += w_out; } else if (c >= w_out) { ++row; c -= w_out; }
+                const float* __restrict__ sr = so + row * ow + c;
+                *reinterpret_cast<PSGD_GLOBAL floatx4*>(yp + f) = floatx4{sr[0], sr[1], sr[2], sr[3]};
+            }
+        } else {
+            for (int i = wv; i < rows_valid; i += 4) {
+                float* __restrict__ yr = Y.ptr + (int64_t)(i0 + i) * Y.ld;
+                for (int c = lane; c < w_out; c += 64) yr[c] = so[i * ow + c];
+            }
+        }
+        if (do_gram) gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)tile * ((w_out * (w_out + 1)) / 2));
+        else if (do_pack) write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which);
+        __syncthreads();
+    }
+}
+
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
 // small: every layer of the launch is narrow (w_in <= 16) and the chain runs the per-workgroup factorisation
 // which: operand copies to leave when cp > 0 (1 = row-major, 2 = transposed, 3 = both)
@@ -404,6 +621,24 @@ hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int m
                         bool small, int which, hipStream_t st) {
     if (n_ids <= 0) return hipSuccess;
     dim3 grid(max_lenP / kGramRows2, n_ids), block(kThreads);
+    if (!small && w_in <= kApplyStreamMaxWidth && w_out <= w_in) {
+        // a few rounds of workgroups over the whole launch, each walking several tiles of its layer
+        // (config 4, width 64: 0.54 ms with one round of 512 workgroups, 0.43 with four, 0.42 with eight, 0.45 with 16)
+        int per_layer = (8 * 512 + n_ids - 1) / n_ids;
+        if (per_layer > (int)grid.x) per_layer = grid.x;
+        if (per_layer < 1) per_layer = 1;
+        // (triangular tmat up to width 80: its fragments fit the registers)
+        const int kp16 = (mode != APPLY_RITZ && w_in <= 80) ? (w_in + 15) / 16 : 0;
+        const size_t lds = apply_stream_lds(w_in, w_out, cp, mode != APPLY_RITZ, kp16);
+        auto kfn = kp16 == 1 ? apply_stream_kernel<1> : kp16 == 2 ? apply_stream_kernel<2> : kp16 == 3 ? apply_stream_kernel<3>
+                 : kp16 == 4 ? apply_stream_kernel<4> : kp16 == 5 ? apply_stream_kernel<5> : apply_stream_kernel<0>;
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(kfn, dim3(per_layer, n_ids), block, lds, st, layers, ids, src_role, dst_role,
+                           mode, cp, gate, w_out, which);
+        return hipGetLastError();
+    }
     // w_in / w_out are upper bounds over the layers: sizes that grow with them cover every layer
     size_t lds = apply_main_lds(w_in, w_out, cp);
     if (small && mode == APPLY_PASS1) {
