@@ -650,31 +650,38 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
     const int64_t ld = L.ld;
     const int rowsP = L.rowsP;
     const PSGD_GLOBAL float* S = as_global(L.S);
-    const unsigned lane_e = 16u * (unsigned)lane;
-    // this thread's pieces of a tile: piece u at row ch * 32 + 8 wv + u, columns col0 + 4 lane .. + 3
+    // this thread's pieces of a tile: piece u at row ch * 32 + 8 wv + u, columns col0 + 4 lane .. + 3.
+    // Every step issues the same loads whatever the tile: where a piece lies outside the matrix the address is moved to a
+    // place inside it (last row; the lane's first column) and the value is dropped afterwards.  The hardware's wait counter
+    // counts loads in issue order, and the compiler can only leave the younger tile in flight while the older one
+    // is consumed if the number of loads between them is the same on every path: with loads under conditions it
+    // waited for all of them (vmcnt(0) before the LDS writes; vmcnt(16) now).  It also costs 54 registers less.  The
+    // pass did not get faster by it (4.85 ms on the 7B-shaped set either way): with everything but the loads compiled
+    // out it still takes 4.65 ms, where the same walk as a bare kernel takes 3.75 on the same buffers.
+    const int c_lane = col0 + 4 * lane;
+    const bool k0 = c_lane < L.cols, k1 = c_lane + 1 < L.cols, k2 = c_lane + 2 < L.cols, k3 = c_lane + 3 < L.cols;
+    const unsigned lane_e = k0 ? 16u * (unsigned)lane : 0u;
+    const int last_row = L.rows - 1;
     auto tile_full = [&](int ch) { return ch * CKR + CKR <= L.rows && col0 + CW <= L.cols; };
     auto load_tile = [&](int ch, floatx4 (&x)[8]) {
-        const PSGD_GLOBAL float* sp0 = S + (int64_t)(ch * CKR + 8 * wv) * ld + col0;
-        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(sp0 + u * ld) + lane_e); };
-        if (tile_full(ch)) {
-            if (nt_s) {
+        const int r0 = min(ch * CKR + 8 * wv, last_row), lim = last_row - r0;           // (uniform)
+        const PSGD_GLOBAL float* sp0 = S + (int64_t)r0 * ld + col0;
+        auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(sp0 + (int64_t)min(u, lim) * ld) + lane_e); };
+        if (nt_s) {
 #pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(at(u));
-            } else {
-#pragma unroll
-                for (int u = 0; u < 8; ++u) x[u] = *at(u);
-            }
+            for (int u = 0; u < 8; ++u) x[u] = __builtin_nontemporal_load(at(u));
         } else {
-            const int c = col0 + 4 * lane;
-            const bool k0 = c < L.cols, k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                x[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-                if (k0 && ch * CKR + 8 * wv + u < L.rows) {
-                    const floatx4 v = *at(u);                       // (the padding up to ld may be read, not used)
-                    x[u] = floatx4{v.x, k1 ? v.y : 0.f, k2 ? v.z : 0.f, k3 ? v.w : 0.f};
-                }
-            }
+            for (int u = 0; u < 8; ++u) x[u] = *at(u);
+        }
+    };
+    // (what load_tile fetched for places outside the matrix, or for a step past the end of the walk, becomes zero)
+    auto mask_tile = [&](int ch, bool live, floatx4 (&x)[8]) {
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const bool row_ok = live && ch * CKR + 8 * wv + u < L.rows;
+            x[u] = floatx4{row_ok && k0 ? x[u].x : 0.f, row_ok && k1 ? x[u].y : 0.f, row_ok && k2 ? x[u].z : 0.f,
+                           row_ok && k3 ? x[u].w : 0.f};
         }
     };
     const PackRef XK = L.pack[SIDE_L];
@@ -706,13 +713,15 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
     constexpr int AHEAD = NB <= 2 ? 2 : 1;
     floatx4 xa[8], xb[AHEAD == 2 ? 8 : 1];
     bf16x8 bfrag[2][NB][PL];
+    auto chunk_at = [&](int it) { return ch0 + min(it, n_loc - 1); };      // (steps past the end: the last tile again, dropped)
     if (n_loc > 0) {
-        load_tile(ch0, xa);
-        load_b(ch0, bfrag);
-        if constexpr (AHEAD == 2) { if (n_loc > 1) load_tile(ch0 + 1, xb); }
+        load_tile(chunk_at(0), xa);
+        load_b(chunk_at(0), bfrag);
+        if constexpr (AHEAD == 2) load_tile(chunk_at(1), xb);
     }
     const int wsw = (lane >> 2) & 3;                  // write side: bits 4, 5 of this thread's columns 4 lane + q
     auto step = [&](int it, floatx4 (&x)[8]) {
+        if (it >= n_loc || !tile_full(ch0 + it)) mask_tile(ch0 + it, it < n_loc, x);
         // ---- tile -> planes -> LDS, transposed: column 4 lane + q gets this thread's 8 rows as one 16-byte write
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -749,14 +758,14 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
                                 acc[rb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bfrag[ks][nb][kb], acc[rb][nb], 0, 0, 0);
                         }
             }
-        if (it + 1 < n_loc) load_b(ch0 + it + 1, bfrag);
-        if (it + AHEAD < n_loc) load_tile(ch0 + it + AHEAD, x);
+        load_b(chunk_at(it + 1), bfrag);
+        load_tile(chunk_at(it + AHEAD), x);
         __syncthreads();
     };
     if constexpr (AHEAD == 2) {
-        for (int it = 0; it < n_loc; it += 2) {
+        for (int it = 0; it < n_loc; it += 2) {      // (an odd walk ends with a step whose tile is dropped)
             step(it, xa);
-            if (it + 1 < n_loc) step(it + 1, xb);
+            step(it + 1, xb);
         }
     } else {
         for (int it = 0; it < n_loc; ++it) step(it, xa);
