@@ -800,13 +800,27 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
             }
             continue;
         }
-        for (int i = t; i < 128 * w; i += kThreads) {
-            const int row = i / w, c = i - row * w;
-            if (r0 + row < L.cols) as_global(T.ptr)[(int64_t)(r0 + row) * T.ld + c] = otile[row * tw + c];
+        if (T.ld == w && (w & 3) == 0) {
+            // (rows of the result are one run of memory: 16-byte stores over the flat range)
+            const int n_valid = (min(L.cols, r0 + 128) - r0) * w;
+            const float inv_w = 1.0f / (float)w;
+            PSGD_GLOBAL float* yp = as_global(T.ptr) + (int64_t)r0 * w;
+            for (int f = 4 * t; f < n_valid; f += 4 * kThreads) {
+                int row = (int)(((float)f + 0.5f) * inv_w);
+                int c = f - row * w;
+                if (c < 0) { --row; c += w; } else if (c >= w) { ++row; c -= w; }
+                const float* __restrict__ sr = otile + row * tw + c;
+                *reinterpret_cast<PSGD_GLOBAL floatx4*>(yp + f) = floatx4{sr[0], sr[1], sr[2], sr[3]};
+            }
+        } else {
+            for (int i = t; i < 128 * w; i += kThreads) {
+                const int row = i / w, c = i - row * w;
+                if (r0 + row < L.cols) as_global(T.ptr)[(int64_t)(r0 + row) * T.ld + c] = otile[row * tw + c];
+            }
         }
         // the partial Gram matrix or the operand copies of the result, per 128 rows as the other kernels expect them
         if (epi == EPI_GRAM) gram_tile_f64(otile, tw, 128, w, L.gram + (int64_t)(r0 / 128) * ((w * (w + 1)) / 2));
-        else if (epi == EPI_PACK) write_packs(L.pack[SIDE_W], L.planes, otile, tw, cp, r0, 128, L.colsP);
+        else if (epi == EPI_PACK) write_packs<PL>(L.pack[SIDE_W], L.planes, otile, tw, cp, r0, 128, L.colsP);
     }
 }
 

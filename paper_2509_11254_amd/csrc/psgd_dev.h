@@ -162,24 +162,27 @@ __device__ inline void divmod_small(int v, int d, int& q, int& r) {
 // Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
 // nrows and row0 multiples of 16); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
 // which: 1 = the row-major copies only, 2 = the transposed ones only, 3 = both.
+// PLT: the plane count as a compile-time constant where the caller has it (0: from `planes`, all kMaxPlanes are formed)
+template <int PLT = 0>
 __device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
                                    int nrows, int lenP, int which = 3) {
+    constexpr int NPL = PLT > 0 ? PLT : kMaxPlanes;
     const int t = threadIdx.x;
     for (int v = t; (which & 1) && v < nrows * (cp / 8); v += kThreads) {
         int row, g8;
         divmod_small(v, cp / 8, row, g8);
         const int c0 = 8 * g8;
-        bf16x8 o[kMaxPlanes];
+        bf16x8 o[NPL];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            bf16_t q[kMaxPlanes];
-            split_planes<kMaxPlanes>(tile[row * tw + c0 + u], q);
+            bf16_t q[NPL];
+            split_planes<NPL>(tile[row * tw + c0 + u], q);
 #pragma unroll
-            for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
+            for (int k = 0; k < NPL; ++k) o[k][u] = q[k];
         }
         const int64_t off = (int64_t)(row0 + row) * cp + c0;
 #pragma unroll
-        for (int k = 0; k < kMaxPlanes; ++k)
+        for (int k = 0; k < NPL; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.n[k]) + off) = o[k];
     }
     // fragment-order copy: the tile's rows are (nrows / 16) * (cp / 32) whole fragments, one run of consecutive memory
@@ -189,17 +192,17 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         int k16, nb;
         divmod_small(frag, cp >> 5, k16, nb);
         const int c = 32 * nb + (ln & 31), ib = 16 * k16 + 8 * (ln >> 5);
-        bf16x8 o[kMaxPlanes];
+        bf16x8 o[NPL];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            bf16_t q[kMaxPlanes];
-            split_planes<kMaxPlanes>(tile[(ib + u) * tw + c], q);
+            bf16_t q[NPL];
+            split_planes<NPL>(tile[(ib + u) * tw + c], q);
 #pragma unroll
-            for (int k = 0; k < kMaxPlanes; ++k) o[k][u] = q[k];
+            for (int k = 0; k < NPL; ++k) o[k][u] = q[k];
         }
         const int64_t off = pack_t_offset(row0 + ib, c, cp);      // (= 8 * (first piece of the tile + v))
 #pragma unroll
-        for (int k = 0; k < kMaxPlanes; ++k)
+        for (int k = 0; k < NPL; ++k)
             if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.t[k]) + off) = o[k];
     }
 }
