@@ -217,6 +217,25 @@ def read_traffic(tag):
     return None, None
 
 
+def run_c5b(torch):
+    """Config 5b, a demonstration rather than a rate: the least-squares problem (N = 16, A_i 512 x 256, X 256 x 128,
+    r = 4) run for 2000 steps as PowerSGD and as PowerSGD+ (tau = 10), every compressor and optimizer step through the
+    library; reported: the gradient norms at the start and at the end, and the wall time per step."""
+    from paper_2509_11254_amd import demo_least_squares, synth
+    problem = synth.least_squares_problem(steps=2000)
+    res = {"workload": "c5b_least_squares_n16_512x256_x256x128_r4", "steps": 2000, "tau": problem.tau, "mu": problem.mu,
+           "sigma": problem.sigma, "eta_scale": problem.eta_scale}
+    for tag, tau in (("powersgd", None), ("powersgd_plus", problem.tau)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        hist = demo_least_squares.run(problem, tau, 2000, record_every=500)
+        dt = time.perf_counter() - t0
+        res["grad_norm_%s" % tag] = hist
+        res["final_grad_norm_%s" % tag] = hist[-1]
+        res["wall_ms_per_step_%s" % tag] = 1e3 * dt / 2000
+    return res
+
+
 def run_workload(name, args, primary):
     """Times one workload; returns (the fields of its bench line, objects the CPU baseline needs)."""
     import torch
@@ -460,6 +479,7 @@ def main():
             sub, keep = run_workload(name, args, False)
             del keep
             others[name] = {k: sub[k] for k in ("value", "unit", "steps", "ms_per_step", "dtype", "config", "roofline", "breakdown")}
+        others["c5b"] = run_c5b(torch)
         out["other_workloads"] = others
     print(json.dumps(out))
 

@@ -259,3 +259,33 @@ def device_gradients(wl, n_sets, torch, no_qr=False):
         P.append(torch.zeros((spec.m, wl.r), dtype=torch.float32, device="cuda"))
         OUT.append(torch.empty((spec.rows, spec.cols), dtype=torch.float32, device="cuda"))
     return sets, E, Q, P, OUT
+
+
+# ----------------------------------------------------------------------------------------------------------------
+# Config 5b: the least-squares problem behind the PowerSGD / PowerSGD+ comparison of Section 3 (Figure 1).  The paper
+# gives none of its parameters; the ones here are this build's (listed in the design notes).  Only the data of the
+# problem and the random signs of the stochastic gradient are made here; the gradient itself, the compressor and the
+# optimizer are the caller's.
+# ----------------------------------------------------------------------------------------------------------------
+@dataclass
+class LeastSquares:
+    a: List[np.ndarray]          # A_i, N x (rows x d), fp32
+    b: List[np.ndarray]          # B_i = A_i X* + noise, N x (rows x k), fp32
+    x_star: np.ndarray           # d x k
+    xi: np.ndarray               # steps x N signs in {-1, +1}; step 0 is all +1
+    r: int = 4
+    tau: int = 10
+    mu: float = 0.9
+    sigma: float = 50.0          # size of the rank-one term of the stochastic gradient
+    eta_scale: float = 0.03      # eta = eta_scale (1 - mu) / lambda_max(mean_i A_i^T A_i / rows)
+
+
+def least_squares_problem(steps: int = 2000, n_workers: int = 16, rows: int = 512, d: int = 256, k: int = 128,
+                          noise: float = 0.1, seed: int = 1234) -> LeastSquares:
+    g = _rng(seed, 55)
+    a = [g.standard_normal((rows, d)).astype(np.float32) for _ in range(n_workers)]
+    x_star = g.standard_normal((d, k)).astype(np.float32)
+    b = [(ai.astype(np.float64) @ x_star + noise * g.standard_normal((rows, k))).astype(np.float32) for ai in a]
+    xi = g.choice(np.array([-1.0, 1.0]), size=(steps, n_workers))
+    xi[0, :] = 1.0
+    return LeastSquares(a, b, x_star, xi)
