@@ -184,7 +184,7 @@ int fail_hip(psgd_ctx* c, hipError_t e) {
     } while (0)
 
 struct LayerRegion {
-    size_t part[2], pack[2][6], lz[2][3], lzf[2][3], z[2], gram, tmat, eval, status, end;
+    size_t part[2], pack[2][6], lzf[2][3], z[2], gram, tmat, eval, status, end;
 };
 
 // byte layout of one layer's private workspace region, relative to its start
@@ -202,10 +202,7 @@ LayerRegion layer_region(const psgd_ctx* c, const Plan& p) {
         for (int k = 0; k < 2 * c->planes; ++k) R.pack[s][k] = take((size_t)lenP[s] * c->cpmax * sizeof(bf16_t));
     if (c->lazy && (!p.transposed || c->lazy_tr))
         for (int s = 0; s < 2; ++s)
-            for (int k = 0; k < c->planes; ++k) {
-                R.lz[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
-                R.lzf[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
-            }
+            for (int k = 0; k < c->planes; ++k) R.lzf[s][k] = take((size_t)lenP[s] * c->cpc * sizeof(bf16_t));
     const int len[2] = {(int)p.d.rows, (int)p.d.cols};
     for (int s = 0; s < 2; ++s) R.z[s] = take((size_t)len[s] * c->wz * sizeof(float));
     const size_t w2 = (size_t)(c->wz + 2) * (c->wz + 2);
@@ -280,7 +277,6 @@ void build_layer_dev(psgd_ctx* c, char* ws, int l, int slot, LayerDev* out) {
         for (int k = 0; k < c->planes; ++k) {
             L.pack[s].n[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k]);
             L.pack[s].t[k] = reinterpret_cast<bf16_t*>(base + R.pack[s][2 * k + 1]);
-            L.lz[s][k] = (c->lazy && (!p.transposed || c->lazy_tr)) ? reinterpret_cast<bf16_t*>(base + R.lz[s][k]) : nullptr;
             L.lzf[s][k] = (c->lazy && (!p.transposed || c->lazy_tr)) ? reinterpret_cast<bf16_t*>(base + R.lzf[s][k]) : nullptr;
         }
     }

@@ -326,10 +326,10 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
         for (int i = 0; i < NB; ++i) {
             const int v = t + i * kThreads;          // 0 .. 64 * 4 NB - 1
             const int c = v / (4 * NB), part = v % (4 * NB);
-            const int64_t goff = (int64_t)(ch * BK + c) * cp + 8 * part;
+            const int64_t goff = frag_piece(ch * BK + c, part, cp) * 8;      // (the kept copies are in fragment order)
 #pragma unroll
             for (int k = 0; k < PL; ++k)
-                cq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lz[src_side][k]) + goff);
+                cq[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.lzf[src_side][k]) + goff);
         }
     };
     auto load_ap = [&]() {
@@ -341,7 +341,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
                 for (int k = 0; k < PL; ++k) {
                     const int own = COLMODE ? 64 * (wv >> 1) + 4 * lj + h : 32 * wv + 16 * h + lj;   // row / column of the tile
                     ap[h][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                        as_global(L.lz[out_side][k]) + (int64_t)(ob * BT + own) * cp + 32 * ks + 8 * lq);
+                        as_global(L.lzf[out_side][k]) + frag_piece(ob * BT + own, 4 * ks + lq, cp) * 8);
                 }
     };
     if (LAZY) load_ap();

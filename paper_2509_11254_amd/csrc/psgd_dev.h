@@ -109,9 +109,8 @@ struct LayerDev {
     ThinRef thin[ROLE_COUNT];
     float* part[2];         // per side: [split][width][lenP] fp32 partial products of a split reduction
     PackRef pack[2];        // per side
-    bf16_t* lz[2][kMaxPlanes];   // per side: row-major [lenP][cp] copies of the compress step's P~ and Q operands,
-                                 // kept while the residual of that step is still owed (deferred residual)
-    bf16_t* lzf[2][kMaxPlanes];  // the same operands in MFMA fragment order (frag_offset), what form_row_kernel reads
+    bf16_t* lzf[2][kMaxPlanes];  // per side: copies of the compress step's P~ and Q operands in MFMA fragment order
+                                 // (frag_piece), kept while the residual of that step is still owed (deferred residual)
     double* gram;           // [slots][w(w+1)/2] partial Gram matrices (packed upper triangles), one slot per
                             // row block of the producer
     double* tmat;           // [wmax*wmax] small factor applied from the right

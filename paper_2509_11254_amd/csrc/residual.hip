@@ -41,13 +41,15 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
 #pragma unroll
     for (int k = 0; k < PL; ++k) {
         // kept: the operand copies put aside by the last compress step (deferred residual) instead of the current ones
-        wk[k] = as_global(kept ? L.lz[SIDE_W][k] : L.pack[SIDE_W].n[k]);
-        lk[k] = as_global(kept ? L.lz[SIDE_L][k] : L.pack[SIDE_L].n[k]);
+        wk[k] = as_global(kept ? L.lzf[SIDE_W][k] : L.pack[SIDE_W].n[k]);
+        lk[k] = as_global(kept ? L.lzf[SIDE_L][k] : L.pack[SIDE_L].n[k]);
     }
     // Every global round trip on the way to the first MFMA is a stretch in which this workgroup moves no
     // matrix bytes, so the requests go out together: the first group of this wave's row operand, then the
     // column operand of the tile in batches of SB pieces per thread.
-    const int64_t aoff = (int64_t)(rb * RT + 32 * wv + li) * cp + 8 * lg;
+    // (offsets of 16-byte pieces: row-major copies by row and column, the kept ones in fragment order)
+    const int arow = rb * RT + 32 * wv + li;
+    auto piece = [&](int row, int g8) { return kept ? frag_piece(row, g8, cp) * 8 : (int64_t)row * cp + 8 * g8; };
     bf16x8 av[2][KG][PL];
     auto load_rows = [&](int g, bf16x8 (&dst)[KG][PL]) {
 #pragma unroll
@@ -55,7 +57,7 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
             if (g * KG + j < KS) {
 #pragma unroll
                 for (int k = 0; k < PL; ++k)
-                    dst[j][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(lk[k] + aoff + 16 * (g * KG + j));
+                    dst[j][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(lk[k] + piece(arow, 2 * (g * KG + j) + lg));
             }
     };
     load_rows(0, av[0]);
@@ -67,7 +69,7 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
         for (int i = 0; i < SB; ++i) {
             const int v = t + (i0 + i) * kThreads;
             const int jj = v / (NB * 4), part = v % (NB * 4);
-            const int64_t goff = (int64_t)(cb * RT + jj) * cp + 8 * part;
+            const int64_t goff = piece(cb * RT + jj, part);
 #pragma unroll
             for (int k = 0; k < PL; ++k)
                 if (i0 + i < NI) tmp[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(wk[k] + goff);

@@ -86,24 +86,26 @@ hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_i
 }
 
 // --------------------------------------------------------------------------------------------
-// keep: put the row-major operand copies of the compress step's P~ and Q aside (deferred residual): the next
-// forming pass subtracts their product on the way, whatever has happened to the current copies in between.
+// keep: put the operand copies of the compress step's P~ and Q aside (deferred residual), in the fragment order of an
+// outer-product operand: the next forming pass subtracts their product on the way, whatever has happened to the
+// current copies in between.  Thread by thread along the destination (consecutive 16-byte pieces).
 // --------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kThreads) void keep_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
                                                         int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int side = blockIdx.z;
-    const int64_t n16 = (int64_t)side_lenP(L, side) * cp / 8;       // 16-byte words per plane
-    const int g8n = cp / 8;                                          // 16-byte pieces per row
+    const int64_t n16 = (int64_t)side_lenP(L, side) * cp / 8;       // 16-byte pieces per plane
+    const int g8n = cp / 8, ksn = cp / 16;                           // pieces per row; k-steps per 32-row block
     for (int k = 0; k < L.planes; ++k) {
         const PSGD_GLOBAL uintx4* src = reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.pack[side].n[k]));
-        PSGD_GLOBAL uintx4* dst = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lz[side][k]));
         PSGD_GLOBAL uintx4* dstf = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lzf[side][k]));
         for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads) {
-            const uintx4 v = src[i];
-            dst[i] = v;
-            const int row = (int)(i / g8n), g8 = (int)(i - (int64_t)row * g8n);
-            dstf[frag_piece(row, g8, cp)] = v;
+            const int ln = (int)(i & 63);
+            const int64_t frag = i >> 6;
+            const int64_t blk = frag / ksn;
+            const int ks = (int)(frag - blk * ksn);
+            const int64_t row = 32 * blk + (ln & 31);
+            dstf[i] = src[row * g8n + 2 * ks + (ln >> 5)];       // (= piece frag_piece(row, 2 ks + (ln >> 5), cp))
         }
     }
 }
