@@ -872,8 +872,8 @@ static hipError_t launch_rowprod_nb(const LayerDev* layers, const int* ids, int 
     return hipGetLastError();
 }
 
-// (width 96 is built but not chosen: every 32 rows fetch the thin operand again, 12 bytes from L2 per 4 bytes of S
-// with two planes, and the pass is L2-bound: 7.1 ms on the 7B-shaped set against 6.4 for prod_kernel's 128-row tiles)
+// (not at width 96: every 32 rows fetch the thin operand again, 12 bytes from L2 per 4 bytes of S with two planes,
+// and the pass is L2-bound there: 7.1 ms on the 7B-shaped set against 6.4 for prod_kernel's 128-row tiles)
 bool row_prod_supported(int nb, int planes) { (void)planes; return nb == 1 || nb == 2; }
 
 // thin[out_role] = S X on row-major layers, S read only.  max_tiles, xtab, xstride, xtiles as for launch_form_row;
@@ -886,7 +886,6 @@ hipError_t launch_row_prod(int nb, int planes, const LayerDev* layers, const int
                                     : launch_rowprod_nb<1, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
     if (nb == 2) return planes == 2 ? launch_rowprod_nb<2, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st)
                                     : launch_rowprod_nb<2, 3>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
-    if (nb == 3 && planes == 2) return launch_rowprod_nb<3, 2>(layers, ids, n_ids, max_tiles, out_role, epi, gate, nt_s, xtab, xstride, xtiles, st);
     return hipErrorInvalidValue;
 }
 

@@ -632,7 +632,8 @@ hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int m
         // (triangular tmat up to width 80: its fragments fit the registers)
         const int kp16 = (mode != APPLY_RITZ && w_in <= 80) ? (w_in + 15) / 16 : 0;
         const size_t lds = apply_stream_lds(w_in, w_out, cp, mode != APPLY_RITZ, kp16);
-        auto kfn = kp16 == 1 ? apply_stream_kernel<1> : kp16 == 2 ? apply_stream_kernel<2> : kp16 == 3 ? apply_stream_kernel<3>
+        // (widths up to 16 are the `small` chain's: kp16 >= 2 here)
+        auto kfn = kp16 == 2 ? apply_stream_kernel<2> : kp16 == 3 ? apply_stream_kernel<3>
                  : kp16 == 4 ? apply_stream_kernel<4> : kp16 == 5 ? apply_stream_kernel<5> : apply_stream_kernel<0>;
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
