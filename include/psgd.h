@@ -88,7 +88,9 @@ typedef struct {
                                    number that the convergence factor rho = (theta_b/theta_r)^2 seen at its
                                    last refresh needs for 1e-5, plus one, if that is within the maximum
                                    (rho <= 0.46 for 16); if it is not -- no gap after sigma_r to converge
-                                   across in the budget -- they run 8 (or the maximum, if smaller)      */
+                                   across in the budget -- they run what keeps the error of the step
+                                   within 1e-5 ||M||^2 of the optimum of Eq. (6) by the same Ritz values, at
+                                   least 2, at most the maximum                                         */
     int32_t refresh_oversample; /* extra block columns beyond r; negative = default max(8, r/4); the
                                    block width r + oversample is rounded up to a multiple of 8 and
                                    capped at n                                                       */
@@ -133,9 +135,12 @@ typedef struct {
     int32_t rank_deficient; /* number of columns of P~ zeroed by the rank test                  */
     int32_t refresh_iters_next; /* iterations the layer's next refresh needs to converge, from the Ritz
                                    values of the last one (0: not known yet; above the maximum: it will
-                                   run 8, see refresh_iters)                                            */
+                                   run refresh_iters_no_gap of them, see refresh_iters)                 */
     float sigma_max;        /* refresh only: largest and r-th Ritz value (singular value estimates) */
     float sigma_r;
+    int32_t refresh_iters_no_gap; /* iterations the next refresh runs when the count above is beyond the
+                                   maximum: what keeps its error within 1e-5 ||M||^2 of the optimum of
+                                   Eq. (6), at least 2 (the maximum caps it)                            */
 } psgd_layer_status;
 
 /* psgd_init -- plan the batched launches for a fixed set of layers (Algorithm 2, "Require"/"Initialize":

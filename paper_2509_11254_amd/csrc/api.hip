@@ -1224,10 +1224,11 @@ int psgd_status(psgd_ctx* ctx, void* workspace, void* stream, int layer, psgd_la
     PSGD_TRY(hipStreamSynchronize(st));
     char* ws = reinterpret_cast<char*>(workspace);
     const LayerRegion R = layer_region(ctx, ctx->plan[layer]);
-    int raw[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    int raw[kStatusWords] = {};
     PSGD_TRY(hipMemcpy(raw, ws + ctx->off_layer[layer] + R.status, sizeof(raw), hipMemcpyDeviceToHost));
     out->rank_deficient = raw[0];
     out->refresh_iters_next = raw[4];
+    out->refresh_iters_no_gap = raw[25] < 2 ? 2 : raw[25];
     std::memcpy(&out->sigma_max, &raw[2], sizeof(float));
     std::memcpy(&out->sigma_r, &raw[3], sizeof(float));
     return PSGD_OK;

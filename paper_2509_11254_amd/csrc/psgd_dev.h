@@ -44,7 +44,8 @@ template <int BIT, class V> __device__ inline void st_stream(PSGD_GLOBAL V* p, V
 }
 
 constexpr int kStatusWords = 8 + 16 + 8; // per layer: 8 diagnostics and counters, one counter per Gram slot group,
-                                         // then: [24] refreshes this layer has run in this workspace
+                                         // then: [24] refreshes this layer has run in this workspace, [25] iterations
+                                         // its next refresh runs if its cut has no gap (see refresh_iterations)
 constexpr int kThreads = 256;      // 4 wavefronts of 64 lanes
 constexpr int kLenPad = 128;       // packed operand rows are padded (with zeros) to this multiple
 constexpr int kGramRows1 = 128;    // rows per partial Gram matrix written by a product's epilogue
@@ -213,14 +214,13 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 // gradient: on a 4096 x 4096 run sigma_{b+1}/sigma_r went from 0.13 at t = 0 to 0.43 at t = 10, and the count taken
 // from t = 0 left sin(theta) = 2e-4); after that status[4] (what
 // its spectrum needs to converge, from the Ritz values of its last refresh) when that is within the budget; and
-// kBudgetIterations when it is not -- the cut is then too close to a cluster of singular values to converge
-// across in the budget, and the members of such a cluster compress almost equally well, so the budget is not
-// burnt on it.  k never exceeds the number of launched iterations (the host may launch fewer than the budget when
+// otherwise -- the cut is then too close to a cluster of singular values to converge across in the budget, and the
+// members of such a cluster compress almost equally well -- the count that keeps the compression error within a
+// tenth of 1e-4 ||M||^2 of the optimum (status[25]), at least 2, at most the budget.  k never exceeds the number of launched iterations (the host may launch fewer than the budget when
 // it knows an upper bound of the counts; should that bound be out of date, a layer's last iteration is still one
 // that was launched).  kind 1 marks the orthonormalisation of Y, which the last executed iteration skips because
 // the Rayleigh-Ritz step wants Y = M^T Z itself; kind 2 is open in the last executed iteration only (the second
 // CholeskyQR pass on Z, which the Rayleigh-Ritz step needs exact).
-constexpr int kBudgetIterations = 8;
 constexpr int kMaxRefreshIterations = 255;
 __host__ __device__ inline int make_gate(int iteration, int kind, int budget, int launched) {
     return iteration | kind << 8 | budget << 10 | launched << 18;
@@ -230,7 +230,12 @@ __host__ __device__ inline int gate_with_kind(int gate, int kind) { return (gate
 __device__ inline int refresh_iterations(const LayerDev& L, int mx) {
     int k = L.status[4];
     if (k <= 0 || L.status[24] < 2) k = mx;
-    else if (k > mx) k = mx < kBudgetIterations ? mx : kBudgetIterations;
+    else if (k > mx) {
+        // no gap to converge across within the budget: as many iterations as the error bound of Lemma 2 needs
+        // (status[25], see jacobi_kernel), at least 2, at most the budget
+        const int ke = L.status[25] < 2 ? 2 : L.status[25];
+        k = mx < ke ? mx : ke;
+    }
     return k;
 }
 __device__ inline bool gate_open(const LayerDev& L, int gate) {

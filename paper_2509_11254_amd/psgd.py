@@ -42,7 +42,7 @@ class Options(C.Structure):
 
 class LayerStatus(C.Structure):
     _fields_ = [("rank_deficient", C.c_int32), ("refresh_iters_next", C.c_int32), ("sigma_max", C.c_float),
-                ("sigma_r", C.c_float)]
+                ("sigma_r", C.c_float), ("refresh_iters_no_gap", C.c_int32)]
 
 
 class PsgdError(RuntimeError):
