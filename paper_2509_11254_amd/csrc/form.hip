@@ -709,15 +709,13 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
     // on its way in the other, and requests the tile of step it + 2 into the buffer it has just emptied -- after its
     // MFMA phase and after the fragments of step it + 1 (the wait counter is in issue order: what the next MFMA phase
     // waits for must be older than the tile that is to stay in flight through it).
-    // (width 96: one tile in flight, the registers do not hold two beside the accumulators)
-    constexpr int AHEAD = NB <= 2 ? 2 : 1;
-    floatx4 xa[8], xb[AHEAD == 2 ? 8 : 1];
+    floatx4 xa[8], xb[8];
     bf16x8 bfrag[2][NB][PL];
     auto chunk_at = [&](int it) { return ch0 + min(it, n_loc - 1); };      // (steps past the end: the last tile again, dropped)
     if (n_loc > 0) {
         load_tile(chunk_at(0), xa);
         load_b(chunk_at(0), bfrag);
-        if constexpr (AHEAD == 2) load_tile(chunk_at(1), xb);
+        load_tile(chunk_at(1), xb);
     }
     const int wsw = (lane >> 2) & 3;                  // write side: bits 4, 5 of this thread's columns 4 lane + q
     auto step = [&](int it, floatx4 (&x)[8]) {
@@ -759,16 +757,12 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
                         }
             }
         load_b(chunk_at(it + 1), bfrag);
-        load_tile(chunk_at(it + AHEAD), x);
+        load_tile(chunk_at(it + 2), x);
         __syncthreads();
     };
-    if constexpr (AHEAD == 2) {
-        for (int it = 0; it < n_loc; it += 2) {      // (an odd walk ends with a step whose tile is dropped)
-            step(it, xa);
-            step(it + 1, xb);
-        }
-    } else {
-        for (int it = 0; it < n_loc; ++it) step(it, xa);
+    for (int it = 0; it < n_loc; it += 2) {          // (an odd walk ends with a step whose tile is dropped)
+        step(it, xa);
+        step(it + 1, xb);
     }
     // ---- the 256 x cp result tile goes out in two halves of 128 rows through LDS (the operand buffer is free: the
     // loop ends in a barrier); half h holds the rows of waves 2 h and 2 h + 1
