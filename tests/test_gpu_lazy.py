@@ -261,3 +261,18 @@ def test_compress_on_another_workspace_while_a_residual_is_owed_is_rejected():
     o1 = orc.compress_step(1, None, wl.r, o0.comp.q, g, o0.e_next)
     assert orc.rel_fro(back(case.E[0]), o1.e_mean) <= 1e-4
     assert orc.rel_fro(back(case.P[0]), o1.comp.p_tilde) <= 1e-4
+
+
+@pytest.mark.parametrize("rows,cols,ld,r,dtype,n_workers", [
+    (257, 129, 136, 17, synth.F32, 2), (1000, 264, 264, 33, synth.BF16, 1), (333, 100, 104, 40, synth.F32, 1),
+    (2049, 260, 264, 65, synth.BF16, 2), (515, 36, 40, 5, synth.BF16, 3), (1200, 520, 520, 72, synth.F32, 1),
+    (900, 300, 304, 96, synth.BF16, 1), (641, 257, 264, 48, synth.F32, 4)])
+def test_deferred_residual_odd_shapes_and_ranks(rows, cols, ld, r, dtype, n_workers):
+    """Shapes that are multiples of nothing (rows not of 8, columns not of 4, a leading dimension beyond the columns) at
+    ranks on both sides of every width class of the kernels (16, 32, 64, 80, 96): three free-running steps with the
+    deferred residual, every step's P~, Q and M and the flushed E against the oracle."""
+    base = synth.config4() if dtype == synth.BF16 else synth.config2()
+    wl = synth.scaled_down(base, rows, cols)
+    wl.r = r
+    wl.n_workers = n_workers
+    print((rows, cols, ld, r, dtype, n_workers), _trajectory(wl, 3, lds=[ld]))
