@@ -33,11 +33,11 @@ bool row_prod_supported(int nb, int planes);
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st);
 hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_ids, int mx, int* out, hipStream_t st);
-hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st);
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                       float* const* moms, float* const* xs, float mu, float eta, hipStream_t st);
+                       float* const* moms, float* const* xs, float mu, float eta, bool kept, hipStream_t st);
 hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, hipStream_t st);
+                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, bool kept,
+                       hipStream_t st);
 hipError_t launch_finish(bool colmode, int form, const LayerDev* layers, const int* ids, int n_ids, int max_blocks,
                          int cp, int out_role, int epi, int gate, int chol_gate, int a2gate, double tol2, int w,
                          int local_ok, hipStream_t st);
@@ -134,6 +134,7 @@ struct psgd_ctx {
     void* msgd_ws = nullptr;     // ... and of the momentum and weight buffers of psgd_decompress_msgd / _adam
     void* m2_ws = nullptr;       // ... and of the second-moment buffers of psgd_decompress_adam
     void* factors_ws = nullptr;  // workspace whose row-major operand copies are the P~, Q of the last compress call
+    bool factors_kept = false;   // ... a call with a deferred residual: in the layers that defer they are the kept copies
     bool tables_valid = false;
     std::vector<const void*> hG;                       // the caller's current table
     std::vector<const void*> hGs[kGSlots];             // what each device slot holds (empty: nothing yet)
@@ -404,6 +405,8 @@ struct Launcher {
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
     bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
+    bool kept_packs = false;  // compress step with a deferred residual: the row-major operand copies of its P~ and Q go
+                              // to the kept copies (fragment order) in the layers that have them
     bool use_form_row = true; // PSGD_FORM_ROW=0 (environment, measurement knob): the older 128 x 64 forming pass
     bool use_xtab = true;     // PSGD_XTAB=0 (environment, measurement knob): plain layer-by-layer launch order
 
@@ -432,7 +435,7 @@ struct Launcher {
               double tol2 = 0.0, int w = 0, bool small = false) {
         // normal storage: P-like result is L-side -> row mode; transposed storage: column mode
         const int k = prof_begin(p_like ? PSGD_PROF_SWEEP1 : PSGD_PROF_SWEEP2);
-        const int ef = epi | (keep_e ? EPI_KEEP_E : 0);
+        const int ef = epi | (keep_e ? EPI_KEEP_E : 0) | (kept_packs && epi == EPI_PACK ? EPI_KEPT : 0);
         const int tiles_row = form ? tiles_row_f : this->tiles_row, tiles_col = form ? tiles_col_f : this->tiles_col;
         const int split_row = form ? split_row_f : this->split_row, split_col = form ? split_col_f : this->split_col;
         const bool onew = ctx->n_workers == 1;
@@ -461,8 +464,8 @@ struct Launcher {
         // workgroup per layer also factorises the Gram matrix; unsplit products need a launch for that
         const bool rv2 = v2 || r2;
         const bool split_n = rv2 ? split_row_v2 > 1 : c2 ? split_col_v2 > 1 : (p_like ? split_row > 1 : split_col > 1), split_t = p_like ? split_col > 1 : split_row > 1;
-        if (split_n) note(launch_finish(!p_like, rv2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
-        if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi, gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_n) note(launch_finish(!p_like, rv2 ? 2 : c2 ? 3 : (form ? 1 : 0), layers, ids_norm, n_norm, p_like ? blocks_row : blocks_col, 32 * nb, out_role, epi | (ef & EPI_KEPT), gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
+        if (split_t) note(launch_finish(p_like, form ? 1 : 0, layers, ids_tr, n_tr, p_like ? blocks_col : blocks_row, 32 * nb, out_role, epi | (ef & EPI_KEPT), gate, chol_gate, a2gate, tol2, w, small ? 1 : 0, st));
         // (an unsplit launch of that kernel writes one partial Gram matrix per 32-row block itself where the
         // factorisation is a launch of its own -- widths above 16 --, and leaves them to a small pass over the result,
         // one per 128 rows, where the apply kernel factorises for itself)
@@ -489,7 +492,7 @@ struct Launcher {
         // factorisation itself; otherwise the second factorisation is a launch of its own
         const bool small = w <= 16;
         // (inside the iteration only products read the result: no row-major operand copies)
-        const int wh = gate >= 0 ? PACK_TRANSPOSED : (PACK_ROWMAJOR | PACK_TRANSPOSED);
+        const int wh = gate >= 0 ? PACK_TRANSPOSED : (PACK_ROWMAJOR | PACK_TRANSPOSED | (kept_packs ? 4 : 0));
         prod(p_like, form, nb, out_role, EPI_GRAM, g, a2, tol2, w, small);
         note(launch_apply(layers, ids_all, n_all, max_lenP(), w, w, out_role, out_role, APPLY_PASS1, cp, g, a2, tol2, small, wh, st));
         if (a2 != -2) {
@@ -515,15 +518,12 @@ struct Launcher {
     }
     // deferred residual: the layers that defer keep their operands; the others (stored with rows < cols, at
     // widths above 32) take their residual at once
-    void residual_deferred(int nb, int cp) {
-        if (ctx->lazy_tr) {
-            note(launch_keep(layers, ids_all, n_all, max_lenP(), cp, st));
-            return;
-        }
+    // (the layers that defer need no launch: the step's apply and product kernels have written their kept copies)
+    void residual_deferred(int nb) {
+        if (ctx->lazy_tr) return;
         const int k = prof_begin(PSGD_PROF_RESIDUAL);
         note(launch_outer(nb, ctx->planes, false, false, false, layers, ids_tr, n_tr, tiles_outer, nullptr, 0, st));
         prof_end(k);
-        note(launch_keep(layers, ids_norm, n_norm, max_lenP(), cp, st));
     }
     // E <- M - (kept P~)(kept Q)^T for the layers that defer: what the deferred residual still owes
     void residual_owed(int nb) {
@@ -870,6 +870,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     // P~ = QR(P), operand copies of P~;  Q_t = M^T P~, operand copies of Q_t;  K times (Eq. (8)), K = 1 by default
     const bool re = ctx->reform_m;
     const int K = ctx->opt.power_iters > 0 ? ctx->opt.power_iters : 1;
+    L.kept_packs = ctx->lazy;
     for (int k = 0; k < K; ++k) {
         L.keep_e = re;
         L.lazy_form = ctx->pending;            // E of the row-major layers is M_{t-1} - (kept P~)(kept Q)^T
@@ -880,13 +881,14 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
         L.keep_e = false;
     }
     if (ctx->lazy) {
-        L.residual_deferred(nb, cp);               // owed: E <- M - P~ Q_t^T, applied by the next forming pass
+        L.residual_deferred(nb);                   // owed: E <- M - P~ Q_t^T, applied by the next forming pass
         ctx->pending = L.n_norm > 0 || ctx->lazy_tr;
     } else {
         L.residual(nb, re);                        // E <- M - P~ Q_t^T
     }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     ctx->factors_ws = workspace;                   // the operand copies of P~_t and Q_t are in place
+    ctx->factors_kept = ctx->lazy;
     return PSGD_OK;
 }
 
@@ -965,6 +967,7 @@ int psgd_compress_finish(psgd_ctx* ctx, void* workspace, void* stream, float* co
     L.residual(nb, false);                              // E <- M - P~ Q^T
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     ctx->factors_ws = workspace;                        // (copies of P~ and of this worker's Q)
+    ctx->factors_kept = false;
     return PSGD_OK;
 }
 
@@ -1061,6 +1064,7 @@ int psgd_compress_refresh(psgd_ctx* ctx, void* workspace, void* stream, const vo
     }
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     ctx->factors_ws = workspace;
+    ctx->factors_kept = false;
     return PSGD_OK;
 }
 
@@ -1137,7 +1141,7 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
-    L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_all, L.n_all, L.tiles_outer,
+    L.note(launch_outer(nb, ctx->planes, true, false, packed && ctx->factors_kept, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                         reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
@@ -1168,7 +1172,7 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
     L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
-                       reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, st));
+                       reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, packed && ctx->factors_kept, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -1213,7 +1217,7 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
     L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
                        reinterpret_cast<float* const*>(ws + ctx->off_moms),
                        reinterpret_cast<float* const*>(ws + ctx->off_m2s),
-                       reinterpret_cast<float* const*>(ws + ctx->off_xs), coef, st));
+                       reinterpret_cast<float* const*>(ws + ctx->off_xs), coef, packed && ctx->factors_kept, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }

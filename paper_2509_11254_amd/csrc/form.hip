@@ -814,7 +814,7 @@ __global__ __launch_bounds__(kThreads, ((PL == 2 && NB == 1) ? 3 : 2)) void col_
         }
         // the partial Gram matrix or the operand copies of the result, per 128 rows as the other kernels expect them
         if (epi == EPI_GRAM) gram_tile_f64(otile, tw, 128, w, L.gram + (int64_t)(r0 / 128) * ((w * (w + 1)) / 2));
-        else if (epi == EPI_PACK) write_packs<PL>(L.pack[SIDE_W], L.planes, otile, tw, cp, r0, 128, L.colsP);
+        else if (epi == EPI_PACK) write_packs<PL>(L.pack[SIDE_W], L.planes, otile, tw, cp, r0, 128, L.colsP, 3, (epi_flags & EPI_KEPT) ? L.lzf[SIDE_W] : nullptr);
     }
 }
 

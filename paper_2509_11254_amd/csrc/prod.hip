@@ -213,7 +213,7 @@ __device__ inline void store_m8(const LayerDev& L, const TileAddr& a, const floa
 // thin result, then either the partial Gram matrix of these rows (fp64, upper triangle, slot = block
 // index) or the split-bf16 operand copies of the rows.  Called by all threads of the workgroup.
 __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int out_side, int ob, int out_len,
-                                     int out_lenP, int cp, int epi, const float* otile, int tw) {
+                                     int out_lenP, int cp, int epi, const float* otile, int tw, bool kept = false) {
     const int t = threadIdx.x;
     const int w = T.width;
     for (int e = t; e < BT * w; e += kThreads) {
@@ -223,7 +223,7 @@ __device__ inline void tile_epilogue(const LayerDev& L, const ThinRef& T, int ou
     if (epi == EPI_GRAM) {
         gram_tile_f64(otile, tw, BT, w, L.gram + (int64_t)ob * ((w * (w + 1)) / 2));
     } else if (epi == EPI_PACK) {
-        write_packs(L.pack[out_side], L.planes, otile, tw, cp, ob * BT, BT, out_lenP);
+        write_packs(L.pack[out_side], L.planes, otile, tw, cp, ob * BT, BT, out_lenP, 3, kept ? L.lzf[out_side] : nullptr);
     }
 }
 
@@ -631,7 +631,7 @@ __global__ __launch_bounds__(kThreads, (prod_lds_elems<NB, PL>(LAZY) * 4 <= 160 
             otile[row * tw + 32 * nb + li] = acc[nb][v];
         }
     __syncthreads();
-    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
+    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw, (epi_flags & EPI_KEPT) != 0);
 }
 
 // Sum of the partial products of a split launch + the same epilogue.  One workgroup per 128-row
@@ -717,7 +717,7 @@ __global__ __launch_bounds__(kThreads) void finish_kernel(const LayerDev* __rest
         else reduce_items(std::integral_constant<int, 1>{}, 0, n_items);
     }
     __syncthreads();
-    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw);
+    tile_epilogue(L, T, out_side, ob, out_len, out_lenP, cp, epi, otile, tw, (epi_flags & EPI_KEPT) != 0);
     if (epi == EPI_GRAM && chol_gate >= -1 && !local_chol(L, out_role, local_ok) && gate_open(L, chol_gate)) {
         const int n_wg = (out_len + BT - 1) / BT;      // = number of Gram slots (BT == kGramRows1)
         if (grouped_slot_sum(T.width, n_wg)) {

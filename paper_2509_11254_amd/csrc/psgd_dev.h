@@ -56,7 +56,8 @@ enum Side { SIDE_L = 0, SIDE_W = 1 };
 // blocks of the subspace iteration (leading dimension wz).
 // what a product's epilogue does besides storing the thin result
 enum Epilogue { EPI_NONE = 0, EPI_GRAM = 1, EPI_PACK = 2, EPI_KIND_MASK = 3,
-                EPI_KEEP_E = 16 };   // flag: a FORM pass uses M but leaves E in place (M is formed again later)
+                EPI_KEEP_E = 16,     // flag: a FORM pass uses M but leaves E in place (M is formed again later)
+                EPI_KEPT = 32 };     // flag: EPI_PACK writes the kept copies (fragment order) in place of the row-major ones
 enum Role { ROLE_P = 0, ROLE_Q = 1, ROLE_ZP = 2, ROLE_ZQ = 3, ROLE_COUNT = 4 };
 
 struct ThinRef {
@@ -162,12 +163,15 @@ __device__ inline void divmod_small(int v, int d, int& q, int& r) {
 // Operand copies of `nrows` finished rows held as an fp32 LDS tile [nrows][tw] (columns >= cp unused,
 // nrows and row0 multiples of 16); global rows row0 .. row0 + nrows - 1.  All threads of the workgroup take part.
 // which: 1 = the row-major copies only, 2 = the transposed ones only, 3 = both.
+// kept: the layer's lzf[side] where the result is a factor of a compress step whose residual is deferred: the pieces of
+// the row-major copies then go there instead, in fragment order (frag_piece), for the layers that have such copies.
 // PLT: the plane count as a compile-time constant where the caller has it (0: from `planes`, all kMaxPlanes are formed)
 template <int PLT = 0>
 __device__ inline void write_packs(const PackRef& K, int planes, const float* tile, int tw, int cp, int row0,
-                                   int nrows, int lenP, int which = 3) {
+                                   int nrows, int lenP, int which = 3, bf16_t* const* kept = nullptr) {
     constexpr int NPL = PLT > 0 ? PLT : kMaxPlanes;
     const int t = threadIdx.x;
+    const bool to_kept = kept && kept[0];
     for (int v = t; (which & 1) && v < nrows * (cp / 8); v += kThreads) {
         int row, g8;
         divmod_small(v, cp / 8, row, g8);
@@ -180,10 +184,10 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
 #pragma unroll
             for (int k = 0; k < NPL; ++k) o[k][u] = q[k];
         }
-        const int64_t off = (int64_t)(row0 + row) * cp + c0;
+        const int64_t off = to_kept ? frag_piece(row0 + row, g8, cp) * 8 : (int64_t)(row0 + row) * cp + c0;
 #pragma unroll
         for (int k = 0; k < NPL; ++k)
-            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.n[k]) + off) = o[k];
+            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(to_kept ? kept[k] : K.n[k]) + off) = o[k];
     }
     // fragment-order copy: the tile's rows are (nrows / 16) * (cp / 32) whole fragments, one run of consecutive memory
     // per plane; thread v writes the v-th 16-byte piece of that run (row0 and nrows are multiples of 16)

@@ -25,7 +25,7 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 // small for the kernels that also hold a tile of M or of the optimizer state, or that want more workgroups per CU
 template <int NB, int PL, int KGH = 2>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
 __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4],
-                                  bool kept = false) {
+                                  bool kept_asked = false) {
     constexpr int CPW = 32 * NB + 8;   // LDS row stride (bf16)
     constexpr int BPL = RT * CPW;      // one plane
     constexpr int KS = 2 * NB;         // k-steps of 16
@@ -38,9 +38,11 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     const int li = lane & 31, lg = lane >> 5;
     const PSGD_GLOBAL bf16_t* wk[PL];
     const PSGD_GLOBAL bf16_t* lk[PL];
+    // kept: the fragment-order copies that a compress step with a deferred residual leaves of its P~ and Q, in the
+    // layers that have them, instead of the row-major ones
+    const bool kept = kept_asked && L.lzf[SIDE_L][0] != nullptr;
 #pragma unroll
     for (int k = 0; k < PL; ++k) {
-        // kept: the operand copies put aside by the last compress step (deferred residual) instead of the current ones
         wk[k] = as_global(kept ? L.lzf[SIDE_W][k] : L.pack[SIDE_W].n[k]);
         lk[k] = as_global(kept ? L.lzf[SIDE_L][k] : L.pack[SIDE_L].n[k]);
     }
@@ -188,7 +190,7 @@ __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* _
 template <int NB, int PL>
 __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_kernel(const LayerDev* __restrict__ layers,
                                                               const int* __restrict__ ids, int cp,
-                                                              void* const* __restrict__ outs, int out_bf16) {
+                                                              void* const* __restrict__ outs, int out_bf16, int kept) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_k
     const int col = cb * RT + 4 * li;
     const int row_base = rb * RT + 32 * wv + 4 * lg;
     floatx16 acc[4];
-    outer_tile<NB, PL, 2>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL, 2>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (col >= L.cols) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -238,7 +240,7 @@ template <int NB, int PL>
 __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __restrict__ layers,
                                                            const int* __restrict__ ids, int cp,
                                                            float* const* __restrict__ moms,
-                                                           float* const* __restrict__ xs, float mu, float eta) {
+                                                           float* const* __restrict__ xs, float mu, float eta, int kept) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -269,7 +271,7 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -302,7 +304,7 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
                                                            const int* __restrict__ ids, int cp,
                                                            float* const* __restrict__ m1s,
                                                            float* const* __restrict__ m2s,
-                                                           float* const* __restrict__ xs, AdamArgs a) {
+                                                           float* const* __restrict__ xs, AdamArgs a, int kept) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -338,7 +340,7 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc);
+    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -394,7 +396,7 @@ static hipError_t launch_outer_nb(bool decomp, bool form, bool kept, const Layer
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16, kept ? 1 : 0);
     } else if (form) {
         auto kfn = residual_kernel<NB, PL, true>;
         if (lds > 48 * 1024) {
@@ -417,7 +419,7 @@ static hipError_t launch_outer_nb(bool decomp, bool form, bool kept, const Layer
 
 template <int NB, int PL>
 static hipError_t launch_msgd_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, float* const* moms,
-                                 float* const* xs, float mu, float eta, hipStream_t st) {
+                                 float* const* xs, float mu, float eta, bool kept, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
     auto kfn = msgd_kernel<NB, PL>;
@@ -426,18 +428,18 @@ static hipError_t launch_msgd_nb(const LayerDev* layers, const int* ids, int n_i
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, moms, xs, mu, eta);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, moms, xs, mu, eta, kept ? 1 : 0);
     return hipGetLastError();
 }
 
-// moms, xs: device arrays of per-layer device pointers
+// moms, xs: device arrays of per-layer device pointers; kept: as for launch_outer
 hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                       float* const* moms, float* const* xs, float mu, float eta, hipStream_t st) {
+                       float* const* moms, float* const* xs, float mu, float eta, bool kept, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
 #define PSGD_CASE(N)                                                                                       \
     case N:                                                                                                \
-        return planes == 2 ? launch_msgd_nb<N, 2>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st)   \
-                           : launch_msgd_nb<N, 3>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, st);
+        return planes == 2 ? launch_msgd_nb<N, 2>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, kept, st)   \
+                           : launch_msgd_nb<N, 3>(layers, ids, n_ids, max_tiles, moms, xs, mu, eta, kept, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;
@@ -447,7 +449,7 @@ hipError_t launch_msgd(int nb, int planes, const LayerDev* layers, const int* id
 
 template <int NB, int PL>
 static hipError_t launch_adam_nb(const LayerDev* layers, const int* ids, int n_ids, int max_tiles, float* const* m1s,
-                                 float* const* m2s, float* const* xs, const AdamArgs& a, hipStream_t st) {
+                                 float* const* m2s, float* const* xs, const AdamArgs& a, bool kept, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
     auto kfn = adam_kernel<NB, PL>;
@@ -456,20 +458,21 @@ static hipError_t launch_adam_nb(const LayerDev* layers, const int* ids, int n_i
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, m1s, m2s, xs, a);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, m1s, m2s, xs, a, kept ? 1 : 0);
     return hipGetLastError();
 }
 
 // m1s, m2s, xs: device arrays of per-layer device pointers; coef = {b1, b2, 1 - b1, 1 - b2, eta / (1 - b1^t),
 // 1 / sqrt(1 - b2^t), eps, eta * weight decay}
 hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* ids, int n_ids, int max_tiles,
-                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, hipStream_t st) {
+                       float* const* m1s, float* const* m2s, float* const* xs, const float* coef, bool kept,
+                       hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
     const AdamArgs a = {coef[0], coef[1], coef[2], coef[3], coef[4], coef[5], coef[6], coef[7]};
 #define PSGD_CASE(N)                                                                                       \
     case N:                                                                                                \
-        return planes == 2 ? launch_adam_nb<N, 2>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, st)     \
-                           : launch_adam_nb<N, 3>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, st);
+        return planes == 2 ? launch_adam_nb<N, 2>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, kept, st)     \
+                           : launch_adam_nb<N, 3>(layers, ids, n_ids, max_tiles, m1s, m2s, xs, a, kept, st);
     switch (nb) {
         PSGD_CASE(1) PSGD_CASE(2) PSGD_CASE(3) PSGD_CASE(4) PSGD_CASE(5) PSGD_CASE(6)
         default: return hipErrorInvalidValue;
@@ -477,7 +480,8 @@ hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* id
 #undef PSGD_CASE
 }
 
-// kept (residual only): subtract the product of the operand copies that the last compress step put aside
+// kept: the factors are the fragment-order copies that the last compress step left in the layers that defer their
+// residual (the row-major copies in the others)
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;

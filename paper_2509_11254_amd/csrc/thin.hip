@@ -86,39 +86,6 @@ hipError_t launch_max_iterations(const LayerDev* layers, const int* ids, int n_i
 }
 
 // --------------------------------------------------------------------------------------------
-// keep: put the operand copies of the compress step's P~ and Q aside (deferred residual), in the fragment order of an
-// outer-product operand: the next forming pass subtracts their product on the way, whatever has happened to the
-// current copies in between.  Thread by thread along the destination (consecutive 16-byte pieces).
-// --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void keep_kernel(const LayerDev* __restrict__ layers, const int* __restrict__ ids,
-                                                        int cp) {
-    const LayerDev& L = layers[ids[blockIdx.y]];
-    const int side = blockIdx.z;
-    const int64_t n16 = (int64_t)side_lenP(L, side) * cp / 8;       // 16-byte pieces per plane
-    const int g8n = cp / 8, ksn = cp / 16;                           // pieces per row; k-steps per 32-row block
-    for (int k = 0; k < L.planes; ++k) {
-        const PSGD_GLOBAL uintx4* src = reinterpret_cast<const PSGD_GLOBAL uintx4*>(as_global(L.pack[side].n[k]));
-        PSGD_GLOBAL uintx4* dstf = reinterpret_cast<PSGD_GLOBAL uintx4*>(as_global(L.lzf[side][k]));
-        for (int64_t i = (int64_t)blockIdx.x * kThreads + threadIdx.x; i < n16; i += (int64_t)gridDim.x * kThreads) {
-            const int ln = (int)(i & 63);
-            const int64_t frag = i >> 6;
-            const int64_t blk = frag / ksn;
-            const int ks = (int)(frag - blk * ksn);
-            const int64_t row = 32 * blk + (ln & 31);
-            dstf[i] = src[row * g8n + 2 * ks + (ln >> 5)];       // (= piece frag_piece(row, 2 ks + (ln >> 5), cp))
-        }
-    }
-}
-
-hipError_t launch_keep(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int cp, hipStream_t st) {
-    if (n_ids <= 0) return hipSuccess;
-    int blocks = (int)(((int64_t)max_lenP * cp / 8 + 4 * kThreads - 1) / (4 * kThreads));
-    if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(keep_kernel, dim3(blocks, n_ids, 2), dim3(kThreads), 0, st, layers, ids, cp);
-    return hipGetLastError();
-}
-
-// --------------------------------------------------------------------------------------------
 // chol: one workgroup per layer runs the factorisation on the partial Gram matrices that the producing
 // kernel has left (used when that kernel cannot hand over to it itself).
 // --------------------------------------------------------------------------------------------
@@ -394,7 +361,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const LayerDev* __restr
             if (last_to_arrive(&L.status[7], n_wg, &s_last)) chol_body<true>(L, dst_role, tol2, 2, kGramRows2, false, smem, L.tmat);
         }
     } else if (do_pack) {
-        write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which);
+        write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which & 3, (which & 4) ? L.lzf[side] : nullptr);
     }
 }
 
@@ -610,14 +577,15 @@ __global__ __launch_bounds__(kThreads) void apply_stream_kernel(const LayerDev* 
             }
         }
         if (do_gram) gram_tile_f64(so, ow, kGramRows2, w_out, L.gram + (int64_t)tile * ((w_out * (w_out + 1)) / 2));
-        else if (do_pack) write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which);
+        else if (do_pack) write_packs(L.pack[side], L.planes, so, ow, cp, i0, kGramRows2, lenP, which & 3, (which & 4) ? L.lzf[side] : nullptr);
         __syncthreads();
     }
 }
 
 // w_in / w_out: upper bounds of the operand widths over the addressed layers (LDS sizing only)
 // small: every layer of the launch is narrow (w_in <= 16) and the chain runs the per-workgroup factorisation
-// which: operand copies to leave when cp > 0 (1 = row-major, 2 = transposed, 3 = both)
+// which: operand copies to leave when cp > 0 (1 = row-major, 2 = transposed, 3 = both; + 4: the row-major pieces go to
+// the layer's kept copies in fragment order where it has them -- the P~ of a compress step with a deferred residual)
 hipError_t launch_apply(const LayerDev* layers, const int* ids, int n_ids, int max_lenP, int w_in, int w_out,
                         int src_role, int dst_role, int mode, int cp, int gate, int a2gate, double tol2,
                         bool small, int which, hipStream_t st) {
