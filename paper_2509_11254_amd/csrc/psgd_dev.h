@@ -174,7 +174,15 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
     const bool to_kept = kept && kept[0];
     for (int v = t; (which & 1) && v < nrows * (cp / 8); v += kThreads) {
         int row, g8;
-        divmod_small(v, cp / 8, row, g8);
+        if (to_kept) {
+            // along the destination: piece v of the tile's run of whole fragments (row0, nrows: multiples of 32)
+            int blk, ks;
+            divmod_small(v >> 6, cp >> 4, blk, ks);
+            row = 32 * blk + (v & 31);
+            g8 = 2 * ks + ((v >> 5) & 1);
+        } else {
+            divmod_small(v, cp / 8, row, g8);
+        }
         const int c0 = 8 * g8;
         bf16x8 o[NPL];
 #pragma unroll
