@@ -1141,8 +1141,15 @@ int psgd_decompress(psgd_ctx* ctx, void* workspace, void* stream, const float* c
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
-    L.note(launch_outer(nb, ctx->planes, true, false, packed && ctx->factors_kept, L.layers, L.ids_all, L.n_all, L.tiles_outer,
-                        reinterpret_cast<void* const*>(ws + ctx->off_outs), out_dtype == PSGD_BF16 ? 1 : 0, st));
+    // (factors of a compress call with a deferred residual: the layers that defer hold them as their kept copies)
+    const bool kept = packed && ctx->factors_kept;
+    const int n_kept = !kept ? 0 : ctx->lazy_tr ? L.n_all : L.n_norm;
+    const int* ids_kept = ctx->lazy_tr ? L.ids_all : L.ids_norm;
+    void* const* outs = reinterpret_cast<void* const*>(ws + ctx->off_outs);
+    const int obf = out_dtype == PSGD_BF16 ? 1 : 0;
+    if (n_kept > 0) L.note(launch_outer(nb, ctx->planes, true, false, true, L.layers, ids_kept, n_kept, L.tiles_outer, outs, obf, st));
+    if (!kept) L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_all, L.n_all, L.tiles_outer, outs, obf, st));
+    else if (!ctx->lazy_tr) L.note(launch_outer(nb, ctx->planes, true, false, false, L.layers, L.ids_tr, L.n_tr, L.tiles_outer, outs, obf, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -1170,9 +1177,14 @@ int psgd_decompress_msgd(psgd_ctx* ctx, void* workspace, void* stream, const flo
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
-    L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
-                       reinterpret_cast<float* const*>(ws + ctx->off_moms),
-                       reinterpret_cast<float* const*>(ws + ctx->off_xs), mu, eta, packed && ctx->factors_kept, st));
+    const bool kept = packed && ctx->factors_kept;      // (see psgd_decompress)
+    const int n_kept = !kept ? 0 : ctx->lazy_tr ? L.n_all : L.n_norm;
+    const int* ids_kept = ctx->lazy_tr ? L.ids_all : L.ids_norm;
+    float* const* dm = reinterpret_cast<float* const*>(ws + ctx->off_moms);
+    float* const* dx = reinterpret_cast<float* const*>(ws + ctx->off_xs);
+    if (n_kept > 0) L.note(launch_msgd(nb, ctx->planes, L.layers, ids_kept, n_kept, L.tiles_outer, dm, dx, mu, eta, true, st));
+    if (!kept) L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer, dm, dx, mu, eta, false, st));
+    else if (!ctx->lazy_tr) L.note(launch_msgd(nb, ctx->planes, L.layers, L.ids_tr, L.n_tr, L.tiles_outer, dm, dx, mu, eta, false, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }
@@ -1214,10 +1226,15 @@ int psgd_decompress_adam(psgd_ctx* ctx, void* workspace, void* stream, const flo
     Launcher L = batch_launcher(ctx, workspace, st);
     const int cp = ctx->cpc, nb = cp / 32;
     if (!packed) L.pack(ROLE_P, cp, Launcher::PACK_ROWMAJOR, ROLE_Q);
-    L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer,
-                       reinterpret_cast<float* const*>(ws + ctx->off_moms),
-                       reinterpret_cast<float* const*>(ws + ctx->off_m2s),
-                       reinterpret_cast<float* const*>(ws + ctx->off_xs), coef, packed && ctx->factors_kept, st));
+    const bool kept = packed && ctx->factors_kept;      // (see psgd_decompress)
+    const int n_kept = !kept ? 0 : ctx->lazy_tr ? L.n_all : L.n_norm;
+    const int* ids_kept = ctx->lazy_tr ? L.ids_all : L.ids_norm;
+    float* const* d1 = reinterpret_cast<float* const*>(ws + ctx->off_moms);
+    float* const* d2 = reinterpret_cast<float* const*>(ws + ctx->off_m2s);
+    float* const* dx = reinterpret_cast<float* const*>(ws + ctx->off_xs);
+    if (n_kept > 0) L.note(launch_adam(nb, ctx->planes, L.layers, ids_kept, n_kept, L.tiles_outer, d1, d2, dx, coef, true, st));
+    if (!kept) L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_all, L.n_all, L.tiles_outer, d1, d2, dx, coef, false, st));
+    else if (!ctx->lazy_tr) L.note(launch_adam(nb, ctx->planes, L.layers, L.ids_tr, L.n_tr, L.tiles_outer, d1, d2, dx, coef, false, st));
     if (L.err != hipSuccess) return fail_hip(ctx, L.err);
     return PSGD_OK;
 }

@@ -23,9 +23,10 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 
 // KGH = half the k-steps whose row operand is held in registers at a time with two planes (a quarter with three):
 // small for the kernels that also hold a tile of M or of the optimizer state, or that want more workgroups per CU
-template <int NB, int PL, int KGH = 2>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
+// KEPT: 0 = the row-major operand copies, 1 = the kept copies, 2 = as the argument says
+template <int NB, int PL, int KGH = 2, int KEPT = 0>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
 __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4],
-                                  bool kept_asked = false) {
+                                  bool kept_arg = false) {
     constexpr int CPW = 32 * NB + 8;   // LDS row stride (bf16)
     constexpr int BPL = RT * CPW;      // one plane
     constexpr int KS = 2 * NB;         // k-steps of 16
@@ -38,9 +39,9 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     const int li = lane & 31, lg = lane >> 5;
     const PSGD_GLOBAL bf16_t* wk[PL];
     const PSGD_GLOBAL bf16_t* lk[PL];
-    // kept: the fragment-order copies that a compress step with a deferred residual leaves of its P~ and Q, in the
-    // layers that have them, instead of the row-major ones
-    const bool kept = kept_asked && L.lzf[SIDE_L][0] != nullptr;
+    // kept: the fragment-order copies that a compress step with a deferred residual leaves of its P~ and Q (in the
+    // layers that defer: the launch addresses only those) instead of the row-major ones
+    const bool kept = KEPT == 1 || (KEPT == 2 && kept_arg);
 #pragma unroll
     for (int k = 0; k < PL; ++k) {
         wk[k] = as_global(kept ? L.lzf[SIDE_W][k] : L.pack[SIDE_W].n[k]);
@@ -70,8 +71,8 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
 #pragma unroll
         for (int i = 0; i < SB; ++i) {
             const int v = t + (i0 + i) * kThreads;
-            const int jj = v / (NB * 4), part = v % (NB * 4);
-            const int64_t goff = piece(cb * RT + jj, part);
+            // (kept copies: the tile's 128 rows are one run of whole fragments, thread v takes its v-th piece)
+            const int64_t goff = kept ? ((int64_t)cb * (RT / 32) * KS * 64 + v) * 8 : piece(cb * RT + v / (NB * 4), v % (NB * 4));
 #pragma unroll
             for (int k = 0; k < PL; ++k)
                 if (i0 + i < NI) tmp[i][k] = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(wk[k] + goff);
@@ -79,7 +80,12 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
 #pragma unroll
         for (int i = 0; i < SB; ++i) {
             const int v = t + (i0 + i) * kThreads;
-            const int jj = v / (NB * 4), part = v % (NB * 4);
+            int jj = v / (NB * 4), part = v % (NB * 4);
+            if (kept) {
+                const int frag = v >> 6, blk = frag / KS;
+                jj = 32 * blk + (v & 31);
+                part = 2 * (frag - blk * KS) + ((v >> 5) & 1);
+            }
             const int lrow = (jj & 3) * 32 + (jj >> 2);
 #pragma unroll
             for (int k = 0; k < PL; ++k)
@@ -164,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* _
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 1, 2>(L, rb, cb, cp, b_pl, acc, kept != 0);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -187,10 +193,10 @@ __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* _
 
 // Write-only: nothing but other workgroups' stores hides this one's operand round trip and MFMA phase, so as many
 // workgroups per compute unit as the operand tile in LDS allows (four at NB * PL <= 6).
-template <int NB, int PL>
+template <int NB, int PL, bool KEPT>
 __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_kernel(const LayerDev* __restrict__ layers,
                                                               const int* __restrict__ ids, int cp,
-                                                              void* const* __restrict__ outs, int out_bf16, int kept) {
+                                                              void* const* __restrict__ outs, int out_bf16) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -204,7 +210,7 @@ __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_k
     const int col = cb * RT + 4 * li;
     const int row_base = rb * RT + 32 * wv + 4 * lg;
     floatx16 acc[4];
-    outer_tile<NB, PL, 2>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 2, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
     if (col >= L.cols) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -236,11 +242,11 @@ __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_k
 
 // Decompress fused with the momentum-SGD update of Eq. (7c): Delta_hat never goes to memory.
 //   m_t = mu m_{t-1} + P~ Q^T,   X_{t+1} = X_t - eta m_t      (both rows x cols fp32 with the layer's ld, in place)
-template <int NB, int PL>
+template <int NB, int PL, bool KEPT>
 __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __restrict__ layers,
                                                            const int* __restrict__ ids, int cp,
                                                            float* const* __restrict__ moms,
-                                                           float* const* __restrict__ xs, float mu, float eta, int kept) {
+                                                           float* const* __restrict__ xs, float mu, float eta) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -271,7 +277,7 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -299,12 +305,12 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
 // with step = eta / (1 - b1^t), rs2 = 1 / sqrt(1 - b2^t), decay = eta lambda folded by the host.
 struct AdamArgs { float b1, b2, c1, c2, step, rs2, eps, decay; };
 
-template <int NB, int PL>
+template <int NB, int PL, bool KEPT>
 __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __restrict__ layers,
                                                            const int* __restrict__ ids, int cp,
                                                            float* const* __restrict__ m1s,
                                                            float* const* __restrict__ m2s,
-                                                           float* const* __restrict__ xs, AdamArgs a, int kept) {
+                                                           float* const* __restrict__ xs, AdamArgs a) {
     const int lid = ids[blockIdx.y];
     const LayerDev& L = layers[lid];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
@@ -340,7 +346,7 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -389,14 +395,16 @@ static hipError_t launch_outer_nb(bool decomp, bool form, bool kept, const Layer
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
     const int cp = 32 * NB;
+    // (kept copies exist up to width 128)
+    if (kept && NB > 4) return hipErrorInvalidValue;
     if (decomp) {
-        auto kfn = decompress_kernel<NB, PL>;
+        auto kfn = (kept && NB <= 4) ? decompress_kernel<NB, PL, (NB <= 4)> : decompress_kernel<NB, PL, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16, kept ? 1 : 0);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16);
     } else if (form) {
         auto kfn = residual_kernel<NB, PL, true>;
         if (lds > 48 * 1024) {
@@ -422,13 +430,14 @@ static hipError_t launch_msgd_nb(const LayerDev* layers, const int* ids, int n_i
                                  float* const* xs, float mu, float eta, bool kept, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
-    auto kfn = msgd_kernel<NB, PL>;
+    if (kept && NB > 4) return hipErrorInvalidValue;
+    auto kfn = (kept && NB <= 4) ? msgd_kernel<NB, PL, (NB <= 4)> : msgd_kernel<NB, PL, false>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, moms, xs, mu, eta, kept ? 1 : 0);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, moms, xs, mu, eta);
     return hipGetLastError();
 }
 
@@ -452,13 +461,14 @@ static hipError_t launch_adam_nb(const LayerDev* layers, const int* ids, int n_i
                                  float* const* m2s, float* const* xs, const AdamArgs& a, bool kept, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
     const size_t lds = outer_lds_bytes(NB, PL);
-    auto kfn = adam_kernel<NB, PL>;
+    if (kept && NB > 4) return hipErrorInvalidValue;
+    auto kfn = (kept && NB <= 4) ? adam_kernel<NB, PL, (NB <= 4)> : adam_kernel<NB, PL, false>;
     if (lds > 48 * 1024) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
     }
-    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, m1s, m2s, xs, a, kept ? 1 : 0);
+    hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, 32 * NB, m1s, m2s, xs, a);
     return hipGetLastError();
 }
 
@@ -480,8 +490,8 @@ hipError_t launch_adam(int nb, int planes, const LayerDev* layers, const int* id
 #undef PSGD_CASE
 }
 
-// kept: the factors are the fragment-order copies that the last compress step left in the layers that defer their
-// residual (the row-major copies in the others)
+// kept: the factors are the fragment-order copies that the last compress step left in the addressed layers (all of
+// them defer their residual)
 hipError_t launch_outer(int nb, int planes, bool decomp, bool form, bool kept, const LayerDev* layers, const int* ids,
                         int n_ids, int max_tiles, void* const* outs, int out_bf16, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;

@@ -190,14 +190,19 @@ def test_halves_on_degenerate_inputs():
     assert np.linalg.norm(e - (mat - p @ (p.T @ mat))) <= 1e-4 * np.linalg.norm(mat)
 
 
-def test_decompress_from_the_factors_of_the_last_compress_call():
+@pytest.mark.parametrize("opts,r", [({}, 32), (dict(lazy_residual=True), 32), (dict(lazy_residual=True), 48)],
+                         ids=["plain", "deferred_r32", "deferred_r48"])
+def test_decompress_from_the_factors_of_the_last_compress_call(opts, r):
     """P = Q = NULL in the decompress-type calls: the operand copies the last compress call left in the workspace.
-    Same bits as with the factors passed explicitly; refused when some other call wrote the copies last."""
+    Same bits as with the factors passed explicitly; refused when some other call wrote the copies last.
+    With the deferred residual the layers that defer hold those copies in another order (all three layers at rank 32,
+    the two stored with rows >= cols at rank 48)."""
     torch = torch_mod()
     wl = synth.scaled_down(synth.config3(), 256, 256)
+    wl.r = r
     wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c")]
     grads, errs, qs = _worker_inputs(wl, 51)
-    case = Case([(s.rows, s.cols) for s in wl.layers], wl.r, wl.n_workers, wl.grad_dtype)
+    case = Case([(s.rows, s.cols) for s in wl.layers], wl.r, wl.n_workers, wl.grad_dtype, **opts)
     case.upload(grads, [errs[l][0] for l in range(3)], qs)
     out_a = [torch.zeros_like(e) for e in case.E]
     out_b = [torch.zeros_like(e) for e in case.E]
