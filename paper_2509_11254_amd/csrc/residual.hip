@@ -23,10 +23,10 @@ template <int PL> __device__ inline bool keep_term(int ka, int kb) { return PL =
 
 // KGH = half the k-steps whose row operand is held in registers at a time with two planes (a quarter with three):
 // small for the kernels that also hold a tile of M or of the optimizer state, or that want more workgroups per CU
-// KEPT: 0 = the row-major operand copies, 1 = the kept copies, 2 = as the argument says
+// KEPT: the kept copies of a deferred-residual step instead of the row-major operand copies (a compile-time choice: as a
+// run-time one it cost the decompress kernel a tenth of its time)
 template <int NB, int PL, int KGH = 2, int KEPT = 0>   // cp = 32*NB columns of the thin operands (reduction length), PL bf16 planes
-__device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4],
-                                  bool kept_arg = false) {
+__device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf16_t* b_pl, floatx16 (&acc)[4]) {
     constexpr int CPW = 32 * NB + 8;   // LDS row stride (bf16)
     constexpr int BPL = RT * CPW;      // one plane
     constexpr int KS = 2 * NB;         // k-steps of 16
@@ -41,7 +41,7 @@ __device__ inline void outer_tile(const LayerDev& L, int rb, int cb, int cp, bf1
     const PSGD_GLOBAL bf16_t* lk[PL];
     // kept: the fragment-order copies that a compress step with a deferred residual leaves of its P~ and Q (in the
     // layers that defer: the launch addresses only those) instead of the row-major ones
-    const bool kept = KEPT == 1 || (KEPT == 2 && kept_arg);
+    constexpr bool kept = KEPT == 1;
 #pragma unroll
     for (int k = 0; k < PL; ++k) {
         wk[k] = as_global(kept ? L.lzf[SIDE_W][k] : L.pack[SIDE_W].n[k]);
@@ -132,9 +132,9 @@ __device__ inline floatx4 load_grad4(const LayerDev& L, int w, int64_t off) {
                    __uint_as_float(v.y & 0xffff0000u)};
 }
 
-template <int NB, int PL, bool FORM>
+template <int NB, int PL, bool FORM, bool KEPT>
 __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* __restrict__ layers,
-                                                                       const int* __restrict__ ids, int cp, int kept) {
+                                                                       const int* __restrict__ ids, int cp) {
     const LayerDev& L = layers[ids[blockIdx.y]];
     const int n_rb = (L.rows + RT - 1) / RT, n_cb = (L.cols + RT - 1) / RT;
     const int tile = blockIdx.x;
@@ -170,7 +170,7 @@ __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* _
         }
     }
     floatx16 acc[4];
-    outer_tile<NB, PL, 1, 2>(L, rb, cb, cp, b_pl, acc, kept != 0);
+    outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
     if (!col_ok) return;
     const bool full = col + 3 < L.cols;
 #pragma unroll
@@ -406,21 +406,22 @@ static hipError_t launch_outer_nb(bool decomp, bool form, bool kept, const Layer
         }
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, outs, out_bf16);
     } else if (form) {
-        auto kfn = residual_kernel<NB, PL, true>;
+        if (kept) return hipErrorInvalidValue;      // (the deferred residual lives in the stored M)
+        auto kfn = residual_kernel<NB, PL, true, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, kept ? 1 : 0);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
     } else {
-        auto kfn = residual_kernel<NB, PL, false>;
+        auto kfn = (kept && NB <= 4) ? residual_kernel<NB, PL, false, (NB <= 4)> : residual_kernel<NB, PL, false, false>;
         if (lds > 48 * 1024) {
             hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn),
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return e;
         }
-        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp, kept ? 1 : 0);
+        hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, cp);
     }
     return hipGetLastError();
 }
