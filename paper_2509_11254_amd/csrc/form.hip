@@ -122,16 +122,19 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         tile = s - pre[j];
     }
     const LayerDev& L = layers[ids[layer_pos]];
+    // (what the loop needs of the layer is read here, once: the loop stores M, and the compiler reads a value again
+    // after every store that might have changed it -- a round trip to the scalar cache in front of the loads of the next tile)
+    const int rows = L.rows, cols = L.cols;
     const bool store_m = !(epi_flags & EPI_KEEP_E);
     const int n_ob = L.rowsP / FR;                       // (row blocks past the end write the zeros of the padding)
     const int n_split = L.split_row_v2;
     if (tile >= n_ob * n_split) return;
     const int sp = tile % n_split, ob = tile / n_split;
     const int row0 = ob * FR;
-    const int n_chunks = (L.cols + FK - 1) / FK;
+    const int n_chunks = (cols + FK - 1) / FK;
     const int cps = (n_chunks + n_split - 1) / n_split;
     const int ch0 = sp * cps;
-    const int n_loc = row0 < L.rows ? max(min(n_chunks, ch0 + cps) - ch0, 0) : 0;
+    const int n_loc = row0 < rows ? max(min(n_chunks, ch0 + cps) - ch0, 0) : 0;
 
     extern __shared__ __align__(16) unsigned char smem[];
     bf16_t* a_pl = reinterpret_cast<bf16_t*>(smem);                              // ABUF x PL planes of [FR][FLD]
@@ -151,9 +154,11 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     const int64_t wave_off = (int64_t)(row0 + wv) * ld;       // (uniform)
     const int64_t ustep = 4 * ld;
     const unsigned lane_e = 16u * (unsigned)lane, lane_g = (unsigned)sizeof(GV) * (unsigned)lane, lane_f = 16u * (unsigned)lane;
-    auto grad_ptr = [&](int w) { return reinterpret_cast<const PSGD_GLOBAL GT*>(as_global(as_global(L.G)[w])); };
-    auto tile_full = [&](int ch) { return row0 + FR <= L.rows && ch * FK + FK <= L.cols; };
-    auto piece_ok = [&](int ch, int u) { return row0 + 4 * u + wv < L.rows && ch * FK + 4 * lane < L.cols; };
+    const auto gtab = as_global(L.G);
+    const PSGD_GLOBAL GT* const g_first = reinterpret_cast<const PSGD_GLOBAL GT*>(as_global(gtab[0]));
+    auto grad_ptr = [&](int w) { return w == 0 ? g_first : reinterpret_cast<const PSGD_GLOBAL GT*>(as_global(gtab[w])); };
+    auto tile_full = [&](int ch) { return row0 + FR <= rows && ch * FK + FK <= cols; };
+    auto piece_ok = [&](int ch, int u) { return row0 + 4 * u + wv < rows && ch * FK + 4 * lane < cols; };
     auto load_g = [&](int w, int ch, GV (&x)[8]) {
         const PSGD_GLOBAL GT* gp = grad_ptr(w) + wave_off + (int64_t)ch * FK;
         auto at = [&](int u) { return reinterpret_cast<const PSGD_GLOBAL GV*>(reinterpret_cast<const PSGD_GLOBAL char*>(gp + u * ustep) + lane_g); };
@@ -216,6 +221,9 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     // the next tile's own loads (the wait counter is in issue order: fragments requested after the tile could only be
     // used once the tile had arrived).
     bf16x8 qv[LAZY ? 2 : 1][LAZY ? 2 * NB : 1][PL];
+    const PSGD_GLOBAL bf16_t* kept_w[PL];
+#pragma unroll
+    for (int k = 0; k < PL; ++k) kept_w[k] = LAZY ? as_global(L.lzf[SIDE_W][k]) : nullptr;
     auto load_q = [&](int ch, int q) {
         {
             // 32-column block of the kept Q copy; past the padded length the last block, whose product lands on
@@ -226,7 +234,7 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
 #pragma unroll
                 for (int k = 0; k < PL; ++k)
                     qv[q][ks][k] = *reinterpret_cast<const PSGD_GLOBAL bf16x8*>(
-                        reinterpret_cast<const PSGD_GLOBAL char*>(as_global(L.lzf[SIDE_W][k]) + ((int64_t)cblk * (2 * NB) + ks) * 512) + lane_f);
+                        reinterpret_cast<const PSGD_GLOBAL char*>(kept_w[k] + ((int64_t)cblk * (2 * NB) + ks) * 512) + lane_f);
         }
     };
     auto correction = [&](int q) {
@@ -328,7 +336,7 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         if (!full) {
             // pieces outside the matrix were loaded as zero; cut the column tail (the padding up to ld is not data)
             const int c = ch * FK + 4 * lane;
-            const bool k0 = c < L.cols, k1 = c + 1 < L.cols, k2 = c + 2 < L.cols, k3 = c + 3 < L.cols;
+            const bool k0 = c < cols, k1 = c + 1 < cols, k2 = c + 2 < cols, k3 = c + 3 < cols;
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 m[u].x = k0 ? m[u].x : 0.f;           // (LAZY: the correction is not zero there)
@@ -355,12 +363,12 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
                 for (int u = 0; u < 8; ++u) {
                     if (!piece_ok(ch, u)) continue;
                     PSGD_GLOBAL float* p = at(u);
-                    if (c + 3 < L.cols) {
+                    if (c + 3 < cols) {
                         *reinterpret_cast<PSGD_GLOBAL floatx4*>(p) = m[u];
                     } else {
                         p[0] = m[u].x;
-                        if (c + 1 < L.cols) p[1] = m[u].y;
-                        if (c + 2 < L.cols) p[2] = m[u].z;
+                        if (c + 1 < cols) p[1] = m[u].y;
+                        if (c + 2 < cols) p[2] = m[u].z;
                     }
                 }
             }

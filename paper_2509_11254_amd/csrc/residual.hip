@@ -13,6 +13,8 @@
 // MFMA block q, column lane i is bound to matrix column 4*i + q, so that after the four blocks each
 // lane holds 4 consecutive columns of 16 rows: S is then read and written with 16-byte accesses
 // straight from/to the accumulator layout and never goes through LDS.
+#include <type_traits>
+
 #include "psgd_dev.h"
 
 namespace psgd {
@@ -145,48 +147,67 @@ __global__ __launch_bounds__(kThreads, 2) void residual_kernel(const LayerDev* _
 
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int li = lane & 31, lg = lane >> 5;
+    // (the layer's numbers are read once, here: the compiler cannot move a scalar load across a store that might alias
+    // it, and read in place every store of the epilogue waited for a round trip to the scalar cache of its own)
+    const int rows = L.rows, cols = L.cols;
+    const int64_t ld = L.ld;
     const int col = cb * RT + 4 * li;
-    const bool col_ok = col < L.cols;
+    const bool col_ok = col < cols;
+    const bool interior = rb * RT + RT <= rows && cb * RT + RT <= cols;     // (uniform) nothing to decide per lane
     // issue the 16 loads of M first; the operand staging and the MFMAs hide their latency
     // addresses = uniform base of tile row 8*(v>>2) + (v&3) (scalar registers) + one per-lane offset
-    PSGD_GLOBAL float* tile0 = as_global(L.S) + (int64_t)(rb * RT) * L.ld + cb * RT;
-    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    PSGD_GLOBAL float* tile0 = as_global(L.S) + (int64_t)(rb * RT) * ld + cb * RT;
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)ld + 4 * li) * 4u;   // < 2^32: 128 rows
     const int row_lane = rb * RT + 32 * wv + 4 * lg;
+    auto at = [&](int k) {
+        return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(tile0 + (int64_t)k * ld) + lane_byte);
+    };
     floatx4 m[16];
+    auto load_m = [&](auto whole) {
+        const int nw = FORM ? L.n_workers : 1;
+        const float inv_n = 1.0f / (float)nw;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = 8 * (v >> 2) + (v & 3);
-        m[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (col_ok && row_lane + k < L.rows) {
-            m[v] = ld_stream<NT_M_RES>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(
-                reinterpret_cast<const PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte));
-            if (FORM) {
-                // same arithmetic and order as the product kernel's FORM path: (sum of workers) / N + E
-                const int64_t off = (int64_t)(rb * RT + k) * L.ld + cb * RT + (lane_byte >> 2);
-                floatx4 g = load_grad4(L, 0, off);
-                for (int w = 1; w < L.n_workers; ++w) g += load_grad4(L, w, off);
-                m[v] = g * (1.0f / (float)L.n_workers) + m[v];
+        for (int v = 0; v < 16; ++v) {
+            const int k = 8 * (v >> 2) + (v & 3);
+            m[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (decltype(whole)::value || (col_ok && row_lane + k < rows)) {
+                m[v] = ld_stream<NT_M_RES>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(k)));
+                if (FORM) {
+                    // same arithmetic and order as the product kernel's FORM path: (sum of workers) / N + E
+                    const int64_t off = (int64_t)(rb * RT + k) * ld + cb * RT + (lane_byte >> 2);
+                    floatx4 g = load_grad4(L, 0, off);
+                    for (int w = 1; w < nw; ++w) g += load_grad4(L, w, off);
+                    m[v] = g * inv_n + m[v];
+                }
             }
         }
-    }
+    };
+    if (interior) load_m(std::true_type{}); else load_m(std::false_type{});
     floatx16 acc[4];
     outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
+    if (interior) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const floatx4 e = {m[v].x - acc[0][v], m[v].y - acc[1][v], m[v].z - acc[2][v], m[v].w - acc[3][v]};
+            st_stream<NT_E_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(8 * (v >> 2) + (v & 3))), e);
+        }
+        return;
+    }
     if (!col_ok) return;
-    const bool full = col + 3 < L.cols;
+    const bool full = col + 3 < cols;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int k = 8 * (v >> 2) + (v & 3);
-        if (row_lane + k >= L.rows) continue;
+        if (row_lane + k >= rows) continue;
         floatx4 e;
         e.x = m[v].x - acc[0][v]; e.y = m[v].y - acc[1][v]; e.z = m[v].z - acc[2][v]; e.w = m[v].w - acc[3][v];
-        PSGD_GLOBAL float* p = reinterpret_cast<PSGD_GLOBAL float*>(
-            reinterpret_cast<PSGD_GLOBAL char*>(tile0 + (int64_t)k * L.ld) + lane_byte);
+        PSGD_GLOBAL float* p = at(k);
         if (full) {
             st_stream<NT_E_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), e);
         } else {
             p[0] = e.x;
-            if (col + 1 < L.cols) p[1] = e.y;
-            if (col + 2 < L.cols) p[2] = e.z;
+            if (col + 1 < cols) p[1] = e.y;
+            if (col + 2 < cols) p[2] = e.z;
         }
     }
 }
@@ -209,32 +230,58 @@ __global__ __launch_bounds__(kThreads, (NB * PL <= 6 ? 4 : 2)) void decompress_k
     const int li = lane & 31, lg = lane >> 5;
     const int col = cb * RT + 4 * li;
     const int row_base = rb * RT + 32 * wv + 4 * lg;
+    // (what the stores need is read before them: the compiler cannot move a scalar load across a store that might
+    // alias it, and left in place every one of the 16 stores waited for its own round trip to the scalar cache)
+    const int rows = L.rows, cols = L.cols;
+    const int64_t ld = L.ld;
+    void* const outp = outs[lid];
     floatx16 acc[4];
     outer_tile<NB, PL, 2, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
-    if (col >= L.cols) return;
-    const bool full = col + 3 < L.cols;
+    const int64_t off0 = (int64_t)row_base * ld + col;
+    if (rb * RT + RT <= rows && cb * RT + RT <= cols) {
+        // interior tile: sixteen stores, nothing to decide
+        if (out_bf16) {
+            PSGD_GLOBAL bf16_t* p = as_global(reinterpret_cast<bf16_t*>(outp)) + off0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                bf16x4 o;
+                o[0] = (bf16_t)acc[0][v]; o[1] = (bf16_t)acc[1][v]; o[2] = (bf16_t)acc[2][v]; o[3] = (bf16_t)acc[3][v];
+                st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL bf16x4*>(p + (int64_t)(8 * (v >> 2) + (v & 3)) * ld), o);
+            }
+        } else {
+            PSGD_GLOBAL float* p = as_global(reinterpret_cast<float*>(outp)) + off0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const floatx4 o = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+                st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p + (int64_t)(8 * (v >> 2) + (v & 3)) * ld), o);
+            }
+        }
+        return;
+    }
+    if (col >= cols) return;
+    const bool full = col + 3 < cols;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int row = row_base + 8 * (v >> 2) + (v & 3);
-        if (row >= L.rows) continue;
+        if (row >= rows) continue;
         const float d[4] = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-        const int64_t off = (int64_t)row * L.ld + col;
+        const int64_t off = (int64_t)row * ld + col;
         if (out_bf16) {
-            PSGD_GLOBAL bf16_t* p = as_global(reinterpret_cast<bf16_t*>(outs[lid])) + off;
+            PSGD_GLOBAL bf16_t* p = as_global(reinterpret_cast<bf16_t*>(outp)) + off;
             if (full) {
                 bf16x4 o;
                 o[0] = (bf16_t)d[0]; o[1] = (bf16_t)d[1]; o[2] = (bf16_t)d[2]; o[3] = (bf16_t)d[3];
                 st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL bf16x4*>(p), o);
             } else {
-                for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = (bf16_t)d[q];
+                for (int q = 0; q < 4; ++q) if (col + q < cols) p[q] = (bf16_t)d[q];
             }
         } else {
-            PSGD_GLOBAL float* p = as_global(reinterpret_cast<float*>(outs[lid])) + off;
+            PSGD_GLOBAL float* p = as_global(reinterpret_cast<float*>(outp)) + off;
             if (full) {
                 floatx4 o = {d[0], d[1], d[2], d[3]};
                 st_stream<NT_DEC>(reinterpret_cast<PSGD_GLOBAL floatx4*>(p), o);
             } else {
-                for (int q = 0; q < 4; ++q) if (col + q < L.cols) p[q] = d[q];
+                for (int q = 0; q < 4; ++q) if (col + q < cols) p[q] = d[q];
             }
         }
     }
@@ -257,44 +304,65 @@ __global__ __launch_bounds__(kThreads, 2) void msgd_kernel(const LayerDev* __res
     bf16_t* b_pl = reinterpret_cast<bf16_t*>(smem);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int li = lane & 31, lg = lane >> 5;
+    const int rows = L.rows, cols = L.cols;          // (read once, before any store: see residual_kernel)
+    const int64_t ld = L.ld;
     const int col = cb * RT + 4 * li;
-    const bool col_ok = col < L.cols;
-    const int64_t tile_off = (int64_t)(rb * RT) * L.ld + cb * RT;
+    const bool col_ok = col < cols;
+    const bool interior = rb * RT + RT <= rows && cb * RT + RT <= cols;
+    const int64_t tile_off = (int64_t)(rb * RT) * ld + cb * RT;
     PSGD_GLOBAL float* m0 = as_global(moms[lid]) + tile_off;
     PSGD_GLOBAL float* x0 = as_global(xs[lid]) + tile_off;
-    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)ld + 4 * li) * 4u;   // < 2^32: 128 rows
     const int row_lane = rb * RT + 32 * wv + 4 * lg;
+    auto at = [&](PSGD_GLOBAL float* base, int k) {
+        return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(base + (int64_t)k * ld) + lane_byte);
+    };
     // momentum and weights of the tile are requested first; the operand staging and the MFMAs hide the latency
     floatx4 mo[16], xo[16];
+    auto load_state = [&](auto whole) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = 8 * (v >> 2) + (v & 3);
-        mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        xo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (col_ok && row_lane + k < L.rows) {
-            mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte));
-            xo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(reinterpret_cast<const PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte));
+        for (int v = 0; v < 16; ++v) {
+            const int k = 8 * (v >> 2) + (v & 3);
+            mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            xo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (decltype(whole)::value || (col_ok && row_lane + k < rows)) {
+                mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(m0, k)));
+                xo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(x0, k)));
+            }
         }
-    }
+    };
+    if (interior) load_state(std::true_type{}); else load_state(std::false_type{});
     floatx16 acc[4];
     outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
+    if (interior) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int k = 8 * (v >> 2) + (v & 3);
+            const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+            const floatx4 mn = mo[v] * mu + d;
+            const floatx4 xn = xo[v] - mn * eta;
+            st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(m0, k)), mn);
+            st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(x0, k)), xn);
+        }
+        return;
+    }
     if (!col_ok) return;
-    const bool full = col + 3 < L.cols;
+    const bool full = col + 3 < cols;
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int k = 8 * (v >> 2) + (v & 3);
-        if (row_lane + k >= L.rows) continue;
+        if (row_lane + k >= rows) continue;
         const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
         const floatx4 mn = mo[v] * mu + d;
         const floatx4 xn = xo[v] - mn * eta;
-        PSGD_GLOBAL float* pm = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(m0 + (int64_t)k * L.ld) + lane_byte);
-        PSGD_GLOBAL float* px = reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(x0 + (int64_t)k * L.ld) + lane_byte);
+        PSGD_GLOBAL float* pm = at(m0, k);
+        PSGD_GLOBAL float* px = at(x0, k);
         if (full) {
             st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(pm), mn);
             st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(px), xn);
         } else {
             for (int q = 0; q < 4; ++q)
-                if (col + q < L.cols) { pm[q] = mn[q]; px[q] = xn[q]; }
+                if (col + q < cols) { pm[q] = mn[q]; px[q] = xn[q]; }
         }
     }
 }
@@ -321,34 +389,66 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
     bf16_t* b_pl = reinterpret_cast<bf16_t*>(smem);
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int li = lane & 31, lg = lane >> 5;
+    const int rows = L.rows, cols = L.cols;          // (read once, before any store: see residual_kernel)
+    const int64_t ld = L.ld;
     const int col = cb * RT + 4 * li;
-    const bool col_ok = col < L.cols;
-    const int64_t tile_off = (int64_t)(rb * RT) * L.ld + cb * RT;
+    const bool col_ok = col < cols;
+    const bool interior = rb * RT + RT <= rows && cb * RT + RT <= cols;
+    const int64_t tile_off = (int64_t)(rb * RT) * ld + cb * RT;
     PSGD_GLOBAL float* m0 = as_global(m1s[lid]) + tile_off;
     PSGD_GLOBAL float* v0 = as_global(m2s[lid]) + tile_off;
     PSGD_GLOBAL float* x0 = as_global(xs[lid]) + tile_off;
-    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)L.ld + 4 * li) * 4u;   // < 2^32: 128 rows
+    const unsigned lane_byte = ((unsigned)(32 * wv + 4 * lg) * (unsigned)ld + 4 * li) * 4u;   // < 2^32: 128 rows
     const int row_lane = rb * RT + 32 * wv + 4 * lg;
     auto at = [&](PSGD_GLOBAL float* base, int k) {
-        return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(base + (int64_t)k * L.ld) + lane_byte);
+        return reinterpret_cast<PSGD_GLOBAL float*>(reinterpret_cast<PSGD_GLOBAL char*>(base + (int64_t)k * ld) + lane_byte);
     };
     // the two moments of the tile are requested before the product (its staging and MFMAs hide their latency);
     // the weights, needed last, are read in the epilogue
     floatx4 mo[16], vo[16];
+    auto load_state = [&](auto whole) {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int k = 8 * (v >> 2) + (v & 3);
-        mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        vo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
-        if (col_ok && row_lane + k < L.rows) {
-            mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(m0, k)));
-            vo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(v0, k)));
+        for (int v = 0; v < 16; ++v) {
+            const int k = 8 * (v >> 2) + (v & 3);
+            mo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            vo[v] = floatx4{0.f, 0.f, 0.f, 0.f};
+            if (decltype(whole)::value || (col_ok && row_lane + k < rows)) {
+                mo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(m0, k)));
+                vo[v] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(v0, k)));
+            }
         }
-    }
+    };
+    if (interior) load_state(std::true_type{}); else load_state(std::false_type{});
     floatx16 acc[4];
     outer_tile<NB, PL, 1, KEPT ? 1 : 0>(L, rb, cb, cp, b_pl, acc);
+    auto update = [&](int v, const floatx4& xo, floatx4& mn, floatx4& vn, floatx4& xn) {
+        const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
+        mn = mo[v] * a.b1 + d * a.c1;
+        vn = vo[v] * a.b2 + (d * d) * a.c2;
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            xn[q] = xo[q] - a.step * (mn[q] / (sqrtf(vn[q]) * a.rs2 + a.eps)) - a.decay * xo[q];
+    };
+    if (interior) {
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            floatx4 xo[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) xo[u] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(x0, 8 * g + u)));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int v = 4 * g + u, k = 8 * g + u;
+                floatx4 mn, vn, xn;
+                update(v, xo[u], mn, vn, xn);
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(m0, k)), mn);
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(v0, k)), vn);
+                st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(at(x0, k)), xn);
+            }
+        }
+        return;
+    }
     if (!col_ok) return;
-    const bool full = col + 3 < L.cols;
+    const bool full = col + 3 < cols;
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
         floatx4 xo[4];
@@ -356,22 +456,17 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
         for (int u = 0; u < 4; ++u) {
             const int k = 8 * g + u;
             xo[u] = floatx4{0.f, 0.f, 0.f, 0.f};
-            if (row_lane + k < L.rows) {
+            if (row_lane + k < rows) {
                 if (full) xo[u] = ld_stream<NT_OPT_IN>(reinterpret_cast<const PSGD_GLOBAL floatx4*>(at(x0, k)));
-                else for (int q = 0; q < 4; ++q) if (col + q < L.cols) xo[u][q] = at(x0, k)[q];
+                else for (int q = 0; q < 4; ++q) if (col + q < cols) xo[u][q] = at(x0, k)[q];
             }
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int v = 4 * g + u, k = 8 * g + u;
-            if (row_lane + k >= L.rows) continue;
-            const floatx4 d = {acc[0][v], acc[1][v], acc[2][v], acc[3][v]};
-            const floatx4 mn = mo[v] * a.b1 + d * a.c1;
-            const floatx4 vn = vo[v] * a.b2 + (d * d) * a.c2;
-            floatx4 xn;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                xn[q] = xo[u][q] - a.step * (mn[q] / (sqrtf(vn[q]) * a.rs2 + a.eps)) - a.decay * xo[u][q];
+            if (row_lane + k >= rows) continue;
+            floatx4 mn, vn, xn;
+            update(v, xo[u], mn, vn, xn);
             PSGD_GLOBAL float* pm = at(m0, k);
             PSGD_GLOBAL float* pv = at(v0, k);
             PSGD_GLOBAL float* px = at(x0, k);
@@ -381,7 +476,7 @@ __global__ __launch_bounds__(kThreads, 2) void adam_kernel(const LayerDev* __res
                 st_stream<NT_OPT_OUT>(reinterpret_cast<PSGD_GLOBAL floatx4*>(px), xn);
             } else {
                 for (int q = 0; q < 4; ++q)
-                    if (col + q < L.cols) { pm[q] = mn[q]; pv[q] = vn[q]; px[q] = xn[q]; }
+                    if (col + q < cols) { pm[q] = mn[q]; pv[q] = vn[q]; px[q] = xn[q]; }
             }
         }
     }
