@@ -172,6 +172,14 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
     constexpr int NPL = PLT > 0 ? PLT : kMaxPlanes;
     const int t = threadIdx.x;
     const bool to_kept = kept && kept[0];
+    // (the destinations are read before the first store: after one, the compiler would read them again)
+    PSGD_GLOBAL bf16_t* dn[NPL];
+    PSGD_GLOBAL bf16_t* dt[NPL];
+#pragma unroll
+    for (int k = 0; k < NPL; ++k) {
+        dn[k] = k < planes ? as_global(to_kept ? kept[k] : K.n[k]) : nullptr;
+        dt[k] = k < planes ? as_global(K.t[k]) : nullptr;
+    }
     for (int v = t; (which & 1) && v < nrows * (cp / 8); v += kThreads) {
         int row, g8;
         if (to_kept) {
@@ -195,7 +203,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         const int64_t off = to_kept ? frag_piece(row0 + row, g8, cp) * 8 : (int64_t)(row0 + row) * cp + c0;
 #pragma unroll
         for (int k = 0; k < NPL; ++k)
-            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(to_kept ? kept[k] : K.n[k]) + off) = o[k];
+            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(dn[k] + off) = o[k];
     }
     // fragment-order copy: the tile's rows are (nrows / 16) * (cp / 32) whole fragments, one run of consecutive memory
     // per plane; thread v writes the v-th 16-byte piece of that run (row0 and nrows are multiples of 16)
@@ -215,7 +223,7 @@ __device__ inline void write_packs(const PackRef& K, int planes, const float* ti
         const int64_t off = pack_t_offset(row0 + ib, c, cp);      // (= 8 * (first piece of the tile + v))
 #pragma unroll
         for (int k = 0; k < NPL; ++k)
-            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(as_global(K.t[k]) + off) = o[k];
+            if (k < planes) *reinterpret_cast<PSGD_GLOBAL bf16x8*>(dt[k] + off) = o[k];
     }
 }
 
