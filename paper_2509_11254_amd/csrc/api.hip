@@ -18,7 +18,7 @@
 namespace psgd {
 hipError_t launch_prod(int nb, int planes, bool colmode, bool form, bool lazy, bool onew, const LayerDev* layers,
                        const int* ids, int n_ids, int max_tiles, int out_role, int epi, int gate, hipStream_t st);
-hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids,
+hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, int lazy, const LayerDev* layers, const int* ids,
                            int n_ids, int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
                            int xtiles, hipStream_t st);
 bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy);
@@ -405,6 +405,8 @@ struct Launcher {
     int gate = -1;            // iteration gate of the launches inside the subspace iteration (-1: none)
     bool keep_e = false;      // FORM products leave E in place (M is formed again by the later passes)
     bool lazy_form = false;   // the forming pass of the row-major layers also applies their pending residual
+    bool lazy_share = false;  // ... and the transposed operand copies of Q_{t-1} are what the step before left: they hold
+                              // the kept Q, which the pass then need not read
     bool kept_packs = false;  // compress step with a deferred residual: the row-major operand copies of its P~ and Q go
                               // to the kept copies (fragment order) in the layers that have them
     bool use_form_row = true; // PSGD_FORM_ROW=0 (environment, measurement knob): the older 128 x 64 forming pass
@@ -456,7 +458,7 @@ struct Launcher {
                                 ? reinterpret_cast<const int*>(ws + ctx->off_xtab_c) : nullptr;
         if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, xtab_c, ctx->xstride, ctx->xtiles_c, st));
         else if (r2) note(launch_row_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), gate, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
-        else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
+        else if (v2) note(launch_form_row(nb, ctx->planes, ctx->grad_kind == 2, onew, lazy_form ? (lazy_share ? 2 : 1) : 0, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
         else note(launch_prod(nb, ctx->planes, !p_like, form, form && p_like && lazy_form, onew, layers, ids_norm, n_norm, p_like ? tiles_row : tiles_col, out_role, ef, gate, st));
         note(launch_prod(nb, ctx->planes, p_like, form, form && p_like && lazy_form && ctx->lazy_tr, onew, layers, ids_tr, n_tr, p_like ? tiles_col : tiles_row, out_role, ef, gate, st));
         prof_end(k);
@@ -874,6 +876,7 @@ int psgd_compress(psgd_ctx* ctx, void* workspace, void* stream, const void* cons
     for (int k = 0; k < K; ++k) {
         L.keep_e = re;
         L.lazy_form = ctx->pending;            // E of the row-major layers is M_{t-1} - (kept P~)(kept Q)^T
+        L.lazy_share = q_in_place;
         L.prod_orth(true, k == 0 || re, nb, ROLE_P, ctx->rmax, tol2_of(ctx), cp, 0, Launcher::PASS2_ALWAYS);
         if (k == 0) ctx->pending = false;      // the buffers hold M_t from here on
         L.lazy_form = false;

@@ -34,8 +34,8 @@ __device__ inline floatx4 widen4(uintx2 v) {
 }
 __device__ inline floatx4 widen4(floatx4 v) { return v; }
 
-template <int NB, int PL, bool LAZY> constexpr int form_abuf() { return (PL == 2 && !LAZY) ? 2 : 1; }
-template <int NB, int PL, bool LAZY> constexpr size_t form_lds_bytes() {
+template <int NB, int PL, int LAZY> constexpr int form_abuf() { return (PL == 2 && !LAZY) ? 2 : 1; }
+template <int NB, int PL, int LAZY> constexpr size_t form_lds_bytes() {
     const size_t a = (size_t)form_abuf<NB, PL, LAZY>() * PL * FR * FLD * sizeof(bf16_t);
     const size_t d = LAZY ? (size_t)FR * FDW * sizeof(float) + (size_t)2 * NB * PL * 64 * 8 * sizeof(bf16_t) : 0;
     const size_t red = (size_t)4 * FR * (32 * NB + 1) * sizeof(float);
@@ -95,8 +95,10 @@ __device__ inline void row_epilogue(unsigned char* smem, const floatx16 (&acc)[N
 }
 
 // GBF: the gradients are bf16 (else fp32); ONEW: one worker (no loop over further gradient buffers);
-// LAZY: the residual of the previous compress step is applied on the way in.
-template <int NB, int PL, bool GBF, bool ONEW, bool LAZY>
+// LAZY: the residual of the previous compress step is applied on the way in (1), and with 2 the kept Q is not read
+// at all: the caller vouches that the transposed operand copies of Q_{t-1}, which the product reads anyway, hold the
+// same numbers, and the correction's operand is made from those fragments in registers (see correction_shared).
+template <int NB, int PL, bool GBF, bool ONEW, int LAZY>
 __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* __restrict__ layers,
                                                                 const int* __restrict__ ids, int out_role,
                                                                 int epi_flags, int nt_m,
@@ -201,9 +203,8 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     // thin operand: this wave's fragments for its 64 columns of the step, four k-steps of 16
     const PackRef XK = L.pack[SIDE_W];
     bf16x8 bfrag[4][NB][PL];
-    auto load_b = [&](int ch) {
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
+    auto load_b_ks = [&](int ch, int ks, bf16x8 (&bfrag)[4][NB][PL]) {
+        {
             // (past the padded length the fragment of the last k-step is read instead: M is zero there, and the
             // operand copies hold finite numbers)
             const int kg = min(ch * (FK / 16) + 4 * wv + ks, colsP / 16 - 1);
@@ -215,15 +216,20 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
                         reinterpret_cast<const PSGD_GLOBAL char*>(as_global(XK.t[k]) + ((int64_t)kg * NB + nb) * 512) + lane_f);
         }
     };
+    auto load_b = [&](int ch, bf16x8 (&bfrag)[4][NB][PL]) {
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) load_b_ks(ch, ks, bfrag);
+    };
     // LAZY: the correction d_lds[row][col] = sum_k P~[row0 + row][k] Q[ch * FK + col][k] of a step; wave v forms it
     // for columns 64 v .. 64 v + 63.  The workgroup's 32 rows of the kept P~ copy (A operand, all k-steps) sit in
     // LDS in fragment order; the kept Q rows of the step's columns (B operand) are requested one step ahead, before
     // the next tile's own loads (the wait counter is in issue order: fragments requested after the tile could only be
     // used once the tile had arrived).
-    bf16x8 qv[LAZY ? 2 : 1][LAZY ? 2 * NB : 1][PL];
+    constexpr bool SHARE = LAZY == 2;
+    bf16x8 qv[LAZY == 1 ? 2 : 1][LAZY == 1 ? 2 * NB : 1][PL];
     const PSGD_GLOBAL bf16_t* kept_w[PL];
 #pragma unroll
-    for (int k = 0; k < PL; ++k) kept_w[k] = LAZY ? as_global(L.lzf[SIDE_W][k]) : nullptr;
+    for (int k = 0; k < PL; ++k) kept_w[k] = LAZY == 1 ? as_global(L.lzf[SIDE_W][k]) : nullptr;
     auto load_q = [&](int ch, int q) {
         {
             // 32-column block of the kept Q copy; past the padded length the last block, whose product lands on
@@ -262,6 +268,64 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         }
     };
 
+    // LAZY == 2.  The product's fragments f[ks][nb][k] hold Q[16 ks + 8 lg + j][32 nb + li] (of the wave's 64 columns):
+    // 8 columns of one rank index per lane, where the correction wants 8 rank indices of one column.  The matrix cores
+    // turn one into the other: with the fragment as A operand (32 rank indices x 16 columns) and a 0/1 selection matrix
+    // as B, two MFMAs leave the 32 x 32 block Q^T[rank][column] in accumulator layout -- lane li + 32 lg: column li,
+    // rank indices 8 g + 4 lg + j -- exactly (x * 1 + 0 in fp32 of bf16 numbers).  Its registers 8 s .. 8 s + 7, cut
+    // back to bf16, are a B operand for k-step s of that block with the rank indices in the order 8 (i >> 2) + 4 lg +
+    // (i & 3), i = 0..7; the kept P~ sits in LDS in the same order (see the fill).  This saves the second stream of Q
+    // fragments from L2 (as many bytes as the first, and 1.3 times the tile's from memory).
+    bf16x8 sel0, sel1;
+    if (SHARE) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            sel0[j] = (bf16_t)((8 * lg + j == li) ? 1.0f : 0.0f);
+            sel1[j] = (bf16_t)((8 * lg + j + 16 == li) ? 1.0f : 0.0f);
+        }
+    }
+    auto correction_shared = [&](const bf16x8 (&f)[4][NB][PL]) {
+        if constexpr (SHARE) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            floatx16 d;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) d[v] = 0.f;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int kb = PL - 1; kb >= 0; --kb) {          // (smaller plane first)
+                    floatx16 tr;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) tr[v] = 0.f;
+                    tr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2 * q][nb][kb], sel0, tr, 0, 0, 0);
+                    tr = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2 * q + 1][nb][kb], sel1, tr, 0, 0, 0);
+#pragma unroll
+                    for (int s2 = 0; s2 < 2; ++s2) {
+                        uintx4 pk;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            pk[i] = __builtin_amdgcn_perm(__float_as_uint(tr[8 * s2 + 2 * i + 1]),
+                                                          __float_as_uint(tr[8 * s2 + 2 * i]), 0x07060302u);
+                        bf16x8 qf;
+                        __builtin_memcpy(&qf, &pk, 16);
+                        const int ks = 2 * nb + s2;
+#pragma unroll
+                        for (int ka = PL - 1; ka >= 0; --ka)
+                            if (form_keep_term<PL>(ka, kb)) {
+                                const bf16x8 pv = *reinterpret_cast<const bf16x8*>(p_lds + ((ks * PL + ka) * 64 + lane) * 8);
+                                d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(pv, qf, d, 0, 0, 0);
+                            }
+                    }
+                }
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+                d_lds[(8 * (v >> 2) + 4 * lg + (v & 3)) * FDW + 64 * wv + 32 * q + li] = d[v];
+            __builtin_amdgcn_sched_barrier(0);      // (one block at a time: interleaved they do not fit the registers)
+        }
+        }
+    };
+
     floatx16 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
@@ -273,18 +337,33 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
     if (n_loc > 0) {
         load_e(chunk_at(0), e);
         load_g(0, chunk_at(0), g);
-        load_b(chunk_at(0));
+        load_b(chunk_at(0), bfrag);
         if (LAZY) {
             for (int i = t; i < 2 * NB * PL * 64; i += kThreads) {
                 const int ks = i / (PL * 64), k = (i / 64) % PL, ln = i & 63;
-                *reinterpret_cast<uintx4*>(p_lds + i * 8) = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(
+                const uintx4 pc = *reinterpret_cast<const PSGD_GLOBAL uintx4*>(
                     as_global(L.lzf[SIDE_L][k]) + (((int64_t)ob * (2 * NB) + ks) * 64 + ln) * 8);
+                if (SHARE) {
+                    // rank indices 16 ks + 8 lg' + 4 h + 0..3 of row ln & 31 (lg' = ln >> 5) go to lane group h, places
+                    // 4 lg' .. 4 lg' + 3: the order in which correction_shared gets the other operand
+                    bf16_t* dst = p_lds + (i - ln) * 8 + (ln & 31) * 8 + 4 * (ln >> 5);
+                    *reinterpret_cast<uintx2*>(dst) = uintx2{pc.x, pc.y};
+                    *reinterpret_cast<uintx2*>(dst + 32 * 8) = uintx2{pc.z, pc.w};
+                } else {
+                    *reinterpret_cast<uintx4*>(p_lds + i * 8) = pc;
+                }
             }
-            load_q(chunk_at(0), 0);
-            load_q(chunk_at(0), 1);
+            if (LAZY == 1) {
+                load_q(chunk_at(0), 0);
+                load_q(chunk_at(0), 1);
+            }
             __syncthreads();
-            correction(0);
-            correction(1);
+            if (SHARE) {
+                correction_shared(bfrag);
+            } else {
+                correction(0);
+                correction(1);
+            }
             __syncthreads();                 // (later steps: the barrier that ends the step before)
         }
     }
@@ -398,7 +477,7 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
         // fragments of the next step go out first, the other half and the tile after this step's product: the
         // registers do not hold the tile, both sets of fragments and the accumulators at once.)
         if (it + 1 < n_loc) {
-            if (LAZY) {
+            if (LAZY == 1) {
                 load_q(chunk_at(it + 1), 0);
             } else {
                 load_e(chunk_at(it + 1), e);
@@ -422,18 +501,25 @@ __global__ __launch_bounds__(kThreads, 2) void form_row_kernel(const LayerDev* _
                         if (kb >= 0 && kb < PL && form_keep_term<PL>(ka, kb))
                             acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[ka], bfrag[ks][nb][kb], acc[nb], 0, 0, 0);
                     }
+            // (LAZY == 2: the fragments of this k-step are used up; the next step's go into their registers now, so
+            // that they are on their way during the rest of the product and there for the correction below)
+            if (SHARE && it + 1 < n_loc) load_b_ks(chunk_at(it + 1), ks, bfrag);
         }
         // ---- the next step's thin operand fragments (their registers are free now); LAZY: its tile and its
         // correction first (d_lds was last read before this step's barrier)
         if (it + 1 < n_loc) {
-            if (LAZY) {
-                load_q(chunk_at(it + 1), 1);      // (before the tile: the wait counter is in issue order)
-                load_e(chunk_at(it + 1), e);
-                load_g(0, chunk_at(it + 1), g);
-                correction(0);
-                correction(1);
+            if (SHARE) {
+                correction_shared(bfrag);
+            } else {
+                if (LAZY) {
+                    load_q(chunk_at(it + 1), 1);      // (before the tile: the wait counter is in issue order)
+                    load_e(chunk_at(it + 1), e);
+                    load_g(0, chunk_at(it + 1), g);
+                    correction(0);
+                    correction(1);
+                }
+                load_b(chunk_at(it + 1), bfrag);
             }
-            load_b(chunk_at(it + 1));
         }
         if (ABUF == 1) __syncthreads();
     }
@@ -892,7 +978,7 @@ hipError_t launch_row_prod(int nb, int planes, const LayerDev* layers, const int
 }
 
 template <int NB, int PL>
-static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids, int n_ids,
+static hipError_t launch_form_nb(bool gbf, bool onew, int lazy, const LayerDev* layers, const int* ids, int n_ids,
                                  int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
                                  int xtiles, hipStream_t st) {
     dim3 grid(max_tiles, n_ids), block(kThreads);
@@ -908,12 +994,15 @@ static hipError_t launch_form_nb(bool gbf, bool onew, bool lazy, const LayerDev*
         }                                                                                                      \
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, nt_m, xtab, xstride);        \
     } while (0)
-    if (lazy) {
-        if (gbf) { if (onew) PSGD_FORM(true, true, true); else PSGD_FORM(true, false, true); }
-        else     { if (onew) PSGD_FORM(false, true, true); else PSGD_FORM(false, false, true); }
+    if (lazy == 2) {
+        if (gbf) { if (onew) PSGD_FORM(true, true, 2); else PSGD_FORM(true, false, 2); }
+        else     { if (onew) PSGD_FORM(false, true, 2); else PSGD_FORM(false, false, 2); }
+    } else if (lazy) {
+        if (gbf) { if (onew) PSGD_FORM(true, true, 1); else PSGD_FORM(true, false, 1); }
+        else     { if (onew) PSGD_FORM(false, true, 1); else PSGD_FORM(false, false, 1); }
     } else {
-        if (gbf) { if (onew) PSGD_FORM(true, true, false); else PSGD_FORM(true, false, false); }
-        else     { if (onew) PSGD_FORM(false, true, false); else PSGD_FORM(false, false, false); }
+        if (gbf) { if (onew) PSGD_FORM(true, true, 0); else PSGD_FORM(true, false, 0); }
+        else     { if (onew) PSGD_FORM(false, true, 0); else PSGD_FORM(false, false, 0); }
     }
 #undef PSGD_FORM
     return hipGetLastError();
@@ -931,11 +1020,12 @@ bool form_row_supported(int nb, int planes, bool gbf, bool onew, bool lazy) {
 }
 
 // nb = width / 32 of the thin operand (1 or 2); gbf: every layer of the launch has bf16 gradients (else every layer
-// fp32); onew: one worker; lazy: apply the owed residual on the way in; nt_m: store M with the non-temporal hint
+// fp32); onew: one worker; lazy: apply the owed residual on the way in (2: the kept Q is what the transposed operand
+// copies of the product hold, and is taken from those); nt_m: store M with the non-temporal hint
 // (matrices too large to be found in a cache by the second pass).  max_tiles: max over the layers of
 // (padded rows / 32) * split_row_v2.  xtab (device, nullable): the XCD table described in the kernel, 16 rows of
 // xstride ints; xtiles: the largest tile total of an XCD.
-hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, const LayerDev* layers, const int* ids,
+hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, int lazy, const LayerDev* layers, const int* ids,
                            int n_ids, int max_tiles, int out_role, int epi, int nt_m, const int* xtab, int xstride,
                            int xtiles, hipStream_t st) {
     if (n_ids <= 0 || max_tiles <= 0) return hipSuccess;
@@ -946,8 +1036,8 @@ hipError_t launch_form_row(int nb, int planes, bool gbf, bool onew, bool lazy, c
     if (nb == 3 && planes == 2 && gbf && onew && !lazy) {
         dim3 grid(max_tiles, n_ids), block(kThreads);
         if (xtab) grid = dim3(8 * xtiles, 1);
-        auto kfn = form_row_kernel<3, 2, true, true, false>;
-        const size_t lds = form_lds_bytes<3, 2, false>();
+        auto kfn = form_row_kernel<3, 2, true, true, 0>;
+        const size_t lds = form_lds_bytes<3, 2, 0>();
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kfn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(kfn, grid, block, lds, st, layers, ids, out_role, epi, nt_m, xtab, xstride);

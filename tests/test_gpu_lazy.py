@@ -90,7 +90,10 @@ def _trajectory(wl, steps, lds=None, refresh_at=(), check_m=True, **opts):
 
 
 @pytest.mark.parametrize("which", ["f32_n4_ragged_r4", "bf16_n1_r64", "bf16_n4_r32", "f32_n2_r128", "f32_r40"])
-def test_deferred_residual_trajectory(which):
+@pytest.mark.parametrize("q_resident", [False, True], ids=["q_packed", "q_resident"])
+def test_deferred_residual_trajectory(which, q_resident):
+    """q_resident: the caller's promise not to write the Q buffers between calls, with which the forming pass takes the
+    kept Q from the product's own operand fragments instead of reading the kept copies (another kernel variant)."""
     lds = None
     if which == "f32_n4_ragged_r4":
         wl = synth.scaled_down(synth.config1(), 333, 203)
@@ -105,7 +108,7 @@ def test_deferred_residual_trajectory(which):
     else:
         wl = synth.scaled_down(synth.config2(), 520, 328)
         wl.r = 40
-    print(which, _trajectory(wl, 4, lds=lds))
+    print(which, _trajectory(wl, 4, lds=lds, q_resident=q_resident))
 
 
 @pytest.mark.parametrize("r", [32, 40, 5])
@@ -189,22 +192,24 @@ def test_lazy_option_rejects_unsupported_combinations():
 
 
 @pytest.mark.parametrize("cfg,rows,cols", [("c4", 4096, 4096), ("c4", 11008, 4096), ("c3", 5632, 2048)])
-def test_deferred_residual_full_size_llm_shapes(cfg, rows, cols):
+@pytest.mark.parametrize("q_resident", [False, True], ids=["q_packed", "q_resident"])
+def test_deferred_residual_full_size_llm_shapes(cfg, rows, cols, q_resident):
     """Two free-running steps at the full size of a benchmark layer, so that the second forming pass applies the
     first step's residual across many row blocks and rotated chunk walks, in the benchmark's launch configuration."""
     base = synth.config3() if cfg == "c3" else synth.config4()
     wl = synth.scaled_down(base, rows, cols)
-    print(cfg, rows, cols, _trajectory(wl, 2))
+    print(cfg, rows, cols, _trajectory(wl, 2, q_resident=q_resident))
 
 
 @pytest.mark.parametrize("rows,cols,dtype,r", [(328, 520, synth.F32, 8), (264, 1000, synth.BF16, 32), (1000, 264, synth.F32, 96)])
-def test_deferred_residual_single_worker(rows, cols, dtype, r):
+@pytest.mark.parametrize("q_resident", [False, True], ids=["q_packed", "q_resident"])
+def test_deferred_residual_single_worker(rows, cols, dtype, r, q_resident):
     """N = 1 with the deferred residual: the single-worker forming kernels in row and column mode."""
     base = synth.config4() if dtype == synth.BF16 else synth.config2()
     wl = synth.scaled_down(base, rows, cols)
     wl.n_workers = 1
     wl.r = r
-    print(_trajectory(wl, 3))
+    print(_trajectory(wl, 3, q_resident=q_resident))
 
 
 def test_flush_on_another_workspace_is_rejected():
@@ -267,7 +272,8 @@ def test_compress_on_another_workspace_while_a_residual_is_owed_is_rejected():
     (257, 129, 136, 17, synth.F32, 2), (1000, 264, 264, 33, synth.BF16, 1), (333, 100, 104, 40, synth.F32, 1),
     (2049, 260, 264, 65, synth.BF16, 2), (515, 36, 40, 5, synth.BF16, 3), (1200, 520, 520, 72, synth.F32, 1),
     (900, 300, 304, 96, synth.BF16, 1), (641, 257, 264, 48, synth.F32, 4)])
-def test_deferred_residual_odd_shapes_and_ranks(rows, cols, ld, r, dtype, n_workers):
+@pytest.mark.parametrize("q_resident", [False, True], ids=["q_packed", "q_resident"])
+def test_deferred_residual_odd_shapes_and_ranks(rows, cols, ld, r, dtype, n_workers, q_resident):
     """Shapes that are multiples of nothing (rows not of 8, columns not of 4, a leading dimension beyond the columns) at
     ranks on both sides of every width class of the kernels (16, 32, 64, 80, 96): three free-running steps with the
     deferred residual, every step's P~, Q and M and the flushed E against the oracle."""
@@ -275,4 +281,4 @@ def test_deferred_residual_odd_shapes_and_ranks(rows, cols, ld, r, dtype, n_work
     wl = synth.scaled_down(base, rows, cols)
     wl.r = r
     wl.n_workers = n_workers
-    print((rows, cols, ld, r, dtype, n_workers), _trajectory(wl, 3, lds=[ld]))
+    print((rows, cols, ld, r, dtype, n_workers), _trajectory(wl, 3, lds=[ld], q_resident=q_resident))

@@ -240,7 +240,10 @@ def test_decompress_from_the_factors_of_the_last_compress_call(opts, r):
 def test_q_resident_gives_the_same_steps(lazy):
     """psgd_options.q_resident: Q_{t-1} taken from the operand copies of the previous call instead of packing the Q
     buffers again.  Same bits as the default over a schedule with refresh steps, the fused decompress in between
-    (NULL factors: the copies stay), and an explicit decompress (which re-packs: the next step packs Q again)."""
+    (NULL factors: the copies stay), and an explicit decompress (which re-packs: the next step packs Q again).
+    With the deferred residual the promise also lets the forming pass take the kept Q from those copies, which adds
+    the terms of the owed residual in another order: the same numbers up to fp32 rounding of that sum, not the same
+    bits; what is compared there is what the factors stand for, P~ Q^T, and E."""
     torch = torch_mod()
     wl = synth.scaled_down(synth.config3(), 256, 256)
     wl.layers = [synth.LayerSpec(256, 256, "a"), synth.LayerSpec(704, 256, "b"), synth.LayerSpec(256, 704, "c")]
@@ -251,6 +254,15 @@ def test_q_resident_gives_the_same_steps(lazy):
     for c in (a, b):
         c.upload(grads0, [errs[l][0] for l in range(3)], qs)
         c.OUT = [torch.zeros_like(e) for e in c.E]
+
+    def same(x, y, t):
+        if not lazy:
+            return torch.equal(x, y)
+        # (rounding-level where the two first differ; a free-running run then drifts apart in the directions the rank
+        # cuts through noise: a tenth per cent after seven steps.  Parity of either variant is the oracle's business,
+        # tests/test_gpu_lazy.py.)
+        return float((x - y).norm()) <= (1e-5 if t <= 2 else 5e-3) * float(y.norm())
+
     for t in range(7):
         for c in (a, b):
             if t > 0:
@@ -265,12 +277,13 @@ def test_q_resident_gives_the_same_steps(lazy):
                 c.comp.decompress(None, None, c.OUT)
         torch.cuda.synchronize()
         for l in range(3):
-            assert torch.equal(a.P[l], b.P[l]) and torch.equal(a.Q[l], b.Q[l]) and torch.equal(a.OUT[l], b.OUT[l]), (t, l)
+            for x, y in ((a.OUT[l], b.OUT[l]),) if lazy else ((a.P[l], b.P[l]), (a.Q[l], b.Q[l]), (a.OUT[l], b.OUT[l])):
+                assert same(x, y, t), (t, l)
     if lazy:
         a.comp.flush_residual(a.E); b.comp.flush_residual(b.E)
         torch.cuda.synchronize()
     for l in range(3):
-        assert torch.equal(a.E[l], b.E[l])
+        assert same(a.E[l], b.E[l], 7)
 
 
 def test_workspace_reset_after_the_workspace_was_overwritten():
