@@ -796,7 +796,11 @@ int psgd_init(psgd_ctx** out, int n_layers, const psgd_layer_desc* layers, int n
         const double e = (double)p.d.rows * (double)p.d.cols, nsg = n_workers * sg;
         const double thin = 4.0 * (double)(p.d.rows + p.d.cols) * 32.0 * ((p.d.r + 31) / 32);
         const bool deferred = c->lazy && (!p.transposed || c->lazy_tr);
-        c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin * (deferred ? 2.0 : 1.0);
+        // (deferred residual: the kept P~ and Q are read as well -- the kept Q not where the pass takes it from the
+        // product's own fragments: q_resident, row-major layers)
+        const double kept_q = 4.0 * (double)p.d.cols * 32.0 * ((p.d.r + 31) / 32);
+        const bool shared_q = deferred && c->opt.q_resident == 1 && !p.transposed;
+        c->kernel_bytes[0] += e * (nsg + 4.0 + (c->reform_m ? 0.0 : 4.0)) + thin * (deferred ? 2.0 : 1.0) - (shared_q ? kept_q : 0.0);
         c->kernel_bytes[1] += e * (c->reform_m ? nsg + 4.0 : 4.0) + thin;
         if (!deferred) c->kernel_bytes[2] += e * (c->reform_m ? nsg + 8.0 : 8.0) + thin;
     }
