@@ -127,7 +127,11 @@ typedef struct {
                                    data-parallel one, which averages Q).  psgd_compress then takes Q_{t-1} from
                                    the operand copies the previous call left in the workspace instead of packing
                                    the Q buffers again (one launch less); the first call, and any call after
-                                   one that re-packed the copies, packs as usual.  0 = default: always pack    */
+                                   one that re-packed the copies, packs as usual.  With lazy_residual = 1 the
+                                   forming pass then also takes the Q of the owed residual from those copies
+                                   instead of reading the ones put aside (same numbers; the sum over the rank
+                                   runs in another order, so results agree with the default to fp32 rounding
+                                   of that sum, not bit for bit).  0 = default: always pack                 */
 } psgd_options;
 
 /* Per-layer diagnostics written by the last call that touched the layer (read with psgd_status). */
