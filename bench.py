@@ -127,7 +127,8 @@ def run_ceilings():
     for colmode, name in ((0, "tile_read_rowmode_128rows_x_256B"), (1, "tile_read_colmode_64rows_x_512B")):
         ms = timed(lambda i: lib.ceil_tile_read(st, colmode, tab.data_ptr(), len(mats), 4096, 4096, sink.data_ptr()), 5)
         out[name] = len(mats) * 4096 * 4096 * 4 / ms / 1e6
-    for pat, name in ((0, "tile_write_128x128_accumulator_layout"), (1, "tile_write_64x256_1KB_per_wave_store")):
+    for pat, name in ((0, "tile_write_128x128_accumulator_layout"), (1, "tile_write_64x256_1KB_per_wave_store"),
+                      (2, "tile_write_128x256_accumulator_layout_8_columns_per_lane")):
         ms = timed(lambda i: lib.ceil_tile_write(st, pat, tab.data_ptr(), len(mats), 4096, 4096), 5)
         out[name] = len(mats) * 4096 * 4096 * 4 / ms / 1e6
     gmats = [torch.randn(4096, 4096, device="cuda").bfloat16() for _ in range(48)]

@@ -137,13 +137,24 @@ __global__ __launch_bounds__(kT) void flat_rmw_nt(float* buf, size_t n4) {
 
 // Write-only in tiles (decompress): a workgroup writes a 128 x 128 tile, consecutive workgroups consecutive column
 // blocks.  PAT 0: per store instruction a wave writes 2 rows x 512 B, rows 4 apart (the MFMA accumulator layout of the
-// outer-product kernels); PAT 1: tile 64 rows x 256 columns, per store a wave writes 1 row x 1 KB.
+// outer-product kernels); PAT 1: tile 64 rows x 256 columns, per store a wave writes 1 row x 1 KB; PAT 2: tile 128 rows x
+// 256 columns in the accumulator layout of eight column blocks, a lane owning 8 consecutive columns: two stores per
+// row pair, each 32 pieces of 16 bytes 32 bytes apart, together 2 rows x 1 KB.
 template <int PAT>
 __global__ __launch_bounds__(kT) void tile_write(float* const* mats, int rows, int cols) {
     GLOBAL_AS float* m = (GLOBAL_AS float*)mats[blockIdx.y];
     const int t = threadIdx.x, lane = t & 63, wv = t >> 6, li = lane & 31, lg = lane >> 5;
     const floatx4 val = {1.f, 2.f, 3.f, (float)blockIdx.x};
-    if (PAT == 1) {
+    if (PAT == 2) {
+        const int n_cb = cols / 256, cb = blockIdx.x % n_cb, rb = blockIdx.x / n_cb;
+        if (rb >= rows / 128) return;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            GLOBAL_AS float* p = m + (size_t)(rb * 128 + 32 * wv + 8 * (v >> 2) + (v & 3) + 4 * lg) * cols + cb * 256 + 8 * li;
+            *(GLOBAL_AS floatx4*)p = val;
+            *(GLOBAL_AS floatx4*)(p + 4) = val;
+        }
+    } else if (PAT == 1) {
         const int n_cb = cols / 256, cb = blockIdx.x % n_cb, rb = blockIdx.x / n_cb;
         if (rb >= rows / 64) return;
 #pragma unroll
@@ -291,7 +302,8 @@ extern "C" int ceil_tile_write(void* stream, int pat, const void* const* mats, i
     if (rows % 128 || cols % 256 || nmat < 1) return (int)hipErrorInvalidValue;
     dim3 grid((rows / 128) * (cols / 128), nmat);
     float* const* m = (float* const*)mats;
-    if (pat) hipLaunchKernelGGL(tile_write<1>, grid, dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
+    if (pat == 2) hipLaunchKernelGGL(tile_write<2>, dim3((rows / 128) * (cols / 256), nmat), dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
+    else if (pat) hipLaunchKernelGGL(tile_write<1>, grid, dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
     else hipLaunchKernelGGL(tile_write<0>, grid, dim3(kT), 0, (hipStream_t)stream, m, rows, cols);
     return (int)hipGetLastError();
 }
