@@ -411,6 +411,7 @@ struct Launcher {
                               // to the kept copies (fragment order) in the layers that have them
     bool use_form_row = true; // PSGD_FORM_ROW=0 (environment, measurement knob): the older 128 x 64 forming pass
     bool use_xtab = true;     // PSGD_XTAB=0 (environment, measurement knob): plain layer-by-layer launch order
+    bool use_xtab_c = true;   // PSGD_XTAB_C=0 (likewise): the same for the column-mode product alone
 
     void note(hipError_t e) { if (err == hipSuccess && e != hipSuccess) err = e; }
     // event pair around one tagged launch group (only when profiling is on and pairs are left)
@@ -454,7 +455,7 @@ struct Launcher {
         const bool gram32 = (v2 || r2) && split_row_v2 == 1 && epi == EPI_GRAM && w > 16 && chol_gate >= -1;
         // the second product on row-major layers at those widths likewise
         const bool c2 = !form && !p_like && n_norm > 0 && use_form_row && col_prod_supported(nb, ctx->planes);
-        const int* xtab_c = (ctx->xstride > 0 && use_xtab && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
+        const int* xtab_c = (ctx->xstride > 0 && use_xtab && use_xtab_c && nb >= 2 && ids_norm == ids_all + ctx->n_layers)
                                 ? reinterpret_cast<const int*>(ws + ctx->off_xtab_c) : nullptr;
         if (c2) note(launch_col_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_col_v2, out_role, ef, gate, ctx->nt_m ? 1 : 0, xtab_c, ctx->xstride, ctx->xtiles_c, st));
         else if (r2) note(launch_row_prod(nb, ctx->planes, layers, ids_norm, n_norm, tiles_row_v2, out_role, gram32 ? ef : (ef & ~EPI_KIND_MASK), gate, ctx->nt_m ? 1 : 0, xtab, ctx->xstride, ctx->xtiles, st));
@@ -568,6 +569,7 @@ Launcher batch_launcher(psgd_ctx* ctx, void* workspace, hipStream_t st) {
     for (int l = 0; l < nl; ++l) geometry(ctx, l, ctx->split_row_b, ctx->split_col_b, ctx->split_row_bf, ctx->split_col_bf, L);
     L.use_form_row = form_row_env();
     { static int v = -1; if (v < 0) { const char* e = std::getenv("PSGD_XTAB"); v = (e && e[0] == '0') ? 0 : 1; } L.use_xtab = v == 1; }
+    { static int v = -1; if (v < 0) { const char* e = std::getenv("PSGD_XTAB_C"); v = (e && e[0] == '0') ? 0 : 1; } L.use_xtab_c = v == 1; }
     return L;
 }
 
