@@ -45,7 +45,9 @@
  *     nothing to upload and the recorded work is kernel launches only (no copy and no memset nodes).  A call that
  *     would have to upload returns PSGD_E_CAPTURE and records nothing; the next eager call uploads everything.  A
  *     captured psgd_compress_refresh launches the whole iteration budget and skips its bookkeeping copy; per-kernel
- *     profiling records nothing under capture.  psgd_refresh and psgd_status cannot be captured.
+ *     profiling records nothing under capture.  psgd_refresh and psgd_status cannot be captured.  What a recorded call
+ *     does is decided when it is recorded (which operand copies are in place, whether a residual is owed): replay it in
+ *     the sequence it was recorded in, and make no eager call on the workspace between replays that changes that state.
  */
 #ifndef PSGD_H_
 #define PSGD_H_
